@@ -1,0 +1,553 @@
+// CPU oracle for the batched MPE simple-spread rollout (TEST INFRASTRUCTURE ONLY).
+//
+// This file is the plain, slow, scalar definition that the HIP library is checked
+// against.  It is not part of the product: only the tests, the smoke check and the
+// cpu_baseline leg of the benchmark may load it.  It shares no code, header, table
+// or constant generator with the HIP path.
+//
+// What it follows.  The paper (JaxMARL, arXiv 2311.10090) describes MPE only as a 2-D
+// world with simple physics in which particle agents move and interact with fixed
+// landmarks (Sec. 3.1 "MPE", App. B.7), exposes it through reset(key) -> (obs, state)
+// and step(key, state, actions) -> (obs, state, reward, done) with an explicit state
+// and an explicit random key (App. C, API listing), uses a shared-parameter
+// feed-forward policy with two tanh layers of width 64 for MPE (Sec. 3.2 "PPO";
+// App. G, IPPO hyper-parameter table), and rolls out 128 steps per update (same
+// table).  Everything quantitative the paper leaves open is fixed by the readings
+// R-1 ... R-12 listed beside each function below.
+//
+// Arithmetic: double throughout (floating-point inputs arrive as float32 or double and
+// are widened once).  No blocking, fusion or reordering: one loop per env, per step,
+// per agent, in the order the definition states.
+//
+// Every function here is pinned by tests that do not depend on this file's own
+// arithmetic: Philox known-answer vectors, hand-worked transitions, closed forms for
+// a collision-free agent, contact-force magnitudes, invariants (antisymmetric
+// contacts, momentum decay, permutation/translation/rotation invariance of the
+// reward), brute-force re-derivations in numpy, a chi-square test of the sampler and
+// a numpy float64 MLP chain.
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <string>
+#include <thread>
+#include <vector>
+
+namespace {
+
+// ---------------------------------------------------------------------------------
+// R-1  Random numbers: Philox4x32 with 10 rounds (Salmon et al., SC'11).
+// Key = (seed, run).  Counter = (env index within the run, absolute step, entity or
+// agent index, tag).
+// ---------------------------------------------------------------------------------
+enum : uint32_t { TAG_RESET_POS = 0, TAG_UNIFORM_ACTION = 1, TAG_GUMBEL0 = 2, TAG_GUMBEL1 = 3 };
+
+void philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+  uint32_t k0 = key[0], k1 = key[1];
+  for (int round = 0; round < 10; ++round) {
+    const uint64_t p0 = uint64_t(0xD2511F53u) * uint64_t(c0);
+    const uint64_t p1 = uint64_t(0xCD9E8D57u) * uint64_t(c2);
+    const uint32_t hi0 = uint32_t(p0 >> 32), lo0 = uint32_t(p0);
+    const uint32_t hi1 = uint32_t(p1 >> 32), lo1 = uint32_t(p1);
+    const uint32_t n0 = hi1 ^ c1 ^ k0;
+    const uint32_t n1 = lo1;
+    const uint32_t n2 = hi0 ^ c3 ^ k1;
+    const uint32_t n3 = lo0;
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// Conversions of a 32-bit word (all exactly representable in float32).
+//   position  in [-1, 1):  (w >> 8) * 2^-23 - 1
+//   open-interval uniform in (0, 1): (2 * (w >> 9) + 1) * 2^-24
+//   uniform action in {0..4}: floor(w * 5 / 2^32)
+double word_to_position(uint32_t w) { return double(w >> 8) * (1.0 / 8388608.0) - 1.0; }
+double word_to_open_uniform(uint32_t w) { return double(2u * (w >> 9) + 1u) * (1.0 / 16777216.0); }
+int word_to_action(uint32_t w) { return int((uint64_t(w) * 5u) >> 32); }
+
+struct Config {
+  int32_t num_envs, num_agents, num_landmarks, num_runs, max_episode_steps;
+  int32_t hidden, weight_dtype;  // weight_dtype: 0 = fp32 weights, 1 = bf16 weights + bf16 layer inputs
+  int32_t env_offset, run_offset;  // this instance simulates envs [env_offset, env_offset+num_envs)
+                                   // of runs [run_offset, run_offset+num_runs) of a larger job
+  double dt, damping, mass, accel;
+  double agent_radius, landmark_radius;
+  double contact_force, contact_margin;
+};
+
+struct Policy {
+  bool set = false;
+  // Per run: W1[D][H], b1[H], W2[H][H], b2[H], W3[H][5], b3[5], row-major [fan_in][fan_out].
+  std::vector<double> W1, b1, W2, b2, W3, b3;
+};
+
+struct Oracle {
+  Config cfg;
+  int E, N, L, R, D, H;
+  uint32_t seed = 0;
+  uint32_t abs_step = 0;
+  bool was_reset = false;
+  // State, plain array-of-structs: [run][env][entity][2].
+  std::vector<double> pos_a, vel_a, pos_l;
+  std::vector<int32_t> ep_step;
+  Policy pol;
+  int nthreads = 1;
+};
+
+constexpr int NUM_ACTIONS = 5;
+
+// Round a double to the nearest bfloat16 value (ties to even), returned as double.
+// bfloat16 = sign, 8 exponent bits, 7 stored mantissa bits (the top half of float32).
+// Values used here are far from the overflow/underflow limits of the format.
+double round_to_bf16(double x) {
+  if (x == 0.0 || !std::isfinite(x)) return x;
+  int e;
+  const double m = std::frexp(x, &e);              // x = m * 2^e, 0.5 <= |m| < 1
+  const double scaled = std::ldexp(m, 8);          // 8 significant bits: 128 <= |scaled| < 256
+  const double r = std::nearbyint(scaled);         // default rounding mode: ties to even
+  return std::ldexp(r, e - 8);
+}
+
+// ---------------------------------------------------------------------------------
+// R-2  Reset at absolute step s: every entity e (agents 0..N-1, then landmarks
+// N..N+L-1) draws Philox(env, s, e, RESET_POS); words 0 and 1 give x and y on the
+// 24-bit grid of [-1, 1).  Agent velocities are 0 and the episode counter is 0.
+// ---------------------------------------------------------------------------------
+void reset_env(Oracle& o, int run, int env, uint32_t s) {
+  const uint32_t key[2] = {o.seed, uint32_t(o.cfg.run_offset + run)};
+  const size_t ge = size_t(run) * o.E + env;
+  for (int e = 0; e < o.N + o.L; ++e) {
+    const uint32_t ctr[4] = {uint32_t(o.cfg.env_offset + env), s, uint32_t(e), TAG_RESET_POS};
+    uint32_t w[4];
+    philox4x32_10(ctr, key, w);
+    const double x = word_to_position(w[0]);
+    const double y = word_to_position(w[1]);
+    if (e < o.N) {
+      o.pos_a[(ge * o.N + e) * 2 + 0] = x;
+      o.pos_a[(ge * o.N + e) * 2 + 1] = y;
+      o.vel_a[(ge * o.N + e) * 2 + 0] = 0.0;
+      o.vel_a[(ge * o.N + e) * 2 + 1] = 0.0;
+    } else {
+      o.pos_l[(ge * o.L + (e - o.N)) * 2 + 0] = x;
+      o.pos_l[(ge * o.L + (e - o.N)) * 2 + 1] = y;
+    }
+  }
+  o.ep_step[ge] = 0;
+}
+
+// ---------------------------------------------------------------------------------
+// R-8  Observation of agent i, length D = 4 + 2L + 4(N-1):
+//   [ v_i, p_i, (l_k - p_i) for k ascending, (p_j - p_i) for j != i ascending,
+//     2(N-1) zeros (the silent communication slots of the other agents) ].
+// ---------------------------------------------------------------------------------
+void observe_env(const Oracle& o, size_t ge, double* obs /* [N][D] */) {
+  const double* pa = &o.pos_a[ge * o.N * 2];
+  const double* va = &o.vel_a[ge * o.N * 2];
+  const double* pl = &o.pos_l[ge * o.L * 2];
+  for (int i = 0; i < o.N; ++i) {
+    double* ob = obs + size_t(i) * o.D;
+    int c = 0;
+    ob[c++] = va[2 * i + 0];
+    ob[c++] = va[2 * i + 1];
+    ob[c++] = pa[2 * i + 0];
+    ob[c++] = pa[2 * i + 1];
+    for (int k = 0; k < o.L; ++k) {
+      ob[c++] = pl[2 * k + 0] - pa[2 * i + 0];
+      ob[c++] = pl[2 * k + 1] - pa[2 * i + 1];
+    }
+    for (int j = 0; j < o.N; ++j) {
+      if (j == i) continue;
+      ob[c++] = pa[2 * j + 0] - pa[2 * i + 0];
+      ob[c++] = pa[2 * j + 1] - pa[2 * i + 1];
+    }
+    for (int z = 0; z < 2 * (o.N - 1); ++z) ob[c++] = 0.0;
+  }
+}
+
+// softplus(x) = log(1 + exp(x)) in the overflow-safe form max(x,0) + log1p(exp(-|x|)).
+double softplus(double x) { return std::max(x, 0.0) + std::log1p(std::exp(-std::fabs(x))); }
+
+// ---------------------------------------------------------------------------------
+// One transition of one env under given actions (readings R-3 ... R-7):
+//  R-3 control force  F_i = accel * dir(a_i), dir: 0 none, 1 -x, 2 +x, 3 -y, 4 +y
+//  R-4 contact force for every unordered agent pair (i, j) on the pre-step positions:
+//        delta = p_i - p_j, d = |delta|, pen = margin * softplus((2 r - d) / margin),
+//        f = contact_force * pen * delta / max(d, 1e-12);  F_i += f, F_j -= f.
+//      Landmarks neither collide nor move.
+//  R-5 integration: p_i += v_i * dt with the old velocity, then
+//        v_i = v_i * (1 - damping) + (F_i / mass) * dt.   No speed clip.
+//  R-6 reward on the post-step positions: r = - sum_k min_i |p_i - l_k|, one per env.
+//  R-7 ep_step += 1; done = (ep_step >= max_episode_steps).  If done, the env is reset
+//      with the counter's step field set to s + 1, so the new episode depends only on
+//      (seed, run, env, s + 1).
+// ---------------------------------------------------------------------------------
+void step_env(Oracle& o, int run, int env, uint32_t s, const uint8_t* act /* [N] */,
+              double* reward, uint8_t* done) {
+  const Config& c = o.cfg;
+  const size_t ge = size_t(run) * o.E + env;
+  double* pa = &o.pos_a[ge * o.N * 2];
+  double* va = &o.vel_a[ge * o.N * 2];
+  const double* pl = &o.pos_l[ge * o.L * 2];
+
+  std::vector<double> F(size_t(o.N) * 2, 0.0);
+  for (int i = 0; i < o.N; ++i) {
+    double ux = 0.0, uy = 0.0;
+    switch (act[i]) {
+      case 1: ux = -1.0; break;
+      case 2: ux = +1.0; break;
+      case 3: uy = -1.0; break;
+      case 4: uy = +1.0; break;
+      default: break;
+    }
+    F[2 * i + 0] = c.accel * ux;
+    F[2 * i + 1] = c.accel * uy;
+  }
+  for (int i = 0; i < o.N; ++i) {
+    for (int j = i + 1; j < o.N; ++j) {
+      const double dx = pa[2 * i + 0] - pa[2 * j + 0];
+      const double dy = pa[2 * i + 1] - pa[2 * j + 1];
+      const double d = std::sqrt(dx * dx + dy * dy);
+      const double pen = c.contact_margin * softplus((2.0 * c.agent_radius - d) / c.contact_margin);
+      const double scale = c.contact_force * pen / std::max(d, 1e-12);
+      F[2 * i + 0] += scale * dx;
+      F[2 * i + 1] += scale * dy;
+      F[2 * j + 0] -= scale * dx;
+      F[2 * j + 1] -= scale * dy;
+    }
+  }
+  for (int i = 0; i < o.N; ++i) {
+    for (int a = 0; a < 2; ++a) {
+      pa[2 * i + a] += va[2 * i + a] * c.dt;
+      va[2 * i + a] = va[2 * i + a] * (1.0 - c.damping) + (F[2 * i + a] / c.mass) * c.dt;
+    }
+  }
+  double r = 0.0;
+  for (int k = 0; k < o.L; ++k) {
+    double best = INFINITY;
+    for (int i = 0; i < o.N; ++i) {
+      const double dx = pa[2 * i + 0] - pl[2 * k + 0];
+      const double dy = pa[2 * i + 1] - pl[2 * k + 1];
+      best = std::min(best, std::sqrt(dx * dx + dy * dy));
+    }
+    r -= best;
+  }
+  *reward = r;
+  o.ep_step[ge] += 1;
+  const bool d = o.ep_step[ge] >= c.max_episode_steps;
+  *done = d ? 1 : 0;
+  if (d) reset_env(o, run, env, s + 1);
+}
+
+// ---------------------------------------------------------------------------------
+// R-9  Policy: h1 = tanh(W1^T o + b1); h2 = tanh(W2^T h1 + b2); z = W3^T h2 + b3, with
+// W stored row-major [fan_in][fan_out] (paper: two hidden layers, tanh, parameters
+// shared by all agents).  bf16 mode: weights were rounded to bf16 when set; o, h1 and
+// h2 are rounded to bf16 where they enter a layer; products, sums, biases and tanh stay
+// in the wide type.
+// ---------------------------------------------------------------------------------
+void policy_logits(const Oracle& o, int run, const double* ob, double* z /* [5] */) {
+  const int D = o.D, H = o.H;
+  const bool bf = o.cfg.weight_dtype == 1;
+  const double* W1 = &o.pol.W1[size_t(run) * D * H];
+  const double* b1 = &o.pol.b1[size_t(run) * H];
+  const double* W2 = &o.pol.W2[size_t(run) * H * H];
+  const double* b2 = &o.pol.b2[size_t(run) * H];
+  const double* W3 = &o.pol.W3[size_t(run) * H * NUM_ACTIONS];
+  const double* b3 = &o.pol.b3[size_t(run) * NUM_ACTIONS];
+  std::vector<double> x(D), h1(H), h2(H);
+  for (int k = 0; k < D; ++k) x[k] = bf ? round_to_bf16(ob[k]) : ob[k];
+  for (int j = 0; j < H; ++j) {
+    double acc = 0.0;
+    for (int k = 0; k < D; ++k) acc += x[k] * W1[size_t(k) * H + j];
+    h1[j] = std::tanh(acc + b1[j]);
+  }
+  if (bf) for (int j = 0; j < H; ++j) h1[j] = round_to_bf16(h1[j]);
+  for (int j = 0; j < H; ++j) {
+    double acc = 0.0;
+    for (int k = 0; k < H; ++k) acc += h1[k] * W2[size_t(k) * H + j];
+    h2[j] = std::tanh(acc + b2[j]);
+  }
+  if (bf) for (int j = 0; j < H; ++j) h2[j] = round_to_bf16(h2[j]);
+  for (int a = 0; a < NUM_ACTIONS; ++a) {
+    double acc = 0.0;
+    for (int k = 0; k < H; ++k) acc += h2[k] * W3[size_t(k) * NUM_ACTIONS + a];
+    z[a] = acc + b3[a];
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// R-10  Gumbel-max sampling: g_k = -ln(-ln u_k); u_0..u_3 are the four words of
+// Philox(env, s, agent, GUMBEL0), u_4 is word 0 of Philox(env, s, agent, GUMBEL1);
+// action = argmax_k (z_k + g_k), lowest index on ties.
+// Without a policy the action is floor(5 * w / 2^32) with w = word 0 of
+// Philox(env, s, agent, UNIFORM_ACTION).
+// ---------------------------------------------------------------------------------
+int gumbel_max_action(uint32_t seed, uint32_t run, uint32_t env, uint32_t s, uint32_t agent,
+                      const double* z) {
+  const uint32_t key[2] = {seed, run};
+  const uint32_t c0[4] = {env, s, agent, TAG_GUMBEL0};
+  const uint32_t c1[4] = {env, s, agent, TAG_GUMBEL1};
+  uint32_t w0[4], w1[4];
+  philox4x32_10(c0, key, w0);
+  philox4x32_10(c1, key, w1);
+  const uint32_t words[NUM_ACTIONS] = {w0[0], w0[1], w0[2], w0[3], w1[0]};
+  int best = 0;
+  double best_v = -INFINITY;
+  for (int k = 0; k < NUM_ACTIONS; ++k) {
+    const double u = word_to_open_uniform(words[k]);
+    const double g = -std::log(-std::log(u));
+    const double v = z[k] + g;
+    if (v > best_v) { best_v = v; best = k; }
+  }
+  return best;
+}
+
+int uniform_action(uint32_t seed, uint32_t run, uint32_t env, uint32_t s, uint32_t agent) {
+  const uint32_t key[2] = {seed, run};
+  const uint32_t c[4] = {env, s, agent, TAG_UNIFORM_ACTION};
+  uint32_t w[4];
+  philox4x32_10(c, key, w);
+  return word_to_action(w[0]);
+}
+
+void choose_actions(const Oracle& o, int run, int env, uint32_t s, const double* obs /* [N][D] */,
+                    uint8_t* act /* [N] */) {
+  for (int i = 0; i < o.N; ++i) {
+    if (o.pol.set) {
+      double z[NUM_ACTIONS];
+      policy_logits(o, run, obs + size_t(i) * o.D, z);
+      act[i] = uint8_t(gumbel_max_action(o.seed, uint32_t(o.cfg.run_offset + run),
+                                         uint32_t(o.cfg.env_offset + env), s, uint32_t(i), z));
+    } else {
+      act[i] = uint8_t(uniform_action(o.seed, uint32_t(o.cfg.run_offset + run),
+                                      uint32_t(o.cfg.env_offset + env), s, uint32_t(i)));
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// R-11  Rollout of T steps: for t = 0..T-1 record the current observation, choose the
+// actions (policy + Gumbel-max, or uniform), record them, apply one transition, record
+// reward and done.  After the loop last_obs is the current observation.
+// ---------------------------------------------------------------------------------
+void rollout_range(Oracle& o, size_t g0, size_t g1, int T, double* obs_traj, uint8_t* act_traj,
+                   double* rew_traj, uint8_t* done_traj, double* last_obs) {
+  const size_t TE = size_t(o.R) * o.E;
+  const size_t row = size_t(o.N) * o.D;
+  std::vector<double> ob(row);
+  std::vector<uint8_t> act(o.N);
+  for (size_t ge = g0; ge < g1; ++ge) {
+    const int run = int(ge / o.E), env = int(ge % o.E);
+    for (int t = 0; t < T; ++t) {
+      const uint32_t s = o.abs_step + uint32_t(t);
+      observe_env(o, ge, ob.data());
+      if (obs_traj) std::memcpy(obs_traj + (size_t(t) * TE + ge) * row, ob.data(), row * sizeof(double));
+      choose_actions(o, run, env, s, ob.data(), act.data());
+      if (act_traj) std::memcpy(act_traj + (size_t(t) * TE + ge) * o.N, act.data(), o.N);
+      double r;
+      uint8_t d;
+      step_env(o, run, env, s, act.data(), &r, &d);
+      if (rew_traj) rew_traj[size_t(t) * TE + ge] = r;
+      if (done_traj) done_traj[size_t(t) * TE + ge] = d;
+    }
+    if (last_obs) observe_env(o, ge, last_obs + ge * row);
+  }
+}
+
+thread_local std::string g_err;
+int fail(const char* msg) { g_err = msg; return -1; }
+
+}  // namespace
+
+// =====================================================================================
+// C interface (host pointers only).  Returns 0 on success, -1 on error.
+// =====================================================================================
+extern "C" {
+
+struct orc_config {
+  int32_t num_envs, num_agents, num_landmarks, num_runs, max_episode_steps;
+  int32_t hidden, weight_dtype;
+  int32_t env_offset, run_offset;
+  double dt, damping, mass, accel;
+  double agent_radius, landmark_radius;
+  double contact_force, contact_margin;
+};
+
+const char* orc_last_error(void) { return g_err.c_str(); }
+
+void orc_philox4x32_10(const uint32_t* ctr, const uint32_t* key, uint32_t* out) {
+  philox4x32_10(ctr, key, out);
+}
+
+int orc_create(const orc_config* c, void** out) {
+  if (!c || !out) return fail("null argument");
+  if (c->num_envs < 1 || c->num_agents < 1 || c->num_landmarks < 1 || c->num_runs < 1 ||
+      c->max_episode_steps < 1)
+    return fail("sizes must be positive");
+  static_assert(sizeof(orc_config) == sizeof(Config), "config mirror");
+  Oracle* o = new Oracle();
+  std::memcpy(&o->cfg, c, sizeof(Config));
+  o->E = c->num_envs; o->N = c->num_agents; o->L = c->num_landmarks; o->R = c->num_runs;
+  o->D = 4 + 2 * o->L + 4 * (o->N - 1);
+  o->H = c->hidden;
+  const size_t TE = size_t(o->R) * o->E;
+  o->pos_a.assign(TE * o->N * 2, 0.0);
+  o->vel_a.assign(TE * o->N * 2, 0.0);
+  o->pos_l.assign(TE * o->L * 2, 0.0);
+  o->ep_step.assign(TE, 0);
+  *out = o;
+  return 0;
+}
+
+int orc_destroy(void* h) { delete static_cast<Oracle*>(h); return 0; }
+
+int orc_set_threads(void* h, int n) {
+  if (!h || n < 1) return fail("bad thread count");
+  static_cast<Oracle*>(h)->nthreads = n;
+  return 0;
+}
+
+int orc_obs_dim(void* h) { return static_cast<Oracle*>(h)->D; }
+
+// obs: [R*E][N][D] doubles, may be null.
+int orc_observe(void* h, double* obs) {
+  Oracle& o = *static_cast<Oracle*>(h);
+  const size_t TE = size_t(o.R) * o.E;
+  for (size_t ge = 0; ge < TE; ++ge) observe_env(o, ge, obs + ge * o.N * o.D);
+  return 0;
+}
+
+int orc_reset(void* h, uint32_t seed, double* obs) {
+  if (!h) return fail("null handle");
+  Oracle& o = *static_cast<Oracle*>(h);
+  o.seed = seed;
+  o.abs_step = 0;
+  for (int run = 0; run < o.R; ++run)
+    for (int env = 0; env < o.E; ++env) reset_env(o, run, env, 0);
+  o.was_reset = true;
+  if (obs) orc_observe(h, obs);
+  return 0;
+}
+
+// actions: [R*E][N]; obs [R*E][N][D] (nullable); reward [R*E]; done [R*E].
+int orc_step(void* h, const uint8_t* actions, double* obs, double* reward, uint8_t* done) {
+  if (!h || !actions) return fail("null argument");
+  Oracle& o = *static_cast<Oracle*>(h);
+  if (!o.was_reset) return fail("step before reset");
+  const size_t TE = size_t(o.R) * o.E;
+  for (size_t ge = 0; ge < TE; ++ge) {
+    for (int i = 0; i < o.N; ++i)
+      if (actions[ge * o.N + i] >= NUM_ACTIONS) return fail("action out of range");
+  }
+  for (size_t ge = 0; ge < TE; ++ge) {
+    double r; uint8_t d;
+    step_env(o, int(ge / o.E), int(ge % o.E), o.abs_step, actions + ge * o.N, &r, &d);
+    if (reward) reward[ge] = r;
+    if (done) done[ge] = d;
+  }
+  o.abs_step += 1;
+  if (obs) orc_observe(h, obs);
+  return 0;
+}
+
+// Weights as float32, [R] leading dimension; layouts W1[D][H] b1[H] W2[H][H] b2[H] W3[H][5] b3[5].
+// All six null => no policy (uniform random actions).
+int orc_set_policy(void* h, const float* W1, const float* b1, const float* W2, const float* b2,
+                   const float* W3, const float* b3) {
+  if (!h) return fail("null handle");
+  Oracle& o = *static_cast<Oracle*>(h);
+  if (!W1 && !b1 && !W2 && !b2 && !W3 && !b3) { o.pol.set = false; return 0; }
+  if (!W1 || !b1 || !W2 || !b2 || !W3 || !b3) return fail("all six policy arrays or none");
+  if (o.H < 1) return fail("hidden width not set");
+  const bool bf = o.cfg.weight_dtype == 1;
+  auto load = [&](std::vector<double>& dst, const float* src, size_t n, bool round_it) {
+    dst.resize(n);
+    for (size_t i = 0; i < n; ++i) dst[i] = round_it ? round_to_bf16(double(src[i])) : double(src[i]);
+  };
+  const size_t R = o.R, D = o.D, H = o.H;
+  load(o.pol.W1, W1, R * D * H, bf);
+  load(o.pol.b1, b1, R * H, false);
+  load(o.pol.W2, W2, R * H * H, bf);
+  load(o.pol.b2, b2, R * H, false);
+  load(o.pol.W3, W3, R * H * NUM_ACTIONS, bf);
+  load(o.pol.b3, b3, R * NUM_ACTIONS, false);
+  o.pol.set = true;
+  return 0;
+}
+
+// Logits of the policy of `run` for n observation rows [n][D] -> [n][5].
+int orc_policy_logits(void* h, int run, const double* obs, int n, double* logits) {
+  Oracle& o = *static_cast<Oracle*>(h);
+  if (!o.pol.set) return fail("no policy");
+  if (run < 0 || run >= o.R) return fail("bad run");
+  for (int r = 0; r < n; ++r) policy_logits(o, run, obs + size_t(r) * o.D, logits + size_t(r) * NUM_ACTIONS);
+  return 0;
+}
+
+int orc_gumbel_max_action(uint32_t seed, uint32_t run, uint32_t env, uint32_t step, uint32_t agent,
+                          const double* logits) {
+  return gumbel_max_action(seed, run, env, step, agent, logits);
+}
+
+int orc_uniform_action(uint32_t seed, uint32_t run, uint32_t env, uint32_t step, uint32_t agent) {
+  return uniform_action(seed, run, env, step, agent);
+}
+
+double orc_round_to_bf16(double x) { return round_to_bf16(x); }
+
+int orc_rollout(void* h, int32_t T, double* obs_traj, uint8_t* act_traj, double* rew_traj,
+                uint8_t* done_traj, double* last_obs) {
+  if (!h || T < 1) return fail("bad argument");
+  Oracle& o = *static_cast<Oracle*>(h);
+  if (!o.was_reset) return fail("rollout before reset");
+  const size_t TE = size_t(o.R) * o.E;
+  const int nt = int(std::min<size_t>(size_t(o.nthreads), TE));
+  if (nt <= 1) {
+    rollout_range(o, 0, TE, T, obs_traj, act_traj, rew_traj, done_traj, last_obs);
+  } else {
+    // Envs are independent: contiguous env ranges on separate threads, same arithmetic.
+    std::vector<std::thread> th;
+    for (int k = 0; k < nt; ++k) {
+      const size_t g0 = TE * k / nt, g1 = TE * (k + 1) / nt;
+      th.emplace_back([&, g0, g1] {
+        rollout_range(o, g0, g1, T, obs_traj, act_traj, rew_traj, done_traj, last_obs);
+      });
+    }
+    for (auto& t : th) t.join();
+  }
+  o.abs_step += uint32_t(T);
+  return 0;
+}
+
+// State in the oracle's own layout: pos_a, vel_a [R*E][N][2]; pos_l [R*E][L][2]; ep_step [R*E].
+int orc_get_state(void* h, double* pos_a, double* vel_a, double* pos_l, int32_t* ep_step,
+                  uint32_t* abs_step) {
+  Oracle& o = *static_cast<Oracle*>(h);
+  if (pos_a) std::memcpy(pos_a, o.pos_a.data(), o.pos_a.size() * sizeof(double));
+  if (vel_a) std::memcpy(vel_a, o.vel_a.data(), o.vel_a.size() * sizeof(double));
+  if (pos_l) std::memcpy(pos_l, o.pos_l.data(), o.pos_l.size() * sizeof(double));
+  if (ep_step) std::memcpy(ep_step, o.ep_step.data(), o.ep_step.size() * sizeof(int32_t));
+  if (abs_step) *abs_step = o.abs_step;
+  return 0;
+}
+
+int orc_set_state(void* h, const double* pos_a, const double* vel_a, const double* pos_l,
+                  const int32_t* ep_step, uint32_t seed, uint32_t abs_step) {
+  if (!h || !pos_a || !vel_a || !pos_l || !ep_step) return fail("null argument");
+  Oracle& o = *static_cast<Oracle*>(h);
+  std::memcpy(o.pos_a.data(), pos_a, o.pos_a.size() * sizeof(double));
+  std::memcpy(o.vel_a.data(), vel_a, o.vel_a.size() * sizeof(double));
+  std::memcpy(o.pos_l.data(), pos_l, o.pos_l.size() * sizeof(double));
+  std::memcpy(o.ep_step.data(), ep_step, o.ep_step.size() * sizeof(int32_t));
+  o.seed = seed;
+  o.abs_step = abs_step;
+  o.was_reset = true;
+  return 0;
+}
+
+}  // extern "C"

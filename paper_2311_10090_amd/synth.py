@@ -1,0 +1,109 @@
+"""Seeded synthetic inputs and workload shapes.  Holds none of the method's arithmetic.
+
+This is the one module that both the HIP path's callers and the oracle's callers may use:
+it only draws numbers from numpy's PCG64 and names the benchmark shapes.  Initial
+environment states are NOT made here (both sides derive them from their own Philox);
+the arrays below are plain inputs that are handed to either side.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+NUM_ACTIONS = 5
+
+# Physical constants of the simple-spread workload (float32 values are what both sides see).
+PHYSICS = dict(dt=0.1, damping=0.25, mass=1.0, accel=5.0, agent_radius=0.15, landmark_radius=0.05,
+               contact_force=100.0, contact_margin=1e-3)
+MAX_EPISODE_STEPS = 25
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    num_envs: int          # envs per run
+    num_agents: int        # = num_landmarks
+    num_runs: int
+    T: int
+    hidden: int            # 0: no policy (seeded uniform actions)
+    weight_dtype: int      # 0 fp32, 1 bf16
+
+    @property
+    def obs_dim(self) -> int:
+        return 6 * self.num_agents
+
+    @property
+    def total_envs(self) -> int:
+        return self.num_envs * self.num_runs
+
+
+WORKLOADS = {
+    # small parity case: no policy, uniform actions from the seed
+    "cfg0": Workload("cfg0_64env_n3_uniform", 64, 3, 1, 100, 0, 0),
+    # fused rollout with the paper's MPE policy shape (two tanh layers of width 64)
+    "cfg1": Workload("cfg1_4096env_n3_mlp64_fp32", 4096, 3, 1, 128, 64, 0),
+    # headline throughput shape
+    "cfg2": Workload("cfg2_65536env_n3_mlp64_fp32", 65536, 3, 1, 128, 64, 0),
+    "cfg2_env": Workload("cfg2_65536env_n3_uniform", 65536, 3, 1, 128, 0, 0),
+    # scaled scenario, bf16 weights
+    "cfg3": Workload("cfg3_16384env_n10_mlp128_bf16", 16384, 10, 1, 128, 128, 1),
+    # vectorised independent runs, per-run weights
+    "cfg4": Workload("cfg4_1024runs_x64env_n3_mlp64_fp32", 64, 3, 1024, 128, 64, 0),
+}
+
+
+def physics_f32() -> dict:
+    """The constants rounded to float32 and widened again: the exact values the fp32 path uses."""
+    return {k: float(np.float32(v)) for k, v in PHYSICS.items()}
+
+
+def policy_weights(seed: int, num_runs: int, obs_dim: int, hidden: int):
+    """Per-run MLP weights, N(0, 1/fan_in), zero biases, float32.
+
+    Layouts: W1[R][D][H], b1[R][H], W2[R][H][H], b2[R][H], W3[R][H][5], b3[R][5]
+    (row-major [fan_in][fan_out]).  Run r uses PCG64(seed + r).
+    """
+    W1 = np.empty((num_runs, obs_dim, hidden), np.float32)
+    W2 = np.empty((num_runs, hidden, hidden), np.float32)
+    W3 = np.empty((num_runs, hidden, NUM_ACTIONS), np.float32)
+    for r in range(num_runs):
+        g = np.random.Generator(np.random.PCG64(seed + r))
+        W1[r] = g.standard_normal((obs_dim, hidden)) / np.sqrt(obs_dim)
+        W2[r] = g.standard_normal((hidden, hidden)) / np.sqrt(hidden)
+        W3[r] = g.standard_normal((hidden, NUM_ACTIONS)) / np.sqrt(hidden)
+    b1 = np.zeros((num_runs, hidden), np.float32)
+    b2 = np.zeros((num_runs, hidden), np.float32)
+    b3 = np.zeros((num_runs, NUM_ACTIONS), np.float32)
+    return W1, b1, W2, b2, W3, b3
+
+
+def policy_weights_with_bias(seed: int, num_runs: int, obs_dim: int, hidden: int):
+    """As policy_weights, but with non-zero biases U(-0.5, 0.5) so a dropped bias shows."""
+    W1, b1, W2, b2, W3, b3 = policy_weights(seed, num_runs, obs_dim, hidden)
+    g = np.random.Generator(np.random.PCG64(seed + 7919))
+    b1 = g.uniform(-0.5, 0.5, b1.shape).astype(np.float32)
+    b2 = g.uniform(-0.5, 0.5, b2.shape).astype(np.float32)
+    b3 = g.uniform(-0.5, 0.5, b3.shape).astype(np.float32)
+    return W1, b1, W2, b2, W3, b3
+
+
+def random_actions(seed: int, shape) -> np.ndarray:
+    g = np.random.Generator(np.random.PCG64(seed))
+    return g.integers(0, NUM_ACTIONS, size=shape, dtype=np.uint8)
+
+
+def random_state(seed: int, total_envs: int, num_agents: int, num_landmarks: int,
+                 max_episode_steps: int = MAX_EPISODE_STEPS, crowded: bool = False):
+    """Arbitrary (not reset-generated) float32-representable states for teacher-forced tests.
+
+    crowded=True draws agent positions in a small box so that most pairs are in contact.
+    Returns pos_a [TE][N][2], vel_a [TE][N][2], pos_l [TE][L][2] (float32) and ep_step [TE] int32.
+    """
+    g = np.random.Generator(np.random.PCG64(seed))
+    span = 0.25 if crowded else 1.0
+    pos_a = g.uniform(-span, span, (total_envs, num_agents, 2)).astype(np.float32)
+    vel_a = g.uniform(-1.5, 1.5, (total_envs, num_agents, 2)).astype(np.float32)
+    pos_l = g.uniform(-1.0, 1.0, (total_envs, num_landmarks, 2)).astype(np.float32)
+    ep = g.integers(0, max_episode_steps, size=total_envs, dtype=np.int32)
+    return pos_a, vel_a, pos_l, ep

@@ -1,0 +1,521 @@
+"""Pins for the CPU oracle: every oracle function is checked against something that is not
+the oracle itself -- published known-answer vectors, hand-worked transitions, closed forms,
+invariants, library routines and brute force.  CPU only."""
+import math
+from decimal import Decimal, getcontext
+
+import numpy as np
+import pytest
+
+from oracle import Oracle, OracleConfig, gumbel_max_action, philox4x32_10, round_to_bf16, uniform_action
+from tests.conftest import read_golden
+
+
+def make(N=3, L=None, E=1, **kw):
+    return Oracle(OracleConfig(num_envs=E, num_agents=N, num_landmarks=N if L is None else L, **kw))
+
+
+def put(o, pos_a, vel_a, pos_l, ep=0, seed=0, abs_step=0):
+    o.set_state(np.asarray(pos_a, float), np.asarray(vel_a, float), np.asarray(pos_l, float),
+                np.full(o.TE, ep, np.int32), seed, abs_step)
+
+
+# --------------------------------------------------------------------------- RNG (R-1)
+def test_philox_known_answer_vectors():
+    _, rows = read_golden("philox4x32_10_kat.txt")
+    assert len(rows) == 3
+    for r in rows:
+        v = [int(x, 16) for x in r]
+        out = philox4x32_10(v[0:4], v[4:6])
+        assert [int(x) for x in out] == v[6:10]
+
+
+def test_philox_counter_and_key_words_are_not_interchangeable():
+    # A transposed counter word or swapped key word must change the output.
+    base = philox4x32_10([1, 2, 3, 4], [5, 6])
+    assert not np.array_equal(base, philox4x32_10([2, 1, 3, 4], [5, 6]))
+    assert not np.array_equal(base, philox4x32_10([1, 2, 4, 3], [5, 6]))
+    assert not np.array_equal(base, philox4x32_10([1, 2, 3, 4], [6, 5]))
+
+
+def test_reset_positions_follow_the_kat_words():
+    # seed 0, run 0, env 0, step 0, entity 0, tag 0 is the all-zero KAT: words 6627e8d5, e169c58d.
+    # position = (w >> 8) * 2^-23 - 1, worked by hand from the two words.
+    o = make(N=3)
+    obs = o.reset(0)
+    x = (0x6627E8D5 >> 8) / 2.0**23 - 1.0
+    y = (0xE169C58D >> 8) / 2.0**23 - 1.0
+    assert x == -0.20190715789794922 and y == 0.7610403299331665
+    pos_a, vel_a, pos_l, ep, s = o.get_state()
+    assert pos_a[0, 0, 0] == x and pos_a[0, 0, 1] == y
+    assert np.all(vel_a == 0) and ep[0] == 0 and s == 0
+    assert obs[0, 0, 2] == x and obs[0, 0, 3] == y
+
+
+def test_reset_counter_layout_env_step_entity_run():
+    # Each field of (key = (seed, run); counter = (env, step, entity, tag=0)) lands where R-1 says.
+    o = Oracle(OracleConfig(num_envs=3, num_agents=2, num_landmarks=2, num_runs=2, env_offset=5, run_offset=7))
+    o.reset(99)
+    pos_a, _, pos_l, _, _ = o.get_state()
+    for run in range(2):
+        for env in range(3):
+            for e in range(4):
+                w = philox4x32_10([5 + env, 0, e, 0], [99, 7 + run])
+                exp = [(int(w[0]) >> 8) / 2.0**23 - 1.0, (int(w[1]) >> 8) / 2.0**23 - 1.0]
+                got = pos_a[run * 3 + env, e] if e < 2 else pos_l[run * 3 + env, e - 2]
+                assert list(got) == exp
+
+
+def test_positions_cover_minus_one_to_one_uniformly():
+    o = make(N=3, E=20000)
+    o.reset(3)
+    pos_a, _, pos_l, _, _ = o.get_state()
+    allp = np.concatenate([pos_a.ravel(), pos_l.ravel()])
+    assert allp.min() >= -1.0 and allp.max() < 1.0
+    assert abs(allp.mean()) < 0.01 and abs(allp.var() - 1.0 / 3.0) < 0.01
+    # 24-bit grid: every value is a multiple of 2^-23
+    assert np.all(allp * 2.0**23 == np.round(allp * 2.0**23))
+    # x and y, agents and landmarks are not copies of each other
+    assert abs(np.corrcoef(pos_a[:, 0, 0], pos_a[:, 0, 1])[0, 1]) < 0.03
+    assert abs(np.corrcoef(pos_a[:, 0, 0], pos_l[:, 0, 0])[0, 1]) < 0.03
+
+
+def test_uniform_action_word_and_distribution():
+    w = philox4x32_10([7, 25, 2, 1], [1234, 0])
+    assert [int(x) for x in w] == [0x4C684F2D, 0x89935CAD, 0x82544FA7, 0x39350C36]
+    assert uniform_action(1234, 0, 7, 25, 2) == (0x4C684F2D * 5) >> 32 == 1
+    counts = np.bincount([uniform_action(5, 0, e, 3, 1) for e in range(50000)], minlength=5)
+    chi2 = ((counts - 10000.0) ** 2 / 10000.0).sum()
+    assert chi2 < 18.5  # 4 dof, p ~ 1e-3
+
+
+# --------------------------------------------------------------- hand-worked example (R-3..R-8)
+def _sqrt_sum(args):
+    getcontext().prec = 40
+    return float(sum(Decimal(a).sqrt() for a in args))
+
+
+def test_hand_worked_two_step_example():
+    g, _ = read_golden("hand_worked_two_step.txt")
+    f = lambda k: np.array([float(x) for x in g[k]])
+    o = make(N=3)
+    put(o, f("pos_a").reshape(1, 3, 2), f("vel_a").reshape(1, 3, 2), f("pos_l").reshape(1, 3, 2))
+    a1 = np.array([[int(x) for x in g["actions1"]]], np.uint8)
+    obs, rew, done = o.step(a1)
+    pos_a, vel_a, pos_l, ep, s = o.get_state()
+    np.testing.assert_allclose(pos_a.ravel(), f("pos_a1"), rtol=0, atol=1e-13)
+    np.testing.assert_allclose(vel_a.ravel(), f("vel_a1"), rtol=0, atol=1e-12)
+    assert rew[0] == pytest.approx(-_sqrt_sum(g["reward1_sqrt_args"]), abs=1e-13)
+    assert rew[0] == pytest.approx(-1.5475079630, abs=1e-9)
+    np.testing.assert_allclose(obs[0, 0], f("obs0_1"), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(obs[0, 2], f("obs2_1"), rtol=0, atol=1e-12)
+    assert done[0] == 0 and ep[0] == 1 and s == 1
+    a2 = np.array([[int(x) for x in g["actions2"]]], np.uint8)
+    obs, rew, done = o.step(a2)
+    pos_a, vel_a, _, _, _ = o.get_state()
+    np.testing.assert_allclose(pos_a.ravel(), f("pos_a2"), rtol=0, atol=1e-13)
+    np.testing.assert_allclose(vel_a.ravel(), f("vel_a2"), rtol=0, atol=1e-12)
+    assert rew[0] == pytest.approx(-_sqrt_sum(g["reward2_sqrt_args"]), abs=1e-13)
+    assert rew[0] == pytest.approx(-1.4751318173, abs=1e-9)
+
+
+# ------------------------------------------------------------- contact force magnitudes (R-4)
+@pytest.mark.parametrize("d,force", [
+    (0.2, 10.0),                       # deep contact: pen = 2r - d = 0.1
+    (0.29, 1.0 + 0.1 * math.log1p(math.exp(-10.0))),   # 1.00000454
+    (0.3, 0.1 * math.log(2.0)),        # touching: 0.1 * ln 2 = 0.0693147181
+    (0.301, 0.1 * math.log1p(math.exp(-1.0))),          # 0.0313261688
+    (0.31, 0.1 * math.log1p(math.exp(-10.0))),          # 4.5399e-6
+    (0.4, 0.0),
+])
+def test_contact_force_magnitude(d, force):
+    # two agents at rest on a 3-4-5 direction; no-op actions; F = v' / dt
+    o = make(N=2)
+    ux, uy = 0.6, 0.8
+    put(o, [[[0.0, 0.0], [d * ux, d * uy]]], np.zeros((1, 2, 2)), np.zeros((1, 2, 2)))
+    o.step(np.zeros((1, 2), np.uint8))
+    _, vel_a, _, _, _ = o.get_state()
+    F = vel_a[0] / 0.1
+    assert np.hypot(*F[0]) == pytest.approx(force, rel=1e-9, abs=1e-40)
+    # agent 0 is pushed away from agent 1 (towards -u), agent 1 the opposite way, exactly
+    np.testing.assert_allclose(F[0], [-force * ux, -force * uy], rtol=1e-9, atol=1e-40)
+    assert np.array_equal(F[0], -F[1])
+
+
+def test_printed_contact_values():
+    assert 0.1 * math.log(2.0) == pytest.approx(0.0693147181, abs=1e-10)
+    assert 0.1 * math.log1p(math.exp(-1.0)) == pytest.approx(0.0313261688, abs=1e-10)
+
+
+def test_coincident_agents_give_zero_force_not_nan():
+    o = make(N=2)
+    put(o, [[[0.3, 0.3], [0.3, 0.3]]], np.zeros((1, 2, 2)), np.zeros((1, 2, 2)))
+    o.step(np.zeros((1, 2), np.uint8))
+    _, vel_a, _, _, _ = o.get_state()
+    assert np.all(vel_a == 0.0)
+
+
+def test_landmarks_do_not_collide_or_move():
+    o = make(N=1)
+    put(o, [[[0.0, 0.0]]], [[[0.0, 0.0]]], [[[0.01, 0.0]]])
+    o.step(np.zeros((1, 1), np.uint8))
+    pos_a, vel_a, pos_l, _, _ = o.get_state()
+    assert np.all(vel_a == 0) and np.all(pos_a == 0) and pos_l[0, 0, 0] == 0.01
+
+
+# --------------------------------------------------------------------- closed forms (R-3, R-5)
+def test_constant_push_closed_form():
+    # one collision-free agent, v0 = 0, constant +x action: a = accel*dt/m = 0.5, g = 0.75
+    #   v_t = 2 (1 - 0.75^t),  x_t = x0 + 0.2 t - 0.8 (1 - 0.75^t)  (position uses the OLD velocity)
+    o = make(N=1, max_episode_steps=1000)
+    x0 = -0.3
+    put(o, [[[x0, 0.1]]], [[[0.0, 0.0]]], [[[0.0, 0.0]]])
+    xs_printed = {1: 0.0, 2: 0.05, 3: 0.1375, 4: 0.253125, 5: 0.38984375}
+    for t in range(1, 40):
+        o.step(np.full((1, 1), 2, np.uint8))
+        pos_a, vel_a, _, _, _ = o.get_state()
+        assert vel_a[0, 0, 0] == pytest.approx(2.0 * (1 - 0.75**t), abs=1e-12)
+        assert pos_a[0, 0, 0] == pytest.approx(x0 + 0.2 * t - 0.8 * (1 - 0.75**t), abs=1e-12)
+        assert vel_a[0, 0, 1] == 0 and pos_a[0, 0, 1] == 0.1
+        if t in xs_printed:
+            assert pos_a[0, 0, 0] - x0 == pytest.approx(xs_printed[t], abs=1e-12)
+    assert vel_a[0, 0, 0] == pytest.approx(2.0, abs=1e-4)  # terminal speed
+
+
+@pytest.mark.parametrize("action,axis,sign", [(1, 0, -1), (2, 0, 1), (3, 1, -1), (4, 1, 1)])
+def test_action_directions(action, axis, sign):
+    o = make(N=1)
+    put(o, [[[0.0, 0.0]]], [[[0.0, 0.0]]], [[[0.0, 0.0]]])
+    o.step(np.full((1, 1), action, np.uint8))
+    _, vel_a, _, _, _ = o.get_state()
+    exp = [0.0, 0.0]
+    exp[axis] = sign * 0.5
+    assert list(vel_a[0, 0]) == pytest.approx(exp, abs=1e-15)
+
+
+def test_coasting_closed_form():
+    # no-op: v_t = v0 0.75^t, x_inf = x0 + dt v0 / damping = x0 + 0.4 v0
+    o = make(N=1, max_episode_steps=1000)
+    put(o, [[[0.1, -0.2]]], [[[1.0, -0.5]]], [[[0.0, 0.0]]])
+    for t in range(1, 200):
+        o.step(np.zeros((1, 1), np.uint8))
+        if t == 3:
+            _, vel_a, _, _, _ = o.get_state()
+            assert list(vel_a[0, 0]) == pytest.approx([0.75**3, -0.5 * 0.75**3], abs=1e-15)
+    pos_a, _, _, _, _ = o.get_state()
+    assert list(pos_a[0, 0]) == pytest.approx([0.1 + 0.4, -0.2 - 0.2], abs=1e-12)
+
+
+def test_mass_and_dt_enter_as_force_over_mass_times_dt():
+    o = make(N=1, mass=2.0, dt=0.05, accel=3.0, damping=0.5)
+    put(o, [[[0.0, 0.0]]], [[[1.0, 0.0]]], [[[0.0, 0.0]]])
+    o.step(np.full((1, 1), 4, np.uint8))
+    pos_a, vel_a, _, _, _ = o.get_state()
+    assert list(pos_a[0, 0]) == pytest.approx([0.05, 0.0], abs=1e-15)
+    assert list(vel_a[0, 0]) == pytest.approx([0.5, 3.0 / 2.0 * 0.05], abs=1e-15)
+
+
+# ------------------------------------------------------------------------- invariants
+def _random_envs(seed, E, N, crowded=False):
+    g = np.random.default_rng(seed)
+    span = 0.3 if crowded else 1.0
+    return (g.uniform(-span, span, (E, N, 2)), g.uniform(-1, 1, (E, N, 2)), g.uniform(-1, 1, (E, N, 2)))
+
+
+def test_contact_forces_antisymmetric_momentum_decays():
+    # all no-op actions: total momentum obeys P' = 0.75 P (contact forces cancel pairwise)
+    for N in (2, 3, 5, 10):
+        E = 50
+        o = make(N=N, E=E)
+        pa, va, pl = _random_envs(N, E, N, crowded=True)
+        put(o, pa, va, pl)
+        o.step(np.zeros((E, N), np.uint8))
+        _, va2, _, _, _ = o.get_state()
+        assert np.abs(va2 - 0.75 * va).max() > 0.1  # contacts really are active
+        np.testing.assert_allclose(va2.sum(axis=1), 0.75 * va.sum(axis=1), rtol=0, atol=1e-11)
+
+
+def test_reward_invariances():
+    E, N = 40, 4
+    pa, va, pl = _random_envs(11, E, N)
+    va[:] = 0
+    acts = np.zeros((E, N), np.uint8)
+
+    def reward_of(pa_, pl_):
+        o = make(N=N, E=E)
+        put(o, pa_, np.zeros_like(pa_), pl_)
+        return o.step(acts)[1]
+
+    r0 = reward_of(pa, pl)
+    assert np.all(r0 < 0)
+    np.testing.assert_allclose(reward_of(pa[:, ::-1], pl), r0, atol=1e-14)           # permute agents
+    np.testing.assert_allclose(reward_of(pa, pl[:, [2, 0, 3, 1]]), r0, atol=1e-14)   # permute landmarks
+    np.testing.assert_allclose(reward_of(pa + 0.37, pl + 0.37), r0, atol=1e-13)      # translation
+    rot = lambda p: np.stack([-p[..., 1], p[..., 0]], axis=-1)                       # 90 degrees
+    np.testing.assert_allclose(reward_of(rot(pa), rot(pl)), r0, atol=1e-14)
+    # every landmark covered exactly -> reward 0
+    assert np.all(reward_of(pl.copy(), pl) == 0.0)
+
+
+def test_reward_is_minus_sum_of_min_distances_brute_force():
+    E, N, L = 30, 5, 3
+    g = np.random.default_rng(5)
+    pa, pl = g.uniform(-1, 1, (E, N, 2)), g.uniform(-1, 1, (E, L, 2))
+    o = make(N=N, L=L, E=E)
+    put(o, pa, np.zeros_like(pa), pl)
+    rew = o.step(np.zeros((E, N), np.uint8))[1]
+    far = pa.max() - pa.min() + 10
+    # velocities are 0 and, with agents spread over [-1,1]^2, contacts may push: recompute from state
+    pa2 = o.get_state()[0]
+    for e in range(E):
+        dists = sorted((math.dist(pa2[e, i], pl[e, k]), k) for i in range(N) for k in range(L))
+        seen, total = set(), 0.0
+        for d, k in dists:  # first time a landmark shows up in the sorted list is its minimum
+            if k not in seen:
+                seen.add(k)
+                total += d
+        assert rew[e] == pytest.approx(-total, abs=1e-13)
+    assert far > 0
+
+
+def test_rotated_dynamics_match_relabelled_actions():
+    # rotating the world by 90 degrees and relabelling actions (+x -> +y, +y -> -x, ...) commutes
+    E, N = 20, 3
+    pa, va, pl = _random_envs(21, E, N, crowded=True)
+    acts = np.random.default_rng(2).integers(0, 5, (E, N)).astype(np.uint8)
+    relabel = np.array([0, 3, 4, 2, 1], np.uint8)  # -x -> -y, +x -> +y, -y -> +x, +y -> -x
+    rot = lambda p: np.stack([-p[..., 1], p[..., 0]], axis=-1)
+    o1, o2 = make(N=N, E=E), make(N=N, E=E)
+    put(o1, pa, va, pl)
+    put(o2, rot(pa), rot(va), rot(pl))
+    _, r1, _ = o1.step(acts)
+    _, r2, _ = o2.step(relabel[acts])
+    np.testing.assert_allclose(r2, r1, atol=1e-13)
+    np.testing.assert_allclose(o2.get_state()[0], rot(o1.get_state()[0]), atol=1e-13)
+    np.testing.assert_allclose(o2.get_state()[1], rot(o1.get_state()[1]), atol=1e-12)
+
+
+def test_step_matches_per_agent_sum_over_others_in_numpy():
+    # independent vectorised re-derivation: each agent sums the force from every other agent
+    E, N = 64, 6
+    pa, va, pl = _random_envs(31, E, N, crowded=True)
+    acts = np.random.default_rng(3).integers(0, 5, (E, N)).astype(np.uint8)
+    o = make(N=N, E=E)
+    put(o, pa, va, pl)
+    o.step(acts)
+    dirs = np.array([[0, 0], [-1, 0], [1, 0], [0, -1], [0, 1]], float)
+    F = 5.0 * dirs[acts]
+    delta = pa[:, :, None, :] - pa[:, None, :, :]
+    d = np.linalg.norm(delta, axis=-1)
+    x = (0.3 - d) / 1e-3
+    pen = 1e-3 * np.logaddexp(0.0, x)
+    contrib = 100.0 * pen[..., None] * delta / np.maximum(d, 1e-12)[..., None]
+    contrib[:, np.arange(N), np.arange(N)] = 0
+    F = F + contrib.sum(axis=2)
+    np.testing.assert_allclose(o.get_state()[0], pa + 0.1 * va, atol=1e-14)
+    np.testing.assert_allclose(o.get_state()[1], 0.75 * va + 0.1 * F, rtol=1e-12, atol=1e-12)
+
+
+# ------------------------------------------------------------------- observation (R-8)
+def test_observation_layout():
+    E, N, L = 10, 4, 3
+    g = np.random.default_rng(8)
+    pa, va, pl = g.uniform(-1, 1, (E, N, 2)), g.uniform(-1, 1, (E, N, 2)), g.uniform(-1, 1, (E, L, 2))
+    o = make(N=N, L=L, E=E)
+    put(o, pa, va, pl)
+    obs = o.observe()
+    D = 4 + 2 * L + 4 * (N - 1)
+    assert obs.shape == (E, N, D) and o.D == D
+    for i in range(N):
+        assert np.array_equal(obs[:, i, 0:2], va[:, i])
+        assert np.array_equal(obs[:, i, 2:4], pa[:, i])
+        # own position + landmark-relative slots give back absolute landmark positions
+        rel_l = obs[:, i, 4:4 + 2 * L].reshape(E, L, 2)
+        np.testing.assert_allclose(rel_l + pa[:, i, None, :], pl, atol=1e-15)
+        others = [j for j in range(N) if j != i]
+        rel_a = obs[:, i, 4 + 2 * L:4 + 2 * L + 2 * (N - 1)].reshape(E, N - 1, 2)
+        np.testing.assert_allclose(rel_a + pa[:, i, None, :], pa[:, others], atol=1e-15)
+        assert np.all(obs[:, i, D - 2 * (N - 1):] == 0.0)
+    assert make(N=3).D == 18 and make(N=10).D == 60
+
+
+# ---------------------------------------------------------------- done / auto-reset (R-7)
+def test_done_every_25_steps_and_reset_uses_next_step_counter():
+    E, N = 4, 3
+    o = make(N=N, E=E)
+    o.reset(77)
+    for t in range(60):
+        acts = np.full((E, N), 2, np.uint8)
+        obs, rew, done = o.step(acts)
+        if t % 25 == 24:
+            assert np.all(done == 1)
+            pos_a, vel_a, pos_l, ep, s = o.get_state()
+            assert s == t + 1 and np.all(ep == 0) and np.all(vel_a == 0)
+            for env in range(E):
+                for e in range(2 * N):
+                    w = philox4x32_10([env, t + 1, e, 0], [77, 0])
+                    exp = [(int(w[0]) >> 8) / 2.0**23 - 1.0, (int(w[1]) >> 8) / 2.0**23 - 1.0]
+                    got = pos_a[env, e] if e < N else pos_l[env, e - N]
+                    assert list(got) == exp
+            # the observation returned with done=1 is that of the new episode
+            assert np.array_equal(obs[:, :, 2:4], pos_a) and np.all(obs[:, :, 0:2] == 0)
+        else:
+            assert np.all(done == 0)
+
+
+def test_reward_at_done_is_from_the_pre_reset_state():
+    o = make(N=1, max_episode_steps=1)
+    o.reset(5)
+    put(o, [[[0.0, 0.0]]], [[[0.0, 0.0]]], [[[0.3, 0.4]]], seed=5)
+    obs, rew, done = o.step(np.zeros((1, 1), np.uint8))
+    assert done[0] == 1 and rew[0] == pytest.approx(-0.5, abs=1e-15)
+    assert o.get_state()[0][0, 0, 0] != 0.0  # already reset
+
+
+def test_rollout_equals_repeated_steps_with_uniform_actions():
+    E, N, T = 6, 3, 60
+    o1, o2 = make(N=N, E=E), make(N=N, E=E)
+    obs0 = o1.reset(9)
+    o2.reset(9)
+    obs_t, act_t, rew_t, done_t, last = o1.rollout(T)
+    cur = obs0
+    for t in range(T):
+        assert np.array_equal(obs_t[t], cur)
+        exp_act = np.array([[uniform_action(9, 0, e, t, i) for i in range(N)] for e in range(E)], np.uint8)
+        assert np.array_equal(act_t[t], exp_act)
+        cur, rew, done = o2.step(act_t[t])
+        assert np.array_equal(rew_t[t], rew) and np.array_equal(done_t[t], done)
+    assert np.array_equal(last, cur)
+    assert list(np.nonzero(done_t[:, 0])[0]) == [24, 49]
+    # threads only split the env range
+    o3 = Oracle(OracleConfig(num_envs=E, num_agents=N, num_landmarks=N), threads=3)
+    o3.reset(9)
+    r3 = o3.rollout(T)
+    assert all(np.array_equal(a, b) for a, b in zip(r3, (obs_t, act_t, rew_t, done_t, last)))
+
+
+def test_env_offset_selects_the_same_streams():
+    big = Oracle(OracleConfig(num_envs=10, num_agents=3, num_landmarks=3, num_runs=3))
+    sub = Oracle(OracleConfig(num_envs=2, num_agents=3, num_landmarks=3, num_runs=1, env_offset=4, run_offset=2))
+    big.reset(1)
+    sub.reset(1)
+    rb, rs = big.rollout(30), sub.rollout(30)
+    idx = [2 * 10 + 4, 2 * 10 + 5]
+    assert np.array_equal(rb[0][:, idx], rs[0]) and np.array_equal(rb[1][:, idx], rs[1])
+
+
+# ------------------------------------------------------------------------ policy (R-9)
+def _np_mlp(x, W1, b1, W2, b2, W3, b3):
+    x = np.asarray(x, np.float64)
+    h1 = np.tanh(x @ W1.astype(np.float64) + b1)
+    h2 = np.tanh(h1 @ W2.astype(np.float64) + b2)
+    return h2 @ W3.astype(np.float64) + b3
+
+
+def test_mlp_matches_numpy_float64_chain():
+    from paper_2311_10090_amd.synth import policy_weights_with_bias
+    for N, H in ((3, 64), (10, 128)):
+        D = 6 * N
+        w = policy_weights_with_bias(4, 2, D, H)
+        o = Oracle(OracleConfig(num_envs=1, num_agents=N, num_landmarks=N, num_runs=2, hidden=H))
+        o.set_policy(*w)
+        x = np.random.default_rng(0).uniform(-2, 2, (50, D))
+        for run in range(2):
+            ref = _np_mlp(x, *[a[run] for a in w])
+            np.testing.assert_allclose(o.policy_logits(x, run), ref, rtol=1e-12, atol=1e-13)
+
+
+def test_mlp_closed_forms():
+    N, H, D = 3, 64, 18
+    o = Oracle(OracleConfig(num_envs=1, num_agents=N, num_landmarks=N, hidden=H))
+    z = lambda *s: np.zeros(s, np.float32)
+    b3 = np.arange(5, dtype=np.float32).reshape(1, 5)
+    o.set_policy(z(1, D, H), z(1, H), z(1, H, H), z(1, H), z(1, H, 5), b3)
+    assert np.array_equal(o.policy_logits(np.ones((1, D)))[0], np.arange(5.0))
+    # one path: obs[3] -> h1[7] -> h2[11] -> logit 2 ; z = c * tanh(b * tanh(a * x))
+    W1, W2, W3 = z(1, D, H), z(1, H, H), z(1, H, 5)
+    W1[0, 3, 7], W2[0, 7, 11], W3[0, 11, 2] = 0.5, -2.0, 3.0
+    o.set_policy(W1, z(1, H), W2, z(1, H), W3, z(1, 5))
+    x = np.zeros((1, D)); x[0, 3] = 0.8
+    out = o.policy_logits(x)[0]
+    assert out[2] == pytest.approx(3.0 * math.tanh(-2.0 * math.tanh(0.4)), abs=1e-15)
+    assert np.all(out[[0, 1, 3, 4]] == 0)
+
+
+def test_bf16_rounding_matches_torch():
+    import torch
+    g = np.random.default_rng(1)
+    xs = np.concatenate([g.standard_normal(2000), g.standard_normal(2000) * 1e-3, [1.00390625, 1.01171875, 0.0, -2.5]])
+    xs32 = xs.astype(np.float32)
+    ref = torch.from_numpy(xs32).to(torch.bfloat16).to(torch.float64).numpy()
+    got = np.array([round_to_bf16(float(v)) for v in xs32])
+    assert np.array_equal(got, ref)
+    # ties to even: 1 + 2^-8 is halfway between 1 and 1 + 2^-7 -> 1 ; 1 + 3*2^-8 -> 1 + 2^-6
+    assert round_to_bf16(1.00390625) == 1.0 and round_to_bf16(1.01171875) == 1.015625
+
+
+def test_bf16_policy_matches_torch_bf16_rounded_chain():
+    import torch
+    from paper_2311_10090_amd.synth import policy_weights_with_bias
+    N, H, D = 10, 128, 60
+    w = policy_weights_with_bias(6, 1, D, H)
+    o = Oracle(OracleConfig(num_envs=1, num_agents=N, num_landmarks=N, hidden=H, weight_dtype=1))
+    o.set_policy(*w)
+    bf = lambda a: torch.from_numpy(np.asarray(a, np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    x = np.random.default_rng(0).uniform(-1, 1, (20, D)).astype(np.float32)
+    W1, b1, W2, b2, W3, b3 = [a[0] for a in w]
+    h1 = np.tanh(bf(x) @ bf(W1) + b1.astype(np.float64))
+    h2 = np.tanh(bf(h1.astype(np.float32)) @ bf(W2) + b2.astype(np.float64))
+    ref = bf(h2.astype(np.float32)) @ bf(W3) + b3.astype(np.float64)
+    # double -> bf16 directly vs double -> float32 -> bf16 can differ only on exact float32 ties
+    np.testing.assert_allclose(o.policy_logits(x.astype(np.float64)), ref, rtol=0, atol=2e-2)
+    assert np.abs(o.policy_logits(x.astype(np.float64)) - ref).mean() < 1e-3
+
+
+# ----------------------------------------------------------------------- sampler (R-10)
+def test_gumbel_max_frequencies_match_softmax():
+    z = np.array([0.3, -1.0, 1.2, 0.0, 0.5])
+    p = np.exp(z) / np.exp(z).sum()
+    n = 200000
+    counts = np.bincount([gumbel_max_action(42, 1, e, 7, 2, z) for e in range(n)], minlength=5)
+    chi2 = ((counts - n * p) ** 2 / (n * p)).sum()
+    assert chi2 < 18.5  # 4 dof, p ~ 1e-3
+
+
+def test_gumbel_max_special_cases():
+    n = 50000
+    counts = np.bincount([gumbel_max_action(1, 0, e, 0, 0, np.zeros(5)) for e in range(n)], minlength=5)
+    assert ((counts - n / 5.0) ** 2 / (n / 5.0)).sum() < 18.5
+    z = np.zeros(5); z[3] = 40.0
+    assert all(gumbel_max_action(1, 0, e, 0, 0, z) == 3 for e in range(2000))
+    # fifth action uses word 0 of the second block, not a copy of the first four
+    z = np.array([-50.0, -50.0, -50.0, -50.0, 0.0])
+    assert all(gumbel_max_action(1, 0, e, 0, 0, z) == 4 for e in range(200))
+
+
+def test_gumbel_uses_documented_words_and_transform():
+    # recompute one sample from the raw Philox words: u = (2 (w >> 9) + 1) 2^-24, g = -ln(-ln u)
+    z = np.array([0.1, 0.2, -0.3, 0.05, 0.0])
+    for env in range(300):
+        w0 = philox4x32_10([env, 12, 1, 2], [8, 3])
+        w1 = philox4x32_10([env, 12, 1, 3], [8, 3])
+        words = [int(w0[0]), int(w0[1]), int(w0[2]), int(w0[3]), int(w1[0])]
+        u = [(2 * (w >> 9) + 1) / 2.0**24 for w in words]
+        assert all(0.0 < v < 1.0 for v in u)
+        v = [z[k] - math.log(-math.log(u[k])) for k in range(5)]
+        assert gumbel_max_action(8, 3, env, 12, 1, z) == int(np.argmax(v))
+
+
+def test_policy_rollout_actions_are_sampler_of_logits_of_recorded_obs():
+    from paper_2311_10090_amd.synth import policy_weights_with_bias
+    E, N, T, H = 5, 3, 30, 64
+    w = policy_weights_with_bias(2, 1, 18, H)
+    o = Oracle(OracleConfig(num_envs=E, num_agents=N, num_landmarks=N, hidden=H))
+    o.set_policy(*w)
+    o.reset(13)
+    obs_t, act_t, rew_t, done_t, last = o.rollout(T)
+    for t in range(T):
+        logits = _np_mlp(obs_t[t].reshape(-1, 18), *[a[0] for a in w]).reshape(E, N, 5)
+        for e in range(E):
+            for i in range(N):
+                assert act_t[t, e, i] == gumbel_max_action(13, 0, e, t, i, logits[e, i])
