@@ -1,0 +1,138 @@
+/*
+ * mpe.h -- C ABI of libmpe: batched MPE simple-spread rollouts on one MI355X (gfx950).
+ *
+ * The calls follow the environment interface of JaxMARL (arXiv 2311.10090, App. C, API
+ * listing): reset(key) -> (obs, state) and step(key, state, actions) -> (obs, state,
+ * reward, done), with the state an explicit value and the random key explicit.  Here the
+ * state lives in device memory owned by the handle (readable and writable through
+ * mpe_get_state / mpe_set_state), the key is (seed, run) plus the absolute step counter,
+ * and thousands of independent environments advance in lockstep (the paper's vmap over
+ * environments, Sec. 2 "Hardware-accelerated environments").  mpe_rollout is the fused
+ * T-step loop of policy forward, sampling and environment step that the paper obtains by
+ * jit-compiling the scan of its training loop (Sec. 3.2; App. G: 128 rollout steps, two
+ * tanh layers of width 64 with parameters shared by all agents).
+ *
+ * Conventions for every function:
+ *   - returns MPE_OK (0) or a negative MPE_E* code; mpe_last_error() then describes it;
+ *   - no C++ exception crosses this boundary;
+ *   - every data pointer is a DEVICE pointer owned by the caller and at least 16-byte
+ *     aligned unless stated otherwise; the library neither frees nor keeps them after the
+ *     enqueued work has run (mpe_set_policy copies the weights into its own buffers);
+ *   - `stream` is a hipStream_t (NULL = the default stream); work is enqueued on it and the
+ *     call returns without waiting; calls on one handle must be stream-ordered by the caller;
+ *   - arguments are validated on the host before any device work is enqueued.
+ *
+ * Sizes: E = num_envs (per run), R = num_runs, TE = R*E, N = num_agents, L = num_landmarks
+ * (= N), D = 4 + 2L + 4(N-1) = 6N floats per observation, A = 5 actions.
+ * Global env index g = run*E + env.  All trajectory arrays are row-major, env-major
+ * inside a time slice: obs[t][g][agent][D], act[t][g][agent], rew[t][g], done[t][g].
+ */
+#ifndef MPE_H_
+#define MPE_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MPE_OK       0
+#define MPE_EINVAL  (-1)  /* bad config, NULL or misaligned pointer, size out of range */
+#define MPE_ESTATE  (-2)  /* call out of order: step/rollout before reset or set_state  */
+#define MPE_EHIP    (-3)  /* a HIP runtime call failed; text in mpe_last_error()        */
+
+#define MPE_NUM_ACTIONS 5
+#define MPE_MAX_AGENTS  10
+
+#define MPE_WEIGHTS_FP32 0
+#define MPE_WEIGHTS_BF16 1  /* weights and layer inputs rounded to bf16 (RNE), fp32 accumulate */
+
+typedef struct mpe_env mpe_env; /* opaque; host memory owned by the library */
+
+typedef struct {
+  int32_t num_envs;          /* E >= 1, environments per run                               */
+  int32_t num_agents;        /* N in [1, MPE_MAX_AGENTS]                                   */
+  int32_t num_landmarks;     /* L, must equal N (simple-spread)                            */
+  int32_t num_runs;          /* R >= 1 independent runs (own RNG key, own policy weights)  */
+  int32_t max_episode_steps; /* done fires on this many steps after a reset (25)           */
+  float   dt;                /* 0.1                                                        */
+  float   damping;           /* 0.25 : v <- v * (1 - damping) + (F / mass) * dt            */
+  float   mass;              /* 1                                                          */
+  float   accel;             /* 5   : control force = accel * unit direction of the action */
+  float   agent_radius;      /* 0.15: agents touch at distance 2 * agent_radius            */
+  float   landmark_radius;   /* 0.05: carried for completeness; landmarks never collide    */
+  float   contact_force;     /* 100                                                        */
+  float   contact_margin;    /* 1e-3: softness of the softplus penetration                 */
+  int32_t hidden;            /* policy width H: 64 or 128 (0 if no policy will be set)     */
+  int32_t weight_dtype;      /* MPE_WEIGHTS_FP32 or MPE_WEIGHTS_BF16                       */
+} mpe_config;
+
+/* Validate `cfg` (host only), then allocate the device state of TE environments:
+ * pos_a, vel_a [2][N][TE] fp32, pos_l [2][L][TE] fp32, ep_step [TE] int32.
+ * `*out` receives the handle.  MPE_EINVAL for a bad config, MPE_EHIP if allocation fails. */
+int mpe_create(const mpe_config* cfg, mpe_env** out);
+
+/* Free the handle and its device buffers (synchronises the device first). NULL is allowed. */
+int mpe_destroy(mpe_env* env);
+
+/* Observation length D of this handle (6N), or MPE_EINVAL for NULL. */
+int mpe_obs_dim(const mpe_env* env);
+
+/* reset(key): start every environment from the seeded initial distribution -- agent and
+ * landmark positions uniform on the 24-bit grid of [-1,1)^2, velocities 0, episode counter
+ * 0 -- drawn from Philox4x32-10 with key (seed, run) and counter (env, 0, entity, 0).
+ * Sets the absolute step counter to 0 and remembers `seed` for later calls.
+ * obs: [TE][N][D] fp32 out, may be NULL. */
+int mpe_reset(mpe_env* env, uint32_t seed, float* obs, void* stream);
+
+/* step(key, state, actions): one transition of every environment under given actions.
+ * actions: [TE][N] uint8 in, values 0..4 (0 none, 1 -x, 2 +x, 3 -y, 4 +y); a value above 4 is
+ *          treated as 0 (device data is not read back for validation).
+ * obs:     [TE][N][D] fp32 out, observation after the step (of the new episode where done),
+ *          may be NULL.
+ * reward:  [TE] fp32 out, shared by the env's agents: -sum_l min_a |p_a - p_l| after the step.
+ * done:    [TE] uint8 out, 1 when the episode reached max_episode_steps; that env has then
+ *          already been reset with counter (env, abs_step + 1, entity, 0).
+ * reward and done may be NULL.  Advances the absolute step counter by 1.
+ * MPE_ESTATE if neither mpe_reset nor mpe_set_state has been called. */
+int mpe_step(mpe_env* env, const uint8_t* actions, float* obs, float* reward, uint8_t* done,
+             void* stream);
+
+/* Install (or with all six NULL, remove) the policy used by mpe_rollout:
+ *   logits = W3^T tanh(W2^T tanh(W1^T obs + b1) + b2) + b3
+ * W1 [R][D][H], b1 [R][H], W2 [R][H][H], b2 [R][H], W3 [R][H][5], b3 [R][5], all fp32,
+ * row-major [fan_in][fan_out], device pointers.  The library copies them into its own
+ * operand layout on `stream` (rounding W to bf16, ties to even, when weight_dtype is
+ * MPE_WEIGHTS_BF16); the caller's arrays are not referenced after that work has run.
+ * MPE_EINVAL if only some pointers are NULL or the config has no usable `hidden`. */
+int mpe_set_policy(mpe_env* env, const float* W1, const float* b1, const float* W2,
+                   const float* b2, const float* W3, const float* b3, void* stream);
+
+/* T fused steps.  For t = 0..T-1: record the current observation, choose every agent's
+ * action (policy + Gumbel-max with Philox counter (env, abs_step + t, agent, 2|3); or, with
+ * no policy, uniform with counter (env, abs_step + t, agent, 1)), record it, apply the
+ * transition, record reward and done.
+ * obs_traj [T][TE][N][D] fp32, act_traj [T][TE][N] uint8, rew_traj [T][TE] fp32,
+ * done_traj [T][TE] uint8, last_obs [TE][N][D] fp32 (observation after the last step).
+ * Any of the five may be NULL (that output is then not written).
+ * T >= 1.  Advances the absolute step counter by T.  MPE_ESTATE as for mpe_step. */
+int mpe_rollout(mpe_env* env, int32_t T, float* obs_traj, uint8_t* act_traj, float* rew_traj,
+                uint8_t* done_traj, float* last_obs, void* stream);
+
+/* Copy the state out / in (device to device, on `stream`).  Layouts: pos_a, vel_a
+ * [2][N][TE], pos_l [2][L][TE] fp32 (coordinate-major, env fastest), ep_step [TE] int32.
+ * Output pointers of mpe_get_state may be NULL individually; abs_step is a HOST pointer
+ * (may be NULL).  mpe_set_state needs all four arrays, replaces seed and absolute step
+ * counter, and makes the handle steppable. */
+int mpe_get_state(mpe_env* env, float* pos_a, float* vel_a, float* pos_l, int32_t* ep_step,
+                  uint32_t* abs_step, void* stream);
+int mpe_set_state(mpe_env* env, const float* pos_a, const float* vel_a, const float* pos_l,
+                  const int32_t* ep_step, uint32_t seed, uint32_t abs_step, void* stream);
+
+/* Text of the calling thread's most recent error ("" if none). Never NULL; static storage. */
+const char* mpe_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MPE_H_ */

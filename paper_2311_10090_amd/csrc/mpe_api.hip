@@ -1,0 +1,247 @@
+// C ABI of libmpe (see include/mpe.h): handle, host-side validation, dispatch to kernels.
+#include "../../include/mpe.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "mpe_launch.h"
+
+using namespace mpe;
+
+struct mpe_env {
+  mpe_config cfg;
+  int N = 0, D = 0, H = 0;
+  uint32_t TE = 0, E = 0, R = 0;
+  Phys ph{};
+  StatePtrs st{};
+  bool ready = false;  // reset or set_state has been called
+  uint32_t seed = 0;
+  uint32_t abs_step = 0;
+  PolicyBuffers pol{};
+  bool has_policy = false;
+};
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define MPE_HIP(call)                                                                  \
+  do {                                                                                 \
+    hipError_t e_ = (call);                                                            \
+    if (e_ != hipSuccess) return fail(MPE_EHIP, "%s: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool finite_pos(float v) { return std::isfinite(v) && v > 0.0f; }
+
+int validate(const mpe_config* c) {
+  if (c->num_envs < 1) return fail(MPE_EINVAL, "num_envs must be >= 1 (got %d)", c->num_envs);
+  if (c->num_runs < 1) return fail(MPE_EINVAL, "num_runs must be >= 1 (got %d)", c->num_runs);
+  if (c->num_agents < 1 || c->num_agents > MPE_MAX_AGENTS)
+    return fail(MPE_EINVAL, "num_agents must be in [1, %d] (got %d)", MPE_MAX_AGENTS, c->num_agents);
+  if (c->num_landmarks != c->num_agents)
+    return fail(MPE_EINVAL, "simple-spread needs num_landmarks == num_agents (got %d, %d)",
+                c->num_landmarks, c->num_agents);
+  const uint64_t te = uint64_t(c->num_envs) * uint64_t(c->num_runs);
+  if (te > (1ull << 30)) return fail(MPE_EINVAL, "num_envs * num_runs must be <= 2^30");
+  if (c->max_episode_steps < 1) return fail(MPE_EINVAL, "max_episode_steps must be >= 1");
+  if (!finite_pos(c->dt) || !finite_pos(c->mass) || !finite_pos(c->contact_margin))
+    return fail(MPE_EINVAL, "dt, mass and contact_margin must be finite and > 0");
+  if (!std::isfinite(c->damping) || c->damping < 0.0f || c->damping > 1.0f)
+    return fail(MPE_EINVAL, "damping must be in [0, 1]");
+  if (!std::isfinite(c->accel) || !std::isfinite(c->contact_force) || !std::isfinite(c->agent_radius) ||
+      !std::isfinite(c->landmark_radius) || c->agent_radius < 0.0f || c->landmark_radius < 0.0f)
+    return fail(MPE_EINVAL, "accel, contact_force and radii must be finite, radii >= 0");
+  if (c->hidden != 0 && c->hidden != 64 && c->hidden != 128)
+    return fail(MPE_EINVAL, "hidden must be 0 (no policy), 64 or 128 (got %d)", c->hidden);
+  if (c->weight_dtype != MPE_WEIGHTS_FP32 && c->weight_dtype != MPE_WEIGHTS_BF16)
+    return fail(MPE_EINVAL, "weight_dtype must be MPE_WEIGHTS_FP32 or MPE_WEIGHTS_BF16");
+  return MPE_OK;
+}
+
+size_t agent_floats(const mpe_env* e) { return size_t(2) * e->N * e->TE; }
+
+}  // namespace
+
+extern "C" {
+
+const char* mpe_last_error(void) { return g_err; }
+
+int mpe_create(const mpe_config* cfg, mpe_env** out) {
+  if (!cfg || !out) return fail(MPE_EINVAL, "mpe_create: NULL argument");
+  *out = nullptr;
+  if (int rc = validate(cfg)) return rc;
+  mpe_env* e = new (std::nothrow) mpe_env();
+  if (!e) return fail(MPE_EHIP, "out of host memory");
+  e->cfg = *cfg;
+  e->N = cfg->num_agents;
+  e->D = 6 * e->N;
+  e->H = cfg->hidden;
+  e->E = uint32_t(cfg->num_envs);
+  e->R = uint32_t(cfg->num_runs);
+  e->TE = e->E * e->R;
+  // Combine constants in double, round once.
+  e->ph.dt = cfg->dt;
+  e->ph.keep = float(1.0 - double(cfg->damping));
+  e->ph.dt_over_mass = float(double(cfg->dt) / double(cfg->mass));
+  e->ph.accel = cfg->accel;
+  e->ph.two_r = float(2.0 * double(cfg->agent_radius));
+  e->ph.inv_margin = float(1.0 / double(cfg->contact_margin));
+  e->ph.force_margin = float(double(cfg->contact_force) * double(cfg->contact_margin));
+  e->ph.max_ep = cfg->max_episode_steps;
+  const size_t nf = agent_floats(e) * sizeof(float);
+  hipError_t err = hipMalloc(&e->st.pos_a, nf);
+  if (err == hipSuccess) err = hipMalloc(&e->st.vel_a, nf);
+  if (err == hipSuccess) err = hipMalloc(&e->st.pos_l, nf);
+  if (err == hipSuccess) err = hipMalloc(&e->st.ep_step, size_t(e->TE) * sizeof(int32_t));
+  if (err != hipSuccess) {
+    int rc = fail(MPE_EHIP, "mpe_create: hipMalloc failed: %s", hipGetErrorString(err));
+    (void)hipFree(e->st.pos_a); (void)hipFree(e->st.vel_a); (void)hipFree(e->st.pos_l); (void)hipFree(e->st.ep_step);
+    delete e;
+    return rc;
+  }
+  *out = e;
+  return MPE_OK;
+}
+
+int mpe_destroy(mpe_env* e) {
+  if (!e) return MPE_OK;
+  (void)hipDeviceSynchronize();
+  (void)hipFree(e->st.pos_a);
+  (void)hipFree(e->st.vel_a);
+  (void)hipFree(e->st.pos_l);
+  (void)hipFree(e->st.ep_step);
+  free_policy(e->pol);
+  delete e;
+  return MPE_OK;
+}
+
+int mpe_obs_dim(const mpe_env* e) {
+  if (!e) return fail(MPE_EINVAL, "mpe_obs_dim: NULL handle");
+  return e->D;
+}
+
+int mpe_reset(mpe_env* e, uint32_t seed, float* obs, void* stream) {
+  if (!e) return fail(MPE_EINVAL, "mpe_reset: NULL handle");
+  if (obs && !aligned16(obs)) return fail(MPE_EINVAL, "mpe_reset: obs must be 16-byte aligned");
+  launch_reset(e->N, e->st, e->TE, e->E, seed, obs, static_cast<hipStream_t>(stream));
+  MPE_HIP(hipGetLastError());
+  e->seed = seed;
+  e->abs_step = 0;
+  e->ready = true;
+  return MPE_OK;
+}
+
+int mpe_step(mpe_env* e, const uint8_t* actions, float* obs, float* reward, uint8_t* done, void* stream) {
+  if (!e) return fail(MPE_EINVAL, "mpe_step: NULL handle");
+  if (!actions) return fail(MPE_EINVAL, "mpe_step: actions is NULL");
+  if (!e->ready) return fail(MPE_ESTATE, "mpe_step: call mpe_reset or mpe_set_state first");
+  if ((obs && !aligned16(obs)) || (reward && !aligned16(reward)))
+    return fail(MPE_EINVAL, "mpe_step: obs and reward must be 16-byte aligned");
+  launch_step(e->N, e->st, e->ph, e->TE, e->E, e->seed, e->abs_step, actions, obs, reward, done,
+              static_cast<hipStream_t>(stream));
+  MPE_HIP(hipGetLastError());
+  e->abs_step += 1;
+  return MPE_OK;
+}
+
+int mpe_set_policy(mpe_env* e, const float* W1, const float* b1, const float* W2, const float* b2,
+                   const float* W3, const float* b3, void* stream) {
+  if (!e) return fail(MPE_EINVAL, "mpe_set_policy: NULL handle");
+  const int given = (W1 != nullptr) + (b1 != nullptr) + (W2 != nullptr) + (b2 != nullptr) +
+                    (W3 != nullptr) + (b3 != nullptr);
+  if (given == 0) {
+    e->has_policy = false;
+    return MPE_OK;
+  }
+  if (given != 6) return fail(MPE_EINVAL, "mpe_set_policy: pass all six arrays or none");
+  if (e->H != 64 && e->H != 128) return fail(MPE_EINVAL, "mpe_set_policy: config.hidden must be 64 or 128");
+  const char* why = nullptr;
+  hipError_t err = pack_policy(e->pol, e->N, e->H, int(e->R), e->cfg.weight_dtype, W1, b1, W2, b2, W3, b3,
+                               static_cast<hipStream_t>(stream), &why);
+  if (why) return fail(MPE_EINVAL, "mpe_set_policy: %s", why);
+  if (err != hipSuccess) return fail(MPE_EHIP, "mpe_set_policy: %s", hipGetErrorString(err));
+  e->has_policy = true;
+  return MPE_OK;
+}
+
+int mpe_rollout(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, float* rew_traj,
+                uint8_t* done_traj, float* last_obs, void* stream) {
+  if (!e) return fail(MPE_EINVAL, "mpe_rollout: NULL handle");
+  if (T < 1) return fail(MPE_EINVAL, "mpe_rollout: T must be >= 1 (got %d)", T);
+  if (!e->ready) return fail(MPE_ESTATE, "mpe_rollout: call mpe_reset or mpe_set_state first");
+  if ((obs_traj && !aligned16(obs_traj)) || (rew_traj && !aligned16(rew_traj)) ||
+      (last_obs && !aligned16(last_obs)))
+    return fail(MPE_EINVAL, "mpe_rollout: float outputs must be 16-byte aligned");
+  if (uint64_t(e->abs_step) + uint64_t(T) > 0xFFFFFFFFull)
+    return fail(MPE_EINVAL, "mpe_rollout: absolute step counter would overflow 32 bits");
+  RolloutArgs A;
+  A.st = e->st;
+  A.ph = e->ph;
+  A.TE = e->TE;
+  A.E = e->E;
+  A.seed = e->seed;
+  A.abs_step = e->abs_step;
+  A.T = T;
+  A.obs_traj = obs_traj;
+  A.act_traj = act_traj;
+  A.rew_traj = rew_traj;
+  A.done_traj = done_traj;
+  A.last_obs = last_obs;
+  if (e->has_policy) {
+    const char* why = nullptr;
+    hipError_t err = launch_rollout_policy(e->N, e->H, e->cfg.weight_dtype, A, e->pol,
+                                           static_cast<hipStream_t>(stream), &why);
+    if (why) return fail(MPE_EINVAL, "mpe_rollout: %s", why);
+    if (err != hipSuccess) return fail(MPE_EHIP, "mpe_rollout: %s", hipGetErrorString(err));
+  } else {
+    launch_rollout_uniform(e->N, A, static_cast<hipStream_t>(stream));
+  }
+  MPE_HIP(hipGetLastError());
+  e->abs_step += uint32_t(T);
+  return MPE_OK;
+}
+
+int mpe_get_state(mpe_env* e, float* pos_a, float* vel_a, float* pos_l, int32_t* ep_step,
+                  uint32_t* abs_step, void* stream) {
+  if (!e) return fail(MPE_EINVAL, "mpe_get_state: NULL handle");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t nf = agent_floats(e) * sizeof(float);
+  if (pos_a) MPE_HIP(hipMemcpyAsync(pos_a, e->st.pos_a, nf, hipMemcpyDeviceToDevice, s));
+  if (vel_a) MPE_HIP(hipMemcpyAsync(vel_a, e->st.vel_a, nf, hipMemcpyDeviceToDevice, s));
+  if (pos_l) MPE_HIP(hipMemcpyAsync(pos_l, e->st.pos_l, nf, hipMemcpyDeviceToDevice, s));
+  if (ep_step)
+    MPE_HIP(hipMemcpyAsync(ep_step, e->st.ep_step, size_t(e->TE) * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
+  if (abs_step) *abs_step = e->abs_step;
+  return MPE_OK;
+}
+
+int mpe_set_state(mpe_env* e, const float* pos_a, const float* vel_a, const float* pos_l,
+                  const int32_t* ep_step, uint32_t seed, uint32_t abs_step, void* stream) {
+  if (!e) return fail(MPE_EINVAL, "mpe_set_state: NULL handle");
+  if (!pos_a || !vel_a || !pos_l || !ep_step) return fail(MPE_EINVAL, "mpe_set_state: NULL array");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t nf = agent_floats(e) * sizeof(float);
+  MPE_HIP(hipMemcpyAsync(e->st.pos_a, pos_a, nf, hipMemcpyDeviceToDevice, s));
+  MPE_HIP(hipMemcpyAsync(e->st.vel_a, vel_a, nf, hipMemcpyDeviceToDevice, s));
+  MPE_HIP(hipMemcpyAsync(e->st.pos_l, pos_l, nf, hipMemcpyDeviceToDevice, s));
+  MPE_HIP(hipMemcpyAsync(e->st.ep_step, ep_step, size_t(e->TE) * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
+  e->seed = seed;
+  e->abs_step = abs_step;
+  e->ready = true;
+  return MPE_OK;
+}
+
+}  // extern "C"

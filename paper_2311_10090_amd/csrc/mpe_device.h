@@ -1,0 +1,294 @@
+// Device-side building blocks of libmpe (gfx950 only): Philox4x32-10, the simple-spread
+// transition of one environment held in registers, and the LDS-staged observation writer.
+//
+// The paper (JaxMARL, arXiv 2311.10090) states the MPE scenario in words only (Sec. 3.1
+// "MPE", App. B.7) and its interface in App. C; the quantitative definition implemented
+// here is the one documented in include/mpe.h and in the repository's design notes.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mpe {
+
+constexpr int kWave = 64;          // CDNA wavefront; every kernel here uses 64-thread blocks
+constexpr int kNumActions = 5;
+
+enum PhiloxTag : uint32_t { kTagResetPos = 0, kTagUniformAction = 1, kTagGumbel0 = 2, kTagGumbel1 = 3 };
+
+// Physics constants, pre-combined on the host in double and rounded once to fp32.
+struct Phys {
+  float dt;
+  float keep;           // 1 - damping
+  float dt_over_mass;   // dt / mass
+  float accel;
+  float two_r;          // 2 * agent_radius
+  float inv_margin;     // 1 / contact_margin
+  float force_margin;   // contact_force * contact_margin
+  int32_t max_ep;
+};
+
+// --------------------------------------------------------------------------------------
+// Philox4x32 with 10 rounds (Salmon et al., SC'11).  key = (seed, run),
+// counter = (env in run, absolute step, entity/agent, tag).
+// --------------------------------------------------------------------------------------
+__device__ __forceinline__ uint4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                               uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint64_t p0 = uint64_t(0xD2511F53u) * c0;
+    const uint64_t p1 = uint64_t(0xCD9E8D57u) * c2;
+    const uint32_t n0 = uint32_t(p1 >> 32) ^ c1 ^ k0;
+    const uint32_t n2 = uint32_t(p0 >> 32) ^ c3 ^ k1;
+    c1 = uint32_t(p1);
+    c3 = uint32_t(p0);
+    c0 = n0;
+    c2 = n2;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  return make_uint4(c0, c1, c2, c3);
+}
+
+// 24-bit grid on [-1, 1): exact in fp32.
+__device__ __forceinline__ float word_to_position(uint32_t w) {
+  return float(w >> 8) * (1.0f / 8388608.0f) - 1.0f;
+}
+// Odd multiples of 2^-24 in (0, 1): exact in fp32, never 0 or 1.
+__device__ __forceinline__ float word_to_open_uniform(uint32_t w) {
+  return float(2u * (w >> 9) + 1u) * (1.0f / 16777216.0f);
+}
+__device__ __forceinline__ uint32_t word_to_action(uint32_t w) { return __umulhi(w, 5u); }
+
+// --------------------------------------------------------------------------------------
+// One environment in registers.
+// --------------------------------------------------------------------------------------
+template <int N>
+struct Env {
+  float px[N], py[N], vx[N], vy[N];  // agents
+  float lx[N], ly[N];                // landmarks (L = N)
+  int32_t ep;                        // steps since the last reset
+};
+
+template <int N>
+__device__ __forceinline__ void reset_env(Env<N>& s, uint32_t seed, uint32_t run, uint32_t env,
+                                          uint32_t step) {
+#pragma unroll
+  for (int e = 0; e < N; ++e) {
+    const uint4 w = philox4x32_10(env, step, uint32_t(e), kTagResetPos, seed, run);
+    s.px[e] = word_to_position(w.x);
+    s.py[e] = word_to_position(w.y);
+    s.vx[e] = 0.0f;
+    s.vy[e] = 0.0f;
+  }
+#pragma unroll
+  for (int e = 0; e < N; ++e) {
+    const uint4 w = philox4x32_10(env, step, uint32_t(N + e), kTagResetPos, seed, run);
+    s.lx[e] = word_to_position(w.x);
+    s.ly[e] = word_to_position(w.y);
+  }
+  s.ep = 0;
+}
+
+// log(1 + exp(x)) as max(x, 0) + log(1 + exp(-|x|)); the second term is in (0, ln 2], so
+// the hardware exp2/log2 (absolute error ~1e-7 there) are accurate enough: the force picks
+// up at most ~1e-8 absolute error from them.
+__device__ __forceinline__ float softplus(float x) {
+  const float e = __expf(-fabsf(x));
+  return fmaxf(x, 0.0f) + __logf(1.0f + e);
+}
+
+// One transition under actions a[0..N): control force, pairwise softplus contacts on the
+// pre-step positions, position update with the old velocity, damped velocity update, shared
+// coverage reward on the new positions, episode counter, auto-reset keyed by step + 1.
+template <int N>
+__device__ __forceinline__ void transition(Env<N>& s, const uint32_t (&a)[N], const Phys& ph,
+                                           uint32_t seed, uint32_t run, uint32_t env, uint32_t step,
+                                           float& reward, bool& done) {
+  float fx[N], fy[N];
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    fx[i] = (a[i] == 1u) ? -ph.accel : ((a[i] == 2u) ? ph.accel : 0.0f);
+    fy[i] = (a[i] == 3u) ? -ph.accel : ((a[i] == 4u) ? ph.accel : 0.0f);
+  }
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+#pragma unroll
+    for (int j = i + 1; j < N; ++j) {
+      const float dx = s.px[i] - s.px[j];
+      const float dy = s.py[i] - s.py[j];
+      const float d = sqrtf(dx * dx + dy * dy);
+      const float sp = softplus((ph.two_r - d) * ph.inv_margin);
+      const float k = ph.force_margin * sp / fmaxf(d, 1e-12f);
+      fx[i] += k * dx;
+      fy[i] += k * dy;
+      fx[j] -= k * dx;
+      fy[j] -= k * dy;
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    s.px[i] += s.vx[i] * ph.dt;
+    s.py[i] += s.vy[i] * ph.dt;
+    s.vx[i] = s.vx[i] * ph.keep + fx[i] * ph.dt_over_mass;
+    s.vy[i] = s.vy[i] * ph.keep + fy[i] * ph.dt_over_mass;
+  }
+  float r = 0.0f;
+#pragma unroll
+  for (int l = 0; l < N; ++l) {
+    float best2 = INFINITY;  // sqrt is monotone: take the min of squared distances, one sqrt
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const float dx = s.px[i] - s.lx[l];
+      const float dy = s.py[i] - s.ly[l];
+      best2 = fminf(best2, dx * dx + dy * dy);
+    }
+    r -= sqrtf(best2);
+  }
+  reward = r;
+  s.ep += 1;
+  done = s.ep >= ph.max_ep;
+  if (done) reset_env<N>(s, seed, run, env, step + 1u);
+}
+
+// --------------------------------------------------------------------------------------
+// SoA state in HBM: pos_a, vel_a [2][N][TE]; pos_l [2][N][TE]; ep_step [TE].
+// --------------------------------------------------------------------------------------
+struct StatePtrs {
+  float* pos_a;
+  float* vel_a;
+  float* pos_l;
+  int32_t* ep_step;
+};
+
+template <int N>
+__device__ __forceinline__ void load_state(Env<N>& s, const StatePtrs& st, size_t TE, size_t g) {
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    s.px[i] = st.pos_a[(0 * N + i) * TE + g];
+    s.py[i] = st.pos_a[(1 * N + i) * TE + g];
+    s.vx[i] = st.vel_a[(0 * N + i) * TE + g];
+    s.vy[i] = st.vel_a[(1 * N + i) * TE + g];
+    s.lx[i] = st.pos_l[(0 * N + i) * TE + g];
+    s.ly[i] = st.pos_l[(1 * N + i) * TE + g];
+  }
+  s.ep = st.ep_step[g];
+}
+
+template <int N>
+__device__ __forceinline__ void store_state(const Env<N>& s, const StatePtrs& st, size_t TE, size_t g) {
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    st.pos_a[(0 * N + i) * TE + g] = s.px[i];
+    st.pos_a[(1 * N + i) * TE + g] = s.py[i];
+    st.vel_a[(0 * N + i) * TE + g] = s.vx[i];
+    st.vel_a[(1 * N + i) * TE + g] = s.vy[i];
+    st.pos_l[(0 * N + i) * TE + g] = s.lx[i];
+    st.pos_l[(1 * N + i) * TE + g] = s.ly[i];
+  }
+  st.ep_step[g] = s.ep;
+}
+
+template <int N>
+__device__ __forceinline__ void zero_env(Env<N>& s) {
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    s.px[i] = s.py[i] = s.vx[i] = s.vy[i] = s.lx[i] = s.ly[i] = 0.0f;
+  }
+  s.ep = 0;
+}
+
+// --------------------------------------------------------------------------------------
+// Observation writer.  A lane owns one env; its N*D floats are contiguous in the output
+// ([g][agent][D]) but lanes are N*D*4 bytes apart, so direct stores would be dword
+// scatters.  Instead each lane drops its float2 pairs into a per-wave LDS tile and the wave
+// then streams the tile out with 16-byte (or 8-byte, when alignment forbids) stores that
+// cover whole cache lines.
+//   N <= 3 : the tile holds all agents, [lane][N*D]; the wave's output block is one
+//            contiguous run of nvalid*N*D floats.
+//   N  > 3 : one agent at a time, tile [lane][D]; rows of D floats, N*D apart in the output.
+// The block is one wavefront, so __syncthreads() is only a wave-level LDS fence.
+// --------------------------------------------------------------------------------------
+template <int N>
+struct ObsTile {
+  static constexpr int D = 6 * N;
+  static constexpr bool kFull = (N <= 3);
+  static constexpr int kRow = kFull ? N * D : D;  // floats per lane in the tile
+  static constexpr int kFloats = kWave * kRow;
+};
+
+// Agent i's observation of env state s, as D/2 float2 pairs written to row[0..D).
+template <int N>
+__device__ __forceinline__ void build_agent_obs(const Env<N>& s, int i, float2* row) {
+  int c = 0;
+  row[c++] = make_float2(s.vx[i], s.vy[i]);
+  row[c++] = make_float2(s.px[i], s.py[i]);
+#pragma unroll
+  for (int l = 0; l < N; ++l) row[c++] = make_float2(s.lx[l] - s.px[i], s.ly[l] - s.py[i]);
+#pragma unroll
+  for (int j = 0; j < N; ++j) {
+    if (j == i) continue;
+    row[c++] = make_float2(s.px[j] - s.px[i], s.py[j] - s.py[i]);
+  }
+#pragma unroll
+  for (int z = 0; z < N - 1; ++z) row[c++] = make_float2(0.0f, 0.0f);
+}
+
+// Stream `nfloats` (even) contiguous floats from the LDS tile to dst.  vec4 requires dst to
+// be 16-byte aligned; otherwise 8-byte stores are used.
+__device__ __forceinline__ void stream_out(const float* tile, float* dst, int nfloats, bool vec4, int lane) {
+  if (vec4) {
+    const int n4 = nfloats >> 2;
+    for (int j = lane; j < n4; j += kWave)
+      reinterpret_cast<float4*>(dst)[j] = reinterpret_cast<const float4*>(tile)[j];
+    if ((nfloats & 2) && lane == 0)
+      reinterpret_cast<float2*>(dst)[nfloats / 2 - 1] = reinterpret_cast<const float2*>(tile)[nfloats / 2 - 1];
+  } else {
+    const int n2 = nfloats >> 1;
+    for (int j = lane; j < n2; j += kWave)
+      reinterpret_cast<float2*>(dst)[j] = reinterpret_cast<const float2*>(tile)[j];
+  }
+}
+
+// Write the observations of the wave's envs [g0, g0 + nvalid) to obs ([TE][N][D] slice).
+// 16-byte stores are used whenever the destination rows are 16-byte aligned.
+template <int N>
+__device__ __forceinline__ void emit_obs(const Env<N>& s, float* tile, float* obs, size_t g0,
+                                         int nvalid, int lane) {
+  using OT = ObsTile<N>;
+  constexpr int D = OT::D;
+  if constexpr (OT::kFull) {
+    float2* row = reinterpret_cast<float2*>(tile + lane * OT::kRow);
+#pragma unroll
+    for (int i = 0; i < N; ++i) build_agent_obs<N>(s, i, row + i * (D / 2));
+    __syncthreads();
+    float* dst = obs + g0 * (N * D);
+    const bool vec4 = (reinterpret_cast<uintptr_t>(dst) & 15u) == 0;
+    stream_out(tile, dst, nvalid * N * D, vec4, lane);
+    __syncthreads();
+  } else {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      build_agent_obs<N>(s, i, reinterpret_cast<float2*>(tile + lane * D));
+      __syncthreads();
+      float* dst = obs + (g0 * N + i) * D;
+      const bool vec4 = (D % 4 == 0) && (reinterpret_cast<uintptr_t>(dst) & 15u) == 0;
+      if (vec4) {
+        constexpr int Q = (D % 4 == 0) ? D / 4 : 1;
+        for (int j = lane; j < nvalid * Q; j += kWave) {
+          const int e = j / Q, q = j - e * Q;
+          reinterpret_cast<float4*>(dst + size_t(e) * N * D)[q] = reinterpret_cast<const float4*>(tile + e * D)[q];
+        }
+      } else {
+        constexpr int Q = D / 2;
+        for (int j = lane; j < nvalid * Q; j += kWave) {
+          const int e = j / Q, q = j - e * Q;
+          reinterpret_cast<float2*>(dst + size_t(e) * N * D)[q] = reinterpret_cast<const float2*>(tile + e * D)[q];
+        }
+      }
+      __syncthreads();
+    }
+  }
+}
+
+}  // namespace mpe

@@ -1,0 +1,44 @@
+// Host-side launch interface between the C ABI (mpe_api.hip) and the kernel files.
+#pragma once
+
+#include "mpe_device.h"
+
+namespace mpe {
+
+struct RolloutArgs {
+  StatePtrs st;
+  Phys ph;
+  uint32_t TE;        // total envs = runs * envs per run
+  uint32_t E;         // envs per run
+  uint32_t seed;
+  uint32_t abs_step;  // absolute step of the first transition
+  int32_t T;
+  float* obs_traj;    // [T][TE][N][D] or null
+  uint8_t* act_traj;  // [T][TE][N]    or null
+  float* rew_traj;    // [T][TE]       or null
+  uint8_t* done_traj; // [T][TE]       or null
+  float* last_obs;    // [TE][N][D]    or null
+};
+
+void launch_reset(int N, const StatePtrs& st, uint32_t TE, uint32_t E, uint32_t seed, float* obs,
+                  hipStream_t s);
+void launch_step(int N, const StatePtrs& st, const Phys& ph, uint32_t TE, uint32_t E, uint32_t seed,
+                 uint32_t abs_step, const uint8_t* actions, float* obs, float* reward, uint8_t* done,
+                 hipStream_t s);
+void launch_rollout_uniform(int N, const RolloutArgs& A, hipStream_t s);
+
+// Policy weights re-packed into MFMA A-operand order (device memory owned by the handle).
+struct PolicyBuffers {
+  void* packed = nullptr;
+  size_t bytes = 0;
+};
+
+// Both return a HIP status; *why is set (and nothing launched) when the shape is unsupported.
+hipError_t pack_policy(PolicyBuffers& pb, int N, int H, int R, int weight_dtype, const float* W1,
+                       const float* b1, const float* W2, const float* b2, const float* W3,
+                       const float* b3, hipStream_t s, const char** why);
+hipError_t launch_rollout_policy(int N, int H, int weight_dtype, const RolloutArgs& A,
+                                 const PolicyBuffers& pb, hipStream_t s, const char** why);
+void free_policy(PolicyBuffers& pb);
+
+}  // namespace mpe

@@ -1,0 +1,587 @@
+// Fused rollout: policy MLP forward (MFMA) -> Gumbel-max sampling (Philox) -> environment
+// transition -> reward / auto-reset -> observation, T times inside one persistent kernel.
+//
+// Mapping.  A block owns EB consecutive environments; one lane owns one AGENT (row =
+// env_local * N + agent), so a wavefront is 64 consecutive agent rows = four 16-row MFMA
+// tiles.  The block keeps the current observations of its rows in an LDS tile that serves
+// three readers: the coalesced 16-byte trajectory stores, the B operands of layer 1, and
+// nothing else -- environment state itself stays in registers for all T steps.
+//
+// MLP on the matrix cores, transposed: H^T[hidden x rows] = W^T[hidden x in] * X^T[in x rows].
+// With v_mfma_f32_16x16x4_f32 (and v_mfma_f32_16x16x32_bf16) the accumulator layout of one
+// layer -- lane l holds column (row of the batch) l%16 and hidden units 16m + 4(l/16) + r --
+// is exactly a B-operand layout for the next layer once the weights are stored with the
+// matching K order, so activations never leave registers between layers.  Weights are
+// packed once (mpe_set_policy) into that A-operand order and staged in LDS per block.
+//
+// Policy shape follows the paper's MPE setting (App. G, IPPO table: two tanh layers of width
+// 64, parameters shared by all agents; Sec. 3.2 "PPO"); the scaled scenario uses width 128
+// with bf16 operands and fp32 accumulation.
+#include "mpe_launch.h"
+
+namespace mpe {
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+__host__ __device__ constexpr int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+template <int N, int H, bool BF16>
+struct Shape {
+  static constexpr int D = 6 * N;
+  static constexpr int KIN = 4 * N + 2;           // non-zero leading entries of an observation
+  static constexpr int KS = BF16 ? 32 : 4;        // K extent of one MFMA
+  static constexpr int MT = H / 16;               // 16-wide tiles of hidden units
+  static constexpr int S1 = cdiv(KIN, KS);        // K slices of layer 1
+  static constexpr int S2 = H / KS;               // K slices of layers 2 and 3
+  static constexpr int ELT = BF16 ? 2 : 4;        // bytes per weight
+  static constexpr int LANE_ELTS = BF16 ? 8 : 1;  // A-operand elements one lane holds per MFMA
+  // packed buffer sections (bytes), all multiples of 16
+  static constexpr size_t W1A_BYTES = size_t(MT) * S1 * 64 * LANE_ELTS * ELT;
+  static constexpr size_t W2A_BYTES = size_t(MT) * S2 * 64 * LANE_ELTS * ELT;
+  static constexpr size_t W3A_BYTES = size_t(S2) * 64 * LANE_ELTS * ELT;
+  static constexpr size_t BIAS_BYTES = size_t(2 * H + 16) * 4;
+  static constexpr size_t OFF_W1A = 0;
+  static constexpr size_t OFF_W2A = OFF_W1A + W1A_BYTES;
+  static constexpr size_t OFF_W3A = OFF_W2A + W2A_BYTES;
+  static constexpr size_t OFF_BIAS = OFF_W3A + W3A_BYTES;
+  static constexpr size_t RUN_BYTES = OFF_BIAS + BIAS_BYTES;
+};
+
+// Hidden unit that K position (slice s, lane group gq, element e) of layers 2/3 refers to:
+// the accumulator register (tile m, r) of lane group gq holds unit 16m + 4gq + r.
+template <bool BF16>
+__host__ __device__ constexpr int hidden_of(int s, int gq, int e) {
+  return BF16 ? (32 * s + 16 * (e / 4) + 4 * gq + (e % 4)) : (16 * (s / 4) + 4 * gq + (s % 4));
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return uint16_t((u >> 16) | 0x40u);  // NaN stays NaN
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return uint16_t(u >> 16);
+}
+
+// One thread per packed element of one run.
+template <int N, int H, bool BF16>
+__global__ void pack_policy_kernel(uint8_t* __restrict__ packed, const float* __restrict__ W1,
+                                   const float* __restrict__ b1, const float* __restrict__ W2,
+                                   const float* __restrict__ b2, const float* __restrict__ W3,
+                                   const float* __restrict__ b3) {
+  using S = Shape<N, H, BF16>;
+  const int run = blockIdx.y;
+  uint8_t* out = packed + size_t(run) * S::RUN_BYTES;
+  W1 += size_t(run) * S::D * H;
+  b1 += size_t(run) * H;
+  W2 += size_t(run) * H * H;
+  b2 += size_t(run) * H;
+  W3 += size_t(run) * H * kNumActions;
+  b3 += size_t(run) * kNumActions;
+  const int n1 = S::MT * S::S1 * 64 * S::LANE_ELTS;
+  const int n2 = S::MT * S::S2 * 64 * S::LANE_ELTS;
+  const int n3 = S::S2 * 64 * S::LANE_ELTS;
+  const int nb = 2 * H + 16;
+  int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  auto put = [&](size_t off, int i, float v) {
+    if (BF16) reinterpret_cast<uint16_t*>(out + off)[i] = f32_to_bf16_rne(v);
+    else reinterpret_cast<float*>(out + off)[i] = v;
+  };
+  if (idx < n1) {
+    // [m][s][lane][e] ; lane (i = lane%16, gq = lane/16) ; k = KS*s + LANE_ELTS*gq + e (natural order)
+    const int e = idx % S::LANE_ELTS, lane = (idx / S::LANE_ELTS) % 64;
+    const int s = (idx / (S::LANE_ELTS * 64)) % S::S1, m = idx / (S::LANE_ELTS * 64 * S::S1);
+    const int k = S::KS * s + S::LANE_ELTS * (lane / 16) + e;
+    const int o = 16 * m + lane % 16;
+    put(S::OFF_W1A, idx, k < S::KIN ? W1[size_t(k) * H + o] : 0.0f);
+    return;
+  }
+  idx -= n1;
+  if (idx < n2) {
+    int m, s, lane, e;
+    if (BF16) {  // [m][s][lane][8]
+      e = idx % 8; lane = (idx / 8) % 64; s = (idx / 512) % S::S2; m = idx / (512 * S::S2);
+    } else {     // [m][s/4][lane][s%4]
+      const int s_lo = idx % 4; lane = (idx / 4) % 64; const int s_hi = (idx / 256) % (S::S2 / 4);
+      m = idx / (256 * (S::S2 / 4)); s = 4 * s_hi + s_lo; e = 0;
+    }
+    const int k = hidden_of<BF16>(s, lane / 16, e);
+    put(S::OFF_W2A, idx, W2[size_t(k) * H + 16 * m + lane % 16]);
+    return;
+  }
+  idx -= n2;
+  if (idx < n3) {
+    int s, lane, e;
+    if (BF16) { e = idx % 8; lane = (idx / 8) % 64; s = idx / 512; }
+    else { const int s_lo = idx % 4; lane = (idx / 4) % 64; s = 4 * (idx / 256) + s_lo; e = 0; }
+    const int k = hidden_of<BF16>(s, lane / 16, e);
+    const int o = lane % 16;
+    put(S::OFF_W3A, idx, o < kNumActions ? W3[size_t(k) * kNumActions + o] : 0.0f);
+    return;
+  }
+  idx -= n3;
+  if (idx < nb) {
+    float v;
+    if (idx < H) v = b1[idx];
+    else if (idx < 2 * H) v = b2[idx - H];
+    else v = (idx - 2 * H) < kNumActions ? b3[idx - 2 * H] : 0.0f;
+    reinterpret_cast<float*>(out + S::OFF_BIAS)[idx] = v;
+  }
+}
+
+// tanh(x) = 1 - 2 / (exp(2x) + 1) on the hardware exp2 / rcp units.  Absolute error ~1e-7;
+// saturates cleanly (exp2 -> inf gives 1, exp2 -> 0 gives -1).
+__device__ __forceinline__ float fast_tanh(float x) {
+  const float t = __builtin_amdgcn_exp2f(x * 2.8853900817779268f);
+  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(t + 1.0f);
+}
+
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Gumbel-max over 5 logits: g = -ln(-ln u), u odd multiples of 2^-24 from two Philox blocks.
+__device__ __forceinline__ uint32_t gumbel_argmax(const float (&z)[kNumActions], uint32_t seed,
+                                                  uint32_t run, uint32_t env, uint32_t step, uint32_t agent) {
+  const uint4 w0 = philox4x32_10(env, step, agent, kTagGumbel0, seed, run);
+  const uint4 w1 = philox4x32_10(env, step, agent, kTagGumbel1, seed, run);
+  const uint32_t w[kNumActions] = {w0.x, w0.y, w0.z, w0.w, w1.x};
+  uint32_t best = 0;
+  float best_v = -INFINITY;
+#pragma unroll
+  for (int k = 0; k < kNumActions; ++k) {
+    const float u = word_to_open_uniform(w[k]);
+    const float v = z[k] - __logf(-logf(u));
+    if (v > best_v) { best_v = v; best = uint32_t(k); }
+  }
+  return best;
+}
+
+// LDS plan of one block (bytes).
+template <int N, int H, bool BF16, int EB>
+struct Smem {
+  using S = Shape<N, H, BF16>;
+  static constexpr int ROWS = EB * N;
+  static constexpr size_t WEIGHTS = S::RUN_BYTES;
+  static constexpr size_t OBS = size_t(ROWS) * S::D * 4 + 64;  // + zeroed tail for K padding reads
+  static constexpr size_t Z = size_t(ROWS) * 5 * 4;
+  static constexpr size_t NEWPOS = size_t(ROWS) * 8;
+  static constexpr size_t DMIN = size_t(ROWS) * 4;
+  static constexpr size_t OFF_OBS = (WEIGHTS + 15) & ~size_t(15);
+  static constexpr size_t OFF_Z = OFF_OBS + ((OBS + 15) & ~size_t(15));
+  static constexpr size_t OFF_NEWPOS = OFF_Z + ((Z + 15) & ~size_t(15));
+  static constexpr size_t OFF_DMIN = OFF_NEWPOS + ((NEWPOS + 15) & ~size_t(15));
+  static constexpr size_t TOTAL = OFF_DMIN + ((DMIN + 15) & ~size_t(15));
+};
+
+// MLP forward of one 16-row tile; rows' observations are in the LDS tile at obs_rows
+// (row stride D floats).  Leaves logits of row j in zrow[j*5 .. j*5+4].
+template <int N, int H, bool BF16>
+__device__ __forceinline__ void policy_tile(const uint8_t* __restrict__ wsm, const float* __restrict__ obs_rows,
+                                            float* __restrict__ zrows, int lane) {
+  using S = Shape<N, H, BF16>;
+  constexpr int D = S::D, MT = S::MT;
+  const int j = lane & 15, gq = lane >> 4;
+  const float* bias = reinterpret_cast<const float*>(wsm + S::OFF_BIAS);
+  f32x4 acc[MT];
+  f32x4 hid[MT];
+#pragma unroll
+  for (int m = 0; m < MT; ++m) acc[m] = *reinterpret_cast<const f32x4*>(bias + 16 * m + 4 * gq);
+  // ---- layer 1
+  if constexpr (!BF16) {
+    const float* w1 = reinterpret_cast<const float*>(wsm + S::OFF_W1A);
+#pragma unroll
+    for (int s = 0; s < S::S1; ++s) {
+      const float b = obs_rows[j * D + 4 * s + gq];
+#pragma unroll
+      for (int m = 0; m < MT; ++m)
+        acc[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(w1[(m * S::S1 + s) * 64 + lane], b, acc[m], 0, 0, 0);
+    }
+  } else {
+    const bf16x8* w1 = reinterpret_cast<const bf16x8*>(wsm + S::OFF_W1A);
+#pragma unroll
+    for (int s = 0; s < S::S1; ++s) {
+      const float* src = obs_rows + j * D + 32 * s + 8 * gq;
+      const f32x4 lo = *reinterpret_cast<const f32x4*>(src);
+      const f32x4 hi = *reinterpret_cast<const f32x4*>(src + 4);
+      bf16x8 b;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { b[e] = __bf16(lo[e]); b[4 + e] = __bf16(hi[e]); }
+#pragma unroll
+      for (int m = 0; m < MT; ++m)
+        acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1[(m * S::S1 + s) * 64 + lane], b, acc[m], 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int m = 0; m < MT; ++m) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) hid[m][r] = fast_tanh(acc[m][r]);
+    acc[m] = *reinterpret_cast<const f32x4*>(bias + H + 16 * m + 4 * gq);
+  }
+  // ---- layer 2
+  if constexpr (!BF16) {
+    const f32x4* w2 = reinterpret_cast<const f32x4*>(wsm + S::OFF_W2A);
+#pragma unroll
+    for (int s4 = 0; s4 < S::S2 / 4; ++s4) {
+      f32x4 a[MT];
+#pragma unroll
+      for (int m = 0; m < MT; ++m) a[m] = w2[(m * (S::S2 / 4) + s4) * 64 + lane];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+          acc[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[m][r], hid[s4][r], acc[m], 0, 0, 0);
+      }
+    }
+  } else {
+    const bf16x8* w2 = reinterpret_cast<const bf16x8*>(wsm + S::OFF_W2A);
+#pragma unroll
+    for (int s = 0; s < S::S2; ++s) {
+      bf16x8 b;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { b[e] = __bf16(hid[2 * s][e]); b[4 + e] = __bf16(hid[2 * s + 1][e]); }
+#pragma unroll
+      for (int m = 0; m < MT; ++m)
+        acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w2[(m * S::S2 + s) * 64 + lane], b, acc[m], 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int m = 0; m < MT; ++m) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) hid[m][r] = fast_tanh(acc[m][r]);
+  }
+  // ---- layer 3 (5 outputs padded to one 16-wide tile); two accumulators break the chain
+  f32x4 z0 = *reinterpret_cast<const f32x4*>(bias + 2 * H + 4 * gq);
+  f32x4 z1 = {0.0f, 0.0f, 0.0f, 0.0f};
+  if constexpr (!BF16) {
+    const f32x4* w3 = reinterpret_cast<const f32x4*>(wsm + S::OFF_W3A);
+#pragma unroll
+    for (int s4 = 0; s4 < S::S2 / 4; ++s4) {
+      const f32x4 a = w3[s4 * 64 + lane];
+      z0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], hid[s4][0], z0, 0, 0, 0);
+      z1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], hid[s4][1], z1, 0, 0, 0);
+      z0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], hid[s4][2], z0, 0, 0, 0);
+      z1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], hid[s4][3], z1, 0, 0, 0);
+    }
+  } else {
+    const bf16x8* w3 = reinterpret_cast<const bf16x8*>(wsm + S::OFF_W3A);
+#pragma unroll
+    for (int s = 0; s < S::S2; ++s) {
+      bf16x8 b;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { b[e] = __bf16(hid[2 * s][e]); b[4 + e] = __bf16(hid[2 * s + 1][e]); }
+      if (s & 1) z1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w3[s * 64 + lane], b, z1, 0, 0, 0);
+      else z0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w3[s * 64 + lane], b, z0, 0, 0, 0);
+    }
+  }
+  z0 += z1;
+  // lane (j, gq) holds outputs 4gq + r of row j: outputs 0..3 in group 0, output 4 in group 1
+  if (gq == 0) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) zrows[j * 5 + r] = z0[r];
+  } else if (gq == 1) {
+    zrows[j * 5 + 4] = z0[0];
+  }
+}
+
+template <int N, int H, bool BF16, int EB>
+__global__ __launch_bounds__(EB * N) void rollout_policy_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
+                                                                int per_run_weights) {
+  using S = Shape<N, H, BF16>;
+  using M = Smem<N, H, BF16, EB>;
+  constexpr int D = S::D, ROWS = EB * N, THREADS = ROWS;
+  static_assert(THREADS % 64 == 0, "block must be whole wavefronts");
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+  uint8_t* wsm = smem;
+  float* tile = reinterpret_cast<float*>(smem + M::OFF_OBS);
+  float* zbuf = reinterpret_cast<float*>(smem + M::OFF_Z);
+  float2* newpos = reinterpret_cast<float2*>(smem + M::OFF_NEWPOS);
+  float* dminbuf = reinterpret_cast<float*>(smem + M::OFF_DMIN);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int el = tid / N, i = tid - el * N;          // env within block, agent
+  const size_t TE = A.TE;
+  const size_t g0 = size_t(blockIdx.x) * EB;
+  const size_t g = g0 + el;
+  const bool valid = g < TE;
+  const uint32_t gc = valid ? uint32_t(g) : uint32_t(g0);
+  const uint32_t run = gc / A.E;
+  const uint32_t env = gc - run * A.E;
+  const size_t left = TE - g0;
+  const int nvalid = left < size_t(EB) ? int(left) : EB;   // valid envs in this block
+
+  // ---- stage this block's weights (the run of its first env) in LDS
+  {
+    const uint32_t run0 = uint32_t(g0) / A.E;
+    const uint4* src = reinterpret_cast<const uint4*>(packed + (per_run_weights ? size_t(run0) * S::RUN_BYTES : 0));
+    uint4* dst = reinterpret_cast<uint4*>(wsm);
+    for (int k = tid; k < int(S::RUN_BYTES / 16); k += THREADS) dst[k] = src[k];
+    if (tid < 16) tile[ROWS * D + tid] = 0.0f;
+  }
+
+  // ---- registers: own agent, all agents' positions, all landmarks
+  float px, py, vx, vy;
+  float qx[N], qy[N], lx[N], ly[N];
+  int32_t ep;
+  if (valid) {
+#pragma unroll
+    for (int a = 0; a < N; ++a) {
+      qx[a] = A.st.pos_a[(0 * N + a) * TE + g];
+      qy[a] = A.st.pos_a[(1 * N + a) * TE + g];
+      lx[a] = A.st.pos_l[(0 * N + a) * TE + g];
+      ly[a] = A.st.pos_l[(1 * N + a) * TE + g];
+    }
+    vx = A.st.vel_a[(0 * N + i) * TE + g];
+    vy = A.st.vel_a[(1 * N + i) * TE + g];
+    ep = A.st.ep_step[g];
+  } else {
+#pragma unroll
+    for (int a = 0; a < N; ++a) qx[a] = qy[a] = lx[a] = ly[a] = 0.0f;
+    vx = vy = 0.0f;
+    ep = 0;
+  }
+  px = py = 0.0f;
+#pragma unroll
+  for (int a = 0; a < N; ++a) {
+    if (a == i) { px = qx[a]; py = qy[a]; }
+  }
+
+  // Write this lane's observation row into the tile (zeros of the comm slots included).
+  auto write_obs_row = [&](bool with_zeros) {
+    float2* row = reinterpret_cast<float2*>(tile + tid * D);
+    int c = 0;
+    row[c++] = make_float2(vx, vy);
+    row[c++] = make_float2(px, py);
+#pragma unroll
+    for (int l = 0; l < N; ++l) row[c++] = make_float2(lx[l] - px, ly[l] - py);
+#pragma unroll
+    for (int a = 0; a < N; ++a) {
+      if (a != i) row[c++] = make_float2(qx[a] - px, qy[a] - py);
+    }
+    if (with_zeros) {
+      for (int zc = 0; zc < N - 1; ++zc) row[c + zc] = make_float2(0.0f, 0.0f);
+    }
+  };
+  write_obs_row(true);
+
+  float dmin_prev = 0.0f;  // unused before t = 1
+  bool done_prev = false;
+  (void)dmin_prev;
+
+  const int n_out_floats = nvalid * N * D;  // floats of one time slice this block writes
+
+  for (int t = 0; t <= A.T; ++t) {
+    __syncthreads();  // (A) tile, dminbuf complete
+    // reward and done of the step finished in the previous iteration
+    if (t > 0 && i == 0 && valid) {
+      float r = 0.0f;
+#pragma unroll
+      for (int a = 0; a < N; ++a) r -= dminbuf[el * N + a];
+      if (A.rew_traj) A.rew_traj[size_t(t - 1) * TE + g] = r;
+      if (A.done_traj) A.done_traj[size_t(t - 1) * TE + g] = done_prev ? 1 : 0;
+    }
+    // stream the tile out: obs_traj[t] for t < T, last_obs at t == T
+    {
+      float* dst = (t < A.T) ? (A.obs_traj ? A.obs_traj + (size_t(t) * TE + g0) * (N * D) : nullptr)
+                             : (A.last_obs ? A.last_obs + g0 * (N * D) : nullptr);
+      if (dst) {
+        if ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
+          const int n4 = n_out_floats >> 2;
+          for (int k = tid; k < n4; k += THREADS)
+            reinterpret_cast<float4*>(dst)[k] = reinterpret_cast<const float4*>(tile)[k];
+          if ((n_out_floats & 2) && tid == 0)
+            reinterpret_cast<float2*>(dst)[n_out_floats / 2 - 1] = reinterpret_cast<const float2*>(tile)[n_out_floats / 2 - 1];
+        } else {
+          for (int k = tid; k < (n_out_floats >> 1); k += THREADS)
+            reinterpret_cast<float2*>(dst)[k] = reinterpret_cast<const float2*>(tile)[k];
+        }
+      }
+    }
+    if (t == A.T) break;
+    const uint32_t step = A.abs_step + uint32_t(t);
+
+    // ---- policy: four 16-row tiles per wavefront
+#pragma unroll 1
+    for (int q = 0; q < 4; ++q) {
+      const int r0 = wave * 64 + q * 16;
+      policy_tile<N, H, BF16>(wsm, tile + r0 * D, zbuf + r0 * 5, lane);
+    }
+    wave_sync();
+    float z[kNumActions];
+#pragma unroll
+    for (int k = 0; k < kNumActions; ++k) z[k] = zbuf[tid * 5 + k];
+    const uint32_t act = gumbel_argmax(z, A.seed, run, env, step, uint32_t(i));
+    if (A.act_traj && valid) A.act_traj[(size_t(t) * TE + g) * N + i] = uint8_t(act);
+
+    // ---- transition of this lane's agent
+    float fx = (act == 1u) ? -A.ph.accel : ((act == 2u) ? A.ph.accel : 0.0f);
+    float fy = (act == 3u) ? -A.ph.accel : ((act == 4u) ? A.ph.accel : 0.0f);
+#pragma unroll
+    for (int a = 0; a < N; ++a) {
+      if (a != i) {
+        const float dx = px - qx[a];
+        const float dy = py - qy[a];
+        const float d = sqrtf(dx * dx + dy * dy);
+        const float sp = softplus((A.ph.two_r - d) * A.ph.inv_margin);
+        const float k = A.ph.force_margin * sp / fmaxf(d, 1e-12f);
+        fx += k * dx;
+        fy += k * dy;
+      }
+    }
+    px += vx * A.ph.dt;
+    py += vy * A.ph.dt;
+    vx = vx * A.ph.keep + fx * A.ph.dt_over_mass;
+    vy = vy * A.ph.keep + fy * A.ph.dt_over_mass;
+    newpos[tid] = make_float2(px, py);
+    __syncthreads();  // (C) new positions visible; everyone is done reading the tile
+
+#pragma unroll
+    for (int a = 0; a < N; ++a) {
+      const float2 p = newpos[el * N + a];
+      qx[a] = p.x;
+      qy[a] = p.y;
+    }
+    // coverage term of landmark i: min over agents of the distance to it
+    {
+      float mylx = 0.0f, myly = 0.0f;
+#pragma unroll
+      for (int l = 0; l < N; ++l) {
+        if (l == i) { mylx = lx[l]; myly = ly[l]; }
+      }
+      float best2 = INFINITY;
+#pragma unroll
+      for (int a = 0; a < N; ++a) {
+        const float dx = qx[a] - mylx, dy = qy[a] - myly;
+        best2 = fminf(best2, dx * dx + dy * dy);
+      }
+      dminbuf[tid] = sqrtf(best2);
+    }
+    ep += 1;
+    done_prev = ep >= A.ph.max_ep;
+    if (done_prev) {
+      // new episode keyed by step + 1; every lane regenerates the whole env (rare: 1 step in max_ep)
+#pragma unroll
+      for (int a = 0; a < N; ++a) {
+        const uint4 w = philox4x32_10(env, step + 1u, uint32_t(a), kTagResetPos, A.seed, run);
+        qx[a] = word_to_position(w.x);
+        qy[a] = word_to_position(w.y);
+        const uint4 wl = philox4x32_10(env, step + 1u, uint32_t(N + a), kTagResetPos, A.seed, run);
+        lx[a] = word_to_position(wl.x);
+        ly[a] = word_to_position(wl.y);
+      }
+#pragma unroll
+      for (int a = 0; a < N; ++a) {
+        if (a == i) { px = qx[a]; py = qy[a]; }
+      }
+      vx = vy = 0.0f;
+      ep = 0;
+    }
+    write_obs_row(false);
+  }
+
+  // ---- state back to HBM
+  if (valid) {
+    A.st.pos_a[(0 * N + i) * TE + g] = px;
+    A.st.pos_a[(1 * N + i) * TE + g] = py;
+    A.st.vel_a[(0 * N + i) * TE + g] = vx;
+    A.st.vel_a[(1 * N + i) * TE + g] = vy;
+#pragma unroll
+    for (int l = 0; l < N; ++l) {
+      if (l == i) {
+        A.st.pos_l[(0 * N + l) * TE + g] = lx[l];
+        A.st.pos_l[(1 * N + l) * TE + g] = ly[l];
+      }
+    }
+    if (i == 0) A.st.ep_step[g] = ep;
+  }
+}
+
+template <int N, int H, bool BF16>
+hipError_t pack_impl(PolicyBuffers& pb, int R, const float* W1, const float* b1, const float* W2,
+                     const float* b2, const float* W3, const float* b3, hipStream_t s) {
+  using S = Shape<N, H, BF16>;
+  const size_t bytes = size_t(R) * S::RUN_BYTES;
+  if (pb.bytes < bytes) {
+    if (pb.packed) {
+      hipError_t e = hipFree(pb.packed);
+      if (e != hipSuccess) return e;
+      pb.packed = nullptr;
+      pb.bytes = 0;
+    }
+    hipError_t e = hipMalloc(&pb.packed, bytes);
+    if (e != hipSuccess) return e;
+    pb.bytes = bytes;
+  }
+  const int total = int(S::RUN_BYTES / S::ELT);  // upper bound on elements of one run
+  dim3 grid(cdiv(total, 256), R);
+  hipLaunchKernelGGL((pack_policy_kernel<N, H, BF16>), grid, dim3(256), 0, s,
+                     static_cast<uint8_t*>(pb.packed), W1, b1, W2, b2, W3, b3);
+  return hipGetLastError();
+}
+
+template <int N, int H, bool BF16, int EB>
+hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s) {
+  using M = Smem<N, H, BF16, EB>;
+  auto kern = rollout_policy_kernel<N, H, BF16, EB>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(M::TOTAL));
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const dim3 grid((A.TE + EB - 1) / EB);
+  hipLaunchKernelGGL(kern, grid, dim3(EB * N), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),
+                     int(A.TE != A.E));
+  return hipGetLastError();
+}
+
+}  // namespace
+
+void free_policy(PolicyBuffers& pb) {
+  if (pb.packed) (void)hipFree(pb.packed);
+  pb.packed = nullptr;
+  pb.bytes = 0;
+}
+
+// Supported policy shapes: (N, H, dtype) = (1|2|3, 64, fp32) and (10, 128, bf16).
+#define MPE_POLICY_CASES(X)        \
+  X(1, 64, false, 64)              \
+  X(2, 64, false, 64)              \
+  X(3, 64, false, 64)              \
+  X(10, 128, true, 32)
+
+hipError_t pack_policy(PolicyBuffers& pb, int N, int H, int R, int weight_dtype, const float* W1,
+                       const float* b1, const float* W2, const float* b2, const float* W3,
+                       const float* b3, hipStream_t s, const char** why) {
+  const bool bf = weight_dtype == 1;
+#define X(N_, H_, BF_, EB_) \
+  if (N == N_ && H == H_ && bf == BF_) return pack_impl<N_, H_, BF_>(pb, R, W1, b1, W2, b2, W3, b3, s);
+  MPE_POLICY_CASES(X)
+#undef X
+  *why = "unsupported policy shape: need (num_agents, hidden, dtype) in {(1..3, 64, fp32), (10, 128, bf16)}";
+  return hipSuccess;
+}
+
+hipError_t launch_rollout_policy(int N, int H, int weight_dtype, const RolloutArgs& A,
+                                 const PolicyBuffers& pb, hipStream_t s, const char** why) {
+  const bool bf = weight_dtype == 1;
+#define X(N_, H_, BF_, EB_)                                                                      \
+  if (N == N_ && H == H_ && bf == BF_) {                                                         \
+    if (A.TE != A.E && (A.E % EB_) != 0) {                                                       \
+      *why = "with several runs, num_envs per run must be a multiple of the block's env count";  \
+      return hipSuccess;                                                                         \
+    }                                                                                            \
+    return rollout_impl<N_, H_, BF_, EB_>(A, pb, s);                                             \
+  }
+  MPE_POLICY_CASES(X)
+#undef X
+  *why = "unsupported policy shape";
+  return hipSuccess;
+}
+
+}  // namespace mpe
