@@ -11,7 +11,9 @@
 
 namespace mpe {
 
-constexpr int kWave = 64;          // CDNA wavefront; every kernel here uses 64-thread blocks
+typedef float v4f __attribute__((ext_vector_type(4)));  // native 16-byte vector (stays in VGPRs)
+
+constexpr int kWave = 64;          // CDNA wavefront
 constexpr int kNumActions = 5;
 
 enum PhiloxTag : uint32_t { kTagResetPos = 0, kTagUniformAction = 1, kTagGumbel0 = 2, kTagGumbel1 = 3 };
@@ -90,13 +92,40 @@ __device__ __forceinline__ void reset_env(Env<N>& s, uint32_t seed, uint32_t run
   s.ep = 0;
 }
 
-// log(1 + exp(x)) as max(x, 0) + log(1 + exp(-|x|)); the second term is in (0, ln 2], so
-// the hardware exp2/log2 (absolute error ~1e-7 there) are accurate enough: the force picks
-// up at most ~1e-8 absolute error from them.
+// Hardware transcendentals (v_exp_f32 = 2^x, v_log_f32 = log2, v_rsq_f32, v_sqrt_f32, v_rcp_f32:
+// about 1 ulp each, no denormal or range fix-ups).  Every use below stays inside their normal
+// range, and the oracle comparison (1e-5 per transition) leaves two orders of magnitude of room.
+__device__ __forceinline__ float hw_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float hw_log2(float x) { return __builtin_amdgcn_logf(x); }
+__device__ __forceinline__ float hw_rsq(float x) { return __builtin_amdgcn_rsqf(x); }
+__device__ __forceinline__ float hw_sqrt(float x) { return __builtin_amdgcn_sqrtf(x); }
+__device__ __forceinline__ float hw_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// log(1 + exp(x)) as max(x, 0) + log(1 + exp(-|x|)); the second term is in (0, ln 2].
 __device__ __forceinline__ float softplus(float x) {
-  const float e = __expf(-fabsf(x));
-  return fmaxf(x, 0.0f) + __logf(1.0f + e);
+  const float e = hw_exp2(-fabsf(x) * kLog2e);
+  return fmaf(hw_log2(1.0f + e), kLn2, fmaxf(x, 0.0f));
 }
+
+// Contact force factor k of one agent pair with separation (dx, dy): the force on the first
+// agent is k * (dx, dy), on the second -k * (dx, dy).
+//   d = |delta| (clamped below at 1e-12, so coincident agents get zero force, no NaN)
+//   k = contact_force * margin * softplus((2r - d) / margin) / d
+__device__ __forceinline__ float contact_factor(float dx, float dy, const Phys& ph) {
+  const float d2 = fmaxf(fmaf(dx, dx, dy * dy), 1e-24f);
+  const float inv_d = hw_rsq(d2);
+  const float d = d2 * inv_d;
+  const float sp = softplus((ph.two_r - d) * ph.inv_margin);
+  return ph.force_margin * sp * inv_d;
+}
+
+// Control force component from a discrete action (0 none, 1 -x, 2 +x, 3 -y, 4 +y), branch-free:
+// two-bit fields of a constant hold direction + 1 for each action.
+__device__ __forceinline__ float action_dir_x(uint32_t a) { return float((0x161u >> (2u * a)) & 3u) - 1.0f; }
+__device__ __forceinline__ float action_dir_y(uint32_t a) { return float((0x215u >> (2u * a)) & 3u) - 1.0f; }
 
 // One transition under actions a[0..N): control force, pairwise softplus contacts on the
 // pre-step positions, position update with the old velocity, damped velocity update, shared
@@ -108,8 +137,8 @@ __device__ __forceinline__ void transition(Env<N>& s, const uint32_t (&a)[N], co
   float fx[N], fy[N];
 #pragma unroll
   for (int i = 0; i < N; ++i) {
-    fx[i] = (a[i] == 1u) ? -ph.accel : ((a[i] == 2u) ? ph.accel : 0.0f);
-    fy[i] = (a[i] == 3u) ? -ph.accel : ((a[i] == 4u) ? ph.accel : 0.0f);
+    fx[i] = ph.accel * action_dir_x(a[i]);
+    fy[i] = ph.accel * action_dir_y(a[i]);
   }
 #pragma unroll
   for (int i = 0; i < N; ++i) {
@@ -117,21 +146,19 @@ __device__ __forceinline__ void transition(Env<N>& s, const uint32_t (&a)[N], co
     for (int j = i + 1; j < N; ++j) {
       const float dx = s.px[i] - s.px[j];
       const float dy = s.py[i] - s.py[j];
-      const float d = sqrtf(dx * dx + dy * dy);
-      const float sp = softplus((ph.two_r - d) * ph.inv_margin);
-      const float k = ph.force_margin * sp / fmaxf(d, 1e-12f);
-      fx[i] += k * dx;
-      fy[i] += k * dy;
-      fx[j] -= k * dx;
-      fy[j] -= k * dy;
+      const float k = contact_factor(dx, dy, ph);
+      fx[i] = fmaf(k, dx, fx[i]);
+      fy[i] = fmaf(k, dy, fy[i]);
+      fx[j] = fmaf(-k, dx, fx[j]);
+      fy[j] = fmaf(-k, dy, fy[j]);
     }
   }
 #pragma unroll
   for (int i = 0; i < N; ++i) {
-    s.px[i] += s.vx[i] * ph.dt;
-    s.py[i] += s.vy[i] * ph.dt;
-    s.vx[i] = s.vx[i] * ph.keep + fx[i] * ph.dt_over_mass;
-    s.vy[i] = s.vy[i] * ph.keep + fy[i] * ph.dt_over_mass;
+    s.px[i] = fmaf(s.vx[i], ph.dt, s.px[i]);
+    s.py[i] = fmaf(s.vy[i], ph.dt, s.py[i]);
+    s.vx[i] = fmaf(fx[i], ph.dt_over_mass, s.vx[i] * ph.keep);
+    s.vy[i] = fmaf(fy[i], ph.dt_over_mass, s.vy[i] * ph.keep);
   }
   float r = 0.0f;
 #pragma unroll
@@ -141,9 +168,9 @@ __device__ __forceinline__ void transition(Env<N>& s, const uint32_t (&a)[N], co
     for (int i = 0; i < N; ++i) {
       const float dx = s.px[i] - s.lx[l];
       const float dy = s.py[i] - s.ly[l];
-      best2 = fminf(best2, dx * dx + dy * dy);
+      best2 = fminf(best2, fmaf(dx, dx, dy * dy));
     }
-    r -= sqrtf(best2);
+    r -= hw_sqrt(best2);
   }
   reward = r;
   s.ep += 1;
@@ -235,7 +262,7 @@ __device__ __forceinline__ void build_agent_obs(const Env<N>& s, int i, float2* 
 }
 
 // Stream `nfloats` (even) contiguous floats from the LDS tile to dst.  vec4 requires dst to
-// be 16-byte aligned; otherwise 8-byte stores are used.
+// be 16-byte aligned; otherwise 8-byte stores are used.  Generic (ragged) version.
 __device__ __forceinline__ void stream_out(const float* tile, float* dst, int nfloats, bool vec4, int lane) {
   if (vec4) {
     const int n4 = nfloats >> 2;
@@ -250,11 +277,28 @@ __device__ __forceinline__ void stream_out(const float* tile, float* dst, int nf
   }
 }
 
-// Write the observations of the wave's envs [g0, g0 + nvalid) to obs ([TE][N][D] slice).
-// 16-byte stores are used whenever the destination rows are 16-byte aligned.
+// Full-wave, 16-byte-aligned fast path: NF4 float4 per wave, known at compile time.  All LDS
+// reads are issued before the first store so their latency overlaps instead of adding up.
+template <int NF4>
+__device__ __forceinline__ void stream_out_full(const float* tile, float* dst, int lane) {
+  constexpr int kFullIters = NF4 / kWave;
+  constexpr int kTail = NF4 % kWave;
+  const v4f* src4 = reinterpret_cast<const v4f*>(tile) + lane;
+  v4f* dst4 = reinterpret_cast<v4f*>(dst) + lane;
+  v4f v[kFullIters > 0 ? kFullIters : 1];
+  v4f vt = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+  for (int k = 0; k < kFullIters; ++k) v[k] = src4[k * kWave];
+  if (kTail > 0 && lane < kTail) vt = src4[kFullIters * kWave];
+#pragma unroll
+  for (int k = 0; k < kFullIters; ++k) dst4[k * kWave] = v[k];
+  if (kTail > 0 && lane < kTail) dst4[kFullIters * kWave] = vt;
+}
+
+// Write the observations of the wave's nvalid envs to dst_wave, which points at the row of the
+// wave's first env inside an [env][N][D] slice.
 template <int N>
-__device__ __forceinline__ void emit_obs(const Env<N>& s, float* tile, float* obs, size_t g0,
-                                         int nvalid, int lane) {
+__device__ __forceinline__ void emit_obs(const Env<N>& s, float* tile, float* dst_wave, int nvalid, int lane) {
   using OT = ObsTile<N>;
   constexpr int D = OT::D;
   if constexpr (OT::kFull) {
@@ -262,22 +306,33 @@ __device__ __forceinline__ void emit_obs(const Env<N>& s, float* tile, float* ob
 #pragma unroll
     for (int i = 0; i < N; ++i) build_agent_obs<N>(s, i, row + i * (D / 2));
     __syncthreads();
-    float* dst = obs + g0 * (N * D);
-    const bool vec4 = (reinterpret_cast<uintptr_t>(dst) & 15u) == 0;
-    stream_out(tile, dst, nvalid * N * D, vec4, lane);
+    const bool vec4 = (reinterpret_cast<uintptr_t>(dst_wave) & 15u) == 0;
+    if (vec4 && nvalid == kWave) stream_out_full<kWave * N * D / 4>(tile, dst_wave, lane);
+    else stream_out(tile, dst_wave, nvalid * N * D, vec4, lane);
     __syncthreads();
   } else {
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       build_agent_obs<N>(s, i, reinterpret_cast<float2*>(tile + lane * D));
       __syncthreads();
-      float* dst = obs + (g0 * N + i) * D;
+      float* dst = dst_wave + i * D;
       const bool vec4 = (D % 4 == 0) && (reinterpret_cast<uintptr_t>(dst) & 15u) == 0;
       if (vec4) {
         constexpr int Q = (D % 4 == 0) ? D / 4 : 1;
-        for (int j = lane; j < nvalid * Q; j += kWave) {
-          const int e = j / Q, q = j - e * Q;
-          reinterpret_cast<float4*>(dst + size_t(e) * N * D)[q] = reinterpret_cast<const float4*>(tile + e * D)[q];
+        if (nvalid == kWave) {
+          v4f v[Q];
+#pragma unroll
+          for (int k = 0; k < Q; ++k) v[k] = reinterpret_cast<const v4f*>(tile)[k * kWave + lane];
+#pragma unroll
+          for (int k = 0; k < Q; ++k) {
+            const int j = k * kWave + lane, e = j / Q, q = j - e * Q;
+            reinterpret_cast<v4f*>(dst + size_t(e) * N * D)[q] = v[k];
+          }
+        } else {
+          for (int j = lane; j < nvalid * Q; j += kWave) {
+            const int e = j / Q, q = j - e * Q;
+            reinterpret_cast<float4*>(dst + size_t(e) * N * D)[q] = reinterpret_cast<const float4*>(tile + e * D)[q];
+          }
         }
       } else {
         constexpr int Q = D / 2;

@@ -39,7 +39,7 @@ __global__ __launch_bounds__(kWave) void reset_kernel(StatePtrs st, uint32_t TE,
   Env<N> s;
   reset_env<N>(s, seed, L.run, L.env, 0u);
   if (L.valid) store_state<N>(s, st, TE, L.g);
-  if (obs) emit_obs<N>(s, tile, obs, L.g0, L.nvalid, L.lane);
+  if (obs) emit_obs<N>(s, tile, obs + L.g0 * (N * 6 * N), L.nvalid, L.lane);
 }
 
 template <int N>
@@ -72,10 +72,11 @@ __global__ __launch_bounds__(kWave) void step_kernel(StatePtrs st, Phys ph, uint
     if (reward) reward[L.g] = r;
     if (done) done[L.g] = d ? 1 : 0;
   }
-  if (obs) emit_obs<N>(s, tile, obs, L.g0, L.nvalid, L.lane);
+  if (obs) emit_obs<N>(s, tile, obs + L.g0 * (N * 6 * N), L.nvalid, L.lane);
 }
 
-// Persistent rollout with uniform random actions (no policy installed).
+// Persistent rollout with uniform random actions (no policy installed).  Output pointers are
+// advanced by one time slice per step instead of being recomputed from (t, env).
 template <int N>
 __global__ __launch_bounds__(kWave) void rollout_uniform_kernel(RolloutArgs A) {
   __shared__ __attribute__((aligned(16))) float tile[ObsTile<N>::kFloats];
@@ -84,33 +85,190 @@ __global__ __launch_bounds__(kWave) void rollout_uniform_kernel(RolloutArgs A) {
   Env<N> s;
   if (L.valid) load_state<N>(s, A.st, A.TE, L.g); else zero_env<N>(s);
   const size_t TE = A.TE;
-  for (int t = 0; t < A.T; ++t) {
-    const uint32_t step = A.abs_step + uint32_t(t);
-    if (A.obs_traj) emit_obs<N>(s, tile, A.obs_traj + size_t(t) * TE * N * D, L.g0, L.nvalid, L.lane);
+  float* obs_p = A.obs_traj ? A.obs_traj + L.g0 * (N * D) : nullptr;
+  uint8_t* act_p = (A.act_traj && L.valid) ? A.act_traj + L.g * N : nullptr;
+  float* rew_p = (A.rew_traj && L.valid) ? A.rew_traj + L.g : nullptr;
+  uint8_t* done_p = (A.done_traj && L.valid) ? A.done_traj + L.g : nullptr;
+  uint32_t step = A.abs_step;
+  for (int t = 0; t < A.T; ++t, ++step) {
+    if (obs_p) {
+      emit_obs<N>(s, tile, obs_p, L.nvalid, L.lane);
+      obs_p += TE * (N * D);
+    }
     uint32_t a[N];
 #pragma unroll
     for (int i = 0; i < N; ++i) {
       const uint4 w = philox4x32_10(L.env, step, uint32_t(i), kTagUniformAction, A.seed, L.run);
       a[i] = word_to_action(w.x);
     }
-    if (A.act_traj && L.valid) {
-      uint8_t* dst = A.act_traj + (size_t(t) * TE + L.g) * N;
+    if (act_p) {
 #pragma unroll
-      for (int i = 0; i < N; ++i) dst[i] = uint8_t(a[i]);
+      for (int i = 0; i < N; ++i) act_p[i] = uint8_t(a[i]);
+      act_p += TE * N;
     }
     float r;
     bool d;
     transition<N>(s, a, A.ph, A.seed, L.run, L.env, step, r, d);
-    if (L.valid) {
-      if (A.rew_traj) A.rew_traj[size_t(t) * TE + L.g] = r;
-      if (A.done_traj) A.done_traj[size_t(t) * TE + L.g] = d ? 1 : 0;
-    }
+    if (rew_p) { *rew_p = r; rew_p += TE; }
+    if (done_p) { *done_p = d ? 1 : 0; done_p += TE; }
   }
-  if (A.last_obs) emit_obs<N>(s, tile, A.last_obs, L.g0, L.nvalid, L.lane);
+  if (A.last_obs) emit_obs<N>(s, tile, A.last_obs + L.g0 * (N * D), L.nvalid, L.lane);
   if (L.valid) store_state<N>(s, A.st, A.TE, L.g);
 }
 
+// --------------------------------------------------------------------------------------
+// Wave-specialised persistent rollout for N <= 3, whole waves only (TE % 64 == 0, 16-byte
+// aligned time slices).  A block is two wavefronts over the same 64 envs:
+//   wave 0 (compute) keeps the 64 envs in registers, steps them, and drops each finished time
+//           slice -- obs, reward, actions, done -- into one of two LDS slice buffers;
+//   wave 1 (writer)  copies finished slices to HBM with 16-byte stores covering whole lines.
+// The stores of a 1.9 GB trajectory back-pressure the issuing wave for most of a step; in a
+// single wave that stall serialises with the arithmetic of the next step, here it overlaps.
+// Two barriers per step hand the buffers back and forth:
+//   X_t: writer has read slice t-1 out of buf[(t+1)&1]  -> compute may overwrite it
+//   Y_t: compute has completed slice t in buf[t&1]       -> writer may read it
+// Blocks are mapped to env groups XCD-aware: the hardware deals block b to XCD b % 8, so
+// group = (b % 8) * groups_per_xcd + b / 8 gives each XCD one contiguous range of envs and
+// the partial cache lines of neighbouring groups (actions: 192 B, done: 64 B per group and
+// step) meet in the same L2 instead of being written back separately.
+// --------------------------------------------------------------------------------------
+template <int N>
+struct SliceBuf {
+  static constexpr int D = 6 * N;
+  static constexpr int OBS_BYTES = kWave * N * D * 4;
+  static constexpr int REW_OFF = OBS_BYTES;            // 64 floats
+  static constexpr int ACT_OFF = REW_OFF + kWave * 4;  // 64 * N bytes
+  static constexpr int DONE_OFF = ACT_OFF + kWave * N; // 64 bytes
+  static constexpr int BYTES = (DONE_OFF + kWave + 15) & ~15;
+  static constexpr int OBS_F4 = OBS_BYTES / 16;
+  static constexpr int FULL = OBS_F4 / kWave;          // full 64-lane rounds of obs
+  static constexpr int TAIL = OBS_F4 % kWave;          // obs float4 left for the mixed round
+  static constexpr int REW_L = TAIL, ACT_L = REW_L + 16, DONE_L = ACT_L + 4 * N, END_L = DONE_L + 4;
+  static_assert(END_L <= kWave, "mixed round must fit one wavefront");
+};
+
+template <int N>
+__global__ __launch_bounds__(2 * kWave) void rollout_uniform_ws_kernel(RolloutArgs A, uint32_t groups,
+                                                                       uint32_t groups_per_xcd) {
+  using SB = SliceBuf<N>;
+  constexpr int D = 6 * N;
+  __shared__ __attribute__((aligned(16))) uint8_t buf[2][SB::BYTES];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t grp = (blockIdx.x & 7u) * groups_per_xcd + (blockIdx.x >> 3);
+  if (grp >= groups) return;  // whole block, before any barrier
+  const size_t TE = A.TE;
+  const size_t g0 = size_t(grp) * kWave;
+
+  if (wave == 0) {
+    // ------------------------------------------------------------------ compute wave
+    const size_t g = g0 + lane;
+    const uint32_t run = uint32_t(g) / A.E;
+    const uint32_t env = uint32_t(g) - run * A.E;
+    Env<N> s;
+    load_state<N>(s, A.st, TE, g);
+    auto write_obs = [&](uint8_t* b) {
+      float2* row = reinterpret_cast<float2*>(b) + lane * (N * D / 2);
+#pragma unroll
+      for (int i = 0; i < N; ++i) build_agent_obs<N>(s, i, row + i * (D / 2));
+    };
+    write_obs(buf[0]);
+    uint32_t step = A.abs_step;
+    for (int t = 0; t < A.T; ++t, ++step) {
+      uint32_t a[N];
+#pragma unroll
+      for (int i = 0; i < N; ++i) {
+        const uint4 w = philox4x32_10(env, step, uint32_t(i), kTagUniformAction, A.seed, run);
+        a[i] = word_to_action(w.x);
+      }
+      float r;
+      bool d;
+      transition<N>(s, a, A.ph, A.seed, run, env, step, r, d);
+      __syncthreads();  // X_t
+      uint8_t* cur = buf[t & 1];
+      reinterpret_cast<float*>(cur + SB::REW_OFF)[lane] = r;
+#pragma unroll
+      for (int i = 0; i < N; ++i) cur[SB::ACT_OFF + lane * N + i] = uint8_t(a[i]);
+      cur[SB::DONE_OFF + lane] = d ? 1 : 0;
+      write_obs(buf[(t + 1) & 1]);
+      __syncthreads();  // Y_t
+    }
+    if (A.last_obs) stream_out_full<SB::OBS_F4>(reinterpret_cast<const float*>(buf[A.T & 1]),
+                                                A.last_obs + g0 * (N * D), lane);
+    store_state<N>(s, A.st, TE, g);
+  } else {
+    // ------------------------------------------------------------------ writer wave
+    // Full rounds: lane l moves obs float4 number k*64 + l.  Mixed round: the obs tail, then
+    // reward (16 lanes), actions (4N lanes) and done (4 lanes), one float4 each.
+    uint8_t* obs_g = A.obs_traj ? reinterpret_cast<uint8_t*>(A.obs_traj + g0 * (N * D)) + lane * 16 : nullptr;
+    const size_t obs_stride = TE * (N * D) * 4;
+    int mix_lds = -1;          // byte offset inside a slice buffer, -1: lane idle in the mixed round
+    uint8_t* mix_g = nullptr;
+    size_t mix_stride = 0;
+    if (lane < SB::TAIL) {
+      if (A.obs_traj) {
+        mix_lds = (SB::FULL * kWave + lane) * 16;
+        mix_g = reinterpret_cast<uint8_t*>(A.obs_traj + g0 * (N * D)) + mix_lds;
+        mix_stride = obs_stride;
+      }
+    } else if (lane < SB::ACT_L) {
+      if (A.rew_traj) {
+        mix_lds = SB::REW_OFF + (lane - SB::REW_L) * 16;
+        mix_g = reinterpret_cast<uint8_t*>(A.rew_traj + g0) + (lane - SB::REW_L) * 16;
+        mix_stride = TE * 4;
+      }
+    } else if (lane < SB::DONE_L) {
+      if (A.act_traj) {
+        mix_lds = SB::ACT_OFF + (lane - SB::ACT_L) * 16;
+        mix_g = A.act_traj + g0 * N + (lane - SB::ACT_L) * 16;
+        mix_stride = TE * N;
+      }
+    } else if (lane < SB::END_L) {
+      if (A.done_traj) {
+        mix_lds = SB::DONE_OFF + (lane - SB::DONE_L) * 16;
+        mix_g = A.done_traj + g0 + (lane - SB::DONE_L) * 16;
+        mix_stride = TE;
+      }
+    }
+    v4f v[SB::FULL > 0 ? SB::FULL : 1];
+    v4f vm = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int t = 0; t <= A.T; ++t) {
+      if (t > 0) {
+        if (obs_g) {
+#pragma unroll
+          for (int k = 0; k < SB::FULL; ++k) *reinterpret_cast<v4f*>(obs_g + k * (kWave * 16)) = v[k];
+          obs_g += obs_stride;
+        }
+        if (mix_lds >= 0) {
+          *reinterpret_cast<v4f*>(mix_g) = vm;
+          mix_g += mix_stride;
+        }
+      }
+      if (t == A.T) break;
+      __syncthreads();  // X_t
+      __syncthreads();  // Y_t
+      const uint8_t* cur = buf[t & 1];
+      if (obs_g) {
+#pragma unroll
+        for (int k = 0; k < SB::FULL; ++k) v[k] = *reinterpret_cast<const v4f*>(cur + (k * kWave + lane) * 16);
+      }
+      if (mix_lds >= 0) vm = *reinterpret_cast<const v4f*>(cur + mix_lds);
+    }
+  }
+}
+
 inline dim3 env_grid(uint32_t TE) { return dim3((TE + kWave - 1) / kWave); }
+
+inline bool aligned16p(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// The wave-specialised kernel needs whole waves and 16-byte aligned slices of every output.
+template <int N>
+inline bool ws_eligible(const RolloutArgs& A) {
+  if (N > 3 || A.TE % kWave != 0) return false;
+  if ((size_t(A.TE) * N) % 16 != 0) return false;  // action slices
+  return aligned16p(A.obs_traj) && aligned16p(A.act_traj) && aligned16p(A.rew_traj) &&
+         aligned16p(A.done_traj) && aligned16p(A.last_obs);
+}
 
 template <int N>
 struct EnvLaunch {
@@ -124,6 +282,14 @@ struct EnvLaunch {
                        actions, obs, reward, done);
   }
   static void rollout(const RolloutArgs& A, hipStream_t s) {
+    if constexpr (N <= 3) {
+      if (ws_eligible<N>(A)) {
+        const uint32_t groups = A.TE / kWave;
+        const uint32_t per_xcd = (groups + 7) / 8;
+        hipLaunchKernelGGL(rollout_uniform_ws_kernel<N>, dim3(per_xcd * 8), dim3(2 * kWave), 0, s, A, groups, per_xcd);
+        return;
+      }
+    }
     hipLaunchKernelGGL(rollout_uniform_kernel<N>, env_grid(A.TE), dim3(kWave), 0, s, A);
   }
 };

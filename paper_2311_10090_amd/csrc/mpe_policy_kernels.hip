@@ -133,8 +133,8 @@ __global__ void pack_policy_kernel(uint8_t* __restrict__ packed, const float* __
 // tanh(x) = 1 - 2 / (exp(2x) + 1) on the hardware exp2 / rcp units.  Absolute error ~1e-7;
 // saturates cleanly (exp2 -> inf gives 1, exp2 -> 0 gives -1).
 __device__ __forceinline__ float fast_tanh(float x) {
-  const float t = __builtin_amdgcn_exp2f(x * 2.8853900817779268f);
-  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(t + 1.0f);
+  const float t = hw_exp2(x * (2.0f * kLog2e));
+  return fmaf(-2.0f, hw_rcp(t + 1.0f), 1.0f);
 }
 
 __device__ __forceinline__ void wave_sync() {
@@ -144,6 +144,8 @@ __device__ __forceinline__ void wave_sync() {
 }
 
 // Gumbel-max over 5 logits: g = -ln(-ln u), u odd multiples of 2^-24 from two Philox blocks.
+// ln = ln2 * log2 on the hardware unit (u >= 2^-24 is a normal number; -ln u is in
+// [6e-8, 16.7], also normal), so v_k = z_k - ln2 * log2(-ln2 * log2(u_k)).
 __device__ __forceinline__ uint32_t gumbel_argmax(const float (&z)[kNumActions], uint32_t seed,
                                                   uint32_t run, uint32_t env, uint32_t step, uint32_t agent) {
   const uint4 w0 = philox4x32_10(env, step, agent, kTagGumbel0, seed, run);
@@ -154,38 +156,71 @@ __device__ __forceinline__ uint32_t gumbel_argmax(const float (&z)[kNumActions],
 #pragma unroll
   for (int k = 0; k < kNumActions; ++k) {
     const float u = word_to_open_uniform(w[k]);
-    const float v = z[k] - __logf(-logf(u));
+    const float e = -kLn2 * hw_log2(u);               // -ln u  > 0
+    const float v = fmaf(-kLn2, hw_log2(e), z[k]);     // z - ln(-ln u)
     if (v > best_v) { best_v = v; best = uint32_t(k); }
   }
   return best;
 }
 
-// LDS plan of one block (bytes).
+// LDS plan of one block (bytes).  The logits buffer and the new-position exchange share one
+// region: within a phase each wavefront touches only its own 64 rows of it (logits first, then
+// its agents' new positions), and block barriers separate that phase from the one in which
+// every wavefront reads the positions.
 template <int N, int H, bool BF16, int EB>
 struct Smem {
   using S = Shape<N, H, BF16>;
   static constexpr int ROWS = EB * N;
-  static constexpr size_t WEIGHTS = S::RUN_BYTES;
-  static constexpr size_t OBS = size_t(ROWS) * S::D * 4 + 64;  // + zeroed tail for K padding reads
-  static constexpr size_t Z = size_t(ROWS) * 5 * 4;
-  static constexpr size_t NEWPOS = size_t(ROWS) * 8;
-  static constexpr size_t DMIN = size_t(ROWS) * 4;
-  static constexpr size_t OFF_OBS = (WEIGHTS + 15) & ~size_t(15);
-  static constexpr size_t OFF_Z = OFF_OBS + ((OBS + 15) & ~size_t(15));
-  static constexpr size_t OFF_NEWPOS = OFF_Z + ((Z + 15) & ~size_t(15));
-  static constexpr size_t OFF_DMIN = OFF_NEWPOS + ((NEWPOS + 15) & ~size_t(15));
+  static constexpr bool kRewardInRegs = (N <= 4);   // every lane evaluates the N*N distances itself
+  static constexpr size_t WEIGHTS = S::OFF_W3A;                   // W1A + W2A (W3A lives in registers)
+  static constexpr size_t BIAS = S::BIAS_BYTES;
+  static constexpr size_t OBS = size_t(ROWS) * S::D * 4 + 64;     // + zeroed tail for K padding reads
+  static constexpr size_t ZP = size_t(ROWS) * 5 * 4;              // logits [row][5]; newpos [row] float2 inside
+  static constexpr size_t DMIN = kRewardInRegs ? 0 : size_t(ROWS) * 4;
+  static constexpr size_t OFF_BIAS = (WEIGHTS + 15) & ~size_t(15);
+  static constexpr size_t OFF_OBS = OFF_BIAS + ((BIAS + 15) & ~size_t(15));
+  static constexpr size_t OFF_ZP = OFF_OBS + ((OBS + 15) & ~size_t(15));
+  static constexpr size_t OFF_DMIN = OFF_ZP + ((ZP + 15) & ~size_t(15));
   static constexpr size_t TOTAL = OFF_DMIN + ((DMIN + 15) & ~size_t(15));
 };
 
-// MLP forward of one 16-row tile; rows' observations are in the LDS tile at obs_rows
-// (row stride D floats).  Leaves logits of row j in zrow[j*5 .. j*5+4].
+// A-operand registers of layer 3 (5 outputs padded to one 16-wide tile), loaded once per kernel.
 template <int N, int H, bool BF16>
-__device__ __forceinline__ void policy_tile(const uint8_t* __restrict__ wsm, const float* __restrict__ obs_rows,
+struct W3Regs {
+  using S = Shape<N, H, BF16>;
+  f32x4 f[BF16 ? 1 : S::S2 / 4];
+  bf16x8 b[BF16 ? S::S2 : 1];
+  __device__ __forceinline__ void load(const uint8_t* __restrict__ run_weights, int lane) {
+    if constexpr (BF16) {
+#pragma unroll
+      for (int s = 0; s < S::S2; ++s) b[s] = reinterpret_cast<const bf16x8*>(run_weights + S::OFF_W3A)[s * 64 + lane];
+    } else {
+#pragma unroll
+      for (int s4 = 0; s4 < S::S2 / 4; ++s4) f[s4] = reinterpret_cast<const f32x4*>(run_weights + S::OFF_W3A)[s4 * 64 + lane];
+    }
+  }
+};
+
+// MLP forward of one 16-row tile; rows' observations are in the LDS tile at obs_rows
+// (row stride D floats).  wsm holds W1A then W2A, bias holds b1, b2, b3 (padded to 16).
+// Leaves logits of row j in zrows[j*5 .. j*5+4].
+template <int N, int H, bool BF16>
+__device__ __forceinline__ void policy_tile(const uint8_t* __restrict__ wsm, const float* __restrict__ bias,
+                                            const W3Regs<N, H, BF16>& w3, const float* __restrict__ obs_rows,
                                             float* __restrict__ zrows, int lane) {
   using S = Shape<N, H, BF16>;
   constexpr int D = S::D, MT = S::MT;
   const int j = lane & 15, gq = lane >> 4;
-  const float* bias = reinterpret_cast<const float*>(wsm + S::OFF_BIAS);
+  // Weights and biases are re-read from LDS for every tile on purpose: the addresses go through
+  // an opaque zero offset, so the compiler cannot hoist ~100 registers of loop-invariant
+  // operands out of the step loop (which would cost a wavefront of occupancy).  The offset is an
+  // integer, not a laundered pointer, so the loads stay LDS (ds_read) instructions.
+  {
+    uint32_t zero = 0;
+    asm volatile("" : "+v"(zero));
+    wsm += zero;
+    bias += zero;
+  }
   f32x4 acc[MT];
   f32x4 hid[MT];
 #pragma unroll
@@ -253,28 +288,25 @@ __device__ __forceinline__ void policy_tile(const uint8_t* __restrict__ wsm, con
 #pragma unroll
     for (int r = 0; r < 4; ++r) hid[m][r] = fast_tanh(acc[m][r]);
   }
-  // ---- layer 3 (5 outputs padded to one 16-wide tile); two accumulators break the chain
+  // ---- layer 3; two accumulators break the dependent chain
   f32x4 z0 = *reinterpret_cast<const f32x4*>(bias + 2 * H + 4 * gq);
   f32x4 z1 = {0.0f, 0.0f, 0.0f, 0.0f};
   if constexpr (!BF16) {
-    const f32x4* w3 = reinterpret_cast<const f32x4*>(wsm + S::OFF_W3A);
 #pragma unroll
     for (int s4 = 0; s4 < S::S2 / 4; ++s4) {
-      const f32x4 a = w3[s4 * 64 + lane];
-      z0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], hid[s4][0], z0, 0, 0, 0);
-      z1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], hid[s4][1], z1, 0, 0, 0);
-      z0 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], hid[s4][2], z0, 0, 0, 0);
-      z1 = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], hid[s4][3], z1, 0, 0, 0);
+      z0 = __builtin_amdgcn_mfma_f32_16x16x4f32(w3.f[s4][0], hid[s4][0], z0, 0, 0, 0);
+      z1 = __builtin_amdgcn_mfma_f32_16x16x4f32(w3.f[s4][1], hid[s4][1], z1, 0, 0, 0);
+      z0 = __builtin_amdgcn_mfma_f32_16x16x4f32(w3.f[s4][2], hid[s4][2], z0, 0, 0, 0);
+      z1 = __builtin_amdgcn_mfma_f32_16x16x4f32(w3.f[s4][3], hid[s4][3], z1, 0, 0, 0);
     }
   } else {
-    const bf16x8* w3 = reinterpret_cast<const bf16x8*>(wsm + S::OFF_W3A);
 #pragma unroll
     for (int s = 0; s < S::S2; ++s) {
       bf16x8 b;
 #pragma unroll
       for (int e = 0; e < 4; ++e) { b[e] = __bf16(hid[2 * s][e]); b[4 + e] = __bf16(hid[2 * s + 1][e]); }
-      if (s & 1) z1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w3[s * 64 + lane], b, z1, 0, 0, 0);
-      else z0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w3[s * 64 + lane], b, z0, 0, 0, 0);
+      if (s & 1) z1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w3.b[s], b, z1, 0, 0, 0);
+      else z0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w3.b[s], b, z0, 0, 0, 0);
     }
   }
   z0 += z1;
@@ -287,18 +319,35 @@ __device__ __forceinline__ void policy_tile(const uint8_t* __restrict__ wsm, con
   }
 }
 
-template <int N, int H, bool BF16, int EB>
-__global__ __launch_bounds__(EB * N) void rollout_policy_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
-                                                                int per_run_weights) {
+// Cooperative copy of NF4 float4 from LDS to global by THREADS lanes; all reads issued first.
+template <int NF4, int THREADS>
+__device__ __forceinline__ void block_stream_out_full(const float* tile, float* dst, int tid) {
+  constexpr int kFullIters = NF4 / THREADS;
+  constexpr int kTail = NF4 % THREADS;
+  const v4f* src4 = reinterpret_cast<const v4f*>(tile) + tid;
+  v4f* dst4 = reinterpret_cast<v4f*>(dst) + tid;
+  v4f v[kFullIters > 0 ? kFullIters : 1];
+  v4f vt = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+  for (int k = 0; k < kFullIters; ++k) v[k] = src4[k * THREADS];
+  if (kTail > 0 && tid < kTail) vt = src4[kFullIters * THREADS];
+#pragma unroll
+  for (int k = 0; k < kFullIters; ++k) dst4[k * THREADS] = v[k];
+  if (kTail > 0 && tid < kTail) dst4[kFullIters * THREADS] = vt;
+}
+
+template <int N, int H, bool BF16, int EB, int MINW>
+__global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
+                                                                      int per_run_weights) {
   using S = Shape<N, H, BF16>;
   using M = Smem<N, H, BF16, EB>;
   constexpr int D = S::D, ROWS = EB * N, THREADS = ROWS;
   static_assert(THREADS % 64 == 0, "block must be whole wavefronts");
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   uint8_t* wsm = smem;
+  float* bias = reinterpret_cast<float*>(smem + M::OFF_BIAS);
   float* tile = reinterpret_cast<float*>(smem + M::OFF_OBS);
-  float* zbuf = reinterpret_cast<float*>(smem + M::OFF_Z);
-  float2* newpos = reinterpret_cast<float2*>(smem + M::OFF_NEWPOS);
+  float* zbuf = reinterpret_cast<float*>(smem + M::OFF_ZP);     // [ROWS][5]; wave w owns rows 64w..64w+63
   float* dminbuf = reinterpret_cast<float*>(smem + M::OFF_DMIN);
 
   const int tid = threadIdx.x;
@@ -313,20 +362,30 @@ __global__ __launch_bounds__(EB * N) void rollout_policy_kernel(RolloutArgs A, c
   const uint32_t env = gc - run * A.E;
   const size_t left = TE - g0;
   const int nvalid = left < size_t(EB) ? int(left) : EB;   // valid envs in this block
+  // new-position slot of row r inside the shared logits/positions region: the first 8 bytes of
+  // the 20-byte logits slot of that row's wavefront-local index
+  auto newpos_of = [&](int r) -> float2* { return reinterpret_cast<float2*>(zbuf + (r >> 6) * (64 * 5)) + (r & 63); };
 
-  // ---- stage this block's weights (the run of its first env) in LDS
+  // ---- stage this block's weights (the run of its first env): W1A, W2A, biases in LDS; W3A in registers
+  const uint8_t* run_weights = packed + (per_run_weights ? size_t(uint32_t(g0) / A.E) * S::RUN_BYTES : 0);
+  W3Regs<N, H, BF16> w3;
+  w3.load(run_weights, lane);
   {
-    const uint32_t run0 = uint32_t(g0) / A.E;
-    const uint4* src = reinterpret_cast<const uint4*>(packed + (per_run_weights ? size_t(run0) * S::RUN_BYTES : 0));
+    const uint4* src = reinterpret_cast<const uint4*>(run_weights);
     uint4* dst = reinterpret_cast<uint4*>(wsm);
-    for (int k = tid; k < int(S::RUN_BYTES / 16); k += THREADS) dst[k] = src[k];
+    for (int k = tid; k < int(S::OFF_W3A / 16); k += THREADS) dst[k] = src[k];
+    const uint4* bsrc = reinterpret_cast<const uint4*>(run_weights + S::OFF_BIAS);
+    uint4* bdst = reinterpret_cast<uint4*>(bias);
+    for (int k = tid; k < int(S::BIAS_BYTES / 16); k += THREADS) bdst[k] = bsrc[k];
     if (tid < 16) tile[ROWS * D + tid] = 0.0f;
   }
 
   // ---- registers: own agent, all agents' positions, all landmarks
-  float px, py, vx, vy;
+  float px = 0.0f, py = 0.0f, vx = 0.0f, vy = 0.0f;
   float qx[N], qy[N], lx[N], ly[N];
-  int32_t ep;
+  int32_t ep = 0;
+#pragma unroll
+  for (int a = 0; a < N; ++a) qx[a] = qy[a] = lx[a] = ly[a] = 0.0f;
   if (valid) {
 #pragma unroll
     for (int a = 0; a < N; ++a) {
@@ -338,19 +397,13 @@ __global__ __launch_bounds__(EB * N) void rollout_policy_kernel(RolloutArgs A, c
     vx = A.st.vel_a[(0 * N + i) * TE + g];
     vy = A.st.vel_a[(1 * N + i) * TE + g];
     ep = A.st.ep_step[g];
-  } else {
-#pragma unroll
-    for (int a = 0; a < N; ++a) qx[a] = qy[a] = lx[a] = ly[a] = 0.0f;
-    vx = vy = 0.0f;
-    ep = 0;
   }
-  px = py = 0.0f;
 #pragma unroll
   for (int a = 0; a < N; ++a) {
     if (a == i) { px = qx[a]; py = qy[a]; }
   }
 
-  // Write this lane's observation row into the tile (zeros of the comm slots included).
+  // Write this lane's observation row into the tile (the zero comm slots only the first time).
   auto write_obs_row = [&](bool with_zeros) {
     float2* row = reinterpret_cast<float2*>(tile + tid * D);
     int c = 0;
@@ -368,28 +421,42 @@ __global__ __launch_bounds__(EB * N) void rollout_policy_kernel(RolloutArgs A, c
   };
   write_obs_row(true);
 
-  float dmin_prev = 0.0f;  // unused before t = 1
   bool done_prev = false;
-  (void)dmin_prev;
-
   const int n_out_floats = nvalid * N * D;  // floats of one time slice this block writes
+  // Output addresses = uniform per-step base (advanced once per step, lives in SGPRs) + a
+  // 32-bit lane offset that never changes.
+  float* obs_p = A.obs_traj ? A.obs_traj + g0 * (N * D) : nullptr;
+  uint8_t* act_base = A.act_traj;
+  float* rew_base = A.rew_traj;
+  uint8_t* done_base = A.done_traj;
+  const uint32_t row_off = uint32_t(gc) * N + i;      // index of this agent inside a time slice
+  const bool env_writer = valid && i == 0;            // the lane that stores per-env outputs
+  uint32_t step = A.abs_step;
 
-  for (int t = 0; t <= A.T; ++t) {
-    __syncthreads();  // (A) tile, dminbuf complete
-    // reward and done of the step finished in the previous iteration
-    if (t > 0 && i == 0 && valid) {
-      float r = 0.0f;
+  for (int t = 0; t <= A.T; ++t, ++step) {
+    __syncthreads();  // (A) tile (and dminbuf) complete
+    if constexpr (!M::kRewardInRegs) {
+      // reward and done of the step finished in the previous iteration
+      if (t > 0) {
+        if (env_writer) {
+          if (rew_base) {
+            float r = 0.0f;
 #pragma unroll
-      for (int a = 0; a < N; ++a) r -= dminbuf[el * N + a];
-      if (A.rew_traj) A.rew_traj[size_t(t - 1) * TE + g] = r;
-      if (A.done_traj) A.done_traj[size_t(t - 1) * TE + g] = done_prev ? 1 : 0;
+            for (int a = 0; a < N; ++a) r -= dminbuf[el * N + a];
+            (rew_base - TE)[gc] = r;
+          }
+          if (done_base) (done_base - TE)[gc] = done_prev ? 1 : 0;
+        }
+      }
     }
     // stream the tile out: obs_traj[t] for t < T, last_obs at t == T
     {
-      float* dst = (t < A.T) ? (A.obs_traj ? A.obs_traj + (size_t(t) * TE + g0) * (N * D) : nullptr)
-                             : (A.last_obs ? A.last_obs + g0 * (N * D) : nullptr);
+      float* dst = (t < A.T) ? obs_p : (A.last_obs ? A.last_obs + g0 * (N * D) : nullptr);
       if (dst) {
-        if ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
+        const bool vec4 = (reinterpret_cast<uintptr_t>(dst) & 15u) == 0;
+        if (vec4 && nvalid == EB) {
+          block_stream_out_full<ROWS * D / 4, THREADS>(tile, dst, tid);
+        } else if (vec4) {
           const int n4 = n_out_floats >> 2;
           for (int k = tid; k < n4; k += THREADS)
             reinterpret_cast<float4*>(dst)[k] = reinterpret_cast<const float4*>(tile)[k];
@@ -400,53 +467,69 @@ __global__ __launch_bounds__(EB * N) void rollout_policy_kernel(RolloutArgs A, c
             reinterpret_cast<float2*>(dst)[k] = reinterpret_cast<const float2*>(tile)[k];
         }
       }
+      if (obs_p) obs_p += TE * (N * D);
     }
     if (t == A.T) break;
-    const uint32_t step = A.abs_step + uint32_t(t);
 
     // ---- policy: four 16-row tiles per wavefront
 #pragma unroll 1
     for (int q = 0; q < 4; ++q) {
       const int r0 = wave * 64 + q * 16;
-      policy_tile<N, H, BF16>(wsm, tile + r0 * D, zbuf + r0 * 5, lane);
+      policy_tile<N, H, BF16>(wsm, bias, w3, tile + r0 * D, zbuf + r0 * 5, lane);
     }
     wave_sync();
     float z[kNumActions];
 #pragma unroll
     for (int k = 0; k < kNumActions; ++k) z[k] = zbuf[tid * 5 + k];
     const uint32_t act = gumbel_argmax(z, A.seed, run, env, step, uint32_t(i));
-    if (A.act_traj && valid) A.act_traj[(size_t(t) * TE + g) * N + i] = uint8_t(act);
+    if (act_base) {
+      if (valid) act_base[row_off] = uint8_t(act);
+      act_base += TE * N;
+    }
 
     // ---- transition of this lane's agent
-    float fx = (act == 1u) ? -A.ph.accel : ((act == 2u) ? A.ph.accel : 0.0f);
-    float fy = (act == 3u) ? -A.ph.accel : ((act == 4u) ? A.ph.accel : 0.0f);
+    float fx = A.ph.accel * action_dir_x(act);
+    float fy = A.ph.accel * action_dir_y(act);
 #pragma unroll
     for (int a = 0; a < N; ++a) {
       if (a != i) {
         const float dx = px - qx[a];
         const float dy = py - qy[a];
-        const float d = sqrtf(dx * dx + dy * dy);
-        const float sp = softplus((A.ph.two_r - d) * A.ph.inv_margin);
-        const float k = A.ph.force_margin * sp / fmaxf(d, 1e-12f);
-        fx += k * dx;
-        fy += k * dy;
+        const float k = contact_factor(dx, dy, A.ph);
+        fx = fmaf(k, dx, fx);
+        fy = fmaf(k, dy, fy);
       }
     }
-    px += vx * A.ph.dt;
-    py += vy * A.ph.dt;
-    vx = vx * A.ph.keep + fx * A.ph.dt_over_mass;
-    vy = vy * A.ph.keep + fy * A.ph.dt_over_mass;
-    newpos[tid] = make_float2(px, py);
+    px = fmaf(vx, A.ph.dt, px);
+    py = fmaf(vy, A.ph.dt, py);
+    vx = fmaf(fx, A.ph.dt_over_mass, vx * A.ph.keep);
+    vy = fmaf(fy, A.ph.dt_over_mass, vy * A.ph.keep);
+    wave_sync();      // every lane of this wavefront has read its logits: the slots may be reused
+    *newpos_of(tid) = make_float2(px, py);
     __syncthreads();  // (C) new positions visible; everyone is done reading the tile
 
 #pragma unroll
     for (int a = 0; a < N; ++a) {
-      const float2 p = newpos[el * N + a];
+      const float2 p = *newpos_of(el * N + a);
       qx[a] = p.x;
       qy[a] = p.y;
     }
-    // coverage term of landmark i: min over agents of the distance to it
-    {
+    if constexpr (M::kRewardInRegs) {
+      // shared coverage reward, evaluated by every lane (N*N distances), stored by agent 0
+      float r = 0.0f;
+#pragma unroll
+      for (int l = 0; l < N; ++l) {
+        float best2 = INFINITY;
+#pragma unroll
+        for (int a = 0; a < N; ++a) {
+          const float dx = qx[a] - lx[l], dy = qy[a] - ly[l];
+          best2 = fminf(best2, fmaf(dx, dx, dy * dy));
+        }
+        r -= hw_sqrt(best2);
+      }
+      if (rew_base && env_writer) rew_base[gc] = r;
+    } else {
+      // coverage term of landmark i: min over agents of the distance to it
       float mylx = 0.0f, myly = 0.0f;
 #pragma unroll
       for (int l = 0; l < N; ++l) {
@@ -456,20 +539,29 @@ __global__ __launch_bounds__(EB * N) void rollout_policy_kernel(RolloutArgs A, c
 #pragma unroll
       for (int a = 0; a < N; ++a) {
         const float dx = qx[a] - mylx, dy = qy[a] - myly;
-        best2 = fminf(best2, dx * dx + dy * dy);
+        best2 = fminf(best2, fmaf(dx, dx, dy * dy));
       }
-      dminbuf[tid] = sqrtf(best2);
+      dminbuf[tid] = hw_sqrt(best2);
     }
     ep += 1;
     done_prev = ep >= A.ph.max_ep;
+    if constexpr (M::kRewardInRegs) {
+      if (done_base && env_writer) done_base[gc] = done_prev ? 1 : 0;
+    }
+    if (rew_base) rew_base += TE;
+    if (done_base) done_base += TE;
     if (done_prev) {
-      // new episode keyed by step + 1; every lane regenerates the whole env (rare: 1 step in max_ep)
+      // new episode keyed by step + 1; every lane regenerates the whole env (rare: 1 step in
+      // max_ep).  The empty asm keeps the compiler from hoisting the env-dependent first Philox
+      // round of all 2N streams out of the step loop, where it would only cost registers.
+      uint32_t env_r = env;
+      asm volatile("" : "+v"(env_r));
 #pragma unroll
       for (int a = 0; a < N; ++a) {
-        const uint4 w = philox4x32_10(env, step + 1u, uint32_t(a), kTagResetPos, A.seed, run);
+        const uint4 w = philox4x32_10(env_r, step + 1u, uint32_t(a), kTagResetPos, A.seed, run);
         qx[a] = word_to_position(w.x);
         qy[a] = word_to_position(w.y);
-        const uint4 wl = philox4x32_10(env, step + 1u, uint32_t(N + a), kTagResetPos, A.seed, run);
+        const uint4 wl = philox4x32_10(env_r, step + 1u, uint32_t(N + a), kTagResetPos, A.seed, run);
         lx[a] = word_to_position(wl.x);
         ly[a] = word_to_position(wl.y);
       }
@@ -523,10 +615,10 @@ hipError_t pack_impl(PolicyBuffers& pb, int R, const float* W1, const float* b1,
   return hipGetLastError();
 }
 
-template <int N, int H, bool BF16, int EB>
+template <int N, int H, bool BF16, int EB, int MINW>
 hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s) {
   using M = Smem<N, H, BF16, EB>;
-  auto kern = rollout_policy_kernel<N, H, BF16, EB>;
+  auto kern = rollout_policy_kernel<N, H, BF16, EB, MINW>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -548,18 +640,19 @@ void free_policy(PolicyBuffers& pb) {
   pb.bytes = 0;
 }
 
-// Supported policy shapes: (N, H, dtype) = (1|2|3, 64, fp32) and (10, 128, bf16).
+// Supported policy shapes (N, H, bf16, envs per block, min waves per SIMD):
+// (1|2|3, 64, fp32) and (10, 128, bf16).
 #define MPE_POLICY_CASES(X)        \
-  X(1, 64, false, 64)              \
-  X(2, 64, false, 64)              \
-  X(3, 64, false, 64)              \
-  X(10, 128, true, 32)
+  X(1, 64, false, 64, 3)           \
+  X(2, 64, false, 64, 3)           \
+  X(3, 64, false, 64, 3)           \
+  X(10, 128, true, 32, 2)
 
 hipError_t pack_policy(PolicyBuffers& pb, int N, int H, int R, int weight_dtype, const float* W1,
                        const float* b1, const float* W2, const float* b2, const float* W3,
                        const float* b3, hipStream_t s, const char** why) {
   const bool bf = weight_dtype == 1;
-#define X(N_, H_, BF_, EB_) \
+#define X(N_, H_, BF_, EB_, MW_) \
   if (N == N_ && H == H_ && bf == BF_) return pack_impl<N_, H_, BF_>(pb, R, W1, b1, W2, b2, W3, b3, s);
   MPE_POLICY_CASES(X)
 #undef X
@@ -570,13 +663,13 @@ hipError_t pack_policy(PolicyBuffers& pb, int N, int H, int R, int weight_dtype,
 hipError_t launch_rollout_policy(int N, int H, int weight_dtype, const RolloutArgs& A,
                                  const PolicyBuffers& pb, hipStream_t s, const char** why) {
   const bool bf = weight_dtype == 1;
-#define X(N_, H_, BF_, EB_)                                                                      \
+#define X(N_, H_, BF_, EB_, MW_)                                                                 \
   if (N == N_ && H == H_ && bf == BF_) {                                                         \
     if (A.TE != A.E && (A.E % EB_) != 0) {                                                       \
       *why = "with several runs, num_envs per run must be a multiple of the block's env count";  \
       return hipSuccess;                                                                         \
     }                                                                                            \
-    return rollout_impl<N_, H_, BF_, EB_>(A, pb, s);                                             \
+    return rollout_impl<N_, H_, BF_, EB_, MW_>(A, pb, s);                                        \
   }
   MPE_POLICY_CASES(X)
 #undef X

@@ -106,7 +106,8 @@ def _episode_errors(obs, ref_obs, done_ref):
 
 @pytest.mark.parametrize("E,N,T,seed,strict", [(64, 3, 100, 1, True), (64, 3, 100, 2, False), (200, 3, 60, 3, False),
                                                (50, 10, 60, 4, False), (64, 1, 30, 5, True), (65, 2, 30, 6, False),
-                                               (33, 4, 30, 7, False), (1000, 3, 125, 8, False)])
+                                               (33, 4, 30, 7, False), (1000, 3, 125, 8, False),
+                                               (1024, 3, 50, 9, False), (128, 2, 30, 10, False)])
 def test_uniform_rollout_matches_oracle(mods, E, N, T, seed, strict):
     MpeEnv, Oracle = mods
     say("uniform rollout E=%d N=%d T=%d seed=%d" % (E, N, T, seed))
@@ -145,9 +146,10 @@ def test_uniform_rollout_matches_oracle(mods, E, N, T, seed, strict):
     env.close()
 
 
-def test_rollout_continues_where_the_last_call_stopped(mods):
+@pytest.mark.parametrize("E", [100, 128])   # ragged (one wave per 64 envs) and whole-wave (two-wave blocks) kernels
+def test_rollout_continues_where_the_last_call_stopped(mods, E):
     MpeEnv, Oracle = mods
-    E, N = 100, 3
+    N = 3
     a, b = MpeEnv(Hp.gpu_config(E, N)), MpeEnv(Hp.gpu_config(E, N))
     a.reset(11)
     b.reset(11)
@@ -168,9 +170,10 @@ def test_rollout_continues_where_the_last_call_stopped(mods):
         e.close()
 
 
-def test_null_outputs_and_t1(mods):
+@pytest.mark.parametrize("E", [70, 192])
+def test_null_outputs_and_t1(mods, E):
     MpeEnv, _ = mods
-    E, N = 70, 3
+    N = 3
     a, b = MpeEnv(Hp.gpu_config(E, N)), MpeEnv(Hp.gpu_config(E, N))
     a.reset(3)
     b.reset(3)
@@ -180,6 +183,14 @@ def test_null_outputs_and_t1(mods):
     o = a.rollout(1, None, None, a.empty_traj(1)[2], None, None)
     r = b.rollout(1, *b.empty_traj(1))
     assert torch.equal(o[2], r[2])
+    # every single output on its own equals the all-outputs call
+    for k in range(5):
+        a.reset(8)
+        b.reset(8)
+        sel = [None] * 5
+        sel[k] = a.empty_traj(7)[k]
+        got = a.rollout(7, *sel)[k]
+        assert torch.equal(got, b.rollout(7, *b.empty_traj(7))[k]), k
     a.close()
     b.close()
 
