@@ -41,4 +41,17 @@ hipError_t launch_rollout_policy(int N, int H, int weight_dtype, const RolloutAr
                                  const PolicyBuffers& pb, hipStream_t s, const char** why);
 void free_policy(PolicyBuffers& pb);
 
+// Per-kernel-family entry points behind pack_policy / launch_rollout_policy.
+bool wide_supported(int N, int H);                       // bf16 general kernel
+hipError_t pack_policy_wide(PolicyBuffers& pb, int N, int H, int R, const float* W1, const float* b1,
+                            const float* W2, const float* b2, const float* W3, const float* b3, hipStream_t s);
+hipError_t launch_rollout_policy_wide(int N, int H, const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s,
+                                      const char** why);
+bool f32_supported(int N, int H);                        // fp32 headline kernel (H = 64, N <= 3)
+hipError_t pack_policy_f32(PolicyBuffers& pb, int N, int R, const float* W1, const float* b1, const float* W2,
+                           const float* b2, const float* W3, const float* b3, hipStream_t s);
+hipError_t launch_rollout_policy_f32(int N, const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s,
+                                     const char** why);
+hipError_t ensure_policy_bytes(PolicyBuffers& pb, size_t bytes);
+
 }  // namespace mpe

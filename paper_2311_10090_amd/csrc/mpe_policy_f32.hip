@@ -1,0 +1,597 @@
+// Fused rollout kernel for the headline shape: fp32 policy 6N -> 64 -> 64 -> 5 (N <= 3 agents),
+// shared by all agents or one set of weights per run (paper: App. G IPPO table, two tanh layers
+// of width 64; Sec. 3.2 parameter sharing; Sec. 4.2 / App. F vmap over whole training runs).
+//
+// Where the contraction runs.  On gfx950 the fp32 MFMA shares the vector datapath: fp32 matrix
+// and fp32 vector peaks are the same number, and measured MFMA-f32 and VALU time add up instead
+// of overlapping.  The 16-bit matrix cores are a separate unit, 16x faster per K, and do overlap
+// with VALU work.  So every fp32 operand is split EXACTLY into three bf16 terms
+//     x = h + m + l,   h = top 16 bits of x, m = top 16 bits of (x - h), l = x - h - m
+// (8 + 8 + 8 = 24 significant bits; each difference is exact in fp32) and the product of two
+// operands is accumulated in fp32 from the six cross terms of weight >= 2^-16:
+//     x*w ~= hh + hm + mh + hl + lh + mm      (dropped: ml + lm + ll <= 2^-23 |x w|)
+// i.e. the same operand values as an fp32 GEMM, with a truncation of the order of one fp32
+// rounding.  Weights are split once by the pack kernel; activations are split in registers.
+//
+// Mapping: one lane per agent row; a wavefront owns 64 rows = two pairs of 16-row tiles; each
+// A operand (weights, from LDS) is loaded once per pair.  The accumulator layout of
+// v_mfma_f32_16x16x32_bf16 (lane (j, gq) holds batch row j and hidden units 16m + 4gq + r) is
+// again a B-operand layout for the next layer when the weights are packed in the matching K
+// order, so activations stay in registers between layers.  Every wavefront works on its own
+// rows of the LDS observation tile; the only cross-wavefront data are the new positions of the
+// envs that straddle a wavefront boundary: one block barrier per step.
+#include "mpe_policy_common.h"
+
+namespace mpe {
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kH = 64;                    // hidden width
+constexpr float kPre = 2.0f * kLog2e;     // both tanh layers get pre-activations already times 2*log2(e)
+
+// ------------------------------------------------------------------------------ exact split
+// Bit patterns of the three terms as floats whose low 16 bits are zero.
+__host__ __device__ __forceinline__ void split3(float x, uint32_t& h, uint32_t& m, uint32_t& l) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  h = __float_as_uint(x) & 0xFFFF0000u;
+  const float r1 = x - __uint_as_float(h);
+  m = __float_as_uint(r1) & 0xFFFF0000u;
+  l = __float_as_uint(r1 - __uint_as_float(m));
+#else
+  h = m = l = 0;
+  (void)x;
+#endif
+}
+// Pack the high halves of two float bit patterns: low 16 bits <- a, high 16 bits <- b.
+__device__ __forceinline__ uint32_t pack_hi16(uint32_t a, uint32_t b) {
+  return __builtin_amdgcn_perm(b, a, 0x07060302u);
+}
+
+// Packed per-run layout (bytes).  A operands of v_mfma_f32_16x16x32_bf16: lane (i = lane%16,
+// gq = lane/16) holds weights [k = 8 gq + e][out = 16 m + i], e = 0..7 (16 bytes), per term.
+//   W1A [m 4][term 3][lane 32]   layer 1 reads 16 inputs: lanes gq >= 2 see zero activations and
+//                                 simply reuse the operand of lane - 32
+//   W2A [m 4][s 2][term 3][lane 64]
+//   W3A [s 2][term 3][lane 64]   (5 outputs padded to 16)
+//   bias b1*pre [64], b2*pre [64], b3 [16] fp32
+struct Pk {
+  static constexpr size_t OFF_W1A = 0;
+  static constexpr size_t W1A_BYTES = 4 * 3 * 32 * 16;
+  static constexpr size_t OFF_W2A = OFF_W1A + W1A_BYTES;
+  static constexpr size_t W2A_BYTES = 4 * 2 * 3 * 64 * 16;
+  static constexpr size_t OFF_W3A = OFF_W2A + W2A_BYTES;
+  static constexpr size_t W3A_BYTES = 2 * 3 * 64 * 16;
+  static constexpr size_t OFF_BIAS = OFF_W3A + W3A_BYTES;
+  static constexpr size_t BIAS_BYTES = (2 * kH + 16) * 4;
+  static constexpr size_t RUN_BYTES = OFF_BIAS + BIAS_BYTES;
+  static constexpr size_t LDS_BYTES = OFF_W3A;   // W1A + W2A live in LDS, W3A in registers
+};
+
+// hidden unit of K position (slice s, lane group gq, element e) in layers 2/3
+__host__ __device__ constexpr int hidden_k(int s, int gq, int e) { return 32 * s + 16 * (e / 4) + 4 * gq + (e % 4); }
+
+// One thread per packed bf16 element (all three terms of one weight) or bias value.
+template <int N>
+__global__ void pack_split_kernel(uint8_t* __restrict__ packed, const float* __restrict__ W1,
+                                  const float* __restrict__ b1, const float* __restrict__ W2,
+                                  const float* __restrict__ b2, const float* __restrict__ W3,
+                                  const float* __restrict__ b3) {
+  constexpr int D = 6 * N, KIN = 4 * N + 2;
+  const int run = blockIdx.y;
+  uint8_t* out = packed + size_t(run) * Pk::RUN_BYTES;
+  W1 += size_t(run) * D * kH;
+  b1 += size_t(run) * kH;
+  W2 += size_t(run) * kH * kH;
+  b2 += size_t(run) * kH;
+  W3 += size_t(run) * kH * kNumActions;
+  b3 += size_t(run) * kNumActions;
+  constexpr int n1 = 4 * 32 * 8, n2 = 4 * 2 * 64 * 8, n3 = 2 * 64 * 8, nb = 2 * kH + 16;
+  int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  auto put3 = [&](size_t off, int blk, int lanes, int lane, int e, float v) {
+    // blk = index of the [term][lane] group; terms are `lanes` * 16 bytes apart
+    uint32_t h, m, l;
+    split3(v, h, m, l);
+    uint16_t* base = reinterpret_cast<uint16_t*>(out + off) + size_t(blk) * 3 * lanes * 8 + lane * 8 + e;
+    base[0] = uint16_t(h >> 16);
+    base[size_t(lanes) * 8] = uint16_t(m >> 16);
+    base[size_t(2) * lanes * 8] = uint16_t(l >> 16);
+  };
+  if (idx < n1) {
+    const int e = idx % 8, lane = (idx / 8) % 32, m = idx / 256;
+    const int k = 8 * (lane / 16) + e, o = 16 * m + lane % 16;
+    put3(Pk::OFF_W1A, m, 32, lane, e, k < KIN ? kPre * W1[size_t(k) * kH + o] : 0.0f);
+    return;
+  }
+  idx -= n1;
+  if (idx < n2) {
+    const int e = idx % 8, lane = (idx / 8) % 64, s = (idx / 512) % 2, m = idx / 1024;
+    const int k = hidden_k(s, lane / 16, e), o = 16 * m + lane % 16;
+    put3(Pk::OFF_W2A, m * 2 + s, 64, lane, e, kPre * W2[size_t(k) * kH + o]);
+    return;
+  }
+  idx -= n2;
+  if (idx < n3) {
+    const int e = idx % 8, lane = (idx / 8) % 64, s = idx / 512;
+    const int k = hidden_k(s, lane / 16, e), o = lane % 16;
+    put3(Pk::OFF_W3A, s, 64, lane, e, o < kNumActions ? W3[size_t(k) * kNumActions + o] : 0.0f);
+    return;
+  }
+  idx -= n3;
+  if (idx < nb) {
+    float v;
+    if (idx < kH) v = kPre * b1[idx];
+    else if (idx < 2 * kH) v = kPre * b2[idx - kH];
+    else v = (idx - 2 * kH) < kNumActions ? b3[idx - 2 * kH] : 0.0f;
+    reinterpret_cast<float*>(out + Pk::OFF_BIAS)[idx] = v;
+  }
+}
+
+// ------------------------------------------------------------------------------ operands
+struct Terms {   // the three bf16x8 terms of one B (or A) operand
+  bf16x8 h, m, l;
+};
+
+// Split 8 fp32 activations into the three packed terms.
+__device__ __forceinline__ Terms split_operand(const float (&v)[8]) {
+  uint32_t h[8], m[8], l[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) split3(v[e], h[e], m[e], l[e]);
+  u32x4 ph, pm, pl;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    ph[q] = pack_hi16(h[2 * q], h[2 * q + 1]);
+    pm[q] = pack_hi16(m[2 * q], m[2 * q + 1]);
+    pl[q] = pack_hi16(l[2 * q], l[2 * q + 1]);
+  }
+  Terms t;
+  t.h = __builtin_bit_cast(bf16x8, ph);
+  t.m = __builtin_bit_cast(bf16x8, pm);
+  t.l = __builtin_bit_cast(bf16x8, pl);
+  return t;
+}
+
+#define MPE_MFMA_BF(A, B, C) __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, B, C, 0, 0, 0)
+
+// acc += A * B from the six significant cross terms, smallest first.
+__device__ __forceinline__ f32x4 mma_split(const Terms& a, const Terms& b, f32x4 acc) {
+  acc = MPE_MFMA_BF(a.l, b.h, acc);
+  acc = MPE_MFMA_BF(a.h, b.l, acc);
+  acc = MPE_MFMA_BF(a.m, b.m, acc);
+  acc = MPE_MFMA_BF(a.m, b.h, acc);
+  acc = MPE_MFMA_BF(a.h, b.m, acc);
+  acc = MPE_MFMA_BF(a.h, b.h, acc);
+  return acc;
+}
+
+// tanh of a pre-activation that arrives already multiplied by 2*log2(e).
+__device__ __forceinline__ float tanh_prescaled(float y) {
+  return fmaf(-2.0f, hw_rcp(hw_exp2(y) + 1.0f), 1.0f);
+}
+
+struct W3Terms {
+  Terms s[2];
+};
+
+// Policy forward of two 16-row tiles X and Y whose observation rows are in LDS (row stride D).
+// Logits of row j go to cols 0..4 of that row (they are rewritten by the next observation).
+template <int N>
+__device__ __forceinline__ void policy_pair(const uint8_t* __restrict__ wsm, const float* __restrict__ bias,
+                                            const W3Terms& w3, float* __restrict__ rowsX,
+                                            float* __restrict__ rowsY, int lane) {
+  constexpr int D = 6 * N;
+  const int j = lane & 15, gq = lane >> 4;
+  {
+    // Opaque zero offset: keeps the (loop-invariant) LDS weight reads inside the step loop, where
+    // hoisting them would cost ~100 registers and a wavefront of occupancy.  An integer, not a
+    // laundered pointer, so the loads stay ds_read instructions.
+    uint32_t zero = 0;
+    asm volatile("" : "+v"(zero));
+    wsm += zero;
+    bias += zero;
+  }
+  const bf16x8* w1 = reinterpret_cast<const bf16x8*>(wsm + Pk::OFF_W1A);  // [m][term][lane32]
+  const bf16x8* w2 = reinterpret_cast<const bf16x8*>(wsm + Pk::OFF_W2A);  // [m][s][term][lane64]
+  // ---- layer 1: 16 inputs (cols 0..15 of the row; cols >= 4N+2 are zeros or meet zero weights)
+  Terms bx, by;
+  {
+    float vx[8], vy[8];
+    if (gq < 2) {
+      // rows are D*4 bytes apart (a multiple of 8, not of 16): read as float2
+      const float2* xs = reinterpret_cast<const float2*>(rowsX + j * D + 8 * gq);
+      const float2* ys = reinterpret_cast<const float2*>(rowsY + j * D + 8 * gq);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float2 xv = xs[q], yv = ys[q];
+        vx[2 * q] = xv.x; vx[2 * q + 1] = xv.y;
+        vy[2 * q] = yv.x; vy[2 * q + 1] = yv.y;
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vx[e] = vy[e] = 0.0f;
+    }
+    bx = split_operand(vx);
+    by = split_operand(vy);
+  }
+  f32x4 accX[4], accY[4];
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    accX[m] = *reinterpret_cast<const f32x4*>(bias + 16 * m + 4 * gq);
+    accY[m] = accX[m];
+    Terms a;
+    a.h = w1[(m * 3 + 0) * 32 + (lane & 31)];
+    a.m = w1[(m * 3 + 1) * 32 + (lane & 31)];
+    a.l = w1[(m * 3 + 2) * 32 + (lane & 31)];
+    accX[m] = mma_split(a, bx, accX[m]);
+    accY[m] = mma_split(a, by, accY[m]);
+  }
+  // ---- tanh, layer 2
+  float hx[16], hy[16];
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      hx[4 * m + r] = tanh_prescaled(accX[m][r]);
+      hy[4 * m + r] = tanh_prescaled(accY[m][r]);
+    }
+    accX[m] = *reinterpret_cast<const f32x4*>(bias + kH + 16 * m + 4 * gq);
+    accY[m] = accX[m];
+  }
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    // K slice s takes accumulator tiles 2s and 2s+1: element e <-> tile 2s + e/4, register e%4
+    float vx[8], vy[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { vx[e] = hx[8 * s + e]; vy[e] = hy[8 * s + e]; }
+    bx = split_operand(vx);
+    by = split_operand(vy);
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+      Terms a;
+      a.h = w2[((m * 2 + s) * 3 + 0) * 64 + lane];
+      a.m = w2[((m * 2 + s) * 3 + 1) * 64 + lane];
+      a.l = w2[((m * 2 + s) * 3 + 2) * 64 + lane];
+      accX[m] = mma_split(a, bx, accX[m]);
+      accY[m] = mma_split(a, by, accY[m]);
+    }
+  }
+  // ---- tanh, layer 3 (5 outputs padded to one 16-wide tile)
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      hx[4 * m + r] = tanh_prescaled(accX[m][r]);
+      hy[4 * m + r] = tanh_prescaled(accY[m][r]);
+    }
+  }
+  f32x4 zX = *reinterpret_cast<const f32x4*>(bias + 2 * kH + 4 * gq);
+  f32x4 zY = zX;
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    float vx[8], vy[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { vx[e] = hx[8 * s + e]; vy[e] = hy[8 * s + e]; }
+    bx = split_operand(vx);
+    by = split_operand(vy);
+    zX = mma_split(w3.s[s], bx, zX);
+    zY = mma_split(w3.s[s], by, zY);
+  }
+  // lane (j, gq) holds outputs 4gq + r of row j: outputs 0..3 in group 0, output 4 in group 1
+  if (gq == 0) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      rowsX[j * D + r] = zX[r];
+      rowsY[j * D + r] = zY[r];
+    }
+  } else if (gq == 1) {
+    rowsX[j * D + 4] = zX[0];
+    rowsY[j * D + 4] = zY[0];
+  }
+}
+
+// LDS plan (bytes).
+template <int N, int EB>
+struct SmemF32 {
+  static constexpr int D = 6 * N;
+  static constexpr int ROWS = EB * N;
+  static constexpr size_t OFF_BIAS = Pk::LDS_BYTES;
+  static constexpr size_t OFF_OBS = OFF_BIAS + Pk::BIAS_BYTES;
+  static constexpr size_t OBS = size_t(ROWS) * D * 4 + 64;           // + zeroed tail: layer 1 reads 16 cols
+  static constexpr size_t OFF_NEWPOS = OFF_OBS + OBS;                // [2][ROWS] float2, by step parity
+  static constexpr size_t TOTAL = OFF_NEWPOS + size_t(2) * ROWS * 8;
+  static_assert(OFF_OBS % 16 == 0 && OFF_NEWPOS % 16 == 0, "alignment");
+};
+
+template <int N, int EB, int MINW>
+__global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
+                                                                          int per_run_weights) {
+  using M = SmemF32<N, EB>;
+  constexpr int D = 6 * N, ROWS = EB * N, THREADS = ROWS;
+  static_assert(THREADS % 64 == 0, "block must be whole wavefronts");
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+  uint8_t* wsm = smem;
+  float* bias = reinterpret_cast<float*>(smem + M::OFF_BIAS);
+  float* tile = reinterpret_cast<float*>(smem + M::OFF_OBS);
+  float2* newpos = reinterpret_cast<float2*>(smem + M::OFF_NEWPOS);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int el = tid / N, i = tid - el * N;          // env within block, agent
+  const size_t TE = A.TE;
+  const size_t g0 = size_t(blockIdx.x) * EB;
+  const size_t g = g0 + el;
+  const bool valid = g < TE;
+  const uint32_t gc = valid ? uint32_t(g) : uint32_t(g0);
+  const uint32_t run = gc / A.E;
+  const uint32_t env = gc - run * A.E;
+  const size_t left = TE - g0;
+  const int nvalid = left < size_t(EB) ? int(left) : EB;   // valid envs in this block
+  // rows of this wavefront that belong to valid envs
+  const int wave_rows = min(max(nvalid * N - wave * 64, 0), 64);
+
+  // ---- stage this block's weights (the run of its first env): W1A, W2A, biases in LDS; W3A in registers
+  const uint8_t* run_weights = packed + (per_run_weights ? size_t(uint32_t(g0) / A.E) * Pk::RUN_BYTES : 0);
+  W3Terms w3;
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    const bf16x8* src = reinterpret_cast<const bf16x8*>(run_weights + Pk::OFF_W3A) + s * 3 * 64 + lane;
+    w3.s[s].h = src[0];
+    w3.s[s].m = src[64];
+    w3.s[s].l = src[128];
+  }
+  {
+    const uint4* src = reinterpret_cast<const uint4*>(run_weights);
+    uint4* dst = reinterpret_cast<uint4*>(wsm);
+    for (int k = tid; k < int(Pk::LDS_BYTES / 16); k += THREADS) dst[k] = src[k];
+    const uint4* bsrc = reinterpret_cast<const uint4*>(run_weights + Pk::OFF_BIAS);
+    uint4* bdst = reinterpret_cast<uint4*>(bias);
+    for (int k = tid; k < int(Pk::BIAS_BYTES / 16); k += THREADS) bdst[k] = bsrc[k];
+    if (tid < 16) tile[ROWS * D + tid] = 0.0f;
+  }
+
+  // ---- registers: own agent, all agents' positions, all landmarks
+  float px = 0.0f, py = 0.0f, vx = 0.0f, vy = 0.0f;
+  float qx[N], qy[N], lx[N], ly[N];
+  int32_t ep = 0;
+#pragma unroll
+  for (int a = 0; a < N; ++a) qx[a] = qy[a] = lx[a] = ly[a] = 0.0f;
+  if (valid) {
+#pragma unroll
+    for (int a = 0; a < N; ++a) {
+      qx[a] = A.st.pos_a[(0 * N + a) * TE + g];
+      qy[a] = A.st.pos_a[(1 * N + a) * TE + g];
+      lx[a] = A.st.pos_l[(0 * N + a) * TE + g];
+      ly[a] = A.st.pos_l[(1 * N + a) * TE + g];
+    }
+    vx = A.st.vel_a[(0 * N + i) * TE + g];
+    vy = A.st.vel_a[(1 * N + i) * TE + g];
+    ep = A.st.ep_step[g];
+  }
+#pragma unroll
+  for (int a = 0; a < N; ++a) {
+    if (a == i) { px = qx[a]; py = qy[a]; }
+  }
+
+  // Write this lane's observation row into the tile (the zero comm slots only the first time).
+  auto write_obs_row = [&](bool with_zeros) {
+    float2* row = reinterpret_cast<float2*>(tile + tid * D);
+    int c = 0;
+    row[c++] = make_float2(vx, vy);
+    row[c++] = make_float2(px, py);
+#pragma unroll
+    for (int l = 0; l < N; ++l) row[c++] = make_float2(lx[l] - px, ly[l] - py);
+#pragma unroll
+    for (int a = 0; a < N; ++a) {
+      if (a != i) row[c++] = make_float2(qx[a] - px, qy[a] - py);
+    }
+    if (with_zeros) {
+      for (int zc = 0; zc < N - 1; ++zc) row[c + zc] = make_float2(0.0f, 0.0f);
+    }
+  };
+  write_obs_row(true);
+  __syncthreads();  // weights, biases, zero tail staged; from here on wavefronts only meet at (C)
+
+  // Output addresses = uniform per-step base (advanced once per step, lives in SGPRs) + a
+  // 32-bit lane offset that never changes.
+  const size_t wave_row0 = (g0 * N + size_t(wave) * 64) * D;   // float offset of this wavefront's rows in a slice
+  float* obs_p = A.obs_traj ? A.obs_traj + wave_row0 : nullptr;
+  uint8_t* act_base = A.act_traj;
+  float* rew_base = A.rew_traj;
+  uint8_t* done_base = A.done_traj;
+  const uint32_t row_off = uint32_t(gc) * N + i;      // index of this agent inside a time slice
+  const bool env_writer = valid && i == 0;            // the lane that stores per-env outputs
+  uint32_t step = A.abs_step;
+  const float* wtile = tile + wave * (64 * D);        // this wavefront's rows
+
+  // Stream this wavefront's rows of the tile to dst (its slot in a [env][N][D] slice).
+  auto flush_rows = [&](float* dst) {
+    const bool vec4 = (reinterpret_cast<uintptr_t>(dst) & 15u) == 0;
+    if (vec4 && wave_rows == 64) stream_out_full<64 * D / 4>(wtile, dst, lane);
+    else stream_out(wtile, dst, wave_rows * D, vec4, lane);
+  };
+
+  for (int t = 0; t < A.T; ++t, ++step) {
+    wave_sync();  // this wavefront's rows of the tile are complete
+    if (obs_p) {
+      flush_rows(obs_p);
+      obs_p += TE * (N * D);
+    }
+    // ---- policy: two pairs of 16-row tiles per wavefront
+#pragma unroll 1
+    for (int pr = 0; pr < 2; ++pr) {
+      float* rows = tile + (wave * 64 + pr * 32) * D;
+      policy_pair<N>(wsm, bias, w3, rows, rows + 16 * D, lane);
+    }
+    wave_sync();
+    float z[kNumActions];
+#pragma unroll
+    for (int k = 0; k < kNumActions; ++k) z[k] = tile[tid * D + k];
+    const uint32_t act = gumbel_argmax(z, A.seed, run, env, step, uint32_t(i));
+    if (act_base) {
+      if (valid) act_base[row_off] = uint8_t(act);
+      act_base += TE * N;
+    }
+
+    // ---- transition of this lane's agent
+    float fx = A.ph.accel * action_dir_x(act);
+    float fy = A.ph.accel * action_dir_y(act);
+#pragma unroll
+    for (int a = 0; a < N; ++a) {
+      if (a != i) {
+        const float dx = px - qx[a];
+        const float dy = py - qy[a];
+        const float k = contact_factor(dx, dy, A.ph);
+        fx = fmaf(k, dx, fx);
+        fy = fmaf(k, dy, fy);
+      }
+    }
+    px = fmaf(vx, A.ph.dt, px);
+    py = fmaf(vy, A.ph.dt, py);
+    vx = fmaf(fx, A.ph.dt_over_mass, vx * A.ph.keep);
+    vy = fmaf(fy, A.ph.dt_over_mass, vy * A.ph.keep);
+    float2* np = newpos + (t & 1) * ROWS;
+    np[tid] = make_float2(px, py);
+    __syncthreads();  // (C) new positions of every agent of every env of the block are visible
+
+#pragma unroll
+    for (int a = 0; a < N; ++a) {
+      const float2 p = np[el * N + a];
+      qx[a] = p.x;
+      qy[a] = p.y;
+    }
+    // shared coverage reward, evaluated by every lane (N*N distances), stored by agent 0
+    {
+      float r = 0.0f;
+#pragma unroll
+      for (int l = 0; l < N; ++l) {
+        float best2 = INFINITY;
+#pragma unroll
+        for (int a = 0; a < N; ++a) {
+          const float dx = qx[a] - lx[l], dy = qy[a] - ly[l];
+          best2 = fminf(best2, fmaf(dx, dx, dy * dy));
+        }
+        r -= hw_sqrt(best2);
+      }
+      if (rew_base) {
+        if (env_writer) rew_base[gc] = r;
+        rew_base += TE;
+      }
+    }
+    ep += 1;
+    const bool done = ep >= A.ph.max_ep;
+    if (done_base) {
+      if (env_writer) done_base[gc] = done ? 1 : 0;
+      done_base += TE;
+    }
+    if (done) {
+      // new episode keyed by step + 1; every lane regenerates the whole env (rare: 1 step in
+      // max_ep).  The empty asm keeps the compiler from hoisting the env-dependent first Philox
+      // round of all 2N streams out of the step loop, where it would only cost registers.
+      uint32_t env_r = env;
+      asm volatile("" : "+v"(env_r));
+#pragma unroll
+      for (int a = 0; a < N; ++a) {
+        const uint4 w = philox4x32_10(env_r, step + 1u, uint32_t(a), kTagResetPos, A.seed, run);
+        qx[a] = word_to_position(w.x);
+        qy[a] = word_to_position(w.y);
+        const uint4 wl = philox4x32_10(env_r, step + 1u, uint32_t(N + a), kTagResetPos, A.seed, run);
+        lx[a] = word_to_position(wl.x);
+        ly[a] = word_to_position(wl.y);
+      }
+#pragma unroll
+      for (int a = 0; a < N; ++a) {
+        if (a == i) { px = qx[a]; py = qy[a]; }
+      }
+      vx = vy = 0.0f;
+      ep = 0;
+    }
+    write_obs_row(false);
+  }
+  if (A.last_obs) {
+    wave_sync();
+    flush_rows(A.last_obs + wave_row0);
+  }
+
+  // ---- state back to HBM
+  if (valid) {
+    A.st.pos_a[(0 * N + i) * TE + g] = px;
+    A.st.pos_a[(1 * N + i) * TE + g] = py;
+    A.st.vel_a[(0 * N + i) * TE + g] = vx;
+    A.st.vel_a[(1 * N + i) * TE + g] = vy;
+#pragma unroll
+    for (int l = 0; l < N; ++l) {
+      if (l == i) {
+        A.st.pos_l[(0 * N + l) * TE + g] = lx[l];
+        A.st.pos_l[(1 * N + l) * TE + g] = ly[l];
+      }
+    }
+    if (i == 0) A.st.ep_step[g] = ep;
+  }
+}
+
+template <int N, int EB, int MINW>
+hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s) {
+  using M = SmemF32<N, EB>;
+  auto kern = rollout_policy_f32_kernel<N, EB, MINW>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(M::TOTAL));
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const dim3 grid((A.TE + EB - 1) / EB);
+  hipLaunchKernelGGL(kern, grid, dim3(EB * N), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),
+                     int(A.TE != A.E));
+  return hipGetLastError();
+}
+
+template <int N>
+hipError_t pack_impl(PolicyBuffers& pb, int R, const float* W1, const float* b1, const float* W2,
+                     const float* b2, const float* W3, const float* b3, hipStream_t s) {
+  if (hipError_t e = ensure_policy_bytes(pb, size_t(R) * Pk::RUN_BYTES); e != hipSuccess) return e;
+  constexpr int total = 4 * 32 * 8 + 4 * 2 * 64 * 8 + 2 * 64 * 8 + 2 * kH + 16;
+  dim3 grid((total + 255) / 256, R);
+  hipLaunchKernelGGL(pack_split_kernel<N>, grid, dim3(256), 0, s, static_cast<uint8_t*>(pb.packed), W1, b1, W2,
+                     b2, W3, b3);
+  return hipGetLastError();
+}
+
+// Envs per block: 64 (N wavefronts).  Measured at 65,536 envs x 3 agents: three resident blocks
+// of 64 envs per CU beat two of 128 (a barrier among six wavefronts costs more than the second
+// round of blocks).  With several runs every block must lie inside one run.
+template <int N>
+hipError_t launch_n(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s, const char** why) {
+  const bool one_run = A.TE == A.E;
+  if (one_run || A.E % 64 == 0) return rollout_impl<N, 64, 3>(A, pb, s);
+  *why = "with several runs, num_envs per run must be a multiple of 64";
+  return hipSuccess;
+}
+
+}  // namespace
+
+bool f32_supported(int N, int H) { return H == kH && N >= 1 && N <= 3; }
+
+hipError_t pack_policy_f32(PolicyBuffers& pb, int N, int R, const float* W1, const float* b1, const float* W2,
+                           const float* b2, const float* W3, const float* b3, hipStream_t s) {
+  switch (N) {
+    case 1: return pack_impl<1>(pb, R, W1, b1, W2, b2, W3, b3, s);
+    case 2: return pack_impl<2>(pb, R, W1, b1, W2, b2, W3, b3, s);
+    case 3: return pack_impl<3>(pb, R, W1, b1, W2, b2, W3, b3, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_rollout_policy_f32(int N, const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s,
+                                     const char** why) {
+  switch (N) {
+    case 1: return launch_n<1>(A, pb, s, why);
+    case 2: return launch_n<2>(A, pb, s, why);
+    case 3: return launch_n<3>(A, pb, s, why);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace mpe

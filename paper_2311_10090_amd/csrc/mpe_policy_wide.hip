@@ -14,154 +14,17 @@
 // matching K order, so activations never leave registers between layers.  Weights are
 // packed once (mpe_set_policy) into that A-operand order and staged in LDS per block.
 //
+// This file holds the general kernel (bf16 operands, wide layers, many agents); the fp32
+// headline shape has its own kernel in mpe_policy_f32.hip.
+//
 // Policy shape follows the paper's MPE setting (App. G, IPPO table: two tanh layers of width
 // 64, parameters shared by all agents; Sec. 3.2 "PPO"); the scaled scenario uses width 128
 // with bf16 operands and fp32 accumulation.
-#include "mpe_launch.h"
+#include "mpe_policy_common.h"
 
 namespace mpe {
 
 namespace {
-
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-
-__host__ __device__ constexpr int cdiv(int a, int b) { return (a + b - 1) / b; }
-
-template <int N, int H, bool BF16>
-struct Shape {
-  static constexpr int D = 6 * N;
-  static constexpr int KIN = 4 * N + 2;           // non-zero leading entries of an observation
-  static constexpr int KS = BF16 ? 32 : 4;        // K extent of one MFMA
-  static constexpr int MT = H / 16;               // 16-wide tiles of hidden units
-  static constexpr int S1 = cdiv(KIN, KS);        // K slices of layer 1
-  static constexpr int S2 = H / KS;               // K slices of layers 2 and 3
-  static constexpr int ELT = BF16 ? 2 : 4;        // bytes per weight
-  static constexpr int LANE_ELTS = BF16 ? 8 : 1;  // A-operand elements one lane holds per MFMA
-  // packed buffer sections (bytes), all multiples of 16
-  static constexpr size_t W1A_BYTES = size_t(MT) * S1 * 64 * LANE_ELTS * ELT;
-  static constexpr size_t W2A_BYTES = size_t(MT) * S2 * 64 * LANE_ELTS * ELT;
-  static constexpr size_t W3A_BYTES = size_t(S2) * 64 * LANE_ELTS * ELT;
-  static constexpr size_t BIAS_BYTES = size_t(2 * H + 16) * 4;
-  static constexpr size_t OFF_W1A = 0;
-  static constexpr size_t OFF_W2A = OFF_W1A + W1A_BYTES;
-  static constexpr size_t OFF_W3A = OFF_W2A + W2A_BYTES;
-  static constexpr size_t OFF_BIAS = OFF_W3A + W3A_BYTES;
-  static constexpr size_t RUN_BYTES = OFF_BIAS + BIAS_BYTES;
-};
-
-// Hidden unit that K position (slice s, lane group gq, element e) of layers 2/3 refers to:
-// the accumulator register (tile m, r) of lane group gq holds unit 16m + 4gq + r.
-template <bool BF16>
-__host__ __device__ constexpr int hidden_of(int s, int gq, int e) {
-  return BF16 ? (32 * s + 16 * (e / 4) + 4 * gq + (e % 4)) : (16 * (s / 4) + 4 * gq + (s % 4));
-}
-
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return uint16_t((u >> 16) | 0x40u);  // NaN stays NaN
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return uint16_t(u >> 16);
-}
-
-// One thread per packed element of one run.
-template <int N, int H, bool BF16>
-__global__ void pack_policy_kernel(uint8_t* __restrict__ packed, const float* __restrict__ W1,
-                                   const float* __restrict__ b1, const float* __restrict__ W2,
-                                   const float* __restrict__ b2, const float* __restrict__ W3,
-                                   const float* __restrict__ b3) {
-  using S = Shape<N, H, BF16>;
-  const int run = blockIdx.y;
-  uint8_t* out = packed + size_t(run) * S::RUN_BYTES;
-  W1 += size_t(run) * S::D * H;
-  b1 += size_t(run) * H;
-  W2 += size_t(run) * H * H;
-  b2 += size_t(run) * H;
-  W3 += size_t(run) * H * kNumActions;
-  b3 += size_t(run) * kNumActions;
-  const int n1 = S::MT * S::S1 * 64 * S::LANE_ELTS;
-  const int n2 = S::MT * S::S2 * 64 * S::LANE_ELTS;
-  const int n3 = S::S2 * 64 * S::LANE_ELTS;
-  const int nb = 2 * H + 16;
-  int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  auto put = [&](size_t off, int i, float v) {
-    if (BF16) reinterpret_cast<uint16_t*>(out + off)[i] = f32_to_bf16_rne(v);
-    else reinterpret_cast<float*>(out + off)[i] = v;
-  };
-  if (idx < n1) {
-    // [m][s][lane][e] ; lane (i = lane%16, gq = lane/16) ; k = KS*s + LANE_ELTS*gq + e (natural order)
-    const int e = idx % S::LANE_ELTS, lane = (idx / S::LANE_ELTS) % 64;
-    const int s = (idx / (S::LANE_ELTS * 64)) % S::S1, m = idx / (S::LANE_ELTS * 64 * S::S1);
-    const int k = S::KS * s + S::LANE_ELTS * (lane / 16) + e;
-    const int o = 16 * m + lane % 16;
-    put(S::OFF_W1A, idx, k < S::KIN ? W1[size_t(k) * H + o] : 0.0f);
-    return;
-  }
-  idx -= n1;
-  if (idx < n2) {
-    int m, s, lane, e;
-    if (BF16) {  // [m][s][lane][8]
-      e = idx % 8; lane = (idx / 8) % 64; s = (idx / 512) % S::S2; m = idx / (512 * S::S2);
-    } else {     // [m][s/4][lane][s%4]
-      const int s_lo = idx % 4; lane = (idx / 4) % 64; const int s_hi = (idx / 256) % (S::S2 / 4);
-      m = idx / (256 * (S::S2 / 4)); s = 4 * s_hi + s_lo; e = 0;
-    }
-    const int k = hidden_of<BF16>(s, lane / 16, e);
-    put(S::OFF_W2A, idx, W2[size_t(k) * H + 16 * m + lane % 16]);
-    return;
-  }
-  idx -= n2;
-  if (idx < n3) {
-    int s, lane, e;
-    if (BF16) { e = idx % 8; lane = (idx / 8) % 64; s = idx / 512; }
-    else { const int s_lo = idx % 4; lane = (idx / 4) % 64; s = 4 * (idx / 256) + s_lo; e = 0; }
-    const int k = hidden_of<BF16>(s, lane / 16, e);
-    const int o = lane % 16;
-    put(S::OFF_W3A, idx, o < kNumActions ? W3[size_t(k) * kNumActions + o] : 0.0f);
-    return;
-  }
-  idx -= n3;
-  if (idx < nb) {
-    float v;
-    if (idx < H) v = b1[idx];
-    else if (idx < 2 * H) v = b2[idx - H];
-    else v = (idx - 2 * H) < kNumActions ? b3[idx - 2 * H] : 0.0f;
-    reinterpret_cast<float*>(out + S::OFF_BIAS)[idx] = v;
-  }
-}
-
-// tanh(x) = 1 - 2 / (exp(2x) + 1) on the hardware exp2 / rcp units.  Absolute error ~1e-7;
-// saturates cleanly (exp2 -> inf gives 1, exp2 -> 0 gives -1).
-__device__ __forceinline__ float fast_tanh(float x) {
-  const float t = hw_exp2(x * (2.0f * kLog2e));
-  return fmaf(-2.0f, hw_rcp(t + 1.0f), 1.0f);
-}
-
-__device__ __forceinline__ void wave_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// Gumbel-max over 5 logits: g = -ln(-ln u), u odd multiples of 2^-24 from two Philox blocks.
-// ln = ln2 * log2 on the hardware unit (u >= 2^-24 is a normal number; -ln u is in
-// [6e-8, 16.7], also normal), so v_k = z_k - ln2 * log2(-ln2 * log2(u_k)).
-__device__ __forceinline__ uint32_t gumbel_argmax(const float (&z)[kNumActions], uint32_t seed,
-                                                  uint32_t run, uint32_t env, uint32_t step, uint32_t agent) {
-  const uint4 w0 = philox4x32_10(env, step, agent, kTagGumbel0, seed, run);
-  const uint4 w1 = philox4x32_10(env, step, agent, kTagGumbel1, seed, run);
-  const uint32_t w[kNumActions] = {w0.x, w0.y, w0.z, w0.w, w1.x};
-  uint32_t best = 0;
-  float best_v = -INFINITY;
-#pragma unroll
-  for (int k = 0; k < kNumActions; ++k) {
-    const float u = word_to_open_uniform(w[k]);
-    const float e = -kLn2 * hw_log2(u);               // -ln u  > 0
-    const float v = fmaf(-kLn2, hw_log2(e), z[k]);     // z - ln(-ln u)
-    if (v > best_v) { best_v = v; best = uint32_t(k); }
-  }
-  return best;
-}
 
 // LDS plan of one block (bytes).  The logits buffer and the new-position exchange share one
 // region: within a phase each wavefront touches only its own 64 rows of it (logits first, then
@@ -201,13 +64,14 @@ struct W3Regs {
   }
 };
 
-// MLP forward of one 16-row tile; rows' observations are in the LDS tile at obs_rows
-// (row stride D floats).  wsm holds W1A then W2A, bias holds b1, b2, b3 (padded to 16).
-// Leaves logits of row j in zrows[j*5 .. j*5+4].
+// MLP forward of one 16-row tile (general kernel: bf16 operands, fp32 accumulation); rows'
+// observations are in the LDS tile at obs_rows (row stride D floats).  wsm holds W1A then W2A,
+// bias holds b1, b2, b3 (padded to 16).  Leaves logits of row j in zrows[j*5 .. j*5+4].
 template <int N, int H, bool BF16>
 __device__ __forceinline__ void policy_tile(const uint8_t* __restrict__ wsm, const float* __restrict__ bias,
                                             const W3Regs<N, H, BF16>& w3, const float* __restrict__ obs_rows,
                                             float* __restrict__ zrows, int lane) {
+  static_assert(BF16, "the fp32 shape has its own pipelined kernel");
   using S = Shape<N, H, BF16>;
   constexpr int D = S::D, MT = S::MT;
   const int j = lane & 15, gq = lane >> 4;
@@ -226,16 +90,7 @@ __device__ __forceinline__ void policy_tile(const uint8_t* __restrict__ wsm, con
 #pragma unroll
   for (int m = 0; m < MT; ++m) acc[m] = *reinterpret_cast<const f32x4*>(bias + 16 * m + 4 * gq);
   // ---- layer 1
-  if constexpr (!BF16) {
-    const float* w1 = reinterpret_cast<const float*>(wsm + S::OFF_W1A);
-#pragma unroll
-    for (int s = 0; s < S::S1; ++s) {
-      const float b = obs_rows[j * D + 4 * s + gq];
-#pragma unroll
-      for (int m = 0; m < MT; ++m)
-        acc[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(w1[(m * S::S1 + s) * 64 + lane], b, acc[m], 0, 0, 0);
-    }
-  } else {
+  {
     const bf16x8* w1 = reinterpret_cast<const bf16x8*>(wsm + S::OFF_W1A);
 #pragma unroll
     for (int s = 0; s < S::S1; ++s) {
@@ -257,21 +112,7 @@ __device__ __forceinline__ void policy_tile(const uint8_t* __restrict__ wsm, con
     acc[m] = *reinterpret_cast<const f32x4*>(bias + H + 16 * m + 4 * gq);
   }
   // ---- layer 2
-  if constexpr (!BF16) {
-    const f32x4* w2 = reinterpret_cast<const f32x4*>(wsm + S::OFF_W2A);
-#pragma unroll
-    for (int s4 = 0; s4 < S::S2 / 4; ++s4) {
-      f32x4 a[MT];
-#pragma unroll
-      for (int m = 0; m < MT; ++m) a[m] = w2[(m * (S::S2 / 4) + s4) * 64 + lane];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-#pragma unroll
-        for (int m = 0; m < MT; ++m)
-          acc[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[m][r], hid[s4][r], acc[m], 0, 0, 0);
-      }
-    }
-  } else {
+  {
     const bf16x8* w2 = reinterpret_cast<const bf16x8*>(wsm + S::OFF_W2A);
 #pragma unroll
     for (int s = 0; s < S::S2; ++s) {
@@ -291,23 +132,13 @@ __device__ __forceinline__ void policy_tile(const uint8_t* __restrict__ wsm, con
   // ---- layer 3; two accumulators break the dependent chain
   f32x4 z0 = *reinterpret_cast<const f32x4*>(bias + 2 * H + 4 * gq);
   f32x4 z1 = {0.0f, 0.0f, 0.0f, 0.0f};
-  if constexpr (!BF16) {
 #pragma unroll
-    for (int s4 = 0; s4 < S::S2 / 4; ++s4) {
-      z0 = __builtin_amdgcn_mfma_f32_16x16x4f32(w3.f[s4][0], hid[s4][0], z0, 0, 0, 0);
-      z1 = __builtin_amdgcn_mfma_f32_16x16x4f32(w3.f[s4][1], hid[s4][1], z1, 0, 0, 0);
-      z0 = __builtin_amdgcn_mfma_f32_16x16x4f32(w3.f[s4][2], hid[s4][2], z0, 0, 0, 0);
-      z1 = __builtin_amdgcn_mfma_f32_16x16x4f32(w3.f[s4][3], hid[s4][3], z1, 0, 0, 0);
-    }
-  } else {
+  for (int s = 0; s < S::S2; ++s) {
+    bf16x8 b;
 #pragma unroll
-    for (int s = 0; s < S::S2; ++s) {
-      bf16x8 b;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) { b[e] = __bf16(hid[2 * s][e]); b[4 + e] = __bf16(hid[2 * s + 1][e]); }
-      if (s & 1) z1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w3.b[s], b, z1, 0, 0, 0);
-      else z0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w3.b[s], b, z0, 0, 0, 0);
-    }
+    for (int e = 0; e < 4; ++e) { b[e] = __bf16(hid[2 * s][e]); b[4 + e] = __bf16(hid[2 * s + 1][e]); }
+    if (s & 1) z1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w3.b[s], b, z1, 0, 0, 0);
+    else z0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w3.b[s], b, z0, 0, 0, 0);
   }
   z0 += z1;
   // lane (j, gq) holds outputs 4gq + r of row j: outputs 0..3 in group 0, output 4 in group 1
@@ -596,18 +427,7 @@ template <int N, int H, bool BF16>
 hipError_t pack_impl(PolicyBuffers& pb, int R, const float* W1, const float* b1, const float* W2,
                      const float* b2, const float* W3, const float* b3, hipStream_t s) {
   using S = Shape<N, H, BF16>;
-  const size_t bytes = size_t(R) * S::RUN_BYTES;
-  if (pb.bytes < bytes) {
-    if (pb.packed) {
-      hipError_t e = hipFree(pb.packed);
-      if (e != hipSuccess) return e;
-      pb.packed = nullptr;
-      pb.bytes = 0;
-    }
-    hipError_t e = hipMalloc(&pb.packed, bytes);
-    if (e != hipSuccess) return e;
-    pb.bytes = bytes;
-  }
+  if (hipError_t e = ensure_policy_bytes(pb, size_t(R) * S::RUN_BYTES); e != hipSuccess) return e;
   const int total = int(S::RUN_BYTES / S::ELT);  // upper bound on elements of one run
   dim3 grid(cdiv(total, 256), R);
   hipLaunchKernelGGL((pack_policy_kernel<N, H, BF16>), grid, dim3(256), 0, s,
@@ -618,6 +438,7 @@ hipError_t pack_impl(PolicyBuffers& pb, int R, const float* W1, const float* b1,
 template <int N, int H, bool BF16, int EB, int MINW>
 hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s) {
   using M = Smem<N, H, BF16, EB>;
+  const dim3 grid((A.TE + EB - 1) / EB);
   auto kern = rollout_policy_kernel<N, H, BF16, EB, MINW>;
   static bool attr_set = false;
   if (!attr_set) {
@@ -626,7 +447,6 @@ hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const dim3 grid((A.TE + EB - 1) / EB);
   hipLaunchKernelGGL(kern, grid, dim3(EB * N), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),
                      int(A.TE != A.E));
   return hipGetLastError();
@@ -634,47 +454,37 @@ hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream
 
 }  // namespace
 
-void free_policy(PolicyBuffers& pb) {
-  if (pb.packed) (void)hipFree(pb.packed);
-  pb.packed = nullptr;
-  pb.bytes = 0;
-}
+// General shapes built: (N, H, envs per block, min waves per SIMD), bf16 operands.
+#define MPE_WIDE_CASES(X) X(10, 128, 32, 2)
 
-// Supported policy shapes (N, H, bf16, envs per block, min waves per SIMD):
-// (1|2|3, 64, fp32) and (10, 128, bf16).
-#define MPE_POLICY_CASES(X)        \
-  X(1, 64, false, 64, 3)           \
-  X(2, 64, false, 64, 3)           \
-  X(3, 64, false, 64, 3)           \
-  X(10, 128, true, 32, 2)
-
-hipError_t pack_policy(PolicyBuffers& pb, int N, int H, int R, int weight_dtype, const float* W1,
-                       const float* b1, const float* W2, const float* b2, const float* W3,
-                       const float* b3, hipStream_t s, const char** why) {
-  const bool bf = weight_dtype == 1;
-#define X(N_, H_, BF_, EB_, MW_) \
-  if (N == N_ && H == H_ && bf == BF_) return pack_impl<N_, H_, BF_>(pb, R, W1, b1, W2, b2, W3, b3, s);
-  MPE_POLICY_CASES(X)
+bool wide_supported(int N, int H) {
+#define X(N_, H_, EB_, MW_) if (N == N_ && H == H_) return true;
+  MPE_WIDE_CASES(X)
 #undef X
-  *why = "unsupported policy shape: need (num_agents, hidden, dtype) in {(1..3, 64, fp32), (10, 128, bf16)}";
-  return hipSuccess;
+  return false;
 }
 
-hipError_t launch_rollout_policy(int N, int H, int weight_dtype, const RolloutArgs& A,
-                                 const PolicyBuffers& pb, hipStream_t s, const char** why) {
-  const bool bf = weight_dtype == 1;
-#define X(N_, H_, BF_, EB_, MW_)                                                                 \
-  if (N == N_ && H == H_ && bf == BF_) {                                                         \
+hipError_t pack_policy_wide(PolicyBuffers& pb, int N, int H, int R, const float* W1, const float* b1,
+                            const float* W2, const float* b2, const float* W3, const float* b3, hipStream_t s) {
+#define X(N_, H_, EB_, MW_) if (N == N_ && H == H_) return pack_impl<N_, H_, true>(pb, R, W1, b1, W2, b2, W3, b3, s);
+  MPE_WIDE_CASES(X)
+#undef X
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_rollout_policy_wide(int N, int H, const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s,
+                                      const char** why) {
+#define X(N_, H_, EB_, MW_)                                                                      \
+  if (N == N_ && H == H_) {                                                                      \
     if (A.TE != A.E && (A.E % EB_) != 0) {                                                       \
       *why = "with several runs, num_envs per run must be a multiple of the block's env count";  \
       return hipSuccess;                                                                         \
     }                                                                                            \
-    return rollout_impl<N_, H_, BF_, EB_, MW_>(A, pb, s);                                        \
+    return rollout_impl<N_, H_, true, EB_, MW_>(A, pb, s);                                       \
   }
-  MPE_POLICY_CASES(X)
+  MPE_WIDE_CASES(X)
 #undef X
-  *why = "unsupported policy shape";
-  return hipSuccess;
+  return hipErrorInvalidValue;
 }
 
 }  // namespace mpe
