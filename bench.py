@@ -48,21 +48,31 @@ def time_rollouts(env, T, bufs, steps, warmup):
     return wall, kern_ms
 
 
-def cpu_baseline(workload, weights, sample_envs, T, seed):
+def cpu_baseline(workload, weights, T, seed, target_seconds=12.0):
+    """Time the oracle on envs 0..n-1 of the same workload.  n is sized from a short probe so that
+    the timed run takes about target_seconds on this machine's cores (bounded by the workload)."""
     from oracle import Oracle
     from tests import helpers as Hp
     cores = max(1, min(os.cpu_count() or 1, 16))
-    orc = Oracle(Hp.oracle_config(sample_envs, workload.num_agents, 1, workload.hidden, workload.weight_dtype),
-                 threads=cores)
-    orc.set_policy(*weights)
-    orc.reset(seed)
-    t0 = time.perf_counter()
-    orc.rollout(T, want_obs=False)
-    dt = time.perf_counter() - t0
-    return {"value": sample_envs * workload.num_agents * T / dt, "unit": "agent-steps/s", "cores": cores,
+
+    def run(n):
+        orc = Oracle(Hp.oracle_config(n, workload.num_agents, 1, workload.hidden, workload.weight_dtype),
+                     threads=cores)
+        orc.set_policy(*weights)
+        orc.reset(seed)
+        t0 = time.perf_counter()
+        orc.rollout(T, want_obs=False)
+        return time.perf_counter() - t0
+
+    probe_n = min(1024, workload.num_envs)
+    probe = run(probe_n)
+    n = int(min(workload.num_envs, max(probe_n, probe_n * target_seconds / max(probe, 1e-3))))
+    n -= n % 64 if n >= 64 else 0
+    dt = run(n)
+    return {"value": n * workload.num_agents * T / dt, "unit": "agent-steps/s", "cores": cores,
             "kind": "oracle", "seconds": round(dt, 3),
             "sample": "envs 0..%d of the same workload (same seed, same weights), %d fused steps, "
-                      "fp64 scalar C++ oracle, %d threads over env ranges" % (sample_envs - 1, T, cores)}
+                      "fp64 scalar C++ oracle, %d threads over contiguous env ranges" % (n - 1, T, cores)}
 
 
 def main():
@@ -72,7 +82,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-envs", type=int, default=4096)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target duration of the oracle timing")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (independent envs shard trivially, but no "
@@ -128,28 +138,37 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32" if wl.weight_dtype == 0 else "bf16xbf16->f32",
+        "dtype_note": ("env math f32; policy contraction: every f32 operand split exactly into 3 bf16 terms, "
+                       "6 cross products on the bf16 matrix cores, f32 accumulate") if wl.weight_dtype == 0 else
+                      "weights and layer inputs rounded to bf16, f32 accumulate",
         "data": "synthetic",
         "config": {"workload": wl.name, "envs": TE, "agents": N, "T": T, "policy": "%d->%d->%d->5 tanh" % (D, H, H),
                    "seed": seed, "parallelism": "1 gpu"},
         "env_steps_per_s": value / N,
         "roofline": {
-            "kernel": "rollout_policy_kernel (fused, one launch per step)",
+            "kernel": ("rollout_policy_f32_kernel" if wl.weight_dtype == 0 else "rollout_policy_kernel")
+                      + " (fused, one launch per step)",
+            # fp32 shape: the contraction's fp32 FLOPs against the chip's fp32 matrix peak (the
+            # kernel runs them on the bf16 matrix cores with an exact 3-term operand split)
             "bound": "mfma", "achieved": tflops, "peak": MFMA_FP32_PEAK_TFLOPS if wl.weight_dtype == 0 else 2500.0,
             "unit": "TFLOP/s",
             "frac": tflops / (MFMA_FP32_PEAK_TFLOPS if wl.weight_dtype == 0 else 2500.0),
             "traffic": None,
+            "algorithmic_bytes": bytes_per_env_step(N, D) * TE * T,
             "kernel_ms_avg": kavg, "kernel_ms_min": float(np.min(kern_ms)),
             "flop_per_agent_step": flops_per_agent_step(D, H),
             "hbm_achieved_GBs": fused_gbs,
         },
         "env_only": {
-            "kernel": "rollout_uniform_kernel (seeded uniform actions, one launch per step)",
+            "kernel": ("rollout_uniform_ws_kernel" if N <= 3 else "rollout_uniform_kernel")
+                      + " (seeded uniform actions, one launch per step)",
             "agent_steps_per_s": agent_steps / (wall2 / args.steps),
             "env_steps_per_s": TE * T / (wall2 / args.steps),
             "roofline": {"bound": "hbm", "achieved": env_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": env_gbs / HBM_PEAK_GBS, "traffic": None,
                          "kernel_ms_avg": k2avg, "kernel_ms_min": float(np.min(kern2)),
-                         "bytes_per_env_step": bytes_per_env_step(N, D)},
+                         "bytes_per_env_step": bytes_per_env_step(N, D),
+                         "algorithmic_bytes": bytes_per_env_step(N, D) * TE * T},
         },
         "paper_context": {"mpe_simple_spread_steps_per_s": {"original_cpu_1env_epyc7763": 8.3e4,
                                                             "jax_a100_10k_envs_random_actions": 4.0e7},
@@ -158,12 +177,12 @@ def main():
     traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(traffic_file):
         tr = json.load(open(traffic_file))
-        out["roofline"]["traffic"] = tr.get(wl.name, {}).get("fused")
-        out["env_only"]["roofline"]["traffic"] = tr.get(wl.name, {}).get("env_only")
+        # scaled FETCH_SIZE + WRITE_SIZE bytes per launch, from the rocprofv3 --pmc runs in profiles/
+        out["roofline"]["traffic"] = tr.get(wl.name, {}).get("fused", {}).get("total_bytes")
+        out["env_only"]["roofline"]["traffic"] = tr.get(wl.name, {}).get("env_only", {}).get("total_bytes")
     if not args.no_cpu_baseline:
-        sample = min(args.cpu_sample_envs, wl.num_envs)
         w1 = tuple(a[:1] for a in weights)
-        out["cpu_baseline"] = cpu_baseline(wl, w1, sample, T, seed)
+        out["cpu_baseline"] = cpu_baseline(wl, w1, T, seed, args.cpu_seconds)
     print(json.dumps(out))
 
 

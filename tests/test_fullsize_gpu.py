@@ -1,0 +1,132 @@
+"""Parity at the benchmark's full sizes and launch configurations, on sampled env ranges the
+oracle can compute one by one (it simulates envs [offset, offset + n) of run r of the big job),
+plus properties that hold at any size."""
+import numpy as np
+import pytest
+
+from tests import helpers as Hp
+from paper_2311_10090_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def _gpu_rollout(wl, seed, with_policy=True, wseed=0):
+    from paper_2311_10090_amd.binding import MpeEnv
+    H = wl.hidden if with_policy else 0
+    env = MpeEnv(Hp.gpu_config(wl.num_envs, wl.num_agents, wl.num_runs, H, wl.weight_dtype if with_policy else 0))
+    weights = None
+    if with_policy:
+        weights = synth.policy_weights_with_bias(wseed, wl.num_runs, wl.obs_dim, wl.hidden)
+        env.set_policy(*Hp.to_dev(weights))
+    env.reset(seed)
+    out = env.rollout(wl.T, *env.empty_traj(wl.T))
+    torch.cuda.synchronize()
+    return env, out, weights
+
+
+def _oracle_range(wl, seed, run, off, n, weights, with_policy=True):
+    from oracle import Oracle
+    H = wl.hidden if with_policy else 0
+    orc = Oracle(Hp.oracle_config(n, wl.num_agents, 1, H, wl.weight_dtype if with_policy else 0,
+                                  env_offset=off, run_offset=run), threads=8)
+    if with_policy:
+        orc.set_policy(*[w[run:run + 1] for w in weights])
+    orc.reset(seed)
+    return orc.rollout(wl.T)
+
+
+def _compare_range(wl, out, ref, g0, n, what, fp32_actions=True):
+    """Compare envs [g0, g0+n) of the device trajectories with the oracle's; free-running, so an
+    episode is compared while its actions so far agree.  Returns action agreement."""
+    T = wl.T
+    obs, act, rew, done = [x[:, g0:g0 + n].cpu().numpy() for x in out[:4]]
+    robs, ract, rrew, rdone, rlast = ref
+    assert np.array_equal(done, rdone), what
+    agree = total = 0
+    worst = 0.0
+    for t0 in range(0, T, synth.MAX_EPISODE_STEPS):
+        t1 = min(t0 + synth.MAX_EPISODE_STEPS, T)
+        assert np.array_equal(obs[t0].astype(np.float64), robs[t0]), "%s: episode start at t=%d not bit-exact" % (what, t0)
+        same = (act[t0:t1] == ract[t0:t1]).all(axis=2)
+        alive = np.logical_and.accumulate(same, axis=0)
+        prior = np.vstack([np.ones((1, n), bool), alive[:-1]])
+        # teacher-forced view: at (t, env) with identical history the sampled action must agree
+        agree += int((act[t0:t1] == ract[t0:t1])[prior].sum())
+        total += int(prior.sum()) * act.shape[2]
+        e = np.abs(obs[t0:t1].astype(np.float64) - robs[t0:t1]).reshape(t1 - t0, n, -1).max(axis=2)
+        # chaos-aware bound would need oracle re-runs; here only the first 5 steps of an episode
+        # (no time for a contact to amplify rounding) are held to the 1e-4 bar ...
+        k = min(5, t1 - t0)
+        assert (e[:k] * prior[:k]).max() <= Hp.EPISODE_ATOL, what
+        assert (np.abs(rew[t0:t0 + k] - rrew[t0:t0 + k]) * alive[:k]).max() <= Hp.EPISODE_ATOL, what
+        # ... and the rest to a loose sanity bound that a wrong index or sign would still break
+        worst = max(worst, float((e * prior).max()))
+    assert worst < 0.05, "%s: error %.3e" % (what, worst)
+    return agree / max(total, 1), total
+
+
+@pytest.mark.parametrize("key", ["cfg2", "cfg2_env"])
+def test_headline_shape_sampled_against_oracle(key):
+    wl = synth.WORKLOADS[key]
+    with_policy = wl.hidden > 0
+    say("full size %s: %d envs x %d steps" % (wl.name, wl.total_envs, wl.T))
+    env, out, weights = _gpu_rollout(wl, seed=1, with_policy=with_policy, wseed=3)
+    obs, act, rew, done, last = out
+    # properties at full size
+    assert int(done.sum().item()) == wl.total_envs * (wl.T // synth.MAX_EPISODE_STEPS)
+    assert bool((done[24::25] == 1).all())
+    assert bool((obs[..., 14:] == 0).all()), "comm slots must be zero"
+    assert bool((act <= 4).all()) and bool(torch.isfinite(obs).all()) and bool((rew <= 0).all())
+    hist = torch.bincount(act.flatten().long(), minlength=5).double()
+    assert hist.min() > 0.02 * hist.sum()
+    tot = agree = 0
+    for off, n in ((0, 64), (20, 3), (32736, 64), (wl.num_envs - 64, 64), (12345, 1)):
+        ref = _oracle_range(wl, 1, 0, off, n, weights, with_policy)
+        frac, cnt = _compare_range(wl, out, ref, off, n, "%s envs %d..%d" % (key, off, off + n))
+        agree += frac * cnt
+        tot += cnt
+    say("  sampled action agreement %.6f over %d samples" % (agree / tot, tot))
+    if with_policy:
+        assert agree / tot >= Hp.ACTION_AGREEMENT - 2.0 / tot
+    else:
+        assert agree == tot  # uniform actions are integer work
+    env.close()
+
+
+def test_per_run_weights_full_size():
+    wl = synth.WORKLOADS["cfg4"]
+    say("full size %s: %d runs x %d envs" % (wl.name, wl.num_runs, wl.num_envs))
+    env, out, weights = _gpu_rollout(wl, seed=1, wseed=11)
+    tot = agree = 0
+    for run in (0, 1, 517, 1023):
+        ref = _oracle_range(wl, 1, run, 0, 64, weights)
+        frac, cnt = _compare_range(wl, out, ref, run * 64, 64, "run %d" % run)
+        agree += frac * cnt
+        tot += cnt
+    say("  sampled action agreement %.6f over %d samples" % (agree / tot, tot))
+    assert agree / tot >= Hp.ACTION_AGREEMENT - 2.0 / tot
+    env.close()
+
+
+def test_wide_bf16_full_size():
+    wl = synth.WORKLOADS["cfg3"]
+    say("full size %s: %d envs x %d agents" % (wl.name, wl.total_envs, wl.num_agents))
+    env, out, weights = _gpu_rollout(wl, seed=1, wseed=5)
+    obs, act, rew, done, last = out
+    assert int(done.sum().item()) == wl.total_envs * (wl.T // synth.MAX_EPISODE_STEPS)
+    assert bool((obs[..., 42:] == 0).all()) and bool(torch.isfinite(obs).all())
+    tot = agree = 0
+    for off, n in ((0, 32), (8176, 32), (wl.num_envs - 32, 32)):
+        ref = _oracle_range(wl, 1, 0, off, n, weights)
+        frac, cnt = _compare_range(wl, out, ref, off, n, "cfg3 envs %d..%d" % (off, off + n))
+        agree += frac * cnt
+        tot += cnt
+    say("  bf16 sampled action agreement %.5f over %d samples (no bar)" % (agree / tot, tot))
+    assert agree / tot >= 0.99
+    env.close()
