@@ -174,8 +174,28 @@ struct W3Terms {
   Terms s[2];
 };
 
+// tanh of 8 accumulator values (tiles 2s and 2s+1 of one batch tile) and their split: the B
+// operand of K slice s of the next layer (element e <-> tile 2s + e/4, register e%4).
+__device__ __forceinline__ Terms tanh_split(const f32x4& a0, const f32x4& a1) {
+  float v[8];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    v[e] = tanh_prescaled(a0[e]);
+    v[4 + e] = tanh_prescaled(a1[e]);
+  }
+  return split_operand(v);
+}
+
 // Policy forward of two 16-row tiles X and Y whose observation rows are in LDS (row stride D).
 // Logits of row j go to cols 0..4 of that row (they are rewritten by the next observation).
+//
+// Schedule.  Matrix-core and vector work only overlap when both are in flight at the same time,
+// so the stages are cut where the data dependences allow it: a K slice of the next layer needs
+// only HALF of the accumulator tiles of this one (slice s <- tiles 2s, 2s+1), so the tanh + split
+// of one half runs on the VALU while the matrix cores finish the other half:
+//   split(obs) | L1 m01 | L1 m23 + T1 s0 | L2 s0 + T1 s1 | L2 s1 m01 | L2 s1 m23 + T2 s0 |
+//   L3 s0 + T2 s1 | L3 s1
+// sched_barrier fences keep the compiler from regrouping the stages.
 template <int N>
 __device__ __forceinline__ void policy_pair(const uint8_t* __restrict__ wsm, const float* __restrict__ bias,
                                             const W3Terms& w3, float* __restrict__ rowsX,
@@ -193,7 +213,21 @@ __device__ __forceinline__ void policy_pair(const uint8_t* __restrict__ wsm, con
   }
   const bf16x8* w1 = reinterpret_cast<const bf16x8*>(wsm + Pk::OFF_W1A);  // [m][term][lane32]
   const bf16x8* w2 = reinterpret_cast<const bf16x8*>(wsm + Pk::OFF_W2A);  // [m][s][term][lane64]
-  // ---- layer 1: 16 inputs (cols 0..15 of the row; cols >= 4N+2 are zeros or meet zero weights)
+  auto load_w1 = [&](int m) {
+    Terms a;
+    a.h = w1[(m * 3 + 0) * 32 + (lane & 31)];
+    a.m = w1[(m * 3 + 1) * 32 + (lane & 31)];
+    a.l = w1[(m * 3 + 2) * 32 + (lane & 31)];
+    return a;
+  };
+  auto load_w2 = [&](int m, int s) {
+    Terms a;
+    a.h = w2[((m * 2 + s) * 3 + 0) * 64 + lane];
+    a.m = w2[((m * 2 + s) * 3 + 1) * 64 + lane];
+    a.l = w2[((m * 2 + s) * 3 + 2) * 64 + lane];
+    return a;
+  };
+  // ---- split(obs): 16 inputs (cols 0..15 of the row; cols >= 4N+2 are zeros or meet zero weights)
   Terms bx, by;
   {
     float vx[8], vy[8];
@@ -219,64 +253,90 @@ __device__ __forceinline__ void policy_pair(const uint8_t* __restrict__ wsm, con
   for (int m = 0; m < 4; ++m) {
     accX[m] = *reinterpret_cast<const f32x4*>(bias + 16 * m + 4 * gq);
     accY[m] = accX[m];
-    Terms a;
-    a.h = w1[(m * 3 + 0) * 32 + (lane & 31)];
-    a.m = w1[(m * 3 + 1) * 32 + (lane & 31)];
-    a.l = w1[(m * 3 + 2) * 32 + (lane & 31)];
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // ---- L1 m01
+#pragma unroll
+  for (int m = 0; m < 2; ++m) {
+    const Terms a = load_w1(m);
     accX[m] = mma_split(a, bx, accX[m]);
     accY[m] = mma_split(a, by, accY[m]);
   }
-  // ---- tanh, layer 2
-  float hx[16], hy[16];
+  __builtin_amdgcn_sched_barrier(0);
+  // ---- L1 m23 + T1 s0
+  Terms cx0, cy0, cx1, cy1;  // B operands of the next layer, K slices 0 and 1
 #pragma unroll
-  for (int m = 0; m < 4; ++m) {
+  for (int m = 2; m < 4; ++m) {
+    const Terms a = load_w1(m);
+    accX[m] = mma_split(a, bx, accX[m]);
+    accY[m] = mma_split(a, by, accY[m]);
+  }
+  cx0 = tanh_split(accX[0], accX[1]);
+  cy0 = tanh_split(accY[0], accY[1]);
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      hx[4 * m + r] = tanh_prescaled(accX[m][r]);
-      hy[4 * m + r] = tanh_prescaled(accY[m][r]);
-    }
+  for (int m = 0; m < 2; ++m) {
     accX[m] = *reinterpret_cast<const f32x4*>(bias + kH + 16 * m + 4 * gq);
     accY[m] = accX[m];
   }
+  __builtin_amdgcn_sched_barrier(0);
+  // ---- L2 s0 (tiles m01 first: their accumulators are free) + T1 s1
+  {
+    f32x4 tX[2], tY[2];  // L2 accumulators of tiles 2,3 start here; accX/Y[2,3] still hold L1 results
 #pragma unroll
-  for (int s = 0; s < 2; ++s) {
-    // K slice s takes accumulator tiles 2s and 2s+1: element e <-> tile 2s + e/4, register e%4
-    float vx[8], vy[8];
+    for (int m = 2; m < 4; ++m) {
+      tX[m - 2] = *reinterpret_cast<const f32x4*>(bias + kH + 16 * m + 4 * gq);
+      tY[m - 2] = tX[m - 2];
+    }
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { vx[e] = hx[8 * s + e]; vy[e] = hy[8 * s + e]; }
-    bx = split_operand(vx);
-    by = split_operand(vy);
+    for (int m = 0; m < 2; ++m) {
+      const Terms a = load_w2(m, 0);
+      accX[m] = mma_split(a, cx0, accX[m]);
+      accY[m] = mma_split(a, cy0, accY[m]);
+    }
 #pragma unroll
-    for (int m = 0; m < 4; ++m) {
-      Terms a;
-      a.h = w2[((m * 2 + s) * 3 + 0) * 64 + lane];
-      a.m = w2[((m * 2 + s) * 3 + 1) * 64 + lane];
-      a.l = w2[((m * 2 + s) * 3 + 2) * 64 + lane];
-      accX[m] = mma_split(a, bx, accX[m]);
-      accY[m] = mma_split(a, by, accY[m]);
+    for (int m = 2; m < 4; ++m) {
+      const Terms a = load_w2(m, 0);
+      tX[m - 2] = mma_split(a, cx0, tX[m - 2]);
+      tY[m - 2] = mma_split(a, cy0, tY[m - 2]);
+    }
+    cx1 = tanh_split(accX[2], accX[3]);
+    cy1 = tanh_split(accY[2], accY[3]);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int m = 2; m < 4; ++m) {
+      accX[m] = tX[m - 2];
+      accY[m] = tY[m - 2];
     }
   }
-  // ---- tanh, layer 3 (5 outputs padded to one 16-wide tile)
+  // ---- L2 s1 m01
 #pragma unroll
-  for (int m = 0; m < 4; ++m) {
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      hx[4 * m + r] = tanh_prescaled(accX[m][r]);
-      hy[4 * m + r] = tanh_prescaled(accY[m][r]);
-    }
+  for (int m = 0; m < 2; ++m) {
+    const Terms a = load_w2(m, 1);
+    accX[m] = mma_split(a, cx1, accX[m]);
+    accY[m] = mma_split(a, cy1, accY[m]);
   }
+  __builtin_amdgcn_sched_barrier(0);
+  // ---- L2 s1 m23 + T2 s0
+#pragma unroll
+  for (int m = 2; m < 4; ++m) {
+    const Terms a = load_w2(m, 1);
+    accX[m] = mma_split(a, cx1, accX[m]);
+    accY[m] = mma_split(a, cy1, accY[m]);
+  }
+  cx0 = tanh_split(accX[0], accX[1]);
+  cy0 = tanh_split(accY[0], accY[1]);
+  __builtin_amdgcn_sched_barrier(0);
+  // ---- L3 s0 + T2 s1 (5 outputs padded to one 16-wide tile)
   f32x4 zX = *reinterpret_cast<const f32x4*>(bias + 2 * kH + 4 * gq);
   f32x4 zY = zX;
-#pragma unroll
-  for (int s = 0; s < 2; ++s) {
-    float vx[8], vy[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) { vx[e] = hx[8 * s + e]; vy[e] = hy[8 * s + e]; }
-    bx = split_operand(vx);
-    by = split_operand(vy);
-    zX = mma_split(w3.s[s], bx, zX);
-    zY = mma_split(w3.s[s], by, zY);
-  }
+  zX = mma_split(w3.s[0], cx0, zX);
+  zY = mma_split(w3.s[0], cy0, zY);
+  cx1 = tanh_split(accX[2], accX[3]);
+  cy1 = tanh_split(accY[2], accY[3]);
+  __builtin_amdgcn_sched_barrier(0);
+  // ---- L3 s1
+  zX = mma_split(w3.s[1], cx1, zX);
+  zY = mma_split(w3.s[1], cy1, zY);
   // lane (j, gq) holds outputs 4gq + r of row j: outputs 0..3 in group 0, output 4 in group 1
   if (gq == 0) {
 #pragma unroll
@@ -305,7 +365,8 @@ struct SmemF32 {
 
 template <int N, int EB, int MINW>
 __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
-                                                                          int per_run_weights) {
+                                                                          int per_run_weights, uint32_t groups,
+                                                                          uint32_t groups_per_xcd) {
   using M = SmemF32<N, EB>;
   constexpr int D = 6 * N, ROWS = EB * N, THREADS = ROWS;
   static_assert(THREADS % 64 == 0, "block must be whole wavefronts");
@@ -320,7 +381,12 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int el = tid / N, i = tid - el * N;          // env within block, agent
   const size_t TE = A.TE;
-  const size_t g0 = size_t(blockIdx.x) * EB;
+  // XCD-aware mapping: the hardware deals block b to XCD b % 8; giving each XCD one contiguous
+  // range of env groups lets the partial cache lines that neighbouring groups write per step
+  // (actions 3*EB bytes, done EB bytes) merge in one L2 instead of being written back apart.
+  const uint32_t grp = (blockIdx.x & 7u) * groups_per_xcd + (blockIdx.x >> 3);
+  if (grp >= groups) return;  // whole block, before any barrier
+  const size_t g0 = size_t(grp) * EB;
   const size_t g = g0 + el;
   const bool valid = g < TE;
   const uint32_t gc = valid ? uint32_t(g) : uint32_t(g0);
@@ -542,9 +608,10 @@ hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const dim3 grid((A.TE + EB - 1) / EB);
-  hipLaunchKernelGGL(kern, grid, dim3(EB * N), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),
-                     int(A.TE != A.E));
+  const uint32_t groups = (A.TE + EB - 1) / EB;
+  const uint32_t per_xcd = (groups + 7) / 8;
+  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(EB * N), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),
+                     int(A.TE != A.E), groups, per_xcd);
   return hipGetLastError();
 }
 
