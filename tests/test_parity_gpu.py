@@ -349,3 +349,53 @@ def test_set_policy_none_returns_to_uniform(mods):
     assert all(torch.equal(x, y) for x, y in zip(a, b))
     env.close()
     ref.close()
+
+
+def test_rollouts_are_deterministic(mods):
+    MpeEnv, _ = mods
+    outs = []
+    for _ in range(2):
+        env, orc = _policy_pair(mods, 320, 3, 1, 64, 0, wseed=2)
+        env.reset(6)
+        outs.append([x.clone() for x in env.rollout(40, *env.empty_traj(40))])
+        env.close()
+    assert all(torch.equal(a, b) for a, b in zip(*outs))
+
+
+def test_unsupported_policy_shapes_are_refused(mods):
+    MpeEnv, _ = mods
+    from paper_2311_10090_amd.binding import MpeError, MPE_EINVAL
+    # 5 agents with a width-64 policy: no kernel is built for it
+    env = MpeEnv(Hp.gpu_config(64, 5, 1, 64, 0))
+    w = synth.policy_weights(0, 1, 30, 64)
+    with pytest.raises(MpeError) as ei:
+        env.set_policy(*Hp.to_dev(w))
+    assert ei.value.code == MPE_EINVAL and "unsupported" in str(ei.value)
+    env.reset(0)
+    env.rollout(3)   # still usable without a policy
+    env.close()
+    # several runs whose size is not a multiple of the block's env count
+    env = MpeEnv(Hp.gpu_config(40, 3, 2, 64, 0))
+    env.set_policy(*Hp.to_dev(synth.policy_weights(0, 2, 18, 64)))
+    env.reset(0)
+    with pytest.raises(MpeError) as ei:
+        env.rollout(2)
+    assert ei.value.code == MPE_EINVAL
+    # only some of the six arrays
+    with pytest.raises(MpeError) as ei:
+        env.set_policy(Hp.to_dev(synth.policy_weights(0, 2, 18, 64))[0])
+    assert ei.value.code == MPE_EINVAL
+    env.close()
+
+
+def test_misaligned_output_is_refused(mods):
+    MpeEnv, _ = mods
+    from paper_2311_10090_amd.binding import MpeError, MPE_EINVAL
+    env = MpeEnv(Hp.gpu_config(64, 3))
+    env.reset(0)
+    buf = torch.empty(64 * 3 * 18 + 1, device="cuda")
+    from paper_2311_10090_amd.binding import _check
+    with pytest.raises(MpeError) as ei:
+        _check(env.lib.mpe_reset(env.h, 0, buf.data_ptr() + 4, None))
+    assert ei.value.code == MPE_EINVAL
+    env.close()
