@@ -51,14 +51,20 @@ __device__ __forceinline__ uint32_t pack_hi16(uint32_t a, uint32_t b) {
 
 // Packed per-run layout (bytes).  A operands of v_mfma_f32_16x16x32_bf16: lane (i = lane%16,
 // gq = lane/16) holds weights [k = 8 gq + e][out = 16 m + i], e = 0..7 (16 bytes), per term.
-//   W1A [m 4][term 3][lane 32]   layer 1 reads 16 inputs: lanes gq >= 2 see zero activations and
-//                                 simply reuse the operand of lane - 32
+//   W1A [m 4][combo 2][lane 64]  layer 1 has only 16 inputs, half of the instruction's K = 32, so
+//                                 two cross terms share one instruction: K positions 0..15 (lanes
+//                                 gq < 2) carry one term of input k' = 8 (gq & 1) + e, positions
+//                                 16..31 (gq >= 2) another term of the same inputs.
+//                                 combo 0 = (h | m), combo 1 = (h | l)
 //   W2A [m 4][s 2][term 3][lane 64]
-//   W3A [s 2][term 3][lane 64]   (5 outputs padded to 16)
-//   bias b1*pre [64], b2*pre [64], b3 [16] fp32
+//   W3A [s 2][term 3][lane 64]   (5 outputs padded to 16), N = 1 only
+//   W3A [s 2][lane 64]           N >= 2: the 16 output rows of the instruction carry the three
+//                                 terms of the 5 outputs (row_of below), so ONE A operand meets
+//                                 the three activation terms in three instructions per K slice
+//   bias b1*pre [64], b2*pre [64], b3 [16] fp32 (N >= 2: b3 in the h-term row of each output)
 struct Pk {
   static constexpr size_t OFF_W1A = 0;
-  static constexpr size_t W1A_BYTES = 4 * 3 * 32 * 16;
+  static constexpr size_t W1A_BYTES = 4 * 2 * 64 * 16;
   static constexpr size_t OFF_W2A = OFF_W1A + W1A_BYTES;
   static constexpr size_t W2A_BYTES = 4 * 2 * 3 * 64 * 16;
   static constexpr size_t OFF_W3A = OFF_W2A + W2A_BYTES;
@@ -68,6 +74,17 @@ struct Pk {
   static constexpr size_t RUN_BYTES = OFF_BIAS + BIAS_BYTES;
   static constexpr size_t LDS_BYTES = OFF_W3A;   // W1A + W2A live in LDS, W3A in registers
 };
+
+// Layer 3 with the weight terms along the output rows (N >= 2; the logits of a row then need 7
+// floats of scratch in its observation row, which has 4N + 2 rewritten columns).  Accumulator
+// lane group g holds rows 4g..4g+3: rows 4g + {0,1,2} = terms h, m, l of output g, so their sum
+// is lane-local; rows 4g + 3 (g < 3) = term g of output 4, summed by the reader.
+template <int N>
+struct L3 {
+  static constexpr bool kRowTerms = 4 * N + 2 >= 7;
+};
+__host__ __device__ constexpr int l3_row_output(int i) { return i % 4 < 3 ? i / 4 : (i / 4 < 3 ? 4 : -1); }
+__host__ __device__ constexpr int l3_row_term(int i) { return i % 4 < 3 ? i % 4 : i / 4; }
 
 // hidden unit of K position (slice s, lane group gq, element e) in layers 2/3
 __host__ __device__ constexpr int hidden_k(int s, int gq, int e) { return 32 * s + 16 * (e / 4) + 4 * gq + (e % 4); }
@@ -87,7 +104,7 @@ __global__ void pack_split_kernel(uint8_t* __restrict__ packed, const float* __r
   b2 += size_t(run) * kH;
   W3 += size_t(run) * kH * kNumActions;
   b3 += size_t(run) * kNumActions;
-  constexpr int n1 = 4 * 32 * 8, n2 = 4 * 2 * 64 * 8, n3 = 2 * 64 * 8, nb = 2 * kH + 16;
+  constexpr int n1 = 4 * 64 * 8, n2 = 4 * 2 * 64 * 8, n3 = 2 * 64 * 8, nb = 2 * kH + 16;
   int idx = blockIdx.x * blockDim.x + threadIdx.x;
   auto put3 = [&](size_t off, int blk, int lanes, int lane, int e, float v) {
     // blk = index of the [term][lane] group; terms are `lanes` * 16 bytes apart
@@ -99,9 +116,13 @@ __global__ void pack_split_kernel(uint8_t* __restrict__ packed, const float* __r
     base[size_t(2) * lanes * 8] = uint16_t(l >> 16);
   };
   if (idx < n1) {
-    const int e = idx % 8, lane = (idx / 8) % 32, m = idx / 256;
-    const int k = 8 * (lane / 16) + e, o = 16 * m + lane % 16;
-    put3(Pk::OFF_W1A, m, 32, lane, e, k < KIN ? kPre * W1[size_t(k) * kH + o] : 0.0f);
+    const int e = idx % 8, lane = (idx / 8) % 64, m = idx / 512;
+    const int gq = lane / 16, k = 8 * (gq & 1) + e, o = 16 * m + lane % 16;
+    uint32_t h, mm, l;
+    split3(k < KIN ? kPre * W1[size_t(k) * kH + o] : 0.0f, h, mm, l);
+    uint16_t* base = reinterpret_cast<uint16_t*>(out + Pk::OFF_W1A) + size_t(m) * 2 * 64 * 8 + lane * 8 + e;
+    base[0] = uint16_t((gq < 2 ? h : mm) >> 16);        // combo 0 = (h | m)
+    base[64 * 8] = uint16_t((gq < 2 ? h : l) >> 16);    // combo 1 = (h | l)
     return;
   }
   idx -= n1;
@@ -115,7 +136,14 @@ __global__ void pack_split_kernel(uint8_t* __restrict__ packed, const float* __r
   if (idx < n3) {
     const int e = idx % 8, lane = (idx / 8) % 64, s = idx / 512;
     const int k = hidden_k(s, lane / 16, e), o = lane % 16;
-    put3(Pk::OFF_W3A, s, 64, lane, e, o < kNumActions ? W3[size_t(k) * kNumActions + o] : 0.0f);
+    if constexpr (L3<N>::kRowTerms) {
+      const int out_o = l3_row_output(o), term = l3_row_term(o);
+      uint32_t t3[3] = {0u, 0u, 0u};
+      if (out_o >= 0) split3(W3[size_t(k) * kNumActions + out_o], t3[0], t3[1], t3[2]);
+      reinterpret_cast<uint16_t*>(out + Pk::OFF_W3A)[(size_t(s) * 64 + lane) * 8 + e] = uint16_t(t3[term] >> 16);
+    } else {
+      put3(Pk::OFF_W3A, s, 64, lane, e, o < kNumActions ? W3[size_t(k) * kNumActions + o] : 0.0f);
+    }
     return;
   }
   idx -= n3;
@@ -123,7 +151,10 @@ __global__ void pack_split_kernel(uint8_t* __restrict__ packed, const float* __r
     float v;
     if (idx < kH) v = kPre * b1[idx];
     else if (idx < 2 * kH) v = kPre * b2[idx - kH];
-    else v = (idx - 2 * kH) < kNumActions ? b3[idx - 2 * kH] : 0.0f;
+    else if constexpr (L3<N>::kRowTerms) {
+      const int i = idx - 2 * kH;
+      v = (l3_row_output(i) >= 0 && l3_row_term(i) == 0) ? b3[l3_row_output(i)] : 0.0f;
+    } else v = (idx - 2 * kH) < kNumActions ? b3[idx - 2 * kH] : 0.0f;
     reinterpret_cast<float*>(out + Pk::OFF_BIAS)[idx] = v;
   }
 }
@@ -187,7 +218,7 @@ __device__ __forceinline__ Terms tanh_split(const f32x4& a0, const f32x4& a1) {
 }
 
 // Policy forward of two 16-row tiles X and Y whose observation rows are in LDS (row stride D).
-// Logits of row j go to cols 0..4 of that row (they are rewritten by the next observation).
+// Logits of row j go to the first cols of that row (they are rewritten by the next observation).
 //
 // Schedule.  Matrix-core and vector work only overlap when both are in flight at the same time,
 // so the stages are cut where the data dependences allow it: a K slice of the next layer needs
@@ -211,14 +242,17 @@ __device__ __forceinline__ void policy_pair(const uint8_t* __restrict__ wsm, con
     wsm += zero;
     bias += zero;
   }
-  const bf16x8* w1 = reinterpret_cast<const bf16x8*>(wsm + Pk::OFF_W1A);  // [m][term][lane32]
+  const bf16x8* w1 = reinterpret_cast<const bf16x8*>(wsm + Pk::OFF_W1A);  // [m][combo][lane64]
   const bf16x8* w2 = reinterpret_cast<const bf16x8*>(wsm + Pk::OFF_W2A);  // [m][s][term][lane64]
-  auto load_w1 = [&](int m) {
-    Terms a;
-    a.h = w1[(m * 3 + 0) * 32 + (lane & 31)];
-    a.m = w1[(m * 3 + 1) * 32 + (lane & 31)];
-    a.l = w1[(m * 3 + 2) * 32 + (lane & 31)];
-    return a;
+  // Layer 1, one output tile: the six cross terms in three instructions, smallest first:
+  //   (Wh | Wl) x (Xl | Xh) = hl + lh,  (Wh | Wm) x (Xm | Xm) = hm + mm,  (Wh | Wm) x (Xh | Xh) = hh + mh
+  auto layer1 = [&](int m, const Terms& b, const bf16x8& b_lh, f32x4 acc) {
+    const bf16x8 a_hm = w1[(m * 2 + 0) * 64 + lane];
+    const bf16x8 a_hl = w1[(m * 2 + 1) * 64 + lane];
+    acc = MPE_MFMA_BF(a_hl, b_lh, acc);
+    acc = MPE_MFMA_BF(a_hm, b.m, acc);
+    acc = MPE_MFMA_BF(a_hm, b.h, acc);
+    return acc;
   };
   auto load_w2 = [&](int m, int s) {
     Terms a;
@@ -227,26 +261,37 @@ __device__ __forceinline__ void policy_pair(const uint8_t* __restrict__ wsm, con
     a.l = w2[((m * 2 + s) * 3 + 2) * 64 + lane];
     return a;
   };
-  // ---- split(obs): 16 inputs (cols 0..15 of the row; cols >= 4N+2 are zeros or meet zero weights)
+  // Layer 3, one K slice.  Row-term layout: the one A operand against the three activation terms
+  // (all nine cross terms, smallest first); otherwise the six significant ones.
+  auto layer3 = [&](const Terms& a, const Terms& b, f32x4 acc) {
+    if constexpr (L3<N>::kRowTerms) {
+      acc = MPE_MFMA_BF(a.h, b.l, acc);
+      acc = MPE_MFMA_BF(a.h, b.m, acc);
+      acc = MPE_MFMA_BF(a.h, b.h, acc);
+      return acc;
+    } else {
+      return mma_split(a, b, acc);
+    }
+  };
+  // ---- split(obs): 16 inputs (cols 0..15 of the row; cols >= 4N+2 are zeros or meet zero weights);
+  // lanes gq and gq + 2 hold the same 8 inputs
   Terms bx, by;
+  bf16x8 bx_lh, by_lh;  // (Xl | Xh): l in K positions 0..15, h in 16..31
   {
     float vx[8], vy[8];
-    if (gq < 2) {
-      // rows are D*4 bytes apart (a multiple of 8, not of 16): read as float2
-      const float2* xs = reinterpret_cast<const float2*>(rowsX + j * D + 8 * gq);
-      const float2* ys = reinterpret_cast<const float2*>(rowsY + j * D + 8 * gq);
+    // rows are D*4 bytes apart (a multiple of 8, not of 16): read as float2
+    const float2* xs = reinterpret_cast<const float2*>(rowsX + j * D + 8 * (gq & 1));
+    const float2* ys = reinterpret_cast<const float2*>(rowsY + j * D + 8 * (gq & 1));
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float2 xv = xs[q], yv = ys[q];
-        vx[2 * q] = xv.x; vx[2 * q + 1] = xv.y;
-        vy[2 * q] = yv.x; vy[2 * q + 1] = yv.y;
-      }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) vx[e] = vy[e] = 0.0f;
+    for (int q = 0; q < 4; ++q) {
+      const float2 xv = xs[q], yv = ys[q];
+      vx[2 * q] = xv.x; vx[2 * q + 1] = xv.y;
+      vy[2 * q] = yv.x; vy[2 * q + 1] = yv.y;
     }
     bx = split_operand(vx);
     by = split_operand(vy);
+    bx_lh = gq < 2 ? bx.l : bx.h;
+    by_lh = gq < 2 ? by.l : by.h;
   }
   f32x4 accX[4], accY[4];
 #pragma unroll
@@ -258,18 +303,16 @@ __device__ __forceinline__ void policy_pair(const uint8_t* __restrict__ wsm, con
   // ---- L1 m01
 #pragma unroll
   for (int m = 0; m < 2; ++m) {
-    const Terms a = load_w1(m);
-    accX[m] = mma_split(a, bx, accX[m]);
-    accY[m] = mma_split(a, by, accY[m]);
+    accX[m] = layer1(m, bx, bx_lh, accX[m]);
+    accY[m] = layer1(m, by, by_lh, accY[m]);
   }
   __builtin_amdgcn_sched_barrier(0);
   // ---- L1 m23 + T1 s0
   Terms cx0, cy0, cx1, cy1;  // B operands of the next layer, K slices 0 and 1
 #pragma unroll
   for (int m = 2; m < 4; ++m) {
-    const Terms a = load_w1(m);
-    accX[m] = mma_split(a, bx, accX[m]);
-    accY[m] = mma_split(a, by, accY[m]);
+    accX[m] = layer1(m, bx, bx_lh, accX[m]);
+    accY[m] = layer1(m, by, by_lh, accY[m]);
   }
   cx0 = tanh_split(accX[0], accX[1]);
   cy0 = tanh_split(accY[0], accY[1]);
@@ -329,24 +372,34 @@ __device__ __forceinline__ void policy_pair(const uint8_t* __restrict__ wsm, con
   // ---- L3 s0 + T2 s1 (5 outputs padded to one 16-wide tile)
   f32x4 zX = *reinterpret_cast<const f32x4*>(bias + 2 * kH + 4 * gq);
   f32x4 zY = zX;
-  zX = mma_split(w3.s[0], cx0, zX);
-  zY = mma_split(w3.s[0], cy0, zY);
+  zX = layer3(w3.s[0], cx0, zX);
+  zY = layer3(w3.s[0], cy0, zY);
   cx1 = tanh_split(accX[2], accX[3]);
   cy1 = tanh_split(accY[2], accY[3]);
   __builtin_amdgcn_sched_barrier(0);
   // ---- L3 s1
-  zX = mma_split(w3.s[1], cx1, zX);
-  zY = mma_split(w3.s[1], cy1, zY);
-  // lane (j, gq) holds outputs 4gq + r of row j: outputs 0..3 in group 0, output 4 in group 1
-  if (gq == 0) {
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      rowsX[j * D + r] = zX[r];
-      rowsY[j * D + r] = zY[r];
+  zX = layer3(w3.s[1], cx1, zX);
+  zY = layer3(w3.s[1], cy1, zY);
+  if constexpr (L3<N>::kRowTerms) {
+    // lane (j, gq): output gq = sum of its three term rows -> col gq; term gq of output 4 -> col 4 + gq
+    rowsX[j * D + gq] = (zX[0] + zX[1]) + zX[2];
+    rowsY[j * D + gq] = (zY[0] + zY[1]) + zY[2];
+    if (gq < 3) {
+      rowsX[j * D + 4 + gq] = zX[3];
+      rowsY[j * D + 4 + gq] = zY[3];
     }
-  } else if (gq == 1) {
-    rowsX[j * D + 4] = zX[0];
-    rowsY[j * D + 4] = zY[0];
+  } else {
+    // lane (j, gq) holds outputs 4gq + r of row j: outputs 0..3 in group 0, output 4 in group 1
+    if (gq == 0) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        rowsX[j * D + r] = zX[r];
+        rowsY[j * D + r] = zY[r];
+      }
+    } else if (gq == 1) {
+      rowsX[j * D + 4] = zX[0];
+      rowsY[j * D + 4] = zY[0];
+    }
   }
 }
 
@@ -402,10 +455,14 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
   W3Terms w3;
 #pragma unroll
   for (int s = 0; s < 2; ++s) {
-    const bf16x8* src = reinterpret_cast<const bf16x8*>(run_weights + Pk::OFF_W3A) + s * 3 * 64 + lane;
-    w3.s[s].h = src[0];
-    w3.s[s].m = src[64];
-    w3.s[s].l = src[128];
+    if constexpr (L3<N>::kRowTerms) {
+      w3.s[s].h = reinterpret_cast<const bf16x8*>(run_weights + Pk::OFF_W3A)[s * 64 + lane];
+    } else {
+      const bf16x8* src = reinterpret_cast<const bf16x8*>(run_weights + Pk::OFF_W3A) + s * 3 * 64 + lane;
+      w3.s[s].h = src[0];
+      w3.s[s].m = src[64];
+      w3.s[s].l = src[128];
+    }
   }
   {
     const uint4* src = reinterpret_cast<const uint4*>(run_weights);
@@ -494,6 +551,7 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
     float z[kNumActions];
 #pragma unroll
     for (int k = 0; k < kNumActions; ++k) z[k] = tile[tid * D + k];
+    if constexpr (L3<N>::kRowTerms) z[4] = (z[4] + tile[tid * D + 5]) + tile[tid * D + 6];
     const uint32_t act = gumbel_argmax(z, A.seed, run, env, step, uint32_t(i));
     if (act_base) {
       if (valid) act_base[row_off] = uint8_t(act);
@@ -619,7 +677,7 @@ template <int N>
 hipError_t pack_impl(PolicyBuffers& pb, int R, const float* W1, const float* b1, const float* W2,
                      const float* b2, const float* W3, const float* b3, hipStream_t s) {
   if (hipError_t e = ensure_policy_bytes(pb, size_t(R) * Pk::RUN_BYTES); e != hipSuccess) return e;
-  constexpr int total = 4 * 32 * 8 + 4 * 2 * 64 * 8 + 2 * 64 * 8 + 2 * kH + 16;
+  constexpr int total = 4 * 64 * 8 + 4 * 2 * 64 * 8 + 2 * 64 * 8 + 2 * kH + 16;
   dim3 grid((total + 255) / 256, R);
   hipLaunchKernelGGL(pack_split_kernel<N>, grid, dim3(256), 0, s, static_cast<uint8_t*>(pb.packed), W1, b1, W2,
                      b2, W3, b3);
