@@ -1,144 +1,172 @@
-// Fused rollout: policy MLP forward (MFMA) -> Gumbel-max sampling (Philox) -> environment
-// transition -> reward / auto-reset -> observation, T times inside one persistent kernel.
+// Fused rollout for wide shapes: many agents, wide hidden layers, bf16 operands with fp32
+// accumulation (the scaled scenario: 10 agents, 60 -> 128 -> 128 -> 5).  Policy MLP forward
+// (MFMA) -> Gumbel-max sampling (Philox) -> environment transition -> reward / auto-reset ->
+// observation, T times inside one persistent kernel.  The fp32 headline shape has its own kernel
+// in mpe_policy_f32.hip.
+//
+// Policy shape follows the paper's MPE setting (App. G, IPPO table: two tanh layers, parameters
+// shared by all agents; Sec. 3.2 "PPO"), widened to 128 with bf16 operands.
 //
 // Mapping.  A block owns EB consecutive environments; one lane owns one AGENT (row =
-// env_local * N + agent), so a wavefront is 64 consecutive agent rows = four 16-row MFMA
-// tiles.  The block keeps the current observations of its rows in an LDS tile that serves
-// three readers: the coalesced 16-byte trajectory stores, the B operands of layer 1, and
-// nothing else -- environment state itself stays in registers for all T steps.
+// env_local * N + agent), so a wavefront is 64 consecutive agent rows = four 16-row MFMA tiles.
+// Environment state and the lane's own observation row stay in registers for all T steps.
 //
-// MLP on the matrix cores, transposed: H^T[hidden x rows] = W^T[hidden x in] * X^T[in x rows].
-// With v_mfma_f32_16x16x4_f32 (and v_mfma_f32_16x16x32_bf16) the accumulator layout of one
-// layer -- lane l holds column (row of the batch) l%16 and hidden units 16m + 4(l/16) + r --
-// is exactly a B-operand layout for the next layer once the weights are stored with the
-// matching K order, so activations never leave registers between layers.  Weights are
-// packed once (mpe_set_policy) into that A-operand order and staged in LDS per block.
+// Keeping LDS small is what buys occupancy here (the packed weights alone are 49 KB per block),
+// so the observation rows never sit in LDS as a whole:
+//  * B operands of layer 1: the lane rounds its row to bf16 in registers; the matrix instruction
+//    wants lane (j, g) to hold 8 consecutive inputs (chunk g) of row 16c + j for tile c, and the
+//    owner of that row is lane (j, c): a 4 x 4 transpose between register index and lane group,
+//    done with v_permlane32_swap + v_permlane16_swap, no memory involved.
+//  * trajectory stores: every lane stores its own row straight from registers as 16-byte
+//    chunks.  (Measured alternatives: staging 16 rows at a time through LDS makes the stores
+//    contiguous but costs 60 quarter-occupied ds_write_b128 per wavefront and step -- an LDS
+//    write costs ~13.5 cycles per CU whatever its lane count -- and came out slower.)
+//  * layers 2 and 3: the accumulator layout of one layer -- lane (j, g) holds batch row j and
+//    hidden units 16m + 4g + r -- is a B-operand layout for the next layer once the weights are
+//    packed in the matching K order, so activations never leave registers.
+// The only data that cross wavefronts are the new positions and the per-landmark coverage
+// distances of an env's agents (double-buffered by step parity): one barrier per step.
 //
-// This file holds the general kernel (bf16 operands, wide layers, many agents); the fp32
-// headline shape has its own kernel in mpe_policy_f32.hip.
-//
-// Policy shape follows the paper's MPE setting (App. G, IPPO table: two tanh layers of width
-// 64, parameters shared by all agents; Sec. 3.2 "PPO"); the scaled scenario uses width 128
-// with bf16 operands and fp32 accumulation.
+// Occupancy.  At ~168 registers a SIMD holds three wavefronts, and the hardware places a block's
+// wavefronts on the four SIMDs as a unit: two 5-wavefront blocks do not fit one CU (measured:
+// one resident block per CU), a 10-wavefront block does (3 + 3 + 2 + 2).  So a block is TWO
+// independent 32-env groups of 5 wavefronts that share the staged weights, and the per-step
+// barrier is per group: an arrival counter in LDS instead of the block barrier, so that a group
+// never waits for the other one.
 #include "mpe_policy_common.h"
 
 namespace mpe {
 
 namespace {
 
-// LDS plan of one block (bytes).  The logits buffer and the new-position exchange share one
-// region: within a phase each wavefront touches only its own 64 rows of it (logits first, then
-// its agents' new positions), and block barriers separate that phase from the one in which
-// every wavefront reads the positions.
-template <int N, int H, bool BF16, int EB>
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// LDS plan of one block (bytes).
+template <int N, int H, int EB>
 struct Smem {
-  using S = Shape<N, H, BF16>;
-  static constexpr int ROWS = EB * N;
-  static constexpr bool kRewardInRegs = (N <= 4);   // every lane evaluates the N*N distances itself
-  static constexpr size_t WEIGHTS = S::OFF_W3A;                   // W1A + W2A (W3A lives in registers)
-  static constexpr size_t BIAS = S::BIAS_BYTES;
-  static constexpr size_t OBS = size_t(ROWS) * S::D * 4 + 64;     // + zeroed tail for K padding reads
-  static constexpr size_t ZP = size_t(ROWS) * 5 * 4;              // logits [row][5]; newpos [row] float2 inside
-  static constexpr size_t DMIN = kRewardInRegs ? 0 : size_t(ROWS) * 4;
-  static constexpr size_t OFF_BIAS = (WEIGHTS + 15) & ~size_t(15);
-  static constexpr size_t OFF_OBS = OFF_BIAS + ((BIAS + 15) & ~size_t(15));
-  static constexpr size_t OFF_ZP = OFF_OBS + ((OBS + 15) & ~size_t(15));
-  static constexpr size_t OFF_DMIN = OFF_ZP + ((ZP + 15) & ~size_t(15));
-  static constexpr size_t TOTAL = OFF_DMIN + ((DMIN + 15) & ~size_t(15));
+  using S = Shape<N, H, true>;
+  static constexpr int ROWS = EB * N, WAVES = ROWS / 64;
+  static constexpr size_t WEIGHTS = S::OFF_BIAS;                   // W1A + W2A + W3A
+  static constexpr size_t OFF_BIAS = WEIGHTS;
+  static constexpr size_t STAGE_WAVE = size_t(64) * 5 * 4;         // the wave's logits [64][5]
+  static constexpr size_t OFF_STAGE = OFF_BIAS + S::BIAS_BYTES;
+  static constexpr size_t OFF_NEWPOS = OFF_STAGE + WAVES * STAGE_WAVE;   // [2][ROWS] float2, by step parity
+  static constexpr size_t OFF_DMIN = OFF_NEWPOS + size_t(2) * ROWS * 8;  // [2][ROWS] float,  by step parity
+  static constexpr size_t OFF_LM = OFF_DMIN + size_t(2) * ROWS * 4;      // [EB][N] float2 landmark positions
+  static constexpr size_t OFF_ARRIVED = OFF_LM + size_t(ROWS) * 8;       // arrival counter of each sync group
+  static constexpr size_t TOTAL = OFF_ARRIVED + 16;
+  static_assert(OFF_STAGE % 16 == 0 && STAGE_WAVE % 16 == 0 && OFF_NEWPOS % 16 == 0, "alignment");
 };
 
-// A-operand registers of layer 3 (5 outputs padded to one 16-wide tile), loaded once per kernel.
-template <int N, int H, bool BF16>
-struct W3Regs {
-  using S = Shape<N, H, BF16>;
-  f32x4 f[BF16 ? 1 : S::S2 / 4];
-  bf16x8 b[BF16 ? S::S2 : 1];
-  __device__ __forceinline__ void load(const uint8_t* __restrict__ run_weights, int lane) {
-    if constexpr (BF16) {
-#pragma unroll
-      for (int s = 0; s < S::S2; ++s) b[s] = reinterpret_cast<const bf16x8*>(run_weights + S::OFF_W3A)[s * 64 + lane];
-    } else {
-#pragma unroll
-      for (int s4 = 0; s4 < S::S2 / 4; ++s4) f[s4] = reinterpret_cast<const f32x4*>(run_weights + S::OFF_W3A)[s4 * 64 + lane];
-    }
-  }
-};
+// Round two floats to bf16 (nearest even) and pack them: low half <- a.
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  const f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
 
-// MLP forward of one 16-row tile (general kernel: bf16 operands, fp32 accumulation); rows'
-// observations are in the LDS tile at obs_rows (row stride D floats).  wsm holds W1A then W2A,
-// bias holds b1, b2, b3 (padded to 16).  Leaves logits of row j in zrows[j*5 .. j*5+4].
-template <int N, int H, bool BF16>
+// 4 x 4 transpose between register index and lane group (lane = 16 * group + j):
+// out[c] at lane (j, g) = in[g] at lane (j, c).
+__device__ __forceinline__ void transpose_groups(uint32_t (&v)[4]) {
+  const auto s0 = __builtin_amdgcn_permlane32_swap(v[0], v[2], false, false);   // upper half of v0 <-> lower half of v2
+  const auto s1 = __builtin_amdgcn_permlane32_swap(v[1], v[3], false, false);
+  const auto t0 = __builtin_amdgcn_permlane16_swap(s0[0], s1[0], false, false);  // odd 16-lane rows of v0 <-> even rows of v1
+  const auto t1 = __builtin_amdgcn_permlane16_swap(s0[1], s1[1], false, false);
+  v[0] = t0[0]; v[1] = t0[1]; v[2] = t1[0]; v[3] = t1[1];
+}
+
+// tanh of 8 accumulator values (hidden tiles 2s and 2s+1 of one batch tile), rounded to bf16: the
+// B operand of K slice s of the next layer (element e <-> tile 2s + e/4, register e%4).
+__device__ __forceinline__ bf16x8 tanh_pack(const f32x4& a0, const f32x4& a1) {
+  u32x4 p;
+  p[0] = pack_bf16(fast_tanh(a0[0]), fast_tanh(a0[1]));
+  p[1] = pack_bf16(fast_tanh(a0[2]), fast_tanh(a0[3]));
+  p[2] = pack_bf16(fast_tanh(a1[0]), fast_tanh(a1[1]));
+  p[3] = pack_bf16(fast_tanh(a1[2]), fast_tanh(a1[3]));
+  return __builtin_bit_cast(bf16x8, p);
+}
+
+// Envs of one sync group: the smallest count whose agent rows fill whole wavefronts.
+__host__ __device__ constexpr int sync_group_envs(int n) {
+  int g = 64;
+  while (g > 1 && (n % 2 == 0)) { g /= 2; n /= 2; }
+  return g;
+}
+
+// Barrier among the wavefronts of one sync group.  `arrived` counts arrivals since the start of
+// the kernel; `target` = (wavefronts per group) * (barriers so far).  Every wavefront of a block
+// runs the same number of steps and none leaves early, and a block is resident as a whole, so
+// each wait ends.
+__device__ __forceinline__ void group_barrier(uint32_t* arrived, uint32_t target, int lane) {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  if (lane == 0) __hip_atomic_fetch_add(arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  while (__hip_atomic_load(arrived, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < target)
+    __builtin_amdgcn_s_sleep(1);
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
+#define MPE_MFMA_BF(A, B, C) __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, B, C, 0, 0, 0)
+
+// MLP forward of one 16-row tile from its layer-1 B operands b1[slice].  wsm holds W1A then W2A,
+// then W3A, bias holds b1, b2, b3 (padded to 16).  Leaves the logits of row j in
+// zrows[j*5 .. j*5+4].
+template <int N, int H>
 __device__ __forceinline__ void policy_tile(const uint8_t* __restrict__ wsm, const float* __restrict__ bias,
-                                            const W3Regs<N, H, BF16>& w3, const float* __restrict__ obs_rows,
-                                            float* __restrict__ zrows, int lane) {
-  static_assert(BF16, "the fp32 shape has its own pipelined kernel");
-  using S = Shape<N, H, BF16>;
-  constexpr int D = S::D, MT = S::MT;
+                                            const bf16x8 (&b1)[Shape<N, H, true>::S1], float* __restrict__ zrows,
+                                            int lane) {
+  using S = Shape<N, H, true>;
+  constexpr int MT = S::MT;
   const int j = lane & 15, gq = lane >> 4;
   // Weights and biases are re-read from LDS for every tile on purpose: the addresses go through
-  // an opaque zero offset, so the compiler cannot hoist ~100 registers of loop-invariant
-  // operands out of the step loop (which would cost a wavefront of occupancy).  The offset is an
-  // integer, not a laundered pointer, so the loads stay LDS (ds_read) instructions.
+  // an opaque zero offset, so the compiler cannot hoist loop-invariant operands out of the step
+  // loop (which would cost registers and a wavefront of occupancy).  The offset is an integer,
+  // not a laundered pointer, so the loads stay LDS (ds_read) instructions.
   {
     uint32_t zero = 0;
     asm volatile("" : "+v"(zero));
     wsm += zero;
     bias += zero;
   }
+  const bf16x8* w1 = reinterpret_cast<const bf16x8*>(wsm + S::OFF_W1A) + lane;   // [m][s][lane]
+  const bf16x8* w2 = reinterpret_cast<const bf16x8*>(wsm + S::OFF_W2A) + lane;   // [m][s][lane]
+  const bf16x8* w3 = reinterpret_cast<const bf16x8*>(wsm + S::OFF_W3A) + lane;   // [s][lane]
+  // The A operands of layers 1 and 2 are used in the order k = (layer, slice, m); a ring of kAhead
+  // of them is kept in flight so that an LDS read is issued kAhead matrix instructions before
+  // the one that consumes it.
+  constexpr int K1 = S::S1 * MT, K2 = S::S2 * MT, kAhead = 4;
+  auto a_ptr = [&](int k) -> const bf16x8* {
+    return k < K1 ? w1 + ((k % MT) * S::S1 + k / MT) * 64 : w2 + (((k - K1) % MT) * S::S2 + (k - K1) / MT) * 64;
+  };
+  bf16x8 ring[kAhead];
+#pragma unroll
+  for (int k = 0; k < kAhead; ++k) ring[k] = *a_ptr(k);
   f32x4 acc[MT];
-  f32x4 hid[MT];
 #pragma unroll
   for (int m = 0; m < MT; ++m) acc[m] = *reinterpret_cast<const f32x4*>(bias + 16 * m + 4 * gq);
-  // ---- layer 1
-  {
-    const bf16x8* w1 = reinterpret_cast<const bf16x8*>(wsm + S::OFF_W1A);
 #pragma unroll
-    for (int s = 0; s < S::S1; ++s) {
-      const float* src = obs_rows + j * D + 32 * s + 8 * gq;
-      const f32x4 lo = *reinterpret_cast<const f32x4*>(src);
-      const f32x4 hi = *reinterpret_cast<const f32x4*>(src + 4);
-      bf16x8 b;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) { b[e] = __bf16(lo[e]); b[4 + e] = __bf16(hi[e]); }
-#pragma unroll
-      for (int m = 0; m < MT; ++m)
-        acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1[(m * S::S1 + s) * 64 + lane], b, acc[m], 0, 0, 0);
-    }
+  for (int k = 0; k < K1; ++k) {
+    acc[k % MT] = MPE_MFMA_BF(ring[k % kAhead], b1[k / MT], acc[k % MT]);
+    ring[k % kAhead] = *a_ptr(k + kAhead);
   }
+  bf16x8 hb[S::S2];
 #pragma unroll
-  for (int m = 0; m < MT; ++m) {
+  for (int s = 0; s < S::S2; ++s) hb[s] = tanh_pack(acc[2 * s], acc[2 * s + 1]);
 #pragma unroll
-    for (int r = 0; r < 4; ++r) hid[m][r] = fast_tanh(acc[m][r]);
-    acc[m] = *reinterpret_cast<const f32x4*>(bias + H + 16 * m + 4 * gq);
+  for (int m = 0; m < MT; ++m) acc[m] = *reinterpret_cast<const f32x4*>(bias + H + 16 * m + 4 * gq);
+#pragma unroll
+  for (int k = K1; k < K1 + K2; ++k) {
+    acc[k % MT] = MPE_MFMA_BF(ring[k % kAhead], hb[(k - K1) / MT], acc[k % MT]);
+    if (k + kAhead < K1 + K2) ring[k % kAhead] = *a_ptr(k + kAhead);
   }
-  // ---- layer 2
-  {
-    const bf16x8* w2 = reinterpret_cast<const bf16x8*>(wsm + S::OFF_W2A);
-#pragma unroll
-    for (int s = 0; s < S::S2; ++s) {
-      bf16x8 b;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) { b[e] = __bf16(hid[2 * s][e]); b[4 + e] = __bf16(hid[2 * s + 1][e]); }
-#pragma unroll
-      for (int m = 0; m < MT; ++m)
-        acc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w2[(m * S::S2 + s) * 64 + lane], b, acc[m], 0, 0, 0);
-    }
-  }
-#pragma unroll
-  for (int m = 0; m < MT; ++m) {
-#pragma unroll
-    for (int r = 0; r < 4; ++r) hid[m][r] = fast_tanh(acc[m][r]);
-  }
-  // ---- layer 3; two accumulators break the dependent chain
+  // layer 3; two accumulators break the dependent chain
   f32x4 z0 = *reinterpret_cast<const f32x4*>(bias + 2 * H + 4 * gq);
   f32x4 z1 = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
   for (int s = 0; s < S::S2; ++s) {
-    bf16x8 b;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) { b[e] = __bf16(hid[2 * s][e]); b[4 + e] = __bf16(hid[2 * s + 1][e]); }
-    if (s & 1) z1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w3.b[s], b, z1, 0, 0, 0);
-    else z0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w3.b[s], b, z0, 0, 0, 0);
+    const bf16x8 b = tanh_pack(acc[2 * s], acc[2 * s + 1]);
+    if (s & 1) z1 = MPE_MFMA_BF(w3[s * 64], b, z1);
+    else z0 = MPE_MFMA_BF(w3[s * 64], b, z0);
   }
   z0 += z1;
   // lane (j, gq) holds outputs 4gq + r of row j: outputs 0..3 in group 0, output 4 in group 1
@@ -150,42 +178,37 @@ __device__ __forceinline__ void policy_tile(const uint8_t* __restrict__ wsm, con
   }
 }
 
-// Cooperative copy of NF4 float4 from LDS to global by THREADS lanes; all reads issued first.
-template <int NF4, int THREADS>
-__device__ __forceinline__ void block_stream_out_full(const float* tile, float* dst, int tid) {
-  constexpr int kFullIters = NF4 / THREADS;
-  constexpr int kTail = NF4 % THREADS;
-  const v4f* src4 = reinterpret_cast<const v4f*>(tile) + tid;
-  v4f* dst4 = reinterpret_cast<v4f*>(dst) + tid;
-  v4f v[kFullIters > 0 ? kFullIters : 1];
-  v4f vt = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-  for (int k = 0; k < kFullIters; ++k) v[k] = src4[k * THREADS];
-  if (kTail > 0 && tid < kTail) vt = src4[kFullIters * THREADS];
-#pragma unroll
-  for (int k = 0; k < kFullIters; ++k) dst4[k * THREADS] = v[k];
-  if (kTail > 0 && tid < kTail) dst4[kFullIters * THREADS] = vt;
-}
-
-template <int N, int H, bool BF16, int EB, int MINW>
+template <int N, int H, int EB, int MINW>
 __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
-                                                                      int per_run_weights) {
-  using S = Shape<N, H, BF16>;
-  using M = Smem<N, H, BF16, EB>;
-  constexpr int D = S::D, ROWS = EB * N, THREADS = ROWS;
-  static_assert(THREADS % 64 == 0, "block must be whole wavefronts");
+                                                                      int per_run_weights, uint32_t groups,
+                                                                      uint32_t groups_per_xcd) {
+  using S = Shape<N, H, true>;
+  using M = Smem<N, H, EB>;
+  constexpr int D = S::D, KIN = S::KIN, ROWS = EB * N, THREADS = ROWS;
+  constexpr int RF4 = D / 4;                 // 16-byte chunks of one observation row
+  constexpr int PD = S::S1 * 16;             // dwords of one row as bf16 pairs, zero padded to whole K slices
+  constexpr int GE = sync_group_envs(N), GW = GE * N / 64;   // envs / wavefronts of one sync group
+  static_assert(EB % GE == 0 && EB / GE <= 4, "a block is whole sync groups");
+  static_assert(D % 4 == 0 && KIN % 2 == 0, "rows are stored as 16-byte chunks and packed as bf16 pairs");
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   uint8_t* wsm = smem;
   float* bias = reinterpret_cast<float*>(smem + M::OFF_BIAS);
-  float* tile = reinterpret_cast<float*>(smem + M::OFF_OBS);
-  float* zbuf = reinterpret_cast<float*>(smem + M::OFF_ZP);     // [ROWS][5]; wave w owns rows 64w..64w+63
+  float2* newpos = reinterpret_cast<float2*>(smem + M::OFF_NEWPOS);
   float* dminbuf = reinterpret_cast<float*>(smem + M::OFF_DMIN);
+  float2* lmbuf = reinterpret_cast<float2*>(smem + M::OFF_LM);
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int el = tid / N, i = tid - el * N;          // env within block, agent
+  float* stage = reinterpret_cast<float*>(smem + M::OFF_STAGE + size_t(wave) * M::STAGE_WAVE);
+  uint32_t* arrived = reinterpret_cast<uint32_t*>(smem + M::OFF_ARRIVED) + wave / GW;
   const size_t TE = A.TE;
-  const size_t g0 = size_t(blockIdx.x) * EB;
+  // XCD-aware mapping: the hardware deals block b to XCD b % 8; each XCD gets one contiguous range
+  // of env groups, so the partial cache lines of neighbouring groups meet in one L2.
+  const uint32_t grp = (blockIdx.x & 7u) * groups_per_xcd + (blockIdx.x >> 3);
+  if (grp >= groups) return;  // whole block, before any barrier
+  const size_t g0 = size_t(grp) * EB;
   const size_t g = g0 + el;
   const bool valid = g < TE;
   const uint32_t gc = valid ? uint32_t(g) : uint32_t(g0);
@@ -193,38 +216,32 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
   const uint32_t env = gc - run * A.E;
   const size_t left = TE - g0;
   const int nvalid = left < size_t(EB) ? int(left) : EB;   // valid envs in this block
-  // new-position slot of row r inside the shared logits/positions region: the first 8 bytes of
-  // the 20-byte logits slot of that row's wavefront-local index
-  auto newpos_of = [&](int r) -> float2* { return reinterpret_cast<float2*>(zbuf + (r >> 6) * (64 * 5)) + (r & 63); };
+  const int wave_rows = min(max(nvalid * N - wave * 64, 0), 64);   // rows of this wavefront that belong to valid envs
 
-  // ---- stage this block's weights (the run of its first env): W1A, W2A, biases in LDS; W3A in registers
+  // ---- stage this block's weights (the run of its first env) in LDS: the packed buffer is
+  // W1A, W2A, W3A, biases in that order, and so is the LDS image
   const uint8_t* run_weights = packed + (per_run_weights ? size_t(uint32_t(g0) / A.E) * S::RUN_BYTES : 0);
-  W3Regs<N, H, BF16> w3;
-  w3.load(run_weights, lane);
   {
     const uint4* src = reinterpret_cast<const uint4*>(run_weights);
     uint4* dst = reinterpret_cast<uint4*>(wsm);
-    for (int k = tid; k < int(S::OFF_W3A / 16); k += THREADS) dst[k] = src[k];
-    const uint4* bsrc = reinterpret_cast<const uint4*>(run_weights + S::OFF_BIAS);
-    uint4* bdst = reinterpret_cast<uint4*>(bias);
-    for (int k = tid; k < int(S::BIAS_BYTES / 16); k += THREADS) bdst[k] = bsrc[k];
-    if (tid < 16) tile[ROWS * D + tid] = 0.0f;
+    for (int k = tid; k < int(S::RUN_BYTES / 16); k += THREADS) dst[k] = src[k];
   }
 
-  // ---- registers: own agent, all agents' positions, all landmarks
-  float px = 0.0f, py = 0.0f, vx = 0.0f, vy = 0.0f;
-  float qx[N], qy[N], lx[N], ly[N];
+  // ---- registers: own agent, all agents' positions, landmark i (the one whose coverage distance
+  // this lane evaluates); LDS: all landmarks of the block's envs (they change only at a reset)
+  float px = 0.0f, py = 0.0f, vx = 0.0f, vy = 0.0f, mylx = 0.0f, myly = 0.0f;
+  float qx[N], qy[N];
   int32_t ep = 0;
 #pragma unroll
-  for (int a = 0; a < N; ++a) qx[a] = qy[a] = lx[a] = ly[a] = 0.0f;
+  for (int a = 0; a < N; ++a) qx[a] = qy[a] = 0.0f;
   if (valid) {
 #pragma unroll
     for (int a = 0; a < N; ++a) {
       qx[a] = A.st.pos_a[(0 * N + a) * TE + g];
       qy[a] = A.st.pos_a[(1 * N + a) * TE + g];
-      lx[a] = A.st.pos_l[(0 * N + a) * TE + g];
-      ly[a] = A.st.pos_l[(1 * N + a) * TE + g];
     }
+    mylx = A.st.pos_l[(0 * N + i) * TE + g];
+    myly = A.st.pos_l[(1 * N + i) * TE + g];
     vx = A.st.vel_a[(0 * N + i) * TE + g];
     vy = A.st.vel_a[(1 * N + i) * TE + g];
     ep = A.st.ep_step[g];
@@ -233,30 +250,43 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
   for (int a = 0; a < N; ++a) {
     if (a == i) { px = qx[a]; py = qy[a]; }
   }
+  lmbuf[tid] = make_float2(mylx, myly);   // tid = el * N + i
+  if (tid < EB / GE) reinterpret_cast<uint32_t*>(smem + M::OFF_ARRIVED)[tid] = 0u;
+  __syncthreads();  // weights, biases, landmarks and counters staged; the only block-wide barrier
 
-  // Write this lane's observation row into the tile (the zero comm slots only the first time).
-  auto write_obs_row = [&](bool with_zeros) {
-    float2* row = reinterpret_cast<float2*>(tile + tid * D);
-    int c = 0;
-    row[c++] = make_float2(vx, vy);
-    row[c++] = make_float2(px, py);
+  // The lane's observation: its KIN leading entries (the trailing communication slots are zeros).
+  auto build_obs = [&](float (&o)[KIN]) {
+    o[0] = vx; o[1] = vy; o[2] = px; o[3] = py;
 #pragma unroll
-    for (int l = 0; l < N; ++l) row[c++] = make_float2(lx[l] - px, ly[l] - py);
-#pragma unroll
-    for (int a = 0; a < N; ++a) {
-      if (a != i) row[c++] = make_float2(qx[a] - px, qy[a] - py);
+    for (int l = 0; l < N; ++l) {
+      const float2 lm = lmbuf[el * N + l];
+      o[4 + 2 * l] = lm.x - px;
+      o[5 + 2 * l] = lm.y - py;
     }
-    if (with_zeros) {
-      for (int zc = 0; zc < N - 1; ++zc) row[c + zc] = make_float2(0.0f, 0.0f);
+#pragma unroll
+    for (int c = 0; c < N - 1; ++c) {   // other agents, ascending: slot c holds agent c + (c >= i)
+      const float ox = c >= i ? qx[c + 1] : qx[c];
+      const float oy = c >= i ? qy[c + 1] : qy[c];
+      o[4 + 2 * N + 2 * c] = ox - px;
+      o[5 + 2 * N + 2 * c] = oy - py;
     }
   };
-  write_obs_row(true);
+  // Store this wavefront's rows to dst (its slot in a [env][N][D] slice).
+  auto flush_rows = [&](const float (&o)[KIN], float* dst) {
+    if (lane < wave_rows) {
+      v4f* d4 = reinterpret_cast<v4f*>(dst) + lane * RF4;
+#pragma unroll
+      for (int q = 0; q < RF4; ++q) {
+        v4f v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (4 * q + e < KIN) ? o[(4 * q + e < KIN) ? 4 * q + e : 0] : 0.0f;
+        d4[q] = v;
+      }
+    }
+  };
 
-  bool done_prev = false;
-  const int n_out_floats = nvalid * N * D;  // floats of one time slice this block writes
-  // Output addresses = uniform per-step base (advanced once per step, lives in SGPRs) + a
-  // 32-bit lane offset that never changes.
-  float* obs_p = A.obs_traj ? A.obs_traj + g0 * (N * D) : nullptr;
+  const size_t wave_row0 = (g0 * N + size_t(wave) * 64) * D;   // float offset of this wavefront's rows in a slice
+  float* obs_p = A.obs_traj ? A.obs_traj + wave_row0 : nullptr;
   uint8_t* act_base = A.act_traj;
   float* rew_base = A.rew_traj;
   uint8_t* done_base = A.done_traj;
@@ -264,54 +294,41 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
   const bool env_writer = valid && i == 0;            // the lane that stores per-env outputs
   uint32_t step = A.abs_step;
 
-  for (int t = 0; t <= A.T; ++t, ++step) {
-    __syncthreads();  // (A) tile (and dminbuf) complete
-    if constexpr (!M::kRewardInRegs) {
-      // reward and done of the step finished in the previous iteration
-      if (t > 0) {
-        if (env_writer) {
-          if (rew_base) {
-            float r = 0.0f;
-#pragma unroll
-            for (int a = 0; a < N; ++a) r -= dminbuf[el * N + a];
-            (rew_base - TE)[gc] = r;
-          }
-          if (done_base) (done_base - TE)[gc] = done_prev ? 1 : 0;
-        }
-      }
-    }
-    // stream the tile out: obs_traj[t] for t < T, last_obs at t == T
+  for (int t = 0; t < A.T; ++t, ++step) {
+    // ---- observation row -> trajectory, and -> bf16 B operands of layer 1 for the wave's 4 tiles
+    bf16x8 b1[4][S::S1];
     {
-      float* dst = (t < A.T) ? obs_p : (A.last_obs ? A.last_obs + g0 * (N * D) : nullptr);
-      if (dst) {
-        const bool vec4 = (reinterpret_cast<uintptr_t>(dst) & 15u) == 0;
-        if (vec4 && nvalid == EB) {
-          block_stream_out_full<ROWS * D / 4, THREADS>(tile, dst, tid);
-        } else if (vec4) {
-          const int n4 = n_out_floats >> 2;
-          for (int k = tid; k < n4; k += THREADS)
-            reinterpret_cast<float4*>(dst)[k] = reinterpret_cast<const float4*>(tile)[k];
-          if ((n_out_floats & 2) && tid == 0)
-            reinterpret_cast<float2*>(dst)[n_out_floats / 2 - 1] = reinterpret_cast<const float2*>(tile)[n_out_floats / 2 - 1];
-        } else {
-          for (int k = tid; k < (n_out_floats >> 1); k += THREADS)
-            reinterpret_cast<float2*>(dst)[k] = reinterpret_cast<const float2*>(tile)[k];
-        }
+      float o[KIN];
+      build_obs(o);
+      if (obs_p) {
+        flush_rows(o, obs_p);
+        obs_p += TE * (N * D);
       }
-      if (obs_p) obs_p += TE * (N * D);
+      uint32_t pk[PD];
+#pragma unroll
+      for (int d = 0; d < PD; ++d) pk[d] = (2 * d < KIN) ? pack_bf16(o[(2 * d < KIN) ? 2 * d : 0], o[(2 * d < KIN) ? 2 * d + 1 : 0]) : 0u;
+      // chunk g of slice s = dwords 16 s + 4 g .. + 3 of the packed row
+#pragma unroll
+      for (int s = 0; s < S::S1; ++s) {
+        u32x4 tile_b[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          uint32_t v[4] = {pk[16 * s + d], pk[16 * s + 4 + d], pk[16 * s + 8 + d], pk[16 * s + 12 + d]};
+          transpose_groups(v);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) tile_b[c][d] = v[c];
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) b1[c][s] = __builtin_bit_cast(bf16x8, tile_b[c]);
+      }
     }
-    if (t == A.T) break;
-
     // ---- policy: four 16-row tiles per wavefront
-#pragma unroll 1
-    for (int q = 0; q < 4; ++q) {
-      const int r0 = wave * 64 + q * 16;
-      policy_tile<N, H, BF16>(wsm, bias, w3, tile + r0 * D, zbuf + r0 * 5, lane);
-    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) policy_tile<N, H>(wsm, bias, b1[c], stage + c * 16 * 5, lane);
     wave_sync();
     float z[kNumActions];
 #pragma unroll
-    for (int k = 0; k < kNumActions; ++k) z[k] = zbuf[tid * 5 + k];
+    for (int k = 0; k < kNumActions; ++k) z[k] = stage[lane * 5 + k];
     const uint32_t act = gumbel_argmax(z, A.seed, run, env, step, uint32_t(i));
     if (act_base) {
       if (valid) act_base[row_off] = uint8_t(act);
@@ -335,56 +352,49 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
     py = fmaf(vy, A.ph.dt, py);
     vx = fmaf(fx, A.ph.dt_over_mass, vx * A.ph.keep);
     vy = fmaf(fy, A.ph.dt_over_mass, vy * A.ph.keep);
-    wave_sync();      // every lane of this wavefront has read its logits: the slots may be reused
-    *newpos_of(tid) = make_float2(px, py);
-    __syncthreads();  // (C) new positions visible; everyone is done reading the tile
+    float2* np = newpos + (t & 1) * ROWS;
+    np[tid] = make_float2(px, py);
+    // (C) new positions of this step and coverage distances of the previous one are visible
+    group_barrier(arrived, uint32_t(GW) * uint32_t(t + 1), lane);
 
+    // reward of the previous step: sum of its N per-landmark distances
+    if (t > 0 && rew_base) {
+      if (env_writer) {
+        const float* dm = dminbuf + ((t - 1) & 1) * ROWS + el * N;
+        float r = 0.0f;
+#pragma unroll
+        for (int a = 0; a < N; ++a) r -= dm[a];
+        (rew_base - TE)[gc] = r;
+      }
+    }
+    if (rew_base) rew_base += TE;
 #pragma unroll
     for (int a = 0; a < N; ++a) {
-      const float2 p = *newpos_of(el * N + a);
+      const float2 p = np[el * N + a];
       qx[a] = p.x;
       qy[a] = p.y;
     }
-    if constexpr (M::kRewardInRegs) {
-      // shared coverage reward, evaluated by every lane (N*N distances), stored by agent 0
-      float r = 0.0f;
-#pragma unroll
-      for (int l = 0; l < N; ++l) {
-        float best2 = INFINITY;
-#pragma unroll
-        for (int a = 0; a < N; ++a) {
-          const float dx = qx[a] - lx[l], dy = qy[a] - ly[l];
-          best2 = fminf(best2, fmaf(dx, dx, dy * dy));
-        }
-        r -= hw_sqrt(best2);
-      }
-      if (rew_base && env_writer) rew_base[gc] = r;
-    } else {
-      // coverage term of landmark i: min over agents of the distance to it
-      float mylx = 0.0f, myly = 0.0f;
-#pragma unroll
-      for (int l = 0; l < N; ++l) {
-        if (l == i) { mylx = lx[l]; myly = ly[l]; }
-      }
+    // coverage term of landmark i: min over agents of the distance to it (post-step, pre-reset)
+    {
       float best2 = INFINITY;
 #pragma unroll
       for (int a = 0; a < N; ++a) {
         const float dx = qx[a] - mylx, dy = qy[a] - myly;
         best2 = fminf(best2, fmaf(dx, dx, dy * dy));
       }
-      dminbuf[tid] = hw_sqrt(best2);
+      dminbuf[(t & 1) * ROWS + tid] = hw_sqrt(best2);
     }
     ep += 1;
-    done_prev = ep >= A.ph.max_ep;
-    if constexpr (M::kRewardInRegs) {
-      if (done_base && env_writer) done_base[gc] = done_prev ? 1 : 0;
+    const bool done = ep >= A.ph.max_ep;
+    if (done_base) {
+      if (env_writer) done_base[gc] = done ? 1 : 0;
+      done_base += TE;
     }
-    if (rew_base) rew_base += TE;
-    if (done_base) done_base += TE;
-    if (done_prev) {
+    if (done) {
       // new episode keyed by step + 1; every lane regenerates the whole env (rare: 1 step in
-      // max_ep).  The empty asm keeps the compiler from hoisting the env-dependent first Philox
-      // round of all 2N streams out of the step loop, where it would only cost registers.
+      // max_ep) and writes all its landmarks: the lanes of an env store identical values, and a
+      // lane reads them back only after its own stores.  The empty asm keeps the compiler from
+      // hoisting the env-dependent first Philox round of all 2N streams out of the step loop.
       uint32_t env_r = env;
       asm volatile("" : "+v"(env_r));
 #pragma unroll
@@ -393,17 +403,26 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
         qx[a] = word_to_position(w.x);
         qy[a] = word_to_position(w.y);
         const uint4 wl = philox4x32_10(env_r, step + 1u, uint32_t(N + a), kTagResetPos, A.seed, run);
-        lx[a] = word_to_position(wl.x);
-        ly[a] = word_to_position(wl.y);
-      }
-#pragma unroll
-      for (int a = 0; a < N; ++a) {
-        if (a == i) { px = qx[a]; py = qy[a]; }
+        const float2 lm = make_float2(word_to_position(wl.x), word_to_position(wl.y));
+        lmbuf[el * N + a] = lm;
+        if (a == i) { px = qx[a]; py = qy[a]; mylx = lm.x; myly = lm.y; }
       }
       vx = vy = 0.0f;
       ep = 0;
     }
-    write_obs_row(false);
+  }
+  group_barrier(arrived, uint32_t(GW) * uint32_t(A.T + 1), lane);  // coverage distances of the last step
+  if (A.rew_traj && env_writer) {
+    const float* dm = dminbuf + ((A.T - 1) & 1) * ROWS + el * N;
+    float r = 0.0f;
+#pragma unroll
+    for (int a = 0; a < N; ++a) r -= dm[a];
+    (rew_base - TE)[gc] = r;
+  }
+  if (A.last_obs) {
+    float o[KIN];
+    build_obs(o);
+    flush_rows(o, A.last_obs + wave_row0);
   }
 
   // ---- state back to HBM
@@ -412,13 +431,8 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
     A.st.pos_a[(1 * N + i) * TE + g] = py;
     A.st.vel_a[(0 * N + i) * TE + g] = vx;
     A.st.vel_a[(1 * N + i) * TE + g] = vy;
-#pragma unroll
-    for (int l = 0; l < N; ++l) {
-      if (l == i) {
-        A.st.pos_l[(0 * N + l) * TE + g] = lx[l];
-        A.st.pos_l[(1 * N + l) * TE + g] = ly[l];
-      }
-    }
+    A.st.pos_l[(0 * N + i) * TE + g] = mylx;
+    A.st.pos_l[(1 * N + i) * TE + g] = myly;
     if (i == 0) A.st.ep_step[g] = ep;
   }
 }
@@ -435,11 +449,10 @@ hipError_t pack_impl(PolicyBuffers& pb, int R, const float* W1, const float* b1,
   return hipGetLastError();
 }
 
-template <int N, int H, bool BF16, int EB, int MINW>
+template <int N, int H, int EB, int MINW>
 hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s) {
-  using M = Smem<N, H, BF16, EB>;
-  const dim3 grid((A.TE + EB - 1) / EB);
-  auto kern = rollout_policy_kernel<N, H, BF16, EB, MINW>;
+  using M = Smem<N, H, EB>;
+  auto kern = rollout_policy_kernel<N, H, EB, MINW>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -447,15 +460,17 @@ hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(EB * N), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),
-                     int(A.TE != A.E));
+  const uint32_t groups = (A.TE + EB - 1) / EB;
+  const uint32_t per_xcd = (groups + 7) / 8;
+  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(EB * N), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),
+                     int(A.TE != A.E), groups, per_xcd);
   return hipGetLastError();
 }
 
 }  // namespace
 
 // General shapes built: (N, H, envs per block, min waves per SIMD), bf16 operands.
-#define MPE_WIDE_CASES(X) X(10, 128, 32, 2)
+#define MPE_WIDE_CASES(X) X(10, 128, 64, 3)
 
 bool wide_supported(int N, int H) {
 #define X(N_, H_, EB_, MW_) if (N == N_ && H == H_) return true;
@@ -480,7 +495,7 @@ hipError_t launch_rollout_policy_wide(int N, int H, const RolloutArgs& A, const 
       *why = "with several runs, num_envs per run must be a multiple of the block's env count";  \
       return hipSuccess;                                                                         \
     }                                                                                            \
-    return rollout_impl<N_, H_, true, EB_, MW_>(A, pb, s);                                       \
+    return rollout_impl<N_, H_, EB_, MW_>(A, pb, s);                                       \
   }
   MPE_WIDE_CASES(X)
 #undef X
