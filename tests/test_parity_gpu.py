@@ -337,6 +337,51 @@ def test_policy_bf16_wide(mods):
     env.close()
 
 
+@pytest.mark.parametrize("E,R", [(100, 1), (20, 1), (64, 3)])
+def test_policy_bf16_wide_ragged_and_per_run(mods, E, R):
+    """Sizes that leave the second sync group of a block partly or wholly empty, a block smaller
+    than one group, and one set of weights per run."""
+    say("policy bf16 N=10 H=128 E=%d R=%d" % (E, R))
+    env, orc = _policy_pair(mods, E, 10, R, 128, 1, wseed=12)
+    frac, total, worst = _teacher_forced(env, orc, seed=6, T=8)
+    say("  bf16 agreement %.5f over %d samples" % (frac, total))
+    assert frac >= 0.99
+
+    def make_oracle():
+        o = mods[1](Hp.oracle_config(E, 10, R, 128, 1), threads=8)
+        o.set_policy(*synth.policy_weights_with_bias(12, R, 60, 128))
+        return o
+
+    frac2, ww, n_ill, n_all = _free_running(env, orc, 3, 30, make_oracle)
+    say("  bf16 identical episodes %.4f ; worst error %.2e" % (frac2, ww))
+    env.close()
+
+
+def test_policy_bf16_wide_null_outputs_and_continuation(mods):
+    """Any output may be absent; two rollouts of T/2 equal one of T (rewards of the last step
+    of a call are summed after the loop, all others one step late)."""
+    MpeEnv, _ = mods
+    E, T = 96, 24
+    w = Hp.to_dev(synth.policy_weights_with_bias(2, 1, 60, 128))
+    a = MpeEnv(Hp.gpu_config(E, 10, 1, 128, 1))
+    b = MpeEnv(Hp.gpu_config(E, 10, 1, 128, 1))
+    c = MpeEnv(Hp.gpu_config(E, 10, 1, 128, 1))
+    for e in (a, b, c):
+        e.set_policy(*w)
+        e.reset(5)
+    full = a.rollout(T, *a.empty_traj(T))
+    h1 = [x.clone() for x in b.rollout(T // 2, *b.empty_traj(T // 2))]
+    h2 = b.rollout(T - T // 2, *b.empty_traj(T - T // 2))
+    for k in range(4):
+        assert torch.equal(full[k], torch.cat([h1[k], h2[k]])), "output %d" % k
+    assert torch.equal(full[4], h2[4])
+    c.rollout(T, None, None, None, None, None)      # no outputs at all
+    for x, y in zip(a.get_state(), c.get_state()):
+        assert torch.equal(x, y) if hasattr(x, "shape") else x == y
+    for e in (a, b, c):
+        e.close()
+
+
 def test_set_policy_none_returns_to_uniform(mods):
     MpeEnv, _ = mods
     env, orc = _policy_pair(mods, 64, 3, 1, 64, 0, wseed=1)
