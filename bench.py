@@ -55,9 +55,9 @@ def cpu_baseline(workload, weights, T, seed, target_seconds=12.0):
     from tests import helpers as Hp
     cores = max(1, min(os.cpu_count() or 1, 16))
 
-    def run(n):
+    def run(n, threads=cores):
         orc = Oracle(Hp.oracle_config(n, workload.num_agents, 1, workload.hidden, workload.weight_dtype),
-                     threads=cores)
+                     threads=threads)
         orc.set_policy(*weights)
         orc.reset(seed)
         t0 = time.perf_counter()
@@ -69,8 +69,11 @@ def cpu_baseline(workload, weights, T, seed, target_seconds=12.0):
     n = int(min(workload.num_envs, max(probe_n, probe_n * target_seconds / max(probe, 1e-3))))
     n -= n % 64 if n >= 64 else 0
     dt = run(n)
+    n1 = max(64, n // (4 * cores))          # single-thread figure on a sample sized for ~1/4 of the time
+    dt1 = run(n1, threads=1)
     return {"value": n * workload.num_agents * T / dt, "unit": "agent-steps/s", "cores": cores,
             "kind": "oracle", "seconds": round(dt, 3),
+            "one_thread": {"value": n1 * workload.num_agents * T / dt1, "envs": n1, "seconds": round(dt1, 3)},
             "sample": "envs 0..%d of the same workload (same seed, same weights), %d fused steps, "
                       "fp64 scalar C++ oracle, %d threads over contiguous env ranges" % (n - 1, T, cores)}
 
@@ -113,6 +116,12 @@ def main():
     kavg = float(np.mean(kern_ms))
     tflops = flops_per_agent_step(D, H) * agent_steps / (kavg * 1e-3) / 1e12
     fused_gbs = bytes_per_env_step(N, D) * TE * T / (kavg * 1e-3) / 1e9
+    # other seeds (different initial states, hence different contact patterns), a few calls each
+    by_seed = {str(seed): value}
+    for other in (2, 3):
+        env.reset(other)
+        w_o, _ = time_rollouts(env, T, bufs, max(3, args.steps // 3), 1)
+        by_seed[str(other)] = agent_steps / (w_o / max(3, args.steps // 3))
     # a little sanity: trajectories were really produced
     done_sum = int(bufs[3].sum().item())
     assert done_sum == TE * (T // synth.MAX_EPISODE_STEPS) or done_sum == TE * (T // synth.MAX_EPISODE_STEPS + 1)
@@ -124,6 +133,19 @@ def main():
     wall2, kern2 = time_rollouts(env2, T, bufs, args.steps, args.warmup)
     k2avg = float(np.mean(kern2))
     env_gbs = bytes_per_env_step(N, D) * TE * T / (k2avg * 1e-3) / 1e9
+    # single mpe_step calls (launch-latency dominated at this size; reported, not a roofline figure)
+    actions = torch.zeros((TE, N), dtype=torch.uint8, device="cuda")
+    sbufs = (env2.empty_obs(), torch.empty(TE, dtype=torch.float32, device="cuda"),
+             torch.empty(TE, dtype=torch.uint8, device="cuda"))
+    for _ in range(5):
+        env2.step(actions, *sbufs)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    n_single = 200
+    for _ in range(n_single):
+        env2.step(actions, *sbufs)
+    torch.cuda.synchronize()
+    step_us = (time.perf_counter() - t0) / n_single * 1e6
     env2.close()
 
     out = {
@@ -145,6 +167,7 @@ def main():
         "config": {"workload": wl.name, "envs": TE, "agents": N, "T": T, "policy": "%d->%d->%d->5 tanh" % (D, H, H),
                    "seed": seed, "parallelism": "1 gpu"},
         "env_steps_per_s": value / N,
+        "value_by_seed": by_seed,
         "roofline": {
             "kernel": ("rollout_policy_f32_kernel" if wl.weight_dtype == 0 else "rollout_policy_kernel")
                       + " (fused, one launch per step)",
@@ -170,6 +193,8 @@ def main():
                          "bytes_per_env_step": bytes_per_env_step(N, D),
                          "algorithmic_bytes": bytes_per_env_step(N, D) * TE * T},
         },
+        "single_step": {"us_per_mpe_step_call": step_us, "env_steps_per_s": TE / (step_us * 1e-6),
+                        "note": "back-to-back mpe_step calls with resident actions; 352 B per env-step"},
         "paper_context": {"mpe_simple_spread_steps_per_s": {"original_cpu_1env_epyc7763": 8.3e4,
                                                             "jax_a100_10k_envs_random_actions": 4.0e7},
                           "note": "paper Table 3, env-only random actions, other hardware; context only"},
