@@ -78,6 +78,9 @@ struct Config {
   double dt, damping, mass, accel;
   double agent_radius, landmark_radius;
   double contact_force, contact_margin;
+  int32_t reward_mode;   // 0: one shared coverage reward per env; 1: one mixed reward per agent (R-6b)
+  int32_t reserved;
+  double local_ratio;    // weight of the agent's own collision term in mode 1
 };
 
 struct Policy {
@@ -182,12 +185,17 @@ double softplus(double x) { return std::max(x, 0.0) + std::log1p(std::exp(-std::
 //  R-5 integration: p_i += v_i * dt with the old velocity, then
 //        v_i = v_i * (1 - damping) + (F_i / mass) * dt.   No speed clip.
 //  R-6 reward on the post-step positions: r = - sum_k min_i |p_i - l_k|, one per env.
+//  R-6b (reward_mode 1; the reward of the CPU lineage the paper's MPE port corresponds to, App. C
+//      "environments correspond to existing CPU-based implementations"): agent i also pays 1 for
+//      every other agent it overlaps after the step, c_i = #{ j != i : |p_i - p_j| < 2 r }, and
+//      its reward mixes the two terms:  r_i = (1 - local_ratio) * r - local_ratio * c_i.
+//      `reward` then holds N values.
 //  R-7 ep_step += 1; done = (ep_step >= max_episode_steps).  If done, the env is reset
 //      with the counter's step field set to s + 1, so the new episode depends only on
 //      (seed, run, env, s + 1).
 // ---------------------------------------------------------------------------------
 void step_env(Oracle& o, int run, int env, uint32_t s, const uint8_t* act /* [N] */,
-              double* reward, uint8_t* done) {
+              double* reward /* [1], or [N] in reward_mode 1 */, uint8_t* done) {
   const Config& c = o.cfg;
   const size_t ge = size_t(run) * o.E + env;
   double* pa = &o.pos_a[ge * o.N * 2];
@@ -236,7 +244,20 @@ void step_env(Oracle& o, int run, int env, uint32_t s, const uint8_t* act /* [N]
     }
     r -= best;
   }
-  *reward = r;
+  if (c.reward_mode == 1) {
+    for (int i = 0; i < o.N; ++i) {
+      int overlaps = 0;
+      for (int j = 0; j < o.N; ++j) {
+        if (j == i) continue;
+        const double dx = pa[2 * i + 0] - pa[2 * j + 0];
+        const double dy = pa[2 * i + 1] - pa[2 * j + 1];
+        if (std::sqrt(dx * dx + dy * dy) < 2.0 * c.agent_radius) ++overlaps;
+      }
+      reward[i] = (1.0 - c.local_ratio) * r - c.local_ratio * double(overlaps);
+    }
+  } else {
+    *reward = r;
+  }
   o.ep_step[ge] += 1;
   const bool d = o.ep_step[ge] >= c.max_episode_steps;
   *done = d ? 1 : 0;
@@ -341,6 +362,8 @@ void rollout_range(Oracle& o, size_t g0, size_t g1, int T, double* obs_traj, uin
   const size_t row = size_t(o.N) * o.D;
   std::vector<double> ob(row);
   std::vector<uint8_t> act(o.N);
+  const size_t RW = o.cfg.reward_mode == 1 ? size_t(o.N) : 1;   // rewards per env and step
+  std::vector<double> r(RW);
   for (size_t ge = g0; ge < g1; ++ge) {
     const int run = int(ge / o.E), env = int(ge % o.E);
     for (int t = 0; t < T; ++t) {
@@ -349,10 +372,9 @@ void rollout_range(Oracle& o, size_t g0, size_t g1, int T, double* obs_traj, uin
       if (obs_traj) std::memcpy(obs_traj + (size_t(t) * TE + ge) * row, ob.data(), row * sizeof(double));
       choose_actions(o, run, env, s, ob.data(), act.data());
       if (act_traj) std::memcpy(act_traj + (size_t(t) * TE + ge) * o.N, act.data(), o.N);
-      double r;
       uint8_t d;
-      step_env(o, run, env, s, act.data(), &r, &d);
-      if (rew_traj) rew_traj[size_t(t) * TE + ge] = r;
+      step_env(o, run, env, s, act.data(), r.data(), &d);
+      if (rew_traj) std::memcpy(rew_traj + (size_t(t) * TE + ge) * RW, r.data(), RW * sizeof(double));
       if (done_traj) done_traj[size_t(t) * TE + ge] = d;
     }
     if (last_obs) observe_env(o, ge, last_obs + ge * row);
@@ -376,6 +398,9 @@ struct orc_config {
   double dt, damping, mass, accel;
   double agent_radius, landmark_radius;
   double contact_force, contact_margin;
+  int32_t reward_mode;
+  int32_t reserved;
+  double local_ratio;
 };
 
 const char* orc_last_error(void) { return g_err.c_str(); }
@@ -389,6 +414,7 @@ int orc_create(const orc_config* c, void** out) {
   if (c->num_envs < 1 || c->num_agents < 1 || c->num_landmarks < 1 || c->num_runs < 1 ||
       c->max_episode_steps < 1)
     return fail("sizes must be positive");
+  if (c->reward_mode != 0 && c->reward_mode != 1) return fail("reward_mode must be 0 or 1");
   static_assert(sizeof(orc_config) == sizeof(Config), "config mirror");
   Oracle* o = new Oracle();
   std::memcpy(&o->cfg, c, sizeof(Config));
@@ -434,7 +460,7 @@ int orc_reset(void* h, uint32_t seed, double* obs) {
   return 0;
 }
 
-// actions: [R*E][N]; obs [R*E][N][D] (nullable); reward [R*E]; done [R*E].
+// actions: [R*E][N]; obs [R*E][N][D] (nullable); reward [R*E] ([R*E][N] in reward_mode 1); done [R*E].
 int orc_step(void* h, const uint8_t* actions, double* obs, double* reward, uint8_t* done) {
   if (!h || !actions) return fail("null argument");
   Oracle& o = *static_cast<Oracle*>(h);
@@ -444,10 +470,12 @@ int orc_step(void* h, const uint8_t* actions, double* obs, double* reward, uint8
     for (int i = 0; i < o.N; ++i)
       if (actions[ge * o.N + i] >= NUM_ACTIONS) return fail("action out of range");
   }
+  const size_t RW = o.cfg.reward_mode == 1 ? size_t(o.N) : 1;
+  std::vector<double> r(RW);
   for (size_t ge = 0; ge < TE; ++ge) {
-    double r; uint8_t d;
-    step_env(o, int(ge / o.E), int(ge % o.E), o.abs_step, actions + ge * o.N, &r, &d);
-    if (reward) reward[ge] = r;
+    uint8_t d;
+    step_env(o, int(ge / o.E), int(ge % o.E), o.abs_step, actions + ge * o.N, r.data(), &d);
+    if (reward) std::memcpy(reward + ge * RW, r.data(), RW * sizeof(double));
     if (done) done[ge] = d;
   }
   o.abs_step += 1;

@@ -2,7 +2,8 @@
 
 Argument marshalling and nothing else: every number comes out of the C++ file.
 All arrays are host numpy arrays in the oracle's own plain layouts:
-  obs [R*E][N][D] float64, reward [R*E] float64, done [R*E] uint8, actions [R*E][N] uint8,
+  obs [R*E][N][D] float64, reward [R*E] float64 ([R*E][N] in reward_mode 1), done [R*E] uint8,
+  actions [R*E][N] uint8,
   pos_a / vel_a [R*E][N][2], pos_l [R*E][L][2] float64, ep_step [R*E] int32.
 """
 from __future__ import annotations
@@ -35,7 +36,8 @@ class _CConfig(C.Structure):
         "num_envs", "num_agents", "num_landmarks", "num_runs", "max_episode_steps",
         "hidden", "weight_dtype", "env_offset", "run_offset")] + [(n, C.c_double) for n in (
         "dt", "damping", "mass", "accel", "agent_radius", "landmark_radius",
-        "contact_force", "contact_margin")]
+        "contact_force", "contact_margin")] + [("reward_mode", C.c_int32), ("reserved", C.c_int32),
+                                               ("local_ratio", C.c_double)]
 
 
 @dataclass
@@ -57,6 +59,9 @@ class OracleConfig:
     landmark_radius: float = 0.05
     contact_force: float = 100.0
     contact_margin: float = 1e-3
+    reward_mode: int = 0        # 0: shared coverage reward [R*E]; 1: mixed per-agent reward [R*E][N]
+    reserved: int = 0
+    local_ratio: float = 0.5
 
 
 _lib = None
@@ -130,6 +135,7 @@ class Oracle:
         self.TE = self.E * self.R
         self.D = int(self.lib.orc_obs_dim(self.h))
         self.threads = threads
+        self.rew_shape = (self.TE, self.N) if cfg.reward_mode == 1 else (self.TE,)
         _check(self.lib.orc_set_threads(self.h, threads))
 
     def __del__(self):
@@ -151,7 +157,7 @@ class Oracle:
         a = np.ascontiguousarray(actions, dtype=np.uint8)
         assert a.shape == (self.TE, self.N)
         obs = np.empty((self.TE, self.N, self.D), dtype=np.float64)
-        rew = np.empty(self.TE, dtype=np.float64)
+        rew = np.empty(self.rew_shape, dtype=np.float64)
         done = np.empty(self.TE, dtype=np.uint8)
         _check(self.lib.orc_step(self.h, _ptr(a), _ptr(obs), _ptr(rew), _ptr(done)))
         return obs, rew, done
@@ -177,7 +183,7 @@ class Oracle:
     def rollout(self, T: int, want_obs: bool = True):
         obs = np.empty((T, self.TE, self.N, self.D), dtype=np.float64) if want_obs else None
         act = np.empty((T, self.TE, self.N), dtype=np.uint8)
-        rew = np.empty((T, self.TE), dtype=np.float64)
+        rew = np.empty((T,) + self.rew_shape, dtype=np.float64)
         done = np.empty((T, self.TE), dtype=np.uint8)
         last = np.empty((self.TE, self.N, self.D), dtype=np.float64)
         _check(self.lib.orc_rollout(self.h, T, _ptr(obs), _ptr(act), _ptr(rew), _ptr(done), _ptr(last)))

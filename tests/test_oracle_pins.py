@@ -278,6 +278,81 @@ def test_reward_is_minus_sum_of_min_distances_brute_force():
     assert far > 0
 
 
+# ------------------------------------------------------- mixed per-agent reward (R-6b)
+def test_hand_worked_mixed_reward():
+    g, _ = read_golden("hand_worked_two_step.txt")
+    f = lambda k: np.array([float(x) for x in g[k]])
+    for ratio, keys in ((0.5, ("mixed1_ratio_half", "mixed2_ratio_half")), (0.25, ("mixed1_ratio_quarter",))):
+        o = make(N=3, reward_mode=1, local_ratio=ratio)
+        put(o, f("pos_a").reshape(1, 3, 2), f("vel_a").reshape(1, 3, 2), f("pos_l").reshape(1, 3, 2))
+        for step, key in enumerate(keys, 1):
+            a = np.array([[int(x) for x in g["actions%d" % step]]], np.uint8)
+            rew = o.step(a)[1]
+            assert rew.shape == (1, 3)
+            np.testing.assert_allclose(rew[0], f(key), rtol=0, atol=2e-9)
+            # and from the exact square roots of the shared term
+            shared = -_sqrt_sum(g["reward%d_sqrt_args" % step])
+            np.testing.assert_allclose(rew[0], (1 - ratio) * shared - ratio * f("overlaps%d" % step), rtol=0, atol=1e-13)
+
+
+@pytest.mark.parametrize("ratio", [0.5, 0.3, 1.0, 0.0])
+def test_mixed_reward_brute_force_counts(ratio):
+    """Crowded random states: the shared term from a mode-0 oracle on the same state, the overlap
+    counts from numpy on the post-step positions."""
+    E, N = 40, 6
+    g = np.random.default_rng(11)
+    pa, pl = g.uniform(-0.5, 0.5, (E, N, 2)), g.uniform(-1, 1, (E, N, 2))
+    va = g.uniform(-1, 1, (E, N, 2))
+    act = g.integers(0, 5, (E, N)).astype(np.uint8)
+    o1, o0 = make(N=N, E=E, reward_mode=1, local_ratio=ratio), make(N=N, E=E)
+    put(o1, pa, va, pl)
+    put(o0, pa, va, pl)
+    mixed, shared = o1.step(act)[1], o0.step(act)[1]
+    post = o1.get_state()[0]
+    np.testing.assert_array_equal(post, o0.get_state()[0])       # the reward mode does not touch dynamics
+    d = np.linalg.norm(post[:, :, None, :] - post[:, None, :, :], axis=3)
+    assert np.abs(d[d > 0] - 0.3).min() > 1e-9                    # no pair sits on the threshold
+    counts = (d < 0.3).sum(axis=2) - 1                            # minus the agent itself
+    assert counts.max() >= 2 and counts.min() == 0
+    np.testing.assert_allclose(mixed, (1 - ratio) * shared[:, None] - ratio * counts, rtol=0, atol=1e-13)
+    if ratio > 0:
+        pairs = ((d < 0.3).sum(axis=(1, 2)) - N) // 2
+        np.testing.assert_allclose(((1 - ratio) * shared[:, None] - mixed).sum(axis=1) / ratio, 2 * pairs, atol=1e-9)
+
+
+@pytest.mark.parametrize("d,overlap", [(0.2999, 1), (0.3001, 0), (0.3, 0), (0.0, 1)])
+def test_mixed_reward_overlap_threshold_is_strict(d, overlap):
+    # zero velocities and no action: post-step positions are the given ones
+    o = make(N=2, reward_mode=1, local_ratio=1.0)
+    put(o, [[[0, 0], [d, 0]]], np.zeros((1, 2, 2)), [[[5, 5], [6, 6]]])
+    rew = o.step(np.zeros((1, 2), np.uint8))[1]
+    np.testing.assert_array_equal(rew[0], [-overlap, -overlap])
+
+
+def test_mixed_reward_single_agent_and_rollout():
+    o1, o0 = make(N=1, E=8, reward_mode=1, local_ratio=0.5), make(N=1, E=8)
+    o1.reset(3)
+    o0.reset(3)
+    r1, r0 = o1.rollout(30)[2], o0.rollout(30)[2]
+    assert r1.shape == (30, 8, 1)
+    np.testing.assert_allclose(r1[:, :, 0], 0.5 * r0, rtol=0, atol=1e-15)
+    # rollout == repeated steps, across a reset (reward of the 25th step is from the pre-reset state)
+    a, b = make(N=4, E=6, reward_mode=1), make(N=4, E=6, reward_mode=1)
+    a.reset(9)
+    b.reset(9)
+    obs, act, rew, done, last = a.rollout(27)
+    for t in range(27):
+        o_t, r_t, d_t = b.step(act[t])
+        np.testing.assert_array_equal(r_t, rew[t])
+        np.testing.assert_array_equal(d_t, done[t])
+    assert done[24].all()
+
+
+def test_reward_mode_is_validated():
+    with pytest.raises(RuntimeError):
+        make(N=2, reward_mode=2)
+
+
 def test_rotated_dynamics_match_relabelled_actions():
     # rotating the world by 90 degrees and relabelling actions (+x -> +y, +y -> -x, ...) commutes
     E, N = 20, 3
