@@ -148,6 +148,25 @@ def main():
     step_us = (time.perf_counter() - t0) / n_single * 1e6
     env2.close()
 
+    # the mixed per-agent reward mode on the same shape (rewards [T][TE][N]; a few calls)
+    mixed = {}
+    if wl.weight_dtype == 0 or N == 10:
+        k = max(3, args.steps // 3)
+        env3 = MpeEnv(Hp.gpu_config(wl.num_envs, N, wl.num_runs, H, wl.weight_dtype, reward_mode=1, local_ratio=0.5))
+        env3.set_policy(*Hp.to_dev(weights))
+        env3.reset(seed)
+        b3 = env3.empty_traj(T)
+        w3, k3 = time_rollouts(env3, T, b3, k, 2)
+        env3.set_policy()
+        env3.reset(seed)
+        w4, k4 = time_rollouts(env3, T, b3, k, 2)
+        mixed = {"fused_agent_steps_per_s": agent_steps / (w3 / k), "fused_kernel_ms_avg": float(np.mean(k3)),
+                 "env_only_agent_steps_per_s": agent_steps / (w4 / k), "env_only_kernel_ms_avg": float(np.mean(k4)),
+                 "bytes_per_env_step": bytes_per_env_step(N, D) + 4 * (N - 1),
+                 "note": "MPE_REWARD_MIXED, local_ratio 0.5; env-only uses the general one-wave-per-64-envs kernel"}
+        env3.close()
+        del b3
+
     out = {
         "metric": "agent-steps/sec fused MPE rollout @65,536 envs, 1 MI355X; % HBM roofline",
         "value": value,
@@ -193,6 +212,7 @@ def main():
                          "bytes_per_env_step": bytes_per_env_step(N, D),
                          "algorithmic_bytes": bytes_per_env_step(N, D) * TE * T},
         },
+        "mixed_reward": mixed,
         "single_step": {"us_per_mpe_step_call": step_us, "env_steps_per_s": TE / (step_us * 1e-6),
                         "note": "back-to-back mpe_step calls with resident actions; 352 B per env-step"},
         "paper_context": {"mpe_simple_spread_steps_per_s": {"original_cpu_1env_epyc7763": 8.3e4,

@@ -25,7 +25,8 @@
  * Sizes: E = num_envs (per run), R = num_runs, TE = R*E, N = num_agents, L = num_landmarks
  * (= N), D = 4 + 2L + 4(N-1) = 6N floats per observation, A = 5 actions.
  * Global env index g = run*E + env.  All trajectory arrays are row-major, env-major
- * inside a time slice: obs[t][g][agent][D], act[t][g][agent], rew[t][g], done[t][g].
+ * inside a time slice: obs[t][g][agent][D], act[t][g][agent], rew[t][g] (rew[t][g][agent] with
+ * MPE_REWARD_MIXED), done[t][g].
  */
 #ifndef MPE_H_
 #define MPE_H_
@@ -47,6 +48,16 @@ extern "C" {
 #define MPE_WEIGHTS_FP32 0
 #define MPE_WEIGHTS_BF16 1  /* weights and layer inputs rounded to bf16 (RNE), fp32 accumulate */
 
+/* Reward modes.  SHARED: one value per env, the coverage term  c = -sum_l min_a |p_a - p_l|
+ * on the positions after the step.  MIXED: one value per agent; agent i also pays 1 for every
+ * other agent whose centre is closer than 2 * agent_radius after the step (strictly), and
+ *   r_i = (1 - local_ratio) * c - local_ratio * overlaps_i
+ * -- the reward of the CPU implementation that the paper's MPE port corresponds to (App. C:
+ * the environments match existing CPU-based implementations, version by version).  Reward
+ * arrays then carry N values per env: reward [TE][N], rew_traj [T][TE][N]. */
+#define MPE_REWARD_SHARED 0
+#define MPE_REWARD_MIXED  1
+
 typedef struct mpe_env mpe_env; /* opaque; host memory owned by the library */
 
 typedef struct {
@@ -65,6 +76,8 @@ typedef struct {
   float   contact_margin;    /* 1e-3: softness of the softplus penetration                 */
   int32_t hidden;            /* policy width H: 64 or 128 (0 if no policy will be set)     */
   int32_t weight_dtype;      /* MPE_WEIGHTS_FP32 or MPE_WEIGHTS_BF16                       */
+  int32_t reward_mode;       /* MPE_REWARD_SHARED or MPE_REWARD_MIXED                      */
+  float   local_ratio;       /* in [0, 1]; used by MPE_REWARD_MIXED only (0.5)             */
 } mpe_config;
 
 /* Validate `cfg` (host only), then allocate the device state of TE environments:
@@ -90,7 +103,8 @@ int mpe_reset(mpe_env* env, uint32_t seed, float* obs, void* stream);
  *          treated as 0 (device data is not read back for validation).
  * obs:     [TE][N][D] fp32 out, observation after the step (of the new episode where done),
  *          may be NULL.
- * reward:  [TE] fp32 out, shared by the env's agents: -sum_l min_a |p_a - p_l| after the step.
+ * reward:  [TE] fp32 out, shared by the env's agents: -sum_l min_a |p_a - p_l| after the step
+ *          ([TE][N] mixed per-agent rewards with MPE_REWARD_MIXED).
  * done:    [TE] uint8 out, 1 when the episode reached max_episode_steps; that env has then
  *          already been reset with counter (env, abs_step + 1, entity, 0).
  * reward and done may be NULL.  Advances the absolute step counter by 1.
@@ -112,8 +126,9 @@ int mpe_set_policy(mpe_env* env, const float* W1, const float* b1, const float* 
  * action (policy + Gumbel-max with Philox counter (env, abs_step + t, agent, 2|3); or, with
  * no policy, uniform with counter (env, abs_step + t, agent, 1)), record it, apply the
  * transition, record reward and done.
- * obs_traj [T][TE][N][D] fp32, act_traj [T][TE][N] uint8, rew_traj [T][TE] fp32,
- * done_traj [T][TE] uint8, last_obs [TE][N][D] fp32 (observation after the last step).
+ * obs_traj [T][TE][N][D] fp32, act_traj [T][TE][N] uint8, rew_traj [T][TE] fp32
+ * ([T][TE][N] with MPE_REWARD_MIXED), done_traj [T][TE] uint8, last_obs [TE][N][D] fp32
+ * (observation after the last step).
  * Any of the five may be NULL (that output is then not written).
  * T >= 1.  Advances the absolute step counter by T.  MPE_ESTATE as for mpe_step. */
 int mpe_rollout(mpe_env* env, int32_t T, float* obs_traj, uint8_t* act_traj, float* rew_traj,

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libmpe.so")
 
 MPE_OK, MPE_EINVAL, MPE_ESTATE, MPE_EHIP = 0, -1, -2, -3
 WEIGHTS_FP32, WEIGHTS_BF16 = 0, 1
+REWARD_SHARED, REWARD_MIXED = 0, 1
 NUM_ACTIONS = 5
 
 EXPORTS = ("mpe_create", "mpe_destroy", "mpe_obs_dim", "mpe_reset", "mpe_step", "mpe_set_policy",
@@ -34,7 +35,8 @@ class _CConfig(C.Structure):
                                           "max_episode_steps")] +
                 [(n, C.c_float) for n in ("dt", "damping", "mass", "accel", "agent_radius",
                                           "landmark_radius", "contact_force", "contact_margin")] +
-                [("hidden", C.c_int32), ("weight_dtype", C.c_int32)])
+                [("hidden", C.c_int32), ("weight_dtype", C.c_int32), ("reward_mode", C.c_int32),
+                 ("local_ratio", C.c_float)])
 
 
 @dataclass
@@ -54,6 +56,8 @@ class MpeConfig:
     contact_margin: float = 1e-3
     hidden: int = 0
     weight_dtype: int = WEIGHTS_FP32
+    reward_mode: int = REWARD_SHARED
+    local_ratio: float = 0.5
 
     def to_c(self) -> _CConfig:
         return _CConfig(**{f.name: getattr(self, f.name) for f in fields(self)})
@@ -122,6 +126,8 @@ class MpeEnv:
         self.E, self.N, self.R = cfg.num_envs, cfg.num_agents, cfg.num_runs
         self.TE = self.E * self.R
         self.D = _check(self.lib.mpe_obs_dim(self.h))
+        # rewards per env: one shared value, or one per agent in the mixed mode
+        self.rew_shape = (self.TE, self.N) if cfg.reward_mode == REWARD_MIXED else (self.TE,)
 
     def close(self):
         if getattr(self, "h", None) is not None and self.h.value:
@@ -142,7 +148,7 @@ class MpeEnv:
     def empty_traj(self, T):
         return (self.empty_obs(T),
                 torch.empty((T, self.TE, self.N), dtype=torch.uint8, device=self.device),
-                torch.empty((T, self.TE), dtype=torch.float32, device=self.device),
+                torch.empty((T,) + self.rew_shape, dtype=torch.float32, device=self.device),
                 torch.empty((T, self.TE), dtype=torch.uint8, device=self.device),
                 self.empty_obs())
 

@@ -68,6 +68,11 @@ int validate(const mpe_config* c) {
     return fail(MPE_EINVAL, "hidden must be 0 (no policy), 64 or 128 (got %d)", c->hidden);
   if (c->weight_dtype != MPE_WEIGHTS_FP32 && c->weight_dtype != MPE_WEIGHTS_BF16)
     return fail(MPE_EINVAL, "weight_dtype must be MPE_WEIGHTS_FP32 or MPE_WEIGHTS_BF16");
+  if (c->reward_mode != MPE_REWARD_SHARED && c->reward_mode != MPE_REWARD_MIXED)
+    return fail(MPE_EINVAL, "reward_mode must be MPE_REWARD_SHARED or MPE_REWARD_MIXED");
+  if (c->reward_mode == MPE_REWARD_MIXED &&
+      (!std::isfinite(c->local_ratio) || c->local_ratio < 0.0f || c->local_ratio > 1.0f))
+    return fail(MPE_EINVAL, "local_ratio must be in [0, 1]");
   return MPE_OK;
 }
 
@@ -101,6 +106,9 @@ int mpe_create(const mpe_config* cfg, mpe_env** out) {
   e->ph.inv_margin = float(1.0 / double(cfg->contact_margin));
   e->ph.force_margin = float(double(cfg->contact_force) * double(cfg->contact_margin));
   e->ph.max_ep = cfg->max_episode_steps;
+  e->ph.reward_mode = cfg->reward_mode;
+  e->ph.local_ratio = cfg->reward_mode == MPE_REWARD_MIXED ? cfg->local_ratio : 0.0f;
+  e->ph.two_r_sq = float(4.0 * double(cfg->agent_radius) * double(cfg->agent_radius));
   const size_t nf = agent_floats(e) * sizeof(float);
   hipError_t err = hipMalloc(&e->st.pos_a, nf);
   if (err == hipSuccess) err = hipMalloc(&e->st.vel_a, nf);

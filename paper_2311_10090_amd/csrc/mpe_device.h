@@ -28,7 +28,16 @@ struct Phys {
   float inv_margin;     // 1 / contact_margin
   float force_margin;   // contact_force * contact_margin
   int32_t max_ep;
+  int32_t reward_mode;  // 0: one shared coverage reward per env; 1: one mixed reward per agent
+  float local_ratio;    // mode 1: r_i = (1 - local_ratio) * coverage - local_ratio * overlaps_i
+  float two_r_sq;       // (2 * agent_radius)^2
 };
+
+// Mixed per-agent reward from the shared coverage term and the number of other agents that
+// overlap the agent (centre distance below 2 * agent_radius) after the step.
+__device__ __forceinline__ float mixed_reward(float coverage, uint32_t overlaps, const Phys& ph) {
+  return fmaf(-ph.local_ratio, float(overlaps), (1.0f - ph.local_ratio) * coverage);
+}
 
 // --------------------------------------------------------------------------------------
 // Philox4x32 with 10 rounds (Salmon et al., SC'11).  key = (seed, run),
@@ -129,11 +138,12 @@ __device__ __forceinline__ float action_dir_y(uint32_t a) { return float((0x215u
 
 // One transition under actions a[0..N): control force, pairwise softplus contacts on the
 // pre-step positions, position update with the old velocity, damped velocity update, shared
-// coverage reward on the new positions, episode counter, auto-reset keyed by step + 1.
-template <int N>
+// coverage reward on the new positions (PER_AGENT: the N mixed rewards instead), episode
+// counter, auto-reset keyed by step + 1.
+template <int N, bool PER_AGENT = false>
 __device__ __forceinline__ void transition(Env<N>& s, const uint32_t (&a)[N], const Phys& ph,
                                            uint32_t seed, uint32_t run, uint32_t env, uint32_t step,
-                                           float& reward, bool& done) {
+                                           float (&reward)[PER_AGENT ? N : 1], bool& done) {
   float fx[N], fy[N];
 #pragma unroll
   for (int i = 0; i < N; ++i) {
@@ -172,7 +182,26 @@ __device__ __forceinline__ void transition(Env<N>& s, const uint32_t (&a)[N], co
     }
     r -= hw_sqrt(best2);
   }
-  reward = r;
+  if constexpr (PER_AGENT) {
+    uint32_t ov[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) ov[i] = 0u;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+#pragma unroll
+      for (int j = i + 1; j < N; ++j) {
+        const float dx = s.px[i] - s.px[j];
+        const float dy = s.py[i] - s.py[j];
+        const uint32_t hit = fmaf(dx, dx, dy * dy) < ph.two_r_sq ? 1u : 0u;
+        ov[i] += hit;
+        ov[j] += hit;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) reward[i] = mixed_reward(r, ov[i], ph);
+  } else {
+    reward[0] = r;
+  }
   s.ep += 1;
   done = s.ep >= ph.max_ep;
   if (done) reset_env<N>(s, seed, run, env, step + 1u);

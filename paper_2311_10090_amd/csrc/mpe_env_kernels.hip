@@ -64,20 +64,30 @@ __global__ __launch_bounds__(kWave) void step_kernel(StatePtrs st, Phys ph, uint
 #pragma unroll
     for (int i = 0; i < N; ++i) a[i] = 0u;
   }
-  float r;
   bool d;
-  transition<N>(s, a, ph, seed, L.run, L.env, abs_step, r, d);
+  if (ph.reward_mode == 1) {
+    float r[N];
+    transition<N, true>(s, a, ph, seed, L.run, L.env, abs_step, r, d);
+    if (L.valid && reward) {
+#pragma unroll
+      for (int i = 0; i < N; ++i) reward[L.g * N + i] = r[i];
+    }
+  } else {
+    float r[1];
+    transition<N>(s, a, ph, seed, L.run, L.env, abs_step, r, d);
+    if (L.valid && reward) reward[L.g] = r[0];
+  }
   if (L.valid) {
     store_state<N>(s, st, TE, L.g);
-    if (reward) reward[L.g] = r;
     if (done) done[L.g] = d ? 1 : 0;
   }
   if (obs) emit_obs<N>(s, tile, obs + L.g0 * (N * 6 * N), L.nvalid, L.lane);
 }
 
 // Persistent rollout with uniform random actions (no policy installed).  Output pointers are
-// advanced by one time slice per step instead of being recomputed from (t, env).
-template <int N>
+// advanced by one time slice per step instead of being recomputed from (t, env).  PER_AGENT:
+// rew_traj is [T][TE][N] (mixed per-agent reward).
+template <int N, bool PER_AGENT>
 __global__ __launch_bounds__(kWave) void rollout_uniform_kernel(RolloutArgs A) {
   __shared__ __attribute__((aligned(16))) float tile[ObsTile<N>::kFloats];
   constexpr int D = 6 * N;
@@ -87,7 +97,8 @@ __global__ __launch_bounds__(kWave) void rollout_uniform_kernel(RolloutArgs A) {
   const size_t TE = A.TE;
   float* obs_p = A.obs_traj ? A.obs_traj + L.g0 * (N * D) : nullptr;
   uint8_t* act_p = (A.act_traj && L.valid) ? A.act_traj + L.g * N : nullptr;
-  float* rew_p = (A.rew_traj && L.valid) ? A.rew_traj + L.g : nullptr;
+  constexpr int RW = PER_AGENT ? N : 1;   // rewards per env and step
+  float* rew_p = (A.rew_traj && L.valid) ? A.rew_traj + L.g * RW : nullptr;
   uint8_t* done_p = (A.done_traj && L.valid) ? A.done_traj + L.g : nullptr;
   uint32_t step = A.abs_step;
   for (int t = 0; t < A.T; ++t, ++step) {
@@ -106,10 +117,14 @@ __global__ __launch_bounds__(kWave) void rollout_uniform_kernel(RolloutArgs A) {
       for (int i = 0; i < N; ++i) act_p[i] = uint8_t(a[i]);
       act_p += TE * N;
     }
-    float r;
+    float r[RW];
     bool d;
-    transition<N>(s, a, A.ph, A.seed, L.run, L.env, step, r, d);
-    if (rew_p) { *rew_p = r; rew_p += TE; }
+    transition<N, PER_AGENT>(s, a, A.ph, A.seed, L.run, L.env, step, r, d);
+    if (rew_p) {
+#pragma unroll
+      for (int i = 0; i < RW; ++i) rew_p[i] = r[i];
+      rew_p += TE * RW;
+    }
     if (done_p) { *done_p = d ? 1 : 0; done_p += TE; }
   }
   if (A.last_obs) emit_obs<N>(s, tile, A.last_obs + L.g0 * (N * D), L.nvalid, L.lane);
@@ -181,12 +196,12 @@ __global__ __launch_bounds__(2 * kWave) void rollout_uniform_ws_kernel(RolloutAr
         const uint4 w = philox4x32_10(env, step, uint32_t(i), kTagUniformAction, A.seed, run);
         a[i] = word_to_action(w.x);
       }
-      float r;
+      float r[1];
       bool d;
       transition<N>(s, a, A.ph, A.seed, run, env, step, r, d);
       __syncthreads();  // X_t
       uint8_t* cur = buf[t & 1];
-      reinterpret_cast<float*>(cur + SB::REW_OFF)[lane] = r;
+      reinterpret_cast<float*>(cur + SB::REW_OFF)[lane] = r[0];
 #pragma unroll
       for (int i = 0; i < N; ++i) cur[SB::ACT_OFF + lane * N + i] = uint8_t(a[i]);
       cur[SB::DONE_OFF + lane] = d ? 1 : 0;
@@ -282,6 +297,10 @@ struct EnvLaunch {
                        actions, obs, reward, done);
   }
   static void rollout(const RolloutArgs& A, hipStream_t s) {
+    if (A.ph.reward_mode == 1) {  // [T][TE][N] rewards: the general kernel
+      hipLaunchKernelGGL((rollout_uniform_kernel<N, true>), env_grid(A.TE), dim3(kWave), 0, s, A);
+      return;
+    }
     if constexpr (N <= 3) {
       if (ws_eligible<N>(A)) {
         const uint32_t groups = A.TE / kWave;
@@ -290,7 +309,7 @@ struct EnvLaunch {
         return;
       }
     }
-    hipLaunchKernelGGL(rollout_uniform_kernel<N>, env_grid(A.TE), dim3(kWave), 0, s, A);
+    hipLaunchKernelGGL((rollout_uniform_kernel<N, false>), env_grid(A.TE), dim3(kWave), 0, s, A);
   }
 };
 

@@ -416,7 +416,8 @@ struct SmemF32 {
   static_assert(OFF_OBS % 16 == 0 && OFF_NEWPOS % 16 == 0, "alignment");
 };
 
-template <int N, int EB, int MINW>
+// PER_AGENT: rew_traj is [T][TE][N], the mixed per-agent reward; every lane stores its agent's.
+template <int N, int EB, int MINW, bool PER_AGENT>
 __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
                                                                           int per_run_weights, uint32_t groups,
                                                                           uint32_t groups_per_xcd) {
@@ -598,7 +599,20 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
         }
         r -= hw_sqrt(best2);
       }
-      if (rew_base) {
+      if constexpr (PER_AGENT) {
+        uint32_t overlaps = 0;
+#pragma unroll
+        for (int a = 0; a < N; ++a) {
+          if (a != i) {
+            const float dx = px - qx[a], dy = py - qy[a];
+            overlaps += fmaf(dx, dx, dy * dy) < A.ph.two_r_sq ? 1u : 0u;
+          }
+        }
+        if (rew_base) {
+          if (valid) rew_base[row_off] = mixed_reward(r, overlaps, A.ph);
+          rew_base += TE * N;
+        }
+      } else if (rew_base) {
         if (env_writer) rew_base[gc] = r;
         rew_base += TE;
       }
@@ -655,10 +669,10 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
   }
 }
 
-template <int N, int EB, int MINW>
+template <int N, int EB, int MINW, bool PER_AGENT>
 hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s) {
   using M = SmemF32<N, EB>;
-  auto kern = rollout_policy_f32_kernel<N, EB, MINW>;
+  auto kern = rollout_policy_f32_kernel<N, EB, MINW, PER_AGENT>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -690,7 +704,8 @@ hipError_t pack_impl(PolicyBuffers& pb, int R, const float* W1, const float* b1,
 template <int N>
 hipError_t launch_n(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s, const char** why) {
   const bool one_run = A.TE == A.E;
-  if (one_run || A.E % 64 == 0) return rollout_impl<N, 64, 3>(A, pb, s);
+  if (one_run || A.E % 64 == 0)
+    return A.ph.reward_mode == 1 ? rollout_impl<N, 64, 3, true>(A, pb, s) : rollout_impl<N, 64, 3, false>(A, pb, s);
   *why = "with several runs, num_envs per run must be a multiple of 64";
   return hipSuccess;
 }

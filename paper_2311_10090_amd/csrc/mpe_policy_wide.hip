@@ -178,7 +178,8 @@ __device__ __forceinline__ void policy_tile(const uint8_t* __restrict__ wsm, con
   }
 }
 
-template <int N, int H, int EB, int MINW>
+// PER_AGENT: rew_traj is [T][TE][N], the mixed per-agent reward; every lane stores its agent's.
+template <int N, int H, int EB, int MINW, bool PER_AGENT>
 __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
                                                                       int per_run_weights, uint32_t groups,
                                                                       uint32_t groups_per_xcd) {
@@ -293,6 +294,22 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
   const uint32_t row_off = uint32_t(gc) * N + i;      // index of this agent inside a time slice
   const bool env_writer = valid && i == 0;            // the lane that stores per-env outputs
   uint32_t step = A.abs_step;
+  uint32_t overlaps = 0;   // PER_AGENT: other agents this one overlapped after the latest step
+
+  // Reward of the step whose coverage distances are in dminbuf[parity]: their sum (negated) per env,
+  // or, PER_AGENT, mixed with the lane's overlap count of that step.  Advances rew_base.
+  auto store_reward = [&](int parity) {
+    if (!rew_base) return;
+    if (PER_AGENT ? valid : env_writer) {
+      const float* dm = dminbuf + parity * ROWS + el * N;
+      float r = 0.0f;
+#pragma unroll
+      for (int a = 0; a < N; ++a) r -= dm[a];
+      if constexpr (PER_AGENT) rew_base[row_off] = mixed_reward(r, overlaps, A.ph);
+      else rew_base[gc] = r;
+    }
+    rew_base += PER_AGENT ? TE * N : TE;
+  };
 
   for (int t = 0; t < A.T; ++t, ++step) {
     // ---- observation row -> trajectory, and -> bf16 B operands of layer 1 for the wave's 4 tiles
@@ -358,21 +375,22 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
     group_barrier(arrived, uint32_t(GW) * uint32_t(t + 1), lane);
 
     // reward of the previous step: sum of its N per-landmark distances
-    if (t > 0 && rew_base) {
-      if (env_writer) {
-        const float* dm = dminbuf + ((t - 1) & 1) * ROWS + el * N;
-        float r = 0.0f;
-#pragma unroll
-        for (int a = 0; a < N; ++a) r -= dm[a];
-        (rew_base - TE)[gc] = r;
-      }
-    }
-    if (rew_base) rew_base += TE;
+    if (t > 0) store_reward((t - 1) & 1);
 #pragma unroll
     for (int a = 0; a < N; ++a) {
       const float2 p = np[el * N + a];
       qx[a] = p.x;
       qy[a] = p.y;
+    }
+    if constexpr (PER_AGENT) {
+      overlaps = 0;
+#pragma unroll
+      for (int a = 0; a < N; ++a) {
+        if (a != i) {
+          const float dx = px - qx[a], dy = py - qy[a];
+          overlaps += fmaf(dx, dx, dy * dy) < A.ph.two_r_sq ? 1u : 0u;
+        }
+      }
     }
     // coverage term of landmark i: min over agents of the distance to it (post-step, pre-reset)
     {
@@ -412,13 +430,7 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
     }
   }
   group_barrier(arrived, uint32_t(GW) * uint32_t(A.T + 1), lane);  // coverage distances of the last step
-  if (A.rew_traj && env_writer) {
-    const float* dm = dminbuf + ((A.T - 1) & 1) * ROWS + el * N;
-    float r = 0.0f;
-#pragma unroll
-    for (int a = 0; a < N; ++a) r -= dm[a];
-    (rew_base - TE)[gc] = r;
-  }
+  store_reward((A.T - 1) & 1);
   if (A.last_obs) {
     float o[KIN];
     build_obs(o);
@@ -449,10 +461,10 @@ hipError_t pack_impl(PolicyBuffers& pb, int R, const float* W1, const float* b1,
   return hipGetLastError();
 }
 
-template <int N, int H, int EB, int MINW>
+template <int N, int H, int EB, int MINW, bool PER_AGENT>
 hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s) {
   using M = Smem<N, H, EB>;
-  auto kern = rollout_policy_kernel<N, H, EB, MINW>;
+  auto kern = rollout_policy_kernel<N, H, EB, MINW, PER_AGENT>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -495,7 +507,8 @@ hipError_t launch_rollout_policy_wide(int N, int H, const RolloutArgs& A, const 
       *why = "with several runs, num_envs per run must be a multiple of the block's env count";  \
       return hipSuccess;                                                                         \
     }                                                                                            \
-    return rollout_impl<N_, H_, EB_, MW_>(A, pb, s);                                       \
+    return A.ph.reward_mode == 1 ? rollout_impl<N_, H_, EB_, MW_, true>(A, pb, s)                \
+                                 : rollout_impl<N_, H_, EB_, MW_, false>(A, pb, s);              \
   }
   MPE_WIDE_CASES(X)
 #undef X

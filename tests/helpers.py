@@ -14,20 +14,22 @@ EPISODE_ATOL = 1e-4
 ACTION_AGREEMENT = 0.9999
 
 
-def oracle_config(E, N, R=1, H=0, wd=0, env_offset=0, run_offset=0, max_ep=synth.MAX_EPISODE_STEPS, **phys):
+def oracle_config(E, N, R=1, H=0, wd=0, env_offset=0, run_offset=0, max_ep=synth.MAX_EPISODE_STEPS,
+                  reward_mode=0, local_ratio=0.5, **phys):
     from oracle import OracleConfig
     p = synth.physics_f32()
     p.update({k: float(np.float32(v)) for k, v in phys.items()})
     return OracleConfig(num_envs=E, num_agents=N, num_landmarks=N, num_runs=R, max_episode_steps=max_ep,
-                        hidden=H, weight_dtype=wd, env_offset=env_offset, run_offset=run_offset, **p)
+                        hidden=H, weight_dtype=wd, env_offset=env_offset, run_offset=run_offset,
+                        reward_mode=reward_mode, local_ratio=float(np.float32(local_ratio)), **p)
 
 
-def gpu_config(E, N, R=1, H=0, wd=0, max_ep=synth.MAX_EPISODE_STEPS, **phys):
+def gpu_config(E, N, R=1, H=0, wd=0, max_ep=synth.MAX_EPISODE_STEPS, reward_mode=0, local_ratio=0.5, **phys):
     from paper_2311_10090_amd.binding import MpeConfig
     p = dict(synth.PHYSICS)
     p.update(phys)
     return MpeConfig(num_envs=E, num_agents=N, num_landmarks=N, num_runs=R, max_episode_steps=max_ep,
-                     hidden=H, weight_dtype=wd, **p)
+                     hidden=H, weight_dtype=wd, reward_mode=reward_mode, local_ratio=local_ratio, **p)
 
 
 def state_to_gpu(pos_a, vel_a, pos_l, ep, device="cuda:0"):

@@ -34,8 +34,8 @@ def test_header_symbols_are_exported(lib):
 
 
 def test_config_struct_matches_header():
-    # 5 int32 + 8 float + 2 int32, no padding
-    assert C.sizeof(binding._CConfig) == 15 * 4
+    # 5 int32 + 8 float + 3 int32 + 1 float, no padding
+    assert C.sizeof(binding._CConfig) == 17 * 4
     text = open(os.path.join(ROOT, "include", "mpe.h")).read()
     body = re.search(r"typedef struct \{(.*?)\} mpe_config;", text, flags=re.S).group(1)
     body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
@@ -50,6 +50,7 @@ def test_config_struct_matches_header():
     dict(num_landmarks=2), dict(max_episode_steps=0), dict(dt=0.0), dict(mass=-1.0),
     dict(contact_margin=0.0), dict(damping=1.5), dict(hidden=32), dict(weight_dtype=7),
     dict(dt=float("nan")), dict(accel=float("inf")), dict(num_envs=1 << 20, num_runs=1 << 11),
+    dict(reward_mode=2), dict(reward_mode=1, local_ratio=1.5), dict(reward_mode=1, local_ratio=float("nan")),
 ])
 def test_bad_config_is_rejected_on_host(lib, bad):
     cfg = MpeConfig(**bad).to_c()
