@@ -99,6 +99,7 @@ struct Oracle {
   std::vector<double> pos_a, vel_a, pos_l;
   std::vector<int32_t> ep_step;
   Policy pol;
+  Policy critic;   // same shape with ONE output: W3[H][1], b3[1]  (R-13)
   int nthreads = 1;
 };
 
@@ -271,15 +272,15 @@ void step_env(Oracle& o, int run, int env, uint32_t s, const uint8_t* act /* [N]
 // h2 are rounded to bf16 where they enter a layer; products, sums, biases and tanh stay
 // in the wide type.
 // ---------------------------------------------------------------------------------
-void policy_logits(const Oracle& o, int run, const double* ob, double* z /* [5] */) {
+void mlp_forward(const Oracle& o, const Policy& P, int nout, int run, const double* ob, double* z /* [nout] */) {
   const int D = o.D, H = o.H;
   const bool bf = o.cfg.weight_dtype == 1;
-  const double* W1 = &o.pol.W1[size_t(run) * D * H];
-  const double* b1 = &o.pol.b1[size_t(run) * H];
-  const double* W2 = &o.pol.W2[size_t(run) * H * H];
-  const double* b2 = &o.pol.b2[size_t(run) * H];
-  const double* W3 = &o.pol.W3[size_t(run) * H * NUM_ACTIONS];
-  const double* b3 = &o.pol.b3[size_t(run) * NUM_ACTIONS];
+  const double* W1 = &P.W1[size_t(run) * D * H];
+  const double* b1 = &P.b1[size_t(run) * H];
+  const double* W2 = &P.W2[size_t(run) * H * H];
+  const double* b2 = &P.b2[size_t(run) * H];
+  const double* W3 = &P.W3[size_t(run) * H * nout];
+  const double* b3 = &P.b3[size_t(run) * nout];
   std::vector<double> x(D), h1(H), h2(H);
   for (int k = 0; k < D; ++k) x[k] = bf ? round_to_bf16(ob[k]) : ob[k];
   for (int j = 0; j < H; ++j) {
@@ -294,11 +295,39 @@ void policy_logits(const Oracle& o, int run, const double* ob, double* z /* [5] 
     h2[j] = std::tanh(acc + b2[j]);
   }
   if (bf) for (int j = 0; j < H; ++j) h2[j] = round_to_bf16(h2[j]);
-  for (int a = 0; a < NUM_ACTIONS; ++a) {
+  for (int a = 0; a < nout; ++a) {
     double acc = 0.0;
-    for (int k = 0; k < H; ++k) acc += h2[k] * W3[size_t(k) * NUM_ACTIONS + a];
+    for (int k = 0; k < H; ++k) acc += h2[k] * W3[size_t(k) * nout + a];
     z[a] = acc + b3[a];
   }
+}
+
+void policy_logits(const Oracle& o, int run, const double* ob, double* z /* [5] */) {
+  mlp_forward(o, o.pol, NUM_ACTIONS, run, ob, z);
+}
+
+// ---------------------------------------------------------------------------------
+// R-13  What an actor-critic learner (the paper's IPPO / MAPPO, Sec. 3.2; App. G: feed-forward
+// networks of two tanh layers of width 64) takes from a rollout besides obs, action, reward and
+// done: the log-probability of the sampled action under the categorical policy,
+//     log pi(a | o) = z_a - ln sum_k exp(z_k),
+// and the critic's value of the observation acted on.  The critic is a second network of the
+// same shape with one output (the paper does not print the critic; this is the reading taken),
+// fed the agent's own observation.
+// ---------------------------------------------------------------------------------
+void log_probs(const double* z, double* lp /* [5] */) {
+  double m = z[0];
+  for (int k = 1; k < NUM_ACTIONS; ++k) m = std::max(m, z[k]);
+  double sum = 0.0;
+  for (int k = 0; k < NUM_ACTIONS; ++k) sum += std::exp(z[k] - m);
+  const double lse = m + std::log(sum);
+  for (int k = 0; k < NUM_ACTIONS; ++k) lp[k] = z[k] - lse;
+}
+
+double critic_value(const Oracle& o, int run, const double* ob) {
+  double v;
+  mlp_forward(o, o.critic, 1, run, ob, &v);
+  return v;
 }
 
 // ---------------------------------------------------------------------------------
@@ -337,13 +366,18 @@ int uniform_action(uint32_t seed, uint32_t run, uint32_t env, uint32_t s, uint32
 }
 
 void choose_actions(const Oracle& o, int run, int env, uint32_t s, const double* obs /* [N][D] */,
-                    uint8_t* act /* [N] */) {
+                    uint8_t* act /* [N] */, double* logp = nullptr /* [N], needs a policy */) {
   for (int i = 0; i < o.N; ++i) {
     if (o.pol.set) {
       double z[NUM_ACTIONS];
       policy_logits(o, run, obs + size_t(i) * o.D, z);
       act[i] = uint8_t(gumbel_max_action(o.seed, uint32_t(o.cfg.run_offset + run),
                                          uint32_t(o.cfg.env_offset + env), s, uint32_t(i), z));
+      if (logp) {
+        double lp[NUM_ACTIONS];
+        log_probs(z, lp);
+        logp[i] = lp[act[i]];
+      }
     } else {
       act[i] = uint8_t(uniform_action(o.seed, uint32_t(o.cfg.run_offset + run),
                                       uint32_t(o.cfg.env_offset + env), s, uint32_t(i)));
@@ -354,10 +388,13 @@ void choose_actions(const Oracle& o, int run, int env, uint32_t s, const double*
 // ---------------------------------------------------------------------------------
 // R-11  Rollout of T steps: for t = 0..T-1 record the current observation, choose the
 // actions (policy + Gumbel-max, or uniform), record them, apply one transition, record
-// reward and done.  After the loop last_obs is the current observation.
+// reward and done.  After the loop last_obs is the current observation.  Actor-critic outputs
+// (R-13, all nullable): logp_traj, value_traj [T][TE][N] and last_value [TE][N], the value of
+// last_obs.
 // ---------------------------------------------------------------------------------
 void rollout_range(Oracle& o, size_t g0, size_t g1, int T, double* obs_traj, uint8_t* act_traj,
-                   double* rew_traj, uint8_t* done_traj, double* last_obs) {
+                   double* rew_traj, uint8_t* done_traj, double* last_obs, double* logp_traj = nullptr,
+                   double* value_traj = nullptr, double* last_value = nullptr) {
   const size_t TE = size_t(o.R) * o.E;
   const size_t row = size_t(o.N) * o.D;
   std::vector<double> ob(row);
@@ -370,14 +407,23 @@ void rollout_range(Oracle& o, size_t g0, size_t g1, int T, double* obs_traj, uin
       const uint32_t s = o.abs_step + uint32_t(t);
       observe_env(o, ge, ob.data());
       if (obs_traj) std::memcpy(obs_traj + (size_t(t) * TE + ge) * row, ob.data(), row * sizeof(double));
-      choose_actions(o, run, env, s, ob.data(), act.data());
+      std::vector<double> lp(o.N);
+      choose_actions(o, run, env, s, ob.data(), act.data(), logp_traj ? lp.data() : nullptr);
       if (act_traj) std::memcpy(act_traj + (size_t(t) * TE + ge) * o.N, act.data(), o.N);
+      if (logp_traj) std::memcpy(logp_traj + (size_t(t) * TE + ge) * o.N, lp.data(), o.N * sizeof(double));
+      if (value_traj)
+        for (int i = 0; i < o.N; ++i)
+          value_traj[(size_t(t) * TE + ge) * o.N + i] = critic_value(o, run, ob.data() + size_t(i) * o.D);
       uint8_t d;
       step_env(o, run, env, s, act.data(), r.data(), &d);
       if (rew_traj) std::memcpy(rew_traj + (size_t(t) * TE + ge) * RW, r.data(), RW * sizeof(double));
       if (done_traj) done_traj[size_t(t) * TE + ge] = d;
     }
     if (last_obs) observe_env(o, ge, last_obs + ge * row);
+    if (last_value) {
+      observe_env(o, ge, ob.data());
+      for (int i = 0; i < o.N; ++i) last_value[ge * o.N + i] = critic_value(o, run, ob.data() + size_t(i) * o.D);
+    }
   }
 }
 
@@ -508,6 +554,43 @@ int orc_set_policy(void* h, const float* W1, const float* b1, const float* W2, c
   return 0;
 }
 
+// Critic weights as float32, [R] leading dimension: V1[D][H] c1[H] V2[H][H] c2[H] V3[H] c3[1].
+// All six null => no critic.
+int orc_set_critic(void* h, const float* V1, const float* c1, const float* V2, const float* c2,
+                   const float* V3, const float* c3) {
+  if (!h) return fail("null handle");
+  Oracle& o = *static_cast<Oracle*>(h);
+  if (!V1 && !c1 && !V2 && !c2 && !V3 && !c3) { o.critic.set = false; return 0; }
+  if (!V1 || !c1 || !V2 || !c2 || !V3 || !c3) return fail("all six critic arrays or none");
+  if (o.H < 1) return fail("hidden width not set");
+  const bool bf = o.cfg.weight_dtype == 1;
+  auto load = [&](std::vector<double>& dst, const float* src, size_t n, bool round_it) {
+    dst.resize(n);
+    for (size_t i = 0; i < n; ++i) dst[i] = round_it ? round_to_bf16(double(src[i])) : double(src[i]);
+  };
+  const size_t R = o.R, D = o.D, H = o.H;
+  load(o.critic.W1, V1, R * D * H, bf);
+  load(o.critic.b1, c1, R * H, false);
+  load(o.critic.W2, V2, R * H * H, bf);
+  load(o.critic.b2, c2, R * H, false);
+  load(o.critic.W3, V3, R * H, bf);
+  load(o.critic.b3, c3, R, false);
+  o.critic.set = true;
+  return 0;
+}
+
+// Critic values of `run` for n observation rows [n][D] -> [n].
+int orc_value(void* h, int run, const double* obs, int n, double* values) {
+  Oracle& o = *static_cast<Oracle*>(h);
+  if (!o.critic.set) return fail("no critic");
+  if (run < 0 || run >= o.R) return fail("bad run");
+  for (int r = 0; r < n; ++r) values[r] = critic_value(o, run, obs + size_t(r) * o.D);
+  return 0;
+}
+
+// log pi(k | logits) for all five actions.
+void orc_log_probs(const double* logits, double* lp) { log_probs(logits, lp); }
+
 // Logits of the policy of `run` for n observation rows [n][D] -> [n][5].
 int orc_policy_logits(void* h, int run, const double* obs, int n, double* logits) {
   Oracle& o = *static_cast<Oracle*>(h);
@@ -548,6 +631,29 @@ int orc_rollout(void* h, int32_t T, double* obs_traj, uint8_t* act_traj, double*
     }
     for (auto& t : th) t.join();
   }
+  o.abs_step += uint32_t(T);
+  return 0;
+}
+
+// Actor-critic rollout: orc_rollout plus logp_traj, value_traj [T][R*E][N] and last_value [R*E][N].
+int orc_rollout_ac(void* h, int32_t T, double* obs_traj, uint8_t* act_traj, double* logp_traj,
+                   double* value_traj, double* rew_traj, uint8_t* done_traj, double* last_obs,
+                   double* last_value) {
+  if (!h || T < 1) return fail("bad argument");
+  Oracle& o = *static_cast<Oracle*>(h);
+  if (!o.was_reset) return fail("rollout before reset");
+  if (!o.pol.set || !o.critic.set) return fail("actor-critic rollout needs a policy and a critic");
+  const size_t TE = size_t(o.R) * o.E;
+  const int nt = int(std::max<size_t>(1, std::min<size_t>(size_t(o.nthreads), TE)));
+  std::vector<std::thread> th;
+  for (int k = 0; k < nt; ++k) {
+    const size_t g0 = TE * k / nt, g1 = TE * (k + 1) / nt;
+    th.emplace_back([&, g0, g1] {
+      rollout_range(o, g0, g1, T, obs_traj, act_traj, rew_traj, done_traj, last_obs, logp_traj, value_traj,
+                    last_value);
+    });
+  }
+  for (auto& t : th) t.join();
   o.abs_step += uint32_t(T);
   return 0;
 }

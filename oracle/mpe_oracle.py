@@ -89,6 +89,11 @@ def _load():
         _lib.orc_get_state.argtypes = [C.c_void_p] + [C.c_void_p] * 5
         _lib.orc_set_state.argtypes = [C.c_void_p] + [C.c_void_p] * 4 + [C.c_uint32, C.c_uint32]
         _lib.orc_philox4x32_10.argtypes = [C.c_void_p] * 3
+        _lib.orc_set_critic.argtypes = [C.c_void_p] + [C.c_void_p] * 6
+        _lib.orc_value.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p]
+        _lib.orc_log_probs.argtypes = [C.c_void_p, C.c_void_p]
+        _lib.orc_log_probs.restype = None
+        _lib.orc_rollout_ac.argtypes = [C.c_void_p, C.c_int32] + [C.c_void_p] * 8
     return _lib
 
 
@@ -117,6 +122,14 @@ def gumbel_max_action(seed, run, env, step, agent, logits) -> int:
 
 def uniform_action(seed, run, env, step, agent) -> int:
     return int(_load().orc_uniform_action(seed, run, env, step, agent))
+
+
+def log_probs(logits) -> np.ndarray:
+    z = np.ascontiguousarray(logits, dtype=np.float64)
+    assert z.shape == (5,)
+    out = np.empty(5, dtype=np.float64)
+    _load().orc_log_probs(_ptr(z), _ptr(out))
+    return out
 
 
 def round_to_bf16(x: float) -> float:
@@ -173,6 +186,36 @@ class Oracle:
             a = np.ascontiguousarray(a, dtype=np.float32).reshape(s)
             arrs.append(a)
         _check(self.lib.orc_set_policy(self.h, *[_ptr(a) for a in arrs]))
+
+    def set_critic(self, V1, c1, V2, c2, V3, c3):
+        """Critic of the actor-critic rollout: same shape as the policy with one output."""
+        if V1 is None:
+            _check(self.lib.orc_set_critic(self.h, None, None, None, None, None, None))
+            return
+        H = self.cfg.hidden
+        shapes = [(self.R, self.D, H), (self.R, H), (self.R, H, H), (self.R, H), (self.R, H), (self.R,)]
+        arrs = [np.ascontiguousarray(a, dtype=np.float32).reshape(s) for a, s in zip((V1, c1, V2, c2, V3, c3), shapes)]
+        _check(self.lib.orc_set_critic(self.h, *[_ptr(a) for a in arrs]))
+
+    def value(self, obs_rows: np.ndarray, run: int = 0) -> np.ndarray:
+        o = np.ascontiguousarray(obs_rows, dtype=np.float64).reshape(-1, self.D)
+        out = np.empty(o.shape[0], dtype=np.float64)
+        _check(self.lib.orc_value(self.h, run, _ptr(o), o.shape[0], _ptr(out)))
+        return out
+
+    def rollout_ac(self, T: int):
+        """Returns obs, act, logp, value, rew, done, last_obs, last_value."""
+        obs = np.empty((T, self.TE, self.N, self.D), dtype=np.float64)
+        act = np.empty((T, self.TE, self.N), dtype=np.uint8)
+        logp = np.empty((T, self.TE, self.N), dtype=np.float64)
+        val = np.empty((T, self.TE, self.N), dtype=np.float64)
+        rew = np.empty((T,) + self.rew_shape, dtype=np.float64)
+        done = np.empty((T, self.TE), dtype=np.uint8)
+        last = np.empty((self.TE, self.N, self.D), dtype=np.float64)
+        lastv = np.empty((self.TE, self.N), dtype=np.float64)
+        _check(self.lib.orc_rollout_ac(self.h, T, _ptr(obs), _ptr(act), _ptr(logp), _ptr(val), _ptr(rew),
+                                       _ptr(done), _ptr(last), _ptr(lastv)))
+        return obs, act, logp, val, rew, done, last, lastv
 
     def policy_logits(self, obs_rows: np.ndarray, run: int = 0) -> np.ndarray:
         o = np.ascontiguousarray(obs_rows, dtype=np.float64).reshape(-1, self.D)

@@ -88,6 +88,24 @@ def policy_weights_with_bias(seed: int, num_runs: int, obs_dim: int, hidden: int
     return W1, b1, W2, b2, W3, b3
 
 
+def critic_weights(seed: int, num_runs: int, obs_dim: int, hidden: int):
+    """Per-run critic weights (same shape as the policy, one output), N(0, 1/fan_in), biases
+    U(-0.5, 0.5), float32: V1[R][D][H], c1[R][H], V2[R][H][H], c2[R][H], V3[R][H], c3[R]."""
+    V1 = np.empty((num_runs, obs_dim, hidden), np.float32)
+    V2 = np.empty((num_runs, hidden, hidden), np.float32)
+    V3 = np.empty((num_runs, hidden), np.float32)
+    for r in range(num_runs):
+        g = np.random.Generator(np.random.PCG64(seed + 104729 + r))
+        V1[r] = g.standard_normal((obs_dim, hidden)) / np.sqrt(obs_dim)
+        V2[r] = g.standard_normal((hidden, hidden)) / np.sqrt(hidden)
+        V3[r] = g.standard_normal(hidden) / np.sqrt(hidden)
+    g = np.random.Generator(np.random.PCG64(seed + 15485863))
+    c1 = g.uniform(-0.5, 0.5, (num_runs, hidden)).astype(np.float32)
+    c2 = g.uniform(-0.5, 0.5, (num_runs, hidden)).astype(np.float32)
+    c3 = g.uniform(-0.5, 0.5, (num_runs,)).astype(np.float32)
+    return V1, c1, V2, c2, V3, c3
+
+
 def random_actions(seed: int, shape) -> np.ndarray:
     g = np.random.Generator(np.random.PCG64(seed))
     return g.integers(0, NUM_ACTIONS, size=shape, dtype=np.uint8)

@@ -7,7 +7,7 @@ from decimal import Decimal, getcontext
 import numpy as np
 import pytest
 
-from oracle import Oracle, OracleConfig, gumbel_max_action, philox4x32_10, round_to_bf16, uniform_action
+from oracle import Oracle, OracleConfig, gumbel_max_action, log_probs, philox4x32_10, round_to_bf16, uniform_action
 from tests.conftest import read_golden
 
 
@@ -594,3 +594,90 @@ def test_policy_rollout_actions_are_sampler_of_logits_of_recorded_obs():
         for e in range(E):
             for i in range(N):
                 assert act_t[t, e, i] == gumbel_max_action(13, 0, e, t, i, logits[e, i])
+
+
+# ------------------------------------------------- critic value and log-probability (R-13)
+def test_critic_matches_numpy_float64_chain_and_closed_forms():
+    from paper_2311_10090_amd.synth import critic_weights
+    for N, H in ((3, 64), (10, 128)):
+        D = 6 * N
+        w = critic_weights(3, 2, D, H)
+        o = Oracle(OracleConfig(num_envs=1, num_agents=N, num_landmarks=N, num_runs=2, hidden=H))
+        o.set_critic(*w)
+        x = np.random.default_rng(1).uniform(-2, 2, (40, D))
+        for run in range(2):
+            V1, c1, V2, c2, V3, c3 = [a[run] for a in w]
+            ref = _np_mlp(x, V1, c1, V2, c2, V3[:, None], c3)[:, 0]
+            np.testing.assert_allclose(o.value(x, run), ref, rtol=1e-12, atol=1e-13)
+    # all weights zero: the value is the last bias; first layer zero: a constant of the other layers
+    D, H = 18, 64
+    z = lambda *s: np.zeros(s, np.float32)
+    o = Oracle(OracleConfig(num_envs=1, hidden=H))
+    o.set_critic(z(1, D, H), z(1, H), z(1, H, H), z(1, H), z(1, H), np.array([0.375], np.float32))
+    assert o.value(np.ones((1, D)))[0] == 0.375
+    c1 = np.full((1, H), 0.25, np.float32)
+    V2 = np.full((1, H, H), 1.0 / H, np.float32)
+    V3 = np.full((1, H), 2.0 / H, np.float32)
+    o.set_critic(z(1, D, H), c1, V2, z(1, H), V3, z(1))
+    expect = 2.0 * math.tanh(math.tanh(0.25))
+    assert o.value(np.random.default_rng(0).normal(size=(1, D)))[0] == pytest.approx(expect, abs=1e-14)
+
+
+def test_log_probs_match_scipy_and_normalise():
+    from scipy.special import log_softmax
+    g = np.random.default_rng(2)
+    for _ in range(200):
+        z = g.normal(scale=3.0, size=5)
+        lp = log_probs(z)
+        np.testing.assert_allclose(lp, log_softmax(z), rtol=0, atol=1e-14)
+        assert abs(np.exp(lp).sum() - 1.0) < 1e-14
+        np.testing.assert_allclose(log_probs(z + 123.0), lp, atol=1e-12)      # shift invariance
+    np.testing.assert_allclose(log_probs(np.zeros(5)), -math.log(5.0), atol=1e-15)
+    lp = log_probs(np.array([1000.0, 0.0, -1000.0, 0.0, 0.0]))                # no overflow
+    assert lp[0] == pytest.approx(0.0, abs=1e-300) and lp[1] == -1000.0 and lp[2] == -2000.0
+
+
+def test_actor_critic_rollout_outputs_are_functions_of_the_recorded_rollout():
+    from paper_2311_10090_amd.synth import critic_weights, policy_weights_with_bias
+    from scipy.special import log_softmax
+    E, N, R, H, T = 5, 3, 2, 64, 30
+    cfg = OracleConfig(num_envs=E, num_agents=N, num_landmarks=N, num_runs=R, hidden=H)
+    a, b = Oracle(cfg, threads=3), Oracle(cfg)
+    pw, cw = policy_weights_with_bias(1, R, 6 * N, H), critic_weights(1, R, 6 * N, H)
+    for o in (a, b):
+        o.set_policy(*pw)
+        o.set_critic(*cw)
+        o.reset(4)
+    obs, act, logp, val, rew, done, last, lastv = a.rollout_ac(T)
+    plain = b.rollout(T)
+    for x, y in zip((obs, act, rew, done, last), plain):      # the extra outputs do not change the rollout
+        assert np.array_equal(x, y)
+    for run in range(R):
+        sl = slice(run * E, (run + 1) * E)
+        z = a.policy_logits(obs[:, sl].reshape(-1, 6 * N), run)
+        lp = log_softmax(z, axis=1)[np.arange(z.shape[0]), act[:, sl].reshape(-1)]
+        np.testing.assert_allclose(logp[:, sl].reshape(-1), lp, rtol=0, atol=1e-13)
+        np.testing.assert_array_equal(val[:, sl].reshape(-1), a.value(obs[:, sl].reshape(-1, 6 * N), run))
+        np.testing.assert_array_equal(lastv[sl].reshape(-1), a.value(last[sl].reshape(-1, 6 * N), run))
+    assert (logp < 0).all() and logp.min() > -20
+    with pytest.raises(RuntimeError):
+        o2 = Oracle(cfg)
+        o2.set_policy(*pw)
+        o2.reset(0)
+        o2.rollout_ac(2)          # no critic set
+
+
+def test_bf16_critic_rounds_like_the_policy():
+    from paper_2311_10090_amd.synth import critic_weights
+    N, H = 10, 128
+    D = 6 * N
+    w = critic_weights(5, 1, D, H)
+    o = Oracle(OracleConfig(num_envs=1, num_agents=N, num_landmarks=N, hidden=H, weight_dtype=1))
+    o.set_critic(*w)
+    rb = np.vectorize(round_to_bf16)
+    x = np.random.default_rng(3).uniform(-2, 2, (10, D))
+    V1, c1, V2, c2, V3, c3 = [a[0].astype(np.float64) for a in w]
+    h1 = np.tanh(rb(x) @ rb(V1) + c1)
+    h2 = np.tanh(rb(h1) @ rb(V2) + c2)
+    ref = rb(h2) @ rb(V3) + c3
+    np.testing.assert_allclose(o.value(x), ref, rtol=1e-12, atol=1e-13)
