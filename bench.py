@@ -167,6 +167,31 @@ def main():
         env3.close()
         del b3
 
+    # actor-critic rollout on the same shape (adds log-prob, value and bootstrap value outputs)
+    ac = {}
+    if wl.weight_dtype == 0 and wl.num_runs == 1:
+        k = max(3, args.steps // 3)
+        env4 = MpeEnv(Hp.gpu_config(wl.num_envs, N, wl.num_runs, H, 0))
+        env4.set_policy(*Hp.to_dev(weights))
+        env4.set_critic(*Hp.to_dev(synth.critic_weights(0, wl.num_runs, D, H)))
+        env4.reset(seed)
+        b4 = env4.empty_traj_ac(T)
+        for _ in range(2):
+            env4.rollout_ac(T, *b4)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(k):
+            env4.rollout_ac(T, *b4)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / k
+        ac = {"agent_steps_per_s": agent_steps / dt, "ms_per_rollout": dt * 1e3,
+              "flop_per_agent_step": flops_per_agent_step(D, H) + flops_per_agent_step(D, H, 1),
+              "fp32_equivalent_TFLOPs": (flops_per_agent_step(D, H) + flops_per_agent_step(D, H, 1)) * agent_steps / dt / 1e12,
+              "bytes_per_env_step": bytes_per_env_step(N, D) + 8 * N,
+              "note": "mpe_rollout_ac: policy + critic (18->64->64->1), 256-env blocks of four sync groups"}
+        env4.close()
+        del b4
+
     out = {
         "metric": "agent-steps/sec fused MPE rollout @65,536 envs, 1 MI355X; % HBM roofline",
         "value": value,
@@ -213,6 +238,7 @@ def main():
                          "algorithmic_bytes": bytes_per_env_step(N, D) * TE * T},
         },
         "mixed_reward": mixed,
+        "actor_critic": ac,
         "single_step": {"us_per_mpe_step_call": step_us, "env_steps_per_s": TE / (step_us * 1e-6),
                         "note": "back-to-back mpe_step calls with resident actions; 352 B per env-step"},
         "paper_context": {"mpe_simple_spread_steps_per_s": {"original_cpu_1env_epyc7763": 8.3e4,

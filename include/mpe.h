@@ -134,6 +134,27 @@ int mpe_set_policy(mpe_env* env, const float* W1, const float* b1, const float* 
 int mpe_rollout(mpe_env* env, int32_t T, float* obs_traj, uint8_t* act_traj, float* rew_traj,
                 uint8_t* done_traj, float* last_obs, void* stream);
 
+/* Install (or with all six NULL, remove) the critic used by mpe_rollout_ac: a second network of
+ * the policy's shape with ONE output, fed the agent's own observation (the actor-critic pair of
+ * the paper's IPPO, Sec. 3.2; App. G: two tanh layers of width 64):
+ *   value = V3^T tanh(V2^T tanh(V1^T obs + c1) + c2) + c3
+ * V1 [R][D][H], c1 [R][H], V2 [R][H][H], c2 [R][H], V3 [R][H], c3 [R], fp32 device pointers;
+ * copied as in mpe_set_policy.  Built for the fp32 shapes (hidden 64, 1..3 agents); MPE_EINVAL
+ * otherwise. */
+int mpe_set_critic(mpe_env* env, const float* V1, const float* c1, const float* V2,
+                   const float* c2, const float* V3, const float* c3, void* stream);
+
+/* mpe_rollout plus what an actor-critic learner takes from a rollout: for every step and agent
+ * the log-probability of the sampled action, log pi(a|obs) = z_a - ln sum_k exp(z_k), and the
+ * critic's value of the observation acted on; and the value of the observation after the last
+ * step (the bootstrap value).
+ * logp_traj, value_traj [T][TE][N] fp32, last_value [TE][N] fp32; the other arrays as in
+ * mpe_rollout.  Any of the eight may be NULL.  Needs a policy and a critic (MPE_ESTATE if one is
+ * missing); with several runs num_envs must be a multiple of 256 (MPE_EINVAL otherwise). */
+int mpe_rollout_ac(mpe_env* env, int32_t T, float* obs_traj, uint8_t* act_traj, float* logp_traj,
+                   float* value_traj, float* rew_traj, uint8_t* done_traj, float* last_obs,
+                   float* last_value, void* stream);
+
 /* Copy the state out / in (device to device, on `stream`).  Layouts: pos_a, vel_a
  * [2][N][TE], pos_l [2][L][TE] fp32 (coordinate-major, env fastest), ep_step [TE] int32.
  * Output pointers of mpe_get_state may be NULL individually; abs_step is a HOST pointer

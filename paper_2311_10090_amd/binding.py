@@ -21,7 +21,8 @@ REWARD_SHARED, REWARD_MIXED = 0, 1
 NUM_ACTIONS = 5
 
 EXPORTS = ("mpe_create", "mpe_destroy", "mpe_obs_dim", "mpe_reset", "mpe_step", "mpe_set_policy",
-           "mpe_rollout", "mpe_get_state", "mpe_set_state", "mpe_last_error")
+           "mpe_rollout", "mpe_set_critic", "mpe_rollout_ac", "mpe_get_state", "mpe_set_state",
+           "mpe_last_error")
 
 
 class MpeError(RuntimeError):
@@ -175,6 +176,26 @@ class MpeEnv:
                                         _ptr(rew_traj, torch.float32), _ptr(done_traj, torch.uint8),
                                         _ptr(last_obs, torch.float32), _stream()))
         return obs_traj, act_traj, rew_traj, done_traj, last_obs
+
+    def set_critic(self, V1=None, c1=None, V2=None, c2=None, V3=None, c3=None):
+        args = [_ptr(a, torch.float32) for a in (V1, c1, V2, c2, V3, c3)]
+        with torch.cuda.device(self.device):
+            _check(self.lib.mpe_set_critic(self.h, *args, _stream()))
+
+    def empty_traj_ac(self, T):
+        """obs, act, logp, value, rew, done, last_obs, last_value buffers of mpe_rollout_ac."""
+        obs, act, rew, done, last = self.empty_traj(T)
+        per_agent = lambda *lead: torch.empty(lead + (self.TE, self.N), dtype=torch.float32, device=self.device)
+        return obs, act, per_agent(T), per_agent(T), rew, done, last, per_agent()
+
+    def rollout_ac(self, T: int, obs_traj=None, act_traj=None, logp_traj=None, value_traj=None, rew_traj=None,
+                   done_traj=None, last_obs=None, last_value=None):
+        with torch.cuda.device(self.device):
+            _check(self.lib.mpe_rollout_ac(self.h, T, _ptr(obs_traj, torch.float32), _ptr(act_traj, torch.uint8),
+                                           _ptr(logp_traj, torch.float32), _ptr(value_traj, torch.float32),
+                                           _ptr(rew_traj, torch.float32), _ptr(done_traj, torch.uint8),
+                                           _ptr(last_obs, torch.float32), _ptr(last_value, torch.float32), _stream()))
+        return obs_traj, act_traj, logp_traj, value_traj, rew_traj, done_traj, last_obs, last_value
 
     def get_state(self):
         """Returns pos_a, vel_a, pos_l ([2][N][TE] fp32), ep_step ([TE] int32) tensors and abs_step."""

@@ -5,6 +5,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <initializer_list>
 #include <new>
 
 #include "mpe_launch.h"
@@ -22,6 +23,8 @@ struct mpe_env {
   uint32_t abs_step = 0;
   PolicyBuffers pol{};
   bool has_policy = false;
+  PolicyBuffers critic{};
+  bool has_critic = false;
 };
 
 namespace {
@@ -132,6 +135,7 @@ int mpe_destroy(mpe_env* e) {
   (void)hipFree(e->st.pos_l);
   (void)hipFree(e->st.ep_step);
   free_policy(e->pol);
+  free_policy(e->critic);
   delete e;
   return MPE_OK;
 }
@@ -217,6 +221,65 @@ int mpe_rollout(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, float
   } else {
     launch_rollout_uniform(e->N, A, static_cast<hipStream_t>(stream));
   }
+  MPE_HIP(hipGetLastError());
+  e->abs_step += uint32_t(T);
+  return MPE_OK;
+}
+
+int mpe_set_critic(mpe_env* e, const float* V1, const float* c1, const float* V2, const float* c2,
+                   const float* V3, const float* c3, void* stream) {
+  if (!e) return fail(MPE_EINVAL, "mpe_set_critic: NULL handle");
+  const int given = (V1 != nullptr) + (c1 != nullptr) + (V2 != nullptr) + (c2 != nullptr) +
+                    (V3 != nullptr) + (c3 != nullptr);
+  if (given == 0) {
+    e->has_critic = false;
+    return MPE_OK;
+  }
+  if (given != 6) return fail(MPE_EINVAL, "mpe_set_critic: pass all six arrays or none");
+  if (e->cfg.weight_dtype != MPE_WEIGHTS_FP32 || !f32_supported(e->N, e->H))
+    return fail(MPE_EINVAL, "mpe_set_critic: unsupported shape: the actor-critic rollout is built for "
+                            "fp32 weights, hidden 64 and 1..3 agents");
+  hipError_t err = pack_policy_f32(e->critic, e->N, int(e->R), V1, c1, V2, c2, V3, c3, 1,
+                                   static_cast<hipStream_t>(stream));
+  if (err != hipSuccess) return fail(MPE_EHIP, "mpe_set_critic: %s", hipGetErrorString(err));
+  e->has_critic = true;
+  return MPE_OK;
+}
+
+int mpe_rollout_ac(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, float* logp_traj,
+                   float* value_traj, float* rew_traj, uint8_t* done_traj, float* last_obs,
+                   float* last_value, void* stream) {
+  if (!e) return fail(MPE_EINVAL, "mpe_rollout_ac: NULL handle");
+  if (T < 1) return fail(MPE_EINVAL, "mpe_rollout_ac: T must be >= 1 (got %d)", T);
+  if (!e->ready) return fail(MPE_ESTATE, "mpe_rollout_ac: call mpe_reset or mpe_set_state first");
+  if (!e->has_policy || !e->has_critic)
+    return fail(MPE_ESTATE, "mpe_rollout_ac: needs mpe_set_policy and mpe_set_critic first");
+  if (e->cfg.weight_dtype != MPE_WEIGHTS_FP32 || !f32_supported(e->N, e->H))
+    return fail(MPE_EINVAL, "mpe_rollout_ac: unsupported shape");
+  for (const float* p : {obs_traj, logp_traj, value_traj, rew_traj, last_obs, last_value})
+    if (p && !aligned16(p)) return fail(MPE_EINVAL, "mpe_rollout_ac: float outputs must be 16-byte aligned");
+  if (uint64_t(e->abs_step) + uint64_t(T) > 0xFFFFFFFFull)
+    return fail(MPE_EINVAL, "mpe_rollout_ac: absolute step counter would overflow 32 bits");
+  RolloutArgs A;
+  A.st = e->st;
+  A.ph = e->ph;
+  A.TE = e->TE;
+  A.E = e->E;
+  A.seed = e->seed;
+  A.abs_step = e->abs_step;
+  A.T = T;
+  A.obs_traj = obs_traj;
+  A.act_traj = act_traj;
+  A.rew_traj = rew_traj;
+  A.done_traj = done_traj;
+  A.last_obs = last_obs;
+  A.logp_traj = logp_traj;
+  A.value_traj = value_traj;
+  A.last_value = last_value;
+  const char* why = nullptr;
+  hipError_t err = launch_rollout_ac_f32(e->N, A, e->pol, e->critic, static_cast<hipStream_t>(stream), &why);
+  if (why) return fail(MPE_EINVAL, "mpe_rollout_ac: %s", why);
+  if (err != hipSuccess) return fail(MPE_EHIP, "mpe_rollout_ac: %s", hipGetErrorString(err));
   MPE_HIP(hipGetLastError());
   e->abs_step += uint32_t(T);
   return MPE_OK;

@@ -18,6 +18,10 @@ struct RolloutArgs {
   float* rew_traj;    // [T][TE]       or null
   uint8_t* done_traj; // [T][TE]       or null
   float* last_obs;    // [TE][N][D]    or null
+  // actor-critic rollout only (null otherwise)
+  float* logp_traj = nullptr;   // [T][TE][N] log-probability of the sampled action
+  float* value_traj = nullptr;  // [T][TE][N] critic value of the observation acted on
+  float* last_value = nullptr;  // [TE][N]    critic value of last_obs
 };
 
 void launch_reset(int N, const StatePtrs& st, uint32_t TE, uint32_t E, uint32_t seed, float* obs,
@@ -49,7 +53,9 @@ hipError_t launch_rollout_policy_wide(int N, int H, const RolloutArgs& A, const 
                                       const char** why);
 bool f32_supported(int N, int H);                        // fp32 headline kernel (H = 64, N <= 3)
 hipError_t pack_policy_f32(PolicyBuffers& pb, int N, int R, const float* W1, const float* b1, const float* W2,
-                           const float* b2, const float* W3, const float* b3, hipStream_t s);
+                           const float* b2, const float* W3, const float* b3, int nout, hipStream_t s);
+hipError_t launch_rollout_ac_f32(int N, const RolloutArgs& A, const PolicyBuffers& pb, const PolicyBuffers& critic,
+                                 hipStream_t s, const char** why);
 hipError_t launch_rollout_policy_f32(int N, const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s,
                                      const char** why);
 hipError_t ensure_policy_bytes(PolicyBuffers& pb, size_t bytes);

@@ -94,7 +94,8 @@ template <int N>
 __global__ void pack_split_kernel(uint8_t* __restrict__ packed, const float* __restrict__ W1,
                                   const float* __restrict__ b1, const float* __restrict__ W2,
                                   const float* __restrict__ b2, const float* __restrict__ W3,
-                                  const float* __restrict__ b3) {
+                                  const float* __restrict__ b3, int nout) {
+  // nout = outputs of the last layer: 5 (policy logits) or 1 (critic value); W3 is [H][nout]
   constexpr int D = 6 * N, KIN = 4 * N + 2;
   const int run = blockIdx.y;
   uint8_t* out = packed + size_t(run) * Pk::RUN_BYTES;
@@ -102,8 +103,8 @@ __global__ void pack_split_kernel(uint8_t* __restrict__ packed, const float* __r
   b1 += size_t(run) * kH;
   W2 += size_t(run) * kH * kH;
   b2 += size_t(run) * kH;
-  W3 += size_t(run) * kH * kNumActions;
-  b3 += size_t(run) * kNumActions;
+  W3 += size_t(run) * kH * nout;
+  b3 += size_t(run) * nout;
   constexpr int n1 = 4 * 64 * 8, n2 = 4 * 2 * 64 * 8, n3 = 2 * 64 * 8, nb = 2 * kH + 16;
   int idx = blockIdx.x * blockDim.x + threadIdx.x;
   auto put3 = [&](size_t off, int blk, int lanes, int lane, int e, float v) {
@@ -139,10 +140,10 @@ __global__ void pack_split_kernel(uint8_t* __restrict__ packed, const float* __r
     if constexpr (L3<N>::kRowTerms) {
       const int out_o = l3_row_output(o), term = l3_row_term(o);
       uint32_t t3[3] = {0u, 0u, 0u};
-      if (out_o >= 0) split3(W3[size_t(k) * kNumActions + out_o], t3[0], t3[1], t3[2]);
+      if (out_o >= 0 && out_o < nout) split3(W3[size_t(k) * nout + out_o], t3[0], t3[1], t3[2]);
       reinterpret_cast<uint16_t*>(out + Pk::OFF_W3A)[(size_t(s) * 64 + lane) * 8 + e] = uint16_t(t3[term] >> 16);
     } else {
-      put3(Pk::OFF_W3A, s, 64, lane, e, o < kNumActions ? W3[size_t(k) * kNumActions + o] : 0.0f);
+      put3(Pk::OFF_W3A, s, 64, lane, e, o < nout ? W3[size_t(k) * nout + o] : 0.0f);
     }
     return;
   }
@@ -153,8 +154,8 @@ __global__ void pack_split_kernel(uint8_t* __restrict__ packed, const float* __r
     else if (idx < 2 * kH) v = kPre * b2[idx - kH];
     else if constexpr (L3<N>::kRowTerms) {
       const int i = idx - 2 * kH;
-      v = (l3_row_output(i) >= 0 && l3_row_term(i) == 0) ? b3[l3_row_output(i)] : 0.0f;
-    } else v = (idx - 2 * kH) < kNumActions ? b3[idx - 2 * kH] : 0.0f;
+      v = (l3_row_output(i) >= 0 && l3_row_output(i) < nout && l3_row_term(i) == 0) ? b3[l3_row_output(i)] : 0.0f;
+    } else v = (idx - 2 * kH) < nout ? b3[idx - 2 * kH] : 0.0f;
     reinterpret_cast<float*>(out + Pk::OFF_BIAS)[idx] = v;
   }
 }
@@ -227,10 +228,13 @@ __device__ __forceinline__ Terms tanh_split(const f32x4& a0, const f32x4& a1) {
 //   split(obs) | L1 m01 | L1 m23 + T1 s0 | L2 s0 + T1 s1 | L2 s1 m01 | L2 s1 m23 + T2 s0 |
 //   L3 s0 + T2 s1 | L3 s1
 // sched_barrier fences keep the compiler from regrouping the stages.
-template <int N>
+// VALUE: the network has one output (a critic); it goes to valX[j] / valY[j] and the rows are
+// left untouched.
+template <int N, bool VALUE = false>
 __device__ __forceinline__ void policy_pair(const uint8_t* __restrict__ wsm, const float* __restrict__ bias,
                                             const W3Terms& w3, float* __restrict__ rowsX,
-                                            float* __restrict__ rowsY, int lane) {
+                                            float* __restrict__ rowsY, int lane,
+                                            float* __restrict__ valX = nullptr, float* __restrict__ valY = nullptr) {
   constexpr int D = 6 * N;
   const int j = lane & 15, gq = lane >> 4;
   {
@@ -380,7 +384,13 @@ __device__ __forceinline__ void policy_pair(const uint8_t* __restrict__ wsm, con
   // ---- L3 s1
   zX = layer3(w3.s[1], cx1, zX);
   zY = layer3(w3.s[1], cy1, zY);
-  if constexpr (L3<N>::kRowTerms) {
+  if constexpr (VALUE) {
+    // output 0: lane group 0; row-term layout: its three term rows, otherwise register 0
+    if (gq == 0) {
+      valX[j] = L3<N>::kRowTerms ? (zX[0] + zX[1]) + zX[2] : zX[0];
+      valY[j] = L3<N>::kRowTerms ? (zY[0] + zY[1]) + zY[2] : zY[0];
+    }
+  } else if constexpr (L3<N>::kRowTerms) {
     // lane (j, gq): output gq = sum of its three term rows -> col gq; term gq of output 4 -> col 4 + gq
     rowsX[j * D + gq] = (zX[0] + zX[1]) + zX[2];
     rowsY[j * D + gq] = (zY[0] + zY[1]) + zY[2];
@@ -404,24 +414,48 @@ __device__ __forceinline__ void policy_pair(const uint8_t* __restrict__ wsm, con
 }
 
 // LDS plan (bytes).
-template <int N, int EB>
+// Plain rollout: W1A + W2A and the biases of the policy (its W3A lives in registers).
+// Actor-critic rollout (AC): the whole packed image of the policy and of the critic (W1A, W2A,
+// W3A, biases each), a value per row, and one arrival counter per 64-env sync group.
+template <int N, int EB, bool AC = false>
 struct SmemF32 {
   static constexpr int D = 6 * N;
   static constexpr int ROWS = EB * N;
-  static constexpr size_t OFF_BIAS = Pk::LDS_BYTES;
-  static constexpr size_t OFF_OBS = OFF_BIAS + Pk::BIAS_BYTES;
+  static constexpr size_t OFF_BIAS = AC ? Pk::OFF_BIAS : Pk::LDS_BYTES;
+  static constexpr size_t OFF_CRITIC = OFF_BIAS + Pk::BIAS_BYTES;    // AC: the critic's packed image
+  static constexpr size_t OFF_OBS = OFF_CRITIC + (AC ? Pk::RUN_BYTES : 0);
   static constexpr size_t OBS = size_t(ROWS) * D * 4 + 64;           // + zeroed tail: layer 1 reads 16 cols
   static constexpr size_t OFF_NEWPOS = OFF_OBS + OBS;                // [2][ROWS] float2, by step parity
-  static constexpr size_t TOTAL = OFF_NEWPOS + size_t(2) * ROWS * 8;
-  static_assert(OFF_OBS % 16 == 0 && OFF_NEWPOS % 16 == 0, "alignment");
+  static constexpr size_t OFF_VALUE = OFF_NEWPOS + size_t(2) * ROWS * 8;   // AC: [ROWS] float
+  static constexpr size_t OFF_ARRIVED = OFF_VALUE + (AC ? size_t(ROWS) * 4 : 0);
+  static constexpr size_t TOTAL = OFF_ARRIVED + (EB > 64 ? 16 : 0);
+  static_assert(OFF_OBS % 16 == 0 && OFF_NEWPOS % 16 == 0 && OFF_CRITIC % 16 == 0 && EB / 64 <= 4, "alignment");
 };
 
+// Barrier among the wavefronts of one 64-env sync group inside a larger block.  `arrived` counts
+// arrivals since the start of the kernel; `target` = (wavefronts per group) * (barriers so far).
+// Every wavefront of the block runs the same number of steps and none leaves early, and a block
+// is resident as a whole, so each wait ends.
+__device__ __forceinline__ void group_barrier(uint32_t* arrived, uint32_t target, int lane) {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  if (lane == 0) __hip_atomic_fetch_add(arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+  while (__hip_atomic_load(arrived, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < target)
+    __builtin_amdgcn_s_sleep(1);
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+
 // PER_AGENT: rew_traj is [T][TE][N], the mixed per-agent reward; every lane stores its agent's.
-template <int N, int EB, int MINW, bool PER_AGENT>
+// AC (actor-critic outputs): a second network of the same shape with one output, `packed_critic`,
+// is evaluated on every observation acted on, and the log-probability of the sampled action is
+// recorded (paper Sec. 3.2: IPPO / MAPPO; App. G: two tanh layers of width 64).  A block is then
+// EB / 64 independent 64-env sync groups that share the two staged networks.
+template <int N, int EB, int MINW, bool PER_AGENT, bool AC>
 __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
+                                                                          const uint8_t* __restrict__ packed_critic,
                                                                           int per_run_weights, uint32_t groups,
                                                                           uint32_t groups_per_xcd) {
-  using M = SmemF32<N, EB>;
+  using M = SmemF32<N, EB, AC>;
+  static_assert(AC || EB == 64, "plain rollouts use 64-env blocks");
   constexpr int D = 6 * N, ROWS = EB * N, THREADS = ROWS;
   static_assert(THREADS % 64 == 0, "block must be whole wavefronts");
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -429,6 +463,9 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
   float* bias = reinterpret_cast<float*>(smem + M::OFF_BIAS);
   float* tile = reinterpret_cast<float*>(smem + M::OFF_OBS);
   float2* newpos = reinterpret_cast<float2*>(smem + M::OFF_NEWPOS);
+  const uint8_t* csm = smem + M::OFF_CRITIC;                                         // AC only
+  const float* cbias = reinterpret_cast<const float*>(smem + M::OFF_CRITIC + Pk::OFF_BIAS);
+  float* values = reinterpret_cast<float*>(smem + M::OFF_VALUE);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -453,26 +490,44 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
 
   // ---- stage this block's weights (the run of its first env): W1A, W2A, biases in LDS; W3A in registers
   const uint8_t* run_weights = packed + (per_run_weights ? size_t(uint32_t(g0) / A.E) * Pk::RUN_BYTES : 0);
-  W3Terms w3;
+  // A operands of layer 3 from a packed image (global memory or LDS)
+  auto load_w3 = [&](const uint8_t* image) {
+    W3Terms w;
 #pragma unroll
-  for (int s = 0; s < 2; ++s) {
-    if constexpr (L3<N>::kRowTerms) {
-      w3.s[s].h = reinterpret_cast<const bf16x8*>(run_weights + Pk::OFF_W3A)[s * 64 + lane];
-    } else {
-      const bf16x8* src = reinterpret_cast<const bf16x8*>(run_weights + Pk::OFF_W3A) + s * 3 * 64 + lane;
-      w3.s[s].h = src[0];
-      w3.s[s].m = src[64];
-      w3.s[s].l = src[128];
+    for (int s = 0; s < 2; ++s) {
+      if constexpr (L3<N>::kRowTerms) {
+        w.s[s].h = reinterpret_cast<const bf16x8*>(image + Pk::OFF_W3A)[s * 64 + lane];
+      } else {
+        const bf16x8* src = reinterpret_cast<const bf16x8*>(image + Pk::OFF_W3A) + s * 3 * 64 + lane;
+        w.s[s].h = src[0];
+        w.s[s].m = src[64];
+        w.s[s].l = src[128];
+      }
     }
-  }
+    return w;
+  };
+  W3Terms w3;
+  if constexpr (!AC) w3 = load_w3(run_weights);
   {
+    // the packed image is W1A, W2A, W3A, biases; plain rollouts skip W3A (it is in registers)
     const uint4* src = reinterpret_cast<const uint4*>(run_weights);
     uint4* dst = reinterpret_cast<uint4*>(wsm);
-    for (int k = tid; k < int(Pk::LDS_BYTES / 16); k += THREADS) dst[k] = src[k];
-    const uint4* bsrc = reinterpret_cast<const uint4*>(run_weights + Pk::OFF_BIAS);
-    uint4* bdst = reinterpret_cast<uint4*>(bias);
-    for (int k = tid; k < int(Pk::BIAS_BYTES / 16); k += THREADS) bdst[k] = bsrc[k];
+    if constexpr (AC) {
+      for (int k = tid; k < int(Pk::RUN_BYTES / 16); k += THREADS) dst[k] = src[k];
+      const uint4* csrc = reinterpret_cast<const uint4*>(
+          packed_critic + (per_run_weights ? size_t(uint32_t(g0) / A.E) * Pk::RUN_BYTES : 0));
+      uint4* cdst = reinterpret_cast<uint4*>(smem + M::OFF_CRITIC);
+      for (int k = tid; k < int(Pk::RUN_BYTES / 16); k += THREADS) cdst[k] = csrc[k];
+    } else {
+      for (int k = tid; k < int(Pk::LDS_BYTES / 16); k += THREADS) dst[k] = src[k];
+      const uint4* bsrc = reinterpret_cast<const uint4*>(run_weights + Pk::OFF_BIAS);
+      uint4* bdst = reinterpret_cast<uint4*>(bias);
+      for (int k = tid; k < int(Pk::BIAS_BYTES / 16); k += THREADS) bdst[k] = bsrc[k];
+    }
     if (tid < 16) tile[ROWS * D + tid] = 0.0f;
+    if constexpr (EB > 64) {
+      if (tid < EB / 64) reinterpret_cast<uint32_t*>(smem + M::OFF_ARRIVED)[tid] = 0u;
+    }
   }
 
   // ---- registers: own agent, all agents' positions, all landmarks
@@ -524,10 +579,24 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
   uint8_t* act_base = A.act_traj;
   float* rew_base = A.rew_traj;
   uint8_t* done_base = A.done_traj;
+  float* logp_base = A.logp_traj;
+  float* value_base = A.value_traj;
   const uint32_t row_off = uint32_t(gc) * N + i;      // index of this agent inside a time slice
   const bool env_writer = valid && i == 0;            // the lane that stores per-env outputs
   uint32_t step = A.abs_step;
   const float* wtile = tile + wave * (64 * D);        // this wavefront's rows
+  uint32_t* arrived = reinterpret_cast<uint32_t*>(smem + M::OFF_ARRIVED) + wave / N;   // EB > 64 only
+
+  // Critic forward of this wavefront's rows: values[row] (wave-local rows).
+  auto critic_rows = [&]() {
+#pragma unroll 1
+    for (int pr = 0; pr < 2; ++pr) {
+      float* rows = tile + (wave * 64 + pr * 32) * D;
+      float* vals = values + wave * 64 + pr * 32;
+      const W3Terms wc = load_w3(csm);
+      policy_pair<N, true>(csm, cbias, wc, rows, rows + 16 * D, lane, vals, vals + 16);
+    }
+  };
 
   // Stream this wavefront's rows of the tile to dst (its slot in a [env][N][D] slice).
   auto flush_rows = [&](float* dst) {
@@ -542,10 +611,13 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
       flush_rows(obs_p);
       obs_p += TE * (N * D);
     }
-    // ---- policy: two pairs of 16-row tiles per wavefront
+    // ---- critic first (it leaves the rows untouched), then the policy, whose logits replace the
+    // first columns of the rows: two pairs of 16-row tiles per wavefront each
+    if constexpr (AC) critic_rows();
 #pragma unroll 1
     for (int pr = 0; pr < 2; ++pr) {
       float* rows = tile + (wave * 64 + pr * 32) * D;
+      if constexpr (AC) w3 = load_w3(wsm);
       policy_pair<N>(wsm, bias, w3, rows, rows + 16 * D, lane);
     }
     wave_sync();
@@ -557,6 +629,26 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
     if (act_base) {
       if (valid) act_base[row_off] = uint8_t(act);
       act_base += TE * N;
+    }
+    if constexpr (AC) {
+      // log pi(act | obs) = z_act - max - ln sum exp(z - max)
+      float zmax = z[0], zact = z[0];
+#pragma unroll
+      for (int k = 1; k < kNumActions; ++k) {
+        zmax = fmaxf(zmax, z[k]);
+        zact = act == uint32_t(k) ? z[k] : zact;
+      }
+      float sum = 0.0f;
+#pragma unroll
+      for (int k = 0; k < kNumActions; ++k) sum += hw_exp2((z[k] - zmax) * kLog2e);
+      if (logp_base) {
+        if (valid) logp_base[row_off] = (zact - zmax) - kLn2 * hw_log2(sum);
+        logp_base += TE * N;
+      }
+      if (value_base) {
+        if (valid) value_base[row_off] = values[tid];
+        value_base += TE * N;
+      }
     }
 
     // ---- transition of this lane's agent
@@ -578,7 +670,10 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
     vy = fmaf(fy, A.ph.dt_over_mass, vy * A.ph.keep);
     float2* np = newpos + (t & 1) * ROWS;
     np[tid] = make_float2(px, py);
-    __syncthreads();  // (C) new positions of every agent of every env of the block are visible
+    // (C) new positions of every agent of every env of this 64-env group are visible
+    if constexpr (EB == 64) __syncthreads();
+    else if constexpr (N > 1) group_barrier(arrived, uint32_t(N) * uint32_t(t + 1), lane);
+    else wave_sync();
 
 #pragma unroll
     for (int a = 0; a < N; ++a) {
@@ -651,6 +746,14 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
     wave_sync();
     flush_rows(A.last_obs + wave_row0);
   }
+  if constexpr (AC) {
+    if (A.last_value) {   // value of the observation after the last step
+      wave_sync();
+      critic_rows();
+      wave_sync();
+      if (valid) A.last_value[row_off] = values[tid];
+    }
+  }
 
   // ---- state back to HBM
   if (valid) {
@@ -669,10 +772,10 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
   }
 }
 
-template <int N, int EB, int MINW, bool PER_AGENT>
-hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s) {
-  using M = SmemF32<N, EB>;
-  auto kern = rollout_policy_f32_kernel<N, EB, MINW, PER_AGENT>;
+template <int N, int EB, int MINW, bool PER_AGENT, bool AC = false>
+hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s, const void* critic = nullptr) {
+  using M = SmemF32<N, EB, AC>;
+  auto kern = rollout_policy_f32_kernel<N, EB, MINW, PER_AGENT, AC>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -683,18 +786,18 @@ hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream
   const uint32_t groups = (A.TE + EB - 1) / EB;
   const uint32_t per_xcd = (groups + 7) / 8;
   hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(EB * N), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),
-                     int(A.TE != A.E), groups, per_xcd);
+                     static_cast<const uint8_t*>(critic), int(A.TE != A.E), groups, per_xcd);
   return hipGetLastError();
 }
 
 template <int N>
 hipError_t pack_impl(PolicyBuffers& pb, int R, const float* W1, const float* b1, const float* W2,
-                     const float* b2, const float* W3, const float* b3, hipStream_t s) {
+                     const float* b2, const float* W3, const float* b3, int nout, hipStream_t s) {
   if (hipError_t e = ensure_policy_bytes(pb, size_t(R) * Pk::RUN_BYTES); e != hipSuccess) return e;
   constexpr int total = 4 * 64 * 8 + 4 * 2 * 64 * 8 + 2 * 64 * 8 + 2 * kH + 16;
   dim3 grid((total + 255) / 256, R);
   hipLaunchKernelGGL(pack_split_kernel<N>, grid, dim3(256), 0, s, static_cast<uint8_t*>(pb.packed), W1, b1, W2,
-                     b2, W3, b3);
+                     b2, W3, b3, nout);
   return hipGetLastError();
 }
 
@@ -710,16 +813,40 @@ hipError_t launch_n(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s
   return hipSuccess;
 }
 
+// Actor-critic rollout: 256 envs per block = four 64-env sync groups (12 wavefronts at N = 3)
+// around one staged copy of the two networks (79 KB of the 160 KB LDS).
+template <int N>
+hipError_t launch_ac_n(const RolloutArgs& A, const PolicyBuffers& pb, const PolicyBuffers& critic, hipStream_t s,
+                       const char** why) {
+  const bool one_run = A.TE == A.E;
+  if (!one_run && A.E % 256 != 0) {
+    *why = "actor-critic rollout with several runs: num_envs per run must be a multiple of 256";
+    return hipSuccess;
+  }
+  return A.ph.reward_mode == 1 ? rollout_impl<N, 256, 3, true, true>(A, pb, s, critic.packed)
+                               : rollout_impl<N, 256, 3, false, true>(A, pb, s, critic.packed);
+}
+
 }  // namespace
 
 bool f32_supported(int N, int H) { return H == kH && N >= 1 && N <= 3; }
 
 hipError_t pack_policy_f32(PolicyBuffers& pb, int N, int R, const float* W1, const float* b1, const float* W2,
-                           const float* b2, const float* W3, const float* b3, hipStream_t s) {
+                           const float* b2, const float* W3, const float* b3, int nout, hipStream_t s) {
   switch (N) {
-    case 1: return pack_impl<1>(pb, R, W1, b1, W2, b2, W3, b3, s);
-    case 2: return pack_impl<2>(pb, R, W1, b1, W2, b2, W3, b3, s);
-    case 3: return pack_impl<3>(pb, R, W1, b1, W2, b2, W3, b3, s);
+    case 1: return pack_impl<1>(pb, R, W1, b1, W2, b2, W3, b3, nout, s);
+    case 2: return pack_impl<2>(pb, R, W1, b1, W2, b2, W3, b3, nout, s);
+    case 3: return pack_impl<3>(pb, R, W1, b1, W2, b2, W3, b3, nout, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_rollout_ac_f32(int N, const RolloutArgs& A, const PolicyBuffers& pb, const PolicyBuffers& critic,
+                                 hipStream_t s, const char** why) {
+  switch (N) {
+    case 1: return launch_ac_n<1>(A, pb, critic, s, why);
+    case 2: return launch_ac_n<2>(A, pb, critic, s, why);
+    case 3: return launch_ac_n<3>(A, pb, critic, s, why);
     default: return hipErrorInvalidValue;
   }
 }

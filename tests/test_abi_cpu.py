@@ -72,6 +72,8 @@ def test_null_arguments(lib):
     assert lib.mpe_step(None, None, None, None, None, None) == MPE_EINVAL
     assert lib.mpe_rollout(None, 1, None, None, None, None, None, None) == MPE_EINVAL
     assert lib.mpe_set_policy(None, None, None, None, None, None, None, None) == MPE_EINVAL
+    assert lib.mpe_set_critic(None, None, None, None, None, None, None, None) == MPE_EINVAL
+    assert lib.mpe_rollout_ac(None, 1, None, None, None, None, None, None, None, None, None) == MPE_EINVAL
     assert lib.mpe_get_state(None, None, None, None, None, None, None) == MPE_EINVAL
     assert lib.mpe_set_state(None, None, None, None, None, 0, 0, None) == MPE_EINVAL
     assert b"NULL" in lib.mpe_last_error()

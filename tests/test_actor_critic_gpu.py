@@ -1,0 +1,145 @@
+"""Parity of mpe_rollout_ac (log-probability of the sampled action, critic value, bootstrap value)
+against the oracle, through the C ABI.  Bars: actions as in the plain fused rollout; log-prob and
+value within 1e-5 * max(1, |ref|) of the oracle on teacher-forced observations; the plain outputs
+bit-identical to mpe_rollout's."""
+import numpy as np
+import pytest
+
+from tests import helpers as Hp
+from paper_2311_10090_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def mods():
+    if not torch.cuda.is_available():
+        pytest.fail("gpu tests need a device; the library has no CPU fallback")
+    from paper_2311_10090_amd.binding import MpeEnv
+    from oracle import Oracle
+    return MpeEnv, Oracle
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def _pair(mods, E, N, R=1, wseed=3, **kw):
+    MpeEnv, Oracle = mods
+    env = MpeEnv(Hp.gpu_config(E, N, R, 64, 0, **kw))
+    orc = Oracle(Hp.oracle_config(E, N, R, 64, 0, **kw), threads=8)
+    pw = synth.policy_weights_with_bias(wseed, R, 6 * N, 64)
+    cw = synth.critic_weights(wseed, R, 6 * N, 64)
+    env.set_policy(*Hp.to_dev(pw))
+    env.set_critic(*Hp.to_dev(cw))
+    orc.set_policy(*pw)
+    orc.set_critic(*cw)
+    return env, orc
+
+
+@pytest.mark.parametrize("E,N,R,T", [(1024, 3, 1, 30), (300, 3, 1, 30), (100, 2, 1, 20), (70, 1, 1, 20),
+                                     (256, 3, 2, 12)])
+def test_actor_critic_teacher_forced(mods, E, N, R, T):
+    """The oracle runs free; before every step its state is forced into the library, which then does
+    one actor-critic step."""
+    say("actor-critic teacher-forced E=%d N=%d R=%d T=%d" % (E, N, R, T))
+    env, orc = _pair(mods, E, N, R)
+    orc.reset(13)
+    env.reset(13)
+    bufs = env.empty_traj_ac(1)
+    agree = total = 0
+    worst_lp = worst_v = 0.0
+    for t in range(T):
+        pa, va, pl, ep, s = orc.get_state()
+        env.set_state(*Hp.state_to_gpu(pa, va, pl, ep), 13, s)
+        robs, ract, rlogp, rval, rrew, rdone, rlast, rlastv = orc.rollout_ac(1)
+        obs, act, logp, val, rew, done, last, lastv = [x.cpu().numpy() for x in env.rollout_ac(1, *bufs)]
+        Hp.assert_close_step(obs, robs, "obs acted on")
+        assert np.array_equal(done, rdone)
+        same = act == ract
+        agree += int(same.sum())
+        total += same.size
+        worst_v = max(worst_v, Hp.assert_close_step(val, rval, "value"))
+        worst_lp = max(worst_lp, Hp.assert_close_step(logp[same], rlogp[same], "log-prob of the sampled action"))
+        ok = same.all(axis=2)[0]
+        scale = Hp.step_scale(pa)[ok]
+        Hp.assert_close_step(lastv[ok], rlastv[ok], "bootstrap value", scale[:, None])
+        Hp.assert_close_step(rew[0][ok], rrew[0][ok], "reward", scale)
+    say("  action agreement %.6f over %d; worst log-prob error %.2e, value error %.2e" % (agree / total, total, worst_lp, worst_v))
+    assert (1.0 - agree / total) * total <= max(2, 1e-4 * total)
+    env.close()
+
+
+@pytest.mark.parametrize("E,N,kw", [(512, 3, {}), (200, 3, dict(reward_mode=1, local_ratio=0.5)), (130, 2, {})])
+def test_actor_critic_rollout_matches_plain_rollout_and_itself(mods, E, N, kw):
+    """obs, actions, rewards, done and last_obs are bit-identical to mpe_rollout's (the same policy
+    arithmetic in another block shape), log-prob and value of step t are functions of obs[t] only
+    (checked against the oracle's networks on the recorded observations), T steps = T/2 + T/2."""
+    MpeEnv, Oracle = mods
+    T = 32
+    say("actor-critic free-running E=%d N=%d %s" % (E, N, kw))
+    a, orc = _pair(mods, E, N, 1, wseed=9, **kw)
+    b, _ = _pair(mods, E, N, 1, wseed=9, **kw)
+    c, _ = _pair(mods, E, N, 1, wseed=9, **kw)
+    for e in (a, b, c):
+        e.reset(21)
+    full = a.rollout_ac(T, *a.empty_traj_ac(T))
+    plain = b.rollout(T, *b.empty_traj(T))
+    for k_ac, k_pl in ((0, 0), (1, 1), (4, 2), (5, 3), (6, 4)):
+        assert torch.equal(full[k_ac], plain[k_pl]), "output %d differs from mpe_rollout" % k_ac
+    h1 = [x.clone() for x in c.rollout_ac(T // 2, *c.empty_traj_ac(T // 2))]
+    h2 = c.rollout_ac(T // 2, *c.empty_traj_ac(T // 2))
+    for k in range(6):
+        assert torch.equal(full[k], torch.cat([h1[k], h2[k]])), "continuation, output %d" % k
+    assert torch.equal(full[6], h2[6]) and torch.equal(full[7], h2[7])
+    obs, act, logp, val = [x.cpu().numpy() for x in full[:4]]
+    rows = obs.reshape(-1, 6 * N).astype(np.float64)
+    z = orc.policy_logits(rows)
+    from scipy.special import log_softmax
+    ref_lp = log_softmax(z, axis=1)[np.arange(z.shape[0]), act.reshape(-1)]
+    Hp.assert_close_step(logp.reshape(-1), ref_lp, "log-prob from recorded obs and actions")
+    Hp.assert_close_step(val.reshape(-1), orc.value(rows), "value from recorded obs")
+    Hp.assert_close_step(full[7].cpu().numpy().reshape(-1),
+                         orc.value(full[6].cpu().numpy().reshape(-1, 6 * N).astype(np.float64)), "bootstrap value")
+    assert bool((full[2] <= 0).all()) and bool(torch.isfinite(full[3]).all())
+    for e in (a, b, c):
+        e.close()
+
+
+def test_actor_critic_errors_and_absent_outputs(mods):
+    MpeEnv, _ = mods
+    from paper_2311_10090_amd.binding import MpeError, MPE_EINVAL, MPE_ESTATE
+    env = MpeEnv(Hp.gpu_config(64, 3, 1, 64, 0))
+    env.reset(0)
+    with pytest.raises(MpeError) as ei:
+        env.rollout_ac(2)
+    assert ei.value.code == MPE_ESTATE
+    env.set_policy(*Hp.to_dev(synth.policy_weights(0, 1, 18, 64)))
+    with pytest.raises(MpeError) as ei:
+        env.rollout_ac(2)
+    assert ei.value.code == MPE_ESTATE
+    env.set_critic(*Hp.to_dev(synth.critic_weights(0, 1, 18, 64)))
+    ref = MpeEnv(Hp.gpu_config(64, 3, 1, 64, 0))
+    ref.set_policy(*Hp.to_dev(synth.policy_weights(0, 1, 18, 64)))
+    ref.reset(0)
+    env.rollout_ac(7)                       # no outputs at all
+    ref.rollout(7)
+    for x, y in zip(env.get_state(), ref.get_state()):
+        assert torch.equal(x, y) if hasattr(x, "shape") else x == y
+    env.close()
+    ref.close()
+    wide = MpeEnv(Hp.gpu_config(64, 10, 1, 128, 1))
+    with pytest.raises(MpeError) as ei:
+        wide.set_critic(*Hp.to_dev(synth.critic_weights(0, 1, 60, 128)))
+    assert ei.value.code == MPE_EINVAL
+    wide.close()
+    runs = MpeEnv(Hp.gpu_config(64, 3, 2, 64, 0))     # several runs need num_envs % 256 == 0
+    runs.set_policy(*Hp.to_dev(synth.policy_weights(0, 2, 18, 64)))
+    runs.set_critic(*Hp.to_dev(synth.critic_weights(0, 2, 18, 64)))
+    runs.reset(0)
+    with pytest.raises(MpeError) as ei:
+        runs.rollout_ac(2)
+    assert ei.value.code == MPE_EINVAL
+    runs.close()
