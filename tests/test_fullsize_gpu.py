@@ -130,3 +130,32 @@ def test_wide_bf16_full_size():
     say("  bf16 sampled action agreement %.5f over %d samples (no bar)" % (agree / tot, tot))
     assert agree / tot >= 0.99
     env.close()
+
+
+def test_large_ragged_size_uses_256_env_blocks():
+    """A single run a little over 65,536 envs: the fused kernel runs 256-env blocks of four sync
+    groups, the last block holds 74 valid envs (one full group, one group of 10, two empty)."""
+    wl = synth.Workload("ragged_65610env_n3_mlp64_fp32", 65610, 3, 1, 60, 64, 0)
+    say("full size %s" % wl.name)
+    env, out, weights = _gpu_rollout(wl, seed=2, wseed=7)
+    obs, act, rew, done, last = out
+    assert int(done.sum().item()) == wl.total_envs * (wl.T // synth.MAX_EPISODE_STEPS)
+    assert bool(torch.isfinite(obs).all()) and bool((act <= 4).all())
+    tot = agree = 0
+    for off, n in ((65536 - 40, 40), (65536, 64), (65600, 10), (300, 20)):
+        ref = _oracle_range(wl, 2, 0, off, n, weights)
+        frac, cnt = _compare_range(wl, out, ref, off, n, "ragged envs %d..%d" % (off, off + n))
+        agree += frac * cnt
+        tot += cnt
+    say("  sampled action agreement %.6f over %d samples" % (agree / tot, tot))
+    assert agree / tot >= Hp.ACTION_AGREEMENT - 2.0 / tot
+    # same job through the actor-critic entry point (also 256-env blocks): identical plain outputs
+    env2, _, _ = _gpu_rollout(wl, seed=2, wseed=7)
+    env2.set_critic(*Hp.to_dev(synth.critic_weights(7, 1, wl.obs_dim, wl.hidden)))
+    env2.reset(2)
+    ac = env2.rollout_ac(wl.T, *env2.empty_traj_ac(wl.T))
+    for k_ac, k_pl in ((0, 0), (1, 1), (4, 2), (5, 3), (6, 4)):
+        assert torch.equal(ac[k_ac], out[k_pl])
+    assert bool(torch.isfinite(ac[2]).all()) and bool(torch.isfinite(ac[3]).all()) and bool(torch.isfinite(ac[7]).all())
+    env.close()
+    env2.close()
