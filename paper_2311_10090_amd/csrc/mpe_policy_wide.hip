@@ -43,10 +43,94 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
+// Packed weight layout of one run (bf16): A operands of v_mfma_f32_16x16x32_bf16, lane (i = lane%16,
+// gq = lane/16) holds weights [k = 8 gq + e][out = 16 m + i], e = 0..7 (16 bytes).
+//   W1A [m][s][lane]  layer 1, K slices of 32 inputs in natural order, zero padded past the
+//                     4N + 2 live observation entries
+//   W2A [m][s][lane]  layer 2, K position (s, gq, e) = hidden unit hidden_of(s, gq, e): the order
+//                     in which the accumulators of the previous layer hold the hidden units
+//   W3A [s][lane]     layer 3 (5 outputs padded to 16)
+//   bias b1 [H], b2 [H], b3 [16] fp32
+template <int N, int H>
+struct Shape {
+  static constexpr int D = 6 * N;
+  static constexpr int KIN = 4 * N + 2;           // non-zero leading entries of an observation
+  static constexpr int KS = 32;                   // K extent of one MFMA
+  static constexpr int MT = H / 16;               // 16-wide tiles of hidden units
+  static constexpr int S1 = cdiv(KIN, KS);        // K slices of layer 1
+  static constexpr int S2 = H / KS;               // K slices of layers 2 and 3
+  static constexpr size_t W1A_BYTES = size_t(MT) * S1 * 64 * 16;
+  static constexpr size_t W2A_BYTES = size_t(MT) * S2 * 64 * 16;
+  static constexpr size_t W3A_BYTES = size_t(S2) * 64 * 16;
+  static constexpr size_t BIAS_BYTES = size_t(2 * H + 16) * 4;
+  static constexpr size_t OFF_W1A = 0;
+  static constexpr size_t OFF_W2A = OFF_W1A + W1A_BYTES;
+  static constexpr size_t OFF_W3A = OFF_W2A + W2A_BYTES;
+  static constexpr size_t OFF_BIAS = OFF_W3A + W3A_BYTES;
+  static constexpr size_t RUN_BYTES = OFF_BIAS + BIAS_BYTES;
+};
+
+// Hidden unit that K position (slice s, lane group gq, element e) of layers 2/3 refers to:
+// the accumulator register (tile m, r) of lane group gq holds unit 16m + 4gq + r.
+__host__ __device__ constexpr int hidden_of(int s, int gq, int e) { return 32 * s + 16 * (e / 4) + 4 * gq + (e % 4); }
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return uint16_t((u >> 16) | 0x40u);  // NaN stays NaN
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return uint16_t(u >> 16);
+}
+
+// One thread per packed element of one run (weights rounded to bf16, ties to even).
+template <int N, int H>
+__global__ void pack_policy_kernel(uint8_t* __restrict__ packed, const float* __restrict__ W1,
+                                   const float* __restrict__ b1, const float* __restrict__ W2,
+                                   const float* __restrict__ b2, const float* __restrict__ W3,
+                                   const float* __restrict__ b3) {
+  using S = Shape<N, H>;
+  const int run = blockIdx.y;
+  uint8_t* out = packed + size_t(run) * S::RUN_BYTES;
+  W1 += size_t(run) * S::D * H;
+  b1 += size_t(run) * H;
+  W2 += size_t(run) * H * H;
+  b2 += size_t(run) * H;
+  W3 += size_t(run) * H * kNumActions;
+  b3 += size_t(run) * kNumActions;
+  constexpr int n1 = S::MT * S::S1 * 64 * 8, n2 = S::MT * S::S2 * 64 * 8, n3 = S::S2 * 64 * 8, nb = 2 * H + 16;
+  int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  auto put = [&](size_t off, int i, float v) { reinterpret_cast<uint16_t*>(out + off)[i] = f32_to_bf16_rne(v); };
+  if (idx < n1) {   // [m][s][lane][e]; k = 32 s + 8 gq + e (natural order)
+    const int e = idx % 8, lane = (idx / 8) % 64, s = (idx / 512) % S::S1, m = idx / (512 * S::S1);
+    const int k = S::KS * s + 8 * (lane / 16) + e, o = 16 * m + lane % 16;
+    put(S::OFF_W1A, idx, k < S::KIN ? W1[size_t(k) * H + o] : 0.0f);
+    return;
+  }
+  idx -= n1;
+  if (idx < n2) {   // [m][s][lane][e]
+    const int e = idx % 8, lane = (idx / 8) % 64, s = (idx / 512) % S::S2, m = idx / (512 * S::S2);
+    put(S::OFF_W2A, idx, W2[size_t(hidden_of(s, lane / 16, e)) * H + 16 * m + lane % 16]);
+    return;
+  }
+  idx -= n2;
+  if (idx < n3) {   // [s][lane][e]
+    const int e = idx % 8, lane = (idx / 8) % 64, s = idx / 512, o = lane % 16;
+    put(S::OFF_W3A, idx, o < kNumActions ? W3[size_t(hidden_of(s, lane / 16, e)) * kNumActions + o] : 0.0f);
+    return;
+  }
+  idx -= n3;
+  if (idx < nb) {
+    float v;
+    if (idx < H) v = b1[idx];
+    else if (idx < 2 * H) v = b2[idx - H];
+    else v = (idx - 2 * H) < kNumActions ? b3[idx - 2 * H] : 0.0f;
+    reinterpret_cast<float*>(out + S::OFF_BIAS)[idx] = v;
+  }
+}
+
 // LDS plan of one block (bytes).
 template <int N, int H, int EB>
 struct Smem {
-  using S = Shape<N, H, true>;
+  using S = Shape<N, H>;
   static constexpr int ROWS = EB * N, WAVES = ROWS / 64;
   static constexpr size_t WEIGHTS = S::OFF_BIAS;                   // W1A + W2A + W3A
   static constexpr size_t OFF_BIAS = WEIGHTS;
@@ -113,9 +197,9 @@ __device__ __forceinline__ void group_barrier(uint32_t* arrived, uint32_t target
 // zrows[j*5 .. j*5+4].
 template <int N, int H>
 __device__ __forceinline__ void policy_tile(const uint8_t* __restrict__ wsm, const float* __restrict__ bias,
-                                            const bf16x8 (&b1)[Shape<N, H, true>::S1], float* __restrict__ zrows,
+                                            const bf16x8 (&b1)[Shape<N, H>::S1], float* __restrict__ zrows,
                                             int lane) {
-  using S = Shape<N, H, true>;
+  using S = Shape<N, H>;
   constexpr int MT = S::MT;
   const int j = lane & 15, gq = lane >> 4;
   // Weights and biases are re-read from LDS for every tile on purpose: the addresses go through
@@ -183,7 +267,7 @@ template <int N, int H, int EB, int MINW, bool PER_AGENT>
 __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
                                                                       int per_run_weights, uint32_t groups,
                                                                       uint32_t groups_per_xcd) {
-  using S = Shape<N, H, true>;
+  using S = Shape<N, H>;
   using M = Smem<N, H, EB>;
   constexpr int D = S::D, KIN = S::KIN, ROWS = EB * N, THREADS = ROWS;
   constexpr int RF4 = D / 4;                 // 16-byte chunks of one observation row
@@ -449,14 +533,14 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
   }
 }
 
-template <int N, int H, bool BF16>
+template <int N, int H>
 hipError_t pack_impl(PolicyBuffers& pb, int R, const float* W1, const float* b1, const float* W2,
                      const float* b2, const float* W3, const float* b3, hipStream_t s) {
-  using S = Shape<N, H, BF16>;
+  using S = Shape<N, H>;
   if (hipError_t e = ensure_policy_bytes(pb, size_t(R) * S::RUN_BYTES); e != hipSuccess) return e;
-  const int total = int(S::RUN_BYTES / S::ELT);  // upper bound on elements of one run
+  const int total = int(S::RUN_BYTES / 2);  // upper bound on elements of one run
   dim3 grid(cdiv(total, 256), R);
-  hipLaunchKernelGGL((pack_policy_kernel<N, H, BF16>), grid, dim3(256), 0, s,
+  hipLaunchKernelGGL((pack_policy_kernel<N, H>), grid, dim3(256), 0, s,
                      static_cast<uint8_t*>(pb.packed), W1, b1, W2, b2, W3, b3);
   return hipGetLastError();
 }
@@ -493,7 +577,7 @@ bool wide_supported(int N, int H) {
 
 hipError_t pack_policy_wide(PolicyBuffers& pb, int N, int H, int R, const float* W1, const float* b1,
                             const float* W2, const float* b2, const float* W3, const float* b3, hipStream_t s) {
-#define X(N_, H_, EB_, MW_) if (N == N_ && H == H_) return pack_impl<N_, H_, true>(pb, R, W1, b1, W2, b2, W3, b3, s);
+#define X(N_, H_, EB_, MW_) if (N == N_ && H == H_) return pack_impl<N_, H_>(pb, R, W1, b1, W2, b2, W3, b3, s);
   MPE_WIDE_CASES(X)
 #undef X
   return hipErrorInvalidValue;
