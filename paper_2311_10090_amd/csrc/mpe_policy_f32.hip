@@ -19,7 +19,13 @@
 // again a B-operand layout for the next layer when the weights are packed in the matching K
 // order, so activations stay in registers between layers.  Every wavefront works on its own
 // rows of the LDS observation tile; the only cross-wavefront data are the new positions of the
-// envs that straddle a wavefront boundary: one block barrier per step.
+// envs that straddle a wavefront boundary: one barrier per step among the N wavefronts of a
+// 64-env sync group (the block barrier for 64-env blocks, an arrival counter in LDS for the
+// 256-env blocks of four independent groups).
+//
+// The same kernel also serves the mixed per-agent reward (PER_AGENT) and the actor-critic
+// rollout (AC: a second pass of the tile code over a critic's packed image, log-probability of
+// the sampled action).
 #include "mpe_policy_common.h"
 
 namespace mpe {
@@ -59,7 +65,7 @@ __device__ __forceinline__ uint32_t pack_hi16(uint32_t a, uint32_t b) {
 //   W2A [m 4][s 2][term 3][lane 64]
 //   W3A [s 2][term 3][lane 64]   (5 outputs padded to 16), N = 1 only
 //   W3A [s 2][lane 64]           N >= 2: the 16 output rows of the instruction carry the three
-//                                 terms of the 5 outputs (row_of below), so ONE A operand meets
+//                                 terms of the 5 outputs (l3_row_* below), so ONE A operand meets
 //                                 the three activation terms in three instructions per K slice
 //   bias b1*pre [64], b2*pre [64], b3 [16] fp32 (N >= 2: b3 in the h-term row of each output)
 struct Pk {
