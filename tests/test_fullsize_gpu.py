@@ -159,3 +159,42 @@ def test_large_ragged_size_uses_256_env_blocks():
     assert bool(torch.isfinite(ac[2]).all()) and bool(torch.isfinite(ac[3]).all()) and bool(torch.isfinite(ac[7]).all())
     env.close()
     env2.close()
+
+
+def test_large_size_mixed_reward():
+    """Mixed per-agent reward through the 256-env block path, sampled against the oracle.  Rewards
+    are compared on the first steps of each episode, for envs whose actions so far agree, leaving
+    out agents within 1e-4 of the overlap threshold."""
+    from paper_2311_10090_amd.binding import MpeEnv
+    from oracle import Oracle
+    E, N, T = 65610, 3, 30
+    say("full size mixed reward: %d envs" % E)
+    w = synth.policy_weights_with_bias(5, 1, 18, 64)
+    env = MpeEnv(Hp.gpu_config(E, N, 1, 64, 0, reward_mode=1, local_ratio=0.5))
+    env.set_policy(*Hp.to_dev(w))
+    env.reset(3)
+    obs, act, rew, done, last = env.rollout(T, *env.empty_traj(T))
+    assert rew.shape == (T, E, N)
+    compared = 0
+    for off, n in ((0, 64), (65536 - 20, 40), (65600, 10), (40000, 64)):
+        orc = Oracle(Hp.oracle_config(n, N, 1, 64, 0, env_offset=off, reward_mode=1, local_ratio=0.5), threads=8)
+        orc.set_policy(*w)
+        orc.reset(3)
+        robs, ract, rrew, rdone, rlast = orc.rollout(T)
+        a = act[:, off:off + n].cpu().numpy()
+        r = rew[:, off:off + n].cpu().numpy()
+        o = obs[:, off:off + n].cpu().numpy()
+        for t0 in (0, 25):
+            for t in range(t0, min(t0 + 4, T - 1)):
+                alive = (a[t0:t + 1] == ract[t0:t + 1]).all(axis=(0, 2))
+                # positions after step t = own-position entries of the next observation (no reset inside)
+                pos = robs[t + 1][:, :, 2:4]
+                d = np.linalg.norm(pos[:, :, None, :] - pos[:, None, :, :], axis=3)
+                d[:, np.arange(N), np.arange(N)] = np.inf
+                mask = (np.abs(d - 0.3) > 1e-4).all(axis=2) & alive[:, None]
+                assert np.abs(r[t][mask] - rrew[t][mask]).max() <= Hp.EPISODE_ATOL, "t=%d envs %d.." % (t, off)
+                compared += int(mask.sum())
+        assert np.array_equal(o[0].astype(np.float64), robs[0]) and np.array_equal(o[25].astype(np.float64), robs[25])
+    say("  %d agent rewards compared" % compared)
+    assert compared > 3000
+    env.close()
