@@ -139,7 +139,8 @@ struct Smem {
   static constexpr size_t OFF_NEWPOS = OFF_STAGE + WAVES * STAGE_WAVE;   // [2][ROWS] float2, by step parity
   static constexpr size_t OFF_DMIN = OFF_NEWPOS + size_t(2) * ROWS * 8;  // [2][ROWS] float,  by step parity
   static constexpr size_t OFF_LM = OFF_DMIN + size_t(2) * ROWS * 4;      // [EB][N] float2 landmark positions
-  static constexpr size_t OFF_ARRIVED = OFF_LM + size_t(ROWS) * 8;       // arrival counter of each sync group
+  static constexpr size_t OFF_RESPOS = OFF_LM + size_t(ROWS) * 8;        // [EB][N] float2 positions after a reset
+  static constexpr size_t OFF_ARRIVED = OFF_RESPOS + size_t(ROWS) * 8;   // arrival counter of each sync group
   static constexpr size_t TOTAL = OFF_ARRIVED + 16;
   static_assert(OFF_STAGE % 16 == 0 && STAGE_WAVE % 16 == 0 && OFF_NEWPOS % 16 == 0, "alignment");
 };
@@ -281,6 +282,7 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
   float2* newpos = reinterpret_cast<float2*>(smem + M::OFF_NEWPOS);
   float* dminbuf = reinterpret_cast<float*>(smem + M::OFF_DMIN);
   float2* lmbuf = reinterpret_cast<float2*>(smem + M::OFF_LM);
+  float2* respos = reinterpret_cast<float2*>(smem + M::OFF_RESPOS);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -312,29 +314,25 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
     for (int k = tid; k < int(S::RUN_BYTES / 16); k += THREADS) dst[k] = src[k];
   }
 
-  // ---- registers: own agent, all agents' positions, landmark i (the one whose coverage distance
-  // this lane evaluates); LDS: all landmarks of the block's envs (they change only at a reset)
+  // ---- registers: own agent and landmark i (the one whose coverage distance this lane
+  // evaluates).  LDS: all landmarks of the block's envs (they change only at a reset) and the
+  // positions of all agents: the other agents' positions are read where they are needed
+  // (observation, contacts, reward) instead of being held in 2N registers through the policy.
+  // `cur` is where the env's current positions are: the exchange buffer of the latest step, or
+  // `respos` when the env has just been reset (or at the start of the call).
   float px = 0.0f, py = 0.0f, vx = 0.0f, vy = 0.0f, mylx = 0.0f, myly = 0.0f;
-  float qx[N], qy[N];
   int32_t ep = 0;
-#pragma unroll
-  for (int a = 0; a < N; ++a) qx[a] = qy[a] = 0.0f;
   if (valid) {
-#pragma unroll
-    for (int a = 0; a < N; ++a) {
-      qx[a] = A.st.pos_a[(0 * N + a) * TE + g];
-      qy[a] = A.st.pos_a[(1 * N + a) * TE + g];
-    }
+    px = A.st.pos_a[(0 * N + i) * TE + g];
+    py = A.st.pos_a[(1 * N + i) * TE + g];
     mylx = A.st.pos_l[(0 * N + i) * TE + g];
     myly = A.st.pos_l[(1 * N + i) * TE + g];
     vx = A.st.vel_a[(0 * N + i) * TE + g];
     vy = A.st.vel_a[(1 * N + i) * TE + g];
     ep = A.st.ep_step[g];
   }
-#pragma unroll
-  for (int a = 0; a < N; ++a) {
-    if (a == i) { px = qx[a]; py = qy[a]; }
-  }
+  respos[tid] = make_float2(px, py);
+  const float2* cur = respos + el * N;
   lmbuf[tid] = make_float2(mylx, myly);   // tid = el * N + i
   if (tid < EB / GE) reinterpret_cast<uint32_t*>(smem + M::OFF_ARRIVED)[tid] = 0u;
   __syncthreads();  // weights, biases, landmarks and counters staged; the only block-wide barrier
@@ -348,10 +346,13 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
       o[4 + 2 * l] = lm.x - px;
       o[5 + 2 * l] = lm.y - py;
     }
+    float2 q[N];
+#pragma unroll
+    for (int a = 0; a < N; ++a) q[a] = cur[a];
 #pragma unroll
     for (int c = 0; c < N - 1; ++c) {   // other agents, ascending: slot c holds agent c + (c >= i)
-      const float ox = c >= i ? qx[c + 1] : qx[c];
-      const float oy = c >= i ? qy[c + 1] : qy[c];
+      const float ox = c >= i ? q[c + 1].x : q[c].x;
+      const float oy = c >= i ? q[c + 1].y : q[c].y;
       o[4 + 2 * N + 2 * c] = ox - px;
       o[5 + 2 * N + 2 * c] = oy - py;
     }
@@ -442,8 +443,9 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
 #pragma unroll
     for (int a = 0; a < N; ++a) {
       if (a != i) {
-        const float dx = px - qx[a];
-        const float dy = py - qy[a];
+        const float2 q = cur[a];
+        const float dx = px - q.x;
+        const float dy = py - q.y;
         const float k = contact_factor(dx, dy, A.ph);
         fx = fmaf(k, dx, fx);
         fy = fmaf(k, dy, fy);
@@ -460,12 +462,14 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
 
     // reward of the previous step: sum of its N per-landmark distances
     if (t > 0) store_reward((t - 1) & 1);
+    float qx[N], qy[N];
 #pragma unroll
     for (int a = 0; a < N; ++a) {
       const float2 p = np[el * N + a];
       qx[a] = p.x;
       qy[a] = p.y;
     }
+    cur = np + el * N;
     if constexpr (PER_AGENT) {
       overlaps = 0;
 #pragma unroll
@@ -494,21 +498,24 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
     }
     if (done) {
       // new episode keyed by step + 1; every lane regenerates the whole env (rare: 1 step in
-      // max_ep) and writes all its landmarks: the lanes of an env store identical values, and a
-      // lane reads them back only after its own stores.  The empty asm keeps the compiler from
-      // hoisting the env-dependent first Philox round of all 2N streams out of the step loop.
+      // max_ep) and writes all its positions and landmarks: the lanes of an env store identical
+      // values, and a lane reads them back only after its own stores (the exchange buffer itself
+      // is left alone: slower lanes of the env may still be reading the pre-reset positions).
+      // The empty asm keeps the compiler from hoisting the env-dependent first Philox round of
+      // all 2N streams out of the step loop.
       uint32_t env_r = env;
       asm volatile("" : "+v"(env_r));
 #pragma unroll
       for (int a = 0; a < N; ++a) {
         const uint4 w = philox4x32_10(env_r, step + 1u, uint32_t(a), kTagResetPos, A.seed, run);
-        qx[a] = word_to_position(w.x);
-        qy[a] = word_to_position(w.y);
+        const float2 p = make_float2(word_to_position(w.x), word_to_position(w.y));
+        respos[el * N + a] = p;
         const uint4 wl = philox4x32_10(env_r, step + 1u, uint32_t(N + a), kTagResetPos, A.seed, run);
         const float2 lm = make_float2(word_to_position(wl.x), word_to_position(wl.y));
         lmbuf[el * N + a] = lm;
-        if (a == i) { px = qx[a]; py = qy[a]; mylx = lm.x; myly = lm.y; }
+        if (a == i) { px = p.x; py = p.y; mylx = lm.x; myly = lm.y; }
       }
+      cur = respos + el * N;
       vx = vy = 0.0f;
       ep = 0;
     }
