@@ -192,6 +192,21 @@ def main():
         env4.close()
         del b4
 
+    # the same shape with bf16 weights and layer inputs (fp32 accumulate), as defined by the oracle's bf16 mode
+    bf = {}
+    if wl.weight_dtype == 0:
+        k = max(3, args.steps // 3)
+        env5 = MpeEnv(Hp.gpu_config(wl.num_envs, N, wl.num_runs, H, 1))
+        env5.set_policy(*Hp.to_dev(weights))
+        env5.reset(seed)
+        b5 = env5.empty_traj(T)
+        w5, k5 = time_rollouts(env5, T, b5, k, 2)
+        bf = {"agent_steps_per_s": agent_steps / (w5 / k), "kernel_ms_avg": float(np.mean(k5)),
+              "hbm_GBs": bytes_per_env_step(N, D) * TE * T / (float(np.mean(k5)) * 1e-3) / 1e9,
+              "note": "weight_dtype = MPE_WEIGHTS_BF16: one bf16 matrix instruction per product, no operand split"}
+        env5.close()
+        del b5
+
     out = {
         "metric": "agent-steps/sec fused MPE rollout @65,536 envs, 1 MI355X; % HBM roofline",
         "value": value,
@@ -239,6 +254,7 @@ def main():
         },
         "mixed_reward": mixed,
         "actor_critic": ac,
+        "bf16_policy": bf,
         "single_step": {"us_per_mpe_step_call": step_us, "env_steps_per_s": TE / (step_us * 1e-6),
                         "note": "back-to-back mpe_step calls with resident actions; 352 B per env-step"},
         "paper_context": {"mpe_simple_spread_steps_per_s": {"original_cpu_1env_epyc7763": 8.3e4,

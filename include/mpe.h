@@ -118,7 +118,9 @@ int mpe_step(mpe_env* env, const uint8_t* actions, float* obs, float* reward, ui
  * row-major [fan_in][fan_out], device pointers.  The library copies them into its own
  * operand layout on `stream` (rounding W to bf16, ties to even, when weight_dtype is
  * MPE_WEIGHTS_BF16); the caller's arrays are not referenced after that work has run.
- * MPE_EINVAL if only some pointers are NULL or the config has no usable `hidden`. */
+ * Policies are built for (num_agents, hidden, weight_dtype) in (1..3, 64, fp32 or bf16) and
+ * (10, 128, bf16).  MPE_EINVAL for other shapes, if only some pointers are NULL, or if the config
+ * has no usable `hidden`. */
 int mpe_set_policy(mpe_env* env, const float* W1, const float* b1, const float* W2,
                    const float* b2, const float* W3, const float* b3, void* stream);
 
@@ -139,8 +141,8 @@ int mpe_rollout(mpe_env* env, int32_t T, float* obs_traj, uint8_t* act_traj, flo
  * the paper's IPPO, Sec. 3.2; App. G: two tanh layers of width 64):
  *   value = V3^T tanh(V2^T tanh(V1^T obs + c1) + c2) + c3
  * V1 [R][D][H], c1 [R][H], V2 [R][H][H], c2 [R][H], V3 [R][H], c3 [R], fp32 device pointers;
- * copied as in mpe_set_policy.  Built for the fp32 shapes (hidden 64, 1..3 agents); MPE_EINVAL
- * otherwise. */
+ * copied (and rounded, with MPE_WEIGHTS_BF16) as in mpe_set_policy.  Built for hidden 64 and
+ * 1..3 agents; MPE_EINVAL otherwise. */
 int mpe_set_critic(mpe_env* env, const float* V1, const float* c1, const float* V2,
                    const float* c2, const float* V3, const float* c3, void* stream);
 

@@ -236,11 +236,11 @@ int mpe_set_critic(mpe_env* e, const float* V1, const float* c1, const float* V2
     return MPE_OK;
   }
   if (given != 6) return fail(MPE_EINVAL, "mpe_set_critic: pass all six arrays or none");
-  if (e->cfg.weight_dtype != MPE_WEIGHTS_FP32 || !f32_supported(e->N, e->H))
+  if (!f32_supported(e->N, e->H))
     return fail(MPE_EINVAL, "mpe_set_critic: unsupported shape: the actor-critic rollout is built for "
-                            "fp32 weights, hidden 64 and 1..3 agents");
+                            "hidden 64 and 1..3 agents");
   hipError_t err = pack_policy_f32(e->critic, e->N, int(e->R), V1, c1, V2, c2, V3, c3, 1,
-                                   static_cast<hipStream_t>(stream));
+                                   e->cfg.weight_dtype == MPE_WEIGHTS_BF16, static_cast<hipStream_t>(stream));
   if (err != hipSuccess) return fail(MPE_EHIP, "mpe_set_critic: %s", hipGetErrorString(err));
   e->has_critic = true;
   return MPE_OK;
@@ -254,8 +254,7 @@ int mpe_rollout_ac(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, fl
   if (!e->ready) return fail(MPE_ESTATE, "mpe_rollout_ac: call mpe_reset or mpe_set_state first");
   if (!e->has_policy || !e->has_critic)
     return fail(MPE_ESTATE, "mpe_rollout_ac: needs mpe_set_policy and mpe_set_critic first");
-  if (e->cfg.weight_dtype != MPE_WEIGHTS_FP32 || !f32_supported(e->N, e->H))
-    return fail(MPE_EINVAL, "mpe_rollout_ac: unsupported shape");
+  if (!f32_supported(e->N, e->H)) return fail(MPE_EINVAL, "mpe_rollout_ac: unsupported shape");
   for (const float* p : {obs_traj, logp_traj, value_traj, rew_traj, last_obs, last_value})
     if (p && !aligned16(p)) return fail(MPE_EINVAL, "mpe_rollout_ac: float outputs must be 16-byte aligned");
   if (uint64_t(e->abs_step) + uint64_t(T) > 0xFFFFFFFFull)
@@ -277,7 +276,8 @@ int mpe_rollout_ac(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, fl
   A.value_traj = value_traj;
   A.last_value = last_value;
   const char* why = nullptr;
-  hipError_t err = launch_rollout_ac_f32(e->N, A, e->pol, e->critic, static_cast<hipStream_t>(stream), &why);
+  hipError_t err = launch_rollout_ac_f32(e->N, e->cfg.weight_dtype == MPE_WEIGHTS_BF16, A, e->pol, e->critic,
+                                         static_cast<hipStream_t>(stream), &why);
   if (why) return fail(MPE_EINVAL, "mpe_rollout_ac: %s", why);
   if (err != hipSuccess) return fail(MPE_EHIP, "mpe_rollout_ac: %s", hipGetErrorString(err));
   MPE_HIP(hipGetLastError());

@@ -51,12 +51,12 @@ hipError_t pack_policy_wide(PolicyBuffers& pb, int N, int H, int R, const float*
                             const float* W2, const float* b2, const float* W3, const float* b3, hipStream_t s);
 hipError_t launch_rollout_policy_wide(int N, int H, const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s,
                                       const char** why);
-bool f32_supported(int N, int H);                        // fp32 headline kernel (H = 64, N <= 3)
+bool f32_supported(int N, int H);                        // headline kernel (H = 64, N <= 3), fp32 or bf16 weights
 hipError_t pack_policy_f32(PolicyBuffers& pb, int N, int R, const float* W1, const float* b1, const float* W2,
-                           const float* b2, const float* W3, const float* b3, int nout, hipStream_t s);
-hipError_t launch_rollout_ac_f32(int N, const RolloutArgs& A, const PolicyBuffers& pb, const PolicyBuffers& critic,
-                                 hipStream_t s, const char** why);
-hipError_t launch_rollout_policy_f32(int N, const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s,
+                           const float* b2, const float* W3, const float* b3, int nout, bool bf16, hipStream_t s);
+hipError_t launch_rollout_ac_f32(int N, bool bf16, const RolloutArgs& A, const PolicyBuffers& pb,
+                                 const PolicyBuffers& critic, hipStream_t s, const char** why);
+hipError_t launch_rollout_policy_f32(int N, bool bf16, const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s,
                                      const char** why);
 hipError_t ensure_policy_bytes(PolicyBuffers& pb, size_t bytes);
 

@@ -24,13 +24,13 @@ void free_policy(PolicyBuffers& pb) {
 }
 
 static const char* kUnsupported =
-    "unsupported policy shape: need (num_agents, hidden, dtype) in {(1..3, 64, fp32), (10, 128, bf16)}";
+    "unsupported policy shape: need (num_agents, hidden, dtype) in {(1..3, 64, fp32 or bf16), (10, 128, bf16)}";
 
 hipError_t pack_policy(PolicyBuffers& pb, int N, int H, int R, int weight_dtype, const float* W1,
                        const float* b1, const float* W2, const float* b2, const float* W3,
                        const float* b3, hipStream_t s, const char** why) {
   if (weight_dtype == 1 && wide_supported(N, H)) return pack_policy_wide(pb, N, H, R, W1, b1, W2, b2, W3, b3, s);
-  if (weight_dtype == 0 && f32_supported(N, H)) return pack_policy_f32(pb, N, R, W1, b1, W2, b2, W3, b3, 5, s);
+  if (f32_supported(N, H)) return pack_policy_f32(pb, N, R, W1, b1, W2, b2, W3, b3, 5, weight_dtype == 1, s);
   *why = kUnsupported;
   return hipSuccess;
 }
@@ -38,7 +38,7 @@ hipError_t pack_policy(PolicyBuffers& pb, int N, int H, int R, int weight_dtype,
 hipError_t launch_rollout_policy(int N, int H, int weight_dtype, const RolloutArgs& A,
                                  const PolicyBuffers& pb, hipStream_t s, const char** why) {
   if (weight_dtype == 1 && wide_supported(N, H)) return launch_rollout_policy_wide(N, H, A, pb, s, why);
-  if (weight_dtype == 0 && f32_supported(N, H)) return launch_rollout_policy_f32(N, A, pb, s, why);
+  if (f32_supported(N, H)) return launch_rollout_policy_f32(N, weight_dtype == 1, A, pb, s, why);
   *why = kUnsupported;
   return hipSuccess;
 }

@@ -23,9 +23,11 @@
 // 64-env sync group (the block barrier for 64-env blocks, an arrival counter in LDS for the
 // 256-env blocks of four independent groups).
 //
-// The same kernel also serves the mixed per-agent reward (PER_AGENT) and the actor-critic
-// rollout (AC: a second pass of the tile code over a critic's packed image, log-probability of
-// the sampled action).
+// The same kernel also serves the mixed per-agent reward (PER_AGENT), the actor-critic rollout
+// (AC: a second pass of the tile code over a critic's packed image, log-probability of the
+// sampled action) and the bf16 variant of the same shapes (BF: weights and layer inputs rounded
+// to bf16, nearest even, fp32 accumulation -- one matrix instruction per product instead of
+// six, no operand split; policy_pair_bf).
 #include "mpe_policy_common.h"
 
 namespace mpe {
@@ -68,18 +70,25 @@ __device__ __forceinline__ uint32_t pack_hi16(uint32_t a, uint32_t b) {
 //                                 terms of the 5 outputs (l3_row_* below), so ONE A operand meets
 //                                 the three activation terms in three instructions per K slice
 //   bias b1*pre [64], b2*pre [64], b3 [16] fp32 (N >= 2: b3 in the h-term row of each output)
-struct Pk {
+//
+// bf16 variant (BF): one term per weight, rounded to bf16 (nearest even), nothing pre-scaled:
+//   W1A [m 4][lane 64]  (K positions 16..31 are zero), W2A [m 4][s 2][lane 64], W3A [s 2][lane 64]
+//   (5 outputs padded to 16), bias b1 [64], b2 [64], b3 [16] fp32
+template <bool BF>
+struct PkT {
   static constexpr size_t OFF_W1A = 0;
-  static constexpr size_t W1A_BYTES = 4 * 2 * 64 * 16;
+  static constexpr size_t W1A_BYTES = BF ? 4 * 64 * 16 : 4 * 2 * 64 * 16;
   static constexpr size_t OFF_W2A = OFF_W1A + W1A_BYTES;
-  static constexpr size_t W2A_BYTES = 4 * 2 * 3 * 64 * 16;
+  static constexpr size_t W2A_BYTES = BF ? 4 * 2 * 64 * 16 : 4 * 2 * 3 * 64 * 16;
   static constexpr size_t OFF_W3A = OFF_W2A + W2A_BYTES;
-  static constexpr size_t W3A_BYTES = 2 * 3 * 64 * 16;
+  static constexpr size_t W3A_BYTES = BF ? 2 * 64 * 16 : 2 * 3 * 64 * 16;
   static constexpr size_t OFF_BIAS = OFF_W3A + W3A_BYTES;
   static constexpr size_t BIAS_BYTES = (2 * kH + 16) * 4;
   static constexpr size_t RUN_BYTES = OFF_BIAS + BIAS_BYTES;
   static constexpr size_t LDS_BYTES = OFF_W3A;   // W1A + W2A live in LDS, W3A in registers
 };
+using Pk = PkT<false>;
+using PkB = PkT<true>;
 
 // Layer 3 with the weight terms along the output rows (N >= 2; the logits of a row then need 7
 // floats of scratch in its observation row, which has 4N + 2 rewritten columns).  Accumulator
@@ -420,16 +429,181 @@ __device__ __forceinline__ void policy_pair(const uint8_t* __restrict__ wsm, con
 }
 
 // LDS plan (bytes).
+// ------------------------------------------------------------------------------ bf16 variant
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return uint16_t((u >> 16) | 0x40u);  // NaN stays NaN
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return uint16_t(u >> 16);
+}
+
+// One thread per packed bf16 weight or bias value of one run; nout as in pack_split_kernel.
+template <int N>
+__global__ void pack_bf16_kernel(uint8_t* __restrict__ packed, const float* __restrict__ W1,
+                                 const float* __restrict__ b1, const float* __restrict__ W2,
+                                 const float* __restrict__ b2, const float* __restrict__ W3,
+                                 const float* __restrict__ b3, int nout) {
+  constexpr int D = 6 * N, KIN = 4 * N + 2;
+  const int run = blockIdx.y;
+  uint8_t* out = packed + size_t(run) * PkB::RUN_BYTES;
+  W1 += size_t(run) * D * kH;
+  b1 += size_t(run) * kH;
+  W2 += size_t(run) * kH * kH;
+  b2 += size_t(run) * kH;
+  W3 += size_t(run) * kH * nout;
+  b3 += size_t(run) * nout;
+  constexpr int n1 = 4 * 64 * 8, n2 = 4 * 2 * 64 * 8, n3 = 2 * 64 * 8, nb = 2 * kH + 16;
+  int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < n1) {   // [m][lane][e]; k = 8 gq + e for gq < 2, zero above
+    const int e = idx % 8, lane = (idx / 8) % 64, m = idx / 512;
+    const int gq = lane / 16, k = 8 * gq + e, o = 16 * m + lane % 16;
+    reinterpret_cast<uint16_t*>(out + PkB::OFF_W1A)[idx] = f32_to_bf16_rne((gq < 2 && k < KIN) ? W1[size_t(k) * kH + o] : 0.0f);
+    return;
+  }
+  idx -= n1;
+  if (idx < n2) {   // [m][s][lane][e]
+    const int e = idx % 8, lane = (idx / 8) % 64, s = (idx / 512) % 2, m = idx / 1024;
+    reinterpret_cast<uint16_t*>(out + PkB::OFF_W2A)[idx] = f32_to_bf16_rne(W2[size_t(hidden_k(s, lane / 16, e)) * kH + 16 * m + lane % 16]);
+    return;
+  }
+  idx -= n2;
+  if (idx < n3) {   // [s][lane][e]
+    const int e = idx % 8, lane = (idx / 8) % 64, s = idx / 512, o = lane % 16;
+    reinterpret_cast<uint16_t*>(out + PkB::OFF_W3A)[idx] = f32_to_bf16_rne(o < nout ? W3[size_t(hidden_k(s, lane / 16, e)) * nout + o] : 0.0f);
+    return;
+  }
+  idx -= n3;
+  if (idx < nb) {
+    float v;
+    if (idx < kH) v = b1[idx];
+    else if (idx < 2 * kH) v = b2[idx - kH];
+    else v = (idx - 2 * kH) < nout ? b3[idx - 2 * kH] : 0.0f;
+    reinterpret_cast<float*>(out + PkB::OFF_BIAS)[idx] = v;
+  }
+}
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// Round two floats to bf16 (nearest even) and pack them: low half <- a.
+__device__ __forceinline__ uint32_t pack_bf16_rne(float a, float b) {
+  const f32x2 v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// tanh of 8 accumulator values (hidden tiles 2s, 2s+1 of one batch tile) rounded to bf16: the B
+// operand of K slice s of the next layer.
+__device__ __forceinline__ bf16x8 tanh_pack_bf(const f32x4& a0, const f32x4& a1) {
+  u32x4 p;
+  p[0] = pack_bf16_rne(fast_tanh(a0[0]), fast_tanh(a0[1]));
+  p[1] = pack_bf16_rne(fast_tanh(a0[2]), fast_tanh(a0[3]));
+  p[2] = pack_bf16_rne(fast_tanh(a1[0]), fast_tanh(a1[1]));
+  p[3] = pack_bf16_rne(fast_tanh(a1[2]), fast_tanh(a1[3]));
+  return __builtin_bit_cast(bf16x8, p);
+}
+
+// bf16 policy forward of two 16-row tiles X and Y (same interface as policy_pair): weights and
+// layer inputs bf16, fp32 accumulation and tanh.  Logits of row j go to cols 0..4 of that row.
+template <int N, bool VALUE = false>
+__device__ __forceinline__ void policy_pair_bf(const uint8_t* __restrict__ wsm, const float* __restrict__ bias,
+                                               const W3Terms& w3, float* __restrict__ rowsX,
+                                               float* __restrict__ rowsY, int lane,
+                                               float* __restrict__ valX = nullptr, float* __restrict__ valY = nullptr) {
+  constexpr int D = 6 * N;
+  const int j = lane & 15, gq = lane >> 4;
+  {
+    uint32_t zero = 0;   // see policy_pair: keeps the LDS weight reads inside the step loop
+    asm volatile("" : "+v"(zero));
+    wsm += zero;
+    bias += zero;
+  }
+  const bf16x8* w1 = reinterpret_cast<const bf16x8*>(wsm + PkB::OFF_W1A);  // [m][lane]
+  const bf16x8* w2 = reinterpret_cast<const bf16x8*>(wsm + PkB::OFF_W2A);  // [m][s][lane]
+  // layer-1 B operands: inputs 8 (gq & 1) .. + 7 of the row; lane groups 2, 3 meet zero weights
+  bf16x8 bx, by;
+  {
+    const float2* xs = reinterpret_cast<const float2*>(rowsX + j * D + 8 * (gq & 1));
+    const float2* ys = reinterpret_cast<const float2*>(rowsY + j * D + 8 * (gq & 1));
+    u32x4 px, py;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float2 xv = xs[q], yv = ys[q];
+      px[q] = pack_bf16_rne(xv.x, xv.y);
+      py[q] = pack_bf16_rne(yv.x, yv.y);
+    }
+    bx = __builtin_bit_cast(bf16x8, px);
+    by = __builtin_bit_cast(bf16x8, py);
+  }
+  f32x4 accX[4], accY[4];
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    accX[m] = *reinterpret_cast<const f32x4*>(bias + 16 * m + 4 * gq);
+    accY[m] = accX[m];
+  }
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    const bf16x8 a = w1[m * 64 + lane];
+    accX[m] = MPE_MFMA_BF(a, bx, accX[m]);
+    accY[m] = MPE_MFMA_BF(a, by, accY[m]);
+  }
+  bf16x8 hx[2], hy[2];
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    hx[s] = tanh_pack_bf(accX[2 * s], accX[2 * s + 1]);
+    hy[s] = tanh_pack_bf(accY[2 * s], accY[2 * s + 1]);
+  }
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    accX[m] = *reinterpret_cast<const f32x4*>(bias + kH + 16 * m + 4 * gq);
+    accY[m] = accX[m];
+  }
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+      const bf16x8 a = w2[(m * 2 + s) * 64 + lane];
+      accX[m] = MPE_MFMA_BF(a, hx[s], accX[m]);
+      accY[m] = MPE_MFMA_BF(a, hy[s], accY[m]);
+    }
+  }
+  f32x4 zX = *reinterpret_cast<const f32x4*>(bias + 2 * kH + 4 * gq);
+  f32x4 zY = zX;
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    zX = MPE_MFMA_BF(w3.s[s].h, tanh_pack_bf(accX[2 * s], accX[2 * s + 1]), zX);
+    zY = MPE_MFMA_BF(w3.s[s].h, tanh_pack_bf(accY[2 * s], accY[2 * s + 1]), zY);
+  }
+  // lane (j, gq) holds outputs 4gq + r of row j: outputs 0..3 in group 0, output 4 in group 1
+  if constexpr (VALUE) {
+    if (gq == 0) {
+      valX[j] = zX[0];
+      valY[j] = zY[0];
+    }
+  } else {
+    if (gq == 0) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        rowsX[j * D + r] = zX[r];
+        rowsY[j * D + r] = zY[r];
+      }
+    } else if (gq == 1) {
+      rowsX[j * D + 4] = zX[0];
+      rowsY[j * D + 4] = zY[0];
+    }
+  }
+}
+
 // Plain rollout: W1A + W2A and the biases of the policy (its W3A lives in registers).
 // Actor-critic rollout (AC): the whole packed image of the policy and of the critic (W1A, W2A,
 // W3A, biases each), a value per row, and one arrival counter per 64-env sync group.
-template <int N, int EB, bool AC = false>
+template <int N, int EB, bool AC = false, bool BF = false>
 struct SmemF32 {
+  using P = PkT<BF>;
   static constexpr int D = 6 * N;
   static constexpr int ROWS = EB * N;
-  static constexpr size_t OFF_BIAS = AC ? Pk::OFF_BIAS : Pk::LDS_BYTES;
-  static constexpr size_t OFF_CRITIC = OFF_BIAS + Pk::BIAS_BYTES;    // AC: the critic's packed image
-  static constexpr size_t OFF_OBS = OFF_CRITIC + (AC ? Pk::RUN_BYTES : 0);
+  static constexpr size_t OFF_BIAS = AC ? P::OFF_BIAS : P::LDS_BYTES;
+  static constexpr size_t OFF_CRITIC = OFF_BIAS + P::BIAS_BYTES;     // AC: the critic's packed image
+  static constexpr size_t OFF_OBS = OFF_CRITIC + (AC ? P::RUN_BYTES : 0);
   static constexpr size_t OBS = size_t(ROWS) * D * 4 + 64;           // + zeroed tail: layer 1 reads 16 cols
   static constexpr size_t OFF_NEWPOS = OFF_OBS + OBS;                // [2][ROWS] float2, by step parity
   static constexpr size_t OFF_VALUE = OFF_NEWPOS + size_t(2) * ROWS * 8;   // AC: [ROWS] float
@@ -455,12 +629,13 @@ __device__ __forceinline__ void group_barrier(uint32_t* arrived, uint32_t target
 // is evaluated on every observation acted on, and the log-probability of the sampled action is
 // recorded (paper Sec. 3.2: IPPO / MAPPO; App. G: two tanh layers of width 64).  A block is then
 // EB / 64 independent 64-env sync groups that share the two staged networks.
-template <int N, int EB, int MINW, bool PER_AGENT, bool AC>
+template <int N, int EB, int MINW, bool PER_AGENT, bool AC, bool BF>
 __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
                                                                           const uint8_t* __restrict__ packed_critic,
                                                                           int per_run_weights, uint32_t groups,
                                                                           uint32_t groups_per_xcd) {
-  using M = SmemF32<N, EB, AC>;
+  using M = SmemF32<N, EB, AC, BF>;
+  using P = PkT<BF>;
 
   constexpr int D = 6 * N, ROWS = EB * N, THREADS = ROWS;
   static_assert(THREADS % 64 == 0, "block must be whole wavefronts");
@@ -470,7 +645,7 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
   float* tile = reinterpret_cast<float*>(smem + M::OFF_OBS);
   float2* newpos = reinterpret_cast<float2*>(smem + M::OFF_NEWPOS);
   const uint8_t* csm = smem + M::OFF_CRITIC;                                         // AC only
-  const float* cbias = reinterpret_cast<const float*>(smem + M::OFF_CRITIC + Pk::OFF_BIAS);
+  const float* cbias = reinterpret_cast<const float*>(smem + M::OFF_CRITIC + P::OFF_BIAS);
   float* values = reinterpret_cast<float*>(smem + M::OFF_VALUE);
 
   const int tid = threadIdx.x;
@@ -495,16 +670,16 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
   const int wave_rows = min(max(nvalid * N - wave * 64, 0), 64);
 
   // ---- stage this block's weights (the run of its first env): W1A, W2A, biases in LDS; W3A in registers
-  const uint8_t* run_weights = packed + (per_run_weights ? size_t(uint32_t(g0) / A.E) * Pk::RUN_BYTES : 0);
+  const uint8_t* run_weights = packed + (per_run_weights ? size_t(uint32_t(g0) / A.E) * P::RUN_BYTES : 0);
   // A operands of layer 3 from a packed image (global memory or LDS)
   auto load_w3 = [&](const uint8_t* image) {
     W3Terms w;
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-      if constexpr (L3<N>::kRowTerms) {
-        w.s[s].h = reinterpret_cast<const bf16x8*>(image + Pk::OFF_W3A)[s * 64 + lane];
+      if constexpr (BF || L3<N>::kRowTerms) {
+        w.s[s].h = reinterpret_cast<const bf16x8*>(image + P::OFF_W3A)[s * 64 + lane];
       } else {
-        const bf16x8* src = reinterpret_cast<const bf16x8*>(image + Pk::OFF_W3A) + s * 3 * 64 + lane;
+        const bf16x8* src = reinterpret_cast<const bf16x8*>(image + P::OFF_W3A) + s * 3 * 64 + lane;
         w.s[s].h = src[0];
         w.s[s].m = src[64];
         w.s[s].l = src[128];
@@ -519,16 +694,16 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
     const uint4* src = reinterpret_cast<const uint4*>(run_weights);
     uint4* dst = reinterpret_cast<uint4*>(wsm);
     if constexpr (AC) {
-      for (int k = tid; k < int(Pk::RUN_BYTES / 16); k += THREADS) dst[k] = src[k];
+      for (int k = tid; k < int(P::RUN_BYTES / 16); k += THREADS) dst[k] = src[k];
       const uint4* csrc = reinterpret_cast<const uint4*>(
-          packed_critic + (per_run_weights ? size_t(uint32_t(g0) / A.E) * Pk::RUN_BYTES : 0));
+          packed_critic + (per_run_weights ? size_t(uint32_t(g0) / A.E) * P::RUN_BYTES : 0));
       uint4* cdst = reinterpret_cast<uint4*>(smem + M::OFF_CRITIC);
-      for (int k = tid; k < int(Pk::RUN_BYTES / 16); k += THREADS) cdst[k] = csrc[k];
+      for (int k = tid; k < int(P::RUN_BYTES / 16); k += THREADS) cdst[k] = csrc[k];
     } else {
-      for (int k = tid; k < int(Pk::LDS_BYTES / 16); k += THREADS) dst[k] = src[k];
-      const uint4* bsrc = reinterpret_cast<const uint4*>(run_weights + Pk::OFF_BIAS);
+      for (int k = tid; k < int(P::LDS_BYTES / 16); k += THREADS) dst[k] = src[k];
+      const uint4* bsrc = reinterpret_cast<const uint4*>(run_weights + P::OFF_BIAS);
       uint4* bdst = reinterpret_cast<uint4*>(bias);
-      for (int k = tid; k < int(Pk::BIAS_BYTES / 16); k += THREADS) bdst[k] = bsrc[k];
+      for (int k = tid; k < int(P::BIAS_BYTES / 16); k += THREADS) bdst[k] = bsrc[k];
     }
     if (tid < 16) tile[ROWS * D + tid] = 0.0f;
     if constexpr (EB > 64) {
@@ -600,7 +775,8 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
       float* rows = tile + (wave * 64 + pr * 32) * D;
       float* vals = values + wave * 64 + pr * 32;
       const W3Terms wc = load_w3(csm);
-      policy_pair<N, true>(csm, cbias, wc, rows, rows + 16 * D, lane, vals, vals + 16);
+      if constexpr (BF) policy_pair_bf<N, true>(csm, cbias, wc, rows, rows + 16 * D, lane, vals, vals + 16);
+      else policy_pair<N, true>(csm, cbias, wc, rows, rows + 16 * D, lane, vals, vals + 16);
     }
   };
 
@@ -624,13 +800,14 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
     for (int pr = 0; pr < 2; ++pr) {
       float* rows = tile + (wave * 64 + pr * 32) * D;
       if constexpr (AC) w3 = load_w3(wsm);
-      policy_pair<N>(wsm, bias, w3, rows, rows + 16 * D, lane);
+      if constexpr (BF) policy_pair_bf<N>(wsm, bias, w3, rows, rows + 16 * D, lane);
+      else policy_pair<N>(wsm, bias, w3, rows, rows + 16 * D, lane);
     }
     wave_sync();
     float z[kNumActions];
 #pragma unroll
     for (int k = 0; k < kNumActions; ++k) z[k] = tile[tid * D + k];
-    if constexpr (L3<N>::kRowTerms) z[4] = (z[4] + tile[tid * D + 5]) + tile[tid * D + 6];
+    if constexpr (!BF && L3<N>::kRowTerms) z[4] = (z[4] + tile[tid * D + 5]) + tile[tid * D + 6];
     const uint32_t act = gumbel_argmax(z, A.seed, run, env, step, uint32_t(i));
     if (act_base) {
       if (valid) act_base[row_off] = uint8_t(act);
@@ -778,10 +955,10 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
   }
 }
 
-template <int N, int EB, int MINW, bool PER_AGENT, bool AC = false>
+template <int N, int EB, int MINW, bool PER_AGENT, bool AC, bool BF>
 hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s, const void* critic = nullptr) {
-  using M = SmemF32<N, EB, AC>;
-  auto kern = rollout_policy_f32_kernel<N, EB, MINW, PER_AGENT, AC>;
+  using M = SmemF32<N, EB, AC, BF>;
+  auto kern = rollout_policy_f32_kernel<N, EB, MINW, PER_AGENT, AC, BF>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -798,12 +975,17 @@ hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream
 
 template <int N>
 hipError_t pack_impl(PolicyBuffers& pb, int R, const float* W1, const float* b1, const float* W2,
-                     const float* b2, const float* W3, const float* b3, int nout, hipStream_t s) {
-  if (hipError_t e = ensure_policy_bytes(pb, size_t(R) * Pk::RUN_BYTES); e != hipSuccess) return e;
-  constexpr int total = 4 * 64 * 8 + 4 * 2 * 64 * 8 + 2 * 64 * 8 + 2 * kH + 16;
+                     const float* b2, const float* W3, const float* b3, int nout, bool bf16, hipStream_t s) {
+  const size_t run_bytes = bf16 ? PkB::RUN_BYTES : Pk::RUN_BYTES;
+  if (hipError_t e = ensure_policy_bytes(pb, size_t(R) * run_bytes); e != hipSuccess) return e;
+  constexpr int total = 4 * 64 * 8 + 4 * 2 * 64 * 8 + 2 * 64 * 8 + 2 * kH + 16;   // threads: one per weight / bias
   dim3 grid((total + 255) / 256, R);
-  hipLaunchKernelGGL(pack_split_kernel<N>, grid, dim3(256), 0, s, static_cast<uint8_t*>(pb.packed), W1, b1, W2,
-                     b2, W3, b3, nout);
+  if (bf16)
+    hipLaunchKernelGGL(pack_bf16_kernel<N>, grid, dim3(256), 0, s, static_cast<uint8_t*>(pb.packed), W1, b1, W2,
+                       b2, W3, b3, nout);
+  else
+    hipLaunchKernelGGL(pack_split_kernel<N>, grid, dim3(256), 0, s, static_cast<uint8_t*>(pb.packed), W1, b1, W2,
+                       b2, W3, b3, nout);
   return hipGetLastError();
 }
 
@@ -827,20 +1009,21 @@ uint32_t compute_units() {
 // sync groups (12 wavefronts, per-group arrival counters) fill the chip in whole rounds with no
 // tail of single resident blocks: measured 2.31 ms against 2.37 ms at 65,536 envs x 3 agents.
 // (Two 128-env blocks per CU with ONE block barrier among six wavefronts were slower: 2.97 ms.)
-template <int N>
+template <int N, bool BF>
 hipError_t launch_n(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s, const char** why) {
   const bool one_run = A.TE == A.E;
+  const bool per_agent = A.ph.reward_mode == 1;
   if (one_run && A.TE / 256 >= compute_units())
-    return A.ph.reward_mode == 1 ? rollout_impl<N, 256, 3, true>(A, pb, s) : rollout_impl<N, 256, 3, false>(A, pb, s);
+    return per_agent ? rollout_impl<N, 256, 3, true, false, BF>(A, pb, s) : rollout_impl<N, 256, 3, false, false, BF>(A, pb, s);
   if (one_run || A.E % 64 == 0)
-    return A.ph.reward_mode == 1 ? rollout_impl<N, 64, 3, true>(A, pb, s) : rollout_impl<N, 64, 3, false>(A, pb, s);
+    return per_agent ? rollout_impl<N, 64, 3, true, false, BF>(A, pb, s) : rollout_impl<N, 64, 3, false, false, BF>(A, pb, s);
   *why = "with several runs, num_envs per run must be a multiple of 64";
   return hipSuccess;
 }
 
 // Actor-critic rollout: 256 envs per block = four 64-env sync groups (12 wavefronts at N = 3)
-// around one staged copy of the two networks (79 KB of the 160 KB LDS).
-template <int N>
+// around one staged copy of the two networks (79 KB of the 160 KB LDS for fp32 weights).
+template <int N, bool BF>
 hipError_t launch_ac_n(const RolloutArgs& A, const PolicyBuffers& pb, const PolicyBuffers& critic, hipStream_t s,
                        const char** why) {
   const bool one_run = A.TE == A.E;
@@ -848,8 +1031,8 @@ hipError_t launch_ac_n(const RolloutArgs& A, const PolicyBuffers& pb, const Poli
     *why = "actor-critic rollout with several runs: num_envs per run must be a multiple of 256";
     return hipSuccess;
   }
-  return A.ph.reward_mode == 1 ? rollout_impl<N, 256, 3, true, true>(A, pb, s, critic.packed)
-                               : rollout_impl<N, 256, 3, false, true>(A, pb, s, critic.packed);
+  return A.ph.reward_mode == 1 ? rollout_impl<N, 256, 3, true, true, BF>(A, pb, s, critic.packed)
+                               : rollout_impl<N, 256, 3, false, true, BF>(A, pb, s, critic.packed);
 }
 
 }  // namespace
@@ -857,33 +1040,31 @@ hipError_t launch_ac_n(const RolloutArgs& A, const PolicyBuffers& pb, const Poli
 bool f32_supported(int N, int H) { return H == kH && N >= 1 && N <= 3; }
 
 hipError_t pack_policy_f32(PolicyBuffers& pb, int N, int R, const float* W1, const float* b1, const float* W2,
-                           const float* b2, const float* W3, const float* b3, int nout, hipStream_t s) {
+                           const float* b2, const float* W3, const float* b3, int nout, bool bf16, hipStream_t s) {
   switch (N) {
-    case 1: return pack_impl<1>(pb, R, W1, b1, W2, b2, W3, b3, nout, s);
-    case 2: return pack_impl<2>(pb, R, W1, b1, W2, b2, W3, b3, nout, s);
-    case 3: return pack_impl<3>(pb, R, W1, b1, W2, b2, W3, b3, nout, s);
+    case 1: return pack_impl<1>(pb, R, W1, b1, W2, b2, W3, b3, nout, bf16, s);
+    case 2: return pack_impl<2>(pb, R, W1, b1, W2, b2, W3, b3, nout, bf16, s);
+    case 3: return pack_impl<3>(pb, R, W1, b1, W2, b2, W3, b3, nout, bf16, s);
     default: return hipErrorInvalidValue;
   }
 }
 
-hipError_t launch_rollout_ac_f32(int N, const RolloutArgs& A, const PolicyBuffers& pb, const PolicyBuffers& critic,
-                                 hipStream_t s, const char** why) {
-  switch (N) {
-    case 1: return launch_ac_n<1>(A, pb, critic, s, why);
-    case 2: return launch_ac_n<2>(A, pb, critic, s, why);
-    case 3: return launch_ac_n<3>(A, pb, critic, s, why);
-    default: return hipErrorInvalidValue;
+#define MPE_BY_N_AND_DTYPE(FN, ...)                                              \
+  switch (N) {                                                                   \
+    case 1: return bf16 ? FN<1, true>(__VA_ARGS__) : FN<1, false>(__VA_ARGS__);  \
+    case 2: return bf16 ? FN<2, true>(__VA_ARGS__) : FN<2, false>(__VA_ARGS__);  \
+    case 3: return bf16 ? FN<3, true>(__VA_ARGS__) : FN<3, false>(__VA_ARGS__);  \
+    default: return hipErrorInvalidValue;                                        \
   }
+
+hipError_t launch_rollout_ac_f32(int N, bool bf16, const RolloutArgs& A, const PolicyBuffers& pb,
+                                 const PolicyBuffers& critic, hipStream_t s, const char** why) {
+  MPE_BY_N_AND_DTYPE(launch_ac_n, A, pb, critic, s, why)
 }
 
-hipError_t launch_rollout_policy_f32(int N, const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s,
+hipError_t launch_rollout_policy_f32(int N, bool bf16, const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s,
                                      const char** why) {
-  switch (N) {
-    case 1: return launch_n<1>(A, pb, s, why);
-    case 2: return launch_n<2>(A, pb, s, why);
-    case 3: return launch_n<3>(A, pb, s, why);
-    default: return hipErrorInvalidValue;
-  }
+  MPE_BY_N_AND_DTYPE(launch_n, A, pb, s, why)
 }
 
 }  // namespace mpe

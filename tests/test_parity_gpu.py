@@ -337,6 +337,27 @@ def test_policy_bf16_wide(mods):
     env.close()
 
 
+@pytest.mark.parametrize("E,N,R,T", [(4096, 3, 1, 30), (200, 3, 1, 40), (100, 2, 1, 30), (64, 1, 1, 30), (64, 3, 3, 20)])
+def test_policy_bf16_small_shapes(mods, E, N, R, T):
+    """bf16 weights and layer inputs for the 1..3-agent shapes (the headline kernel's bf16 variant),
+    against the oracle's bf16 mode (same rounding points)."""
+    say("policy bf16 E=%d N=%d R=%d H=64" % (E, N, R))
+    env, orc = _policy_pair(mods, E, N, R, 64, 1, wseed=14)
+    frac, total, worst = _teacher_forced(env, orc, seed=8, T=T)
+    say("  bf16 agreement %.6f over %d samples; worst step error %.2e" % (frac, total, worst))
+    assert (1.0 - frac) * total <= max(2, 1e-4 * total)
+
+    def make_oracle():
+        o = mods[1](Hp.oracle_config(E, N, R, 64, 1), threads=8)
+        o.set_policy(*synth.policy_weights_with_bias(14, R, 6 * N, 64))
+        return o
+
+    frac2, ww, n_ill, n_all = _free_running(env, orc, 6, 50, make_oracle)
+    say("  bf16 identical episodes %.4f ; worst error %.2e" % (frac2, ww))
+    assert frac2 >= 0.99
+    env.close()
+
+
 @pytest.mark.parametrize("E,R", [(100, 1), (20, 1), (64, 3)])
 def test_policy_bf16_wide_ragged_and_per_run(mods, E, R):
     """Sizes that leave the second sync group of a block partly or wholly empty, a block smaller
