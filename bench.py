@@ -163,7 +163,7 @@ def main():
         mixed = {"fused_agent_steps_per_s": agent_steps / (w3 / k), "fused_kernel_ms_avg": float(np.mean(k3)),
                  "env_only_agent_steps_per_s": agent_steps / (w4 / k), "env_only_kernel_ms_avg": float(np.mean(k4)),
                  "bytes_per_env_step": bytes_per_env_step(N, D) + 4 * (N - 1),
-                 "note": "MPE_REWARD_MIXED, local_ratio 0.5; env-only uses the general one-wave-per-64-envs kernel"}
+                 "note": "MPE_REWARD_MIXED, local_ratio 0.5; env-only at N <= 3 uses the general one-wave-per-64-envs kernel"}
         env3.close()
         del b3
 
@@ -242,7 +242,8 @@ def main():
             "hbm_achieved_GBs": fused_gbs,
         },
         "env_only": {
-            "kernel": ("rollout_uniform_ws_kernel" if N <= 3 else "rollout_uniform_kernel")
+            "kernel": ("rollout_uniform_ws_kernel" if N <= 3 else
+                       "rollout_policy_kernel<..., UNIFORM> (lane per agent)" if N == 10 else "rollout_uniform_kernel")
                       + " (seeded uniform actions, one launch per step)",
             "agent_steps_per_s": agent_steps / (wall2 / args.steps),
             "env_steps_per_s": TE * T / (wall2 / args.steps),

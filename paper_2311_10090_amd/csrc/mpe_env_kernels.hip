@@ -342,6 +342,9 @@ void launch_step(int N, const StatePtrs& st, const Phys& ph, uint32_t TE, uint32
 }
 
 void launch_rollout_uniform(int N, const RolloutArgs& A, hipStream_t s) {
+  // many agents: one lane per agent (the wide fused kernel without its policy) writes contiguous
+  // pieces of the trajectory; the lane-per-env kernels below write one agent's rows at a time
+  if (uniform_wide_supported(N) && launch_rollout_uniform_wide(N, A, s) == hipSuccess) return;
   MPE_DISPATCH_N(N, EnvLaunch<kN>::rollout(A, s));
 }
 

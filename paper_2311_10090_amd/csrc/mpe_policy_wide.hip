@@ -128,14 +128,16 @@ __global__ void pack_policy_kernel(uint8_t* __restrict__ packed, const float* __
 }
 
 // LDS plan of one block (bytes).
-template <int N, int H, int EB>
+// UNIFORM (no policy: seeded uniform actions): no weights; the stage holds one 16-row tile of
+// observations on its way to the trajectory.
+template <int N, int H, int EB, bool UNIFORM = false>
 struct Smem {
   using S = Shape<N, H>;
   static constexpr int ROWS = EB * N, WAVES = ROWS / 64;
-  static constexpr size_t WEIGHTS = S::OFF_BIAS;                   // W1A + W2A + W3A
+  static constexpr size_t WEIGHTS = UNIFORM ? 0 : S::OFF_BIAS;     // W1A + W2A + W3A
   static constexpr size_t OFF_BIAS = WEIGHTS;
-  static constexpr size_t STAGE_WAVE = size_t(64) * 5 * 4;         // the wave's logits [64][5]
-  static constexpr size_t OFF_STAGE = OFF_BIAS + S::BIAS_BYTES;
+  static constexpr size_t STAGE_WAVE = UNIFORM ? size_t(16) * S::D * 4 : size_t(64) * 5 * 4;   // else the wave's logits [64][5]
+  static constexpr size_t OFF_STAGE = OFF_BIAS + (UNIFORM ? 0 : S::BIAS_BYTES);
   static constexpr size_t OFF_NEWPOS = OFF_STAGE + WAVES * STAGE_WAVE;   // [2][ROWS] float2, by step parity
   static constexpr size_t OFF_DMIN = OFF_NEWPOS + size_t(2) * ROWS * 8;  // [2][ROWS] float,  by step parity
   static constexpr size_t OFF_LM = OFF_DMIN + size_t(2) * ROWS * 4;      // [EB][N] float2 landmark positions
@@ -264,12 +266,15 @@ __device__ __forceinline__ void policy_tile(const uint8_t* __restrict__ wsm, con
 }
 
 // PER_AGENT: rew_traj is [T][TE][N], the mixed per-agent reward; every lane stores its agent's.
-template <int N, int H, int EB, int MINW, bool PER_AGENT>
+// UNIFORM: no policy; every agent's action is the seeded uniform draw.  The kernel is then bound
+// by the trajectory stores, and the observation rows leave 16 at a time through the wave's LDS
+// stage as contiguous 3,840-byte pieces (per-lane stores of 240-byte rows sustain only ~3 TB/s).
+template <int N, int H, int EB, int MINW, bool PER_AGENT, bool UNIFORM>
 __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
                                                                       int per_run_weights, uint32_t groups,
                                                                       uint32_t groups_per_xcd) {
   using S = Shape<N, H>;
-  using M = Smem<N, H, EB>;
+  using M = Smem<N, H, EB, UNIFORM>;
   constexpr int D = S::D, KIN = S::KIN, ROWS = EB * N, THREADS = ROWS;
   constexpr int RF4 = D / 4;                 // 16-byte chunks of one observation row
   constexpr int PD = S::S1 * 16;             // dwords of one row as bf16 pairs, zero padded to whole K slices
@@ -307,8 +312,8 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
 
   // ---- stage this block's weights (the run of its first env) in LDS: the packed buffer is
   // W1A, W2A, W3A, biases in that order, and so is the LDS image
-  const uint8_t* run_weights = packed + (per_run_weights ? size_t(uint32_t(g0) / A.E) * S::RUN_BYTES : 0);
-  {
+  if constexpr (!UNIFORM) {
+    const uint8_t* run_weights = packed + (per_run_weights ? size_t(uint32_t(g0) / A.E) * S::RUN_BYTES : 0);
     const uint4* src = reinterpret_cast<const uint4*>(run_weights);
     uint4* dst = reinterpret_cast<uint4*>(wsm);
     for (int k = tid; k < int(S::RUN_BYTES / 16); k += THREADS) dst[k] = src[k];
@@ -359,7 +364,34 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
   };
   // Store this wavefront's rows to dst (its slot in a [env][N][D] slice).
   auto flush_rows = [&](const float (&o)[KIN], float* dst) {
-    if (lane < wave_rows) {
+    if constexpr (UNIFORM) {
+      v4f* st4 = reinterpret_cast<v4f*>(stage);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        wave_sync();  // the stage is free (previous readers done)
+        if ((lane >> 4) == c) {
+#pragma unroll
+          for (int q = 0; q < RF4; ++q) {
+            v4f v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = (4 * q + e < KIN) ? o[(4 * q + e < KIN) ? 4 * q + e : 0] : 0.0f;
+            st4[(lane & 15) * RF4 + q] = v;
+          }
+        }
+        wave_sync();
+        const int n4 = min(max(wave_rows - 16 * c, 0), 16) * RF4;   // 16-byte chunks of this tile that are valid
+        constexpr int kRounds = (16 * RF4 + 63) / 64;
+        v4f v[kRounds];
+#pragma unroll
+        for (int rd = 0; rd < kRounds; ++rd)
+          if (rd * 64 + lane < n4) v[rd] = st4[rd * 64 + lane];
+        v4f* d4 = reinterpret_cast<v4f*>(dst) + c * (16 * RF4);
+#pragma unroll
+        for (int rd = 0; rd < kRounds; ++rd)
+          if (rd * 64 + lane < n4) d4[rd * 64 + lane] = v[rd];
+      }
+      wave_sync();
+    } else if (lane < wave_rows) {
       v4f* d4 = reinterpret_cast<v4f*>(dst) + lane * RF4;
 #pragma unroll
       for (int q = 0; q < RF4; ++q) {
@@ -399,7 +431,16 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
   for (int t = 0; t < A.T; ++t, ++step) {
     // ---- observation row -> trajectory, and -> bf16 B operands of layer 1 for the wave's 4 tiles
     bf16x8 b1[4][S::S1];
-    {
+    uint32_t act;
+    if constexpr (UNIFORM) {
+      if (obs_p) {
+        float o[KIN];
+        build_obs(o);
+        flush_rows(o, obs_p);
+        obs_p += TE * (N * D);
+      }
+      act = word_to_action(philox4x32_10(env, step, uint32_t(i), kTagUniformAction, A.seed, run).x);
+    } else {
       float o[KIN];
       build_obs(o);
       if (obs_p) {
@@ -425,13 +466,15 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
       }
     }
     // ---- policy: four 16-row tiles per wavefront
+    if constexpr (!UNIFORM) {
 #pragma unroll
-    for (int c = 0; c < 4; ++c) policy_tile<N, H>(wsm, bias, b1[c], stage + c * 16 * 5, lane);
-    wave_sync();
-    float z[kNumActions];
+      for (int c = 0; c < 4; ++c) policy_tile<N, H>(wsm, bias, b1[c], stage + c * 16 * 5, lane);
+      wave_sync();
+      float z[kNumActions];
 #pragma unroll
-    for (int k = 0; k < kNumActions; ++k) z[k] = stage[lane * 5 + k];
-    const uint32_t act = gumbel_argmax(z, A.seed, run, env, step, uint32_t(i));
+      for (int k = 0; k < kNumActions; ++k) z[k] = stage[lane * 5 + k];
+      act = gumbel_argmax(z, A.seed, run, env, step, uint32_t(i));
+    }
     if (act_base) {
       if (valid) act_base[row_off] = uint8_t(act);
       act_base += TE * N;
@@ -552,10 +595,10 @@ hipError_t pack_impl(PolicyBuffers& pb, int R, const float* W1, const float* b1,
   return hipGetLastError();
 }
 
-template <int N, int H, int EB, int MINW, bool PER_AGENT>
+template <int N, int H, int EB, int MINW, bool PER_AGENT, bool UNIFORM = false>
 hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s) {
-  using M = Smem<N, H, EB>;
-  auto kern = rollout_policy_kernel<N, H, EB, MINW, PER_AGENT>;
+  using M = Smem<N, H, EB, UNIFORM>;
+  auto kern = rollout_policy_kernel<N, H, EB, MINW, PER_AGENT, UNIFORM>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -585,6 +628,25 @@ bool wide_supported(int N, int H) {
 hipError_t pack_policy_wide(PolicyBuffers& pb, int N, int H, int R, const float* W1, const float* b1,
                             const float* W2, const float* b2, const float* W3, const float* b3, hipStream_t s) {
 #define X(N_, H_, EB_, MW_) if (N == N_ && H == H_) return pack_impl<N_, H_>(pb, R, W1, b1, W2, b2, W3, b3, s);
+  MPE_WIDE_CASES(X)
+#undef X
+  return hipErrorInvalidValue;
+}
+
+// Env-only rollout (seeded uniform actions) with the lane-per-agent mapping of the wide kernel.
+bool uniform_wide_supported(int N) {
+#define X(N_, H_, EB_, MW_) if (N == N_) return true;
+  MPE_WIDE_CASES(X)
+#undef X
+  return false;
+}
+
+hipError_t launch_rollout_uniform_wide(int N, const RolloutArgs& A, hipStream_t s) {
+  const PolicyBuffers none{};
+#define X(N_, H_, EB_, MW_)                                                                      \
+  if (N == N_)                                                                                   \
+    return A.ph.reward_mode == 1 ? rollout_impl<N_, H_, EB_, MW_, true, true>(A, none, s)        \
+                                 : rollout_impl<N_, H_, EB_, MW_, false, true>(A, none, s);
   MPE_WIDE_CASES(X)
 #undef X
   return hipErrorInvalidValue;

@@ -107,7 +107,8 @@ def _episode_errors(obs, ref_obs, done_ref):
 @pytest.mark.parametrize("E,N,T,seed,strict", [(64, 3, 100, 1, True), (64, 3, 100, 2, False), (200, 3, 60, 3, False),
                                                (50, 10, 60, 4, False), (64, 1, 30, 5, True), (65, 2, 30, 6, False),
                                                (33, 4, 30, 7, False), (1000, 3, 125, 8, False),
-                                               (1024, 3, 50, 9, False), (128, 2, 30, 10, False)])
+                                               (1024, 3, 50, 9, False), (128, 2, 30, 10, False),
+                                               (130, 10, 30, 11, False), (64, 10, 27, 12, False)])
 def test_uniform_rollout_matches_oracle(mods, E, N, T, seed, strict):
     MpeEnv, Oracle = mods
     say("uniform rollout E=%d N=%d T=%d seed=%d" % (E, N, T, seed))
