@@ -188,7 +188,7 @@ def main():
               "flop_per_agent_step": flops_per_agent_step(D, H) + flops_per_agent_step(D, H, 1),
               "fp32_equivalent_TFLOPs": (flops_per_agent_step(D, H) + flops_per_agent_step(D, H, 1)) * agent_steps / dt / 1e12,
               "bytes_per_env_step": bytes_per_env_step(N, D) + 8 * N,
-              "note": "mpe_rollout_ac: policy + critic (18->64->64->1), 256-env blocks of four sync groups"}
+              "note": "mpe_rollout_ac: policy + critic (6N->64->64->1); 256-env blocks of four sync groups when they fill half the chip, else 64-env blocks"}
         env4.close()
         del b4
 

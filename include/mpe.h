@@ -152,7 +152,7 @@ int mpe_set_critic(mpe_env* env, const float* V1, const float* c1, const float* 
  * step (the bootstrap value).
  * logp_traj, value_traj [T][TE][N] fp32, last_value [TE][N] fp32; the other arrays as in
  * mpe_rollout.  Any of the eight may be NULL.  Needs a policy and a critic (MPE_ESTATE if one is
- * missing); with several runs num_envs must be a multiple of 256 (MPE_EINVAL otherwise). */
+ * missing); with several runs num_envs must be a multiple of 64 (MPE_EINVAL otherwise). */
 int mpe_rollout_ac(mpe_env* env, int32_t T, float* obs_traj, uint8_t* act_traj, float* logp_traj,
                    float* value_traj, float* rew_traj, uint8_t* done_traj, float* last_obs,
                    float* last_value, void* stream);

@@ -1022,17 +1022,22 @@ hipError_t launch_n(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s
 }
 
 // Actor-critic rollout: 256 envs per block = four 64-env sync groups (12 wavefronts at N = 3)
-// around one staged copy of the two networks (79 KB of the 160 KB LDS for fp32 weights).
+// around one staged copy of the two networks (79 KB of the 160 KB LDS for fp32 weights) when that
+// fills at least half of the CUs; 64-env blocks (one per CU) otherwise, and with several runs
+// whose size is a multiple of 64 but not of 256.
 template <int N, bool BF>
 hipError_t launch_ac_n(const RolloutArgs& A, const PolicyBuffers& pb, const PolicyBuffers& critic, hipStream_t s,
                        const char** why) {
   const bool one_run = A.TE == A.E;
-  if (!one_run && A.E % 256 != 0) {
-    *why = "actor-critic rollout with several runs: num_envs per run must be a multiple of 256";
-    return hipSuccess;
-  }
-  return A.ph.reward_mode == 1 ? rollout_impl<N, 256, 3, true, true, BF>(A, pb, s, critic.packed)
-                               : rollout_impl<N, 256, 3, false, true, BF>(A, pb, s, critic.packed);
+  const bool per_agent = A.ph.reward_mode == 1;
+  if (one_run ? A.TE / 256 >= compute_units() / 2 : A.E % 256 == 0)
+    return per_agent ? rollout_impl<N, 256, 3, true, true, BF>(A, pb, s, critic.packed)
+                     : rollout_impl<N, 256, 3, false, true, BF>(A, pb, s, critic.packed);
+  if (one_run || A.E % 64 == 0)
+    return per_agent ? rollout_impl<N, 64, 3, true, true, BF>(A, pb, s, critic.packed)
+                     : rollout_impl<N, 64, 3, false, true, BF>(A, pb, s, critic.packed);
+  *why = "with several runs, num_envs per run must be a multiple of 64";
+  return hipSuccess;
 }
 
 }  // namespace

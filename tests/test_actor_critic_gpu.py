@@ -40,7 +40,7 @@ def _pair(mods, E, N, R=1, wseed=3, wd=0, **kw):
 
 
 @pytest.mark.parametrize("E,N,R,T,wd", [(1024, 3, 1, 30, 0), (300, 3, 1, 30, 0), (100, 2, 1, 20, 0), (70, 1, 1, 20, 0),
-                                        (256, 3, 2, 12, 0), (300, 3, 1, 20, 1), (70, 1, 1, 10, 1)])
+                                        (256, 3, 2, 12, 0), (64, 3, 3, 12, 0), (300, 3, 1, 20, 1), (70, 1, 1, 10, 1)])
 def test_actor_critic_teacher_forced(mods, E, N, R, T, wd):
     """The oracle runs free; before every step its state is forced into the library, which then does
     one actor-critic step.  wd = 1: bf16 weights and layer inputs on both sides."""
@@ -147,7 +147,7 @@ def test_actor_critic_errors_and_absent_outputs(mods):
         wide.set_critic(*Hp.to_dev(synth.critic_weights(0, 1, 60, 128)))
     assert ei.value.code == MPE_EINVAL
     wide.close()
-    runs = MpeEnv(Hp.gpu_config(64, 3, 2, 64, 0))     # several runs need num_envs % 256 == 0
+    runs = MpeEnv(Hp.gpu_config(40, 3, 2, 64, 0))     # several runs need num_envs % 64 == 0
     runs.set_policy(*Hp.to_dev(synth.policy_weights(0, 2, 18, 64)))
     runs.set_critic(*Hp.to_dev(synth.critic_weights(0, 2, 18, 64)))
     runs.reset(0)
