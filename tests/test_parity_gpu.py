@@ -536,3 +536,56 @@ def test_long_rollout_of_many_episodes(mods):
         assert np.array_equal(obs[t0].astype(np.float64), robs[t0])
         assert np.abs(obs[t0:t0 + 5] - robs[t0:t0 + 5]).max() <= Hp.EPISODE_ATOL
     env.close()
+
+
+OTHER_PHYSICS = dict(dt=0.05, damping=0.4, mass=2.5, accel=3.0, agent_radius=0.2, landmark_radius=0.1,
+                     contact_force=50.0, contact_margin=2e-3)
+
+
+@pytest.mark.parametrize("N,H,wd", [(3, 0, 0), (3, 64, 0), (3, 64, 1), (10, 0, 0), (10, 128, 1), (2, 64, 0)])
+def test_other_physics_constants_and_episode_length(mods, N, H, wd):
+    """Every constant of the config differs from the benchmark's, the episode lasts 7 steps, the
+    reward is the mixed one with ratio 0.3: teacher-forced steps of mpe_step and of the rollout
+    kernels against the oracle built with the same numbers."""
+    MpeEnv, Oracle = mods
+    E, T = 96, 16
+    kw = dict(max_ep=7, reward_mode=1, local_ratio=0.3, **OTHER_PHYSICS)
+    say("other constants N=%d H=%d dtype=%d" % (N, H, wd))
+    env = MpeEnv(Hp.gpu_config(E, N, 1, H, wd, **kw))
+    orc = Oracle(Hp.oracle_config(E, N, 1, H, wd, **kw), threads=8)
+    if H:
+        w = synth.policy_weights_with_bias(9, 1, 6 * N, H)
+        env.set_policy(*Hp.to_dev(w))
+        orc.set_policy(*w)
+    orc.reset(17)
+    env.reset(17)
+    two_r = 2 * float(np.float32(OTHER_PHYSICS["agent_radius"]))
+    dones = 0
+    for t in range(T):
+        pa, va, pl, ep, s = orc.get_state()
+        env.set_state(*Hp.state_to_gpu(pa, va, pl, ep), 17, s)
+        if t % 2 == 0:
+            robs, ract, rrew, rdone, rlast = orc.rollout(1)
+            obs, act, rew, done, last = [x.cpu().numpy() for x in env.rollout(1, *env.empty_traj(1))]
+            rew, rrew, done, rdone, nxt, rnxt = rew[0], rrew[0], done[0], rdone[0], last, rlast
+            ok = (act[0] == ract[0]).all(axis=1)
+            assert ok.mean() > 0.98
+        else:
+            a = synth.random_actions(t, (E, N))
+            rnxt, rrew, rdone = orc.step(a)
+            nxt, rew, done = [x.cpu().numpy() for x in env.step(
+                torch.from_numpy(a).cuda(), env.empty_obs(), torch.empty((E, N), dtype=torch.float32, device="cuda"),
+                torch.empty(E, dtype=torch.uint8, device="cuda"))]
+            ok = np.ones(E, bool)
+        assert np.array_equal(done, rdone)
+        dones += int(rdone.sum())
+        scale = Hp.step_scale(pa, agent_radius=OTHER_PHYSICS["agent_radius"])[ok]
+        Hp.assert_close_step(nxt[ok], rnxt[ok], "next obs t=%d" % t, scale[:, None, None])
+        post = orc.get_state()[0]
+        d = np.linalg.norm(post[:, :, None, :] - post[:, None, :, :], axis=3)
+        d[:, np.arange(N), np.arange(N)] = np.inf
+        mask = (np.abs(d - two_r) > 1e-5).all(axis=2) & (ok & (rdone == 0))[:, None]
+        sc = np.maximum(1.0, Hp.step_scale(pa, agent_radius=OTHER_PHYSICS["agent_radius"]))[:, None] * np.ones((1, N))
+        Hp.assert_close_step(rew[mask], rrew[mask], "mixed reward t=%d" % t, sc[mask])
+    assert dones == 2 * E   # 7-step episodes: done on steps 7 and 14
+    env.close()
