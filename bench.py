@@ -240,6 +240,13 @@ def main():
             "kernel_ms_avg": kavg, "kernel_ms_min": float(np.min(kern_ms)),
             "flop_per_agent_step": flops_per_agent_step(D, H),
             "hbm_achieved_GBs": fused_gbs,
+            # what the matrix cores really execute: matrix instructions per 64 agent rows and step
+            # (16 x 16 x 32 bf16 each = 16,384 FLOP), against the bf16 matrix peak
+            "executed_bf16_mfma": (lambda n_mfma: {
+                "instructions_per_64_rows_step": n_mfma,
+                "TFLOPs": n_mfma * 16384 * (agent_steps / 64) / (kavg * 1e-3) / 1e12,
+                "frac_of_bf16_peak": n_mfma * 16384 * (agent_steps / 64) / (kavg * 1e-3) / 1e12 / 2500.0,
+            })(264 if (wl.weight_dtype == 0 and N >= 2) else 288 if wl.weight_dtype == 0 else 208),
         },
         "env_only": {
             "kernel": ("rollout_uniform_ws_kernel" if N <= 3 else
