@@ -246,7 +246,7 @@ def main():
                 "instructions_per_64_rows_step": n_mfma,
                 "TFLOPs": n_mfma * 16384 * (agent_steps / 64) / (kavg * 1e-3) / 1e12,
                 "frac_of_bf16_peak": n_mfma * 16384 * (agent_steps / 64) / (kavg * 1e-3) / 1e12 / 2500.0,
-            })(264 if (wl.weight_dtype == 0 and N >= 2) else 288 if wl.weight_dtype == 0 else 208),
+            })(264 if (wl.weight_dtype == 0 and N >= 2) else 288 if wl.weight_dtype == 0 else 208 if H == 128 else 56),
         },
         "env_only": {
             "kernel": ("rollout_uniform_ws_kernel" if N <= 3 else
