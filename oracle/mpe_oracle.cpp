@@ -13,7 +13,8 @@
 // feed-forward policy with two tanh layers of width 64 for MPE (Sec. 3.2 "PPO";
 // App. G, IPPO hyper-parameter table), and rolls out 128 steps per update (same
 // table).  Everything quantitative the paper leaves open is fixed by the readings
-// R-1 ... R-12 listed beside each function below.
+// R-1 ... R-14 listed beside each function below.  R-14 is a second scenario (predator-prey,
+// "simple tag") of the MPE family the paper says it implements in full (App. B.7).
 //
 // Arithmetic: double throughout (floating-point inputs arrive as float32 or double and
 // are widened once).  No blocking, fusion or reordering: one loop per env, per step,
@@ -81,6 +82,11 @@ struct Config {
   int32_t reward_mode;   // 0: one shared coverage reward per env; 1: one mixed reward per agent (R-6b)
   int32_t reserved;
   double local_ratio;    // weight of the agent's own collision term in mode 1
+  // scenario 1 (R-14, predator-prey): agents 0..num_adversaries-1 are adversaries, the rest are
+  // good agents; agent_radius / accel above are the good agents' values
+  int32_t scenario;        // 0: simple spread, 1: simple tag
+  int32_t num_adversaries;
+  double adv_radius, adv_accel, adv_max_speed, good_max_speed;
 };
 
 struct Policy {
@@ -121,6 +127,9 @@ double round_to_bf16(double x) {
 // R-2  Reset at absolute step s: every entity e (agents 0..N-1, then landmarks
 // N..N+L-1) draws Philox(env, s, e, RESET_POS); words 0 and 1 give x and y on the
 // 24-bit grid of [-1, 1).  Agent velocities are 0 and the episode counter is 0.
+// Scenario 1 (R-14): landmark coordinates lie in [-0.9, 0.9): the grid value times 0.9, the
+// product DEFINED as the float32 product of the two float32 numbers (so that the initial state
+// is one exact float32 value on every implementation).
 // ---------------------------------------------------------------------------------
 void reset_env(Oracle& o, int run, int env, uint32_t s) {
   const uint32_t key[2] = {o.seed, uint32_t(o.cfg.run_offset + run)};
@@ -129,8 +138,12 @@ void reset_env(Oracle& o, int run, int env, uint32_t s) {
     const uint32_t ctr[4] = {uint32_t(o.cfg.env_offset + env), s, uint32_t(e), TAG_RESET_POS};
     uint32_t w[4];
     philox4x32_10(ctr, key, w);
-    const double x = word_to_position(w[0]);
-    const double y = word_to_position(w[1]);
+    double x = word_to_position(w[0]);
+    double y = word_to_position(w[1]);
+    if (o.cfg.scenario == 1 && e >= o.N) {
+      x = double(float(x) * 0.9f);
+      y = double(float(y) * 0.9f);
+    }
     if (e < o.N) {
       o.pos_a[(ge * o.N + e) * 2 + 0] = x;
       o.pos_a[(ge * o.N + e) * 2 + 1] = y;
@@ -149,7 +162,43 @@ void reset_env(Oracle& o, int run, int env, uint32_t s) {
 //   [ v_i, p_i, (l_k - p_i) for k ascending, (p_j - p_i) for j != i ascending,
 //     2(N-1) zeros (the silent communication slots of the other agents) ].
 // ---------------------------------------------------------------------------------
+// R-14 observation (scenario 1), length D = 4 + 2L + 2(N-1) + 2G with G good agents:
+//   [ v_i, p_i, (l_k - p_i) for k ascending, (p_j - p_i) for j != i ascending,
+//     v_j for the good agents j != i ascending ].
+// An adversary sees G velocities, a good agent G - 1: its row ends with two zeros so that every
+// row has the same length (the shared network needs one input width).
+void observe_env_tag(const Oracle& o, size_t ge, double* obs /* [N][D] */) {
+  const double* pa = &o.pos_a[ge * o.N * 2];
+  const double* va = &o.vel_a[ge * o.N * 2];
+  const double* pl = &o.pos_l[ge * o.L * 2];
+  const int A = o.cfg.num_adversaries;
+  for (int i = 0; i < o.N; ++i) {
+    double* ob = obs + size_t(i) * o.D;
+    int c = 0;
+    ob[c++] = va[2 * i + 0];
+    ob[c++] = va[2 * i + 1];
+    ob[c++] = pa[2 * i + 0];
+    ob[c++] = pa[2 * i + 1];
+    for (int k = 0; k < o.L; ++k) {
+      ob[c++] = pl[2 * k + 0] - pa[2 * i + 0];
+      ob[c++] = pl[2 * k + 1] - pa[2 * i + 1];
+    }
+    for (int j = 0; j < o.N; ++j) {
+      if (j == i) continue;
+      ob[c++] = pa[2 * j + 0] - pa[2 * i + 0];
+      ob[c++] = pa[2 * j + 1] - pa[2 * i + 1];
+    }
+    for (int j = A; j < o.N; ++j) {
+      if (j == i) continue;
+      ob[c++] = va[2 * j + 0];
+      ob[c++] = va[2 * j + 1];
+    }
+    while (c < o.D) ob[c++] = 0.0;
+  }
+}
+
 void observe_env(const Oracle& o, size_t ge, double* obs /* [N][D] */) {
+  if (o.cfg.scenario == 1) { observe_env_tag(o, ge, obs); return; }
   const double* pa = &o.pos_a[ge * o.N * 2];
   const double* va = &o.vel_a[ge * o.N * 2];
   const double* pl = &o.pos_l[ge * o.L * 2];
@@ -195,8 +244,118 @@ double softplus(double x) { return std::max(x, 0.0) + std::log1p(std::exp(-std::
 //      with the counter's step field set to s + 1, so the new episode depends only on
 //      (seed, run, env, s + 1).
 // ---------------------------------------------------------------------------------
+// ---------------------------------------------------------------------------------
+// R-14  Second scenario, predator-prey ("simple tag"; paper App. B.7: all scenarios of the MPE
+// family are implemented and their transitions match the CPU implementation; the paper prints
+// none of it, so this is the reading taken, after the published CPU lineage):
+//  roles    agents 0..A-1 are adversaries (radius adv_radius, control gain adv_accel, speed limit
+//           adv_max_speed), agents A..N-1 are good agents (agent_radius, accel, good_max_speed);
+//           L landmarks of radius landmark_radius are fixed obstacles.
+//  forces   F_i = gain_i * dir(a_i).  Every unordered agent pair and every (agent, landmark) pair
+//           collides, on the pre-step positions, with the contact law of R-4 and
+//           d_min = sum of the two radii; a landmark pushes the agent and does not move.
+//  motion   p_i += v_i * dt with the old velocity; v_i = v_i (1 - damping) + (F_i / mass) dt;
+//           then, if |v_i| > limit_i, v_i is scaled to length limit_i.
+//  reward   on the post-step positions, one value per agent.  Two entities touch when their centre
+//           distance is strictly below the sum of their radii.  Every adversary gets
+//           10 * #{(good g, adversary a) touching}.  A good agent g gets
+//           -10 * #{adversaries touching g} - bound(|x_g|) - bound(|y_g|), with
+//           bound(u) = 0 for u < 0.9, 10 (u - 0.9) for 0.9 <= u < 1, min(exp(2u - 2), 10) above.
+//  episode  counter, done and auto-reset as in R-7.
+// ---------------------------------------------------------------------------------
+double tag_bound(double u) {
+  if (u < 0.9) return 0.0;
+  if (u < 1.0) return (u - 0.9) * 10.0;
+  return std::min(std::exp(2.0 * u - 2.0), 10.0);
+}
+
+void step_env_tag(Oracle& o, int run, int env, uint32_t s, const uint8_t* act /* [N] */,
+                  double* reward /* [N] */, uint8_t* done) {
+  const Config& c = o.cfg;
+  const size_t ge = size_t(run) * o.E + env;
+  double* pa = &o.pos_a[ge * o.N * 2];
+  double* va = &o.vel_a[ge * o.N * 2];
+  const double* pl = &o.pos_l[ge * o.L * 2];
+  const int A = c.num_adversaries;
+  auto radius = [&](int i) { return i < A ? c.adv_radius : c.agent_radius; };
+  auto gain = [&](int i) { return i < A ? c.adv_accel : c.accel; };
+  auto limit = [&](int i) { return i < A ? c.adv_max_speed : c.good_max_speed; };
+  // contact force on the first entity of a pair with separation (dx, dy) and contact distance dmin
+  auto contact = [&](double dx, double dy, double dmin, double& fx, double& fy) {
+    const double d = std::sqrt(dx * dx + dy * dy);
+    const double pen = c.contact_margin * softplus((dmin - d) / c.contact_margin);
+    const double scale = c.contact_force * pen / std::max(d, 1e-12);
+    fx = scale * dx;
+    fy = scale * dy;
+  };
+
+  std::vector<double> F(size_t(o.N) * 2, 0.0);
+  for (int i = 0; i < o.N; ++i) {
+    double ux = 0.0, uy = 0.0;
+    switch (act[i]) {
+      case 1: ux = -1.0; break;
+      case 2: ux = +1.0; break;
+      case 3: uy = -1.0; break;
+      case 4: uy = +1.0; break;
+      default: break;
+    }
+    F[2 * i + 0] = gain(i) * ux;
+    F[2 * i + 1] = gain(i) * uy;
+  }
+  for (int i = 0; i < o.N; ++i) {
+    for (int j = i + 1; j < o.N; ++j) {
+      double fx, fy;
+      contact(pa[2 * i + 0] - pa[2 * j + 0], pa[2 * i + 1] - pa[2 * j + 1], radius(i) + radius(j), fx, fy);
+      F[2 * i + 0] += fx;
+      F[2 * i + 1] += fy;
+      F[2 * j + 0] -= fx;
+      F[2 * j + 1] -= fy;
+    }
+  }
+  for (int i = 0; i < o.N; ++i) {
+    for (int k = 0; k < o.L; ++k) {
+      double fx, fy;
+      contact(pa[2 * i + 0] - pl[2 * k + 0], pa[2 * i + 1] - pl[2 * k + 1], radius(i) + c.landmark_radius, fx, fy);
+      F[2 * i + 0] += fx;
+      F[2 * i + 1] += fy;
+    }
+  }
+  for (int i = 0; i < o.N; ++i) {
+    for (int a = 0; a < 2; ++a) {
+      pa[2 * i + a] += va[2 * i + a] * c.dt;
+      va[2 * i + a] = va[2 * i + a] * (1.0 - c.damping) + (F[2 * i + a] / c.mass) * c.dt;
+    }
+    const double speed = std::sqrt(va[2 * i] * va[2 * i] + va[2 * i + 1] * va[2 * i + 1]);
+    if (speed > limit(i)) {
+      va[2 * i + 0] = va[2 * i + 0] / speed * limit(i);
+      va[2 * i + 1] = va[2 * i + 1] / speed * limit(i);
+    }
+  }
+  auto touching = [&](int i, int j) {
+    const double dx = pa[2 * i + 0] - pa[2 * j + 0];
+    const double dy = pa[2 * i + 1] - pa[2 * j + 1];
+    return std::sqrt(dx * dx + dy * dy) < radius(i) + radius(j);
+  };
+  int caught = 0;   // touching (good, adversary) pairs
+  for (int g = A; g < o.N; ++g)
+    for (int a = 0; a < A; ++a)
+      if (touching(g, a)) ++caught;
+  for (int i = 0; i < A; ++i) reward[i] = 10.0 * double(caught);
+  for (int g = A; g < o.N; ++g) {
+    int hits = 0;
+    for (int a = 0; a < A; ++a)
+      if (touching(g, a)) ++hits;
+    reward[g] = -10.0 * double(hits) - tag_bound(std::fabs(pa[2 * g + 0])) - tag_bound(std::fabs(pa[2 * g + 1]));
+  }
+  o.ep_step[ge] += 1;
+  const bool d = o.ep_step[ge] >= c.max_episode_steps;
+  *done = d ? 1 : 0;
+  if (d) reset_env(o, run, env, s + 1);
+}
+
 void step_env(Oracle& o, int run, int env, uint32_t s, const uint8_t* act /* [N] */,
-              double* reward /* [1], or [N] in reward_mode 1 */, uint8_t* done) {
+              double* reward /* [1], or [N] in reward_mode 1 and in scenario 1 */, uint8_t* done) {
+  if (o.cfg.scenario == 1) { step_env_tag(o, run, env, s, act, reward, done); return; }
   const Config& c = o.cfg;
   const size_t ge = size_t(run) * o.E + env;
   double* pa = &o.pos_a[ge * o.N * 2];
@@ -399,7 +558,7 @@ void rollout_range(Oracle& o, size_t g0, size_t g1, int T, double* obs_traj, uin
   const size_t row = size_t(o.N) * o.D;
   std::vector<double> ob(row);
   std::vector<uint8_t> act(o.N);
-  const size_t RW = o.cfg.reward_mode == 1 ? size_t(o.N) : 1;   // rewards per env and step
+  const size_t RW = (o.cfg.reward_mode == 1 || o.cfg.scenario == 1) ? size_t(o.N) : 1;   // rewards per env and step
   std::vector<double> r(RW);
   for (size_t ge = g0; ge < g1; ++ge) {
     const int run = int(ge / o.E), env = int(ge % o.E);
@@ -447,6 +606,9 @@ struct orc_config {
   int32_t reward_mode;
   int32_t reserved;
   double local_ratio;
+  int32_t scenario;
+  int32_t num_adversaries;
+  double adv_radius, adv_accel, adv_max_speed, good_max_speed;
 };
 
 const char* orc_last_error(void) { return g_err.c_str(); }
@@ -457,15 +619,19 @@ void orc_philox4x32_10(const uint32_t* ctr, const uint32_t* key, uint32_t* out) 
 
 int orc_create(const orc_config* c, void** out) {
   if (!c || !out) return fail("null argument");
-  if (c->num_envs < 1 || c->num_agents < 1 || c->num_landmarks < 1 || c->num_runs < 1 ||
+  if (c->scenario != 0 && c->scenario != 1) return fail("scenario must be 0 or 1");
+  if (c->num_envs < 1 || c->num_agents < 1 || c->num_landmarks < (c->scenario == 1 ? 0 : 1) || c->num_runs < 1 ||
       c->max_episode_steps < 1)
     return fail("sizes must be positive");
   if (c->reward_mode != 0 && c->reward_mode != 1) return fail("reward_mode must be 0 or 1");
+  if (c->scenario == 1 && (c->num_adversaries < 1 || c->num_adversaries >= c->num_agents))
+    return fail("scenario 1 needs 1 <= num_adversaries < num_agents");
   static_assert(sizeof(orc_config) == sizeof(Config), "config mirror");
   Oracle* o = new Oracle();
   std::memcpy(&o->cfg, c, sizeof(Config));
   o->E = c->num_envs; o->N = c->num_agents; o->L = c->num_landmarks; o->R = c->num_runs;
-  o->D = 4 + 2 * o->L + 4 * (o->N - 1);
+  o->D = c->scenario == 1 ? 4 + 2 * o->L + 2 * (o->N - 1) + 2 * (o->N - c->num_adversaries)
+                          : 4 + 2 * o->L + 4 * (o->N - 1);
   o->H = c->hidden;
   const size_t TE = size_t(o->R) * o->E;
   o->pos_a.assign(TE * o->N * 2, 0.0);
@@ -516,7 +682,7 @@ int orc_step(void* h, const uint8_t* actions, double* obs, double* reward, uint8
     for (int i = 0; i < o.N; ++i)
       if (actions[ge * o.N + i] >= NUM_ACTIONS) return fail("action out of range");
   }
-  const size_t RW = o.cfg.reward_mode == 1 ? size_t(o.N) : 1;
+  const size_t RW = (o.cfg.reward_mode == 1 || o.cfg.scenario == 1) ? size_t(o.N) : 1;
   std::vector<double> r(RW);
   for (size_t ge = 0; ge < TE; ++ge) {
     uint8_t d;

@@ -2,7 +2,7 @@
 
 Argument marshalling and nothing else: every number comes out of the C++ file.
 All arrays are host numpy arrays in the oracle's own plain layouts:
-  obs [R*E][N][D] float64, reward [R*E] float64 ([R*E][N] in reward_mode 1), done [R*E] uint8,
+  obs [R*E][N][D] float64, reward [R*E] float64 ([R*E][N] in reward_mode 1 and in scenario 1), done [R*E] uint8,
   actions [R*E][N] uint8,
   pos_a / vel_a [R*E][N][2], pos_l [R*E][L][2] float64, ep_step [R*E] int32.
 """
@@ -37,7 +37,9 @@ class _CConfig(C.Structure):
         "hidden", "weight_dtype", "env_offset", "run_offset")] + [(n, C.c_double) for n in (
         "dt", "damping", "mass", "accel", "agent_radius", "landmark_radius",
         "contact_force", "contact_margin")] + [("reward_mode", C.c_int32), ("reserved", C.c_int32),
-                                               ("local_ratio", C.c_double)]
+                                               ("local_ratio", C.c_double),
+                                               ("scenario", C.c_int32), ("num_adversaries", C.c_int32)] + [
+        (n, C.c_double) for n in ("adv_radius", "adv_accel", "adv_max_speed", "good_max_speed")]
 
 
 @dataclass
@@ -62,6 +64,12 @@ class OracleConfig:
     reward_mode: int = 0        # 0: shared coverage reward [R*E]; 1: mixed per-agent reward [R*E][N]
     reserved: int = 0
     local_ratio: float = 0.5
+    scenario: int = 0           # 0 simple spread; 1 simple tag (rewards [R*E][N]; agent_radius / accel: good agents)
+    num_adversaries: int = 0
+    adv_radius: float = 0.075
+    adv_accel: float = 3.0
+    adv_max_speed: float = 1.0
+    good_max_speed: float = 1.3
 
 
 _lib = None
@@ -148,7 +156,7 @@ class Oracle:
         self.TE = self.E * self.R
         self.D = int(self.lib.orc_obs_dim(self.h))
         self.threads = threads
-        self.rew_shape = (self.TE, self.N) if cfg.reward_mode == 1 else (self.TE,)
+        self.rew_shape = (self.TE, self.N) if (cfg.reward_mode == 1 or cfg.scenario == 1) else (self.TE,)
         _check(self.lib.orc_set_threads(self.h, threads))
 
     def __del__(self):

@@ -1,0 +1,418 @@
+"""Pins for the oracle's second scenario (predator-prey, "simple tag"): hand-worked transitions,
+closed forms, invariants, numpy brute force and the reduction to the already pinned simple-spread
+dynamics.  Nothing here re-uses the oracle's own arithmetic.  CPU only."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import Oracle, OracleConfig, philox4x32_10, uniform_action
+from tests.conftest import read_golden
+
+ADV_R, GOOD_R, LM_R = 0.075, 0.05, 0.2
+ADV_GAIN, GOOD_GAIN = 3.0, 4.0
+ADV_LIMIT, GOOD_LIMIT = 1.0, 1.3
+FAR = 1e9
+
+
+def make(N=4, A=3, L=2, E=1, **kw):
+    base = dict(num_envs=E, num_agents=N, num_landmarks=L, scenario=1, num_adversaries=A, hidden=0,
+                agent_radius=GOOD_R, accel=GOOD_GAIN, landmark_radius=LM_R, adv_radius=ADV_R, adv_accel=ADV_GAIN,
+                adv_max_speed=ADV_LIMIT, good_max_speed=GOOD_LIMIT)
+    base.update(kw)
+    return Oracle(OracleConfig(**base))
+
+
+def put(o, pos_a, vel_a, pos_l, ep=0, seed=0, abs_step=0):
+    o.set_state(np.asarray(pos_a, float), np.asarray(vel_a, float), np.asarray(pos_l, float).reshape(o.TE, o.L, 2),
+                np.full(o.TE, ep, np.int32), seed, abs_step)
+
+
+def spread_out(n, gap=3.0):
+    """n points far from each other and from the origin region used by the tests."""
+    return np.array([[10.0 + gap * k, -20.0 - gap * k] for k in range(n)])
+
+
+# ------------------------------------------------------------------ hand-worked example
+def test_hand_worked_two_step_example():
+    g, _ = read_golden("tag_hand_worked_two_step.txt")
+    f = lambda k: np.array([float(x) for x in g[k]])
+    o = make()
+    assert o.D == 16 and o.rew_shape == (1, 4)
+    put(o, f("pos_a").reshape(1, 4, 2), f("vel_a").reshape(1, 4, 2), f("pos_l").reshape(1, 2, 2))
+    obs, rew, done = o.step(np.array([[int(x) for x in g["actions1"]]], np.uint8))
+    pos_a, vel_a, pos_l, ep, s = o.get_state()
+    np.testing.assert_allclose(pos_a.ravel(), f("pos_a1"), rtol=0, atol=1e-13)
+    np.testing.assert_allclose(vel_a.ravel(), f("vel_a1"), rtol=0, atol=1e-11)
+    np.testing.assert_allclose(rew[0], f("reward1"), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(obs[0, 0], f("obs0_1"), rtol=0, atol=1e-11)
+    np.testing.assert_allclose(obs[0, 3], f("obs3_1"), rtol=0, atol=1e-11)
+    np.testing.assert_array_equal(pos_l.ravel(), f("pos_l"))
+    assert done[0] == 0 and ep[0] == 1 and s == 1
+    obs, rew, done = o.step(np.array([[int(x) for x in g["actions2"]]], np.uint8))
+    pos_a, vel_a, _, _, _ = o.get_state()
+    np.testing.assert_allclose(pos_a.ravel(), f("pos_a2"), rtol=0, atol=1e-13)
+    force = 0.5 + 0.1 * math.log1p(math.exp(-5.0))
+    want_v = [-0.4125 - 0.1 * force, 0, 0, -0.4375, 0.6, 0.45, 0.3 + 0.1 * force, 0.3]
+    np.testing.assert_allclose(vel_a.ravel(), want_v, rtol=0, atol=1e-11)
+    np.testing.assert_allclose(vel_a.ravel(), f("vel_a2_printed"), rtol=0, atol=1e-9)
+    np.testing.assert_allclose(rew[0], [0, 0, 0, -math.exp(0.02)], rtol=0, atol=1e-12)
+    np.testing.assert_allclose(rew[0], f("reward2"), rtol=0, atol=1e-9)
+
+
+# ------------------------------------------------------------------ boundary penalty of good agents
+@pytest.mark.parametrize("xy,penalty", [
+    ((0.5, -0.3), 0.0),
+    ((0.95, 0.0), 0.5),                       # linear part: 10 (u - 0.9)
+    ((0.0, -0.99), 0.9),
+    ((1.0, 0.0), 1.0),                        # exp(0)
+    ((-1.5, 0.2), math.e),                    # exp(2 * 1.5 - 2)
+    ((0.95, -1.5), 0.5 + math.e),             # the two coordinates add
+    ((2.2, 0.0), 10.0),                       # exp(2.4) = 11.02 is capped at 10
+    ((-3.0, 3.0), 20.0),
+])
+def test_boundary_penalty_closed_forms(xy, penalty):
+    o = make()
+    pos = spread_out(4)
+    pos[3] = xy
+    put(o, pos[None], np.zeros((1, 4, 2)), spread_out(2, 5.0) + 100.0)
+    _, rew, _ = o.step(np.zeros((1, 4), np.uint8))
+    assert rew[0, 3] == pytest.approx(-penalty, abs=1e-12)
+    np.testing.assert_array_equal(rew[0, :3], 0.0)      # adversaries pay no boundary penalty
+
+
+def test_adversaries_pay_no_boundary_penalty_anywhere():
+    o = make()
+    pos = np.array([[5.0, 0.0], [-7.0, 2.0], [0.0, 9.0], [0.0, 0.0]])
+    put(o, pos[None], np.zeros((1, 4, 2)), spread_out(2) + 50.0)
+    _, rew, _ = o.step(np.zeros((1, 4), np.uint8))
+    np.testing.assert_array_equal(rew[0], [0.0, 0.0, 0.0, 0.0])
+
+
+# ------------------------------------------------------------------ contact forces
+def _force_on(o, i):
+    """Force on agent i in the last step, from its velocity change (zero start velocity, no action)."""
+    _, vel, _, _, _ = o.get_state()
+    return vel[0, i] / 0.1
+
+
+@pytest.mark.parametrize("agent,dmin", [(0, ADV_R + LM_R), (3, GOOD_R + LM_R)])
+@pytest.mark.parametrize("gap,force", [
+    (-0.1, 10.0),                                     # deep contact: penetration = dmin - d
+    (-0.01, 1.0 + 0.1 * math.log1p(math.exp(-10.0))),
+    (0.0, 0.1 * math.log(2.0)),                       # exactly touching: margin * ln 2
+    (0.001, 0.1 * math.log1p(math.exp(-1.0))),
+    (0.1, 0.0),
+])
+def test_landmark_contact_force_magnitude_and_direction(agent, dmin, gap, force):
+    o = make(adv_max_speed=FAR, good_max_speed=FAR)
+    pos = spread_out(4)
+    d = dmin + gap
+    lm = np.array([[0.3, -0.2], [60.0, 60.0]])
+    # the agent sits at distance d from landmark 0 in direction (0.6, 0.8)
+    pos[agent] = lm[0] + d * np.array([0.6, 0.8])
+    put(o, pos[None], np.zeros((1, 4, 2)), lm[None])
+    o.step(np.zeros((1, 4), np.uint8))
+    F = _force_on(o, agent)
+    np.testing.assert_allclose(F, force * np.array([0.6, 0.8]), rtol=0, atol=2e-9)   # away from the landmark
+    _, _, pos_l, _, _ = o.get_state()
+    np.testing.assert_array_equal(pos_l[0], lm)           # landmarks never move
+    for other in range(4):
+        if other != agent:
+            np.testing.assert_array_equal(_force_on(o, other), [0.0, 0.0])
+
+
+@pytest.mark.parametrize("i,j,dmin", [(0, 1, 2 * ADV_R), (1, 3, ADV_R + GOOD_R), (3, 4, 2 * GOOD_R)])
+def test_agent_pair_contact_distance_is_the_sum_of_radii(i, j, dmin):
+    o = make(N=5, A=3, L=1, adv_max_speed=FAR, good_max_speed=FAR)
+    pos = spread_out(5)
+    pos[j] = pos[i] + np.array([dmin - 0.05, 0.0])        # penetration 0.05 -> force 5
+    put(o, pos[None], np.zeros((1, 5, 2)), np.array([[[90.0, 90.0]]]))
+    o.step(np.zeros((1, 5), np.uint8))
+    np.testing.assert_allclose(_force_on(o, i), [-5.0, 0.0], rtol=0, atol=1e-9)
+    np.testing.assert_allclose(_force_on(o, j), [+5.0, 0.0], rtol=0, atol=1e-9)
+
+
+def test_contacts_use_pre_step_positions():
+    # two adversaries approach fast: apart before the step (no force), overlapping after it
+    o = make(adv_max_speed=FAR, good_max_speed=FAR)
+    pos = spread_out(4)
+    pos[1] = pos[0] + np.array([0.4, 0.0])
+    vel = np.zeros((4, 2))
+    vel[0] = [2.0, 0.0]
+    vel[1] = [-2.0, 0.0]
+    put(o, pos[None], vel[None], spread_out(2) + 70.0)
+    o.step(np.zeros((1, 4), np.uint8))
+    p, v, _, _, _ = o.get_state()
+    assert p[0, 1, 0] - p[0, 0, 0] == pytest.approx(0.0, abs=1e-12)      # they now coincide
+    np.testing.assert_allclose(v[0, 0], [1.5, 0.0], atol=1e-12)        # only damping acted
+    np.testing.assert_allclose(v[0, 1], [-1.5, 0.0], atol=1e-12)
+
+
+def test_agent_contacts_antisymmetric_total_momentum():
+    # no landmarks, no speed limit: agent-agent forces cancel, so the total momentum only decays and
+    # takes up the control forces (per-role gains)
+    o = make(N=6, A=4, L=0, E=16, adv_max_speed=FAR, good_max_speed=FAR)
+    g = np.random.Generator(np.random.PCG64(5))
+    pos = g.uniform(-0.15, 0.15, (16, 6, 2))
+    vel = g.uniform(-1, 1, (16, 6, 2))
+    put(o, pos, vel, np.zeros((16, 0, 2)))
+    act = g.integers(0, 5, (16, 6), dtype=np.uint8)
+    o.step(act)
+    _, v, _, _, _ = o.get_state()
+    dirs = np.array([[0, 0], [-1, 0], [1, 0], [0, -1], [0, 1]], float)
+    gain = np.array([ADV_GAIN] * 4 + [GOOD_GAIN] * 2)
+    control = (dirs[act] * gain[None, :, None]).sum(axis=1)
+    np.testing.assert_allclose(v.sum(axis=1), 0.75 * vel.sum(axis=1) + 0.1 * control, rtol=0, atol=1e-9)
+
+
+# ------------------------------------------------------------------ control gains, speed limit
+@pytest.mark.parametrize("agent,gain", [(0, ADV_GAIN), (2, ADV_GAIN), (3, GOOD_GAIN)])
+@pytest.mark.parametrize("action,direction", [(1, (-1, 0)), (2, (1, 0)), (3, (0, -1)), (4, (0, 1)), (0, (0, 0))])
+def test_control_gain_per_role(agent, gain, action, direction):
+    o = make()
+    put(o, spread_out(4)[None], np.zeros((1, 4, 2)), spread_out(2) + 40.0)
+    act = np.zeros((1, 4), np.uint8)
+    act[0, agent] = action
+    o.step(act)
+    _, v, _, _, _ = o.get_state()
+    np.testing.assert_allclose(v[0, agent], 0.1 * gain * np.array(direction, float), rtol=0, atol=1e-15)
+
+
+@pytest.mark.parametrize("agent,limit", [(1, ADV_LIMIT), (3, GOOD_LIMIT)])
+def test_speed_limit_three_four_five(agent, limit):
+    # coasting: v' = 0.75 v.  v = (4, 3) * k has length 5k.
+    o = make()
+    for k, clipped in ((0.2, False), (0.4, True), (2.0, True)):
+        vel = np.zeros((4, 2))
+        vel[agent] = [4 * k, 3 * k]
+        put(o, spread_out(4)[None], vel[None], spread_out(2) + 40.0)
+        o.step(np.zeros((1, 4), np.uint8))
+        p, v, _, _, _ = o.get_state()
+        speed = 0.75 * 5 * k
+        assert (speed > limit) == clipped
+        want = np.array([0.8, 0.6]) * (limit if clipped else speed)
+        np.testing.assert_allclose(v[0, agent], want, rtol=0, atol=1e-12)
+        # the position moved with the old, unclipped velocity
+        np.testing.assert_allclose(p[0, agent], spread_out(4)[agent] + 0.1 * vel[agent], rtol=0, atol=1e-12)
+
+
+def test_speed_limit_is_a_rescaling_of_the_unlimited_velocity():
+    g = np.random.Generator(np.random.PCG64(11))
+    E = 64
+    pos = g.uniform(-0.3, 0.3, (E, 4, 2))
+    vel = g.uniform(-2, 2, (E, 4, 2))
+    lm = g.uniform(-0.3, 0.3, (E, 2, 2))
+    act = g.integers(0, 5, (E, 4), dtype=np.uint8)
+    free = make(E=E, adv_max_speed=FAR, good_max_speed=FAR)
+    lim = make(E=E)
+    for o in (free, lim):
+        put(o, pos, vel, lm)
+        o.step(act)
+    pf, vf, _, _, _ = free.get_state()
+    pl, vl, _, _, _ = lim.get_state()
+    np.testing.assert_array_equal(pf, pl)                    # positions do not see the limit in the same step
+    limit = np.array([ADV_LIMIT] * 3 + [GOOD_LIMIT])[None, :]
+    speed = np.linalg.norm(vf, axis=-1)
+    scale = np.where(speed > limit, limit / speed, 1.0)
+    assert (scale < 1).mean() > 0.2 and (scale == 1).mean() > 0.2
+    np.testing.assert_allclose(vl, vf * scale[..., None], rtol=0, atol=1e-12)
+    assert np.all(np.linalg.norm(vl, axis=-1) <= limit * (1 + 1e-12))
+
+
+def test_reduces_to_simple_spread_dynamics_without_landmarks_roles_or_limit():
+    # equal radii and gains, no speed limit, no obstacle: the agents move exactly as in the
+    # (separately pinned) simple-spread transition, whose landmarks do not collide
+    g = np.random.Generator(np.random.PCG64(21))
+    E, N = 32, 4
+    tag = make(N=N, A=2, L=0, E=E, agent_radius=0.15, adv_radius=0.15, accel=5.0, adv_accel=5.0,
+               adv_max_speed=FAR, good_max_speed=FAR)
+    spread = Oracle(OracleConfig(num_envs=E, num_agents=N, num_landmarks=N, hidden=0))
+    pos = g.uniform(-0.3, 0.3, (E, N, 2))
+    vel = g.uniform(-1, 1, (E, N, 2))
+    put(tag, pos, vel, np.zeros((E, 0, 2)))
+    spread.set_state(pos, vel, g.uniform(-1, 1, (E, N, 2)), np.zeros(E, np.int32), 0, 0)
+    for _ in range(5):
+        act = g.integers(0, 5, (E, N), dtype=np.uint8)
+        tag.step(act)
+        spread.step(act)
+    pt, vt, _, _, _ = tag.get_state()
+    ps, vs, _, _, _ = spread.get_state()
+    np.testing.assert_allclose(pt, ps, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(vt, vs, rtol=0, atol=1e-12)
+
+
+# ------------------------------------------------------------------ rewards
+def _brute_rewards(pos, A, radius):
+    """Rewards from post-step positions [N][2], counted pair by pair (inside |x|,|y| < 0.9)."""
+    N = len(pos)
+    out = np.zeros(N)
+    for g in range(A, N):
+        for a in range(A):
+            if math.dist(pos[g], pos[a]) < radius[g] + radius[a]:
+                out[:A] += 10.0
+                out[g] -= 10.0
+    return out
+
+
+@pytest.mark.parametrize("N,A,L", [(4, 3, 2), (6, 4, 2), (5, 2, 1), (2, 1, 1)])
+def test_rewards_brute_force_counts(N, A, L):
+    g = np.random.Generator(np.random.PCG64(100 + N))
+    E = 200
+    o = make(N=N, A=A, L=L, E=E)
+    pos = g.uniform(-0.25, 0.25, (E, N, 2))
+    put(o, pos, g.uniform(-0.5, 0.5, (E, N, 2)), g.uniform(-0.8, 0.8, (E, L, 2)))
+    _, rew, _ = o.step(g.integers(0, 5, (E, N), dtype=np.uint8))
+    post, _, _, _, _ = o.get_state()
+    assert np.abs(post).max() < 0.9
+    radius = np.array([ADV_R] * A + [GOOD_R] * (N - A))
+    want = np.stack([_brute_rewards(post[e], A, radius) for e in range(E)])
+    np.testing.assert_allclose(rew, want, rtol=0, atol=1e-12)
+    assert (want[:, 0] >= 10).mean() > 0.05 and (want[:, 0] == 0).mean() > 0.1
+    # every adversary gets the same value, and (inside the arena) it is minus the good agents' total
+    assert np.all(rew[:, :A] == rew[:, :1])
+    np.testing.assert_allclose(rew[:, A:].sum(axis=1), -rew[:, 0], rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("gap,touch", [(-1e-9, True), (0.0, False), (1e-9, False)])
+def test_touching_threshold_is_strict_and_uses_post_step_positions(gap, touch):
+    # binary-exact numbers: radii 0.125 + 0.125, dt = 0.125; adversary 1 starts 0.5 + gap from the good
+    # agent and moves 0.25 inward in one step (old velocity -2), ending exactly 0.25 + gap away
+    o = make(adv_radius=0.125, agent_radius=0.125, dt=0.125)
+    pos = np.array([[-0.5, -0.5], [0.5 + gap, 0.0], [-0.5, 0.5], [0.0, 0.0]])
+    vel = np.zeros((4, 2))
+    vel[1] = [-2.0, 0.0]
+    put(o, pos[None], vel[None], spread_out(2) + 40.0)
+    _, rew, _ = o.step(np.zeros((1, 4), np.uint8))
+    post, _, _, _, _ = o.get_state()
+    assert abs(post[0, 1, 0] - (0.25 + gap)) < 1e-15 and post[0, 3, 0] == 0.0
+    assert (post[0, 1, 0] == 0.25) == (gap == 0.0)
+    want = [10, 10, 10, -10] if touch else [0, 0, 0, 0]
+    np.testing.assert_array_equal(rew[0], want)
+
+
+def test_reward_counts_pairs_with_two_good_agents():
+    # adversary 0 touches both good agents, adversary 1 touches good agent 4 only: 3 pairs
+    o = make(N=5, A=3, L=1)
+    pos = np.array([[0.0, 0.0], [0.2, 0.0], [0.6, 0.6], [-0.1, 0.0], [0.1, 0.0]])
+    put(o, pos[None], np.zeros((1, 5, 2)), np.array([[[50.0, 50.0]]]))
+    _, rew, _ = o.step(np.zeros((1, 5), np.uint8))
+    np.testing.assert_array_equal(rew[0], [30, 30, 30, -10, -20])
+
+
+# ------------------------------------------------------------------ observation
+def test_observation_layout_two_good_agents():
+    o = make(N=5, A=3, L=1)
+    assert o.D == 4 + 2 + 8 + 4
+    pos = np.array([[1, 2], [3, 5], [-4, 7], [10, -1], [0.5, 0.25]], float)
+    vel = np.array([[0.1, 0.2], [0.3, 0.4], [0.5, 0.6], [0.7, 0.8], [0.9, 1.0]])
+    lm = np.array([[[2.0, -3.0]]])
+    put(o, pos[None], vel[None], lm)
+    obs = o.observe()[0]
+    # adversary 1: own v, own p, landmark, others 0 2 3 4 (relative), velocities of good agents 3 and 4
+    np.testing.assert_allclose(obs[1], [0.3, 0.4, 3, 5, -1, -8, -2, -3, -7, 2, 7, -6, -2.5, -4.75,
+                                        0.7, 0.8, 0.9, 1.0], atol=1e-15)
+    # good agent 3: others 0 1 2 4, velocity of the other good agent 4, then two zeros
+    np.testing.assert_allclose(obs[3], [0.7, 0.8, 10, -1, -8, -2, -9, 3, -7, 6, -14, 8, -9.5, 1.25,
+                                        0.9, 1.0, 0, 0], atol=1e-15)
+    # good agent 4: velocity of good agent 3
+    np.testing.assert_allclose(obs[4][14:], [0.7, 0.8, 0, 0], atol=1e-15)
+
+
+def test_observation_after_step_is_of_the_new_state():
+    o = make(E=8)
+    o.reset(4)
+    obs, _, _ = o.step(np.full((8, 4), 2, np.uint8))
+    p, v, l, _, _ = o.get_state()
+    np.testing.assert_array_equal(obs[:, :, 0:2], v)
+    np.testing.assert_array_equal(obs[:, :, 2:4], p)
+    np.testing.assert_array_equal(obs[:, 2, 4:6], l[:, 0] - p[:, 2])
+    np.testing.assert_array_equal(obs[:, 0, 14:16], v[:, 3])
+    np.testing.assert_array_equal(obs[:, 3, 14:16], 0.0)
+
+
+# ------------------------------------------------------------------ reset, episode, rollout
+def test_reset_landmarks_lie_in_the_inner_box_agents_in_the_full_one():
+    o = make(E=3, num_runs=2, env_offset=4, run_offset=9)
+    o.reset(77)
+    pos_a, vel_a, pos_l, ep, _ = o.get_state()
+    for run in range(2):
+        for env in range(3):
+            ge = run * 3 + env
+            for e in range(6):
+                w = philox4x32_10([4 + env, 0, e, 0], [77, 9 + run])
+                grid = [np.float32((int(w[k]) >> 8) / 2.0**23 - 1.0) for k in (0, 1)]
+                if e < 4:
+                    assert list(pos_a[ge, e]) == [float(grid[0]), float(grid[1])]
+                else:
+                    # float32 product of the grid value and float32(0.9), as numpy's float32 computes it
+                    want = [float(x * np.float32(0.9)) for x in grid]
+                    assert list(pos_l[ge, e - 4]) == want
+    assert np.all(vel_a == 0) and np.all(ep == 0)
+    big = make(E=4096)
+    big.reset(1)
+    pa, _, pl, _, _ = big.get_state()
+    assert -0.9 <= pl.min() < -0.89 and 0.89 < pl.max() < 0.9
+    assert pa.min() < -0.99 and pa.max() > 0.99
+
+
+def test_done_and_auto_reset_keyed_by_next_step():
+    o = make(E=2, max_episode_steps=3)
+    o.reset(5)
+    for t in range(3):
+        _, rew, done = o.step(np.zeros((2, 4), np.uint8))
+        assert list(done) == ([0, 0] if t < 2 else [1, 1])
+    pos_a, vel_a, pos_l, ep, s = o.get_state()
+    assert s == 3 and np.all(ep == 0) and np.all(vel_a == 0)
+    w = philox4x32_10([1, 3, 2, 0], [5, 0])     # env 1, step 2 + 1, agent 2
+    assert pos_a[1, 2, 0] == (int(w[0]) >> 8) / 2.0**23 - 1.0
+    w = philox4x32_10([0, 3, 5, 0], [5, 0])     # env 0, landmark 1 = entity 5
+    assert pos_l[0, 1, 1] == float(np.float32((int(w[1]) >> 8) / 2.0**23 - 1.0) * np.float32(0.9))
+
+
+def test_reward_at_done_is_from_the_pre_reset_state():
+    o = make(max_episode_steps=1)
+    pos = np.array([[0.0, 0.0], [5.0, 5.0], [-5.0, 5.0], [0.1, 0.0]])
+    put(o, pos[None], np.zeros((1, 4, 2)), spread_out(2) + 40.0)
+    _, rew, done = o.step(np.zeros((1, 4), np.uint8))
+    assert done[0] == 1
+    np.testing.assert_array_equal(rew[0], [10, 10, 10, -10])
+
+
+def test_rollout_equals_repeated_steps_with_uniform_actions():
+    a, b = make(E=5, max_episode_steps=4), make(E=5, max_episode_steps=4)
+    a.reset(8)
+    b.reset(8)
+    obs, act, rew, done, last = a.rollout(9)
+    assert rew.shape == (9, 5, 4)
+    cur = b.observe()
+    for t in range(9):
+        np.testing.assert_array_equal(obs[t], cur)
+        want = np.array([[uniform_action(8, 0, e, t, i) for i in range(4)] for e in range(5)], np.uint8)
+        np.testing.assert_array_equal(act[t], want)
+        cur, r, d = b.step(want)
+        np.testing.assert_array_equal(rew[t], r)
+        np.testing.assert_array_equal(done[t], d)
+    np.testing.assert_array_equal(last, cur)
+
+
+def test_policy_rollout_runs_on_padded_rows():
+    # the shared network takes the 16-wide rows of all four agents (a good agent's row ends in zeros)
+    from paper_2311_10090_amd import synth
+    o = make(E=3, hidden=64)
+    W = synth.policy_weights_with_bias(3, 1, 16, 64)
+    o.set_policy(*W)
+    o.reset(2)
+    obs, act, rew, done, last = o.rollout(4)
+    z = o.policy_logits(obs[1, 2, 3])
+    x = obs[1, 2, 3]
+    h1 = np.tanh(x @ W[0][0].astype(float) + W[1][0])
+    h2 = np.tanh(h1 @ W[2][0].astype(float) + W[3][0])
+    np.testing.assert_allclose(z[0], h2 @ W[4][0].astype(float) + W[5][0], rtol=0, atol=1e-12)
+
+
+def test_scenario_arguments_are_validated():
+    for bad in (dict(A=0), dict(A=4), dict(scenario=2)):
+        with pytest.raises(RuntimeError):
+            make(**bad)
+    make(L=0)      # no obstacles is allowed
