@@ -26,7 +26,24 @@
  * (= N), D = 4 + 2L + 4(N-1) = 6N floats per observation, A = 5 actions.
  * Global env index g = run*E + env.  All trajectory arrays are row-major, env-major
  * inside a time slice: obs[t][g][agent][D], act[t][g][agent], rew[t][g] (rew[t][g][agent] with
- * MPE_REWARD_MIXED), done[t][g].
+ * MPE_REWARD_MIXED and with MPE_SCENARIO_TAG), done[t][g].
+ *
+ * Second scenario, MPE_SCENARIO_TAG (predator-prey; the paper implements the whole MPE family,
+ * App. B.7): agents 0..num_adversaries-1 are adversaries, the other G = N - num_adversaries are
+ * good agents; L >= 0 landmarks are fixed obstacles.  Differences from simple spread:
+ *   - every agent pair AND every (agent, landmark) pair collides, with contact distance = sum of
+ *     the two radii (adv_radius for adversaries, agent_radius for good agents, landmark_radius);
+ *   - control force = adv_accel or accel (good agents) times the action's direction; after the
+ *     velocity update a velocity longer than adv_max_speed / good_max_speed is scaled to that length;
+ *   - rewards are per agent ([TE][N], [T][TE][N]), on the positions after the step; two entities
+ *     touch when their centre distance is strictly below the sum of their radii; every adversary
+ *     gets 10 * (number of touching (good, adversary) pairs); a good agent gets -10 per adversary
+ *     touching it, minus bound(|x|) + bound(|y|), bound(u) = 0 below 0.9, 10 (u - 0.9) below 1,
+ *     min(exp(2u - 2), 10) above;
+ *   - reset draws landmark coordinates in [-0.9, 0.9): the fp32 product of the grid value and 0.9f;
+ *   - observation of agent i, D = 4 + 2L + 2(N-1) + 2G floats: own velocity, own position,
+ *     landmarks relative, other agents relative (ascending), velocities of the other good agents
+ *     (ascending); a good agent's row ends with two zeros so that all rows have the same length.
  */
 #ifndef MPE_H_
 #define MPE_H_
@@ -58,37 +75,52 @@ extern "C" {
 #define MPE_REWARD_SHARED 0
 #define MPE_REWARD_MIXED  1
 
+#define MPE_SCENARIO_SPREAD 0  /* cooperative coverage of N landmarks by N agents           */
+#define MPE_SCENARIO_TAG    1  /* predator-prey with obstacle landmarks (see the top comment) */
+
 typedef struct mpe_env mpe_env; /* opaque; host memory owned by the library */
 
 typedef struct {
   int32_t num_envs;          /* E >= 1, environments per run                               */
   int32_t num_agents;        /* N in [1, MPE_MAX_AGENTS]                                   */
-  int32_t num_landmarks;     /* L, must equal N (simple-spread)                            */
+  int32_t num_landmarks;     /* L, must equal N (simple-spread); 0..4 with MPE_SCENARIO_TAG */
   int32_t num_runs;          /* R >= 1 independent runs (own RNG key, own policy weights)  */
   int32_t max_episode_steps; /* done fires on this many steps after a reset (25)           */
   float   dt;                /* 0.1                                                        */
   float   damping;           /* 0.25 : v <- v * (1 - damping) + (F / mass) * dt            */
   float   mass;              /* 1                                                          */
-  float   accel;             /* 5   : control force = accel * unit direction of the action */
-  float   agent_radius;      /* 0.15: agents touch at distance 2 * agent_radius            */
-  float   landmark_radius;   /* 0.05: carried for completeness; landmarks never collide    */
+  float   accel;             /* 5   : control force = accel * unit direction of the action
+                                (tag: of the good agents, 4)                               */
+  float   agent_radius;      /* 0.15: agents touch at distance 2 * agent_radius
+                                (tag: radius of the good agents, 0.05)                     */
+  float   landmark_radius;   /* 0.05: unused by simple spread, whose landmarks never collide
+                                (tag: radius of the obstacles, 0.2)                        */
   float   contact_force;     /* 100                                                        */
   float   contact_margin;    /* 1e-3: softness of the softplus penetration                 */
   int32_t hidden;            /* policy width H: 64 or 128 (0 if no policy will be set)     */
   int32_t weight_dtype;      /* MPE_WEIGHTS_FP32 or MPE_WEIGHTS_BF16                       */
   int32_t reward_mode;       /* MPE_REWARD_SHARED or MPE_REWARD_MIXED                      */
   float   local_ratio;       /* in [0, 1]; used by MPE_REWARD_MIXED only (0.5)             */
+  int32_t scenario;          /* MPE_SCENARIO_SPREAD or MPE_SCENARIO_TAG                    */
+  /* MPE_SCENARIO_TAG only (ignored otherwise; reward_mode and local_ratio are then unused): */
+  int32_t num_adversaries;   /* in [1, N-1]: agents 0..num_adversaries-1                   */
+  float   adv_radius;        /* 0.075                                                      */
+  float   adv_accel;         /* 3                                                          */
+  float   adv_max_speed;     /* 1.0 : > 0                                                  */
+  float   good_max_speed;    /* 1.3 : > 0                                                  */
 } mpe_config;
 
 /* Validate `cfg` (host only), then allocate the device state of TE environments:
  * pos_a, vel_a [2][N][TE] fp32, pos_l [2][L][TE] fp32, ep_step [TE] int32.
+ * MPE_SCENARIO_TAG is built for (N, L, good agents) in (4, 2, 1), (2, 1, 1), (3, 0, 1), (6, 2, 2);
+ * MPE_EINVAL for other shapes.
  * `*out` receives the handle.  MPE_EINVAL for a bad config, MPE_EHIP if allocation fails. */
 int mpe_create(const mpe_config* cfg, mpe_env** out);
 
 /* Free the handle and its device buffers (synchronises the device first). NULL is allowed. */
 int mpe_destroy(mpe_env* env);
 
-/* Observation length D of this handle (6N), or MPE_EINVAL for NULL. */
+/* Observation length D of this handle (6N; tag: 4 + 2L + 2(N-1) + 2G), or MPE_EINVAL for NULL. */
 int mpe_obs_dim(const mpe_env* env);
 
 /* reset(key): start every environment from the seeded initial distribution -- agent and
@@ -104,7 +136,7 @@ int mpe_reset(mpe_env* env, uint32_t seed, float* obs, void* stream);
  * obs:     [TE][N][D] fp32 out, observation after the step (of the new episode where done),
  *          may be NULL.
  * reward:  [TE] fp32 out, shared by the env's agents: -sum_l min_a |p_a - p_l| after the step
- *          ([TE][N] mixed per-agent rewards with MPE_REWARD_MIXED).
+ *          ([TE][N] per-agent rewards with MPE_REWARD_MIXED and with MPE_SCENARIO_TAG).
  * done:    [TE] uint8 out, 1 when the episode reached max_episode_steps; that env has then
  *          already been reset with counter (env, abs_step + 1, entity, 0).
  * reward and done may be NULL.  Advances the absolute step counter by 1.
@@ -119,8 +151,9 @@ int mpe_step(mpe_env* env, const uint8_t* actions, float* obs, float* reward, ui
  * operand layout on `stream` (rounding W to bf16, ties to even, when weight_dtype is
  * MPE_WEIGHTS_BF16); the caller's arrays are not referenced after that work has run.
  * Policies are built for (num_agents, hidden, weight_dtype) in (1..3, 64, fp32 or bf16) and
- * (10, 128, bf16).  MPE_EINVAL for other shapes, if only some pointers are NULL, or if the config
- * has no usable `hidden`. */
+ * (10, 128, bf16); with MPE_SCENARIO_TAG for hidden 64, fp32, and the shapes with D <= 16 (all but
+ * (6, 2, 2)).  MPE_EINVAL for other shapes, if only some pointers are NULL, or if the config has no
+ * usable `hidden`. */
 int mpe_set_policy(mpe_env* env, const float* W1, const float* b1, const float* W2,
                    const float* b2, const float* W3, const float* b3, void* stream);
 
@@ -129,7 +162,7 @@ int mpe_set_policy(mpe_env* env, const float* W1, const float* b1, const float* 
  * no policy, uniform with counter (env, abs_step + t, agent, 1)), record it, apply the
  * transition, record reward and done.
  * obs_traj [T][TE][N][D] fp32, act_traj [T][TE][N] uint8, rew_traj [T][TE] fp32
- * ([T][TE][N] with MPE_REWARD_MIXED), done_traj [T][TE] uint8, last_obs [TE][N][D] fp32
+ * ([T][TE][N] with MPE_REWARD_MIXED and MPE_SCENARIO_TAG), done_traj [T][TE] uint8, last_obs [TE][N][D] fp32
  * (observation after the last step).
  * Any of the five may be NULL (that output is then not written).
  * T >= 1.  Advances the absolute step counter by T.  MPE_ESTATE as for mpe_step. */
@@ -142,7 +175,7 @@ int mpe_rollout(mpe_env* env, int32_t T, float* obs_traj, uint8_t* act_traj, flo
  *   value = V3^T tanh(V2^T tanh(V1^T obs + c1) + c2) + c3
  * V1 [R][D][H], c1 [R][H], V2 [R][H][H], c2 [R][H], V3 [R][H], c3 [R], fp32 device pointers;
  * copied (and rounded, with MPE_WEIGHTS_BF16) as in mpe_set_policy.  Built for hidden 64 and
- * 1..3 agents; MPE_EINVAL otherwise. */
+ * 1..3 agents of MPE_SCENARIO_SPREAD; MPE_EINVAL otherwise. */
 int mpe_set_critic(mpe_env* env, const float* V1, const float* c1, const float* V2,
                    const float* c2, const float* V3, const float* c3, void* stream);
 
@@ -160,8 +193,8 @@ int mpe_rollout_ac(mpe_env* env, int32_t T, float* obs_traj, uint8_t* act_traj, 
 /* Copy the state out / in (device to device, on `stream`).  Layouts: pos_a, vel_a
  * [2][N][TE], pos_l [2][L][TE] fp32 (coordinate-major, env fastest), ep_step [TE] int32.
  * Output pointers of mpe_get_state may be NULL individually; abs_step is a HOST pointer
- * (may be NULL).  mpe_set_state needs all four arrays, replaces seed and absolute step
- * counter, and makes the handle steppable. */
+ * (may be NULL).  mpe_set_state needs all four arrays (pos_l may be NULL when there are no
+ * landmarks), replaces seed and absolute step counter, and makes the handle steppable. */
 int mpe_get_state(mpe_env* env, float* pos_a, float* vel_a, float* pos_l, int32_t* ep_step,
                   uint32_t* abs_step, void* stream);
 int mpe_set_state(mpe_env* env, const float* pos_a, const float* vel_a, const float* pos_l,

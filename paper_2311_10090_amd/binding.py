@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libmpe.so")
 MPE_OK, MPE_EINVAL, MPE_ESTATE, MPE_EHIP = 0, -1, -2, -3
 WEIGHTS_FP32, WEIGHTS_BF16 = 0, 1
 REWARD_SHARED, REWARD_MIXED = 0, 1
+SCENARIO_SPREAD, SCENARIO_TAG = 0, 1
 NUM_ACTIONS = 5
 
 EXPORTS = ("mpe_create", "mpe_destroy", "mpe_obs_dim", "mpe_reset", "mpe_step", "mpe_set_policy",
@@ -37,7 +38,8 @@ class _CConfig(C.Structure):
                 [(n, C.c_float) for n in ("dt", "damping", "mass", "accel", "agent_radius",
                                           "landmark_radius", "contact_force", "contact_margin")] +
                 [("hidden", C.c_int32), ("weight_dtype", C.c_int32), ("reward_mode", C.c_int32),
-                 ("local_ratio", C.c_float)])
+                 ("local_ratio", C.c_float), ("scenario", C.c_int32), ("num_adversaries", C.c_int32)] +
+                [(n, C.c_float) for n in ("adv_radius", "adv_accel", "adv_max_speed", "good_max_speed")])
 
 
 @dataclass
@@ -59,6 +61,12 @@ class MpeConfig:
     weight_dtype: int = WEIGHTS_FP32
     reward_mode: int = REWARD_SHARED
     local_ratio: float = 0.5
+    scenario: int = SCENARIO_SPREAD
+    num_adversaries: int = 0        # SCENARIO_TAG: agents 0..num_adversaries-1; agent_radius / accel: good agents
+    adv_radius: float = 0.075
+    adv_accel: float = 3.0
+    adv_max_speed: float = 1.0
+    good_max_speed: float = 1.3
 
     def to_c(self) -> _CConfig:
         return _CConfig(**{f.name: getattr(self, f.name) for f in fields(self)})
@@ -124,11 +132,12 @@ class MpeEnv:
         with torch.cuda.device(self.device):
             cc = cfg.to_c()
             _check(self.lib.mpe_create(C.byref(cc), C.byref(self.h)))
-        self.E, self.N, self.R = cfg.num_envs, cfg.num_agents, cfg.num_runs
+        self.E, self.N, self.R, self.L = cfg.num_envs, cfg.num_agents, cfg.num_runs, cfg.num_landmarks
         self.TE = self.E * self.R
         self.D = _check(self.lib.mpe_obs_dim(self.h))
-        # rewards per env: one shared value, or one per agent in the mixed mode
-        self.rew_shape = (self.TE, self.N) if cfg.reward_mode == REWARD_MIXED else (self.TE,)
+        # rewards per env: one shared value, or one per agent in the mixed mode and in the tag scenario
+        per_agent = cfg.reward_mode == REWARD_MIXED or cfg.scenario == SCENARIO_TAG
+        self.rew_shape = (self.TE, self.N) if per_agent else (self.TE,)
 
     def close(self):
         if getattr(self, "h", None) is not None and self.h.value:
@@ -198,10 +207,10 @@ class MpeEnv:
         return obs_traj, act_traj, logp_traj, value_traj, rew_traj, done_traj, last_obs, last_value
 
     def get_state(self):
-        """Returns pos_a, vel_a, pos_l ([2][N][TE] fp32), ep_step ([TE] int32) tensors and abs_step."""
+        """Returns pos_a, vel_a ([2][N][TE]), pos_l ([2][L][TE] fp32), ep_step ([TE] int32) tensors and abs_step."""
         pos_a = torch.empty((2, self.N, self.TE), dtype=torch.float32, device=self.device)
         vel_a = torch.empty_like(pos_a)
-        pos_l = torch.empty_like(pos_a)
+        pos_l = torch.empty((2, self.L, self.TE), dtype=torch.float32, device=self.device)
         ep = torch.empty((self.TE,), dtype=torch.int32, device=self.device)
         s = C.c_uint32()
         with torch.cuda.device(self.device):

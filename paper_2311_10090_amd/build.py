@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmpe.so")
-SOURCES = ["mpe_api.hip", "mpe_env_kernels.hip", "mpe_policy_wide.hip", "mpe_policy_f32.hip", "mpe_policy_dispatch.hip"]
+SOURCES = ["mpe_api.hip", "mpe_env_kernels.hip", "mpe_policy_wide.hip", "mpe_policy_f32.hip", "mpe_policy_dispatch.hip", "mpe_tag.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 
@@ -41,7 +41,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
             print(err, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=6) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     tmp = LIB + ".tmp%d" % os.getpid()
     r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs],

@@ -15,6 +15,9 @@ using namespace mpe;
 struct mpe_env {
   mpe_config cfg;
   int N = 0, D = 0, H = 0;
+  int L = 0, G = 0;     // landmarks; good agents (tag scenario)
+  bool tag = false;
+  TagPhys tg{};
   uint32_t TE = 0, E = 0, R = 0;
   Phys ph{};
   StatePtrs st{};
@@ -54,9 +57,24 @@ int validate(const mpe_config* c) {
   if (c->num_runs < 1) return fail(MPE_EINVAL, "num_runs must be >= 1 (got %d)", c->num_runs);
   if (c->num_agents < 1 || c->num_agents > MPE_MAX_AGENTS)
     return fail(MPE_EINVAL, "num_agents must be in [1, %d] (got %d)", MPE_MAX_AGENTS, c->num_agents);
-  if (c->num_landmarks != c->num_agents)
+  if (c->scenario != MPE_SCENARIO_SPREAD && c->scenario != MPE_SCENARIO_TAG)
+    return fail(MPE_EINVAL, "scenario must be MPE_SCENARIO_SPREAD or MPE_SCENARIO_TAG (got %d)", c->scenario);
+  if (c->scenario == MPE_SCENARIO_SPREAD && c->num_landmarks != c->num_agents)
     return fail(MPE_EINVAL, "simple-spread needs num_landmarks == num_agents (got %d, %d)",
                 c->num_landmarks, c->num_agents);
+  if (c->scenario == MPE_SCENARIO_TAG) {
+    if (c->num_adversaries < 1 || c->num_adversaries >= c->num_agents)
+      return fail(MPE_EINVAL, "MPE_SCENARIO_TAG needs 1 <= num_adversaries < num_agents (got %d, %d)",
+                  c->num_adversaries, c->num_agents);
+    if (!tag_supported(c->num_agents, c->num_landmarks, c->num_agents - c->num_adversaries))
+      return fail(MPE_EINVAL, "MPE_SCENARIO_TAG is built for (agents, landmarks, good agents) in "
+                              "{(4,2,1), (2,1,1), (3,0,1), (6,2,2)} (got %d, %d, %d)",
+                  c->num_agents, c->num_landmarks, c->num_agents - c->num_adversaries);
+    if (!std::isfinite(c->adv_radius) || c->adv_radius < 0.0f || !std::isfinite(c->adv_accel))
+      return fail(MPE_EINVAL, "adv_radius must be finite and >= 0, adv_accel finite");
+    if (!finite_pos(c->adv_max_speed) || !finite_pos(c->good_max_speed))
+      return fail(MPE_EINVAL, "adv_max_speed and good_max_speed must be finite and > 0");
+  }
   const uint64_t te = uint64_t(c->num_envs) * uint64_t(c->num_runs);
   if (te > (1ull << 30)) return fail(MPE_EINVAL, "num_envs * num_runs must be <= 2^30");
   if (c->max_episode_steps < 1) return fail(MPE_EINVAL, "max_episode_steps must be >= 1");
@@ -80,6 +98,7 @@ int validate(const mpe_config* c) {
 }
 
 size_t agent_floats(const mpe_env* e) { return size_t(2) * e->N * e->TE; }
+size_t landmark_floats(const mpe_env* e) { return size_t(2) * e->L * e->TE; }
 
 }  // namespace
 
@@ -95,7 +114,10 @@ int mpe_create(const mpe_config* cfg, mpe_env** out) {
   if (!e) return fail(MPE_EHIP, "out of host memory");
   e->cfg = *cfg;
   e->N = cfg->num_agents;
-  e->D = 6 * e->N;
+  e->L = cfg->num_landmarks;
+  e->tag = cfg->scenario == MPE_SCENARIO_TAG;
+  e->G = e->tag ? e->N - cfg->num_adversaries : 0;
+  e->D = e->tag ? 4 + 2 * e->L + 2 * (e->N - 1) + 2 * e->G : 6 * e->N;
   e->H = cfg->hidden;
   e->E = uint32_t(cfg->num_envs);
   e->R = uint32_t(cfg->num_runs);
@@ -112,10 +134,30 @@ int mpe_create(const mpe_config* cfg, mpe_env** out) {
   e->ph.reward_mode = cfg->reward_mode;
   e->ph.local_ratio = cfg->reward_mode == MPE_REWARD_MIXED ? cfg->local_ratio : 0.0f;
   e->ph.two_r_sq = float(4.0 * double(cfg->agent_radius) * double(cfg->agent_radius));
+  if (e->tag) {
+    TagPhys& t = e->tg;
+    t.dt = cfg->dt;
+    t.keep = e->ph.keep;
+    t.dt_over_mass = e->ph.dt_over_mass;
+    t.inv_margin = e->ph.inv_margin;
+    t.force_margin = e->ph.force_margin;
+    t.max_ep = cfg->max_episode_steps;
+    t.radius[0] = cfg->adv_radius;
+    t.radius[1] = cfg->agent_radius;
+    t.gain[0] = cfg->adv_accel;
+    t.gain[1] = cfg->accel;
+    t.limit[0] = cfg->adv_max_speed;
+    t.limit[1] = cfg->good_max_speed;
+    t.limit_sq[0] = float(double(cfg->adv_max_speed) * double(cfg->adv_max_speed));
+    t.limit_sq[1] = float(double(cfg->good_max_speed) * double(cfg->good_max_speed));
+    t.lm_radius = cfg->landmark_radius;
+    const double touch = double(cfg->adv_radius) + double(cfg->agent_radius);
+    t.touch_sq = float(touch * touch);
+  }
   const size_t nf = agent_floats(e) * sizeof(float);
   hipError_t err = hipMalloc(&e->st.pos_a, nf);
   if (err == hipSuccess) err = hipMalloc(&e->st.vel_a, nf);
-  if (err == hipSuccess) err = hipMalloc(&e->st.pos_l, nf);
+  if (err == hipSuccess) err = hipMalloc(&e->st.pos_l, landmark_floats(e) * sizeof(float) + 16);
   if (err == hipSuccess) err = hipMalloc(&e->st.ep_step, size_t(e->TE) * sizeof(int32_t));
   if (err != hipSuccess) {
     int rc = fail(MPE_EHIP, "mpe_create: hipMalloc failed: %s", hipGetErrorString(err));
@@ -148,7 +190,8 @@ int mpe_obs_dim(const mpe_env* e) {
 int mpe_reset(mpe_env* e, uint32_t seed, float* obs, void* stream) {
   if (!e) return fail(MPE_EINVAL, "mpe_reset: NULL handle");
   if (obs && !aligned16(obs)) return fail(MPE_EINVAL, "mpe_reset: obs must be 16-byte aligned");
-  launch_reset(e->N, e->st, e->TE, e->E, seed, obs, static_cast<hipStream_t>(stream));
+  if (e->tag) launch_tag_reset(e->N, e->L, e->G, e->st, e->TE, e->E, seed, obs, static_cast<hipStream_t>(stream));
+  else launch_reset(e->N, e->st, e->TE, e->E, seed, obs, static_cast<hipStream_t>(stream));
   MPE_HIP(hipGetLastError());
   e->seed = seed;
   e->abs_step = 0;
@@ -162,8 +205,27 @@ int mpe_step(mpe_env* e, const uint8_t* actions, float* obs, float* reward, uint
   if (!e->ready) return fail(MPE_ESTATE, "mpe_step: call mpe_reset or mpe_set_state first");
   if ((obs && !aligned16(obs)) || (reward && !aligned16(reward)))
     return fail(MPE_EINVAL, "mpe_step: obs and reward must be 16-byte aligned");
-  launch_step(e->N, e->st, e->ph, e->TE, e->E, e->seed, e->abs_step, actions, obs, reward, done,
-              static_cast<hipStream_t>(stream));
+  if (e->tag) {
+    TagArgs A{};
+    A.r.st = e->st;
+    A.r.TE = e->TE;
+    A.r.E = e->E;
+    A.r.seed = e->seed;
+    A.r.abs_step = e->abs_step;
+    A.r.T = 1;
+    A.r.rew_traj = reward;
+    A.r.done_traj = done;
+    A.r.last_obs = obs;
+    A.tg = e->tg;
+    A.actions_in = actions;
+    const char* why = nullptr;
+    hipError_t err = launch_tag_rollout(e->N, e->L, e->G, 0, A, nullptr, static_cast<hipStream_t>(stream), &why);
+    if (why) return fail(MPE_EINVAL, "mpe_step: %s", why);
+    if (err != hipSuccess) return fail(MPE_EHIP, "mpe_step: %s", hipGetErrorString(err));
+  } else {
+    launch_step(e->N, e->st, e->ph, e->TE, e->E, e->seed, e->abs_step, actions, obs, reward, done,
+                static_cast<hipStream_t>(stream));
+  }
   MPE_HIP(hipGetLastError());
   e->abs_step += 1;
   return MPE_OK;
@@ -181,8 +243,16 @@ int mpe_set_policy(mpe_env* e, const float* W1, const float* b1, const float* W2
   if (given != 6) return fail(MPE_EINVAL, "mpe_set_policy: pass all six arrays or none");
   if (e->H != 64 && e->H != 128) return fail(MPE_EINVAL, "mpe_set_policy: config.hidden must be 64 or 128");
   const char* why = nullptr;
-  hipError_t err = pack_policy(e->pol, e->N, e->H, int(e->R), e->cfg.weight_dtype, W1, b1, W2, b2, W3, b3,
-                               static_cast<hipStream_t>(stream), &why);
+  hipError_t err;
+  if (e->tag) {
+    if (!tag_policy_supported(e->N, e->L, e->G, e->H, e->cfg.weight_dtype))
+      return fail(MPE_EINVAL, "mpe_set_policy: MPE_SCENARIO_TAG policies are built for hidden 64, fp32 weights and "
+                              "observation rows of at most 16 floats");
+    err = pack_policy_tag(e->pol, e->N, e->L, e->G, int(e->R), W1, b1, W2, b2, W3, b3, static_cast<hipStream_t>(stream));
+  } else {
+    err = pack_policy(e->pol, e->N, e->H, int(e->R), e->cfg.weight_dtype, W1, b1, W2, b2, W3, b3,
+                      static_cast<hipStream_t>(stream), &why);
+  }
   if (why) return fail(MPE_EINVAL, "mpe_set_policy: %s", why);
   if (err != hipSuccess) return fail(MPE_EHIP, "mpe_set_policy: %s", hipGetErrorString(err));
   e->has_policy = true;
@@ -212,7 +282,17 @@ int mpe_rollout(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, float
   A.rew_traj = rew_traj;
   A.done_traj = done_traj;
   A.last_obs = last_obs;
-  if (e->has_policy) {
+  if (e->tag) {
+    TagArgs TA{};
+    TA.r = A;
+    TA.tg = e->tg;
+    TA.actions_in = nullptr;
+    const char* why = nullptr;
+    hipError_t err = launch_tag_rollout(e->N, e->L, e->G, e->has_policy ? 2 : 1, TA, e->pol.packed,
+                                        static_cast<hipStream_t>(stream), &why);
+    if (why) return fail(MPE_EINVAL, "mpe_rollout: %s", why);
+    if (err != hipSuccess) return fail(MPE_EHIP, "mpe_rollout: %s", hipGetErrorString(err));
+  } else if (e->has_policy) {
     const char* why = nullptr;
     hipError_t err = launch_rollout_policy(e->N, e->H, e->cfg.weight_dtype, A, e->pol,
                                            static_cast<hipStream_t>(stream), &why);
@@ -236,7 +316,7 @@ int mpe_set_critic(mpe_env* e, const float* V1, const float* c1, const float* V2
     return MPE_OK;
   }
   if (given != 6) return fail(MPE_EINVAL, "mpe_set_critic: pass all six arrays or none");
-  if (!f32_supported(e->N, e->H))
+  if (e->tag || !f32_supported(e->N, e->H))
     return fail(MPE_EINVAL, "mpe_set_critic: unsupported shape: the actor-critic rollout is built for "
                             "hidden 64 and 1..3 agents");
   hipError_t err = pack_policy_f32(e->critic, e->N, int(e->R), V1, c1, V2, c2, V3, c3, 1,
@@ -254,7 +334,7 @@ int mpe_rollout_ac(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, fl
   if (!e->ready) return fail(MPE_ESTATE, "mpe_rollout_ac: call mpe_reset or mpe_set_state first");
   if (!e->has_policy || !e->has_critic)
     return fail(MPE_ESTATE, "mpe_rollout_ac: needs mpe_set_policy and mpe_set_critic first");
-  if (!f32_supported(e->N, e->H)) return fail(MPE_EINVAL, "mpe_rollout_ac: unsupported shape");
+  if (e->tag || !f32_supported(e->N, e->H)) return fail(MPE_EINVAL, "mpe_rollout_ac: unsupported shape");
   for (const float* p : {obs_traj, logp_traj, value_traj, rew_traj, last_obs, last_value})
     if (p && !aligned16(p)) return fail(MPE_EINVAL, "mpe_rollout_ac: float outputs must be 16-byte aligned");
   if (uint64_t(e->abs_step) + uint64_t(T) > 0xFFFFFFFFull)
@@ -292,7 +372,8 @@ int mpe_get_state(mpe_env* e, float* pos_a, float* vel_a, float* pos_l, int32_t*
   const size_t nf = agent_floats(e) * sizeof(float);
   if (pos_a) MPE_HIP(hipMemcpyAsync(pos_a, e->st.pos_a, nf, hipMemcpyDeviceToDevice, s));
   if (vel_a) MPE_HIP(hipMemcpyAsync(vel_a, e->st.vel_a, nf, hipMemcpyDeviceToDevice, s));
-  if (pos_l) MPE_HIP(hipMemcpyAsync(pos_l, e->st.pos_l, nf, hipMemcpyDeviceToDevice, s));
+  const size_t nl = landmark_floats(e) * sizeof(float);
+  if (pos_l && nl) MPE_HIP(hipMemcpyAsync(pos_l, e->st.pos_l, nl, hipMemcpyDeviceToDevice, s));
   if (ep_step)
     MPE_HIP(hipMemcpyAsync(ep_step, e->st.ep_step, size_t(e->TE) * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
   if (abs_step) *abs_step = e->abs_step;
@@ -302,12 +383,13 @@ int mpe_get_state(mpe_env* e, float* pos_a, float* vel_a, float* pos_l, int32_t*
 int mpe_set_state(mpe_env* e, const float* pos_a, const float* vel_a, const float* pos_l,
                   const int32_t* ep_step, uint32_t seed, uint32_t abs_step, void* stream) {
   if (!e) return fail(MPE_EINVAL, "mpe_set_state: NULL handle");
-  if (!pos_a || !vel_a || !pos_l || !ep_step) return fail(MPE_EINVAL, "mpe_set_state: NULL array");
+  if (!pos_a || !vel_a || (!pos_l && e->L > 0) || !ep_step) return fail(MPE_EINVAL, "mpe_set_state: NULL array");
   hipStream_t s = static_cast<hipStream_t>(stream);
   const size_t nf = agent_floats(e) * sizeof(float);
   MPE_HIP(hipMemcpyAsync(e->st.pos_a, pos_a, nf, hipMemcpyDeviceToDevice, s));
   MPE_HIP(hipMemcpyAsync(e->st.vel_a, vel_a, nf, hipMemcpyDeviceToDevice, s));
-  MPE_HIP(hipMemcpyAsync(e->st.pos_l, pos_l, nf, hipMemcpyDeviceToDevice, s));
+  const size_t nl = landmark_floats(e) * sizeof(float);
+  if (nl) MPE_HIP(hipMemcpyAsync(e->st.pos_l, pos_l, nl, hipMemcpyDeviceToDevice, s));
   MPE_HIP(hipMemcpyAsync(e->st.ep_step, ep_step, size_t(e->TE) * sizeof(int32_t), hipMemcpyDeviceToDevice, s));
   e->seed = seed;
   e->abs_step = abs_step;

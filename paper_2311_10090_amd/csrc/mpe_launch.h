@@ -24,6 +24,38 @@ struct RolloutArgs {
   float* last_value = nullptr;  // [TE][N]    critic value of last_obs
 };
 
+// Predator-prey scenario: constants by role (index 0 adversary, 1 good agent), combined on the
+// host in double and rounded once.
+struct TagPhys {
+  float dt, keep, dt_over_mass, inv_margin, force_margin;
+  int32_t max_ep;
+  float radius[2];
+  float gain[2];
+  float limit[2];      // speed limit
+  float limit_sq[2];
+  float lm_radius;
+  float touch_sq;      // (adversary radius + good radius)^2
+};
+
+struct TagArgs {
+  RolloutArgs r;                 // state, sizes, seed, step, outputs (r.ph is unused)
+  TagPhys tg;
+  const uint8_t* actions_in;     // [TE][N], single step with given actions only
+};
+
+// (N, L, G) = agents, landmarks, good agents
+bool tag_supported(int N, int L, int G);
+bool tag_policy_supported(int N, int L, int G, int H, int weight_dtype);
+void launch_tag_reset(int N, int L, int G, const StatePtrs& st, uint32_t TE, uint32_t E, uint32_t seed, float* obs,
+                      hipStream_t s);
+// mode 0: one step under A.actions_in (r.T must be 1; obs after the step -> r.last_obs, reward ->
+// r.rew_traj, done -> r.done_traj); mode 1: uniform random actions; mode 2: the packed policy
+hipError_t launch_tag_rollout(int N, int L, int G, int mode, const TagArgs& A, const void* packed, hipStream_t s,
+                              const char** why);
+struct PolicyBuffers;
+hipError_t pack_policy_tag(PolicyBuffers& pb, int N, int L, int G, int R, const float* W1, const float* b1,
+                           const float* W2, const float* b2, const float* W3, const float* b3, hipStream_t s);
+
 void launch_reset(int N, const StatePtrs& st, uint32_t TE, uint32_t E, uint32_t seed, float* obs,
                   hipStream_t s);
 void launch_step(int N, const StatePtrs& st, const Phys& ph, uint32_t TE, uint32_t E, uint32_t seed,

@@ -1,0 +1,491 @@
+// Predator-prey ("simple tag") scenario of the MPE family (paper App. B.7: every scenario of the
+// family is implemented; Sec. 3.1 "MPE"): reset, single step, and the persistent T-step rollout
+// with uniform actions or with the fused fp32 policy (App. G: two tanh layers of width 64).
+//
+// Mapping: one lane per agent row, a block is 64 envs = N wavefronts (as in the fused simple-spread
+// kernel).  A lane keeps its own agent's position and velocity, the positions of all agents of its
+// env and the obstacle landmarks in registers; per step the agents of an env exchange their new
+// position and velocity through LDS (one barrier: wavefront-local when 64 % N == 0, the block
+// barrier otherwise).  Every lane writes its own observation row into an LDS tile; a wavefront's
+// 64 rows are one contiguous piece of the trajectory and leave with 16-byte stores over whole
+// cache lines.  Rewards are per agent, so every lane stores its own.
+#include "mpe_mlp64.h"
+
+namespace mpe {
+
+namespace {
+
+template <int N_, int L_, int G_>
+struct TagShape {
+  static constexpr int N = N_, L = L_, G = G_, A = N_ - G_;   // A adversaries first, then G good agents
+  static constexpr int D = 4 + 2 * L_ + 2 * (N_ - 1) + 2 * G_;
+  static constexpr bool kWaveLocal = (64 % N_) == 0;          // the rows of an env lie in one wavefront
+  static_assert(G_ >= 1 && A >= 1 && L_ >= 0 && D % 2 == 0, "roles");
+};
+
+enum TagMode : int { kGiven = 0, kUniform = 1, kPolicy = 2 };
+
+template <typename S, int MODE>
+struct TagSmem {
+  static constexpr int ROWS = 64 * S::N;
+  static constexpr size_t OFF_BIAS = MODE == kPolicy ? Pk::LDS_BYTES : 0;
+  static constexpr size_t OFF_OBS = OFF_BIAS + (MODE == kPolicy ? Pk::BIAS_BYTES : 0);
+  static constexpr size_t OBS = size_t(ROWS) * S::D * 4 + 64;   // + zeroed tail: layer 1 reads 16 cols
+  static constexpr size_t OFF_XCH = OFF_OBS + OBS;              // [parity][ROWS] float4 (px, py, vx, vy)
+  static constexpr size_t TOTAL = OFF_XCH + size_t(S::kWaveLocal ? 1 : 2) * ROWS * 16;
+  static_assert(OFF_OBS % 16 == 0 && OFF_XCH % 16 == 0, "alignment");
+};
+
+// Contact force factor k of a pair with separation (dx, dy) and contact distance dmin: the force
+// on the first entity is k * (dx, dy).
+__device__ __forceinline__ float tag_contact(float dx, float dy, float dmin, const TagPhys& tg) {
+  const float d2 = fmaxf(fmaf(dx, dx, dy * dy), 1e-24f);
+  const float inv_d = hw_rsq(d2);
+  const float d = d2 * inv_d;
+  return tg.force_margin * softplus((dmin - d) * tg.inv_margin) * inv_d;
+}
+
+// Boundary penalty of a good agent for one coordinate, u = |coordinate|.
+__device__ __forceinline__ float tag_bound(float u) {
+  const float lin = (u - 0.9f) * 10.0f;
+  const float ex = fminf(hw_exp2((2.0f * u - 2.0f) * kLog2e), 10.0f);
+  return u < 0.9f ? 0.0f : (u < 1.0f ? lin : ex);
+}
+
+// Fresh positions of every entity of an env for the episode that starts at `step`.
+template <typename S>
+__device__ __forceinline__ void tag_draw_positions(float (&qx)[S::N], float (&qy)[S::N], float (&lx)[S::L + 1],
+                                                   float (&ly)[S::L + 1], uint32_t env, uint32_t step,
+                                                   uint32_t seed, uint32_t run) {
+#pragma unroll
+  for (int a = 0; a < S::N; ++a) {
+    const uint4 w = philox4x32_10(env, step, uint32_t(a), kTagResetPos, seed, run);
+    qx[a] = word_to_position(w.x);
+    qy[a] = word_to_position(w.y);
+  }
+#pragma unroll
+  for (int k = 0; k < S::L; ++k) {
+    const uint4 w = philox4x32_10(env, step, uint32_t(S::N + k), kTagResetPos, seed, run);
+    lx[k] = word_to_position(w.x) * 0.9f;   // obstacles start inside [-0.9, 0.9): one fp32 product
+    ly[k] = word_to_position(w.y) * 0.9f;
+  }
+}
+
+// Observation row of agent i: own velocity, own position, landmarks and other agents relative,
+// velocities of the other good agents, zero padding (good agents see one velocity fewer).
+template <typename S>
+__device__ __forceinline__ void tag_write_row(float2* row, int i, float px, float py, float vx, float vy,
+                                              const float (&qx)[S::N], const float (&qy)[S::N],
+                                              const float (&lx)[S::L + 1], const float (&ly)[S::L + 1],
+                                              const float (&gvx)[S::G], const float (&gvy)[S::G]) {
+  int c = 0;
+  row[c++] = make_float2(vx, vy);
+  row[c++] = make_float2(px, py);
+#pragma unroll
+  for (int k = 0; k < S::L; ++k) row[c++] = make_float2(lx[k] - px, ly[k] - py);
+#pragma unroll
+  for (int a = 0; a < S::N; ++a) {
+    if (a != i) row[c++] = make_float2(qx[a] - px, qy[a] - py);
+  }
+#pragma unroll
+  for (int k = 0; k < S::G; ++k) {
+    if (S::A + k != i) row[c++] = make_float2(gvx[k], gvy[k]);
+  }
+  if (i >= S::A) row[S::D / 2 - 1] = make_float2(0.0f, 0.0f);
+}
+
+template <typename S>
+__global__ __launch_bounds__(64 * S::N) void tag_reset_kernel(StatePtrs st, uint32_t TE, uint32_t E, uint32_t seed,
+                                                              float* __restrict__ obs) {
+  constexpr int N = S::N, L = S::L, D = S::D;
+  const int tid = threadIdx.x;
+  const int el = tid / N, i = tid - el * N;
+  const size_t g = size_t(blockIdx.x) * 64 + el;
+  if (g >= TE) return;
+  const uint32_t run = uint32_t(g) / E, env = uint32_t(g) - run * E;
+  float qx[N], qy[N], lx[L + 1], ly[L + 1], gvx[S::G], gvy[S::G];
+  tag_draw_positions<S>(qx, qy, lx, ly, env, 0u, seed, run);
+#pragma unroll
+  for (int k = 0; k < S::G; ++k) gvx[k] = gvy[k] = 0.0f;
+  float px = 0.0f, py = 0.0f;
+#pragma unroll
+  for (int a = 0; a < N; ++a) {
+    if (a == i) { px = qx[a]; py = qy[a]; }
+  }
+  st.pos_a[(0 * N + i) * size_t(TE) + g] = px;
+  st.pos_a[(1 * N + i) * size_t(TE) + g] = py;
+  st.vel_a[(0 * N + i) * size_t(TE) + g] = 0.0f;
+  st.vel_a[(1 * N + i) * size_t(TE) + g] = 0.0f;
+  if (i == 0) {
+#pragma unroll
+    for (int k = 0; k < L; ++k) {
+      st.pos_l[(0 * L + k) * size_t(TE) + g] = lx[k];
+      st.pos_l[(1 * L + k) * size_t(TE) + g] = ly[k];
+    }
+    st.ep_step[g] = 0;
+  }
+  if (obs) {
+    float2 row[D / 2];
+#pragma unroll
+    for (int c = 0; c < D / 2; ++c) row[c] = make_float2(0.0f, 0.0f);
+    tag_write_row<S>(row, i, px, py, 0.0f, 0.0f, qx, qy, lx, ly, gvx, gvy);
+    float2* dst = reinterpret_cast<float2*>(obs + (g * N + i) * D);
+#pragma unroll
+    for (int c = 0; c < D / 2; ++c) dst[c] = row[c];
+  }
+}
+
+template <typename S, int MODE>
+__global__ __launch_bounds__(64 * S::N, MODE == kPolicy ? 3 : 1) void tag_rollout_kernel(
+    TagArgs TA, const uint8_t* __restrict__ packed, int per_run_weights, uint32_t groups, uint32_t groups_per_xcd) {
+  using M = TagSmem<S, MODE>;
+  using Net = NetShape<S::D, S::D <= 16 ? S::D : 16>;
+  constexpr int N = S::N, L = S::L, G = S::G, NA = S::A, D = S::D, ROWS = 64 * N, THREADS = ROWS;
+  const RolloutArgs& A = TA.r;
+  const TagPhys& tg = TA.tg;
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+  float* tile = reinterpret_cast<float*>(smem + M::OFF_OBS);
+  float4* xch = reinterpret_cast<float4*>(smem + M::OFF_XCH);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int el = tid / N, i = tid - el * N;          // env within block, agent
+  const size_t TE = A.TE;
+  // block b runs on XCD b % 8: give each XCD one contiguous range of env groups
+  const uint32_t grp = (blockIdx.x & 7u) * groups_per_xcd + (blockIdx.x >> 3);
+  if (grp >= groups) return;  // whole block, before any barrier
+  const size_t g0 = size_t(grp) * 64;
+  const size_t g = g0 + el;
+  const bool valid = g < TE;
+  const uint32_t gc = valid ? uint32_t(g) : uint32_t(g0);
+  const uint32_t run = gc / A.E;
+  const uint32_t env = gc - run * A.E;
+  const size_t left = TE - g0;
+  const int nvalid = left < size_t(64) ? int(left) : 64;
+  const int wave_rows = min(max(nvalid * N - wave * 64, 0), 64);   // rows of this wavefront that exist
+
+  // ---- policy: W1A, W2A and the biases in LDS, W3A in registers (the run of the block's first env)
+  W3Terms w3;
+  if constexpr (MODE == kPolicy) {
+    const uint8_t* run_weights = packed + (per_run_weights ? size_t(uint32_t(g0) / A.E) * Pk::RUN_BYTES : 0);
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      if constexpr (Net::kRowTerms) {
+        w3.s[s].h = reinterpret_cast<const bf16x8*>(run_weights + Pk::OFF_W3A)[s * 64 + lane];
+      } else {
+        const bf16x8* src = reinterpret_cast<const bf16x8*>(run_weights + Pk::OFF_W3A) + s * 3 * 64 + lane;
+        w3.s[s].h = src[0];
+        w3.s[s].m = src[64];
+        w3.s[s].l = src[128];
+      }
+    }
+    const uint4* src = reinterpret_cast<const uint4*>(run_weights);
+    uint4* dst = reinterpret_cast<uint4*>(smem);
+    for (int k = tid; k < int(Pk::LDS_BYTES / 16); k += THREADS) dst[k] = src[k];
+    const uint4* bsrc = reinterpret_cast<const uint4*>(run_weights + Pk::OFF_BIAS);
+    uint4* bdst = reinterpret_cast<uint4*>(smem + M::OFF_BIAS);
+    for (int k = tid; k < int(Pk::BIAS_BYTES / 16); k += THREADS) bdst[k] = bsrc[k];
+  }
+  if (tid < 16) tile[ROWS * D + tid] = 0.0f;
+
+  // ---- registers: own agent, all agents' positions, good agents' velocities, landmarks
+  const int role = i < NA ? 0 : 1;
+  const float my_radius = role == 0 ? tg.radius[0] : tg.radius[1];
+  const float my_gain = role == 0 ? tg.gain[0] : tg.gain[1];
+  const float my_limit = role == 0 ? tg.limit[0] : tg.limit[1];
+  const float my_limit_sq = role == 0 ? tg.limit_sq[0] : tg.limit_sq[1];
+  float px = 0.0f, py = 0.0f, vx = 0.0f, vy = 0.0f;
+  float qx[N], qy[N], lx[L + 1], ly[L + 1], gvx[G], gvy[G];
+  int32_t ep = 0;
+#pragma unroll
+  for (int a = 0; a < N; ++a) qx[a] = qy[a] = 0.0f;
+#pragma unroll
+  for (int k = 0; k < L + 1; ++k) lx[k] = ly[k] = 0.0f;
+#pragma unroll
+  for (int k = 0; k < G; ++k) gvx[k] = gvy[k] = 0.0f;
+  if (valid) {
+#pragma unroll
+    for (int a = 0; a < N; ++a) {
+      qx[a] = A.st.pos_a[(0 * N + a) * TE + g];
+      qy[a] = A.st.pos_a[(1 * N + a) * TE + g];
+    }
+#pragma unroll
+    for (int k = 0; k < L; ++k) {
+      lx[k] = A.st.pos_l[(0 * L + k) * TE + g];
+      ly[k] = A.st.pos_l[(1 * L + k) * TE + g];
+    }
+#pragma unroll
+    for (int k = 0; k < G; ++k) {
+      gvx[k] = A.st.vel_a[(0 * N + NA + k) * TE + g];
+      gvy[k] = A.st.vel_a[(1 * N + NA + k) * TE + g];
+    }
+    vx = A.st.vel_a[(0 * N + i) * TE + g];
+    vy = A.st.vel_a[(1 * N + i) * TE + g];
+    ep = A.st.ep_step[g];
+  }
+#pragma unroll
+  for (int a = 0; a < N; ++a) {
+    if (a == i) { px = qx[a]; py = qy[a]; }
+  }
+  float2* my_row = reinterpret_cast<float2*>(tile + tid * D);
+  tag_write_row<S>(my_row, i, px, py, vx, vy, qx, qy, lx, ly, gvx, gvy);
+  __syncthreads();  // weights, biases, zero tail staged
+
+  const size_t wave_row0 = (g0 * N + size_t(wave) * 64) * D;   // float offset of this wavefront's rows in a slice
+  float* obs_p = A.obs_traj ? A.obs_traj + wave_row0 : nullptr;
+  uint8_t* act_base = A.act_traj;
+  float* rew_base = A.rew_traj;
+  uint8_t* done_base = A.done_traj;
+  const size_t row_off = size_t(gc) * N + i;          // index of this agent inside a time slice
+  const bool env_writer = valid && i == 0;            // the lane that stores per-env outputs
+  uint32_t step = A.abs_step;
+  const float* wtile = tile + wave * (64 * D);        // this wavefront's rows
+
+  auto flush_rows = [&](float* dst) {
+    const bool vec4 = (reinterpret_cast<uintptr_t>(dst) & 15u) == 0;
+    if (vec4 && wave_rows == 64) stream_out_full<64 * D / 4>(wtile, dst, lane);
+    else stream_out(wtile, dst, wave_rows * D, vec4, lane);
+  };
+
+  for (int t = 0; t < A.T; ++t, ++step) {
+    wave_sync();  // this wavefront's rows of the tile are complete
+    if (obs_p) {
+      flush_rows(obs_p);
+      obs_p += TE * (N * D);
+    }
+    // ---- action
+    uint32_t act;
+    if constexpr (MODE == kGiven) {
+      const uint32_t v = valid ? TA.actions_in[row_off] : 0u;
+      act = v < uint32_t(kNumActions) ? v : 0u;
+    } else if constexpr (MODE == kUniform) {
+      act = word_to_action(philox4x32_10(env, step, uint32_t(i), kTagUniformAction, A.seed, run).x);
+    } else {
+      const float* bias = reinterpret_cast<const float*>(smem + M::OFF_BIAS);
+#pragma unroll 1
+      for (int pr = 0; pr < 2; ++pr) {
+        float* rows = tile + (wave * 64 + pr * 32) * D;
+        policy_pair<Net>(smem, bias, w3, rows, rows + 16 * D, lane);
+      }
+      wave_sync();
+      float z[kNumActions];
+#pragma unroll
+      for (int k = 0; k < kNumActions; ++k) z[k] = tile[tid * D + k];
+      if constexpr (Net::kRowTerms) z[4] = (z[4] + tile[tid * D + 5]) + tile[tid * D + 6];
+      act = gumbel_argmax(z, A.seed, run, env, step, uint32_t(i));
+    }
+    if (act_base) {
+      if (valid) act_base[row_off] = uint8_t(act);
+      act_base += TE * N;
+    }
+
+    // ---- transition of this lane's agent: control, contacts with agents and obstacles on the
+    // pre-step positions, position with the old velocity, damped velocity, speed limit
+    float fx = my_gain * action_dir_x(act);
+    float fy = my_gain * action_dir_y(act);
+#pragma unroll
+    for (int a = 0; a < N; ++a) {
+      if (a != i) {
+        const float dx = px - qx[a], dy = py - qy[a];
+        const float k = tag_contact(dx, dy, my_radius + tg.radius[a < NA ? 0 : 1], tg);
+        fx = fmaf(k, dx, fx);
+        fy = fmaf(k, dy, fy);
+      }
+    }
+#pragma unroll
+    for (int l = 0; l < L; ++l) {
+      const float dx = px - lx[l], dy = py - ly[l];
+      const float k = tag_contact(dx, dy, my_radius + tg.lm_radius, tg);
+      fx = fmaf(k, dx, fx);
+      fy = fmaf(k, dy, fy);
+    }
+    px = fmaf(vx, tg.dt, px);
+    py = fmaf(vy, tg.dt, py);
+    vx = fmaf(fx, tg.dt_over_mass, vx * tg.keep);
+    vy = fmaf(fy, tg.dt_over_mass, vy * tg.keep);
+    {
+      const float s2 = fmaf(vx, vx, vy * vy);
+      if (s2 > my_limit_sq) {
+        const float k = my_limit * hw_rsq(s2);
+        vx *= k;
+        vy *= k;
+      }
+    }
+    float4* slot = xch + (S::kWaveLocal ? 0 : (t & 1) * ROWS);
+    slot[tid] = make_float4(px, py, vx, vy);
+    // new positions and velocities of every agent of this env are visible
+    if constexpr (S::kWaveLocal) wave_sync(); else __syncthreads();
+#pragma unroll
+    for (int a = 0; a < N; ++a) {
+      const float4 p = slot[el * N + a];
+      qx[a] = p.x;
+      qy[a] = p.y;
+      if (a >= NA) {
+        gvx[a - NA] = p.z;
+        gvy[a - NA] = p.w;
+      }
+    }
+    if constexpr (S::kWaveLocal) wave_sync();   // the slots are rewritten in the next step
+
+    // ---- rewards on the new positions: touching (good, adversary) pairs
+    {
+      uint32_t caught = 0, hits = 0;
+#pragma unroll
+      for (int a = 0; a < NA; ++a) {
+#pragma unroll
+        for (int b = NA; b < N; ++b) {
+          const float dx = qx[a] - qx[b], dy = qy[a] - qy[b];
+          const uint32_t touch = fmaf(dx, dx, dy * dy) < tg.touch_sq ? 1u : 0u;
+          caught += touch;
+          hits += b == i ? touch : 0u;
+        }
+      }
+      const float r_good = -10.0f * float(hits) - tag_bound(fabsf(px)) - tag_bound(fabsf(py));
+      const float r = role == 0 ? 10.0f * float(caught) : r_good;
+      if (rew_base) {
+        if (valid) rew_base[row_off] = r;
+        rew_base += TE * N;
+      }
+    }
+    ep += 1;
+    const bool done = ep >= tg.max_ep;
+    if (done_base) {
+      if (env_writer) done_base[gc] = done ? 1 : 0;
+      done_base += TE;
+    }
+    if (done) {
+      // new episode keyed by step + 1; every lane regenerates the whole env (1 step in max_ep).
+      // The empty asm keeps the env-dependent first Philox round out of the step loop's preamble.
+      uint32_t env_r = env;
+      asm volatile("" : "+v"(env_r));
+      tag_draw_positions<S>(qx, qy, lx, ly, env_r, step + 1u, A.seed, run);
+#pragma unroll
+      for (int a = 0; a < N; ++a) {
+        if (a == i) { px = qx[a]; py = qy[a]; }
+      }
+#pragma unroll
+      for (int k = 0; k < G; ++k) gvx[k] = gvy[k] = 0.0f;
+      vx = vy = 0.0f;
+      ep = 0;
+    }
+    tag_write_row<S>(my_row, i, px, py, vx, vy, qx, qy, lx, ly, gvx, gvy);
+  }
+  if (A.last_obs) {
+    wave_sync();
+    flush_rows(A.last_obs + wave_row0);
+  }
+
+  // ---- state back to HBM
+  if (valid) {
+    A.st.pos_a[(0 * N + i) * TE + g] = px;
+    A.st.pos_a[(1 * N + i) * TE + g] = py;
+    A.st.vel_a[(0 * N + i) * TE + g] = vx;
+    A.st.vel_a[(1 * N + i) * TE + g] = vy;
+    if (i == 0) {
+#pragma unroll
+      for (int k = 0; k < L; ++k) {
+        A.st.pos_l[(0 * L + k) * TE + g] = lx[k];
+        A.st.pos_l[(1 * L + k) * TE + g] = ly[k];
+      }
+      A.st.ep_step[g] = ep;
+    }
+  }
+}
+
+template <typename S, int MODE>
+hipError_t tag_rollout_impl(const TagArgs& A, const void* packed, hipStream_t s) {
+  using M = TagSmem<S, MODE>;
+  auto kern = tag_rollout_kernel<S, MODE>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(M::TOTAL));
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const uint32_t groups = (A.r.TE + 63) / 64;
+  const uint32_t per_xcd = (groups + 7) / 8;
+  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(64 * S::N), M::TOTAL, s, A, static_cast<const uint8_t*>(packed),
+                     int(A.r.TE != A.r.E), groups, per_xcd);
+  return hipGetLastError();
+}
+
+template <typename S>
+hipError_t tag_launch(int mode, const TagArgs& A, const void* packed, hipStream_t s, const char** why) {
+  if (mode == kGiven) return tag_rollout_impl<S, kGiven>(A, nullptr, s);
+  if (mode == kUniform) return tag_rollout_impl<S, kUniform>(A, nullptr, s);
+  if constexpr (S::D <= 16) {
+    if (A.r.TE != A.r.E && A.r.E % 64 != 0) {
+      *why = "with several runs, num_envs per run must be a multiple of 64";
+      return hipSuccess;
+    }
+    return tag_rollout_impl<S, kPolicy>(A, packed, s);
+  } else {
+    *why = "no policy kernel for this shape (observation rows longer than 16)";
+    return hipSuccess;
+  }
+}
+
+template <typename S>
+hipError_t tag_pack(PolicyBuffers& pb, int R, const float* W1, const float* b1, const float* W2, const float* b2,
+                    const float* W3, const float* b3, hipStream_t s) {
+  if constexpr (S::D <= 16) {
+    using Net = NetShape<S::D, S::D>;
+    if (hipError_t e = ensure_policy_bytes(pb, size_t(R) * Pk::RUN_BYTES); e != hipSuccess) return e;
+    constexpr int total = 4 * 64 * 8 + 4 * 2 * 64 * 8 + 2 * 64 * 8 + 2 * kH + 16;   // one thread per weight / bias
+    hipLaunchKernelGGL(pack_split_kernel<Net>, dim3((total + 255) / 256, R), dim3(256), 0, s,
+                       static_cast<uint8_t*>(pb.packed), W1, b1, W2, b2, W3, b3, 5);
+    return hipGetLastError();
+  } else {
+    return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+// The shapes that are built: (agents, landmarks, good agents).
+#define MPE_TAG_SHAPES(X) X(4, 2, 1) X(2, 1, 1) X(3, 0, 1) X(6, 2, 2)
+
+bool tag_supported(int N, int L, int G) {
+#define X(n, l, g) if (N == n && L == l && G == g) return true;
+  MPE_TAG_SHAPES(X)
+#undef X
+  return false;
+}
+
+bool tag_policy_supported(int N, int L, int G, int H, int weight_dtype) {
+  return tag_supported(N, L, G) && H == kH && weight_dtype == 0 && 4 + 2 * L + 2 * (N - 1) + 2 * G <= 16;
+}
+
+void launch_tag_reset(int N, int L, int G, const StatePtrs& st, uint32_t TE, uint32_t E, uint32_t seed, float* obs,
+                      hipStream_t s) {
+#define X(n, l, g)                                                                                      \
+  if (N == n && L == l && G == g) {                                                                     \
+    hipLaunchKernelGGL((tag_reset_kernel<TagShape<n, l, g>>), dim3((TE + 63) / 64), dim3(64 * n), 0, s, st, TE, E, \
+                       seed, obs);                                                                      \
+    return;                                                                                             \
+  }
+  MPE_TAG_SHAPES(X)
+#undef X
+}
+
+hipError_t launch_tag_rollout(int N, int L, int G, int mode, const TagArgs& A, const void* packed, hipStream_t s,
+                              const char** why) {
+#define X(n, l, g) \
+  if (N == n && L == l && G == g) return tag_launch<TagShape<n, l, g>>(mode, A, packed, s, why);
+  MPE_TAG_SHAPES(X)
+#undef X
+  return hipErrorInvalidValue;
+}
+
+hipError_t pack_policy_tag(PolicyBuffers& pb, int N, int L, int G, int R, const float* W1, const float* b1,
+                           const float* W2, const float* b2, const float* W3, const float* b3, hipStream_t s) {
+#define X(n, l, g) \
+  if (N == n && L == l && G == g) return tag_pack<TagShape<n, l, g>>(pb, R, W1, b1, W2, b2, W3, b3, s);
+  MPE_TAG_SHAPES(X)
+#undef X
+  return hipErrorInvalidValue;
+}
+
+}  // namespace mpe

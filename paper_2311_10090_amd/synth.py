@@ -18,6 +18,11 @@ PHYSICS = dict(dt=0.1, damping=0.25, mass=1.0, accel=5.0, agent_radius=0.15, lan
                contact_force=100.0, contact_margin=1e-3)
 MAX_EPISODE_STEPS = 25
 
+# Predator-prey ("simple tag") workload: good agents' radius / gain in agent_radius / accel.
+TAG_PHYSICS = dict(dt=0.1, damping=0.25, mass=1.0, accel=4.0, agent_radius=0.05, landmark_radius=0.2,
+                   contact_force=100.0, contact_margin=1e-3, adv_radius=0.075, adv_accel=3.0,
+                   adv_max_speed=1.0, good_max_speed=1.3)
+
 
 @dataclass(frozen=True)
 class Workload:
@@ -53,9 +58,9 @@ WORKLOADS = {
 }
 
 
-def physics_f32() -> dict:
+def physics_f32(table=None) -> dict:
     """The constants rounded to float32 and widened again: the exact values the fp32 path uses."""
-    return {k: float(np.float32(v)) for k, v in PHYSICS.items()}
+    return {k: float(np.float32(v)) for k, v in (PHYSICS if table is None else table).items()}
 
 
 def policy_weights(seed: int, num_runs: int, obs_dim: int, hidden: int):

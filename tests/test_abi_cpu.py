@@ -34,8 +34,8 @@ def test_header_symbols_are_exported(lib):
 
 
 def test_config_struct_matches_header():
-    # 5 int32 + 8 float + 3 int32 + 1 float, no padding
-    assert C.sizeof(binding._CConfig) == 17 * 4
+    # 5 int32 + 8 float + 3 int32 + 1 float + 2 int32 + 4 float, no padding
+    assert C.sizeof(binding._CConfig) == 23 * 4
     text = open(os.path.join(ROOT, "include", "mpe.h")).read()
     body = re.search(r"typedef struct \{(.*?)\} mpe_config;", text, flags=re.S).group(1)
     body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
@@ -51,6 +51,13 @@ def test_config_struct_matches_header():
     dict(contact_margin=0.0), dict(damping=1.5), dict(hidden=32), dict(weight_dtype=7),
     dict(dt=float("nan")), dict(accel=float("inf")), dict(num_envs=1 << 20, num_runs=1 << 11),
     dict(reward_mode=2), dict(reward_mode=1, local_ratio=1.5), dict(reward_mode=1, local_ratio=float("nan")),
+    dict(scenario=2), dict(scenario=1, num_agents=4, num_landmarks=2, num_adversaries=0),
+    dict(scenario=1, num_agents=4, num_landmarks=2, num_adversaries=4),
+    dict(scenario=1, num_agents=4, num_landmarks=3, num_adversaries=3),      # shape that is not built
+    dict(scenario=1, num_agents=5, num_landmarks=2, num_adversaries=3),
+    dict(scenario=1, num_agents=4, num_landmarks=2, num_adversaries=3, adv_max_speed=0.0),
+    dict(scenario=1, num_agents=4, num_landmarks=2, num_adversaries=3, good_max_speed=float("nan")),
+    dict(scenario=1, num_agents=4, num_landmarks=2, num_adversaries=3, adv_radius=-0.1),
 ])
 def test_bad_config_is_rejected_on_host(lib, bad):
     cfg = MpeConfig(**bad).to_c()
