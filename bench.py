@@ -207,6 +207,36 @@ def main():
         env5.close()
         del b5
 
+    # second scenario (predator-prey, 3 adversaries + 1 good agent + 2 obstacles) at the same number of
+    # envs and steps: fused fp32 policy 16 -> 64 -> 64 -> 5 and env-only with uniform actions
+    tag = {}
+    if args.workload == "cfg2":
+        k = max(3, args.steps // 3)
+        tN, tL, tA = 4, 2, 3
+        tD = Hp.tag_obs_dim(tN, tL, tA)
+        t_bytes = tN * tD * 4 + tN + 4 * tN + 1                 # obs + actions + per-agent rewards + done: 277
+        t_steps = wl.num_envs * tN * T
+        for name, hidden in (("fused", H), ("env_only", 0)):
+            env6 = MpeEnv(Hp.tag_gpu_config(wl.num_envs, tN, tL, tA, 1, hidden))
+            if hidden:
+                env6.set_policy(*Hp.to_dev(synth.policy_weights(0, 1, tD, hidden)))
+            env6.reset(seed)
+            b6 = env6.empty_traj(T)
+            w6, k6 = time_rollouts(env6, T, b6, k, 2)
+            ms6 = float(np.mean(k6))
+            tag[name] = {"agent_steps_per_s": t_steps / (w6 / k), "kernel_ms_avg": ms6,
+                         "hbm_GBs": t_bytes * wl.num_envs * T / (ms6 * 1e-3) / 1e9,
+                         "hbm_frac": t_bytes * wl.num_envs * T / (ms6 * 1e-3) / 1e9 / HBM_PEAK_GBS}
+            if hidden:
+                tf = flops_per_agent_step(tD, hidden) * t_steps / (ms6 * 1e-3) / 1e12
+                tag[name].update({"flop_per_agent_step": flops_per_agent_step(tD, hidden), "fp32_equivalent_TFLOPs": tf,
+                                  "frac_of_fp32_matrix_peak": tf / MFMA_FP32_PEAK_TFLOPS})
+            env6.close()
+            del b6
+        tag["config"] = {"scenario": "MPE_SCENARIO_TAG", "envs": wl.num_envs, "agents": tN, "adversaries": tA,
+                         "landmarks": tL, "obs_dim": tD, "T": T, "bytes_per_env_step": t_bytes,
+                         "kernel": "tag_rollout_kernel (lane per agent; policy / uniform variants)"}
+
     out = {
         "metric": "agent-steps/sec fused MPE rollout @65,536 envs, 1 MI355X; % HBM roofline",
         "value": value,
@@ -263,6 +293,7 @@ def main():
         "mixed_reward": mixed,
         "actor_critic": ac,
         "bf16_policy": bf,
+        "tag_scenario": tag,
         "single_step": {"us_per_mpe_step_call": step_us, "env_steps_per_s": TE / (step_us * 1e-6),
                         "note": "back-to-back mpe_step calls with resident actions; 352 B per env-step"},
         "paper_context": {"mpe_simple_spread_steps_per_s": {"original_cpu_1env_epyc7763": 8.3e4,
