@@ -13,8 +13,9 @@
 // feed-forward policy with two tanh layers of width 64 for MPE (Sec. 3.2 "PPO";
 // App. G, IPPO hyper-parameter table), and rolls out 128 steps per update (same
 // table).  Everything quantitative the paper leaves open is fixed by the readings
-// R-1 ... R-14 listed beside each function below.  R-14 is a second scenario (predator-prey,
-// "simple tag") of the MPE family the paper says it implements in full (App. B.7).
+// R-1 ... R-15 listed beside each function below.  R-14 is a second scenario (predator-prey,
+// "simple tag") of the MPE family the paper says it implements in full (App. B.7); R-15 is the
+// recurrent policy of the paper's headline speed figure (Fig. 3 caption; App. G, "Recurrent network").
 //
 // Arithmetic: double throughout (floating-point inputs arrive as float32 or double and
 // are widened once).  No blocking, fusion or reordering: one loop per env, per step,
@@ -95,6 +96,14 @@ struct Policy {
   std::vector<double> W1, b1, W2, b2, W3, b3;
 };
 
+// R-15 recurrent policy: per run We[D][G], be[G], Wi[G][3G], bi[3G], Wh[G][3G], bh[3G], Wf[G][G],
+// bf[G], Wo[G][5], bo[5] with G = 128, row-major [fan_in][fan_out]; gate columns ordered r | z | n.
+constexpr int GRU_H = 128;
+struct GruPolicy {
+  bool set = false;
+  std::vector<double> We, be, Wi, bi, Wh, bh, Wf, bf, Wo, bo;
+};
+
 struct Oracle {
   Config cfg;
   int E, N, L, R, D, H;
@@ -106,6 +115,8 @@ struct Oracle {
   std::vector<int32_t> ep_step;
   Policy pol;
   Policy critic;   // same shape with ONE output: W3[H][1], b3[1]  (R-13)
+  GruPolicy gru;                 // R-15; takes precedence over `pol` when set
+  std::vector<double> hidden;    // [run][env][agent][GRU_H], carried between steps and calls
   int nthreads = 1;
 };
 
@@ -490,6 +501,77 @@ double critic_value(const Oracle& o, int run, const double* ob) {
 }
 
 // ---------------------------------------------------------------------------------
+// R-15  Recurrent policy (paper Fig. 3: an RNN agent on MPE; App. G "Recurrent network": hidden
+// width 128, two fully-connected layers of width 128; activation tanh per the MPE column).  The
+// paper prints no equations; the reading taken is the standard gated recurrent unit between the two
+// fully-connected layers, parameters shared by all agents, one hidden vector h per agent:
+//     e  = tanh(We^T o + be)                                 (first fully-connected layer)
+//     r  = sigma(Wi_r^T e + bi_r + Wh_r^T h + bh_r)
+//     z  = sigma(Wi_z^T e + bi_z + Wh_z^T h + bh_z)
+//     n  = tanh (Wi_n^T e + bi_n + r * (Wh_n^T h + bh_n))
+//     h' = (1 - z) * n + z * h
+//     y  = tanh(Wf^T h' + bf)                                (second fully-connected layer)
+//     logits = Wo^T y + bo
+// h is zero at the start of an episode (after reset and after every done) and is carried across
+// rollout calls.  bf16 mode (weight_dtype 1): the weight matrices were rounded to bf16 when set;
+// o, e, h, h' and y are rounded to bf16 where they enter a matrix product; sums, biases, sigma, tanh,
+// the gate arithmetic and the carried h stay in the wide type.
+// ---------------------------------------------------------------------------------
+double sigmoid(double x) { return 1.0 / (1.0 + std::exp(-x)); }
+
+void gru_forward(const Oracle& o, int run, const double* ob, double* h /* [GRU_H] in/out */, double* z5 /* [5] */) {
+  const int D = o.D, G = GRU_H;
+  const GruPolicy& P = o.gru;
+  const bool bf = o.cfg.weight_dtype == 1;
+  auto rnd = [&](double v) { return bf ? round_to_bf16(v) : v; };
+  const double* We = &P.We[size_t(run) * D * G];
+  const double* be = &P.be[size_t(run) * G];
+  const double* Wi = &P.Wi[size_t(run) * G * 3 * G];
+  const double* bi = &P.bi[size_t(run) * 3 * G];
+  const double* Wh = &P.Wh[size_t(run) * G * 3 * G];
+  const double* bh = &P.bh[size_t(run) * 3 * G];
+  const double* Wf = &P.Wf[size_t(run) * G * G];
+  const double* bff = &P.bf[size_t(run) * G];
+  const double* Wo = &P.Wo[size_t(run) * G * NUM_ACTIONS];
+  const double* bo = &P.bo[size_t(run) * NUM_ACTIONS];
+  std::vector<double> x(D), e(G), hb(G), gi(3 * G), gh(3 * G), hn(G), y(G);
+  for (int k = 0; k < D; ++k) x[k] = rnd(ob[k]);
+  for (int j = 0; j < G; ++j) {
+    double acc = 0.0;
+    for (int k = 0; k < D; ++k) acc += x[k] * We[size_t(k) * G + j];
+    e[j] = rnd(std::tanh(acc + be[j]));
+  }
+  for (int k = 0; k < G; ++k) hb[k] = rnd(h[k]);
+  for (int j = 0; j < 3 * G; ++j) {
+    double ai = 0.0, ah = 0.0;
+    for (int k = 0; k < G; ++k) {
+      ai += e[k] * Wi[size_t(k) * 3 * G + j];
+      ah += hb[k] * Wh[size_t(k) * 3 * G + j];
+    }
+    gi[j] = ai + bi[j];
+    gh[j] = ah + bh[j];
+  }
+  for (int j = 0; j < G; ++j) {
+    const double r = sigmoid(gi[j] + gh[j]);
+    const double zz = sigmoid(gi[G + j] + gh[G + j]);
+    const double n = std::tanh(gi[2 * G + j] + r * gh[2 * G + j]);
+    hn[j] = (1.0 - zz) * n + zz * h[j];
+  }
+  for (int j = 0; j < G; ++j) h[j] = hn[j];
+  for (int k = 0; k < G; ++k) hb[k] = rnd(hn[k]);
+  for (int j = 0; j < G; ++j) {
+    double acc = 0.0;
+    for (int k = 0; k < G; ++k) acc += hb[k] * Wf[size_t(k) * G + j];
+    y[j] = rnd(std::tanh(acc + bff[j]));
+  }
+  for (int a = 0; a < NUM_ACTIONS; ++a) {
+    double acc = 0.0;
+    for (int k = 0; k < G; ++k) acc += y[k] * Wo[size_t(k) * NUM_ACTIONS + a];
+    z5[a] = acc + bo[a];
+  }
+}
+
+// ---------------------------------------------------------------------------------
 // R-10  Gumbel-max sampling: g_k = -ln(-ln u_k); u_0..u_3 are the four words of
 // Philox(env, s, agent, GUMBEL0), u_4 is word 0 of Philox(env, s, agent, GUMBEL1);
 // action = argmax_k (z_k + g_k), lowest index on ties.
@@ -524,10 +606,16 @@ int uniform_action(uint32_t seed, uint32_t run, uint32_t env, uint32_t s, uint32
   return word_to_action(w[0]);
 }
 
-void choose_actions(const Oracle& o, int run, int env, uint32_t s, const double* obs /* [N][D] */,
+void choose_actions(Oracle& o, int run, int env, uint32_t s, const double* obs /* [N][D] */,
                     uint8_t* act /* [N] */, double* logp = nullptr /* [N], needs a policy */) {
   for (int i = 0; i < o.N; ++i) {
-    if (o.pol.set) {
+    if (o.gru.set) {
+      double z[NUM_ACTIONS];
+      double* h = &o.hidden[((size_t(run) * o.E + env) * o.N + i) * GRU_H];
+      gru_forward(o, run, obs + size_t(i) * o.D, h, z);
+      act[i] = uint8_t(gumbel_max_action(o.seed, uint32_t(o.cfg.run_offset + run),
+                                         uint32_t(o.cfg.env_offset + env), s, uint32_t(i), z));
+    } else if (o.pol.set) {
       double z[NUM_ACTIONS];
       policy_logits(o, run, obs + size_t(i) * o.D, z);
       act[i] = uint8_t(gumbel_max_action(o.seed, uint32_t(o.cfg.run_offset + run),
@@ -575,6 +663,7 @@ void rollout_range(Oracle& o, size_t g0, size_t g1, int T, double* obs_traj, uin
           value_traj[(size_t(t) * TE + ge) * o.N + i] = critic_value(o, run, ob.data() + size_t(i) * o.D);
       uint8_t d;
       step_env(o, run, env, s, act.data(), r.data(), &d);
+      if (d && o.gru.set) std::fill_n(&o.hidden[ge * o.N * GRU_H], size_t(o.N) * GRU_H, 0.0);   // new episode
       if (rew_traj) std::memcpy(rew_traj + (size_t(t) * TE + ge) * RW, r.data(), RW * sizeof(double));
       if (done_traj) done_traj[size_t(t) * TE + ge] = d;
     }
@@ -638,6 +727,7 @@ int orc_create(const orc_config* c, void** out) {
   o->vel_a.assign(TE * o->N * 2, 0.0);
   o->pos_l.assign(TE * o->L * 2, 0.0);
   o->ep_step.assign(TE, 0);
+  o->hidden.assign(TE * o->N * GRU_H, 0.0);
   *out = o;
   return 0;
 }
@@ -667,6 +757,7 @@ int orc_reset(void* h, uint32_t seed, double* obs) {
   o.abs_step = 0;
   for (int run = 0; run < o.R; ++run)
     for (int env = 0; env < o.E; ++env) reset_env(o, run, env, 0);
+  std::fill(o.hidden.begin(), o.hidden.end(), 0.0);
   o.was_reset = true;
   if (obs) orc_observe(h, obs);
   return 0;
@@ -745,6 +836,60 @@ int orc_set_critic(void* h, const float* V1, const float* c1, const float* V2, c
   return 0;
 }
 
+// Recurrent policy (R-15) weights as float32, [R] leading dimension: We[D][128] be[128] Wi[128][384]
+// bi[384] Wh[128][384] bh[384] Wf[128][128] bf[128] Wo[128][5] bo[5].  All ten null => removed.
+int orc_set_gru(void* h, const float* We, const float* be, const float* Wi, const float* bi, const float* Wh,
+                const float* bh, const float* Wf, const float* bf, const float* Wo, const float* bo) {
+  if (!h) return fail("null handle");
+  Oracle& o = *static_cast<Oracle*>(h);
+  const float* all[10] = {We, be, Wi, bi, Wh, bh, Wf, bf, Wo, bo};
+  int given = 0;
+  for (const float* p : all) given += p != nullptr;
+  if (given == 0) { o.gru.set = false; return 0; }
+  if (given != 10) return fail("all ten recurrent-policy arrays or none");
+  const bool b16 = o.cfg.weight_dtype == 1;
+  auto load = [&](std::vector<double>& dst, const float* src, size_t n, bool round_it) {
+    dst.resize(n);
+    for (size_t i = 0; i < n; ++i) dst[i] = round_it ? round_to_bf16(double(src[i])) : double(src[i]);
+  };
+  const size_t R = o.R, D = o.D, G = GRU_H;
+  load(o.gru.We, We, R * D * G, b16);
+  load(o.gru.be, be, R * G, false);
+  load(o.gru.Wi, Wi, R * G * 3 * G, b16);
+  load(o.gru.bi, bi, R * 3 * G, false);
+  load(o.gru.Wh, Wh, R * G * 3 * G, b16);
+  load(o.gru.bh, bh, R * 3 * G, false);
+  load(o.gru.Wf, Wf, R * G * G, b16);
+  load(o.gru.bf, bf, R * G, false);
+  load(o.gru.Wo, Wo, R * G * NUM_ACTIONS, b16);
+  load(o.gru.bo, bo, R * NUM_ACTIONS, false);
+  o.gru.set = true;
+  return 0;
+}
+
+// One recurrent-policy evaluation per row: obs [n][D], hidden [n][128] in/out, logits [n][5].
+int orc_gru_forward(void* h, int run, const double* obs, int n, double* hidden, double* logits) {
+  Oracle& o = *static_cast<Oracle*>(h);
+  if (!o.gru.set) return fail("no recurrent policy");
+  if (run < 0 || run >= o.R) return fail("bad run");
+  for (int r = 0; r < n; ++r)
+    gru_forward(o, run, obs + size_t(r) * o.D, hidden + size_t(r) * GRU_H, logits + size_t(r) * NUM_ACTIONS);
+  return 0;
+}
+
+// Hidden state [R*E][N][128]; orc_set_hidden(null) zeroes it.
+int orc_get_hidden(void* h, double* hidden) {
+  Oracle& o = *static_cast<Oracle*>(h);
+  std::memcpy(hidden, o.hidden.data(), o.hidden.size() * sizeof(double));
+  return 0;
+}
+int orc_set_hidden(void* h, const double* hidden) {
+  Oracle& o = *static_cast<Oracle*>(h);
+  if (hidden) std::memcpy(o.hidden.data(), hidden, o.hidden.size() * sizeof(double));
+  else std::fill(o.hidden.begin(), o.hidden.end(), 0.0);
+  return 0;
+}
+
 // Critic values of `run` for n observation rows [n][D] -> [n].
 int orc_value(void* h, int run, const double* obs, int n, double* values) {
   Oracle& o = *static_cast<Oracle*>(h);
@@ -809,6 +954,7 @@ int orc_rollout_ac(void* h, int32_t T, double* obs_traj, uint8_t* act_traj, doub
   Oracle& o = *static_cast<Oracle*>(h);
   if (!o.was_reset) return fail("rollout before reset");
   if (!o.pol.set || !o.critic.set) return fail("actor-critic rollout needs a policy and a critic");
+  if (o.gru.set) return fail("actor-critic rollout is defined for the feed-forward policy only");
   const size_t TE = size_t(o.R) * o.E;
   const int nt = int(std::max<size_t>(1, std::min<size_t>(size_t(o.nthreads), TE)));
   std::vector<std::thread> th;

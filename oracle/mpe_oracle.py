@@ -102,6 +102,10 @@ def _load():
         _lib.orc_log_probs.argtypes = [C.c_void_p, C.c_void_p]
         _lib.orc_log_probs.restype = None
         _lib.orc_rollout_ac.argtypes = [C.c_void_p, C.c_int32] + [C.c_void_p] * 8
+        _lib.orc_set_gru.argtypes = [C.c_void_p] + [C.c_void_p] * 10
+        _lib.orc_gru_forward.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        _lib.orc_get_hidden.argtypes = [C.c_void_p, C.c_void_p]
+        _lib.orc_set_hidden.argtypes = [C.c_void_p, C.c_void_p]
     return _lib
 
 
@@ -204,6 +208,42 @@ class Oracle:
         shapes = [(self.R, self.D, H), (self.R, H), (self.R, H, H), (self.R, H), (self.R, H), (self.R,)]
         arrs = [np.ascontiguousarray(a, dtype=np.float32).reshape(s) for a, s in zip((V1, c1, V2, c2, V3, c3), shapes)]
         _check(self.lib.orc_set_critic(self.h, *[_ptr(a) for a in arrs]))
+
+    GRU_H = 128
+
+    def gru_shapes(self):
+        G, R, D = self.GRU_H, self.R, self.D
+        return [(R, D, G), (R, G), (R, G, 3 * G), (R, 3 * G), (R, G, 3 * G), (R, 3 * G), (R, G, G), (R, G),
+                (R, G, 5), (R, 5)]
+
+    def set_gru(self, *arrays):
+        """Recurrent policy: We, be, Wi, bi, Wh, bh, Wf, bf, Wo, bo (or nothing to remove it)."""
+        if not arrays or arrays[0] is None:
+            _check(self.lib.orc_set_gru(self.h, *([None] * 10)))
+            return
+        arrs = [np.ascontiguousarray(a, dtype=np.float32).reshape(s) for a, s in zip(arrays, self.gru_shapes())]
+        assert len(arrs) == 10
+        _check(self.lib.orc_set_gru(self.h, *[_ptr(a) for a in arrs]))
+
+    def gru_forward(self, obs_rows, hidden, run: int = 0):
+        """One evaluation per row: returns (new hidden [n][128], logits [n][5])."""
+        o = np.ascontiguousarray(obs_rows, dtype=np.float64).reshape(-1, self.D)
+        h = np.array(hidden, dtype=np.float64).reshape(o.shape[0], self.GRU_H).copy()
+        z = np.empty((o.shape[0], 5), dtype=np.float64)
+        _check(self.lib.orc_gru_forward(self.h, run, _ptr(o), o.shape[0], _ptr(h), _ptr(z)))
+        return h, z
+
+    def get_hidden(self) -> np.ndarray:
+        h = np.empty((self.TE, self.N, self.GRU_H), dtype=np.float64)
+        _check(self.lib.orc_get_hidden(self.h, _ptr(h)))
+        return h
+
+    def set_hidden(self, hidden=None):
+        if hidden is None:
+            _check(self.lib.orc_set_hidden(self.h, None))
+        else:
+            h = np.ascontiguousarray(hidden, dtype=np.float64).reshape(self.TE, self.N, self.GRU_H)
+            _check(self.lib.orc_set_hidden(self.h, _ptr(h)))
 
     def value(self, obs_rows: np.ndarray, run: int = 0) -> np.ndarray:
         o = np.ascontiguousarray(obs_rows, dtype=np.float64).reshape(-1, self.D)

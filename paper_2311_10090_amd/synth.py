@@ -111,6 +111,21 @@ def critic_weights(seed: int, num_runs: int, obs_dim: int, hidden: int):
     return V1, c1, V2, c2, V3, c3
 
 
+GRU_HIDDEN = 128
+
+
+def gru_weights(seed: int, num_runs: int, obs_dim: int):
+    """Recurrent-policy weights (hidden 128), N(0, 1/fan_in), biases U(-0.5, 0.5), float32:
+    We[R][D][G], be[R][G], Wi[R][G][3G], bi[R][3G], Wh[R][G][3G], bh[R][3G], Wf[R][G][G], bf[R][G],
+    Wo[R][G][5], bo[R][5]; gate columns ordered r | z | n."""
+    G, R = GRU_HIDDEN, num_runs
+    g = np.random.Generator(np.random.PCG64(seed + 32452843))
+    mat = lambda fi, fo: (g.standard_normal((R, fi, fo)) / np.sqrt(fi)).astype(np.float32)
+    vec = lambda n: g.uniform(-0.5, 0.5, (R, n)).astype(np.float32)
+    return (mat(obs_dim, G), vec(G), mat(G, 3 * G), vec(3 * G), mat(G, 3 * G), vec(3 * G), mat(G, G), vec(G),
+            mat(G, NUM_ACTIONS), vec(NUM_ACTIONS))
+
+
 def random_actions(seed: int, shape) -> np.ndarray:
     g = np.random.Generator(np.random.PCG64(seed))
     return g.integers(0, NUM_ACTIONS, size=shape, dtype=np.uint8)

@@ -1,0 +1,201 @@
+"""Pins for the oracle's recurrent policy (gated recurrent unit between two fully-connected layers):
+torch's GRUCell and Linear in float64, closed forms, torch's bfloat16 rounding at the stated
+rounding points, and the rollout's handling of the carried hidden state.  CPU only."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import Oracle, OracleConfig, gumbel_max_action
+from paper_2311_10090_amd import synth
+
+G = 128
+
+
+def make(E=2, N=3, wd=0, seed=1, **kw):
+    o = Oracle(OracleConfig(num_envs=E, num_agents=N, num_landmarks=N, hidden=128, weight_dtype=wd, **kw))
+    w = synth.gru_weights(seed, 1, o.D)
+    o.set_gru(*w)
+    return o, w
+
+
+def torch_chain(w, obs, h, rnd=lambda t: t):
+    """The same network from torch's own GRUCell / Linear in float64.  `rnd` is applied to the weight
+    matrices and to every vector that enters a matrix product."""
+    We, be, Wi, bi, Wh, bh, Wf, bf, Wo, bo = [torch.from_numpy(np.asarray(a[0], np.float64)) for a in w]
+    cell = torch.nn.GRUCell(G, G, dtype=torch.float64)
+    with torch.no_grad():
+        cell.weight_ih.copy_(rnd(Wi).T)       # torch stores [3G][in], gate rows r | z | n
+        cell.weight_hh.copy_(rnd(Wh).T)
+        cell.bias_ih.copy_(bi)
+        cell.bias_hh.copy_(bh)
+        o = torch.from_numpy(np.asarray(obs, np.float64))
+        hh = torch.from_numpy(np.asarray(h, np.float64))
+        e = torch.tanh(torch.nn.functional.linear(rnd(o), rnd(We).T, be))
+        # the carried state enters the products rounded, the blend unrounded: GRUCell on the rounded
+        # state, then put the unrounded carry back into the z * h term
+        hr = rnd(hh)
+        h_cell = cell(rnd(e), hr)
+        gi = torch.nn.functional.linear(rnd(e), rnd(Wi).T, bi)
+        gh = torch.nn.functional.linear(hr, rnd(Wh).T, bh)
+        z = torch.sigmoid(gi[:, G:2 * G] + gh[:, G:2 * G])
+        h_new = h_cell + z * (hh - hr)
+        y = torch.tanh(torch.nn.functional.linear(rnd(h_new), rnd(Wf).T, bf))
+        logits = torch.nn.functional.linear(rnd(y), rnd(Wo).T, bo)
+    return h_new.numpy(), logits.numpy()
+
+
+def test_matches_torch_grucell_float64():
+    o, w = make()
+    g = np.random.Generator(np.random.PCG64(3))
+    obs = g.uniform(-1.5, 1.5, (40, o.D))
+    h = g.uniform(-1, 1, (40, G))
+    h1, z1 = o.gru_forward(obs, h)
+    h2, z2 = torch_chain(w, obs, h)
+    np.testing.assert_allclose(h1, h2, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(z1, z2, rtol=0, atol=1e-13)
+    assert np.abs(h1 - h).max() > 0.1 and np.abs(z1).max() > 0.1
+
+
+def _bf16_bits(t):
+    """float64 tensor -> nearest bfloat16 value (ties to even) by integer arithmetic on the bit
+    pattern: bfloat16 keeps 7 of the 52 stored mantissa bits (values here are far from the format's
+    exponent limits).  One rounding, unlike float64 -> float32 -> bfloat16."""
+    u = t.contiguous().view(torch.int64)
+    lsb = (u >> 45) & 1
+    u = (u + ((1 << 44) - 1) + lsb) & ~((1 << 45) - 1)
+    return u.view(torch.float64)
+
+
+def test_bit_rounding_helper_agrees_with_torch_on_float32_inputs():
+    g = np.random.Generator(np.random.PCG64(2))
+    x32 = torch.from_numpy(np.concatenate([g.standard_normal(4000), [1.00390625, 1.01171875, -2.5, 0.0]]).astype(np.float32))
+    assert torch.equal(_bf16_bits(x32.to(torch.float64)), x32.to(torch.bfloat16).to(torch.float64))
+
+
+def test_bf16_mode_rounds_weights_and_layer_inputs_like_torch():
+    o, w = make(wd=1)
+    rnd = _bf16_bits
+    g = np.random.Generator(np.random.PCG64(4))
+    obs = g.uniform(-1.5, 1.5, (40, o.D)).astype(np.float32).astype(np.float64)
+    h = g.uniform(-1, 1, (40, G)).astype(np.float32).astype(np.float64)
+    h1, z1 = o.gru_forward(obs, h)
+    h2, z2 = torch_chain(w, obs, h, rnd)
+    # a value within ~1e-16 of a rounding boundary may round differently after torch's differently
+    # ordered sums: allow a handful of single-step flips (2^-9 relative on one input), nothing else
+    assert (np.abs(h1 - h2) > 1e-13).mean() < 0.002 and np.abs(h1 - h2).max() < 1e-3
+    assert (np.abs(z1 - z2) > 1e-13).mean() < 0.02 and np.abs(z1 - z2).max() < 1e-3
+    # and it is not the unrounded network
+    h3, z3 = torch_chain(w, obs, h)
+    assert np.abs(z1 - z3).max() > 1e-4
+    # the carried state itself is NOT rounded: z * h keeps all bits of h
+    assert np.abs(h1 - np.float64(np.float32(h1))).max() > 0
+
+
+def test_closed_forms_with_zero_matrices():
+    o, _ = make()
+    D = o.D
+    g = np.random.Generator(np.random.PCG64(5))
+    be, bi, bh, bf, bo = (g.uniform(-1, 1, (1, n)) for n in (G, 3 * G, 3 * G, G, 5))
+    zeros = lambda *s: np.zeros((1,) + s)
+    o.set_gru(zeros(D, G), be, zeros(G, 3 * G), bi, zeros(G, 3 * G), bh, zeros(G, G), bf, zeros(G, 5), bo)
+    h = g.uniform(-1, 1, (7, G))
+    h1, z1 = o.gru_forward(g.uniform(-1, 1, (7, D)), h)
+    f32 = lambda a: np.float64(np.float32(a))       # the weights travel as float32
+    bi, bh, bo = f32(bi[0]), f32(bh[0]), f32(bo[0])
+    sig = lambda x: 1 / (1 + np.exp(-x))
+    r = sig(bi[:G] + bh[:G])
+    z = sig(bi[G:2 * G] + bh[G:2 * G])
+    n = np.tanh(bi[2 * G:] + r * bh[2 * G:])
+    np.testing.assert_allclose(h1, (1 - z) * n + z * h, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(z1, np.tile(bo, (7, 1)), rtol=0, atol=0)
+
+
+def test_update_gate_one_keeps_the_state_and_zero_replaces_it():
+    o, w = make()
+    w = [np.array(a, np.float64) for a in w]
+    g = np.random.Generator(np.random.PCG64(6))
+    obs, h = g.uniform(-1, 1, (5, o.D)), g.uniform(-1, 1, (5, G))
+    for shift, keep in ((+60.0, True), (-60.0, False)):
+        bi = w[3].copy()
+        bi[0, G:2 * G] = shift                       # z = sigma(+-60 + ...) = 1 or 0 to 1e-20
+        o.set_gru(w[0], w[1], w[2], bi, w[4], w[5], w[6], w[7], w[8], w[9])
+        h1, _ = o.gru_forward(obs, h)
+        if keep:
+            np.testing.assert_allclose(h1, h, rtol=0, atol=1e-12)
+        else:
+            assert np.abs(h1 - h).max() > 0.1
+            h2, _ = o.gru_forward(obs, np.zeros_like(h))
+            # n still depends on h through r * (Wh_n h): compare with the candidate state formula
+            We, be, Wi, _, Wh, bh = [np.float64(np.float32(a[0])) for a in w[:6]]
+            e = np.tanh(obs @ We + be)
+            gi, gh = e @ Wi + np.float64(np.float32(bi[0])), h @ Wh + bh
+            r = 1 / (1 + np.exp(-(gi[:, :G] + gh[:, :G])))
+            np.testing.assert_allclose(h1, np.tanh(gi[:, 2 * G:] + r * gh[:, 2 * G:]), rtol=0, atol=1e-12)
+            assert np.abs(h2 - h1).max() > 1e-3
+
+
+@pytest.mark.parametrize("wd", [0, 1])
+def test_rollout_carries_the_state_and_clears_it_at_episode_ends(wd):
+    E, N, T = 3, 3, 9
+    o, w = make(E=E, N=N, wd=wd, max_episode_steps=4)
+    o.reset(11)
+    obs, act, rew, done, last = o.rollout(T)
+    h_end = o.get_hidden()
+    h = np.zeros((E, N, G))
+    for t in range(T):
+        hn, z = o.gru_forward(obs[t].reshape(E * N, -1), h.reshape(E * N, G))
+        hn, z = hn.reshape(E, N, G), z.reshape(E, N, 5)
+        for e in range(E):
+            for i in range(N):
+                assert act[t, e, i] == gumbel_max_action(11, 0, e, t, i, z[e, i])
+        h = hn
+        if done[t].all():
+            h[:] = 0.0                      # the next observation starts a new episode
+    assert list(done[:, 0]) == [0, 0, 0, 1, 0, 0, 0, 1, 0]
+    np.testing.assert_array_equal(h_end, h)
+    assert np.abs(h_end).max() > 0.05
+
+
+def test_state_is_carried_across_calls_and_cleared_by_reset():
+    a, _ = make(E=4, wd=1)
+    b, _ = make(E=4, wd=1)
+    a.reset(2)
+    b.reset(2)
+    full = a.rollout(10)
+    p1 = b.rollout(6)
+    assert np.abs(b.get_hidden()).max() > 0
+    p2 = b.rollout(4)
+    for k in range(4):
+        np.testing.assert_array_equal(full[k], np.concatenate([p1[k], p2[k]]))
+    np.testing.assert_array_equal(a.get_hidden(), b.get_hidden())
+    b.reset(2)
+    assert np.all(b.get_hidden() == 0)
+    again = b.rollout(10)
+    np.testing.assert_array_equal(again[1], full[1])
+
+
+def test_get_set_hidden_round_trip_and_effect():
+    o, _ = make(E=2)
+    o.reset(1)
+    g = np.random.Generator(np.random.PCG64(8))
+    h = g.uniform(-1, 1, (2, 3, G))
+    o.set_hidden(h)
+    np.testing.assert_array_equal(o.get_hidden(), h)
+    a1 = o.rollout(6)[1]
+    o.reset(1)
+    a0 = o.rollout(6)[1]
+    assert not np.array_equal(a0, a1)          # the state matters for the actions
+    o.set_hidden(None)
+    assert np.all(o.get_hidden() == 0)
+
+
+def test_recurrent_policy_takes_precedence_and_can_be_removed():
+    o, _ = make(E=8)
+    o.reset(3)
+    a_gru = o.rollout(5)[1]
+    o.set_gru()
+    o.reset(3)
+    a_uni = o.rollout(5)[1]
+    assert not np.array_equal(a_gru, a_uni)
+    with pytest.raises(RuntimeError):
+        o.gru_forward(np.zeros((1, o.D)), np.zeros((1, G)))
