@@ -158,8 +158,8 @@ int mpe_set_policy(mpe_env* env, const float* W1, const float* b1, const float* 
                    const float* b2, const float* W3, const float* b3, void* stream);
 
 /* T fused steps.  For t = 0..T-1: record the current observation, choose every agent's
- * action (policy + Gumbel-max with Philox counter (env, abs_step + t, agent, 2|3); or, with
- * no policy, uniform with counter (env, abs_step + t, agent, 1)), record it, apply the
+ * action (policy -- feed-forward or recurrent -- + Gumbel-max with Philox counter (env, abs_step + t,
+ * agent, 2|3); or, with no policy, uniform with counter (env, abs_step + t, agent, 1)), record it, apply the
  * transition, record reward and done.
  * obs_traj [T][TE][N][D] fp32, act_traj [T][TE][N] uint8, rew_traj [T][TE] fp32
  * ([T][TE][N] with MPE_REWARD_MIXED and MPE_SCENARIO_TAG), done_traj [T][TE] uint8, last_obs [TE][N][D] fp32
@@ -168,6 +168,32 @@ int mpe_set_policy(mpe_env* env, const float* W1, const float* b1, const float* 
  * T >= 1.  Advances the absolute step counter by T.  MPE_ESTATE as for mpe_step. */
 int mpe_rollout(mpe_env* env, int32_t T, float* obs_traj, uint8_t* act_traj, float* rew_traj,
                 uint8_t* done_traj, float* last_obs, void* stream);
+
+/* Install (or with all ten NULL, remove) a RECURRENT policy for mpe_rollout -- the agent network of
+ * the paper's headline speed comparison (Fig. 3: an RNN agent on MPE; App. G "Recurrent network":
+ * hidden width 128, two fully-connected layers of width 128).  Per agent, with one carried vector h
+ * of 128 floats per agent (zero at every episode start):
+ *   e = tanh(We^T obs + be)
+ *   r = sigmoid(Wi_r^T e + bi_r + Wh_r^T h + bh_r),  z likewise,
+ *   n = tanh(Wi_n^T e + bi_n + r * (Wh_n^T h + bh_n)),  h <- (1 - z) * n + z * h
+ *   y = tanh(Wf^T h + bf),  logits = Wo^T y + bo
+ * We [D][128], be [128], Wi, Wh [128][384] (columns r | z | n), bi, bh [384], Wf [128][128], bf [128],
+ * Wo [128][5], bo [5]: fp32 device pointers, row-major [fan_in][fan_out], copied on `stream`.  The
+ * matrices and every vector that enters a matrix product (obs, e, h, y) are rounded to bf16 (ties
+ * to even); sums, biases, gate arithmetic and the carried h are fp32.  While installed it takes
+ * precedence over the policy of mpe_set_policy.  h is owned by the handle, cleared by mpe_reset and
+ * wherever an episode ends, carried across mpe_rollout calls, untouched by mpe_set_state.
+ * Built for MPE_SCENARIO_SPREAD, 1..3 agents, hidden 128, MPE_WEIGHTS_BF16, num_runs 1; MPE_EINVAL
+ * otherwise or if only some pointers are NULL. */
+int mpe_set_gru_policy(mpe_env* env, const float* We, const float* be, const float* Wi, const float* bi,
+                       const float* Wh, const float* bh, const float* Wf, const float* bf, const float* Wo,
+                       const float* bo, void* stream);
+
+/* Copy the carried state of the recurrent policy out / in: hidden [TE][N][128] fp32 device pointer
+ * (device to device, on `stream`); mpe_set_hidden(NULL) clears it.  MPE_ESTATE if no recurrent
+ * policy has been installed on this handle. */
+int mpe_get_hidden(mpe_env* env, float* hidden, void* stream);
+int mpe_set_hidden(mpe_env* env, const float* hidden, void* stream);
 
 /* Install (or with all six NULL, remove) the critic used by mpe_rollout_ac: a second network of
  * the policy's shape with ONE output, fed the agent's own observation (the actor-critic pair of

@@ -23,7 +23,8 @@ NUM_ACTIONS = 5
 
 EXPORTS = ("mpe_create", "mpe_destroy", "mpe_obs_dim", "mpe_reset", "mpe_step", "mpe_set_policy",
            "mpe_rollout", "mpe_set_critic", "mpe_rollout_ac", "mpe_get_state", "mpe_set_state",
-           "mpe_last_error")
+           "mpe_set_gru_policy", "mpe_get_hidden", "mpe_set_hidden", "mpe_last_error")
+GRU_HIDDEN = 128
 
 
 class MpeError(RuntimeError):
@@ -95,6 +96,9 @@ def load_library():
     lib.mpe_rollout.argtypes = [vp, C.c_int32, vp, vp, vp, vp, vp, vp]
     lib.mpe_get_state.argtypes = [vp, vp, vp, vp, vp, C.POINTER(C.c_uint32), vp]
     lib.mpe_set_state.argtypes = [vp, vp, vp, vp, vp, C.c_uint32, C.c_uint32, vp]
+    lib.mpe_set_gru_policy.argtypes = [vp] + [vp] * 10 + [vp]
+    lib.mpe_get_hidden.argtypes = [vp, vp, vp]
+    lib.mpe_set_hidden.argtypes = [vp, vp, vp]
     for n in EXPORTS:
         if n != "mpe_last_error":
             getattr(lib, n).restype = C.c_int
@@ -205,6 +209,23 @@ class MpeEnv:
                                            _ptr(rew_traj, torch.float32), _ptr(done_traj, torch.uint8),
                                            _ptr(last_obs, torch.float32), _ptr(last_value, torch.float32), _stream()))
         return obs_traj, act_traj, logp_traj, value_traj, rew_traj, done_traj, last_obs, last_value
+
+    def set_gru_policy(self, *arrays):
+        """We, be, Wi, bi, Wh, bh, Wf, bf, Wo, bo device tensors (or nothing to remove the policy)."""
+        arrays = arrays if arrays else (None,) * 10
+        assert len(arrays) == 10
+        with torch.cuda.device(self.device):
+            _check(self.lib.mpe_set_gru_policy(self.h, *[_ptr(a, torch.float32) for a in arrays], _stream()))
+
+    def get_hidden(self):
+        h = torch.empty((self.TE, self.N, GRU_HIDDEN), dtype=torch.float32, device=self.device)
+        with torch.cuda.device(self.device):
+            _check(self.lib.mpe_get_hidden(self.h, _ptr(h), _stream()))
+        return h
+
+    def set_hidden(self, hidden=None):
+        with torch.cuda.device(self.device):
+            _check(self.lib.mpe_set_hidden(self.h, _ptr(hidden, torch.float32), _stream()))
 
     def get_state(self):
         """Returns pos_a, vel_a ([2][N][TE]), pos_l ([2][L][TE] fp32), ep_step ([TE] int32) tensors and abs_step."""

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmpe.so")
-SOURCES = ["mpe_api.hip", "mpe_env_kernels.hip", "mpe_policy_wide.hip", "mpe_policy_f32.hip", "mpe_policy_dispatch.hip", "mpe_tag.hip"]
+SOURCES = ["mpe_api.hip", "mpe_env_kernels.hip", "mpe_policy_wide.hip", "mpe_policy_f32.hip", "mpe_policy_dispatch.hip", "mpe_tag.hip", "mpe_policy_gru.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 

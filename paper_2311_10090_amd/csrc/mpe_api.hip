@@ -28,6 +28,9 @@ struct mpe_env {
   bool has_policy = false;
   PolicyBuffers critic{};
   bool has_critic = false;
+  PolicyBuffers gru{};        // recurrent policy; takes precedence over `pol` while set
+  bool has_gru = false;
+  float* hidden = nullptr;    // [TE][N][128] carried state of the recurrent policy (allocated with it)
 };
 
 namespace {
@@ -178,6 +181,8 @@ int mpe_destroy(mpe_env* e) {
   (void)hipFree(e->st.ep_step);
   free_policy(e->pol);
   free_policy(e->critic);
+  free_policy(e->gru);
+  if (e->hidden) (void)hipFree(e->hidden);
   delete e;
   return MPE_OK;
 }
@@ -192,6 +197,7 @@ int mpe_reset(mpe_env* e, uint32_t seed, float* obs, void* stream) {
   if (obs && !aligned16(obs)) return fail(MPE_EINVAL, "mpe_reset: obs must be 16-byte aligned");
   if (e->tag) launch_tag_reset(e->N, e->L, e->G, e->st, e->TE, e->E, seed, obs, static_cast<hipStream_t>(stream));
   else launch_reset(e->N, e->st, e->TE, e->E, seed, obs, static_cast<hipStream_t>(stream));
+  if (e->hidden) launch_fill_zero(e->hidden, size_t(e->TE) * e->N * 128, static_cast<hipStream_t>(stream));
   MPE_HIP(hipGetLastError());
   e->seed = seed;
   e->abs_step = 0;
@@ -282,7 +288,10 @@ int mpe_rollout(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, float
   A.rew_traj = rew_traj;
   A.done_traj = done_traj;
   A.last_obs = last_obs;
-  if (e->tag) {
+  if (e->has_gru) {
+    hipError_t err = launch_rollout_gru(e->N, A, e->gru, e->hidden, static_cast<hipStream_t>(stream));
+    if (err != hipSuccess) return fail(MPE_EHIP, "mpe_rollout: %s", hipGetErrorString(err));
+  } else if (e->tag) {
     TagArgs TA{};
     TA.r = A;
     TA.tg = e->tg;
@@ -303,6 +312,55 @@ int mpe_rollout(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, float
   }
   MPE_HIP(hipGetLastError());
   e->abs_step += uint32_t(T);
+  return MPE_OK;
+}
+
+int mpe_set_gru_policy(mpe_env* e, const float* We, const float* be, const float* Wi, const float* bi,
+                       const float* Wh, const float* bh, const float* Wf, const float* bf, const float* Wo,
+                       const float* bo, void* stream) {
+  if (!e) return fail(MPE_EINVAL, "mpe_set_gru_policy: NULL handle");
+  int given = 0;
+  for (const float* p : {We, be, Wi, bi, Wh, bh, Wf, bf, Wo, bo}) given += p != nullptr;
+  if (given == 0) {
+    e->has_gru = false;
+    return MPE_OK;
+  }
+  if (given != 10) return fail(MPE_EINVAL, "mpe_set_gru_policy: pass all ten arrays or none");
+  if (e->tag || e->R != 1 || !gru_supported(e->N, e->H, e->cfg.weight_dtype))
+    return fail(MPE_EINVAL, "mpe_set_gru_policy: the recurrent policy is built for MPE_SCENARIO_SPREAD with 1..3 "
+                            "agents, hidden 128, MPE_WEIGHTS_BF16 and num_runs 1");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (!e->hidden) {
+    const size_t n = size_t(e->TE) * e->N * 128;
+    MPE_HIP(hipMalloc(&e->hidden, n * sizeof(float)));
+    launch_fill_zero(e->hidden, n, s);
+    MPE_HIP(hipGetLastError());
+  }
+  hipError_t err = pack_policy_gru(e->gru, e->N, We, be, Wi, bi, Wh, bh, Wf, bf, Wo, bo, s);
+  if (err != hipSuccess) return fail(MPE_EHIP, "mpe_set_gru_policy: %s", hipGetErrorString(err));
+  e->has_gru = true;
+  return MPE_OK;
+}
+
+int mpe_get_hidden(mpe_env* e, float* hidden, void* stream) {
+  if (!e || !hidden) return fail(MPE_EINVAL, "mpe_get_hidden: NULL argument");
+  if (!e->hidden) return fail(MPE_ESTATE, "mpe_get_hidden: no recurrent policy has been set");
+  MPE_HIP(hipMemcpyAsync(hidden, e->hidden, size_t(e->TE) * e->N * 128 * sizeof(float), hipMemcpyDeviceToDevice,
+                         static_cast<hipStream_t>(stream)));
+  return MPE_OK;
+}
+
+int mpe_set_hidden(mpe_env* e, const float* hidden, void* stream) {
+  if (!e) return fail(MPE_EINVAL, "mpe_set_hidden: NULL handle");
+  if (!e->hidden) return fail(MPE_ESTATE, "mpe_set_hidden: no recurrent policy has been set");
+  const size_t n = size_t(e->TE) * e->N * 128;
+  if (hidden) {
+    MPE_HIP(hipMemcpyAsync(e->hidden, hidden, n * sizeof(float), hipMemcpyDeviceToDevice,
+                           static_cast<hipStream_t>(stream)));
+  } else {
+    launch_fill_zero(e->hidden, n, static_cast<hipStream_t>(stream));
+    MPE_HIP(hipGetLastError());
+  }
   return MPE_OK;
 }
 
@@ -334,6 +392,7 @@ int mpe_rollout_ac(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, fl
   if (!e->ready) return fail(MPE_ESTATE, "mpe_rollout_ac: call mpe_reset or mpe_set_state first");
   if (!e->has_policy || !e->has_critic)
     return fail(MPE_ESTATE, "mpe_rollout_ac: needs mpe_set_policy and mpe_set_critic first");
+  if (e->has_gru) return fail(MPE_ESTATE, "mpe_rollout_ac: remove the recurrent policy first (feed-forward networks only)");
   if (e->tag || !f32_supported(e->N, e->H)) return fail(MPE_EINVAL, "mpe_rollout_ac: unsupported shape");
   for (const float* p : {obs_traj, logp_traj, value_traj, rew_traj, last_obs, last_value})
     if (p && !aligned16(p)) return fail(MPE_EINVAL, "mpe_rollout_ac: float outputs must be 16-byte aligned");

@@ -1,0 +1,524 @@
+// Fused rollout with the recurrent policy of the paper's headline speed figure (Fig. 3: an RNN
+// agent on MPE; App. G "Recurrent network": hidden width 128, two fully-connected layers of
+// width 128): per agent and step
+//     e = tanh(We^T o + be);  r, z, n gates of a GRU on (e, h);  h' = (1 - z) n + z h;
+//     y = tanh(Wf^T h' + bf);  logits = Wo^T y + bo;  Gumbel-max;  simple-spread transition.
+// bf16 weights and layer inputs (nearest even), fp32 accumulation, gate arithmetic and carried
+// state: the contraction runs on the bf16 matrix cores, one instruction per product.
+//
+// Design.  The network has 240 KB of bf16 weights, more than the 160 KB of LDS, and 236 matrix
+// instructions per 16 rows: re-reading the weights per wavefront from L2 would cost ~90 GB per
+// rollout.  So the weights are STATIONARY and the activations move: a block is 8 wavefronts around
+// 64 envs (64 N agent rows); wavefront u owns hidden units 16u..16u+15 of every layer and keeps
+// its 24 GRU A-operands (r, z, n gates x input/recurrent x 4 K slices) and its embedding operand
+// in registers for the whole rollout (100 of its 256 registers); the small layers' operands
+// (second fully-connected layer, logits) sit in LDS.  Activations of all rows go through LDS as
+// bf16 rows of 128 (+ 16 bytes of padding per row, which spreads the 16-byte operand reads evenly
+// over the banks): every wavefront reads all K of a row tile and writes its own 16 units.  The
+// carried state stays in fp32 registers of the owning wavefront (4 values per lane and row tile);
+// its bf16 copy for the next product lives in LDS.  Phases of a step, separated by block barriers:
+//   flush obs | embed -> X | gates (reads X, HB) | HB <- h' | fc (reads HB) -> Y=X | logits -> L |
+//   agents: sample, move, exchange positions | reward, done, auto-reset, next observation
+// The first 64 N threads are also the agents (one lane per agent row) for the environment part.
+#include "mpe_mlp64.h"
+
+namespace mpe {
+
+namespace {
+
+constexpr int kG = 128;    // hidden width of every layer
+constexpr int kAS = 272;   // bytes per activation row in LDS: 128 bf16 + 16 bytes of padding
+
+// Packed weight image (bytes).  A operands of v_mfma_f32_16x16x32_bf16: lane (i = lane % 16,
+// gq = lane / 16) holds weights [k = 32 s + 8 gq + e][out = 16 u + i], e = 0..7.
+struct GruPk {
+  static constexpr size_t OFF_EMB = 0;                         // [u 8][lane 64]  (K = 32 >= obs width)
+  static constexpr size_t OFF_GRU = OFF_EMB + 8 * 1024;        // [u 8][gate 3][src 2][s 4][lane 64]
+  static constexpr size_t OFF_FC = OFF_GRU + 8 * 24 * 1024;    // [u 8][s 4][lane 64]
+  static constexpr size_t OFF_OUT = OFF_FC + 32 * 1024;        // [s 4][lane 64]  (5 outputs padded to 16)
+  static constexpr size_t OFF_BIAS = OFF_OUT + 4 * 1024;       // fp32: be, bi_r + bh_r, bi_z + bh_z, bi_n, bh_n, bf [128 each], bo [16]
+  static constexpr int BIAS_FLOATS = 6 * kG + 16;
+  static constexpr size_t BYTES = OFF_BIAS + size_t(BIAS_FLOATS) * 4;
+  static constexpr int N_EMB = 8 * 64 * 8, N_GRU = 8 * 24 * 64 * 8, N_FC = 8 * 4 * 64 * 8, N_OUT = 4 * 64 * 8;
+  static constexpr int THREADS = N_EMB + N_GRU + N_FC + N_OUT + BIAS_FLOATS;
+};
+
+// One thread per packed bf16 weight or fp32 bias.  D = observation width (<= 32).
+__global__ void pack_gru_kernel(uint8_t* __restrict__ out, int D, const float* __restrict__ We,
+                                const float* __restrict__ be, const float* __restrict__ Wi,
+                                const float* __restrict__ bi, const float* __restrict__ Wh,
+                                const float* __restrict__ bh, const float* __restrict__ Wf,
+                                const float* __restrict__ bf, const float* __restrict__ Wo,
+                                const float* __restrict__ bo) {
+  int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < GruPk::N_EMB) {
+    const int e = idx % 8, lane = (idx / 8) % 64, u = idx / 512;
+    const int k = 8 * (lane / 16) + e, o = 16 * u + lane % 16;
+    reinterpret_cast<uint16_t*>(out + GruPk::OFF_EMB)[idx] = f32_to_bf16_rne(k < D ? We[size_t(k) * kG + o] : 0.0f);
+    return;
+  }
+  idx -= GruPk::N_EMB;
+  if (idx < GruPk::N_GRU) {
+    const int e = idx % 8, lane = (idx / 8) % 64;
+    int rest = idx / 512;
+    const int s = rest % 4; rest /= 4;
+    const int src = rest % 2; rest /= 2;
+    const int gate = rest % 3, u = rest / 3;
+    const int k = 32 * s + 8 * (lane / 16) + e, col = gate * kG + 16 * u + lane % 16;
+    const float* W = src == 0 ? Wi : Wh;
+    reinterpret_cast<uint16_t*>(out + GruPk::OFF_GRU)[idx] = f32_to_bf16_rne(W[size_t(k) * 3 * kG + col]);
+    return;
+  }
+  idx -= GruPk::N_GRU;
+  if (idx < GruPk::N_FC) {
+    const int e = idx % 8, lane = (idx / 8) % 64, s = (idx / 512) % 4, u = idx / 2048;
+    const int k = 32 * s + 8 * (lane / 16) + e;
+    reinterpret_cast<uint16_t*>(out + GruPk::OFF_FC)[idx] = f32_to_bf16_rne(Wf[size_t(k) * kG + 16 * u + lane % 16]);
+    return;
+  }
+  idx -= GruPk::N_FC;
+  if (idx < GruPk::N_OUT) {
+    const int e = idx % 8, lane = (idx / 8) % 64, s = idx / 512;
+    const int k = 32 * s + 8 * (lane / 16) + e, o = lane % 16;
+    reinterpret_cast<uint16_t*>(out + GruPk::OFF_OUT)[idx] =
+        f32_to_bf16_rne(o < kNumActions ? Wo[size_t(k) * kNumActions + o] : 0.0f);
+    return;
+  }
+  idx -= GruPk::N_OUT;
+  if (idx < GruPk::BIAS_FLOATS) {
+    float v;
+    if (idx < kG) v = be[idx];
+    else if (idx < 2 * kG) v = bi[idx - kG] + bh[idx - kG];               // r
+    else if (idx < 3 * kG) v = bi[idx - kG] + bh[idx - kG];               // z (columns 128..255)
+    else if (idx < 4 * kG) v = bi[idx - kG];                              // n, input part (columns 256..383)
+    else if (idx < 5 * kG) v = bh[idx - 2 * kG];                          // n, recurrent part
+    else if (idx < 6 * kG) v = bf[idx - 5 * kG];
+    else v = (idx - 6 * kG) < kNumActions ? bo[idx - 6 * kG] : 0.0f;
+    reinterpret_cast<float*>(out + GruPk::OFF_BIAS)[idx] = v;
+  }
+}
+
+constexpr size_t up16(size_t x) { return (x + 15) & ~size_t(15); }
+
+template <int N>
+struct GruSmem {
+  static constexpr int B = 64 * N, D = 6 * N, NT = 4 * N;       // rows, obs width, 16-row tiles
+  // fp32 observation tile (+ tail: the embedding reads 32 columns of a row); after the embedding it
+  // is dead, and the logits [B][8] of the same step are stored in its place
+  static constexpr size_t OBS_BYTES = size_t(B) * D * 4 + 128;
+  static constexpr size_t LOGIT_BYTES = size_t(B) * 8 * 4;
+  static constexpr size_t OFF_OBS = 0;
+  static constexpr size_t OFF_X = up16(OBS_BYTES > LOGIT_BYTES ? OBS_BYTES : LOGIT_BYTES);   // e, later y
+  static constexpr size_t OFF_HB = OFF_X + size_t(B) * kAS;                                  // bf16 copy of h
+  static constexpr size_t OFF_FCW = OFF_HB + size_t(B) * kAS;
+  static constexpr size_t OFF_OUTW = OFF_FCW + 32 * 1024;
+  static constexpr size_t OFF_BIAS = OFF_OUTW + 4 * 1024;
+  static constexpr size_t OFF_XCH = up16(OFF_BIAS + size_t(GruPk::BIAS_FLOATS) * 4);         // [B] float2: new positions
+  static constexpr size_t OFF_DONE = OFF_XCH + size_t(B) * 8;                                // [64] bytes
+  static constexpr size_t TOTAL = OFF_DONE + 64;
+  static_assert(TOTAL <= 160 * 1024, "LDS");
+};
+
+__device__ __forceinline__ float fast_sigmoid(float x) { return hw_rcp(1.0f + hw_exp2(-kLog2e * x)); }
+
+__device__ __forceinline__ uint2 pack4_bf16(float a, float b, float c, float d) {
+  return make_uint2(pack_bf16_rne(a, b), pack_bf16_rne(c, d));
+}
+
+template <int N>
+__global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
+                                                          float* __restrict__ hidden, uint32_t groups,
+                                                          uint32_t groups_per_xcd) {
+  using M = GruSmem<N>;
+  constexpr int B = M::B, D = M::D, NT = M::NT;
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+  float* tile = reinterpret_cast<float*>(smem + M::OFF_OBS);
+  float* logits = tile;
+  uint8_t* xbuf = smem + M::OFF_X;
+  uint8_t* hbuf = smem + M::OFF_HB;
+  const bf16x8* fcw = reinterpret_cast<const bf16x8*>(smem + M::OFF_FCW);
+  const bf16x8* outw = reinterpret_cast<const bf16x8*>(smem + M::OFF_OUTW);
+  const float* bias = reinterpret_cast<const float*>(smem + M::OFF_BIAS);
+  float2* xch = reinterpret_cast<float2*>(smem + M::OFF_XCH);
+  uint8_t* donef = smem + M::OFF_DONE;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int u = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront = owned unit tile
+  const int j = lane & 15, gq = lane >> 4;
+  const size_t TE = A.TE;
+  const uint32_t grp = (blockIdx.x & 7u) * groups_per_xcd + (blockIdx.x >> 3);
+  if (grp >= groups) return;  // whole block, before any barrier
+  const size_t g0 = size_t(grp) * 64;
+  const size_t left = TE - g0;
+  const int nvalid = left < size_t(64) ? int(left) : 64;   // valid envs of this block
+  const int vrows = nvalid * N;                            // valid agent rows
+
+  // ---- stationary operands: this wavefront's GRU and embedding tiles in registers; the small
+  // layers and all biases in LDS
+  bf16x8 wg[3][2][4];
+#pragma unroll
+  for (int gate = 0; gate < 3; ++gate)
+#pragma unroll
+    for (int src = 0; src < 2; ++src)
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        wg[gate][src][s] = reinterpret_cast<const bf16x8*>(packed + GruPk::OFF_GRU)[(((u * 3 + gate) * 2 + src) * 4 + s) * 64 + lane];
+  const bf16x8 we = reinterpret_cast<const bf16x8*>(packed + GruPk::OFF_EMB)[u * 64 + lane];
+  {
+    const uint4* src = reinterpret_cast<const uint4*>(packed + GruPk::OFF_FC);
+    uint4* dst = reinterpret_cast<uint4*>(smem + M::OFF_FCW);
+    for (int k = tid; k < (32 + 4) * 1024 / 16; k += 512) dst[k] = src[k];      // FC and OUT are adjacent in both
+    const float* bsrc = reinterpret_cast<const float*>(packed + GruPk::OFF_BIAS);
+    float* bdst = reinterpret_cast<float*>(smem + M::OFF_BIAS);
+    for (int k = tid; k < GruPk::BIAS_FLOATS; k += 512) bdst[k] = bsrc[k];
+    if (tid < 32) tile[B * D + tid] = 0.0f;
+    if (tid < 64) donef[tid] = 0;
+  }
+
+  // ---- carried state of this wavefront's units: hreg[rt][r] = h[row 16 rt + j][unit 16 u + 4 gq + r]
+  float hreg[NT][4];
+#pragma unroll
+  for (int rt = 0; rt < NT; ++rt) {
+    const int row = 16 * rt + j;
+    f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (row < vrows) v = *reinterpret_cast<const f32x4*>(hidden + (g0 * N + row) * kG + 16 * u + 4 * gq);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) hreg[rt][r] = v[r];
+    *reinterpret_cast<uint2*>(hbuf + row * kAS + (16 * u + 4 * gq) * 2) = pack4_bf16(v[0], v[1], v[2], v[3]);
+  }
+
+  // ---- agents: the first B threads, one lane per agent row
+  const bool agent = tid < B;
+  const int el = tid / N, i = tid - el * N;          // env within block, agent (agent lanes only)
+  const size_t g = g0 + el;
+  const bool valid = agent && g < TE;
+  const uint32_t gc = valid ? uint32_t(g) : uint32_t(g0);
+  const uint32_t run = gc / A.E;
+  const uint32_t env = gc - run * A.E;
+  float px = 0.0f, py = 0.0f, vx = 0.0f, vy = 0.0f;
+  float qx[N], qy[N], lx[N], ly[N];     // all agents' positions and the landmarks of this lane's env
+  int32_t ep = 0;
+#pragma unroll
+  for (int a = 0; a < N; ++a) qx[a] = qy[a] = lx[a] = ly[a] = 0.0f;
+  if (valid) {
+#pragma unroll
+    for (int a = 0; a < N; ++a) {
+      qx[a] = A.st.pos_a[(0 * N + a) * TE + g];
+      qy[a] = A.st.pos_a[(1 * N + a) * TE + g];
+      lx[a] = A.st.pos_l[(0 * N + a) * TE + g];
+      ly[a] = A.st.pos_l[(1 * N + a) * TE + g];
+    }
+    vx = A.st.vel_a[(0 * N + i) * TE + g];
+    vy = A.st.vel_a[(1 * N + i) * TE + g];
+    ep = A.st.ep_step[g];
+  }
+#pragma unroll
+  for (int a = 0; a < N; ++a) {
+    if (a == i) { px = qx[a]; py = qy[a]; }
+  }
+
+  // Observation row of this lane from the registers above.
+  auto write_obs_row = [&]() {
+    float2* row = reinterpret_cast<float2*>(tile + tid * D);
+    int c = 0;
+    row[c++] = make_float2(vx, vy);
+    row[c++] = make_float2(px, py);
+#pragma unroll
+    for (int l = 0; l < N; ++l) row[c++] = make_float2(lx[l] - px, ly[l] - py);
+#pragma unroll
+    for (int a = 0; a < N; ++a) {
+      if (a != i) row[c++] = make_float2(qx[a] - px, qy[a] - py);
+    }
+    for (int zc = 0; zc < N - 1; ++zc) row[c + zc] = make_float2(0.0f, 0.0f);
+  };
+  if (agent) write_obs_row();
+  __syncthreads();   // staged weights, biases, HB, first observation
+
+  float* obs_p = A.obs_traj ? A.obs_traj + g0 * N * D : nullptr;
+  uint8_t* act_base = A.act_traj;
+  float* rew_base = A.rew_traj;
+  uint8_t* done_base = A.done_traj;
+  const size_t row_off = size_t(gc) * N + i;
+  const bool env_writer = valid && i == 0;
+  uint32_t step = A.abs_step;
+
+  // Copy the valid rows of the observation tile to dst (all threads of the block).
+  auto flush_tile = [&](float* dst) {
+    const int nf = vrows * D;   // even
+    if ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
+      for (int k = tid; k < (nf >> 2); k += 512)
+        reinterpret_cast<float4*>(dst)[k] = reinterpret_cast<const float4*>(tile)[k];
+      if ((nf & 2) && tid == 0)
+        reinterpret_cast<float2*>(dst)[nf / 2 - 1] = reinterpret_cast<const float2*>(tile)[nf / 2 - 1];
+    } else {
+      for (int k = tid; k < (nf >> 1); k += 512)
+        reinterpret_cast<float2*>(dst)[k] = reinterpret_cast<const float2*>(tile)[k];
+    }
+  };
+
+  for (int t = 0; t < A.T; ++t, ++step) {
+    // ---- observation of this step to the trajectory
+    if (obs_p) {
+      flush_tile(obs_p);
+      obs_p += TE * (N * D);
+    }
+    // ---- embedding: e = tanh(We^T o + be), this wavefront's 16 units of every row -> X
+#pragma unroll
+    for (int rt = 0; rt < NT; ++rt) {
+      const int row = 16 * rt + j;
+      const float2* src = reinterpret_cast<const float2*>(tile + row * D + 8 * gq);
+      u32x4 p;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float2 v = src[q];
+        p[q] = pack_bf16_rne(v.x, v.y);
+      }
+      f32x4 acc = *reinterpret_cast<const f32x4*>(bias + 16 * u + 4 * gq);
+      acc = MPE_MFMA_BF(we, __builtin_bit_cast(bf16x8, p), acc);
+      *reinterpret_cast<uint2*>(xbuf + row * kAS + (16 * u + 4 * gq) * 2) =
+          pack4_bf16(fast_tanh(acc[0]), fast_tanh(acc[1]), fast_tanh(acc[2]), fast_tanh(acc[3]));
+    }
+    __syncthreads();   // X complete; the observation tile has been read
+
+    // ---- gates and new state of this wavefront's units (reads X and HB of all units)
+    uint2 hnew16[NT];
+#pragma unroll
+    for (int rt = 0; rt < NT; ++rt) {
+      const int row = 16 * rt + j;
+      const bool fresh = donef[row / N] != 0;     // the env finished an episode in the last step: h = 0
+      f32x4 ar = *reinterpret_cast<const f32x4*>(bias + 1 * kG + 16 * u + 4 * gq);
+      f32x4 az = *reinterpret_cast<const f32x4*>(bias + 2 * kG + 16 * u + 4 * gq);
+      f32x4 ani = *reinterpret_cast<const f32x4*>(bias + 3 * kG + 16 * u + 4 * gq);
+      f32x4 anh = *reinterpret_cast<const f32x4*>(bias + 4 * kG + 16 * u + 4 * gq);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const bf16x8 bx = *reinterpret_cast<const bf16x8*>(xbuf + row * kAS + 64 * s + 16 * gq);
+        u32x4 hb = *reinterpret_cast<const u32x4*>(hbuf + row * kAS + 64 * s + 16 * gq);
+        if (fresh) hb = u32x4{0u, 0u, 0u, 0u};
+        const bf16x8 bh = __builtin_bit_cast(bf16x8, hb);
+        ar = MPE_MFMA_BF(wg[0][0][s], bx, ar);
+        ar = MPE_MFMA_BF(wg[0][1][s], bh, ar);
+        az = MPE_MFMA_BF(wg[1][0][s], bx, az);
+        az = MPE_MFMA_BF(wg[1][1][s], bh, az);
+        ani = MPE_MFMA_BF(wg[2][0][s], bx, ani);
+        anh = MPE_MFMA_BF(wg[2][1][s], bh, anh);
+      }
+      float hn[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float h = fresh ? 0.0f : hreg[rt][r];
+        const float rr = fast_sigmoid(ar[r]);
+        const float zz = fast_sigmoid(az[r]);
+        const float nn = fast_tanh(fmaf(rr, anh[r], ani[r]));
+        hn[r] = fmaf(zz, h - nn, nn);            // (1 - z) n + z h
+        hreg[rt][r] = hn[r];
+      }
+      hnew16[rt] = pack4_bf16(hn[0], hn[1], hn[2], hn[3]);
+    }
+    __syncthreads();   // every wavefront has read the old HB
+#pragma unroll
+    for (int rt = 0; rt < NT; ++rt)
+      *reinterpret_cast<uint2*>(hbuf + (16 * rt + j) * kAS + (16 * u + 4 * gq) * 2) = hnew16[rt];
+    __syncthreads();   // HB = bf16(h')
+
+    // ---- second fully-connected layer: y = tanh(Wf^T h' + bf) -> X (e is dead)
+    {
+      bf16x8 wf[4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) wf[s] = fcw[(u * 4 + s) * 64 + lane];
+#pragma unroll
+      for (int rt = 0; rt < NT; ++rt) {
+        const int row = 16 * rt + j;
+        f32x4 acc = *reinterpret_cast<const f32x4*>(bias + 5 * kG + 16 * u + 4 * gq);
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+          acc = MPE_MFMA_BF(wf[s], *reinterpret_cast<const bf16x8*>(hbuf + row * kAS + 64 * s + 16 * gq), acc);
+        *reinterpret_cast<uint2*>(xbuf + row * kAS + (16 * u + 4 * gq) * 2) =
+            pack4_bf16(fast_tanh(acc[0]), fast_tanh(acc[1]), fast_tanh(acc[2]), fast_tanh(acc[3]));
+      }
+    }
+    __syncthreads();   // Y complete
+
+    // ---- logits of row tiles u, u + 8 -> L (in place of the observation tile)
+    for (int rt = u; rt < NT; rt += 8) {
+      const int row = 16 * rt + j;
+      f32x4 acc = *reinterpret_cast<const f32x4*>(bias + 6 * kG + 4 * gq);
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        acc = MPE_MFMA_BF(outw[s * 64 + lane], *reinterpret_cast<const bf16x8*>(xbuf + row * kAS + 64 * s + 16 * gq), acc);
+      if (gq == 0) *reinterpret_cast<f32x4*>(logits + row * 8) = acc;       // outputs 0..3
+      else if (gq == 1) logits[row * 8 + 4] = acc[0];                       // output 4
+    }
+    __syncthreads();   // L complete
+
+    // ---- agents: sample, store, move
+    if (agent) {
+      float z[kNumActions];
+#pragma unroll
+      for (int k = 0; k < kNumActions; ++k) z[k] = logits[tid * 8 + k];
+      const uint32_t act = gumbel_argmax(z, A.seed, run, env, step, uint32_t(i));
+      if (act_base && valid) act_base[row_off] = uint8_t(act);
+      float fx = A.ph.accel * action_dir_x(act);
+      float fy = A.ph.accel * action_dir_y(act);
+#pragma unroll
+      for (int a = 0; a < N; ++a) {
+        if (a != i) {
+          const float dx = px - qx[a], dy = py - qy[a];
+          const float k = contact_factor(dx, dy, A.ph);
+          fx = fmaf(k, dx, fx);
+          fy = fmaf(k, dy, fy);
+        }
+      }
+      px = fmaf(vx, A.ph.dt, px);
+      py = fmaf(vy, A.ph.dt, py);
+      vx = fmaf(fx, A.ph.dt_over_mass, vx * A.ph.keep);
+      vy = fmaf(fy, A.ph.dt_over_mass, vy * A.ph.keep);
+      xch[tid] = make_float2(px, py);
+    }
+    if (act_base) act_base += TE * N;
+    __syncthreads();   // new positions visible; L has been read
+
+    // ---- agents: reward, done, auto-reset, next observation (written over L)
+    if (agent) {
+#pragma unroll
+      for (int a = 0; a < N; ++a) {
+        const float2 p = xch[el * N + a];
+        qx[a] = p.x;
+        qy[a] = p.y;
+      }
+      float r = 0.0f;
+#pragma unroll
+      for (int l = 0; l < N; ++l) {
+        float best2 = INFINITY;
+#pragma unroll
+        for (int a = 0; a < N; ++a) {
+          const float dx = qx[a] - lx[l], dy = qy[a] - ly[l];
+          best2 = fminf(best2, fmaf(dx, dx, dy * dy));
+        }
+        r -= hw_sqrt(best2);
+      }
+      if (A.ph.reward_mode == 1) {
+        uint32_t overlaps = 0;
+#pragma unroll
+        for (int a = 0; a < N; ++a) {
+          if (a != i) {
+            const float dx = px - qx[a], dy = py - qy[a];
+            overlaps += fmaf(dx, dx, dy * dy) < A.ph.two_r_sq ? 1u : 0u;
+          }
+        }
+        if (rew_base && valid) rew_base[row_off] = mixed_reward(r, overlaps, A.ph);
+      } else if (rew_base && env_writer) {
+        rew_base[gc] = r;
+      }
+      ep += 1;
+      const bool done = ep >= A.ph.max_ep;
+      if (done_base && env_writer) done_base[gc] = done ? 1 : 0;
+      if (i == 0) donef[el] = done ? 1 : 0;     // read by the gate phase of the next step
+      if (done) {
+        // new episode keyed by step + 1; every lane regenerates its whole env (1 step in max_ep)
+        uint32_t env_r = env;
+        asm volatile("" : "+v"(env_r));
+#pragma unroll
+        for (int a = 0; a < N; ++a) {
+          const uint4 w = philox4x32_10(env_r, step + 1u, uint32_t(a), kTagResetPos, A.seed, run);
+          qx[a] = word_to_position(w.x);
+          qy[a] = word_to_position(w.y);
+          const uint4 wl = philox4x32_10(env_r, step + 1u, uint32_t(N + a), kTagResetPos, A.seed, run);
+          lx[a] = word_to_position(wl.x);
+          ly[a] = word_to_position(wl.y);
+        }
+#pragma unroll
+        for (int a = 0; a < N; ++a) {
+          if (a == i) { px = qx[a]; py = qy[a]; }
+        }
+        vx = vy = 0.0f;
+        ep = 0;
+      }
+      write_obs_row();
+    }
+    if (rew_base) rew_base += A.ph.reward_mode == 1 ? TE * N : TE;
+    if (done_base) done_base += TE;
+    __syncthreads();   // next observation and the done flags complete
+  }
+  if (A.last_obs) flush_tile(A.last_obs + g0 * N * D);
+
+  // ---- state back to HBM: the carried state (cleared where the last step ended an episode), agents
+#pragma unroll
+  for (int rt = 0; rt < NT; ++rt) {
+    const int row = 16 * rt + j;
+    if (row < vrows) {
+      const bool fresh = donef[row / N] != 0;
+      f32x4 v;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) v[r] = fresh ? 0.0f : hreg[rt][r];
+      *reinterpret_cast<f32x4*>(hidden + (g0 * N + row) * kG + 16 * u + 4 * gq) = v;
+    }
+  }
+  if (valid) {
+    A.st.pos_a[(0 * N + i) * TE + g] = px;
+    A.st.pos_a[(1 * N + i) * TE + g] = py;
+    A.st.vel_a[(0 * N + i) * TE + g] = vx;
+    A.st.vel_a[(1 * N + i) * TE + g] = vy;
+#pragma unroll
+    for (int l = 0; l < N; ++l) {
+      if (l == i) {
+        A.st.pos_l[(0 * N + l) * TE + g] = lx[l];
+        A.st.pos_l[(1 * N + l) * TE + g] = ly[l];
+      }
+    }
+    if (i == 0) A.st.ep_step[g] = ep;
+  }
+}
+
+template <int N>
+hipError_t rollout_gru_impl(const RolloutArgs& A, const PolicyBuffers& pb, float* hidden, hipStream_t s) {
+  using M = GruSmem<N>;
+  auto kern = rollout_gru_kernel<N>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(M::TOTAL));
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const uint32_t groups = (A.TE + 63) / 64;
+  const uint32_t per_xcd = (groups + 7) / 8;
+  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(512), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),
+                     hidden, groups, per_xcd);
+  return hipGetLastError();
+}
+
+__global__ void fill_zero_kernel(float* __restrict__ p, size_t n) {
+  for (size_t k = size_t(blockIdx.x) * blockDim.x + threadIdx.x; k < n; k += size_t(gridDim.x) * blockDim.x) p[k] = 0.0f;
+}
+
+}  // namespace
+
+void launch_fill_zero(float* p, size_t n, hipStream_t s) {
+  if (n == 0) return;
+  const size_t blocks = (n + 255) / 256;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(uint32_t(blocks < 4096 ? blocks : 4096)), dim3(256), 0, s, p, n);
+}
+
+bool gru_supported(int N, int H, int weight_dtype) { return N >= 1 && N <= 3 && H == kG && weight_dtype == 1; }
+
+hipError_t pack_policy_gru(PolicyBuffers& pb, int N, const float* We, const float* be, const float* Wi,
+                           const float* bi, const float* Wh, const float* bh, const float* Wf, const float* bf,
+                           const float* Wo, const float* bo, hipStream_t s) {
+  if (hipError_t e = ensure_policy_bytes(pb, GruPk::BYTES); e != hipSuccess) return e;
+  hipLaunchKernelGGL(pack_gru_kernel, dim3((GruPk::THREADS + 255) / 256), dim3(256), 0, s,
+                     static_cast<uint8_t*>(pb.packed), 6 * N, We, be, Wi, bi, Wh, bh, Wf, bf, Wo, bo);
+  return hipGetLastError();
+}
+
+hipError_t launch_rollout_gru(int N, const RolloutArgs& A, const PolicyBuffers& pb, float* hidden, hipStream_t s) {
+  switch (N) {
+    case 1: return rollout_gru_impl<1>(A, pb, hidden, s);
+    case 2: return rollout_gru_impl<2>(A, pb, hidden, s);
+    case 3: return rollout_gru_impl<3>(A, pb, hidden, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace mpe

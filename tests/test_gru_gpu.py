@@ -1,0 +1,196 @@
+"""Parity of the fused rollout with the recurrent policy (bf16 matrices and layer inputs, fp32
+accumulation and carried state) against the oracle, through the C ABI.
+
+What can be asked of a bf16 network: both sides round the same fp32/fp64 values to bf16 at the same
+points, but a value that sits within ~1e-7 of a rounding boundary can round the other way on the
+fp32 path (its tanh / sigmoid / sums carry ~1e-7 of error), which moves one input of the next
+product by 2^-9 relative.  So teacher-forced single steps are compared statistically: most carried
+states within 1e-5, none beyond a few 1e-3, actions >= 99 % equal (the bf16 bar of the wide
+feed-forward policy); everything that is not arithmetic (state carry across calls, clearing at
+episode ends, time slots, determinism) is compared bit for bit."""
+import numpy as np
+import pytest
+
+from tests import helpers as Hp
+from paper_2311_10090_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+G = 128
+
+
+@pytest.fixture(scope="module")
+def mods():
+    if not torch.cuda.is_available():
+        pytest.fail("gpu tests need a device; the library has no CPU fallback")
+    from paper_2311_10090_amd.binding import MpeEnv
+    from oracle import Oracle
+    return MpeEnv, Oracle
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def _pair(mods, E, N, wseed=3, max_ep=synth.MAX_EPISODE_STEPS, reward_mode=0):
+    MpeEnv, Oracle = mods
+    env = MpeEnv(Hp.gpu_config(E, N, 1, 128, 1, max_ep=max_ep, reward_mode=reward_mode))
+    orc = Oracle(Hp.oracle_config(E, N, 1, 128, 1, max_ep=max_ep, reward_mode=reward_mode), threads=8)
+    w = synth.gru_weights(wseed, 1, 6 * N)
+    env.set_gru_policy(*Hp.to_dev(w))
+    orc.set_gru(*w)
+    return env, orc, w
+
+
+@pytest.mark.parametrize("E,N,T", [(256, 3, 12), (100, 3, 12), (64, 1, 12), (130, 2, 12), (2048, 3, 6)])
+def test_teacher_forced_steps(mods, E, N, T):
+    say("recurrent policy, forced steps E=%d N=%d T=%d" % (E, N, T))
+    env, orc, _ = _pair(mods, E, N)
+    orc.reset(21)
+    env.reset(21)
+    g = np.random.Generator(np.random.PCG64(5))
+    agree = total = 0
+    n_h = n_h_close = 0
+    worst_h = sum_h = 0.0
+    bufs = env.empty_traj(1)
+    for t in range(T):
+        if t == 3:      # an arbitrary carried state, not one the network produced
+            orc.set_hidden(g.uniform(-1, 1, (E, N, G)).astype(np.float32).astype(np.float64))
+        pa, va, pl, ep, s = orc.get_state()
+        h0 = orc.get_hidden()
+        env.set_state(*Hp.state_to_gpu(pa, va, pl, ep), 21, s)
+        env.set_hidden(torch.from_numpy(h0.astype(np.float32)).cuda())
+        robs, ract, rrew, rdone, rlast = orc.rollout(1)
+        obs, act, rew, done, last = [x.cpu().numpy() for x in env.rollout(1, *bufs)]
+        Hp.assert_close_step(obs, robs, "obs acted on")
+        assert np.array_equal(done, rdone)
+        same = act == ract
+        agree += int(same.sum())
+        total += same.size
+        ok = same.all(axis=2)[0]
+        scale = Hp.step_scale(pa)[ok]
+        Hp.assert_close_step(last[ok], rlast[ok], "next obs", scale[:, None, None])
+        Hp.assert_close_step(rew[0][ok], rrew[0][ok], "reward", scale)
+        # carried state after the step (all rows: it does not depend on the sampled action)
+        h1 = env.get_hidden().cpu().numpy().astype(np.float64)
+        rh1 = orc.get_hidden()
+        d = np.abs(h1 - rh1)
+        n_h += d.size
+        n_h_close += int((d <= 1e-5).sum())
+        worst_h = max(worst_h, float(d.max()))
+        sum_h += float(d.sum())
+        if rdone.all():
+            assert not h1.any() and not rh1.any()
+    say("  action agreement %.5f over %d samples; carried state: %.4f within 1e-5, mean %.2e, worst %.2e"
+        % (agree / total, total, n_h_close / n_h, sum_h / n_h, worst_h))
+    assert agree / total >= 0.99
+    # each new state element sums 128 products with bf16-rounded e: a few per cent see one flipped input
+    assert n_h_close / n_h >= 0.9 and sum_h / n_h < 1e-4 and worst_h < 2e-2
+    env.close()
+
+
+@pytest.mark.parametrize("E,N", [(200, 3), (64, 2)])
+def test_free_running_statistics(mods, E, N):
+    """Free-running episodes: actions equal until the first bf16 rounding flip that changes a
+    sample; the share of (env, agent, step) samples that agree stays high over an episode."""
+    say("recurrent policy, free running E=%d N=%d" % (E, N))
+    env, orc, _ = _pair(mods, E, N)
+    orc.reset(7)
+    env.reset(7)
+    T = 25
+    obs, act, rew, done, last = [x.cpu().numpy() for x in env.rollout(T, *env.empty_traj(T))]
+    robs, ract, rrew, rdone, rlast = orc.rollout(T)
+    assert np.array_equal(done, rdone)
+    assert np.array_equal(obs[0].astype(np.float64), robs[0])
+    same = (act == ract).all(axis=2)
+    alive = np.logical_and.accumulate(same, axis=0)
+    say("  envs identical after 5 / 25 steps: %.3f / %.3f" % (alive[4].mean(), alive[-1].mean()))
+    assert alive[4].mean() > 0.98 and alive[-1].mean() > 0.95
+    # while an env's actions agree its trajectory does too
+    prior = np.vstack([np.ones((1, E), bool), alive[:-1]])
+    e = np.abs(obs.astype(np.float64) - robs).reshape(T, E, -1).max(axis=2)
+    assert (e * prior).max() < 1e-3
+    assert not env.get_hidden().any()          # the episode ended at the last step
+    env.close()
+
+
+@pytest.mark.parametrize("N,reward_mode", [(3, 0), (3, 1), (1, 0), (2, 0)])
+def test_state_carry_time_slots_and_null_outputs(mods, N, reward_mode):
+    """T steps = T1 + T2 steps bit for bit (the carried state crosses the call boundary and an
+    episode end), one step at a time too; NULL outputs are not written; runs are deterministic."""
+    MpeEnv, _ = mods
+    E, T = 100, 30
+    w = Hp.to_dev(synth.gru_weights(9, 1, 6 * N))
+    envs = [MpeEnv(Hp.gpu_config(E, N, 1, 128, 1, reward_mode=reward_mode)) for _ in range(4)]
+    for e in envs:
+        e.set_gru_policy(*w)
+        e.reset(4)
+    full = envs[0].rollout(T, *envs[0].empty_traj(T))
+    a = envs[1].rollout(13, *envs[1].empty_traj(13))
+    assert bool(envs[1].get_hidden().any())
+    b = envs[1].rollout(T - 13, *envs[1].empty_traj(T - 13))
+    for k in range(4):
+        assert torch.equal(full[k], torch.cat([a[k], b[k]])), "output %d" % k
+    assert torch.equal(full[4], b[4])
+    one = envs[2].empty_traj(1)
+    for t in range(T):
+        envs[2].rollout(1, *one)
+        for k in range(4):
+            assert torch.equal(full[k][t], one[k][0]), "output %d at t=%d" % (k, t)
+    assert bool(full[3][24].all())
+    for e in envs[1:3]:
+        assert torch.equal(e.get_hidden(), envs[0].get_hidden())
+    act = torch.empty((T, E, N), dtype=torch.uint8, device="cuda")
+    envs[3].rollout(T, None, act, None, None, None)
+    assert torch.equal(act, full[1])
+    # the carried state matters: clearing it mid-episode changes the actions that follow
+    envs[3].reset(4)
+    envs[3].rollout(13, *envs[3].empty_traj(13))
+    envs[3].set_hidden(None)
+    c = envs[3].rollout(T - 13, *envs[3].empty_traj(T - 13))
+    assert not torch.equal(c[1][:5], b[1][:5])
+    for e in envs:
+        e.close()
+
+
+def test_hidden_state_access_and_reset(mods):
+    env, orc, _ = _pair(mods, 70, 3)
+    env.reset(1)
+    assert not env.get_hidden().any()
+    h = torch.rand((70, 3, G), device="cuda") - 0.5
+    env.set_hidden(h)
+    assert torch.equal(env.get_hidden(), h)
+    env.rollout(3, *env.empty_traj(3))
+    assert not torch.equal(env.get_hidden(), h)
+    env.reset(1)
+    assert not env.get_hidden().any()
+    env.close()
+
+
+def test_removing_the_recurrent_policy_and_refusals(mods):
+    from paper_2311_10090_amd.binding import MpeError, MPE_EINVAL, MPE_ESTATE
+    MpeEnv, _ = mods
+    env = MpeEnv(Hp.gpu_config(64, 3, 1, 128, 1))
+    with pytest.raises(MpeError) as ei:
+        env.get_hidden()
+    assert ei.value.code == MPE_ESTATE
+    w = Hp.to_dev(synth.gru_weights(2, 1, 18))
+    env.set_gru_policy(*w)
+    env.reset(5)
+    a = env.rollout(4, *env.empty_traj(4))[1].clone()
+    env.set_gru_policy()                 # back to uniform actions
+    env.reset(5)
+    b = env.rollout(4, *env.empty_traj(4))[1]
+    assert not torch.equal(a, b)
+    with pytest.raises(MpeError) as ei:
+        env.set_gru_policy(*w[:9], None)
+    assert ei.value.code == MPE_EINVAL
+    env.close()
+    for cfg in (Hp.gpu_config(64, 3, 1, 64, 0), Hp.gpu_config(64, 3, 1, 128, 0), Hp.gpu_config(64, 5, 1, 128, 1),
+                Hp.gpu_config(64, 3, 2, 128, 1), Hp.tag_gpu_config(64, 4, 2, 3, 1, 64)):
+        env = MpeEnv(cfg)
+        with pytest.raises(MpeError) as ei:
+            env.set_gru_policy(*Hp.to_dev(synth.gru_weights(2, 1, env.D)))
+        assert ei.value.code == MPE_EINVAL
+        env.close()
