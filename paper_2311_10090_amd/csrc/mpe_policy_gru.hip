@@ -17,8 +17,10 @@
 // over the banks): every wavefront reads all K of a row tile and writes its own 16 units.  The
 // carried state stays in fp32 registers of the owning wavefront (4 values per lane and row tile);
 // its bf16 copy for the next product lives in LDS.  Phases of a step, separated by block barriers:
-//   flush obs | embed -> X | gates (reads X, HB) | HB <- h' | fc (reads HB) -> Y=X | logits -> L |
+//   embed -> X | gates (reads X, HB) | HB <- h' | fc (reads HB) -> Y=X | logits -> L |
 //   agents: sample, move, exchange positions | reward, done, auto-reset, next observation
+// (the agent lanes store their fp32 observation rows straight to the trajectory and leave a bf16
+// copy in LDS for the embedding).
 // The first 64 N threads are also the agents (one lane per agent row) for the environment part.
 #include "mpe_mlp64.h"
 
@@ -103,9 +105,10 @@ constexpr size_t up16(size_t x) { return (x + 15) & ~size_t(15); }
 template <int N>
 struct GruSmem {
   static constexpr int B = 64 * N, D = 6 * N, NT = 4 * N;       // rows, obs width, 16-row tiles
-  // fp32 observation tile (+ tail: the embedding reads 32 columns of a row); after the embedding it
-  // is dead, and the logits [B][8] of the same step are stored in its place
-  static constexpr size_t OBS_BYTES = size_t(B) * D * 4 + 128;
+  // bf16 observation tile, 32 columns per row (zero beyond D) + 16 bytes of padding; after the
+  // embedding it is dead, and the logits [B][8] of the same step are stored in its place
+  static constexpr int OS = 80;
+  static constexpr size_t OBS_BYTES = size_t(B) * OS;
   static constexpr size_t LOGIT_BYTES = size_t(B) * 8 * 4;
   static constexpr size_t OFF_OBS = 0;
   static constexpr size_t OFF_X = up16(OBS_BYTES > LOGIT_BYTES ? OBS_BYTES : LOGIT_BYTES);   // e, later y
@@ -132,13 +135,13 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
   using M = GruSmem<N>;
   constexpr int B = M::B, D = M::D, NT = M::NT;
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-  float* tile = reinterpret_cast<float*>(smem + M::OFF_OBS);
-  float* logits = tile;
+  uint8_t* otile = smem + M::OFF_OBS;
+  float* logits = reinterpret_cast<float*>(smem + M::OFF_OBS);
   uint8_t* xbuf = smem + M::OFF_X;
   uint8_t* hbuf = smem + M::OFF_HB;
-  const bf16x8* fcw = reinterpret_cast<const bf16x8*>(smem + M::OFF_FCW);
-  const bf16x8* outw = reinterpret_cast<const bf16x8*>(smem + M::OFF_OUTW);
-  const float* bias = reinterpret_cast<const float*>(smem + M::OFF_BIAS);
+  const bf16x8* fcw0 = reinterpret_cast<const bf16x8*>(smem + M::OFF_FCW);
+  const bf16x8* outw0 = reinterpret_cast<const bf16x8*>(smem + M::OFF_OUTW);
+  const float* bias0 = reinterpret_cast<const float*>(smem + M::OFF_BIAS);
   float2* xch = reinterpret_cast<float2*>(smem + M::OFF_XCH);
   uint8_t* donef = smem + M::OFF_DONE;
 
@@ -172,7 +175,6 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
     const float* bsrc = reinterpret_cast<const float*>(packed + GruPk::OFF_BIAS);
     float* bdst = reinterpret_cast<float*>(smem + M::OFF_BIAS);
     for (int k = tid; k < GruPk::BIAS_FLOATS; k += 512) bdst[k] = bsrc[k];
-    if (tid < 32) tile[B * D + tid] = 0.0f;
     if (tid < 64) donef[tid] = 0;
   }
 
@@ -218,24 +220,45 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
     if (a == i) { px = qx[a]; py = qy[a]; }
   }
 
-  // Observation row of this lane from the registers above.
-  auto write_obs_row = [&]() {
-    float2* row = reinterpret_cast<float2*>(tile + tid * D);
-    int c = 0;
-    row[c++] = make_float2(vx, vy);
-    row[c++] = make_float2(px, py);
+  // Observation row of this lane from the registers above: bf16 (nearest even) into the LDS tile
+  // for the embedding, fp32 to `dst` (this lane's row of a trajectory slice, may be null).
+  auto write_obs_row = [&](float* dst) {
+    float o[32];
 #pragma unroll
-    for (int l = 0; l < N; ++l) row[c++] = make_float2(lx[l] - px, ly[l] - py);
+    for (int c = 0; c < 32; ++c) o[c] = 0.0f;
+    o[0] = vx; o[1] = vy; o[2] = px; o[3] = py;
+#pragma unroll
+    for (int l = 0; l < N; ++l) { o[4 + 2 * l] = lx[l] - px; o[5 + 2 * l] = ly[l] - py; }
 #pragma unroll
     for (int a = 0; a < N; ++a) {
-      if (a != i) row[c++] = make_float2(qx[a] - px, qy[a] - py);
+      // the other agents in ascending order: agent a sits in slot a - (a > i)
+#pragma unroll
+      for (int slot = 0; slot < N - 1; ++slot) {
+        if (a != i && a - (a > i ? 1 : 0) == slot) {
+          o[4 + 2 * N + 2 * slot] = qx[a] - px;
+          o[5 + 2 * N + 2 * slot] = qy[a] - py;
+        }
+      }
     }
-    for (int zc = 0; zc < N - 1; ++zc) row[c + zc] = make_float2(0.0f, 0.0f);
+    u32x4* row = reinterpret_cast<u32x4*>(otile + tid * M::OS);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      u32x4 v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = pack_bf16_rne(o[8 * q + 2 * e], o[8 * q + 2 * e + 1]);
+      row[q] = v;
+    }
+    if (dst && valid) {
+#pragma unroll
+      for (int c = 0; c < D / 2; ++c) reinterpret_cast<float2*>(dst)[c] = make_float2(o[2 * c], o[2 * c + 1]);
+    }
   };
-  if (agent) write_obs_row();
+  const size_t slice = TE * size_t(N * D);                               // floats per time slice
+  float* obs_row = A.obs_traj ? A.obs_traj + (size_t(gc) * N + i) * D : nullptr;   // this lane's row, slot 0
+  float* last_row = A.last_obs ? A.last_obs + (size_t(gc) * N + i) * D : nullptr;
+  if (agent) write_obs_row(obs_row);
   __syncthreads();   // staged weights, biases, HB, first observation
 
-  float* obs_p = A.obs_traj ? A.obs_traj + g0 * N * D : nullptr;
   uint8_t* act_base = A.act_traj;
   float* rew_base = A.rew_traj;
   uint8_t* done_base = A.done_traj;
@@ -243,50 +266,31 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
   const bool env_writer = valid && i == 0;
   uint32_t step = A.abs_step;
 
-  // Copy the valid rows of the observation tile to dst (all threads of the block).
-  auto flush_tile = [&](float* dst) {
-    const int nf = vrows * D;   // even
-    if ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
-      for (int k = tid; k < (nf >> 2); k += 512)
-        reinterpret_cast<float4*>(dst)[k] = reinterpret_cast<const float4*>(tile)[k];
-      if ((nf & 2) && tid == 0)
-        reinterpret_cast<float2*>(dst)[nf / 2 - 1] = reinterpret_cast<const float2*>(tile)[nf / 2 - 1];
-    } else {
-      for (int k = tid; k < (nf >> 1); k += 512)
-        reinterpret_cast<float2*>(dst)[k] = reinterpret_cast<const float2*>(tile)[k];
-    }
-  };
-
   for (int t = 0; t < A.T; ++t, ++step) {
-    // ---- observation of this step to the trajectory
-    if (obs_p) {
-      flush_tile(obs_p);
-      obs_p += TE * (N * D);
-    }
+    // Opaque zero: keeps the step-invariant LDS reads (biases, small-layer operands) inside the step
+    // loop; hoisted out of it they would pin ~40 registers for the whole rollout.
+    uint32_t zero = 0;
+    asm volatile("" : "+v"(zero));
+    const float* bias = bias0 + zero;
+    const bf16x8* fcw = fcw0 + zero;
+    const bf16x8* outw = outw0 + zero;
     // ---- embedding: e = tanh(We^T o + be), this wavefront's 16 units of every row -> X
 #pragma unroll
     for (int rt = 0; rt < NT; ++rt) {
       const int row = 16 * rt + j;
-      const float2* src = reinterpret_cast<const float2*>(tile + row * D + 8 * gq);
-      u32x4 p;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float2 v = src[q];
-        p[q] = pack_bf16_rne(v.x, v.y);
-      }
       f32x4 acc = *reinterpret_cast<const f32x4*>(bias + 16 * u + 4 * gq);
-      acc = MPE_MFMA_BF(we, __builtin_bit_cast(bf16x8, p), acc);
+      acc = MPE_MFMA_BF(we, *reinterpret_cast<const bf16x8*>(otile + row * M::OS + 16 * gq), acc);
       *reinterpret_cast<uint2*>(xbuf + row * kAS + (16 * u + 4 * gq) * 2) =
           pack4_bf16(fast_tanh(acc[0]), fast_tanh(acc[1]), fast_tanh(acc[2]), fast_tanh(acc[3]));
     }
     __syncthreads();   // X complete; the observation tile has been read
 
     // ---- gates and new state of this wavefront's units (reads X and HB of all units)
-    uint2 hnew16[NT];
 #pragma unroll
     for (int rt = 0; rt < NT; ++rt) {
       const int row = 16 * rt + j;
-      const bool fresh = donef[row / N] != 0;     // the env finished an episode in the last step: h = 0
+      // the env finished an episode in the last step: h = 0 (its HB row was cleared by its agent lane)
+      const bool fresh = donef[row / N] != 0;
       f32x4 ar = *reinterpret_cast<const f32x4*>(bias + 1 * kG + 16 * u + 4 * gq);
       f32x4 az = *reinterpret_cast<const f32x4*>(bias + 2 * kG + 16 * u + 4 * gq);
       f32x4 ani = *reinterpret_cast<const f32x4*>(bias + 3 * kG + 16 * u + 4 * gq);
@@ -294,32 +298,29 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
         const bf16x8 bx = *reinterpret_cast<const bf16x8*>(xbuf + row * kAS + 64 * s + 16 * gq);
-        u32x4 hb = *reinterpret_cast<const u32x4*>(hbuf + row * kAS + 64 * s + 16 * gq);
-        if (fresh) hb = u32x4{0u, 0u, 0u, 0u};
-        const bf16x8 bh = __builtin_bit_cast(bf16x8, hb);
+        const bf16x8 bh = *reinterpret_cast<const bf16x8*>(hbuf + row * kAS + 64 * s + 16 * gq);
+        // dependent accumulations three instructions apart
         ar = MPE_MFMA_BF(wg[0][0][s], bx, ar);
-        ar = MPE_MFMA_BF(wg[0][1][s], bh, ar);
         az = MPE_MFMA_BF(wg[1][0][s], bx, az);
-        az = MPE_MFMA_BF(wg[1][1][s], bh, az);
         ani = MPE_MFMA_BF(wg[2][0][s], bx, ani);
+        ar = MPE_MFMA_BF(wg[0][1][s], bh, ar);
+        az = MPE_MFMA_BF(wg[1][1][s], bh, az);
         anh = MPE_MFMA_BF(wg[2][1][s], bh, anh);
       }
-      float hn[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const float h = fresh ? 0.0f : hreg[rt][r];
         const float rr = fast_sigmoid(ar[r]);
         const float zz = fast_sigmoid(az[r]);
         const float nn = fast_tanh(fmaf(rr, anh[r], ani[r]));
-        hn[r] = fmaf(zz, h - nn, nn);            // (1 - z) n + z h
-        hreg[rt][r] = hn[r];
+        hreg[rt][r] = fmaf(zz, h - nn, nn);      // (1 - z) n + z h
       }
-      hnew16[rt] = pack4_bf16(hn[0], hn[1], hn[2], hn[3]);
     }
     __syncthreads();   // every wavefront has read the old HB
 #pragma unroll
     for (int rt = 0; rt < NT; ++rt)
-      *reinterpret_cast<uint2*>(hbuf + (16 * rt + j) * kAS + (16 * u + 4 * gq) * 2) = hnew16[rt];
+      *reinterpret_cast<uint2*>(hbuf + (16 * rt + j) * kAS + (16 * u + 4 * gq) * 2) =
+          pack4_bf16(hreg[rt][0], hreg[rt][1], hreg[rt][2], hreg[rt][3]);
     __syncthreads();   // HB = bf16(h')
 
     // ---- second fully-connected layer: y = tanh(Wf^T h' + bf) -> X (e is dead)
@@ -434,14 +435,18 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
         }
         vx = vy = 0.0f;
         ep = 0;
+        // the carried state of the new episode is zero: clear this row's bf16 copy (the fp32
+        // registers of the owning wavefronts follow the done flag)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) reinterpret_cast<u32x4*>(hbuf + tid * kAS)[q] = u32x4{0u, 0u, 0u, 0u};
       }
-      write_obs_row();
+      if (obs_row) obs_row += slice;
+      write_obs_row(t + 1 < A.T ? obs_row : last_row);
     }
     if (rew_base) rew_base += A.ph.reward_mode == 1 ? TE * N : TE;
     if (done_base) done_base += TE;
     __syncthreads();   // next observation and the done flags complete
   }
-  if (A.last_obs) flush_tile(A.last_obs + g0 * N * D);
 
   // ---- state back to HBM: the carried state (cleared where the last step ended an episode), agents
 #pragma unroll
