@@ -237,6 +237,25 @@ def main():
                          "landmarks": tL, "obs_dim": tD, "T": T, "bytes_per_env_step": t_bytes,
                          "kernel": "tag_rollout_kernel (lane per agent; policy / uniform variants)"}
 
+    # recurrent policy (GRU 128, bf16) on the headline env shape
+    gru = {}
+    if args.workload == "cfg2":
+        k = max(3, args.steps // 3)
+        env7 = MpeEnv(Hp.gpu_config(wl.num_envs, N, 1, 128, 1))
+        env7.set_gru_policy(*Hp.to_dev(synth.gru_weights(0, 1, D)))
+        env7.reset(seed)
+        b7 = env7.empty_traj(T)
+        w7, k7 = time_rollouts(env7, T, b7, k, 2)
+        ms7 = float(np.mean(k7))
+        g_flop = 2 * (D * 128 + 2 * 128 * 384 + 128 * 128 + 128 * 5)       # 235,264 per agent-step
+        g_tf = g_flop * agent_steps / (ms7 * 1e-3) / 1e12
+        gru = {"agent_steps_per_s": agent_steps / (w7 / k), "kernel_ms_avg": ms7, "flop_per_agent_step": g_flop,
+               "roofline": {"bound": "mfma", "achieved": g_tf, "peak": 2500.0, "unit": "TFLOP/s", "frac": g_tf / 2500.0},
+               "dtype": "bf16xbf16->f32", "kernel": "rollout_gru_kernel<3> (weight-stationary, 8 wavefronts per 64 envs)",
+               "note": "mpe_set_gru_policy: 18 -> 128 tanh -> GRU 128 -> 128 tanh -> 5; carried state fp32"}
+        env7.close()
+        del b7
+
     out = {
         "metric": "agent-steps/sec fused MPE rollout @65,536 envs, 1 MI355X; % HBM roofline",
         "value": value,
@@ -294,6 +313,7 @@ def main():
         "actor_critic": ac,
         "bf16_policy": bf,
         "tag_scenario": tag,
+        "recurrent_policy": gru,
         "single_step": {"us_per_mpe_step_call": step_us, "env_steps_per_s": TE / (step_us * 1e-6),
                         "note": "back-to-back mpe_step calls with resident actions; 352 B per env-step"},
         "paper_context": {"mpe_simple_spread_steps_per_s": {"original_cpu_1env_epyc7763": 8.3e4,
