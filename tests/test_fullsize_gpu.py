@@ -198,3 +198,106 @@ def test_large_size_mixed_reward():
     say("  %d agent rewards compared" % compared)
     assert compared > 3000
     env.close()
+
+
+# ------------------------------------------------------------------ second scenario, full size
+@pytest.mark.parametrize("with_policy", [True, False])
+def test_tag_scenario_full_size(with_policy):
+    """Predator-prey at the bench's size (65,536 envs x 4 agents x 128 steps, the launch bench.py
+    times), sampled env ranges against the oracle plus properties of the whole trajectory."""
+    from paper_2311_10090_amd.binding import MpeEnv
+    from oracle import Oracle
+    E, T, shape = 65536, 128, (4, 2, 3)
+    N, L, A = shape
+    H = 64 if with_policy else 0
+    say("full size tag scenario, policy=%s" % with_policy)
+    env = MpeEnv(Hp.tag_gpu_config(E, N, L, A, 1, H))
+    w = synth.policy_weights_with_bias(3, 1, env.D, 64) if with_policy else None
+    if w:
+        env.set_policy(*Hp.to_dev(w))
+    env.reset(1)
+    obs, act, rew, done, last = env.rollout(T, *env.empty_traj(T))
+    torch.cuda.synchronize()
+    assert int(done.sum().item()) == E * (T // 25) and bool((done[24::25] == 1).all())
+    assert bool((act <= 4).all()) and bool(torch.isfinite(obs).all()) and bool(torch.isfinite(rew).all())
+    assert bool((obs[:, :, 3, 14:] == 0).all()), "the good agent's row ends with two zeros"
+    assert bool((rew[:, :, :3] >= 0).all()) and bool((rew[:, :, 3] <= 0).all())
+    assert bool((rew[:, :, 0] == rew[:, :, 1]).all()) and bool((rew[:, :, 0] == rew[:, :, 2]).all())
+    adv = rew[:, :, 0]
+    assert bool(((adv / 10 - (adv / 10).round()).abs() < 1e-6).all()) and float(adv.max()) >= 10.0
+    speed = obs[..., 0:2].norm(dim=-1)
+    assert float(speed[:, :, :3].max()) <= 1.0 + 1e-5 and float(speed[:, :, 3].max()) <= 1.3 + 1e-5
+    tot = agree = 0
+    for off, n in ((0, 64), (32741, 7), (E - 64, 64)):
+        orc = Oracle(Hp.tag_oracle_config(n, N, L, A, 1, H, env_offset=off), threads=8)
+        if w:
+            orc.set_policy(*w)
+        orc.reset(1)
+        robs, ract, rrew, rdone, rlast = orc.rollout(T)
+        o, a, r, d = [x[:, off:off + n].cpu().numpy() for x in (obs, act, rew, done)]
+        assert np.array_equal(d, rdone)
+        for t0 in range(0, T, 25):
+            t1 = min(t0 + 25, T)
+            same = (a[t0:t1] == ract[t0:t1]).all(axis=2)
+            alive = np.logical_and.accumulate(same, axis=0)
+            prior = np.vstack([np.ones((1, n), bool), alive[:-1]])
+            agree += int((a[t0:t1] == ract[t0:t1])[prior].sum())
+            tot += int(prior.sum()) * N
+            e = np.abs(o[t0:t1].astype(np.float64) - robs[t0:t1]).reshape(t1 - t0, n, -1).max(axis=2)
+            assert (e[:5] * prior[:5]).max() <= Hp.EPISODE_ATOL
+            assert (e * prior).max() < 0.05
+            # rewards of the first steps of an episode (same positions to 1e-4: same touching decisions
+            # unless a pair sits on the threshold, which these few samples do not)
+            assert (np.abs(r[t0:t0 + 5] - rrew[t0:t0 + 5]).max(axis=2) * alive[:5]).max() <= 1e-3
+    say("  sampled action agreement %.6f over %d samples" % (agree / tot, tot))
+    assert (agree / tot >= Hp.ACTION_AGREEMENT - 2.0 / tot) if with_policy else agree == tot
+    env.close()
+
+
+# ------------------------------------------------------------------ recurrent policy, full size
+def test_recurrent_policy_full_size():
+    """GRU policy at the bench's size (65,536 envs x 3 agents x 128 steps): sampled env ranges against
+    the oracle (bf16 network: actions agree while no rounding flip has changed a sample; >= 99 %)."""
+    from paper_2311_10090_amd.binding import MpeEnv
+    from oracle import Oracle
+    E, T, N = 65536, 128, 3
+    say("full size recurrent policy")
+    env = MpeEnv(Hp.gpu_config(E, N, 1, 128, 1))
+    w = synth.gru_weights(5, 1, 18)
+    env.set_gru_policy(*Hp.to_dev(w))
+    env.reset(1)
+    obs, act, rew, done, last = env.rollout(T, *env.empty_traj(T))
+    torch.cuda.synchronize()
+    assert int(done.sum().item()) == E * (T // 25) and bool((done[24::25] == 1).all())
+    assert bool((act <= 4).all()) and bool(torch.isfinite(obs).all()) and bool((rew <= 0).all())
+    hist = torch.bincount(act.flatten().long(), minlength=5).double()
+    assert hist.min() > 0.02 * hist.sum()
+    hid = env.get_hidden()
+    assert bool(torch.isfinite(hid).all()) and float(hid.abs().max()) <= 1.0 and bool(hid.any())
+    tot = agree = 0
+    for off, n in ((0, 64), (32741, 7), (E - 64, 64)):
+        orc = Oracle(Hp.oracle_config(n, N, 1, 128, 1, env_offset=off), threads=8)
+        orc.set_gru(*w)
+        orc.reset(1)
+        robs, ract, rrew, rdone, rlast = orc.rollout(T)
+        o, a, r, d = [x[:, off:off + n].cpu().numpy() for x in (obs, act, rew, done)]
+        assert np.array_equal(d, rdone)
+        for t0 in range(0, T, 25):
+            t1 = min(t0 + 25, T)
+            assert np.array_equal(o[t0].astype(np.float64), robs[t0])
+            same = (a[t0:t1] == ract[t0:t1]).all(axis=2)
+            alive = np.logical_and.accumulate(same, axis=0)
+            prior = np.vstack([np.ones((1, n), bool), alive[:-1]])
+            agree += int((a[t0:t1] == ract[t0:t1])[prior].sum())
+            tot += int(prior.sum()) * N
+            e = np.abs(o[t0:t1].astype(np.float64) - robs[t0:t1]).reshape(t1 - t0, n, -1).max(axis=2)
+            assert (e[:5] * prior[:5]).max() <= Hp.EPISODE_ATOL
+            assert (e * prior).max() < 0.05
+        # carried state at the end (T = 128: 3 steps into an episode) where the whole last episode agreed
+        h = hid[off:off + n].cpu().numpy().astype(np.float64)
+        ok = (a[125:] == ract[125:]).all(axis=(0, 2))
+        dh = np.abs(h - orc.get_hidden())[ok]
+        assert dh.size and np.median(dh) < 1e-5 and dh.max() < 2e-2
+    say("  sampled action agreement %.6f over %d samples" % (agree / tot, tot))
+    assert agree / tot >= 0.99
+    env.close()
