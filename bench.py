@@ -216,8 +216,8 @@ def main():
         tD = Hp.tag_obs_dim(tN, tL, tA)
         t_bytes = tN * tD * 4 + tN + 4 * tN + 1                 # obs + actions + per-agent rewards + done: 277
         t_steps = wl.num_envs * tN * T
-        for name, hidden in (("fused", H), ("env_only", 0)):
-            env6 = MpeEnv(Hp.tag_gpu_config(wl.num_envs, tN, tL, tA, 1, hidden))
+        for name, hidden, wd6 in (("fused", H, 0), ("fused_bf16", H, 1), ("env_only", 0, 0)):
+            env6 = MpeEnv(Hp.tag_gpu_config(wl.num_envs, tN, tL, tA, 1, hidden, wd=wd6))
             if hidden:
                 env6.set_policy(*Hp.to_dev(synth.policy_weights(0, 1, tD, hidden)))
             env6.reset(seed)
@@ -227,7 +227,7 @@ def main():
             tag[name] = {"agent_steps_per_s": t_steps / (w6 / k), "kernel_ms_avg": ms6,
                          "hbm_GBs": t_bytes * wl.num_envs * T / (ms6 * 1e-3) / 1e9,
                          "hbm_frac": t_bytes * wl.num_envs * T / (ms6 * 1e-3) / 1e9 / HBM_PEAK_GBS}
-            if hidden:
+            if hidden and wd6 == 0:
                 tf = flops_per_agent_step(tD, hidden) * t_steps / (ms6 * 1e-3) / 1e12
                 tag[name].update({"flop_per_agent_step": flops_per_agent_step(tD, hidden), "fp32_equivalent_TFLOPs": tf,
                                   "frac_of_fp32_matrix_peak": tf / MFMA_FP32_PEAK_TFLOPS})

@@ -252,9 +252,10 @@ int mpe_set_policy(mpe_env* e, const float* W1, const float* b1, const float* W2
   hipError_t err;
   if (e->tag) {
     if (!tag_policy_supported(e->N, e->L, e->G, e->H, e->cfg.weight_dtype))
-      return fail(MPE_EINVAL, "mpe_set_policy: MPE_SCENARIO_TAG policies are built for hidden 64, fp32 weights and "
-                              "observation rows of at most 16 floats");
-    err = pack_policy_tag(e->pol, e->N, e->L, e->G, int(e->R), W1, b1, W2, b2, W3, b3, static_cast<hipStream_t>(stream));
+      return fail(MPE_EINVAL, "mpe_set_policy: MPE_SCENARIO_TAG policies are built for hidden 64 and observation "
+                              "rows of at most 16 floats");
+    err = pack_policy_tag(e->pol, e->N, e->L, e->G, int(e->R), e->cfg.weight_dtype == MPE_WEIGHTS_BF16, W1, b1, W2,
+                          b2, W3, b3, static_cast<hipStream_t>(stream));
   } else {
     err = pack_policy(e->pol, e->N, e->H, int(e->R), e->cfg.weight_dtype, W1, b1, W2, b2, W3, b3,
                       static_cast<hipStream_t>(stream), &why);
@@ -297,7 +298,8 @@ int mpe_rollout(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, float
     TA.tg = e->tg;
     TA.actions_in = nullptr;
     const char* why = nullptr;
-    hipError_t err = launch_tag_rollout(e->N, e->L, e->G, e->has_policy ? 2 : 1, TA, e->pol.packed,
+    const int mode = !e->has_policy ? 1 : (e->cfg.weight_dtype == MPE_WEIGHTS_BF16 ? 3 : 2);
+    hipError_t err = launch_tag_rollout(e->N, e->L, e->G, mode, TA, e->pol.packed,
                                         static_cast<hipStream_t>(stream), &why);
     if (why) return fail(MPE_EINVAL, "mpe_rollout: %s", why);
     if (err != hipSuccess) return fail(MPE_EHIP, "mpe_rollout: %s", hipGetErrorString(err));

@@ -1,6 +1,6 @@
 // Predator-prey ("simple tag") scenario of the MPE family (paper App. B.7: every scenario of the
 // family is implemented; Sec. 3.1 "MPE"): reset, single step, and the persistent T-step rollout
-// with uniform actions or with the fused fp32 policy (App. G: two tanh layers of width 64).
+// with uniform actions or with the fused policy, fp32-exact or bf16 (App. G: two tanh layers of width 64).
 //
 // Mapping: one lane per agent row, a block is 64 envs = N wavefronts (as in the fused simple-spread
 // kernel).  A lane keeps its own agent's position and velocity, the positions of all agents of its
@@ -23,13 +23,15 @@ struct TagShape {
   static_assert(G_ >= 1 && A >= 1 && L_ >= 0 && D % 2 == 0, "roles");
 };
 
-enum TagMode : int { kGiven = 0, kUniform = 1, kPolicy = 2 };
+enum TagMode : int { kGiven = 0, kUniform = 1, kPolicy = 2, kPolicyBf = 3 };   // fp32-exact / bf16 policy
 
 template <typename S, int MODE>
 struct TagSmem {
   static constexpr int ROWS = 64 * S::N;
-  static constexpr size_t OFF_BIAS = MODE == kPolicy ? Pk::LDS_BYTES : 0;
-  static constexpr size_t OFF_OBS = OFF_BIAS + (MODE == kPolicy ? Pk::BIAS_BYTES : 0);
+  static constexpr bool kHasPolicy = MODE == kPolicy || MODE == kPolicyBf;
+  using P = PkT<MODE == kPolicyBf>;
+  static constexpr size_t OFF_BIAS = kHasPolicy ? P::LDS_BYTES : 0;
+  static constexpr size_t OFF_OBS = OFF_BIAS + (kHasPolicy ? P::BIAS_BYTES : 0);
   static constexpr size_t OBS = size_t(ROWS) * S::D * 4 + 64;   // + zeroed tail: layer 1 reads 16 cols
   static constexpr size_t OFF_XCH = OFF_OBS + OBS;              // [parity][ROWS] float4 (px, py, vx, vy)
   static constexpr size_t TOTAL = OFF_XCH + size_t(S::kWaveLocal ? 1 : 2) * ROWS * 16;
@@ -136,7 +138,7 @@ __global__ __launch_bounds__(64 * S::N) void tag_reset_kernel(StatePtrs st, uint
 }
 
 template <typename S, int MODE>
-__global__ __launch_bounds__(64 * S::N, MODE == kPolicy ? 3 : 1) void tag_rollout_kernel(
+__global__ __launch_bounds__(64 * S::N, (MODE == kPolicy || MODE == kPolicyBf) ? 3 : 1) void tag_rollout_kernel(
     TagArgs TA, const uint8_t* __restrict__ packed, int per_run_weights, uint32_t groups, uint32_t groups_per_xcd) {
   using M = TagSmem<S, MODE>;
   using Net = NetShape<S::D, S::D <= 16 ? S::D : 16>;
@@ -167,11 +169,13 @@ __global__ __launch_bounds__(64 * S::N, MODE == kPolicy ? 3 : 1) void tag_rollou
 
   // ---- policy: W1A, W2A and the biases in LDS, W3A in registers (the run of the block's first env)
   W3Terms w3;
-  if constexpr (MODE == kPolicy) {
+  if constexpr (M::kHasPolicy) {
+    using Pk = typename M::P;
+    constexpr bool BF = MODE == kPolicyBf;
     const uint8_t* run_weights = packed + (per_run_weights ? size_t(uint32_t(g0) / A.E) * Pk::RUN_BYTES : 0);
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-      if constexpr (Net::kRowTerms) {
+      if constexpr (BF || Net::kRowTerms) {
         w3.s[s].h = reinterpret_cast<const bf16x8*>(run_weights + Pk::OFF_W3A)[s * 64 + lane];
       } else {
         const bf16x8* src = reinterpret_cast<const bf16x8*>(run_weights + Pk::OFF_W3A) + s * 3 * 64 + lane;
@@ -266,13 +270,14 @@ __global__ __launch_bounds__(64 * S::N, MODE == kPolicy ? 3 : 1) void tag_rollou
 #pragma unroll 1
       for (int pr = 0; pr < 2; ++pr) {
         float* rows = tile + (wave * 64 + pr * 32) * D;
-        policy_pair<Net>(smem, bias, w3, rows, rows + 16 * D, lane);
+        if constexpr (MODE == kPolicyBf) policy_pair_bf<Net>(smem, bias, w3, rows, rows + 16 * D, lane);
+        else policy_pair<Net>(smem, bias, w3, rows, rows + 16 * D, lane);
       }
       wave_sync();
       float z[kNumActions];
 #pragma unroll
       for (int k = 0; k < kNumActions; ++k) z[k] = tile[tid * D + k];
-      if constexpr (Net::kRowTerms) z[4] = (z[4] + tile[tid * D + 5]) + tile[tid * D + 6];
+      if constexpr (MODE == kPolicy && Net::kRowTerms) z[4] = (z[4] + tile[tid * D + 5]) + tile[tid * D + 6];
       act = gumbel_argmax(z, A.seed, run, env, step, uint32_t(i));
     }
     if (act_base) {
@@ -420,7 +425,7 @@ hipError_t tag_launch(int mode, const TagArgs& A, const void* packed, hipStream_
       *why = "with several runs, num_envs per run must be a multiple of 64";
       return hipSuccess;
     }
-    return tag_rollout_impl<S, kPolicy>(A, packed, s);
+    return mode == kPolicyBf ? tag_rollout_impl<S, kPolicyBf>(A, packed, s) : tag_rollout_impl<S, kPolicy>(A, packed, s);
   } else {
     *why = "no policy kernel for this shape (observation rows longer than 16)";
     return hipSuccess;
@@ -428,14 +433,19 @@ hipError_t tag_launch(int mode, const TagArgs& A, const void* packed, hipStream_
 }
 
 template <typename S>
-hipError_t tag_pack(PolicyBuffers& pb, int R, const float* W1, const float* b1, const float* W2, const float* b2,
-                    const float* W3, const float* b3, hipStream_t s) {
+hipError_t tag_pack(PolicyBuffers& pb, int R, bool bf16, const float* W1, const float* b1, const float* W2,
+                    const float* b2, const float* W3, const float* b3, hipStream_t s) {
   if constexpr (S::D <= 16) {
     using Net = NetShape<S::D, S::D>;
-    if (hipError_t e = ensure_policy_bytes(pb, size_t(R) * Pk::RUN_BYTES); e != hipSuccess) return e;
+    if (hipError_t e = ensure_policy_bytes(pb, size_t(R) * (bf16 ? PkB::RUN_BYTES : Pk::RUN_BYTES)); e != hipSuccess)
+      return e;
     constexpr int total = 4 * 64 * 8 + 4 * 2 * 64 * 8 + 2 * 64 * 8 + 2 * kH + 16;   // one thread per weight / bias
-    hipLaunchKernelGGL(pack_split_kernel<Net>, dim3((total + 255) / 256, R), dim3(256), 0, s,
-                       static_cast<uint8_t*>(pb.packed), W1, b1, W2, b2, W3, b3, 5);
+    if (bf16)
+      hipLaunchKernelGGL(pack_bf16_kernel<Net>, dim3((total + 255) / 256, R), dim3(256), 0, s,
+                         static_cast<uint8_t*>(pb.packed), W1, b1, W2, b2, W3, b3, 5);
+    else
+      hipLaunchKernelGGL(pack_split_kernel<Net>, dim3((total + 255) / 256, R), dim3(256), 0, s,
+                         static_cast<uint8_t*>(pb.packed), W1, b1, W2, b2, W3, b3, 5);
     return hipGetLastError();
   } else {
     return hipErrorInvalidValue;
@@ -455,7 +465,8 @@ bool tag_supported(int N, int L, int G) {
 }
 
 bool tag_policy_supported(int N, int L, int G, int H, int weight_dtype) {
-  return tag_supported(N, L, G) && H == kH && weight_dtype == 0 && 4 + 2 * L + 2 * (N - 1) + 2 * G <= 16;
+  return tag_supported(N, L, G) && H == kH && (weight_dtype == 0 || weight_dtype == 1) &&
+         4 + 2 * L + 2 * (N - 1) + 2 * G <= 16;
 }
 
 void launch_tag_reset(int N, int L, int G, const StatePtrs& st, uint32_t TE, uint32_t E, uint32_t seed, float* obs,
@@ -479,10 +490,10 @@ hipError_t launch_tag_rollout(int N, int L, int G, int mode, const TagArgs& A, c
   return hipErrorInvalidValue;
 }
 
-hipError_t pack_policy_tag(PolicyBuffers& pb, int N, int L, int G, int R, const float* W1, const float* b1,
+hipError_t pack_policy_tag(PolicyBuffers& pb, int N, int L, int G, int R, bool bf16, const float* W1, const float* b1,
                            const float* W2, const float* b2, const float* W3, const float* b3, hipStream_t s) {
 #define X(n, l, g) \
-  if (N == n && L == l && G == g) return tag_pack<TagShape<n, l, g>>(pb, R, W1, b1, W2, b2, W3, b3, s);
+  if (N == n && L == l && G == g) return tag_pack<TagShape<n, l, g>>(pb, R, bf16, W1, b1, W2, b2, W3, b3, s);
   MPE_TAG_SHAPES(X)
 #undef X
   return hipErrorInvalidValue;

@@ -36,21 +36,22 @@ def tag_obs_dim(N, L, A):
     return 4 + 2 * L + 2 * (N - 1) + 2 * (N - A)
 
 
-def tag_oracle_config(E, N=4, L=2, A=3, R=1, H=0, env_offset=0, run_offset=0, max_ep=synth.MAX_EPISODE_STEPS, **phys):
+def tag_oracle_config(E, N=4, L=2, A=3, R=1, H=0, env_offset=0, run_offset=0, max_ep=synth.MAX_EPISODE_STEPS, wd=0,
+                      **phys):
     """Predator-prey scenario: N agents of which the first A are adversaries, L obstacle landmarks."""
     from oracle import OracleConfig
     p = synth.physics_f32(synth.TAG_PHYSICS)
     p.update({k: float(np.float32(v)) for k, v in phys.items()})
     return OracleConfig(num_envs=E, num_agents=N, num_landmarks=L, num_runs=R, max_episode_steps=max_ep, hidden=H,
-                        weight_dtype=0, env_offset=env_offset, run_offset=run_offset, scenario=1, num_adversaries=A, **p)
+                        weight_dtype=wd, env_offset=env_offset, run_offset=run_offset, scenario=1, num_adversaries=A, **p)
 
 
-def tag_gpu_config(E, N=4, L=2, A=3, R=1, H=0, max_ep=synth.MAX_EPISODE_STEPS, **phys):
+def tag_gpu_config(E, N=4, L=2, A=3, R=1, H=0, max_ep=synth.MAX_EPISODE_STEPS, wd=0, **phys):
     from paper_2311_10090_amd.binding import MpeConfig, SCENARIO_TAG
     p = dict(synth.TAG_PHYSICS)
     p.update(phys)
     return MpeConfig(num_envs=E, num_agents=N, num_landmarks=L, num_runs=R, max_episode_steps=max_ep, hidden=H,
-                     weight_dtype=0, scenario=SCENARIO_TAG, num_adversaries=A, **p)
+                     weight_dtype=wd, scenario=SCENARIO_TAG, num_adversaries=A, **p)
 
 
 def state_to_gpu(pos_a, vel_a, pos_l, ep, device="cuda:0"):

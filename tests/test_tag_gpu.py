@@ -35,11 +35,11 @@ def say(msg):
     print(msg, flush=True)
 
 
-def _pair(mods, E, shape, R=1, H=0, wseed=None, max_ep=synth.MAX_EPISODE_STEPS, **phys):
+def _pair(mods, E, shape, R=1, H=0, wseed=None, max_ep=synth.MAX_EPISODE_STEPS, wd=0, **phys):
     MpeEnv, Oracle = mods
     N, L, A = shape
-    env = MpeEnv(Hp.tag_gpu_config(E, N, L, A, R, H, max_ep=max_ep, **phys))
-    orc = Oracle(Hp.tag_oracle_config(E, N, L, A, R, H, max_ep=max_ep, **phys), threads=8)
+    env = MpeEnv(Hp.tag_gpu_config(E, N, L, A, R, H, max_ep=max_ep, wd=wd, **phys))
+    orc = Oracle(Hp.tag_oracle_config(E, N, L, A, R, H, max_ep=max_ep, wd=wd, **phys), threads=8)
     assert env.D == orc.D == Hp.tag_obs_dim(N, L, A)
     if wseed is not None:
         w = synth.policy_weights_with_bias(wseed, R, env.D, H)
@@ -311,6 +311,19 @@ def test_policy_free_running(mods, shape, E, T):
     env.close()
 
 
+@pytest.mark.parametrize("shape,E,R,T", [((4, 2, 3), 4096, 1, 8), ((4, 2, 3), 200, 1, 30), ((2, 1, 1), 130, 1, 30),
+                                         ((3, 0, 2), 100, 1, 30), ((4, 2, 3), 64, 3, 20)])
+def test_policy_bf16_teacher_forced(mods, shape, E, R, T):
+    """bf16 weights and layer inputs (the oracle's bf16 mode): the rounding points are the same on both
+    sides, a sample flips only when an fp32 value sits on a bf16 rounding boundary."""
+    say("tag fused rollout bf16, forced steps, shape=%s E=%d R=%d T=%d" % (shape, E, R, T))
+    env, orc = _pair(mods, E, shape, R, 64, wseed=13, wd=1)
+    frac, total, worst, n_rew = _forced_rollout_steps(env, orc, shape, 33, T, crowded_seed=700 if E < 1000 else None)
+    say("  bf16 action agreement %.6f over %d samples; worst step error %.2e" % (frac, total, worst))
+    assert frac >= 0.999
+    env.close()
+
+
 def test_policy_per_run_weights(mods):
     say("tag fused rollout, one set of weights per run, R=5 E=64")
     env, orc = _pair(mods, 64, (4, 2, 3), 5, 64, wseed=40)
@@ -324,14 +337,15 @@ def test_policy_per_run_weights(mods):
 
 
 # ------------------------------------------------------------------------------------- plumbing
-@pytest.mark.parametrize("shape,H", [((4, 2, 3), 0), ((4, 2, 3), 64), ((3, 0, 2), 0), ((3, 0, 2), 64), ((6, 2, 4), 0)])
-def test_time_slots_continuation_and_null_outputs(mods, shape, H):
+@pytest.mark.parametrize("shape,H,wd", [((4, 2, 3), 0, 0), ((4, 2, 3), 64, 0), ((3, 0, 2), 0, 0), ((3, 0, 2), 64, 0),
+                                        ((6, 2, 4), 0, 0), ((4, 2, 3), 64, 1), ((2, 1, 1), 64, 1)])
+def test_time_slots_continuation_and_null_outputs(mods, shape, H, wd):
     """One rollout of T steps equals T rollouts of one step bit for bit (across an episode end), a
     rollout continues where the last one stopped, and outputs that are NULL are simply not written."""
     MpeEnv, _ = mods
     N, L, A = shape
     E, T = 100, 28
-    envs = [MpeEnv(Hp.tag_gpu_config(E, N, L, A, 1, H)) for _ in range(3)]
+    envs = [MpeEnv(Hp.tag_gpu_config(E, N, L, A, 1, H, wd=wd)) for _ in range(3)]
     if H:
         w = Hp.to_dev(synth.policy_weights_with_bias(6, 1, envs[0].D, H))
         for e in envs:
