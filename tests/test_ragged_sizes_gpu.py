@@ -1,0 +1,128 @@
+"""Odd batch sizes around the block and wavefront boundaries (1, 2, 63, 65, 127, 129, 193 envs) for
+every rollout kernel family: a few free-running steps against the oracle.  The first steps of an
+episode leave no time for a contact to amplify rounding, so observations are held to the 1e-4 bar
+and actions must agree (exactly for uniform actions and the fp32 policies; bf16 policies may lose a
+sample to a rounding flip)."""
+import numpy as np
+import pytest
+
+from tests import helpers as Hp
+from paper_2311_10090_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+SIZES = [1, 2, 63, 65, 127, 129, 193]
+T = 6
+
+
+def _check(env, orc, seed, exact_actions, min_agree=1.0):
+    env.reset(seed)
+    orc.reset(seed)
+    obs, act, rew, done, last = [x.cpu().numpy() for x in env.rollout(T, *env.empty_traj(T))]
+    robs, ract, rrew, rdone, rlast = orc.rollout(T)
+    assert np.array_equal(done, rdone)
+    same = (act == ract).all(axis=2)
+    alive = np.logical_and.accumulate(same, axis=0)
+    if exact_actions:
+        assert alive.all()
+    else:
+        assert alive[-1].mean() >= min_agree
+    prior = np.vstack([np.ones((1, obs.shape[1]), bool), alive[:-1]])
+    e = np.abs(obs.astype(np.float64) - robs).reshape(T, obs.shape[1], -1).max(axis=2)
+    assert (e * prior).max() <= Hp.EPISODE_ATOL
+    el = np.abs(last.astype(np.float64) - rlast).reshape(obs.shape[1], -1).max(axis=1)
+    assert (el * alive[-1]).max() <= Hp.EPISODE_ATOL
+    r = np.abs(rew - rrew)
+    r = r.max(axis=2) if r.ndim == 3 else r
+    assert (r * alive).max() <= 1e-3
+    # state written back: continue for one more step and the trajectories still agree
+    o2 = env.rollout(1, *env.empty_traj(1))[0].cpu().numpy()
+    ro2 = orc.rollout(1)[0]
+    assert (np.abs(o2[0].astype(np.float64) - ro2[0]).reshape(obs.shape[1], -1).max(axis=1) * alive[-1]).max() <= Hp.EPISODE_ATOL
+    return alive[-1]
+
+
+@pytest.fixture(scope="module")
+def mods():
+    if not torch.cuda.is_available():
+        pytest.fail("gpu tests need a device; the library has no CPU fallback")
+    from paper_2311_10090_amd.binding import MpeEnv
+    from oracle import Oracle
+    return MpeEnv, Oracle
+
+
+@pytest.mark.parametrize("E", SIZES)
+@pytest.mark.parametrize("N,H,wd", [(3, 0, 0), (3, 64, 0), (3, 64, 1), (1, 64, 0), (2, 0, 0), (10, 0, 0), (10, 128, 1)])
+def test_spread_kernels(mods, E, N, H, wd):
+    MpeEnv, Oracle = mods
+    env = MpeEnv(Hp.gpu_config(E, N, 1, H, wd))
+    orc = Oracle(Hp.oracle_config(E, N, 1, H, wd), threads=4)
+    if H:
+        w = synth.policy_weights_with_bias(2, 1, 6 * N, H)
+        env.set_policy(*Hp.to_dev(w))
+        orc.set_policy(*w)
+    _check(env, orc, 5 + E, exact_actions=(wd == 0), min_agree=0.97)
+    env.close()
+
+
+@pytest.mark.parametrize("E", SIZES)
+@pytest.mark.parametrize("mode", ["mixed", "actor_critic"])
+def test_spread_variants(mods, E, mode):
+    MpeEnv, Oracle = mods
+    rm = 1 if mode == "mixed" else 0
+    env = MpeEnv(Hp.gpu_config(E, 3, 1, 64, 0, reward_mode=rm))
+    orc = Oracle(Hp.oracle_config(E, 3, 1, 64, 0, reward_mode=rm), threads=4)
+    w = synth.policy_weights_with_bias(4, 1, 18, 64)
+    env.set_policy(*Hp.to_dev(w))
+    orc.set_policy(*w)
+    if mode == "mixed":
+        _check(env, orc, 9 + E, exact_actions=True)
+    else:
+        c = synth.critic_weights(4, 1, 18, 64)
+        env.set_critic(*Hp.to_dev(c))
+        orc.set_critic(*c)
+        env.reset(3)
+        orc.reset(3)
+        out = [x.cpu().numpy() for x in env.rollout_ac(T, *env.empty_traj_ac(T))]
+        ref = orc.rollout_ac(T)
+        assert np.array_equal(out[1], ref[1]) and np.array_equal(out[5], ref[5])
+        assert np.abs(out[2] - ref[2]).max() < 1e-4 and np.abs(out[3] - ref[3]).max() < 1e-4
+        assert np.abs(out[7] - ref[7]).max() < 1e-4
+    env.close()
+
+
+@pytest.mark.parametrize("E", SIZES)
+@pytest.mark.parametrize("shape,H,wd", [((4, 2, 3), 0, 0), ((4, 2, 3), 64, 0), ((4, 2, 3), 64, 1), ((3, 0, 2), 64, 0),
+                                        ((2, 1, 1), 0, 0), ((6, 2, 4), 0, 0)])
+def test_tag_kernels(mods, E, shape, H, wd):
+    MpeEnv, Oracle = mods
+    N, L, A = shape
+    env = MpeEnv(Hp.tag_gpu_config(E, N, L, A, 1, H, wd=wd))
+    orc = Oracle(Hp.tag_oracle_config(E, N, L, A, 1, H, wd=wd), threads=4)
+    if H:
+        w = synth.policy_weights_with_bias(2, 1, env.D, H)
+        env.set_policy(*Hp.to_dev(w))
+        orc.set_policy(*w)
+    _check(env, orc, 7 + E, exact_actions=(wd == 0), min_agree=0.97)
+    env.close()
+
+
+@pytest.mark.parametrize("E", SIZES)
+@pytest.mark.parametrize("N", [1, 2, 3])
+def test_recurrent_kernel(mods, E, N):
+    MpeEnv, Oracle = mods
+    env = MpeEnv(Hp.gpu_config(E, N, 1, 128, 1))
+    orc = Oracle(Hp.oracle_config(E, N, 1, 128, 1), threads=4)
+    w = synth.gru_weights(6, 1, 6 * N)
+    env.set_gru_policy(*Hp.to_dev(w))
+    orc.set_gru(*w)
+    ok = _check(env, orc, 11 + E, exact_actions=False, min_agree=0.95)
+    # free-running: rounding flips of earlier steps have spread through the recurrence, so this only
+    # guards against gross errors (a wrong row, unit or gate would be O(0.1..1)); envs whose actions
+    # have diverged are on another trajectory and are left out
+    h, rh = env.get_hidden().cpu().numpy().astype(np.float64), orc.get_hidden()
+    d = np.abs(h - rh)[ok]
+    assert d.size and np.median(d) < 2e-3 and d.max() < 5e-2
+    env.close()
