@@ -52,5 +52,19 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+def build_probe() -> str:
+    """Compile the stand-alone matrix/vector overlap probe (csrc/coexec_probe.hip)."""
+    out = os.path.join(HERE, "coexec_probe")
+    r = subprocess.run([_hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wno-unused-result", "-Xclang",
+                        "-target-feature", "-Xclang", "-packed-fp32-ops", os.path.join(CSRC, "coexec_probe.hip"),
+                        "-o", out], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed for coexec_probe.hip:\n" + r.stderr)
+    return out
+
+
 if __name__ == "__main__":
-    print(build(force=True, verbose=True))
+    if "--probe" in sys.argv:
+        print(build_probe())
+    else:
+        print(build(force=True, verbose=True))
