@@ -182,7 +182,9 @@ int mpe_rollout(mpe_env* env, int32_t T, float* obs_traj, uint8_t* act_traj, flo
  * matrices and every vector that enters a matrix product (obs, e, h, y) are rounded to bf16 (ties
  * to even); sums, biases, gate arithmetic and the carried h are fp32.  While installed it takes
  * precedence over the policy of mpe_set_policy.  h is owned by the handle, cleared by mpe_reset and
- * wherever an episode ends, carried across mpe_rollout calls, untouched by mpe_set_state.
+ * wherever an episode ends inside mpe_rollout, carried across mpe_rollout calls, untouched by
+ * mpe_set_state and by mpe_step (which takes its actions from the caller and neither advances nor
+ * clears h: a caller that mixes the two sets h itself with mpe_set_hidden).
  * Built for MPE_SCENARIO_SPREAD, 1..3 agents, hidden 128, MPE_WEIGHTS_BF16, num_runs 1; MPE_EINVAL
  * otherwise or if only some pointers are NULL. */
 int mpe_set_gru_policy(mpe_env* env, const float* We, const float* be, const float* Wi, const float* bi,
