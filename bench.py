@@ -286,7 +286,7 @@ def main():
             "frac": tflops / (MFMA_FP32_PEAK_TFLOPS if wl.weight_dtype == 0 else 2500.0),
             "traffic": None,
             "algorithmic_bytes": bytes_per_env_step(N, D) * TE * T,
-            "kernel_ms_avg": kavg, "kernel_ms_min": float(np.min(kern_ms)),
+            "kernel_ms_avg": kavg, "kernel_ms_min": float(np.min(kern_ms)), "kernel_ms_median": float(np.median(kern_ms)),
             "flop_per_agent_step": flops_per_agent_step(D, H),
             "hbm_achieved_GBs": fused_gbs,
             # what the matrix cores really execute: matrix instructions per 64 agent rows and step
@@ -306,6 +306,7 @@ def main():
             "roofline": {"bound": "hbm", "achieved": env_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": env_gbs / HBM_PEAK_GBS, "traffic": None,
                          "kernel_ms_avg": k2avg, "kernel_ms_min": float(np.min(kern2)),
+                         "kernel_ms_median": float(np.median(kern2)),
                          "bytes_per_env_step": bytes_per_env_step(N, D),
                          "algorithmic_bytes": bytes_per_env_step(N, D) * TE * T},
         },
