@@ -416,3 +416,77 @@ def test_scenario_arguments_are_validated():
         with pytest.raises(RuntimeError):
             make(**bad)
     make(L=0)      # no obstacles is allowed
+
+
+# ------------------------------------------------------------------ symmetries, numpy re-derivation
+def _crowded(seed, E, N, L):
+    g = np.random.Generator(np.random.PCG64(seed))
+    centre = g.uniform(-0.9, 0.9, (E, 1, 2))
+    return (centre + g.uniform(-0.2, 0.2, (E, N, 2)), g.uniform(-1.6, 1.6, (E, N, 2)),
+            centre + g.uniform(-0.3, 0.3, (E, L, 2)))
+
+
+def test_rotated_world_matches_relabelled_actions():
+    # a quarter turn of the whole world with the actions relabelled accordingly commutes with a step
+    # (contacts, obstacles, speed limit and the boundary penalty are all symmetric under it)
+    E, N, L, A = 40, 5, 2, 3
+    pa, va, pl = _crowded(3, E, N, L)
+    acts = np.random.default_rng(2).integers(0, 5, (E, N)).astype(np.uint8)
+    relabel = np.array([0, 3, 4, 2, 1], np.uint8)  # -x -> -y, +x -> +y, -y -> +x, +y -> -x
+    rot = lambda p: np.stack([-p[..., 1], p[..., 0]], axis=-1)
+    o1, o2 = make(N=N, A=A, L=L, E=E), make(N=N, A=A, L=L, E=E)
+    put(o1, pa, va, pl)
+    put(o2, rot(pa), rot(va), rot(pl))
+    ob1, r1, _ = o1.step(acts)
+    ob2, r2, _ = o2.step(relabel[acts])
+    np.testing.assert_allclose(r2, r1, rtol=0, atol=1e-12)
+    assert (r1[:, 0] > 0).any() and (np.abs(r1[:, A:] % 10) > 1e-6).any()      # catches and penalties occur
+    np.testing.assert_allclose(o2.get_state()[0], rot(o1.get_state()[0]), rtol=0, atol=1e-13)
+    np.testing.assert_allclose(o2.get_state()[1], rot(o1.get_state()[1]), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(ob2.reshape(E, N, -1, 2), rot(ob1.reshape(E, N, -1, 2)), rtol=0, atol=1e-12)
+
+
+def test_relabelling_agents_within_a_role_permutes_the_outcome():
+    E, N, L, A = 30, 6, 2, 4
+    pa, va, pl = _crowded(5, E, N, L)
+    acts = np.random.default_rng(4).integers(0, 5, (E, N)).astype(np.uint8)
+    perm = np.array([2, 0, 3, 1, 5, 4])           # adversaries among themselves, good agents among themselves
+    o1, o2 = make(N=N, A=A, L=L, E=E), make(N=N, A=A, L=L, E=E)
+    put(o1, pa, va, pl)
+    put(o2, pa[:, perm], va[:, perm], pl[:, ::-1])
+    _, r1, _ = o1.step(acts)
+    _, r2, _ = o2.step(acts[:, perm])
+    np.testing.assert_allclose(r2, r1[:, perm], rtol=0, atol=1e-12)
+    np.testing.assert_allclose(o2.get_state()[0], o1.get_state()[0][:, perm], rtol=0, atol=1e-12)
+    np.testing.assert_allclose(o2.get_state()[1], o1.get_state()[1][:, perm], rtol=0, atol=1e-11)
+
+
+def test_step_matches_vectorised_numpy_rederivation():
+    # every agent sums the force from every other agent and every obstacle; clip; numpy only
+    E, N, L, A = 64, 6, 2, 4
+    pa, va, pl = _crowded(7, E, N, L)
+    acts = np.random.default_rng(6).integers(0, 5, (E, N)).astype(np.uint8)
+    o = make(N=N, A=A, L=L, E=E)
+    put(o, pa, va, pl)
+    o.step(acts)
+    radius = np.array([ADV_R] * A + [GOOD_R] * (N - A))
+    gain = np.array([ADV_GAIN] * A + [GOOD_GAIN] * (N - A))
+    limit = np.array([ADV_LIMIT] * A + [GOOD_LIMIT] * (N - A))
+    dirs = np.array([[0, 0], [-1, 0], [1, 0], [0, -1], [0, 1]], float)
+    F = gain[None, :, None] * dirs[acts]
+
+    def push(delta, dmin):
+        d = np.linalg.norm(delta, axis=-1)
+        pen = 1e-3 * np.logaddexp(0.0, (dmin - d) / 1e-3)
+        return 100.0 * pen[..., None] * delta / np.maximum(d, 1e-12)[..., None]
+
+    aa = push(pa[:, :, None, :] - pa[:, None, :, :], radius[:, None] + radius[None, :])
+    aa[:, np.arange(N), np.arange(N)] = 0
+    al = push(pa[:, :, None, :] - pl[:, None, :, :], (radius + LM_R)[None, :, None])
+    F = F + aa.sum(axis=2) + al.sum(axis=2)
+    v = 0.75 * va + 0.1 * F
+    speed = np.linalg.norm(v, axis=-1)
+    v = v * np.where(speed > limit, limit / speed, 1.0)[..., None]
+    np.testing.assert_allclose(o.get_state()[0], pa + 0.1 * va, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(o.get_state()[1], v, rtol=1e-12, atol=1e-11)
+    assert (np.abs(al).max(axis=(1, 2, 3)) > 1).mean() > 0.3 and (speed > limit).mean() > 0.2
