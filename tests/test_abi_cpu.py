@@ -105,3 +105,83 @@ def test_product_package_does_not_import_the_oracle():
                 src = open(os.path.join(dirpath, f)).read()
                 assert not re.search(r"^\s*(from|import)\s+oracle", src, flags=re.M), f
                 assert "liboracle" not in src and "orc_" not in src, f
+
+
+def _expected_valid(c):
+    """The validity rules of include/mpe.h, restated from the header's text."""
+    import math
+    fin = math.isfinite
+    if c["num_envs"] < 1 or c["num_runs"] < 1 or not (1 <= c["num_agents"] <= 10):
+        return False
+    if c["scenario"] not in (0, 1):
+        return False
+    if c["scenario"] == 0 and c["num_landmarks"] != c["num_agents"]:
+        return False
+    if c["scenario"] == 1:
+        if not (1 <= c["num_adversaries"] < c["num_agents"]):
+            return False
+        shape = (c["num_agents"], c["num_landmarks"], c["num_agents"] - c["num_adversaries"])
+        if shape not in ((4, 2, 1), (2, 1, 1), (3, 0, 1), (6, 2, 2)):
+            return False
+        if not (fin(c["adv_radius"]) and c["adv_radius"] >= 0 and fin(c["adv_accel"])):
+            return False
+        if not (fin(c["adv_max_speed"]) and c["adv_max_speed"] > 0 and fin(c["good_max_speed"]) and c["good_max_speed"] > 0):
+            return False
+    if c["num_envs"] * c["num_runs"] > 2 ** 30 or c["max_episode_steps"] < 1:
+        return False
+    for k in ("dt", "mass", "contact_margin"):
+        if not (fin(c[k]) and c[k] > 0):
+            return False
+    if not (fin(c["damping"]) and 0 <= c["damping"] <= 1):
+        return False
+    for k in ("accel", "contact_force", "agent_radius", "landmark_radius"):
+        if not fin(c[k]):
+            return False
+    if c["agent_radius"] < 0 or c["landmark_radius"] < 0:
+        return False
+    if c["hidden"] not in (0, 64, 128) or c["weight_dtype"] not in (0, 1) or c["reward_mode"] not in (0, 1):
+        return False
+    if c["reward_mode"] == 1 and not (fin(c["local_ratio"]) and 0 <= c["local_ratio"] <= 1):
+        return False
+    return True
+
+
+def test_random_configs_are_accepted_or_refused_as_the_header_says(lib):
+    import torch
+    from hypothesis import given, settings, strategies as st
+    if torch.cuda.is_available():
+        pytest.skip("valid configs would allocate device memory; the host rules are checked without a device")
+    small = st.integers(-1, 12)
+    fl = st.one_of(st.floats(-1.0, 2.0, width=32), st.sampled_from([float("nan"), float("inf"), 0.0, 1.0, 0.1]))
+    wild = dict(
+        num_envs=st.sampled_from([0, 1, 64, 1 << 20]), num_agents=small, num_landmarks=small,
+        num_runs=st.sampled_from([0, 1, 3, 1 << 11]), max_episode_steps=st.sampled_from([0, 1, 25]),
+        dt=fl, damping=fl, mass=fl, accel=fl, agent_radius=fl, landmark_radius=fl, contact_force=fl, contact_margin=fl,
+        hidden=st.sampled_from([0, 32, 64, 128]), weight_dtype=st.sampled_from([0, 1, 2]),
+        reward_mode=st.sampled_from([0, 1, 2]), local_ratio=fl, scenario=st.sampled_from([0, 1, 2]),
+        num_adversaries=small, adv_radius=fl, adv_accel=fl, adv_max_speed=fl, good_max_speed=fl)
+    bases = [dict(), dict(scenario=1, num_agents=4, num_landmarks=2, num_adversaries=3),
+             dict(scenario=1, num_agents=6, num_landmarks=2, num_adversaries=4), dict(num_agents=10, num_landmarks=10),
+             dict(reward_mode=1, local_ratio=0.25)]
+    # a valid base config with zero to three fields replaced by arbitrary values
+    cfgs = st.tuples(st.sampled_from(bases),
+                     st.lists(st.sampled_from(sorted(wild)), min_size=0, max_size=3, unique=True).flatmap(
+                         lambda ks: st.fixed_dictionaries({k: wild[k] for k in ks})))
+
+    seen = {True: 0, False: 0}
+
+    @settings(max_examples=600, deadline=None, derandomize=True)
+    @given(cfgs)
+    def check(pair):
+        c = dict(pair[0])
+        c.update(pair[1])
+        cc = MpeConfig(**c).to_c()
+        h = C.c_void_p()
+        rc = lib.mpe_create(C.byref(cc), C.byref(h))
+        valid = _expected_valid({k: getattr(cc, k) for k, _ in binding._CConfig._fields_})
+        seen[valid] += 1
+        assert rc == (MPE_EHIP if valid else MPE_EINVAL), (c, lib.mpe_last_error())
+        assert h.value is None
+
+    check()
+    assert seen[True] > 20 and seen[False] > 100
