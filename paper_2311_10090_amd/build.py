@@ -52,15 +52,22 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
-def build_probe() -> str:
-    """Compile the stand-alone matrix/vector overlap probe (csrc/coexec_probe.hip)."""
-    out = os.path.join(HERE, "coexec_probe")
-    r = subprocess.run([_hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wno-unused-result", "-Xclang",
-                        "-target-feature", "-Xclang", "-packed-fp32-ops", os.path.join(CSRC, "coexec_probe.hip"),
-                        "-o", out], capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("hipcc failed for coexec_probe.hip:\n" + r.stderr)
-    return out
+PROBES = ["coexec_probe", "store_pattern_probe"]
+
+
+def build_probe() -> list:
+    """Compile the stand-alone probes (csrc/coexec_probe.hip: matrix/vector overlap;
+    csrc/store_pattern_probe.hip: HBM write rate by store pattern)."""
+    outs = []
+    for name in PROBES:
+        out = os.path.join(HERE, name)
+        r = subprocess.run([_hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wno-unused-result", "-Xclang",
+                            "-target-feature", "-Xclang", "-packed-fp32-ops", os.path.join(CSRC, name + ".hip"),
+                            "-o", out], capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc failed for %s.hip:\n%s" % (name, r.stderr))
+        outs.append(out)
+    return outs
 
 
 if __name__ == "__main__":
