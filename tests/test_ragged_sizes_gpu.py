@@ -1,4 +1,4 @@
-"""Odd batch sizes around the block and wavefront boundaries (1, 2, 63, 65, 127, 129, 193 envs) for
+"""Batch sizes at and around the block and wavefront boundaries (1, 2, 63, 65, 127, 128, 129, 192, 193 envs) for
 every rollout kernel family: a few free-running steps against the oracle.  The first steps of an
 episode leave no time for a contact to amplify rounding, so observations are held to the 1e-4 bar
 and actions must agree (exactly for uniform actions and the fp32 policies; bf16 policies may lose a
@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
 
-SIZES = [1, 2, 63, 65, 127, 129, 193]
+SIZES = [1, 2, 63, 65, 127, 128, 129, 192, 193]
 T = 6
 
 

@@ -339,12 +339,13 @@ def test_policy_per_run_weights(mods):
 # ------------------------------------------------------------------------------------- plumbing
 @pytest.mark.parametrize("shape,H,wd", [((4, 2, 3), 0, 0), ((4, 2, 3), 64, 0), ((3, 0, 2), 0, 0), ((3, 0, 2), 64, 0),
                                         ((6, 2, 4), 0, 0), ((4, 2, 3), 64, 1), ((2, 1, 1), 64, 1)])
-def test_time_slots_continuation_and_null_outputs(mods, shape, H, wd):
+@pytest.mark.parametrize("E", [100, 128])   # 128: whole blocks, the env-only variant with a writer wavefront
+def test_time_slots_continuation_and_null_outputs(mods, shape, H, wd, E):
     """One rollout of T steps equals T rollouts of one step bit for bit (across an episode end), a
     rollout continues where the last one stopped, and outputs that are NULL are simply not written."""
     MpeEnv, _ = mods
     N, L, A = shape
-    E, T = 100, 28
+    T = 28
     envs = [MpeEnv(Hp.tag_gpu_config(E, N, L, A, 1, H, wd=wd)) for _ in range(3)]
     if H:
         w = Hp.to_dev(synth.policy_weights_with_bias(6, 1, envs[0].D, H))
