@@ -251,7 +251,8 @@ def _teacher_forced(env, orc, seed, T):
     return agree / total, total, worst
 
 
-@pytest.mark.parametrize("E,N,T", [(4096, 3, 30), (200, 3, 60), (64, 1, 30), (100, 2, 30)])
+# 65,536 envs: the launch configuration of the headline measurement (256-env blocks), 4.9 million samples
+@pytest.mark.parametrize("E,N,T", [(4096, 3, 30), (200, 3, 60), (64, 1, 30), (100, 2, 30), (65536, 3, 25)])
 def test_policy_actions_teacher_forced_fp32(mods, E, N, T):
     say("policy teacher-forced E=%d N=%d T=%d" % (E, N, T))
     env, orc = _policy_pair(mods, E, N, 1, 64, 0, wseed=3)
