@@ -289,14 +289,18 @@ __global__ __launch_bounds__(64 * S::N, (MODE == kPolicy || MODE == kPolicyBf) ?
     // pre-step positions, position with the old velocity, damped velocity, speed limit
     float fx = my_gain * action_dir_x(act);
     float fy = my_gain * action_dir_y(act);
+    // the k-th OTHER agent is agent k (k < i) or k + 1: N - 1 evaluations with selected operands, in
+    // ascending agent order (a loop over all agents that skips a == i runs N masked evaluations)
 #pragma unroll
-    for (int a = 0; a < N; ++a) {
-      if (a != i) {
-        const float dx = px - qx[a], dy = py - qy[a];
-        const float k = tag_contact(dx, dy, my_radius + tg.radius[a < NA ? 0 : 1], tg);
-        fx = fmaf(k, dx, fx);
-        fy = fmaf(k, dy, fy);
-      }
+    for (int k = 0; k < N - 1; ++k) {
+      const bool up = k >= i;
+      const float ox = up ? qx[k + 1] : qx[k], oy = up ? qy[k + 1] : qy[k];
+      const float r_lo = tg.radius[k < NA ? 0 : 1], r_hi = tg.radius[k + 1 < NA ? 0 : 1];
+      const float orad = ((k < NA) == (k + 1 < NA)) ? r_lo : (up ? r_hi : r_lo);
+      const float dx = px - ox, dy = py - oy;
+      const float kf = tag_contact(dx, dy, my_radius + orad, tg);
+      fx = fmaf(kf, dx, fx);
+      fy = fmaf(kf, dy, fy);
     }
 #pragma unroll
     for (int l = 0; l < L; ++l) {
