@@ -12,6 +12,7 @@
 namespace mpe {
 
 typedef float v4f __attribute__((ext_vector_type(4)));  // native 16-byte vector (stays in VGPRs)
+typedef float v2f __attribute__((ext_vector_type(2)));  // native 8-byte vector
 
 constexpr int kWave = 64;          // CDNA wavefront
 constexpr int kNumActions = 5;
@@ -292,17 +293,22 @@ __device__ __forceinline__ void build_agent_obs(const Env<N>& s, int i, float2* 
 
 // Stream `nfloats` (even) contiguous floats from the LDS tile to dst.  vec4 requires dst to
 // be 16-byte aligned; otherwise 8-byte stores are used.  Generic (ragged) version.
+// The stores are nontemporal: a wavefront's store covers whole cache lines that nothing reads
+// again, and streaming them past the L2 leaves room there for the partial lines of the small
+// outputs (actions, rewards, done flags) until their neighbours complete them (measured: 8-15 %
+// on the HBM-bound rollouts; per-lane row stores at a stride are NOT made nontemporal, that
+// is several times slower).
 __device__ __forceinline__ void stream_out(const float* tile, float* dst, int nfloats, bool vec4, int lane) {
   if (vec4) {
     const int n4 = nfloats >> 2;
     for (int j = lane; j < n4; j += kWave)
-      reinterpret_cast<float4*>(dst)[j] = reinterpret_cast<const float4*>(tile)[j];
+      __builtin_nontemporal_store(reinterpret_cast<const v4f*>(tile)[j], reinterpret_cast<v4f*>(dst) + j);
     if ((nfloats & 2) && lane == 0)
-      reinterpret_cast<float2*>(dst)[nfloats / 2 - 1] = reinterpret_cast<const float2*>(tile)[nfloats / 2 - 1];
+      __builtin_nontemporal_store(reinterpret_cast<const v2f*>(tile)[nfloats / 2 - 1], reinterpret_cast<v2f*>(dst) + (nfloats / 2 - 1));
   } else {
     const int n2 = nfloats >> 1;
     for (int j = lane; j < n2; j += kWave)
-      reinterpret_cast<float2*>(dst)[j] = reinterpret_cast<const float2*>(tile)[j];
+      __builtin_nontemporal_store(reinterpret_cast<const v2f*>(tile)[j], reinterpret_cast<v2f*>(dst) + j);
   }
 }
 
@@ -320,8 +326,8 @@ __device__ __forceinline__ void stream_out_full(const float* tile, float* dst, i
   for (int k = 0; k < kFullIters; ++k) v[k] = src4[k * kWave];
   if (kTail > 0 && lane < kTail) vt = src4[kFullIters * kWave];
 #pragma unroll
-  for (int k = 0; k < kFullIters; ++k) dst4[k * kWave] = v[k];
-  if (kTail > 0 && lane < kTail) dst4[kFullIters * kWave] = vt;
+  for (int k = 0; k < kFullIters; ++k) __builtin_nontemporal_store(v[k], &dst4[k * kWave]);
+  if (kTail > 0 && lane < kTail) __builtin_nontemporal_store(vt, &dst4[kFullIters * kWave]);
 }
 
 // Write the observations of the wave's nvalid envs to dst_wave, which points at the row of the

@@ -251,7 +251,7 @@ __global__ __launch_bounds__(2 * kWave) void rollout_uniform_ws_kernel(RolloutAr
       if (t > 0) {
         if (obs_g) {
 #pragma unroll
-          for (int k = 0; k < SB::FULL; ++k) *reinterpret_cast<v4f*>(obs_g + k * (kWave * 16)) = v[k];
+          for (int k = 0; k < SB::FULL; ++k) __builtin_nontemporal_store(v[k], reinterpret_cast<v4f*>(obs_g + k * (kWave * 16)));
           obs_g += obs_stride;
         }
         if (mix_lds >= 0) {

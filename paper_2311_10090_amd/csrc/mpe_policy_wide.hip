@@ -388,7 +388,7 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
         v4f* d4 = reinterpret_cast<v4f*>(dst) + c * (16 * RF4);
 #pragma unroll
         for (int rd = 0; rd < kRounds; ++rd)
-          if (rd * 64 + lane < n4) d4[rd * 64 + lane] = v[rd];
+          if (rd * 64 + lane < n4) __builtin_nontemporal_store(v[rd], &d4[rd * 64 + lane]);
       }
       wave_sync();
     } else if (lane < wave_rows) {
