@@ -9,9 +9,14 @@
 //   short   - many short-lived 256-thread blocks, 16 bytes per thread (what library fills do)
 //   blocked - like sweep, but each wavefront owns R consecutive KiB of the window per iteration
 //   rollout - persistent groups, one contiguous chunk per group and time slice (the rollout's pattern),
-//             with the real 54-float rows (obs only) and with rows padded to 64 floats
+//             with the real 54-float rows (obs only) and with rows padded to 64 floats, plain and
+//             nontemporal stores
+//   small   - the rollout's pattern with 64-byte rows plus the small outputs of every step (4-byte reward
+//             and 1-byte action per row, 1-byte done flag per 4 rows) written per lane: what the small
+//             partial-line outputs cost, and what nontemporal row stores change about it
 // Build: python -m paper_2311_10090_amd.build --probe ; run: paper_2311_10090_amd/store_pattern_probe
 #include <hip/hip_runtime.h>
+#include <cstdint>
 #include <cstdio>
 
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -36,12 +41,38 @@ __global__ void blocked_kernel(v4f* out, size_t n16, int R) {
 }
 
 // block g owns [g*chunk16, (g+1)*chunk16) of each of T slices
+template <bool NT>
 __global__ void rollout_kernel(v4f* out, int chunk16, size_t slice16, int T) {
   v4f v = {1.f, 2.f, 3.f, (float)blockIdx.x};
   v4f* p = out + (size_t)blockIdx.x * chunk16;
   for (int t = 0; t < T; ++t) {
-    for (int j = threadIdx.x; j < chunk16; j += blockDim.x) p[j] = v;
+    for (int j = threadIdx.x; j < chunk16; j += blockDim.x) {
+      if (NT) __builtin_nontemporal_store(v, &p[j]); else p[j] = v;
+    }
     p += slice16;
+  }
+}
+
+// 256-thread blocks; wavefront w of block b owns rows [(4b + w) * 64, +64) of each slice: 64 bytes of
+// observation per row, and with SMALL a 4-byte reward and a 1-byte action per row and a 1-byte done flag
+// per 4 rows, each in an array of its own.  `rows` must be gridDim.x * 256.
+template <bool SMALL, bool NT>
+__global__ __launch_bounds__(256) void small_outputs_kernel(v4f* obs, float* rew, uint8_t* act, uint8_t* done,
+                                                             size_t rows, int T) {
+  const int lane = threadIdx.x & 63;
+  const size_t row0 = ((size_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 64;
+  v4f v = {1.f, 2.f, 3.f, (float)blockIdx.x};
+  for (int t = 0; t < T; ++t) {
+    v4f* o = obs + ((size_t)t * rows + row0) * 4;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (NT) __builtin_nontemporal_store(v, &o[k * 64 + lane]); else o[k * 64 + lane] = v;
+    }
+    if (SMALL) {
+      rew[(size_t)t * rows + row0 + lane] = v.x;
+      act[(size_t)t * rows + row0 + lane] = (uint8_t)lane;
+      if ((lane & 3) == 0) done[(size_t)t * (rows / 4) + row0 / 4 + lane / 4] = 0;
+    }
   }
 }
 
@@ -80,10 +111,21 @@ int main() {
   }
   for (int thr : {64, 128}) {
     snprintf(nm, sizeof nm, "rollout, 1024 groups x %d threads, 54-float rows", thr);
-    run(nm, n54, [&] { hipLaunchKernelGGL(rollout_kernel, dim3(1024), dim3(thr), 0, 0, buf, (int)(slice54 / 1024), slice54, T); });
+    run(nm, n54, [&] { hipLaunchKernelGGL(rollout_kernel<false>, dim3(1024), dim3(thr), 0, 0, buf, (int)(slice54 / 1024), slice54, T); });
   }
-  run("rollout, 256 groups x 256 threads, 54-float rows", n54, [&] { hipLaunchKernelGGL(rollout_kernel, dim3(256), dim3(256), 0, 0, buf, (int)(slice54 / 256), slice54, T); });
-  run("rollout, 1024 groups x 64 threads, 64-float rows", n64, [&] { hipLaunchKernelGGL(rollout_kernel, dim3(1024), dim3(64), 0, 0, buf, (int)(slice64 / 1024), slice64, T); });
-  (void)hipFree(buf);
+  run("rollout, 256 groups x 256 threads, 54-float rows", n54, [&] { hipLaunchKernelGGL(rollout_kernel<false>, dim3(256), dim3(256), 0, 0, buf, (int)(slice54 / 256), slice54, T); });
+  run("rollout, 1024 groups x 64 threads, 64-float rows", n64, [&] { hipLaunchKernelGGL(rollout_kernel<false>, dim3(1024), dim3(64), 0, 0, buf, (int)(slice64 / 1024), slice64, T); });
+  run("rollout, 1024 x 64, 54-float rows, nontemporal", n54, [&] { hipLaunchKernelGGL(rollout_kernel<true>, dim3(1024), dim3(64), 0, 0, buf, (int)(slice54 / 1024), slice54, T); });
+  run("rollout, 1024 x 64, 64-float rows, nontemporal", n64, [&] { hipLaunchKernelGGL(rollout_kernel<true>, dim3(1024), dim3(64), 0, 0, buf, (int)(slice64 / 1024), slice64, T); });
+  // small outputs: 262,144 rows x 128 slices; the GB/s column counts the 64-byte rows only
+  const size_t rows = (size_t)1024 * 256, nrow16 = rows * 4 * T;
+  float* rew = nullptr; uint8_t *act = nullptr, *done = nullptr;
+  if (hipMalloc(&rew, rows * 4 * T) != hipSuccess || hipMalloc(&act, rows * T) != hipSuccess ||
+      hipMalloc(&done, rows / 4 * T) != hipSuccess) { printf("allocation failed\n"); return 1; }
+  run("small: rows only", nrow16, [&] { hipLaunchKernelGGL((small_outputs_kernel<false, false>), dim3(1024), dim3(256), 0, 0, buf, rew, act, done, rows, T); });
+  run("small: rows + small outputs", nrow16, [&] { hipLaunchKernelGGL((small_outputs_kernel<true, false>), dim3(1024), dim3(256), 0, 0, buf, rew, act, done, rows, T); });
+  run("small: nontemporal rows only", nrow16, [&] { hipLaunchKernelGGL((small_outputs_kernel<false, true>), dim3(1024), dim3(256), 0, 0, buf, rew, act, done, rows, T); });
+  run("small: nontemporal rows + small outputs", nrow16, [&] { hipLaunchKernelGGL((small_outputs_kernel<true, true>), dim3(1024), dim3(256), 0, 0, buf, rew, act, done, rows, T); });
+  (void)hipFree(buf); (void)hipFree(rew); (void)hipFree(act); (void)hipFree(done);
   return ok ? 0 : 1;
 }
