@@ -581,6 +581,37 @@ def test_gumbel_uses_documented_words_and_transform():
         assert gumbel_max_action(8, 3, env, 12, 1, z) == int(np.argmax(v))
 
 
+def test_gumbel_uniform_is_the_odd_24_bit_grid_and_ties_go_to_the_lowest_index():
+    """The +1 of u = (2 (w >> 9) + 1) 2^-24 (u never 0) moves g = -ln(-ln u) most where u is small:
+    take the sample with the smallest u among 20,000 envs and set a second logit so that the two
+    candidates differ by a fifth of what dropping the +1 would change.  Ties: with every logit
+    at -inf all candidates are equal and the first index wins."""
+    best = None
+    for env in range(20000):
+        w0 = philox4x32_10([env, 3, 0, 2], [5, 0])
+        u0 = (2 * (int(w0[0]) >> 9) + 1) / 2.0**24
+        if best is None or u0 < best[1]:
+            best = (env, u0, [int(x) for x in w0], int(philox4x32_10([env, 3, 0, 3], [5, 0])[0]))
+    env, u0, w0, w4 = best
+    assert u0 < 2e-4
+    g = lambda u: -math.log(-math.log(u))
+    effect = g(u0) - g(u0 - 2.0**-24)                    # what the missing +1 would cost candidate 0
+    assert effect > 1e-5
+    u1 = (2 * (w0[1] >> 9) + 1) / 2.0**24
+    for sign in (+1.0, -1.0):
+        # candidate 1 sits effect/5 below (above) candidate 0; all others are far below
+        z = np.array([0.0, g(u0) - g(u1) - sign * effect / 5.0, -60.0, -60.0, -60.0])
+        assert gumbel_max_action(5, 0, env, 3, 0, z) == (0 if sign > 0 else 1)
+    # ... and with candidate 1 only effect/5 ABOVE, an implementation without the +1 would pick 1 -> 0 flips
+    z = np.array([0.0, g(u0) - g(u1) + 0.6 * effect, -60.0, -60.0, -60.0])
+    assert gumbel_max_action(5, 0, env, 3, 0, z) == 1
+    z = np.array([0.0, g(u0) - g(u1) - 0.6 * effect, -60.0, -60.0, -60.0])
+    assert gumbel_max_action(5, 0, env, 3, 0, z) == 0
+    ninf = -float("inf")
+    assert gumbel_max_action(1, 0, 0, 0, 0, np.full(5, ninf)) == 0
+    assert gumbel_max_action(1, 0, 0, 0, 0, np.array([ninf, ninf, 3.0, ninf, ninf])) == 2
+
+
 def test_policy_rollout_actions_are_sampler_of_logits_of_recorded_obs():
     from paper_2311_10090_amd.synth import policy_weights_with_bias
     E, N, T, H = 5, 3, 30, 64
