@@ -282,15 +282,16 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
     // ---- transition of this lane's agent
     float fx = A.ph.accel * action_dir_x(act);
     float fy = A.ph.accel * action_dir_y(act);
+    // the k-th OTHER agent is agent k (k < i) or k + 1: N - 1 evaluations on selected operands, in
+    // ascending agent order (a loop over all agents that skips a == i runs N masked evaluations)
 #pragma unroll
-    for (int a = 0; a < N; ++a) {
-      if (a != i) {
-        const float dx = px - qx[a];
-        const float dy = py - qy[a];
-        const float k = contact_factor(dx, dy, A.ph);
-        fx = fmaf(k, dx, fx);
-        fy = fmaf(k, dy, fy);
-      }
+    for (int k = 0; k < N - 1; ++k) {
+      const bool up = k >= i;
+      const float dx = px - (up ? qx[k + 1] : qx[k]);
+      const float dy = py - (up ? qy[k + 1] : qy[k]);
+      const float kf = contact_factor(dx, dy, A.ph);
+      fx = fmaf(kf, dx, fx);
+      fy = fmaf(kf, dy, fy);
     }
     px = fmaf(vx, A.ph.dt, px);
     py = fmaf(vy, A.ph.dt, py);

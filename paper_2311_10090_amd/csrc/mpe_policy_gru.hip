@@ -362,14 +362,15 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
       if (act_base && valid) act_base[row_off] = uint8_t(act);
       float fx = A.ph.accel * action_dir_x(act);
       float fy = A.ph.accel * action_dir_y(act);
+      // the k-th OTHER agent is agent k (k < i) or k + 1: N - 1 evaluations, ascending agent order
 #pragma unroll
-      for (int a = 0; a < N; ++a) {
-        if (a != i) {
-          const float dx = px - qx[a], dy = py - qy[a];
-          const float k = contact_factor(dx, dy, A.ph);
-          fx = fmaf(k, dx, fx);
-          fy = fmaf(k, dy, fy);
-        }
+      for (int k = 0; k < N - 1; ++k) {
+        const bool up = k >= i;
+        const float dx = px - (up ? qx[k + 1] : qx[k]);
+        const float dy = py - (up ? qy[k + 1] : qy[k]);
+        const float kf = contact_factor(dx, dy, A.ph);
+        fx = fmaf(kf, dx, fx);
+        fy = fmaf(kf, dy, fy);
       }
       px = fmaf(vx, A.ph.dt, px);
       py = fmaf(vy, A.ph.dt, py);

@@ -483,16 +483,15 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
     // ---- transition of this lane's agent
     float fx = A.ph.accel * action_dir_x(act);
     float fy = A.ph.accel * action_dir_y(act);
+    // the k-th OTHER agent is agent k (k < i) or k + 1: N - 1 evaluations, ascending agent order
 #pragma unroll
-    for (int a = 0; a < N; ++a) {
-      if (a != i) {
-        const float2 q = cur[a];
-        const float dx = px - q.x;
-        const float dy = py - q.y;
-        const float k = contact_factor(dx, dy, A.ph);
-        fx = fmaf(k, dx, fx);
-        fy = fmaf(k, dy, fy);
-      }
+    for (int k = 0; k < N - 1; ++k) {
+      const float2 q = cur[k + (k >= i ? 1 : 0)];
+      const float dx = px - q.x;
+      const float dy = py - q.y;
+      const float kf = contact_factor(dx, dy, A.ph);
+      fx = fmaf(kf, dx, fx);
+      fy = fmaf(kf, dy, fy);
     }
     px = fmaf(vx, A.ph.dt, px);
     py = fmaf(vy, A.ph.dt, py);
