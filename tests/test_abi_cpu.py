@@ -185,3 +185,45 @@ def test_random_configs_are_accepted_or_refused_as_the_header_says(lib):
 
     check()
     assert seen[True] > 20 and seen[False] > 100
+
+
+def test_header_is_plain_c_and_links_from_a_c_program(lib, tmp_path):
+    """include/mpe.h compiles as C99 with a C compiler (no C++ types in the boundary), every declared
+    entry point links, and a host-side refusal works from a program that is not Python."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if not gcc:
+        pytest.skip("no C compiler")
+    names = declared_symbols()
+    refs = "\n".join("  p[%d] = (fn)%s;" % (i, n) for i, n in enumerate(names))
+    src = tmp_path / "use_mpe.c"
+    src.write_text("""#include <stdio.h>
+#include <string.h>
+#include "mpe.h"
+typedef void (*fn)(void);
+int main(void) {
+  fn p[%d];
+  mpe_config cfg;
+  mpe_env* env = NULL;
+  int rc;
+%s
+  if (sizeof(mpe_config) != 92) return 10;
+  memset(&cfg, 0, sizeof cfg);          /* num_envs = 0: refused on the host */
+  rc = mpe_create(&cfg, &env);
+  if (rc != MPE_EINVAL || env != NULL) return 11;
+  if (strstr(mpe_last_error(), "num_envs") == NULL) return 12;
+  if (mpe_destroy(NULL) != MPE_OK && mpe_destroy(NULL) != MPE_EINVAL) return 13;
+  printf("%%d symbols, %%s\\n", (int)(sizeof p / sizeof p[0]), p[0] ? "ok" : "null");
+  return 0;
+}
+""" % (len(names), refs))
+    exe = tmp_path / "use_mpe"
+    libdir = os.path.dirname(binding.LIB_PATH)
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                        str(src), "-o", str(exe), "-L", libdir, "-l:libmpe.so", "-Wl,-rpath," + libdir],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
+    assert "%d symbols, ok" % len(names) in r.stdout
