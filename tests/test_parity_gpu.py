@@ -490,6 +490,51 @@ def test_work_is_enqueued_on_the_callers_stream(mods):
     assert all(torch.equal(a, b) for a, b in zip(*outs))
 
 
+def test_handles_on_two_streams_do_not_disturb_each_other(mods):
+    """Several handles of different kinds (simple spread fp32 and bf16, predator-prey, recurrent) are
+    driven in turn on two streams without synchronising in between; every trajectory equals the one
+    the same handle produces alone.  Guards state shared between handles or calls inside the library."""
+    MpeEnv, _ = mods
+    T, E = 40, 4096
+
+    def make():
+        envs = [MpeEnv(Hp.gpu_config(E, 3, 1, 64, 0)), MpeEnv(Hp.gpu_config(E, 3, 1, 64, 1)),
+                MpeEnv(Hp.tag_gpu_config(E, 4, 2, 3, 1, 64)), MpeEnv(Hp.gpu_config(E, 3, 1, 128, 1)),
+                MpeEnv(Hp.gpu_config(E, 3, 1, 0, 0))]
+        envs[0].set_policy(*Hp.to_dev(synth.policy_weights_with_bias(3, 1, 18, 64)))
+        envs[1].set_policy(*Hp.to_dev(synth.policy_weights_with_bias(4, 1, 18, 64)))
+        envs[2].set_policy(*Hp.to_dev(synth.policy_weights_with_bias(5, 1, envs[2].D, 64)))
+        envs[3].set_gru_policy(*Hp.to_dev(synth.gru_weights(6, 1, 18)))
+        return envs
+
+    # alone, one after the other, on the default stream
+    alone = []
+    for k, env in enumerate(make()):
+        env.reset(20 + k)
+        alone.append([x.clone() for x in env.rollout(T, *env.empty_traj(T))])
+        torch.cuda.synchronize()
+        env.close()
+    # interleaved on two side streams, two calls of T/2 steps each, no synchronisation in between
+    envs = make()
+    torch.cuda.synchronize()   # the weights were packed on the default stream
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    bufs = [[env.empty_traj(T // 2) for _ in range(2)] for env in envs]
+    for k, env in enumerate(envs):
+        with torch.cuda.stream(streams[k % 2]):
+            env.reset(20 + k)
+    for half in range(2):
+        for k, env in enumerate(envs):
+            with torch.cuda.stream(streams[k % 2]):
+                env.rollout(T // 2, *bufs[k][half])
+    torch.cuda.synchronize()
+    for k, env in enumerate(envs):
+        for j in range(4):
+            both = torch.cat([bufs[k][0][j], bufs[k][1][j]], dim=0)
+            assert torch.equal(both, alone[k][j]), "handle %d output %d" % (k, j)
+        assert torch.equal(bufs[k][1][4], alone[k][4]), "handle %d last observation" % k
+        env.close()
+
+
 @pytest.mark.parametrize("N,H", [(3, 0), (3, 64)])
 def test_step_counter_near_the_top_of_its_range(mods, N, H):
     """The absolute step is a 32-bit word of the Philox counter: values just below 2^32 behave like
