@@ -225,7 +225,7 @@ int mpe_step(mpe_env* e, const uint8_t* actions, float* obs, float* reward, uint
     A.tg = e->tg;
     A.actions_in = actions;
     const char* why = nullptr;
-    hipError_t err = launch_tag_rollout(e->N, e->L, e->G, 0, A, nullptr, static_cast<hipStream_t>(stream), &why);
+    hipError_t err = launch_tag_rollout(e->N, e->L, e->G, 0, A, nullptr, nullptr, static_cast<hipStream_t>(stream), &why);
     if (why) return fail(MPE_EINVAL, "mpe_step: %s", why);
     if (err != hipSuccess) return fail(MPE_EHIP, "mpe_step: %s", hipGetErrorString(err));
   } else {
@@ -254,7 +254,7 @@ int mpe_set_policy(mpe_env* e, const float* W1, const float* b1, const float* W2
     if (!tag_policy_supported(e->N, e->L, e->G, e->H, e->cfg.weight_dtype))
       return fail(MPE_EINVAL, "mpe_set_policy: MPE_SCENARIO_TAG policies are built for hidden 64 and observation "
                               "rows of at most 16 floats");
-    err = pack_policy_tag(e->pol, e->N, e->L, e->G, int(e->R), e->cfg.weight_dtype == MPE_WEIGHTS_BF16, W1, b1, W2,
+    err = pack_policy_tag(e->pol, e->N, e->L, e->G, int(e->R), e->cfg.weight_dtype == MPE_WEIGHTS_BF16, 5, W1, b1, W2,
                           b2, W3, b3, static_cast<hipStream_t>(stream));
   } else {
     err = pack_policy(e->pol, e->N, e->H, int(e->R), e->cfg.weight_dtype, W1, b1, W2, b2, W3, b3,
@@ -299,7 +299,7 @@ int mpe_rollout(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, float
     TA.actions_in = nullptr;
     const char* why = nullptr;
     const int mode = !e->has_policy ? 1 : (e->cfg.weight_dtype == MPE_WEIGHTS_BF16 ? 3 : 2);
-    hipError_t err = launch_tag_rollout(e->N, e->L, e->G, mode, TA, e->pol.packed,
+    hipError_t err = launch_tag_rollout(e->N, e->L, e->G, mode, TA, e->pol.packed, nullptr,
                                         static_cast<hipStream_t>(stream), &why);
     if (why) return fail(MPE_EINVAL, "mpe_rollout: %s", why);
     if (err != hipSuccess) return fail(MPE_EHIP, "mpe_rollout: %s", hipGetErrorString(err));
@@ -376,11 +376,20 @@ int mpe_set_critic(mpe_env* e, const float* V1, const float* c1, const float* V2
     return MPE_OK;
   }
   if (given != 6) return fail(MPE_EINVAL, "mpe_set_critic: pass all six arrays or none");
-  if (e->tag || !f32_supported(e->N, e->H))
-    return fail(MPE_EINVAL, "mpe_set_critic: unsupported shape: the actor-critic rollout is built for "
-                            "hidden 64 and 1..3 agents");
-  hipError_t err = pack_policy_f32(e->critic, e->N, int(e->R), V1, c1, V2, c2, V3, c3, 1,
-                                   e->cfg.weight_dtype == MPE_WEIGHTS_BF16, static_cast<hipStream_t>(stream));
+  hipError_t err;
+  if (e->tag) {
+    if (e->cfg.weight_dtype != MPE_WEIGHTS_FP32 || !tag_policy_supported(e->N, e->L, e->G, e->H, e->cfg.weight_dtype))
+      return fail(MPE_EINVAL, "mpe_set_critic: unsupported shape: the MPE_SCENARIO_TAG actor-critic rollout is built "
+                              "for fp32 weights, hidden 64 and observation rows of at most 16 floats");
+    err = pack_policy_tag(e->critic, e->N, e->L, e->G, int(e->R), false, 1, V1, c1, V2, c2, V3, c3,
+                          static_cast<hipStream_t>(stream));
+  } else {
+    if (!f32_supported(e->N, e->H))
+      return fail(MPE_EINVAL, "mpe_set_critic: unsupported shape: the actor-critic rollout is built for "
+                              "hidden 64 and 1..3 agents");
+    err = pack_policy_f32(e->critic, e->N, int(e->R), V1, c1, V2, c2, V3, c3, 1,
+                          e->cfg.weight_dtype == MPE_WEIGHTS_BF16, static_cast<hipStream_t>(stream));
+  }
   if (err != hipSuccess) return fail(MPE_EHIP, "mpe_set_critic: %s", hipGetErrorString(err));
   e->has_critic = true;
   return MPE_OK;
@@ -395,7 +404,8 @@ int mpe_rollout_ac(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, fl
   if (!e->has_policy || !e->has_critic)
     return fail(MPE_ESTATE, "mpe_rollout_ac: needs mpe_set_policy and mpe_set_critic first");
   if (e->has_gru) return fail(MPE_ESTATE, "mpe_rollout_ac: remove the recurrent policy first (feed-forward networks only)");
-  if (e->tag || !f32_supported(e->N, e->H)) return fail(MPE_EINVAL, "mpe_rollout_ac: unsupported shape");
+  if (!e->tag && !f32_supported(e->N, e->H)) return fail(MPE_EINVAL, "mpe_rollout_ac: unsupported shape");
+  if (e->tag && e->cfg.weight_dtype != MPE_WEIGHTS_FP32) return fail(MPE_EINVAL, "mpe_rollout_ac: unsupported shape");
   for (const float* p : {obs_traj, logp_traj, value_traj, rew_traj, last_obs, last_value})
     if (p && !aligned16(p)) return fail(MPE_EINVAL, "mpe_rollout_ac: float outputs must be 16-byte aligned");
   if (uint64_t(e->abs_step) + uint64_t(T) > 0xFFFFFFFFull)
@@ -417,8 +427,18 @@ int mpe_rollout_ac(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, fl
   A.value_traj = value_traj;
   A.last_value = last_value;
   const char* why = nullptr;
-  hipError_t err = launch_rollout_ac_f32(e->N, e->cfg.weight_dtype == MPE_WEIGHTS_BF16, A, e->pol, e->critic,
-                                         static_cast<hipStream_t>(stream), &why);
+  hipError_t err;
+  if (e->tag) {
+    TagArgs TA{};
+    TA.r = A;
+    TA.tg = e->tg;
+    TA.actions_in = nullptr;
+    err = launch_tag_rollout(e->N, e->L, e->G, 4, TA, e->pol.packed, e->critic.packed,
+                             static_cast<hipStream_t>(stream), &why);
+  } else {
+    err = launch_rollout_ac_f32(e->N, e->cfg.weight_dtype == MPE_WEIGHTS_BF16, A, e->pol, e->critic,
+                                static_cast<hipStream_t>(stream), &why);
+  }
   if (why) return fail(MPE_EINVAL, "mpe_rollout_ac: %s", why);
   if (err != hipSuccess) return fail(MPE_EHIP, "mpe_rollout_ac: %s", hipGetErrorString(err));
   MPE_HIP(hipGetLastError());

@@ -50,12 +50,14 @@ void launch_tag_reset(int N, int L, int G, const StatePtrs& st, uint32_t TE, uin
                       hipStream_t s);
 // mode 0: one step under A.actions_in (r.T must be 1; obs after the step -> r.last_obs, reward ->
 // r.rew_traj, done -> r.done_traj); mode 1: uniform random actions; mode 2: the packed fp32 policy;
-// mode 3: the packed bf16 policy
-hipError_t launch_tag_rollout(int N, int L, int G, int mode, const TagArgs& A, const void* packed, hipStream_t s,
-                              const char** why);
+// mode 3: the packed bf16 policy; mode 4: the packed fp32 policy and critic (actor-critic outputs in r)
+hipError_t launch_tag_rollout(int N, int L, int G, int mode, const TagArgs& A, const void* packed,
+                              const void* packed_critic, hipStream_t s, const char** why);
 struct PolicyBuffers;
-hipError_t pack_policy_tag(PolicyBuffers& pb, int N, int L, int G, int R, bool bf16, const float* W1, const float* b1,
-                           const float* W2, const float* b2, const float* W3, const float* b3, hipStream_t s);
+// nout: outputs of the last layer (5 policy logits, 1 critic value)
+hipError_t pack_policy_tag(PolicyBuffers& pb, int N, int L, int G, int R, bool bf16, int nout, const float* W1,
+                           const float* b1, const float* W2, const float* b2, const float* W3, const float* b3,
+                           hipStream_t s);
 
 void launch_reset(int N, const StatePtrs& st, uint32_t TE, uint32_t E, uint32_t seed, float* obs,
                   hipStream_t s);

@@ -23,19 +23,29 @@ struct TagShape {
   static_assert(G_ >= 1 && A >= 1 && L_ >= 0 && D % 2 == 0, "roles");
 };
 
-enum TagMode : int { kGiven = 0, kUniform = 1, kPolicy = 2, kPolicyBf = 3 };   // fp32-exact / bf16 policy
+// kPolicy / kPolicyBf: fp32-exact / bf16 policy.  kPolicyAc: fp32-exact policy plus a critic of the same
+// shape with one output: log-probability of the sampled action and value per agent and step.
+enum TagMode : int { kGiven = 0, kUniform = 1, kPolicy = 2, kPolicyBf = 3, kPolicyAc = 4 };
 
-template <typename S, int MODE>
+// EB = envs per block.  Plain rollouts: 64.  Actor-critic: both packed images (79 KB) are staged per block,
+// so a block is 8 wavefronts where the shape allows it (wavefront-local shapes need no block barrier).
+template <typename S, int MODE, int EB = 64>
 struct TagSmem {
-  static constexpr int ROWS = 64 * S::N;
-  static constexpr bool kHasPolicy = MODE == kPolicy || MODE == kPolicyBf;
+  static constexpr int ROWS = EB * S::N;
+  static constexpr bool kAc = MODE == kPolicyAc;
+  static constexpr bool kHasPolicy = MODE == kPolicy || MODE == kPolicyBf || kAc;
   using P = PkT<MODE == kPolicyBf>;
-  static constexpr size_t OFF_BIAS = kHasPolicy ? P::LDS_BYTES : 0;
-  static constexpr size_t OFF_OBS = OFF_BIAS + (kHasPolicy ? P::BIAS_BYTES : 0);
+  // plain policy: W1A, W2A, then the biases (W3A lives in registers); actor-critic: the whole image of
+  // the policy, then the whole image of the critic (their W3A are re-read every step)
+  static constexpr size_t OFF_BIAS = kAc ? P::OFF_BIAS : (kHasPolicy ? P::LDS_BYTES : 0);
+  static constexpr size_t OFF_CRITIC = P::RUN_BYTES;                                    // kAc only
+  static constexpr size_t OFF_OBS = kAc ? 2 * P::RUN_BYTES : OFF_BIAS + (kHasPolicy ? P::BIAS_BYTES : 0);
   static constexpr size_t OBS = size_t(ROWS) * S::D * 4 + 64;   // + zeroed tail: layer 1 reads 16 cols
   static constexpr size_t OFF_XCH = OFF_OBS + OBS;              // [parity][ROWS] float4 (px, py, vx, vy)
-  static constexpr size_t TOTAL = OFF_XCH + size_t(S::kWaveLocal ? 1 : 2) * ROWS * 16;
-  static_assert(OFF_OBS % 16 == 0 && OFF_XCH % 16 == 0, "alignment");
+  static constexpr size_t OFF_VALUE = OFF_XCH + size_t(S::kWaveLocal ? 1 : 2) * ROWS * 16;   // kAc: [ROWS] float
+  static constexpr size_t TOTAL = OFF_VALUE + (kAc ? size_t(ROWS) * 4 : 0);
+  static_assert(OFF_OBS % 16 == 0 && OFF_XCH % 16 == 0 && P::RUN_BYTES % 16 == 0, "alignment");
+  static_assert(TOTAL <= 160 * 1024, "LDS budget");
 };
 
 // Contact force factor k of a pair with separation (dx, dy) and contact distance dmin: the force
@@ -137,12 +147,15 @@ __global__ __launch_bounds__(64 * S::N) void tag_reset_kernel(StatePtrs st, uint
   }
 }
 
-template <typename S, int MODE>
-__global__ __launch_bounds__(64 * S::N, (MODE == kPolicy || MODE == kPolicyBf) ? 3 : 1) void tag_rollout_kernel(
-    TagArgs TA, const uint8_t* __restrict__ packed, int per_run_weights, uint32_t groups, uint32_t groups_per_xcd) {
-  using M = TagSmem<S, MODE>;
+template <typename S, int MODE, int EB = 64>
+__global__ __launch_bounds__(EB * S::N, (MODE == kPolicy || MODE == kPolicyBf) ? 3 : 1) void tag_rollout_kernel(
+    TagArgs TA, const uint8_t* __restrict__ packed, const uint8_t* __restrict__ packed_critic, int per_run_weights,
+    uint32_t groups, uint32_t groups_per_xcd) {
+  using M = TagSmem<S, MODE, EB>;
+  constexpr bool AC = MODE == kPolicyAc;
+  static_assert(EB == 64 || S::kWaveLocal, "larger blocks only where wavefronts never exchange data");
   using Net = NetShape<S::D, S::D <= 16 ? S::D : 16>;
-  constexpr int N = S::N, L = S::L, G = S::G, NA = S::A, D = S::D, ROWS = 64 * N, THREADS = ROWS;
+  constexpr int N = S::N, L = S::L, G = S::G, NA = S::A, D = S::D, ROWS = EB * N, THREADS = ROWS;
   const RolloutArgs& A = TA.r;
   const TagPhys& tg = TA.tg;
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -157,39 +170,53 @@ __global__ __launch_bounds__(64 * S::N, (MODE == kPolicy || MODE == kPolicyBf) ?
   // block b runs on XCD b % 8: give each XCD one contiguous range of env groups
   const uint32_t grp = (blockIdx.x & 7u) * groups_per_xcd + (blockIdx.x >> 3);
   if (grp >= groups) return;  // whole block, before any barrier
-  const size_t g0 = size_t(grp) * 64;
+  const size_t g0 = size_t(grp) * EB;
   const size_t g = g0 + el;
   const bool valid = g < TE;
   const uint32_t gc = valid ? uint32_t(g) : uint32_t(g0);
   const uint32_t run = gc / A.E;
   const uint32_t env = gc - run * A.E;
   const size_t left = TE - g0;
-  const int nvalid = left < size_t(64) ? int(left) : 64;
+  const int nvalid = left < size_t(EB) ? int(left) : EB;
   const int wave_rows = min(max(nvalid * N - wave * 64, 0), 64);   // rows of this wavefront that exist
 
-  // ---- policy: W1A, W2A and the biases in LDS, W3A in registers (the run of the block's first env)
-  W3Terms w3;
-  if constexpr (M::kHasPolicy) {
-    using Pk = typename M::P;
+  // ---- policy: W1A, W2A and the biases in LDS, W3A in registers (the run of the block's first env);
+  // actor-critic: both whole images in LDS, W3A of the network in use re-read from there
+  using Pk = typename M::P;
+  [[maybe_unused]] auto load_w3 = [&](const uint8_t* image) {
     constexpr bool BF = MODE == kPolicyBf;
-    const uint8_t* run_weights = packed + (per_run_weights ? size_t(uint32_t(g0) / A.E) * Pk::RUN_BYTES : 0);
+    W3Terms w;
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
       if constexpr (BF || Net::kRowTerms) {
-        w3.s[s].h = reinterpret_cast<const bf16x8*>(run_weights + Pk::OFF_W3A)[s * 64 + lane];
+        w.s[s].h = reinterpret_cast<const bf16x8*>(image + Pk::OFF_W3A)[s * 64 + lane];
       } else {
-        const bf16x8* src = reinterpret_cast<const bf16x8*>(run_weights + Pk::OFF_W3A) + s * 3 * 64 + lane;
-        w3.s[s].h = src[0];
-        w3.s[s].m = src[64];
-        w3.s[s].l = src[128];
+        const bf16x8* src = reinterpret_cast<const bf16x8*>(image + Pk::OFF_W3A) + s * 3 * 64 + lane;
+        w.s[s].h = src[0];
+        w.s[s].m = src[64];
+        w.s[s].l = src[128];
       }
     }
+    return w;
+  };
+  W3Terms w3;
+  if constexpr (M::kHasPolicy) {
+    const size_t run_off = per_run_weights ? size_t(uint32_t(g0) / A.E) * Pk::RUN_BYTES : 0;
+    const uint8_t* run_weights = packed + run_off;
     const uint4* src = reinterpret_cast<const uint4*>(run_weights);
     uint4* dst = reinterpret_cast<uint4*>(smem);
-    for (int k = tid; k < int(Pk::LDS_BYTES / 16); k += THREADS) dst[k] = src[k];
-    const uint4* bsrc = reinterpret_cast<const uint4*>(run_weights + Pk::OFF_BIAS);
-    uint4* bdst = reinterpret_cast<uint4*>(smem + M::OFF_BIAS);
-    for (int k = tid; k < int(Pk::BIAS_BYTES / 16); k += THREADS) bdst[k] = bsrc[k];
+    if constexpr (AC) {
+      for (int k = tid; k < int(Pk::RUN_BYTES / 16); k += THREADS) dst[k] = src[k];
+      const uint4* csrc = reinterpret_cast<const uint4*>(packed_critic + run_off);
+      uint4* cdst = reinterpret_cast<uint4*>(smem + M::OFF_CRITIC);
+      for (int k = tid; k < int(Pk::RUN_BYTES / 16); k += THREADS) cdst[k] = csrc[k];
+    } else {
+      w3 = load_w3(run_weights);
+      for (int k = tid; k < int(Pk::LDS_BYTES / 16); k += THREADS) dst[k] = src[k];
+      const uint4* bsrc = reinterpret_cast<const uint4*>(run_weights + Pk::OFF_BIAS);
+      uint4* bdst = reinterpret_cast<uint4*>(smem + M::OFF_BIAS);
+      for (int k = tid; k < int(Pk::BIAS_BYTES / 16); k += THREADS) bdst[k] = bsrc[k];
+    }
   }
   if (tid < 16) tile[ROWS * D + tid] = 0.0f;
 
@@ -246,6 +273,24 @@ __global__ __launch_bounds__(64 * S::N, (MODE == kPolicy || MODE == kPolicyBf) ?
   uint32_t step = A.abs_step;
   const float* wtile = tile + wave * (64 * D);        // this wavefront's rows
 
+  [[maybe_unused]] float* values = reinterpret_cast<float*>(smem + M::OFF_VALUE);   // AC: critic value per row
+  [[maybe_unused]] float* logp_base = A.logp_traj;
+  [[maybe_unused]] float* value_base = A.value_traj;
+  // Critic forward of this wavefront's rows into values[] (its rows only: no other wavefront reads them).
+  [[maybe_unused]] auto critic_rows = [&]() {
+    if constexpr (AC) {
+      const uint8_t* csm = smem + M::OFF_CRITIC;
+      const float* cbias = reinterpret_cast<const float*>(csm + Pk::OFF_BIAS);
+#pragma unroll 1
+      for (int pr = 0; pr < 2; ++pr) {
+        float* rows = tile + (wave * 64 + pr * 32) * D;
+        float* vals = values + wave * 64 + pr * 32;
+        const W3Terms wc = load_w3(csm);
+        policy_pair<Net, true>(csm, cbias, wc, rows, rows + 16 * D, lane, vals, vals + 16);
+      }
+    }
+  };
+
   auto flush_rows = [&](float* dst) {
     const bool vec4 = (reinterpret_cast<uintptr_t>(dst) & 15u) == 0;
     if (vec4 && wave_rows == 64) stream_out_full<64 * D / 4>(wtile, dst, lane);
@@ -267,9 +312,13 @@ __global__ __launch_bounds__(64 * S::N, (MODE == kPolicy || MODE == kPolicyBf) ?
       act = word_to_action(philox4x32_10(env, step, uint32_t(i), kTagUniformAction, A.seed, run).x);
     } else {
       const float* bias = reinterpret_cast<const float*>(smem + M::OFF_BIAS);
+      // the critic first (it leaves the rows untouched), then the policy, whose logits replace the
+      // first columns of the rows
+      if constexpr (AC) critic_rows();
 #pragma unroll 1
       for (int pr = 0; pr < 2; ++pr) {
         float* rows = tile + (wave * 64 + pr * 32) * D;
+        if constexpr (AC) w3 = load_w3(smem);
         if constexpr (MODE == kPolicyBf) policy_pair_bf<Net>(smem, bias, w3, rows, rows + 16 * D, lane);
         else policy_pair<Net>(smem, bias, w3, rows, rows + 16 * D, lane);
       }
@@ -277,8 +326,28 @@ __global__ __launch_bounds__(64 * S::N, (MODE == kPolicy || MODE == kPolicyBf) ?
       float z[kNumActions];
 #pragma unroll
       for (int k = 0; k < kNumActions; ++k) z[k] = tile[tid * D + k];
-      if constexpr (MODE == kPolicy && Net::kRowTerms) z[4] = (z[4] + tile[tid * D + 5]) + tile[tid * D + 6];
+      if constexpr (MODE != kPolicyBf && Net::kRowTerms) z[4] = (z[4] + tile[tid * D + 5]) + tile[tid * D + 6];
       act = gumbel_argmax(z, A.seed, run, env, step, uint32_t(i));
+      if constexpr (AC) {
+        // log pi(act | obs) = z_act - max - ln sum exp(z - max)
+        float zmax = z[0], zact = z[0];
+#pragma unroll
+        for (int k = 1; k < kNumActions; ++k) {
+          zmax = fmaxf(zmax, z[k]);
+          zact = act == uint32_t(k) ? z[k] : zact;
+        }
+        float sum = 0.0f;
+#pragma unroll
+        for (int k = 0; k < kNumActions; ++k) sum += hw_exp2((z[k] - zmax) * kLog2e);
+        if (logp_base) {
+          if (valid) logp_base[row_off] = (zact - zmax) - kLn2 * hw_log2(sum);
+          logp_base += TE * N;
+        }
+        if (value_base) {
+          if (valid) value_base[row_off] = values[tid];
+          value_base += TE * N;
+        }
+      }
     }
     if (act_base) {
       if (valid) act_base[row_off] = uint8_t(act);
@@ -384,6 +453,14 @@ __global__ __launch_bounds__(64 * S::N, (MODE == kPolicy || MODE == kPolicyBf) ?
     wave_sync();
     flush_rows(A.last_obs + wave_row0);
   }
+  if constexpr (AC) {
+    if (A.last_value) {   // value of the observation after the last step
+      wave_sync();
+      critic_rows();
+      wave_sync();
+      if (valid) A.last_value[row_off] = values[tid];
+    }
+  }
 
   // ---- state back to HBM
   if (valid) {
@@ -402,10 +479,10 @@ __global__ __launch_bounds__(64 * S::N, (MODE == kPolicy || MODE == kPolicyBf) ?
   }
 }
 
-template <typename S, int MODE>
-hipError_t tag_rollout_impl(const TagArgs& A, const void* packed, hipStream_t s) {
-  using M = TagSmem<S, MODE>;
-  auto kern = tag_rollout_kernel<S, MODE>;
+template <typename S, int MODE, int EB = 64>
+hipError_t tag_rollout_impl(const TagArgs& A, const void* packed, const void* packed_critic, hipStream_t s) {
+  using M = TagSmem<S, MODE, EB>;
+  auto kern = tag_rollout_kernel<S, MODE, EB>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -413,23 +490,31 @@ hipError_t tag_rollout_impl(const TagArgs& A, const void* packed, hipStream_t s)
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const uint32_t groups = (A.r.TE + 63) / 64;
+  const uint32_t groups = (A.r.TE + EB - 1) / EB;
   const uint32_t per_xcd = (groups + 7) / 8;
-  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(64 * S::N), M::TOTAL, s, A, static_cast<const uint8_t*>(packed),
-                     int(A.r.TE != A.r.E), groups, per_xcd);
+  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(EB * S::N), M::TOTAL, s, A, static_cast<const uint8_t*>(packed),
+                     static_cast<const uint8_t*>(packed_critic), int(A.r.TE != A.r.E), groups, per_xcd);
   return hipGetLastError();
 }
 
 template <typename S>
-hipError_t tag_launch(int mode, const TagArgs& A, const void* packed, hipStream_t s, const char** why) {
-  if (mode == kGiven) return tag_rollout_impl<S, kGiven>(A, nullptr, s);
-  if (mode == kUniform) return tag_rollout_impl<S, kUniform>(A, nullptr, s);
+hipError_t tag_launch(int mode, const TagArgs& A, const void* packed, const void* packed_critic, hipStream_t s,
+                      const char** why) {
+  if (mode == kGiven) return tag_rollout_impl<S, kGiven>(A, nullptr, nullptr, s);
+  if (mode == kUniform) return tag_rollout_impl<S, kUniform>(A, nullptr, nullptr, s);
   if constexpr (S::D <= 16) {
-    if (A.r.TE != A.r.E && A.r.E % 64 != 0) {
-      *why = "with several runs, num_envs per run must be a multiple of 64";
+    // actor-critic: 8 wavefronts share the two staged images where wavefronts never exchange data
+    constexpr int kAcEnvs = S::kWaveLocal ? 512 / S::N : 64;
+    const uint32_t per_block = mode == kPolicyAc ? uint32_t(kAcEnvs) : 64u;
+    if (A.r.TE != A.r.E && A.r.E % per_block != 0) {
+      *why = mode == kPolicyAc ? "with several runs, num_envs per run must be a multiple of the block's envs (512 / agents, "
+                                 "64 for 3 agents)"
+                               : "with several runs, num_envs per run must be a multiple of 64";
       return hipSuccess;
     }
-    return mode == kPolicyBf ? tag_rollout_impl<S, kPolicyBf>(A, packed, s) : tag_rollout_impl<S, kPolicy>(A, packed, s);
+    if (mode == kPolicyAc) return tag_rollout_impl<S, kPolicyAc, kAcEnvs>(A, packed, packed_critic, s);
+    return mode == kPolicyBf ? tag_rollout_impl<S, kPolicyBf>(A, packed, nullptr, s)
+                             : tag_rollout_impl<S, kPolicy>(A, packed, nullptr, s);
   } else {
     *why = "no policy kernel for this shape (observation rows longer than 16)";
     return hipSuccess;
@@ -437,7 +522,7 @@ hipError_t tag_launch(int mode, const TagArgs& A, const void* packed, hipStream_
 }
 
 template <typename S>
-hipError_t tag_pack(PolicyBuffers& pb, int R, bool bf16, const float* W1, const float* b1, const float* W2,
+hipError_t tag_pack(PolicyBuffers& pb, int R, bool bf16, int nout, const float* W1, const float* b1, const float* W2,
                     const float* b2, const float* W3, const float* b3, hipStream_t s) {
   if constexpr (S::D <= 16) {
     using Net = NetShape<S::D, S::D>;
@@ -446,10 +531,10 @@ hipError_t tag_pack(PolicyBuffers& pb, int R, bool bf16, const float* W1, const 
     constexpr int total = 4 * 64 * 8 + 4 * 2 * 64 * 8 + 2 * 64 * 8 + 2 * kH + 16;   // one thread per weight / bias
     if (bf16)
       hipLaunchKernelGGL(pack_bf16_kernel<Net>, dim3((total + 255) / 256, R), dim3(256), 0, s,
-                         static_cast<uint8_t*>(pb.packed), W1, b1, W2, b2, W3, b3, 5);
+                         static_cast<uint8_t*>(pb.packed), W1, b1, W2, b2, W3, b3, nout);
     else
       hipLaunchKernelGGL(pack_split_kernel<Net>, dim3((total + 255) / 256, R), dim3(256), 0, s,
-                         static_cast<uint8_t*>(pb.packed), W1, b1, W2, b2, W3, b3, 5);
+                         static_cast<uint8_t*>(pb.packed), W1, b1, W2, b2, W3, b3, nout);
     return hipGetLastError();
   } else {
     return hipErrorInvalidValue;
@@ -485,19 +570,20 @@ void launch_tag_reset(int N, int L, int G, const StatePtrs& st, uint32_t TE, uin
 #undef X
 }
 
-hipError_t launch_tag_rollout(int N, int L, int G, int mode, const TagArgs& A, const void* packed, hipStream_t s,
-                              const char** why) {
+hipError_t launch_tag_rollout(int N, int L, int G, int mode, const TagArgs& A, const void* packed,
+                              const void* packed_critic, hipStream_t s, const char** why) {
 #define X(n, l, g) \
-  if (N == n && L == l && G == g) return tag_launch<TagShape<n, l, g>>(mode, A, packed, s, why);
+  if (N == n && L == l && G == g) return tag_launch<TagShape<n, l, g>>(mode, A, packed, packed_critic, s, why);
   MPE_TAG_SHAPES(X)
 #undef X
   return hipErrorInvalidValue;
 }
 
-hipError_t pack_policy_tag(PolicyBuffers& pb, int N, int L, int G, int R, bool bf16, const float* W1, const float* b1,
-                           const float* W2, const float* b2, const float* W3, const float* b3, hipStream_t s) {
+hipError_t pack_policy_tag(PolicyBuffers& pb, int N, int L, int G, int R, bool bf16, int nout, const float* W1,
+                           const float* b1, const float* W2, const float* b2, const float* W3, const float* b3,
+                           hipStream_t s) {
 #define X(n, l, g) \
-  if (N == n && L == l && G == g) return tag_pack<TagShape<n, l, g>>(pb, R, bf16, W1, b1, W2, b2, W3, b3, s);
+  if (N == n && L == l && G == g) return tag_pack<TagShape<n, l, g>>(pb, R, bf16, nout, W1, b1, W2, b2, W3, b3, s);
   MPE_TAG_SHAPES(X)
 #undef X
   return hipErrorInvalidValue;

@@ -414,9 +414,9 @@ def test_refusals(mods):
         env.rollout(1, *env.empty_traj(1))                                   # before reset
     assert ei.value.code == MPE_ESTATE
     env.close()
-    env = MpeEnv(Hp.tag_gpu_config(64, 4, 2, 3, 1, 64))
+    env = MpeEnv(Hp.tag_gpu_config(64, 4, 2, 3, 1, 64, wd=1))
     with pytest.raises(MpeError) as ei:
-        env.set_critic(*Hp.to_dev(synth.critic_weights(1, 1, env.D, 64)))    # actor-critic: simple spread only
+        env.set_critic(*Hp.to_dev(synth.critic_weights(1, 1, env.D, 64)))    # actor-critic: fp32 weights only
     assert ei.value.code == MPE_EINVAL
     env.close()
     env = MpeEnv(Hp.tag_gpu_config(50, 4, 2, 3, 2, 64))                    # runs of 50 envs: blocks would straddle runs
