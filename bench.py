@@ -233,6 +233,27 @@ def main():
                                   "frac_of_fp32_matrix_peak": tf / MFMA_FP32_PEAK_TFLOPS})
             env6.close()
             del b6
+        # actor-critic rollout of the same scenario (policy + critic of the same shape with one output)
+        env6 = MpeEnv(Hp.tag_gpu_config(wl.num_envs, tN, tL, tA, 1, H))
+        env6.set_policy(*Hp.to_dev(synth.policy_weights(0, 1, tD, H)))
+        env6.set_critic(*Hp.to_dev(synth.critic_weights(0, 1, tD, H)))
+        env6.reset(seed)
+        b6 = env6.empty_traj_ac(T)
+        for _ in range(2):
+            env6.rollout_ac(T, *b6)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(k):
+            env6.rollout_ac(T, *b6)
+        torch.cuda.synchronize()
+        dt6 = (time.perf_counter() - t0) / k
+        ac_flop = flops_per_agent_step(tD, H) + flops_per_agent_step(tD, H, 1)
+        tag["actor_critic"] = {"agent_steps_per_s": t_steps / dt6, "ms_per_rollout": dt6 * 1e3,
+                               "flop_per_agent_step": ac_flop, "fp32_equivalent_TFLOPs": ac_flop * t_steps / dt6 / 1e12,
+                               "frac_of_fp32_matrix_peak": ac_flop * t_steps / dt6 / 1e12 / MFMA_FP32_PEAK_TFLOPS,
+                               "note": "mpe_rollout_ac, wall time per call; 128-env blocks of 8 wavefronts around both staged networks"}
+        env6.close()
+        del b6
         tag["config"] = {"scenario": "MPE_SCENARIO_TAG", "envs": wl.num_envs, "agents": tN, "adversaries": tA,
                          "landmarks": tL, "obs_dim": tD, "T": T, "bytes_per_env_step": t_bytes,
                          "kernel": "tag_rollout_kernel (lane per agent; policy / uniform variants)"}
