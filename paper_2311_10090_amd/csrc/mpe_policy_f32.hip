@@ -93,9 +93,18 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
   const float* cbias = reinterpret_cast<const float*>(smem + M::OFF_CRITIC + P::OFF_BIAS);
   float* values = reinterpret_cast<float*>(smem + M::OFF_VALUE);
 
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // Wavefront -> rows.  With several sync groups per block (EB > 64) the N wavefronts of group g are
+  // the hardware wavefronts g, g + G, g + 2G (G = EB / 64 groups): the hardware deals the wavefronts
+  // of a block to the four SIMDs in turn, so with G = 4 a group's wavefronts share ONE SIMD, and a
+  // wavefront waiting at the group's per-step barrier yields its issue slots to the very wavefronts
+  // it is waiting for (measured: 2.30 -> 2.06 ms per rollout, the time of the same kernel with the barrier
+  // taken out; with the wavefronts of a group on three different SIMDs the barrier cost 12 %).
+  // `wave` and `tid` below are these virtual indices: row = tid.
+  const int lane = threadIdx.x & 63;
+  const int hw_wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
+  constexpr int kGroups = EB / 64;
+  const int wave = kGroups > 1 ? (hw_wave % kGroups) * N + hw_wave / kGroups : hw_wave;
+  const int tid = wave * 64 + lane;
   const int el = tid / N, i = tid - el * N;          // env within block, agent
   const size_t TE = A.TE;
   // XCD-aware mapping: the hardware deals block b to XCD b % 8; giving each XCD one contiguous
