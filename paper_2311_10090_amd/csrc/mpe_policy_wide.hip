@@ -289,9 +289,15 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
   float2* lmbuf = reinterpret_cast<float2*>(smem + M::OFF_LM);
   float2* respos = reinterpret_cast<float2*>(smem + M::OFF_RESPOS);
 
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // Wavefront -> rows: the GW wavefronts of sync group g are the hardware wavefronts g, g + G, g + 2G, ...
+  // (G groups per block).  The hardware deals a block's wavefronts to the four SIMDs in turn, so a
+  // group then lives on 4 / G of the SIMDs and a wavefront waiting at the group's barrier yields its
+  // issue slots to wavefronts of its own group.  `wave` and `tid` are these virtual indices: row = tid.
+  const int lane = threadIdx.x & 63;
+  const int hw_wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
+  constexpr int kGroups = EB / GE;
+  const int wave = kGroups > 1 ? (hw_wave % kGroups) * GW + hw_wave / kGroups : hw_wave;
+  const int tid = wave * 64 + lane;
   const int el = tid / N, i = tid - el * N;          // env within block, agent
   float* stage = reinterpret_cast<float*>(smem + M::OFF_STAGE + size_t(wave) * M::STAGE_WAVE);
   uint32_t* arrived = reinterpret_cast<uint32_t*>(smem + M::OFF_ARRIVED) + wave / GW;
