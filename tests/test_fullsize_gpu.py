@@ -161,6 +161,26 @@ def test_large_ragged_size_uses_256_env_blocks():
     env2.close()
 
 
+@pytest.mark.parametrize("N", [1, 2])
+def test_large_size_one_and_two_agents_use_256_env_blocks(N):
+    """65,600 envs with 1 and 2 agents: the fused kernel's 256-env blocks (four sync groups of N
+    wavefronts, each group on one SIMD), sampled env ranges against the oracle."""
+    wl = synth.Workload("large_65600env_n%d_mlp64_fp32" % N, 65600, N, 1, 50, 64, 0)
+    say("full size %s" % wl.name)
+    env, out, weights = _gpu_rollout(wl, seed=4, wseed=8)
+    assert int(out[3].sum().item()) == wl.total_envs * (wl.T // synth.MAX_EPISODE_STEPS)
+    assert bool(torch.isfinite(out[0]).all()) and bool((out[1] <= 4).all())
+    tot = agree = 0
+    for off, n in ((0, 64), (255, 130), (32768 - 30, 64), (65536, 64)):
+        ref = _oracle_range(wl, 4, 0, off, n, weights)
+        frac, cnt = _compare_range(wl, out, ref, off, n, "N=%d envs %d..%d" % (N, off, off + n))
+        agree += frac * cnt
+        tot += cnt
+    say("  sampled action agreement %.6f over %d samples" % (agree / tot, tot))
+    assert agree / tot >= Hp.ACTION_AGREEMENT - 2.0 / tot
+    env.close()
+
+
 def test_large_size_mixed_reward():
     """Mixed per-agent reward through the 256-env block path, sampled against the oracle.  Rewards
     are compared on the first steps of each episode, for envs whose actions so far agree, leaving
