@@ -712,3 +712,30 @@ def test_bf16_critic_rounds_like_the_policy():
     h2 = np.tanh(rb(h1) @ rb(V2) + c2)
     ref = rb(h2) @ rb(V3) + c3
     np.testing.assert_allclose(o.value(x), ref, rtol=1e-12, atol=1e-13)
+
+
+def test_derived_vector_of_the_uniform_action_stream():
+    """Key (seed 1234, run 0), counter (env 7, step 25, agent 2, tag UNIFORM_ACTION = 1): the words of the
+    published generator for this counter, evaluated independently of the oracle when the scope was
+    written, and the action floor(5 w0 / 2^32) = 1."""
+    w = philox4x32_10([7, 25, 2, 1], [1234, 0])
+    assert [int(x) for x in w] == [0x4C684F2D, 0x89935CAD, 0x82544FA7, 0x39350C36]
+    assert uniform_action(1234, 0, 7, 25, 2) == 1 == (0x4C684F2D * 5) >> 32
+
+
+def test_head_on_collision_of_two_agents_keeps_mirror_symmetry_exactly():
+    """Two agents placed and moving mirror-symmetrically about the y axis, driven with mirrored actions:
+    the state stays an exact mirror image step after step (every operation of the transition commutes
+    with the sign flip of x), through the contact and after it."""
+    o = make(N=2)
+    o.reset(0)
+    put(o, [[[-0.2, 0.1], [0.2, 0.1]]], [[[0.3, -0.05], [-0.3, -0.05]]], [[[0.0, 0.5], [0.0, -0.5]]])
+    touched = False
+    for t in range(12):
+        a = np.array([[2, 1]], np.uint8) if t < 6 else np.array([[3, 3]], np.uint8)   # towards each other, then both -y
+        o.step(a)
+        pa, va = o.get_state()[0][0], o.get_state()[1][0]
+        assert pa[0, 0] == -pa[1, 0] and pa[0, 1] == pa[1, 1]
+        assert va[0, 0] == -va[1, 0] and va[0, 1] == va[1, 1]
+        touched |= abs(pa[0, 0] - pa[1, 0]) < 0.3
+    assert touched
