@@ -229,13 +229,13 @@ __device__ __forceinline__ Terms tanh_split(const f32x4& a0, const f32x4& a1) {
 // sched_barrier fences keep the compiler from regrouping the stages.
 // VALUE: the network has one output (a critic); it goes to valX[j] / valY[j] and the rows are
 // left untouched.
-template <typename S, bool VALUE = false>
-__device__ __forceinline__ void policy_pair(const uint8_t* __restrict__ wsm, const float* __restrict__ bias,
-                                            const W3Terms& w3, float* __restrict__ rowsX,
-                                            float* __restrict__ rowsY, int lane,
-                                            float* __restrict__ valX = nullptr, float* __restrict__ valY = nullptr) {
-  constexpr int D = S::D;
-  const int j = lane & 15, gq = lane >> 4;
+// The network itself, registers in and out: vx / vy = this lane's 8 inputs of tile X / Y (lane (j, gq):
+// inputs 8 (gq & 1) .. + 7 of row j), zX / zY = the layer-3 accumulators of the two tiles.
+template <typename S>
+__device__ __forceinline__ void policy_core(const uint8_t* __restrict__ wsm, const float* __restrict__ bias,
+                                            const W3Terms& w3, const float (&vx)[8], const float (&vy)[8],
+                                            f32x4& zX, f32x4& zY, int lane) {
+  const int gq = lane >> 4;
   {
     // Opaque zero offset: keeps the (loop-invariant) LDS weight reads inside the step loop, where
     // hoisting them would cost ~100 registers and a wavefront of occupancy.  An integer, not a
@@ -281,16 +281,6 @@ __device__ __forceinline__ void policy_pair(const uint8_t* __restrict__ wsm, con
   Terms bx, by;
   bf16x8 bx_lh, by_lh;  // (Xl | Xh): l in K positions 0..15, h in 16..31
   {
-    float vx[8], vy[8];
-    // rows are D*4 bytes apart (a multiple of 8, not of 16): read as float2
-    const float2* xs = reinterpret_cast<const float2*>(rowsX + j * D + 8 * (gq & 1));
-    const float2* ys = reinterpret_cast<const float2*>(rowsY + j * D + 8 * (gq & 1));
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const float2 xv = xs[q], yv = ys[q];
-      vx[2 * q] = xv.x; vx[2 * q + 1] = xv.y;
-      vy[2 * q] = yv.x; vy[2 * q + 1] = yv.y;
-    }
     bx = split_operand(vx);
     by = split_operand(vy);
     bx_lh = gq < 2 ? bx.l : bx.h;
@@ -373,8 +363,8 @@ __device__ __forceinline__ void policy_pair(const uint8_t* __restrict__ wsm, con
   cy0 = tanh_split(accY[0], accY[1]);
   __builtin_amdgcn_sched_barrier(0);
   // ---- L3 s0 + T2 s1 (5 outputs padded to one 16-wide tile)
-  f32x4 zX = *reinterpret_cast<const f32x4*>(bias + 2 * kH + 4 * gq);
-  f32x4 zY = zX;
+  zX = *reinterpret_cast<const f32x4*>(bias + 2 * kH + 4 * gq);
+  zY = zX;
   zX = layer3(w3.s[0], cx0, zX);
   zY = layer3(w3.s[0], cy0, zY);
   cx1 = tanh_split(accX[2], accX[3]);
@@ -383,6 +373,29 @@ __device__ __forceinline__ void policy_pair(const uint8_t* __restrict__ wsm, con
   // ---- L3 s1
   zX = layer3(w3.s[1], cx1, zX);
   zY = layer3(w3.s[1], cy1, zY);
+}
+
+template <typename S, bool VALUE = false>
+__device__ __forceinline__ void policy_pair(const uint8_t* __restrict__ wsm, const float* __restrict__ bias,
+                                            const W3Terms& w3, float* __restrict__ rowsX,
+                                            float* __restrict__ rowsY, int lane,
+                                            float* __restrict__ valX = nullptr, float* __restrict__ valY = nullptr) {
+  constexpr int D = S::D;
+  const int j = lane & 15, gq = lane >> 4;
+  float vx[8], vy[8];
+  {
+    // rows are D*4 bytes apart (a multiple of 8, not of 16): read as float2
+    const float2* xs = reinterpret_cast<const float2*>(rowsX + j * D + 8 * (gq & 1));
+    const float2* ys = reinterpret_cast<const float2*>(rowsY + j * D + 8 * (gq & 1));
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float2 xv = xs[q], yv = ys[q];
+      vx[2 * q] = xv.x; vx[2 * q + 1] = xv.y;
+      vy[2 * q] = yv.x; vy[2 * q + 1] = yv.y;
+    }
+  }
+  f32x4 zX, zY;
+  policy_core<S>(wsm, bias, w3, vx, vy, zX, zY, lane);
   if constexpr (VALUE) {
     // output 0: lane group 0; row-term layout: its three term rows, otherwise register 0
     if (gq == 0) {

@@ -24,6 +24,16 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// 4 x 4 transpose between register index and lane group (lane = 16 * group + j):
+// out[c] at lane (j, g) = in[g] at lane (j, c).  No memory involved.
+__device__ __forceinline__ void transpose_groups(uint32_t (&v)[4]) {
+  const auto s0 = __builtin_amdgcn_permlane32_swap(v[0], v[2], false, false);   // upper half of v0 <-> lower half of v2
+  const auto s1 = __builtin_amdgcn_permlane32_swap(v[1], v[3], false, false);
+  const auto t0 = __builtin_amdgcn_permlane16_swap(s0[0], s1[0], false, false);  // odd 16-lane rows of v0 <-> even rows of v1
+  const auto t1 = __builtin_amdgcn_permlane16_swap(s0[1], s1[1], false, false);
+  v[0] = t0[0]; v[1] = t0[1]; v[2] = t1[0]; v[3] = t1[1];
+}
+
 // Gumbel-max over 5 logits: g = -ln(-ln u), u odd multiples of 2^-24 from two Philox blocks.
 // ln = ln2 * log2 on the hardware unit (u >= 2^-24 is a normal number; -ln u is in
 // [6e-8, 16.7], also normal), so v_k = z_k - ln2 * log2(-ln2 * log2(u_k)).

@@ -410,6 +410,278 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
   }
 }
 
+// --------------------------------------------------------------------------------------
+// Per-run weights at full occupancy.  A block is 256 envs = four 64-env sync groups, EACH WITH THE
+// WEIGHTS OF ITS OWN RUN in LDS (4 x 33 KB), the wavefronts of a group on one SIMD as above.  That
+// leaves no room for observation tiles, so a lane keeps its row in registers and stores it to the
+// trajectory itself, and the layer-1 operands and the logits travel between the row's lane and the
+// matrix layout by 4 x 4 lane-group transposes (permlane swaps, no memory).  Same arithmetic, in
+// the same order, as the kernel above: results are bit-identical.  fp32 weights, shared reward,
+// N = 2 or 3 (layer 3 in the row-term layout), runs of a multiple of 64 envs.
+// --------------------------------------------------------------------------------------
+template <int N>
+struct SmemReg {
+  static constexpr int G = 4, ROWS_G = 64 * N;                         // groups per block, rows per group
+  static constexpr size_t GROUP_W = Pk::LDS_BYTES + Pk::BIAS_BYTES;    // W1A, W2A, then the biases
+  static constexpr size_t OFF_NEWPOS = G * GROUP_W;                    // [G][2][ROWS_G] float2, by step parity
+  static constexpr size_t OFF_ARRIVED = OFF_NEWPOS + size_t(G) * 2 * ROWS_G * 8;
+  static constexpr size_t TOTAL = OFF_ARRIVED + 16;
+  static_assert(GROUP_W % 16 == 0 && TOTAL <= 160 * 1024, "LDS");
+};
+
+template <int N>
+__global__ __launch_bounds__(256 * N, 1) void rollout_policy_f32_reg_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
+                                                                            uint32_t blocks, uint32_t blocks_per_xcd) {
+  using M = SmemReg<N>;
+  using Net = SpreadNet<N>;
+  static_assert(Net::kRowTerms, "layer 3 in the row-term layout");
+  constexpr int D = 6 * N, KIN = Net::KIN, ROWS_G = M::ROWS_G;
+  extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+
+  const int lane = threadIdx.x & 63;
+  const int hw_wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
+  const int gi = hw_wave & 3;                 // sync group: hardware wavefronts gi, gi + 4, gi + 8 share a SIMD
+  const int r = (hw_wave >> 2) * 64 + lane;   // row inside the group
+  const int el = r / N, i = r - el * N;       // env within the group, agent
+  const size_t TE = A.TE;
+  const uint32_t blk = (blockIdx.x & 7u) * blocks_per_xcd + (blockIdx.x >> 3);
+  if (blk >= blocks) return;  // whole block, before any barrier
+  const size_t gg0 = size_t(blk) * 256 + size_t(gi) * 64;   // first env of this group
+  const size_t g = gg0 + el;
+  const bool valid = g < TE;
+  const uint32_t gc = valid ? uint32_t(g) : uint32_t(blk) * 256u;   // a block has at least one env
+  const uint32_t run = gc / A.E;
+  const uint32_t env = gc - run * A.E;
+
+  // ---- this group's weights (the run of its first env; runs are multiples of 64 envs)
+  uint8_t* wsm = smem + size_t(gi) * M::GROUP_W;
+  const float* bias = reinterpret_cast<const float*>(wsm + Pk::LDS_BYTES);
+  const uint32_t grun = uint32_t(gg0 < TE ? gg0 : size_t(blk) * 256) / A.E;
+  const uint8_t* run_weights = packed + size_t(grun) * Pk::RUN_BYTES;
+  W3Terms w3;
+#pragma unroll
+  for (int s = 0; s < 2; ++s) w3.s[s].h = reinterpret_cast<const bf16x8*>(run_weights + Pk::OFF_W3A)[s * 64 + lane];
+  {
+    const uint4* src = reinterpret_cast<const uint4*>(run_weights);
+    uint4* dst = reinterpret_cast<uint4*>(wsm);
+    for (int k = r; k < int(Pk::LDS_BYTES / 16); k += ROWS_G) dst[k] = src[k];
+    const uint4* bsrc = reinterpret_cast<const uint4*>(run_weights + Pk::OFF_BIAS);
+    uint4* bdst = reinterpret_cast<uint4*>(wsm + Pk::LDS_BYTES);
+    for (int k = r; k < int(Pk::BIAS_BYTES / 16); k += ROWS_G) bdst[k] = bsrc[k];
+    if (threadIdx.x < 4) reinterpret_cast<uint32_t*>(smem + M::OFF_ARRIVED)[threadIdx.x] = 0u;
+  }
+  float2* newpos = reinterpret_cast<float2*>(smem + M::OFF_NEWPOS) + size_t(gi) * 2 * ROWS_G;
+  uint32_t* arrived = reinterpret_cast<uint32_t*>(smem + M::OFF_ARRIVED) + gi;
+
+  // ---- registers: own agent, all agents' positions, all landmarks
+  float px = 0.0f, py = 0.0f, vx = 0.0f, vy = 0.0f;
+  float qx[N], qy[N], lx[N], ly[N];
+  int32_t ep = 0;
+#pragma unroll
+  for (int a = 0; a < N; ++a) qx[a] = qy[a] = lx[a] = ly[a] = 0.0f;
+  if (valid) {
+#pragma unroll
+    for (int a = 0; a < N; ++a) {
+      qx[a] = A.st.pos_a[(0 * N + a) * TE + g];
+      qy[a] = A.st.pos_a[(1 * N + a) * TE + g];
+      lx[a] = A.st.pos_l[(0 * N + a) * TE + g];
+      ly[a] = A.st.pos_l[(1 * N + a) * TE + g];
+    }
+    vx = A.st.vel_a[(0 * N + i) * TE + g];
+    vy = A.st.vel_a[(1 * N + i) * TE + g];
+    ep = A.st.ep_step[g];
+  }
+#pragma unroll
+  for (int a = 0; a < N; ++a) {
+    if (a == i) { px = qx[a]; py = qy[a]; }
+  }
+
+  // This lane's observation row: the KIN leading entries (the rest of the row is zero).
+  float o[16];
+  auto build_row = [&]() {
+#pragma unroll
+    for (int c = 0; c < 16; ++c) o[c] = 0.0f;
+    o[0] = vx; o[1] = vy; o[2] = px; o[3] = py;
+#pragma unroll
+    for (int l = 0; l < N; ++l) { o[4 + 2 * l] = lx[l] - px; o[5 + 2 * l] = ly[l] - py; }
+    // the k-th OTHER agent is agent k (k < i) or k + 1
+#pragma unroll
+    for (int k = 0; k < N - 1; ++k) {
+      const bool up = k >= i;
+      o[4 + 2 * N + 2 * k] = (up ? qx[k + 1] : qx[k]) - px;
+      o[5 + 2 * N + 2 * k] = (up ? qy[k + 1] : qy[k]) - py;
+    }
+  };
+  auto store_row = [&](float* dst) {   // dst: this lane's row of a [TE][N][D] slice
+    float2* d2 = reinterpret_cast<float2*>(dst);
+#pragma unroll
+    for (int c = 0; c < KIN / 2; ++c) d2[c] = make_float2(o[2 * c], o[2 * c + 1]);
+#pragma unroll
+    for (int c = KIN / 2; c < D / 2; ++c) d2[c] = make_float2(0.0f, 0.0f);
+  };
+  build_row();
+  __syncthreads();  // weights and biases staged, counters cleared; from here on wavefronts only meet at (C)
+
+  const size_t row_off = size_t(gc) * N + i;          // index of this agent inside a time slice
+  const bool env_writer = valid && i == 0;            // the lane that stores per-env outputs
+  float* obs_base = A.obs_traj;
+  uint8_t* act_base = A.act_traj;
+  float* rew_base = A.rew_traj;
+  uint8_t* done_base = A.done_traj;
+  uint32_t step = A.abs_step;
+
+  for (int t = 0; t < A.T; ++t, ++step) {
+    if (obs_base) {
+      if (valid) store_row(obs_base + row_off * D);
+      obs_base += TE * (N * D);
+    }
+    // ---- policy: the rows of tile c belong to lane group c; lane (j, gq) needs inputs 8 (gq & 1) .. + 7
+    // of row 16 c + j: the transpose of {low, high, low, high} halves of the row between register index
+    // and lane group
+    f32x4 z[4];
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) {
+      float inX[8], inY[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        uint32_t v[4] = {__float_as_uint(o[e]), __float_as_uint(o[8 + e]), __float_as_uint(o[e]), __float_as_uint(o[8 + e])};
+        transpose_groups(v);
+        inX[e] = __uint_as_float(v[2 * pr]);
+        inY[e] = __uint_as_float(v[2 * pr + 1]);
+      }
+      policy_core<Net>(wsm, bias, w3, inX, inY, z[2 * pr], z[2 * pr + 1], lane);
+    }
+    // ---- logits back to the row's lane: lane (j, gq) holds, for tile c, output gq (sum of its three
+    // term rows) and term gq of output 4
+    float zz[kNumActions];
+    {
+      uint32_t sv[4], tv[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        sv[c] = __float_as_uint((z[c][0] + z[c][1]) + z[c][2]);
+        tv[c] = __float_as_uint(z[c][3]);
+      }
+      transpose_groups(sv);
+      transpose_groups(tv);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) zz[k] = __uint_as_float(sv[k]);
+      zz[4] = (__uint_as_float(tv[0]) + __uint_as_float(tv[1])) + __uint_as_float(tv[2]);
+    }
+    const uint32_t act = gumbel_argmax(zz, A.seed, run, env, step, uint32_t(i));
+    if (act_base) {
+      if (valid) act_base[row_off] = uint8_t(act);
+      act_base += TE * N;
+    }
+
+    // ---- transition of this lane's agent
+    float fx = A.ph.accel * action_dir_x(act);
+    float fy = A.ph.accel * action_dir_y(act);
+#pragma unroll
+    for (int k = 0; k < N - 1; ++k) {
+      const bool up = k >= i;
+      const float dx = px - (up ? qx[k + 1] : qx[k]);
+      const float dy = py - (up ? qy[k + 1] : qy[k]);
+      const float kf = contact_factor(dx, dy, A.ph);
+      fx = fmaf(kf, dx, fx);
+      fy = fmaf(kf, dy, fy);
+    }
+    px = fmaf(vx, A.ph.dt, px);
+    py = fmaf(vy, A.ph.dt, py);
+    vx = fmaf(fx, A.ph.dt_over_mass, vx * A.ph.keep);
+    vy = fmaf(fy, A.ph.dt_over_mass, vy * A.ph.keep);
+    float2* np = newpos + (t & 1) * ROWS_G;
+    np[r] = make_float2(px, py);
+    // (C) new positions of every agent of every env of this 64-env group are visible
+    group_barrier(arrived, uint32_t(N) * uint32_t(t + 1), lane);
+#pragma unroll
+    for (int a = 0; a < N; ++a) {
+      const float2 p = np[el * N + a];
+      qx[a] = p.x;
+      qy[a] = p.y;
+    }
+    // shared coverage reward, evaluated by every lane (N*N distances), stored by agent 0
+    {
+      float rw = 0.0f;
+#pragma unroll
+      for (int l = 0; l < N; ++l) {
+        float best2 = INFINITY;
+#pragma unroll
+        for (int a = 0; a < N; ++a) {
+          const float dx = qx[a] - lx[l], dy = qy[a] - ly[l];
+          best2 = fminf(best2, fmaf(dx, dx, dy * dy));
+        }
+        rw -= hw_sqrt(best2);
+      }
+      if (rew_base) {
+        if (env_writer) rew_base[gc] = rw;
+        rew_base += TE;
+      }
+    }
+    ep += 1;
+    const bool done = ep >= A.ph.max_ep;
+    if (done_base) {
+      if (env_writer) done_base[gc] = done ? 1 : 0;
+      done_base += TE;
+    }
+    if (done) {
+      // new episode keyed by step + 1; every lane regenerates the whole env (1 step in max_ep)
+      uint32_t env_r = env;
+      asm volatile("" : "+v"(env_r));
+#pragma unroll
+      for (int a = 0; a < N; ++a) {
+        const uint4 w = philox4x32_10(env_r, step + 1u, uint32_t(a), kTagResetPos, A.seed, run);
+        qx[a] = word_to_position(w.x);
+        qy[a] = word_to_position(w.y);
+        const uint4 wl = philox4x32_10(env_r, step + 1u, uint32_t(N + a), kTagResetPos, A.seed, run);
+        lx[a] = word_to_position(wl.x);
+        ly[a] = word_to_position(wl.y);
+      }
+#pragma unroll
+      for (int a = 0; a < N; ++a) {
+        if (a == i) { px = qx[a]; py = qy[a]; }
+      }
+      vx = vy = 0.0f;
+      ep = 0;
+    }
+    build_row();
+  }
+  if (A.last_obs && valid) store_row(A.last_obs + row_off * D);
+
+  // ---- state back to HBM
+  if (valid) {
+    A.st.pos_a[(0 * N + i) * TE + g] = px;
+    A.st.pos_a[(1 * N + i) * TE + g] = py;
+    A.st.vel_a[(0 * N + i) * TE + g] = vx;
+    A.st.vel_a[(1 * N + i) * TE + g] = vy;
+#pragma unroll
+    for (int l = 0; l < N; ++l) {
+      if (l == i) {
+        A.st.pos_l[(0 * N + l) * TE + g] = lx[l];
+        A.st.pos_l[(1 * N + l) * TE + g] = ly[l];
+      }
+    }
+    if (i == 0) A.st.ep_step[g] = ep;
+  }
+}
+
+template <int N>
+hipError_t rollout_reg_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s) {
+  using M = SmemReg<N>;
+  auto kern = rollout_policy_f32_reg_kernel<N>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(M::TOTAL));
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const uint32_t blocks = (A.TE + 255) / 256;
+  const uint32_t per_xcd = (blocks + 7) / 8;
+  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(256 * N), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),
+                     blocks, per_xcd);
+  return hipGetLastError();
+}
+
 template <int N, int EB, int MINW, bool PER_AGENT, bool AC, bool BF>
 hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s, const void* critic = nullptr) {
   using M = SmemF32<N, EB, AC, BF>;
@@ -462,7 +734,7 @@ uint32_t compute_units() {
 // blocks are resident per CU, and with several runs every block must lie inside one run.  When
 // one run has at least one 256-env block per CU, blocks of 256 envs = four independent 64-env
 // sync groups (12 wavefronts, per-group arrival counters) fill the chip in whole rounds with no
-// tail of single resident blocks: measured 2.31 ms against 2.37 ms at 65,536 envs x 3 agents.
+// tail of single resident blocks: measured 2.06 ms against 2.37 ms at 65,536 envs x 3 agents.
 // (Two 128-env blocks per CU with ONE block barrier among six wavefronts were slower: 2.97 ms.)
 template <int N, bool BF>
 hipError_t launch_n(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s, const char** why) {
@@ -470,6 +742,16 @@ hipError_t launch_n(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s
   const bool per_agent = A.ph.reward_mode == 1;
   if (one_run && A.TE / 256 >= compute_units())
     return per_agent ? rollout_impl<N, 256, 3, true, false, BF>(A, pb, s) : rollout_impl<N, 256, 3, false, false, BF>(A, pb, s);
+  if constexpr (!BF && N >= 2) {
+    // several runs that fill the chip in (nearly) whole rounds of one block per CU: 256-env blocks of four
+    // groups, each with its own run's weights (1,024 runs x 64 envs x 3 agents: 2.04 ms against 2.44 ms
+    // with 64-env blocks; with a tail round that is mostly empty the 64-env blocks are faster)
+    if (!one_run && !per_agent && A.E % 64 == 0) {
+      const uint32_t blocks = (A.TE + 255) / 256, cus = compute_units();
+      const uint32_t rounds = (blocks + cus - 1) / cus;
+      if (blocks >= cus && uint64_t(blocks) * 10 >= uint64_t(rounds) * cus * 9) return rollout_reg_impl<N>(A, pb, s);
+    }
+  }
   if (one_run || A.E % 64 == 0)
     return per_agent ? rollout_impl<N, 64, 3, true, false, BF>(A, pb, s) : rollout_impl<N, 64, 3, false, false, BF>(A, pb, s);
   *why = "with several runs, num_envs per run must be a multiple of 64";

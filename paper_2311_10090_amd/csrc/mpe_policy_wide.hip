@@ -153,16 +153,6 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-// 4 x 4 transpose between register index and lane group (lane = 16 * group + j):
-// out[c] at lane (j, g) = in[g] at lane (j, c).
-__device__ __forceinline__ void transpose_groups(uint32_t (&v)[4]) {
-  const auto s0 = __builtin_amdgcn_permlane32_swap(v[0], v[2], false, false);   // upper half of v0 <-> lower half of v2
-  const auto s1 = __builtin_amdgcn_permlane32_swap(v[1], v[3], false, false);
-  const auto t0 = __builtin_amdgcn_permlane16_swap(s0[0], s1[0], false, false);  // odd 16-lane rows of v0 <-> even rows of v1
-  const auto t1 = __builtin_amdgcn_permlane16_swap(s0[1], s1[1], false, false);
-  v[0] = t0[0]; v[1] = t0[1]; v[2] = t1[0]; v[3] = t1[1];
-}
-
 // tanh of 8 accumulator values (hidden tiles 2s and 2s+1 of one batch tile), rounded to bf16: the
 // B operand of K slice s of the next layer (element e <-> tile 2s + e/4, register e%4).
 __device__ __forceinline__ bf16x8 tanh_pack(const f32x4& a0, const f32x4& a1) {

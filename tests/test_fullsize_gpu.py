@@ -100,17 +100,51 @@ def test_headline_shape_sampled_against_oracle(key):
 
 
 def test_per_run_weights_full_size():
+    """1,024 runs x 64 envs: the launch of 256-env blocks whose four sync groups hold the weights of four
+    different runs and whose rows live in registers.  Sampled runs against the oracle; run 0 must also
+    equal, bit for bit, a single-run job with that run's weights (the 64-env block kernel with its LDS
+    observation tile: same arithmetic, another data path)."""
+    from paper_2311_10090_amd.binding import MpeEnv
     wl = synth.WORKLOADS["cfg4"]
     say("full size %s: %d runs x %d envs" % (wl.name, wl.num_runs, wl.num_envs))
     env, out, weights = _gpu_rollout(wl, seed=1, wseed=11)
     tot = agree = 0
-    for run in (0, 1, 517, 1023):
+    for run in (0, 1, 2, 3, 517, 1023):
         ref = _oracle_range(wl, 1, run, 0, 64, weights)
         frac, cnt = _compare_range(wl, out, ref, run * 64, 64, "run %d" % run)
         agree += frac * cnt
         tot += cnt
     say("  sampled action agreement %.6f over %d samples" % (agree / tot, tot))
     assert agree / tot >= Hp.ACTION_AGREEMENT - 2.0 / tot
+    one = MpeEnv(Hp.gpu_config(64, wl.num_agents, 1, wl.hidden, 0))
+    one.set_policy(*Hp.to_dev([w[0:1] for w in weights]))
+    one.reset(1)
+    ref0 = one.rollout(wl.T, *one.empty_traj(wl.T))
+    for k in range(4):
+        assert torch.equal(out[k][:, :64], ref0[k]), "run 0, output %d" % k
+    assert torch.equal(out[4][:64], ref0[4])
+    one.close()
+    env.close()
+
+
+@pytest.mark.parametrize("N,R", [(2, 1024), (3, 1023)])
+def test_per_run_weights_other_shapes_full_size(N, R):
+    """Two agents, and a batch whose last 256-env block is ragged (1,023 runs: three groups and an empty one)."""
+    wl = synth.Workload("runs_%dx64env_n%d_mlp64_fp32" % (R, N), 64, N, R, 60, 64, 0)
+    say("full size %s" % wl.name)
+    env, out, weights = _gpu_rollout(wl, seed=2, wseed=12)
+    assert int(out[3].sum().item()) == wl.total_envs * (wl.T // synth.MAX_EPISODE_STEPS)
+    assert bool(torch.isfinite(out[0]).all()) and bool((out[1] <= 4).all())
+    tot = agree = 0
+    for run in (0, 5, R - 2, R - 1):
+        ref = _oracle_range(wl, 2, run, 0, 64, weights)
+        frac, cnt = _compare_range(wl, out, ref, run * 64, 64, "run %d" % run)
+        agree += frac * cnt
+        tot += cnt
+    say("  sampled action agreement %.6f over %d samples" % (agree / tot, tot))
+    assert agree / tot >= Hp.ACTION_AGREEMENT - 2.0 / tot
+    s = env.get_state()
+    assert bool(torch.isfinite(s[0]).all()) and int(s[4]) == wl.T
     env.close()
 
 
