@@ -298,7 +298,8 @@ def main():
         "env_steps_per_s": value / N,
         "value_by_seed": by_seed,
         "roofline": {
-            "kernel": ("rollout_policy_f32_kernel" if wl.weight_dtype == 0 else "rollout_policy_kernel")
+            "kernel": (("rollout_policy_f32_reg_kernel" if wl.num_runs > 1 and wl.num_envs % 64 == 0 and TE >= 65536
+                        else "rollout_policy_f32_kernel") if wl.weight_dtype == 0 else "rollout_policy_kernel")
                       + " (fused, one launch per step)",
             # fp32 shape: the contraction's fp32 FLOPs against the chip's fp32 matrix peak (the
             # kernel runs them on the bf16 matrix cores with an exact 3-term operand split)
