@@ -127,18 +127,19 @@ def test_per_run_weights_full_size():
     env.close()
 
 
-@pytest.mark.parametrize("N,R", [(2, 1024), (3, 1023)])
-def test_per_run_weights_other_shapes_full_size(N, R):
-    """Two agents, and a batch whose last 256-env block is ragged (1,023 runs: three groups and an empty one)."""
-    wl = synth.Workload("runs_%dx64env_n%d_mlp64_fp32" % (R, N), 64, N, R, 60, 64, 0)
+@pytest.mark.parametrize("N,R,E", [(2, 1024, 64), (3, 1023, 64), (3, 512, 128)])
+def test_per_run_weights_other_shapes_full_size(N, R, E):
+    """Two agents; a batch whose last 256-env block is ragged (1,023 runs: three groups and an empty one);
+    runs of 128 envs (two sync groups of a block share a run)."""
+    wl = synth.Workload("runs_%dx%denv_n%d_mlp64_fp32" % (R, E, N), E, N, R, 60, 64, 0)
     say("full size %s" % wl.name)
     env, out, weights = _gpu_rollout(wl, seed=2, wseed=12)
     assert int(out[3].sum().item()) == wl.total_envs * (wl.T // synth.MAX_EPISODE_STEPS)
     assert bool(torch.isfinite(out[0]).all()) and bool((out[1] <= 4).all())
     tot = agree = 0
     for run in (0, 5, R - 2, R - 1):
-        ref = _oracle_range(wl, 2, run, 0, 64, weights)
-        frac, cnt = _compare_range(wl, out, ref, run * 64, 64, "run %d" % run)
+        ref = _oracle_range(wl, 2, run, E - 64, 64, weights)
+        frac, cnt = _compare_range(wl, out, ref, run * E + E - 64, 64, "run %d" % run)
         agree += frac * cnt
         tot += cnt
     say("  sampled action agreement %.6f over %d samples" % (agree / tot, tot))
