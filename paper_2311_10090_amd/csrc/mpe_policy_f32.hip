@@ -416,7 +416,7 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
 // leaves no room for observation tiles, so a lane keeps its row in registers and stores it to the
 // trajectory itself, and the layer-1 operands and the logits travel between the row's lane and the
 // matrix layout by 4 x 4 lane-group transposes (permlane swaps, no memory).  Same arithmetic, in
-// the same order, as the kernel above: results are bit-identical.  fp32 weights, shared reward,
+// the same order, as the kernel above: results are bit-identical.  fp32 weights, either reward,
 // N = 2 or 3 (layer 3 in the row-term layout), runs of a multiple of 64 envs.
 // --------------------------------------------------------------------------------------
 template <int N>
@@ -429,7 +429,7 @@ struct SmemReg {
   static_assert(GROUP_W % 16 == 0 && TOTAL <= 160 * 1024, "LDS");
 };
 
-template <int N>
+template <int N, bool PER_AGENT>
 __global__ __launch_bounds__(256 * N, 1) void rollout_policy_f32_reg_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
                                                                             uint32_t blocks, uint32_t blocks_per_xcd) {
   using M = SmemReg<N>;
@@ -612,7 +612,20 @@ __global__ __launch_bounds__(256 * N, 1) void rollout_policy_f32_reg_kernel(Roll
         }
         rw -= hw_sqrt(best2);
       }
-      if (rew_base) {
+      if constexpr (PER_AGENT) {
+        uint32_t overlaps = 0;
+#pragma unroll
+        for (int a = 0; a < N; ++a) {
+          if (a != i) {
+            const float dx = px - qx[a], dy = py - qy[a];
+            overlaps += fmaf(dx, dx, dy * dy) < A.ph.two_r_sq ? 1u : 0u;
+          }
+        }
+        if (rew_base) {
+          if (valid) rew_base[row_off] = mixed_reward(rw, overlaps, A.ph);
+          rew_base += TE * N;
+        }
+      } else if (rew_base) {
         if (env_writer) rew_base[gc] = rw;
         rew_base += TE;
       }
@@ -664,10 +677,10 @@ __global__ __launch_bounds__(256 * N, 1) void rollout_policy_f32_reg_kernel(Roll
   }
 }
 
-template <int N>
+template <int N, bool PER_AGENT>
 hipError_t rollout_reg_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s) {
   using M = SmemReg<N>;
-  auto kern = rollout_policy_f32_reg_kernel<N>;
+  auto kern = rollout_policy_f32_reg_kernel<N, PER_AGENT>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -746,10 +759,11 @@ hipError_t launch_n(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s
     // several runs that fill the chip in (nearly) whole rounds of one block per CU: 256-env blocks of four
     // groups, each with its own run's weights (1,024 runs x 64 envs x 3 agents: 2.04 ms against 2.44 ms
     // with 64-env blocks; with a tail round that is mostly empty the 64-env blocks are faster)
-    if (!one_run && !per_agent && A.E % 64 == 0) {
+    if (!one_run && A.E % 64 == 0) {
       const uint32_t blocks = (A.TE + 255) / 256, cus = compute_units();
       const uint32_t rounds = (blocks + cus - 1) / cus;
-      if (blocks >= cus && uint64_t(blocks) * 10 >= uint64_t(rounds) * cus * 9) return rollout_reg_impl<N>(A, pb, s);
+      if (blocks >= cus && uint64_t(blocks) * 10 >= uint64_t(rounds) * cus * 9)
+        return per_agent ? rollout_reg_impl<N, true>(A, pb, s) : rollout_reg_impl<N, false>(A, pb, s);
     }
   }
   if (one_run || A.E % 64 == 0)

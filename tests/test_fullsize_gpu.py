@@ -216,10 +216,31 @@ def test_large_size_one_and_two_agents_use_256_env_blocks(N):
     env.close()
 
 
+def _compare_mixed_rewards(outs, ref, g0, n, N, T, what):
+    """Rewards on the first steps of each episode, for envs whose actions so far agree, leaving out agents
+    within 1e-4 of the overlap threshold; episode starts bit-exact.  Returns the number compared."""
+    obs, act, rew = outs[0], outs[1], outs[2]
+    robs, ract, rrew, rdone, rlast = ref
+    a = act[:, g0:g0 + n].cpu().numpy()
+    r = rew[:, g0:g0 + n].cpu().numpy()
+    o = obs[:, g0:g0 + n].cpu().numpy()
+    compared = 0
+    for t0 in (0, 25):
+        for t in range(t0, min(t0 + 4, T - 1)):
+            alive = (a[t0:t + 1] == ract[t0:t + 1]).all(axis=(0, 2))
+            # positions after step t = own-position entries of the next observation (no reset inside)
+            pos = robs[t + 1][:, :, 2:4]
+            d = np.linalg.norm(pos[:, :, None, :] - pos[:, None, :, :], axis=3)
+            d[:, np.arange(N), np.arange(N)] = np.inf
+            mask = (np.abs(d - 0.3) > 1e-4).all(axis=2) & alive[:, None]
+            assert np.abs(r[t][mask] - rrew[t][mask]).max() <= Hp.EPISODE_ATOL, "%s, t=%d" % (what, t)
+            compared += int(mask.sum())
+    assert np.array_equal(o[0].astype(np.float64), robs[0]) and np.array_equal(o[25].astype(np.float64), robs[25]), what
+    return compared
+
+
 def test_large_size_mixed_reward():
-    """Mixed per-agent reward through the 256-env block path, sampled against the oracle.  Rewards
-    are compared on the first steps of each episode, for envs whose actions so far agree, leaving
-    out agents within 1e-4 of the overlap threshold."""
+    """Mixed per-agent reward through the 256-env block path, sampled against the oracle."""
     from paper_2311_10090_amd.binding import MpeEnv
     from oracle import Oracle
     E, N, T = 65610, 3, 30
@@ -228,30 +249,48 @@ def test_large_size_mixed_reward():
     env = MpeEnv(Hp.gpu_config(E, N, 1, 64, 0, reward_mode=1, local_ratio=0.5))
     env.set_policy(*Hp.to_dev(w))
     env.reset(3)
-    obs, act, rew, done, last = env.rollout(T, *env.empty_traj(T))
-    assert rew.shape == (T, E, N)
+    outs = env.rollout(T, *env.empty_traj(T))
+    assert outs[2].shape == (T, E, N)
     compared = 0
     for off, n in ((0, 64), (65536 - 20, 40), (65600, 10), (40000, 64)):
         orc = Oracle(Hp.oracle_config(n, N, 1, 64, 0, env_offset=off, reward_mode=1, local_ratio=0.5), threads=8)
         orc.set_policy(*w)
         orc.reset(3)
-        robs, ract, rrew, rdone, rlast = orc.rollout(T)
-        a = act[:, off:off + n].cpu().numpy()
-        r = rew[:, off:off + n].cpu().numpy()
-        o = obs[:, off:off + n].cpu().numpy()
-        for t0 in (0, 25):
-            for t in range(t0, min(t0 + 4, T - 1)):
-                alive = (a[t0:t + 1] == ract[t0:t + 1]).all(axis=(0, 2))
-                # positions after step t = own-position entries of the next observation (no reset inside)
-                pos = robs[t + 1][:, :, 2:4]
-                d = np.linalg.norm(pos[:, :, None, :] - pos[:, None, :, :], axis=3)
-                d[:, np.arange(N), np.arange(N)] = np.inf
-                mask = (np.abs(d - 0.3) > 1e-4).all(axis=2) & alive[:, None]
-                assert np.abs(r[t][mask] - rrew[t][mask]).max() <= Hp.EPISODE_ATOL, "t=%d envs %d.." % (t, off)
-                compared += int(mask.sum())
-        assert np.array_equal(o[0].astype(np.float64), robs[0]) and np.array_equal(o[25].astype(np.float64), robs[25])
+        compared += _compare_mixed_rewards(outs, orc.rollout(T), off, n, N, T, "envs %d.." % off)
     say("  %d agent rewards compared" % compared)
     assert compared > 3000
+    env.close()
+
+
+def test_per_run_weights_mixed_reward_full_size():
+    """1,024 runs x 64 envs with the mixed per-agent reward (the register-row launch): sampled runs against
+    the oracle, and run 0 bit for bit against a single-run job with that run's weights."""
+    from paper_2311_10090_amd.binding import MpeEnv
+    from oracle import Oracle
+    E, N, R, T = 64, 3, 1024, 30
+    say("full size mixed reward, %d runs x %d envs" % (R, E))
+    w = synth.policy_weights_with_bias(6, R, 18, 64)
+    env = MpeEnv(Hp.gpu_config(E, N, R, 64, 0, reward_mode=1, local_ratio=0.5))
+    env.set_policy(*Hp.to_dev(w))
+    env.reset(4)
+    outs = env.rollout(T, *env.empty_traj(T))
+    assert outs[2].shape == (T, E * R, N)
+    compared = 0
+    for run in (0, 3, 514, R - 1):
+        orc = Oracle(Hp.oracle_config(E, N, 1, 64, 0, run_offset=run, reward_mode=1, local_ratio=0.5), threads=8)
+        orc.set_policy(*[x[run:run + 1] for x in w])
+        orc.reset(4)
+        compared += _compare_mixed_rewards(outs, orc.rollout(T), run * E, E, N, T, "run %d" % run)
+    say("  %d agent rewards compared" % compared)
+    assert compared > 3000
+    one = MpeEnv(Hp.gpu_config(E, N, 1, 64, 0, reward_mode=1, local_ratio=0.5))
+    one.set_policy(*Hp.to_dev([x[0:1] for x in w]))
+    one.reset(4)
+    ref0 = one.rollout(T, *one.empty_traj(T))
+    for k in range(4):
+        assert torch.equal(outs[k][:, :E], ref0[k]), "run 0, output %d" % k
+    assert torch.equal(outs[4][:E], ref0[4])
+    one.close()
     env.close()
 
 
