@@ -20,7 +20,10 @@
  *     enqueued work has run (mpe_set_policy copies the weights into its own buffers);
  *   - `stream` is a hipStream_t (NULL = the default stream); work is enqueued on it and the
  *     call returns without waiting; calls on one handle must be stream-ordered by the caller;
- *   - arguments are validated on the host before any device work is enqueued.
+ *   - arguments are validated on the host before any device work is enqueued;
+ *   - a handle belongs to the device that is current when mpe_create is called: make every later
+ *     call on it with that device current (the library never changes the current device), with
+ *     pointers and a stream of that device.
  *
  * Sizes: E = num_envs (per run), R = num_runs, TE = R*E, N = num_agents, L = num_landmarks
  * (= N), D = 4 + 2L + 4(N-1) = 6N floats per observation, A = 5 actions.
@@ -140,7 +143,8 @@ int mpe_reset(mpe_env* env, uint32_t seed, float* obs, void* stream);
  * done:    [TE] uint8 out, 1 when the episode reached max_episode_steps; that env has then
  *          already been reset with counter (env, abs_step + 1, entity, 0).
  * reward and done may be NULL.  Advances the absolute step counter by 1.
- * MPE_ESTATE if neither mpe_reset nor mpe_set_state has been called. */
+ * MPE_ESTATE if neither mpe_reset nor mpe_set_state has been called; MPE_EINVAL if the absolute
+ * step counter (a 32-bit word of the Philox counter) would pass 2^32 - 1. */
 int mpe_step(mpe_env* env, const uint8_t* actions, float* obs, float* reward, uint8_t* done,
              void* stream);
 
@@ -165,7 +169,8 @@ int mpe_set_policy(mpe_env* env, const float* W1, const float* b1, const float* 
  * ([T][TE][N] with MPE_REWARD_MIXED and MPE_SCENARIO_TAG), done_traj [T][TE] uint8, last_obs [TE][N][D] fp32
  * (observation after the last step).
  * Any of the five may be NULL (that output is then not written).
- * T >= 1.  Advances the absolute step counter by T.  MPE_ESTATE as for mpe_step. */
+ * T >= 1.  Advances the absolute step counter by T.  MPE_ESTATE and the counter's limit as for
+ * mpe_step. */
 int mpe_rollout(mpe_env* env, int32_t T, float* obs_traj, uint8_t* act_traj, float* rew_traj,
                 uint8_t* done_traj, float* last_obs, void* stream);
 

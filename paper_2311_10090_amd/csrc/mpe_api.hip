@@ -211,6 +211,7 @@ int mpe_step(mpe_env* e, const uint8_t* actions, float* obs, float* reward, uint
   if (!e->ready) return fail(MPE_ESTATE, "mpe_step: call mpe_reset or mpe_set_state first");
   if ((obs && !aligned16(obs)) || (reward && !aligned16(reward)))
     return fail(MPE_EINVAL, "mpe_step: obs and reward must be 16-byte aligned");
+  if (e->abs_step == 0xFFFFFFFFu) return fail(MPE_EINVAL, "mpe_step: absolute step counter would overflow 32 bits");
   if (e->tag) {
     TagArgs A{};
     A.r.st = e->st;

@@ -1,9 +1,25 @@
 // Host-side launch interface between the C ABI (mpe_api.hip) and the kernel files.
 #pragma once
 
+#include <atomic>
+
 #include "mpe_device.h"
 
 namespace mpe {
+
+// A kernel that needs more than 64 KB of dynamic LDS must be allowed to, once per device it is
+// launched on (function attributes belong to the device's copy of the code).  `done` holds one bit
+// per device ordinal; setting the attribute twice from two threads is harmless.
+inline hipError_t allow_lds(const void* kern, size_t bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = 1ull << (unsigned(dev) & 63u);
+  if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+  e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, int(bytes));
+  if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
 
 struct RolloutArgs {
   StatePtrs st;

@@ -681,13 +681,8 @@ template <int N, bool PER_AGENT>
 hipError_t rollout_reg_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s) {
   using M = SmemReg<N>;
   auto kern = rollout_policy_f32_reg_kernel<N, PER_AGENT>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(M::TOTAL));
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_allowed{0};
+  if (hipError_t e = allow_lds(reinterpret_cast<const void*>(kern), M::TOTAL, lds_allowed); e != hipSuccess) return e;
   const uint32_t blocks = (A.TE + 255) / 256;
   const uint32_t per_xcd = (blocks + 7) / 8;
   hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(256 * N), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),
@@ -699,13 +694,8 @@ template <int N, int EB, int MINW, bool PER_AGENT, bool AC, bool BF>
 hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s, const void* critic = nullptr) {
   using M = SmemF32<N, EB, AC, BF>;
   auto kern = rollout_policy_f32_kernel<N, EB, MINW, PER_AGENT, AC, BF>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(M::TOTAL));
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_allowed{0};
+  if (hipError_t e = allow_lds(reinterpret_cast<const void*>(kern), M::TOTAL, lds_allowed); e != hipSuccess) return e;
   const uint32_t groups = (A.TE + EB - 1) / EB;
   const uint32_t per_xcd = (groups + 7) / 8;
   hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(EB * N), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),

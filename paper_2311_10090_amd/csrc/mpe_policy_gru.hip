@@ -481,13 +481,8 @@ template <int N>
 hipError_t rollout_gru_impl(const RolloutArgs& A, const PolicyBuffers& pb, float* hidden, hipStream_t s) {
   using M = GruSmem<N>;
   auto kern = rollout_gru_kernel<N>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(M::TOTAL));
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_allowed{0};
+  if (hipError_t e = allow_lds(reinterpret_cast<const void*>(kern), M::TOTAL, lds_allowed); e != hipSuccess) return e;
   const uint32_t groups = (A.TE + 63) / 64;
   const uint32_t per_xcd = (groups + 7) / 8;
   hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(512), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),

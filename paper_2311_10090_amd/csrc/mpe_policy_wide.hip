@@ -594,13 +594,8 @@ template <int N, int H, int EB, int MINW, bool PER_AGENT, bool UNIFORM = false>
 hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s) {
   using M = Smem<N, H, EB, UNIFORM>;
   auto kern = rollout_policy_kernel<N, H, EB, MINW, PER_AGENT, UNIFORM>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(M::TOTAL));
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_allowed{0};
+  if (hipError_t e = allow_lds(reinterpret_cast<const void*>(kern), M::TOTAL, lds_allowed); e != hipSuccess) return e;
   const uint32_t groups = (A.TE + EB - 1) / EB;
   const uint32_t per_xcd = (groups + 7) / 8;
   hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(EB * N), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),

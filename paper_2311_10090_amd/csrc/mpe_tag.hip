@@ -483,13 +483,8 @@ template <typename S, int MODE, int EB = 64>
 hipError_t tag_rollout_impl(const TagArgs& A, const void* packed, const void* packed_critic, hipStream_t s) {
   using M = TagSmem<S, MODE, EB>;
   auto kern = tag_rollout_kernel<S, MODE, EB>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, int(M::TOTAL));
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<uint64_t> lds_allowed{0};
+  if (hipError_t e = allow_lds(reinterpret_cast<const void*>(kern), M::TOTAL, lds_allowed); e != hipSuccess) return e;
   const uint32_t groups = (A.r.TE + EB - 1) / EB;
   const uint32_t per_xcd = (groups + 7) / 8;
   hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(EB * S::N), M::TOTAL, s, A, static_cast<const uint8_t*>(packed),

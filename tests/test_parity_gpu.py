@@ -564,6 +564,11 @@ def test_step_counter_near_the_top_of_its_range(mods, N, H):
     with pytest.raises(MpeError) as ei:
         env.rollout(20)
     assert ei.value.code == MPE_EINVAL
+    env.rollout(10)                                   # up to the last value the counter can hold
+    assert env.get_state()[4] == 0xFFFFFFFF
+    with pytest.raises(MpeError) as ei:
+        env.step(torch.zeros(E, N, dtype=torch.uint8, device="cuda"))
+    assert ei.value.code == MPE_EINVAL
     env.close()
 
 
