@@ -74,16 +74,23 @@ __device__ __forceinline__ void group_barrier(uint32_t* arrived, uint32_t target
 // is evaluated on every observation acted on, and the log-probability of the sampled action is
 // recorded (paper Sec. 3.2: IPPO / MAPPO; App. G: two tanh layers of width 64).  A block is then
 // EB / 64 independent 64-env sync groups that share the two staged networks.
-template <int N, int EB, int MINW, bool PER_AGENT, bool AC, bool BF>
-__global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
+//
+// RW = rows per wavefront.  64: one lane per row.  32 (64-env blocks only, for batches that leave CUs
+// empty): twice the wavefronts, each with ONE pair of 16-row tiles; lanes 32..63 are exact clones of
+// lanes 0..31 (same row, same inputs, same arithmetic, so their LDS writes repeat the same values)
+// that store nothing to global memory.  The step latency of a block, which is all that matters when
+// every block has a CU to itself, is then one pair of tiles plus the env step instead of two pairs.
+template <int N, int EB, int MINW, bool PER_AGENT, bool AC, bool BF, int RW = 64>
+__global__ __launch_bounds__(EB * N * (64 / RW), MINW) void rollout_policy_f32_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
                                                                           const uint8_t* __restrict__ packed_critic,
                                                                           int per_run_weights, uint32_t groups,
                                                                           uint32_t groups_per_xcd) {
   using M = SmemF32<N, EB, AC, BF>;
   using P = PkT<BF>;
 
-  constexpr int D = 6 * N, ROWS = EB * N, THREADS = ROWS;
+  constexpr int D = 6 * N, ROWS = EB * N, THREADS = ROWS * (64 / RW);
   static_assert(THREADS % 64 == 0, "block must be whole wavefronts");
+  static_assert(RW == 64 || (RW == 32 && EB <= 64), "half-filled wavefronts only in blocks of one sync group");
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   uint8_t* wsm = smem;
   float* bias = reinterpret_cast<float*>(smem + M::OFF_BIAS);
@@ -102,9 +109,9 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
   // `wave` and `tid` below are these virtual indices: row = tid.
   const int lane = threadIdx.x & 63;
   const int hw_wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
-  constexpr int kGroups = EB / 64;
+  constexpr int kGroups = EB > 64 ? EB / 64 : 1;
   const int wave = kGroups > 1 ? (hw_wave % kGroups) * N + hw_wave / kGroups : hw_wave;
-  const int tid = wave * 64 + lane;
+  const int tid = wave * RW + (lane & (RW - 1));     // this lane's row
   const int el = tid / N, i = tid - el * N;          // env within block, agent
   const size_t TE = A.TE;
   // XCD-aware mapping: the hardware deals block b to XCD b % 8; giving each XCD one contiguous
@@ -114,14 +121,15 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
   if (grp >= groups) return;  // whole block, before any barrier
   const size_t g0 = size_t(grp) * EB;
   const size_t g = g0 + el;
-  const bool valid = g < TE;
-  const uint32_t gc = valid ? uint32_t(g) : uint32_t(g0);
+  const bool in_range = g < TE;
+  const bool valid = in_range && lane < RW;          // the lane that stores this row's outputs
+  const uint32_t gc = in_range ? uint32_t(g) : uint32_t(g0);
   const uint32_t run = gc / A.E;
   const uint32_t env = gc - run * A.E;
   const size_t left = TE - g0;
   const int nvalid = left < size_t(EB) ? int(left) : EB;   // valid envs in this block
   // rows of this wavefront that belong to valid envs
-  const int wave_rows = min(max(nvalid * N - wave * 64, 0), 64);
+  const int wave_rows = min(max(nvalid * N - wave * RW, 0), RW);
 
   // ---- stage this block's weights (the run of its first env): W1A, W2A, biases in LDS; W3A in registers
   const uint8_t* run_weights = packed + (per_run_weights ? size_t(uint32_t(g0) / A.E) * P::RUN_BYTES : 0);
@@ -148,20 +156,20 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
     const uint4* src = reinterpret_cast<const uint4*>(run_weights);
     uint4* dst = reinterpret_cast<uint4*>(wsm);
     if constexpr (AC) {
-      for (int k = tid; k < int(P::RUN_BYTES / 16); k += THREADS) dst[k] = src[k];
+      for (int k = threadIdx.x; k < int(P::RUN_BYTES / 16); k += THREADS) dst[k] = src[k];
       const uint4* csrc = reinterpret_cast<const uint4*>(
           packed_critic + (per_run_weights ? size_t(uint32_t(g0) / A.E) * P::RUN_BYTES : 0));
       uint4* cdst = reinterpret_cast<uint4*>(smem + M::OFF_CRITIC);
-      for (int k = tid; k < int(P::RUN_BYTES / 16); k += THREADS) cdst[k] = csrc[k];
+      for (int k = threadIdx.x; k < int(P::RUN_BYTES / 16); k += THREADS) cdst[k] = csrc[k];
     } else {
-      for (int k = tid; k < int(P::LDS_BYTES / 16); k += THREADS) dst[k] = src[k];
+      for (int k = threadIdx.x; k < int(P::LDS_BYTES / 16); k += THREADS) dst[k] = src[k];
       const uint4* bsrc = reinterpret_cast<const uint4*>(run_weights + P::OFF_BIAS);
       uint4* bdst = reinterpret_cast<uint4*>(bias);
-      for (int k = tid; k < int(P::BIAS_BYTES / 16); k += THREADS) bdst[k] = bsrc[k];
+      for (int k = threadIdx.x; k < int(P::BIAS_BYTES / 16); k += THREADS) bdst[k] = bsrc[k];
     }
-    if (tid < 16) tile[ROWS * D + tid] = 0.0f;
+    if (threadIdx.x < 16) tile[ROWS * D + threadIdx.x] = 0.0f;
     if constexpr (EB > 64) {
-      if (tid < EB / 64) reinterpret_cast<uint32_t*>(smem + M::OFF_ARRIVED)[tid] = 0u;
+      if (threadIdx.x < EB / 64) reinterpret_cast<uint32_t*>(smem + M::OFF_ARRIVED)[threadIdx.x] = 0u;
     }
   }
 
@@ -171,7 +179,7 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
   int32_t ep = 0;
 #pragma unroll
   for (int a = 0; a < N; ++a) qx[a] = qy[a] = lx[a] = ly[a] = 0.0f;
-  if (valid) {
+  if (in_range) {
 #pragma unroll
     for (int a = 0; a < N; ++a) {
       qx[a] = A.st.pos_a[(0 * N + a) * TE + g];
@@ -209,7 +217,7 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
 
   // Output addresses = uniform per-step base (advanced once per step, lives in SGPRs) + a
   // 32-bit lane offset that never changes.
-  const size_t wave_row0 = (g0 * N + size_t(wave) * 64) * D;   // float offset of this wavefront's rows in a slice
+  const size_t wave_row0 = (g0 * N + size_t(wave) * RW) * D;   // float offset of this wavefront's rows in a slice
   float* obs_p = A.obs_traj ? A.obs_traj + wave_row0 : nullptr;
   uint8_t* act_base = A.act_traj;
   float* rew_base = A.rew_traj;
@@ -219,15 +227,15 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
   const uint32_t row_off = uint32_t(gc) * N + i;      // index of this agent inside a time slice
   const bool env_writer = valid && i == 0;            // the lane that stores per-env outputs
   uint32_t step = A.abs_step;
-  const float* wtile = tile + wave * (64 * D);        // this wavefront's rows
+  const float* wtile = tile + wave * (RW * D);        // this wavefront's rows
   uint32_t* arrived = reinterpret_cast<uint32_t*>(smem + M::OFF_ARRIVED) + wave / N;   // EB > 64 only
 
   // Critic forward of this wavefront's rows: values[row] (wave-local rows).
   auto critic_rows = [&]() {
 #pragma unroll 1
-    for (int pr = 0; pr < 2; ++pr) {
-      float* rows = tile + (wave * 64 + pr * 32) * D;
-      float* vals = values + wave * 64 + pr * 32;
+    for (int pr = 0; pr < RW / 32; ++pr) {
+      float* rows = tile + (wave * RW + pr * 32) * D;
+      float* vals = values + wave * RW + pr * 32;
       const W3Terms wc = load_w3(csm);
       if constexpr (BF) policy_pair_bf<SpreadNet<N>, true>(csm, cbias, wc, rows, rows + 16 * D, lane, vals, vals + 16);
       else policy_pair<SpreadNet<N>, true>(csm, cbias, wc, rows, rows + 16 * D, lane, vals, vals + 16);
@@ -237,7 +245,7 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
   // Stream this wavefront's rows of the tile to dst (its slot in a [env][N][D] slice).
   auto flush_rows = [&](float* dst) {
     const bool vec4 = (reinterpret_cast<uintptr_t>(dst) & 15u) == 0;
-    if (vec4 && wave_rows == 64) stream_out_full<64 * D / 4>(wtile, dst, lane);
+    if (vec4 && wave_rows == RW) stream_out_full<RW * D / 4>(wtile, dst, lane);
     else stream_out(wtile, dst, wave_rows * D, vec4, lane);
   };
 
@@ -251,8 +259,8 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
     // first columns of the rows: two pairs of 16-row tiles per wavefront each
     if constexpr (AC) critic_rows();
 #pragma unroll 1
-    for (int pr = 0; pr < 2; ++pr) {
-      float* rows = tile + (wave * 64 + pr * 32) * D;
+    for (int pr = 0; pr < RW / 32; ++pr) {
+      float* rows = tile + (wave * RW + pr * 32) * D;
       if constexpr (AC) w3 = load_w3(wsm);
       if constexpr (BF) policy_pair_bf<SpreadNet<N>>(wsm, bias, w3, rows, rows + 16 * D, lane);
       else policy_pair<SpreadNet<N>>(wsm, bias, w3, rows, rows + 16 * D, lane);
@@ -309,7 +317,7 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_f32_kernel(Rollou
     float2* np = newpos + (t & 1) * ROWS;
     np[tid] = make_float2(px, py);
     // (C) new positions of every agent of every env of this 64-env group are visible
-    if constexpr (EB == 64) __syncthreads();
+    if constexpr (EB <= 64) __syncthreads();
     else if constexpr (N > 1) group_barrier(arrived, uint32_t(N) * uint32_t(t + 1), lane);
     else wave_sync();
 
@@ -690,16 +698,17 @@ hipError_t rollout_reg_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipSt
   return hipGetLastError();
 }
 
-template <int N, int EB, int MINW, bool PER_AGENT, bool AC, bool BF>
+template <int N, int EB, int MINW, bool PER_AGENT, bool AC, bool BF, int RW = 64>
 hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s, const void* critic = nullptr) {
   using M = SmemF32<N, EB, AC, BF>;
-  auto kern = rollout_policy_f32_kernel<N, EB, MINW, PER_AGENT, AC, BF>;
+  auto kern = rollout_policy_f32_kernel<N, EB, MINW, PER_AGENT, AC, BF, RW>;
   static std::atomic<uint64_t> lds_allowed{0};
   if (hipError_t e = allow_lds(reinterpret_cast<const void*>(kern), M::TOTAL, lds_allowed); e != hipSuccess) return e;
   const uint32_t groups = (A.TE + EB - 1) / EB;
   const uint32_t per_xcd = (groups + 7) / 8;
-  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(EB * N), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),
-                     static_cast<const uint8_t*>(critic), int(A.TE != A.E), groups, per_xcd);
+  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(EB * N * (64 / RW)), M::TOTAL, s, A,
+                     static_cast<const uint8_t*>(pb.packed), static_cast<const uint8_t*>(critic), int(A.TE != A.E), groups,
+                     per_xcd);
   return hipGetLastError();
 }
 
@@ -733,6 +742,35 @@ uint32_t compute_units() {
   return uint32_t(cus);
 }
 
+// Small batches: when every block has a CU (nearly) to itself, the time of a rollout is the step latency of
+// one block (one wavefront per SIMD running its matrix and vector instructions back to back), so the rows
+// are spread over more wavefronts of 32 rows = one pair of 16-row tiles each, one wavefront per SIMD where
+// that works out.  Measured per 128-step rollout, against N wavefronts of 64 rows:
+//   64 envs x 1 or 2 agents = 2 or 4 wavefronts: 0.48 / 0.50 ms against 0.76 / 0.77 ms up to one block per
+//     CU, still 1.07x / 1.18x at three blocks per CU (the most that are resident);
+//   32 envs x 3 agents = 3 wavefronts, while such blocks have a CU each (8,192 envs): 0.51 against 0.81 ms
+//     (actor-critic 0.85 against 1.51 ms);
+//   64 envs x 3 agents = 6 wavefronts, two SIMDs with two: 0.73 against 0.82 ms up to one block per CU,
+//     slower beyond.
+enum SmallShape { kRegular = 0, kHalf64 = 1, kHalf32 = 2 };
+template <int N>
+SmallShape small_shape(const RolloutArgs& A) {
+  const uint32_t cus = compute_units();
+  if (N == 3 && (A.TE + 31) / 32 <= cus) return kHalf32;
+  if ((A.TE + 63) / 64 <= (N == 3 ? cus : 4 * cus)) return kHalf64;
+  return kRegular;
+}
+
+template <int N, bool PER_AGENT, bool AC, bool BF>
+hipError_t launch_blocks64(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s, const void* critic) {
+  const SmallShape shape = small_shape<N>(A);
+  if constexpr (N == 3) {
+    if (shape == kHalf32) return rollout_impl<N, 32, 1, PER_AGENT, AC, BF, 32>(A, pb, s, critic);
+  }
+  if (shape == kHalf64) return rollout_impl<N, 64, 1, PER_AGENT, AC, BF, 32>(A, pb, s, critic);
+  return rollout_impl<N, 64, 3, PER_AGENT, AC, BF>(A, pb, s, critic);
+}
+
 // Envs per block.  64 (N wavefronts, one block barrier per step) is the general shape: three
 // blocks are resident per CU, and with several runs every block must lie inside one run.  When
 // one run has at least one 256-env block per CU, blocks of 256 envs = four independent 64-env
@@ -757,7 +795,8 @@ hipError_t launch_n(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s
     }
   }
   if (one_run || A.E % 64 == 0)
-    return per_agent ? rollout_impl<N, 64, 3, true, false, BF>(A, pb, s) : rollout_impl<N, 64, 3, false, false, BF>(A, pb, s);
+    return per_agent ? launch_blocks64<N, true, false, BF>(A, pb, s, nullptr)
+                     : launch_blocks64<N, false, false, BF>(A, pb, s, nullptr);
   *why = "with several runs, num_envs per run must be a multiple of 64";
   return hipSuccess;
 }
@@ -775,8 +814,8 @@ hipError_t launch_ac_n(const RolloutArgs& A, const PolicyBuffers& pb, const Poli
     return per_agent ? rollout_impl<N, 256, 3, true, true, BF>(A, pb, s, critic.packed)
                      : rollout_impl<N, 256, 3, false, true, BF>(A, pb, s, critic.packed);
   if (one_run || A.E % 64 == 0)
-    return per_agent ? rollout_impl<N, 64, 3, true, true, BF>(A, pb, s, critic.packed)
-                     : rollout_impl<N, 64, 3, false, true, BF>(A, pb, s, critic.packed);
+    return per_agent ? launch_blocks64<N, true, true, BF>(A, pb, s, critic.packed)
+                     : launch_blocks64<N, false, true, BF>(A, pb, s, critic.packed);
   *why = "with several runs, num_envs per run must be a multiple of 64";
   return hipSuccess;
 }

@@ -1,0 +1,90 @@
+"""The fused feed-forward rollout picks its block shape by batch size (32- or 64-env blocks with 32-row
+wavefronts for small batches, 64-env blocks with 64-row wavefronts, 256-env blocks of four sync groups).
+All shapes run the same arithmetic in the same order and an env's trajectory depends only on (seed, run,
+env index), so jobs of different sizes must agree bit for bit on the envs they share; sampled ranges of
+every job, including its ragged tail, are also compared with the oracle."""
+import numpy as np
+import pytest
+
+from tests import helpers as Hp
+from paper_2311_10090_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+T = 30
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+@pytest.fixture(scope="module")
+def mods():
+    if not torch.cuda.is_available():
+        pytest.fail("gpu tests need a device; the library has no CPU fallback")
+    from paper_2311_10090_amd.binding import MpeEnv
+    from oracle import Oracle
+    return MpeEnv, Oracle
+
+
+def _job(mods, E, N, wd, mixed, ac, w, cw, seed):
+    env = mods[0](Hp.gpu_config(E, N, 1, 64, wd, reward_mode=1 if mixed else 0, local_ratio=0.5))
+    env.set_policy(*Hp.to_dev(w))
+    if ac:
+        env.set_critic(*Hp.to_dev(cw))
+    env.reset(seed)
+    out = env.rollout_ac(T, *env.empty_traj_ac(T)) if ac else env.rollout(T, *env.empty_traj(T))
+    state = env.get_state()
+    torch.cuda.synchronize()
+    env.close()
+    return out, state
+
+
+# sizes: N = 3: 32-env blocks up to 8,192 envs, 64-env blocks of six wavefronts up to 16,384, of three up to
+# 65,535, 256-env blocks from 65,536; N <= 2: 64-env blocks of 2N wavefronts below 65,536
+@pytest.mark.parametrize("N,wd,mixed,ac,sizes", [
+    (3, 0, False, False, (8192, 8200, 16384, 20001, 65600)),
+    (3, 0, True, False, (5000, 12000, 30000)),
+    (3, 1, False, False, (8190, 16000, 16390)),
+    (3, 0, False, True, (8192, 16384, 16400)),
+    (2, 0, False, False, (1000, 30000, 65700)),
+    (2, 0, False, True, (1000, 40000)),
+    (1, 0, False, False, (333, 65536 + 64)),
+    (1, 1, True, False, (100, 50000)),
+])
+def test_block_shapes_agree_bit_for_bit_and_with_the_oracle(mods, N, wd, mixed, ac, sizes):
+    say("block shapes N=%d wd=%d mixed=%d ac=%d sizes=%s" % (N, wd, mixed, ac, sizes))
+    w = synth.policy_weights_with_bias(21, 1, 6 * N, 64)
+    cw = synth.critic_weights(21, 1, 6 * N, 64)
+    jobs = [(E,) + _job(mods, E, N, wd, mixed, ac, w, cw, 8) for E in sizes]
+    E0, out0, st0 = jobs[0]
+    nper = 6 if ac else 4          # outputs shaped [T][TE]...; the rest are [TE]...
+    for E, out, st in jobs[1:]:
+        n = min(E, E0)
+        for k, (a, b) in enumerate(zip(out0, out)):
+            same = torch.equal(a[:, :n], b[:, :n]) if k < nper else torch.equal(a[:n], b[:n])
+            assert same, "output %d of the %d-env job differs from the %d-env job's" % (k, E, E0)
+        for a, b in zip(st0[:2], st[:2]):      # agent positions and velocities [2][N][TE]
+            assert torch.equal(a[..., :n], b[..., :n])
+    # oracle: the first envs of the first job and the ragged tail of every job
+    for E, out, st in jobs:
+        for off, n in [(max(0, E - 40), min(40, E))] + ([(0, 48)] if E == E0 else []):
+            orc = mods[1](Hp.oracle_config(n, N, 1, 64, wd, env_offset=off, reward_mode=1 if mixed else 0,
+                                           local_ratio=0.5), threads=8)
+            orc.set_policy(*w)
+            if ac:
+                orc.set_critic(*cw)
+            orc.reset(8)
+            ref = orc.rollout_ac(T) if ac else orc.rollout(T)
+            obs, act = out[0][:, off:off + n].cpu().numpy(), out[1][:, off:off + n].cpu().numpy()
+            done = out[5 if ac else 3][:, off:off + n].cpu().numpy()
+            assert np.array_equal(done, ref[5 if ac else 3])
+            assert np.array_equal(obs[0].astype(np.float64), ref[0][0]) and np.array_equal(obs[25].astype(np.float64), ref[0][25])
+            same = (act == ref[1]).all(axis=2)
+            alive = np.logical_and.accumulate(same[:25], axis=0)
+            assert alive[-1].mean() >= (0.9 if wd else 0.97), "envs %d.. of the %d-env job" % (off, E)
+            prior = np.vstack([np.ones((1, n), bool), alive[:4]])
+            err = np.abs(obs[:5].astype(np.float64) - ref[0][:5]).reshape(5, n, -1).max(axis=2)
+            assert (err * prior).max() <= Hp.EPISODE_ATOL, "envs %d.. of the %d-env job" % (off, E)
