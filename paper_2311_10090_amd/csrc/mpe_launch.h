@@ -21,6 +21,20 @@ inline hipError_t allow_lds(const void* kern, size_t bytes, std::atomic<uint64_t
   return e;
 }
 
+// Compute units of the current device (queried once per process; launch shapes are chosen by it).
+inline uint32_t compute_units() {
+  static std::atomic<int> cus{0};
+  int n = cus.load(std::memory_order_relaxed);
+  if (n == 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+    cus.store(n, std::memory_order_relaxed);
+  }
+  return uint32_t(n);
+}
+
 struct RolloutArgs {
   StatePtrs st;
   Phys ph;

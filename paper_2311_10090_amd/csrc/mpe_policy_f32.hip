@@ -728,20 +728,6 @@ hipError_t pack_impl(PolicyBuffers& pb, int R, const float* W1, const float* b1,
   return hipGetLastError();
 }
 
-// Compute units of the current device (queried once per process).
-uint32_t compute_units() {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-      cus = n;
-    else
-      cus = 256;
-  }
-  return uint32_t(cus);
-}
-
 // Small batches: when every block has a CU (nearly) to itself, the time of a rollout is the step latency of
 // one block (one wavefront per SIMD running its matrix and vector instructions back to back), so the rows
 // are spread over more wavefronts of 32 rows = one pair of 16-row tiles each, one wavefront per SIMD where

@@ -88,3 +88,63 @@ def test_block_shapes_agree_bit_for_bit_and_with_the_oracle(mods, N, wd, mixed, 
             prior = np.vstack([np.ones((1, n), bool), alive[:4]])
             err = np.abs(obs[:5].astype(np.float64) - ref[0][:5]).reshape(5, n, -1).max(axis=2)
             assert (err * prior).max() <= Hp.EPISODE_ATOL, "envs %d.. of the %d-env job" % (off, E)
+
+
+def _tag_job(mods, E, shape, wd, ac, w, cw, seed):
+    env = mods[0](Hp.tag_gpu_config(E, *shape, 1, 64, wd=wd))
+    env.set_policy(*Hp.to_dev(w))
+    if ac:
+        env.set_critic(*Hp.to_dev(cw))
+    env.reset(seed)
+    out = env.rollout_ac(T, *env.empty_traj_ac(T)) if ac else env.rollout(T, *env.empty_traj(T))
+    state = env.get_state()
+    torch.cuda.synchronize()
+    env.close()
+    return out, state
+
+
+# predator-prey: 32-env blocks of 32-row wavefronts up to 8,192 envs (64-env blocks up to 32,768 envs with
+# 2 agents; up to 16,384 envs for the actor-critic rollout of 4 agents), the regular blocks beyond
+@pytest.mark.parametrize("shape,wd,ac,sizes", [
+    ((4, 2, 3), 0, False, (8192, 8200, 20001)),
+    ((4, 2, 3), 1, False, (8000, 9000)),
+    ((4, 2, 3), 0, True, (8192, 16384, 16500)),
+    ((2, 1, 1), 0, False, (1000, 32768, 33000)),
+    ((2, 1, 1), 0, True, (1000, 40000)),
+    ((3, 0, 2), 0, False, (5000, 8193)),
+    ((3, 0, 2), 0, True, (8192, 8200)),
+])
+def test_predator_prey_block_shapes_agree_bit_for_bit_and_with_the_oracle(mods, shape, wd, ac, sizes):
+    say("tag block shapes %s wd=%d ac=%d sizes=%s" % (shape, wd, ac, sizes))
+    N, D = shape[0], Hp.tag_obs_dim(*shape)
+    w = synth.policy_weights_with_bias(22, 1, D, 64)
+    cw = synth.critic_weights(22, 1, D, 64)
+    jobs = [(E,) + _tag_job(mods, E, shape, wd, ac, w, cw, 9) for E in sizes]
+    E0, out0, st0 = jobs[0]
+    nper = 6 if ac else 4
+    for E, out, st in jobs[1:]:
+        n = min(E, E0)
+        for k, (a, b) in enumerate(zip(out0, out)):
+            same = torch.equal(a[:, :n], b[:, :n]) if k < nper else torch.equal(a[:n], b[:n])
+            assert same, "output %d of the %d-env job differs from the %d-env job's" % (k, E, E0)
+        for a, b in zip(st0[:2], st[:2]):
+            assert torch.equal(a[..., :n], b[..., :n])
+    for E, out, st in jobs:
+        off, n = E - 40, 40
+        orc = mods[1](Hp.tag_oracle_config(n, *shape, 1, 64, wd=wd, env_offset=off), threads=8)
+        orc.set_policy(*w)
+        if ac:
+            orc.set_critic(*cw)
+        orc.reset(9)
+        ref = orc.rollout_ac(T) if ac else orc.rollout(T)
+        obs, act = out[0][:, off:off + n].cpu().numpy(), out[1][:, off:off + n].cpu().numpy()
+        done = out[5 if ac else 3][:, off:off + n].cpu().numpy()
+        assert np.array_equal(done, ref[5 if ac else 3])
+        # episode starts: exact up to the fp32 rounding of differences of off-grid landmark coordinates
+        assert np.abs(obs[0] - ref[0][0]).max() <= 1e-6 and np.abs(obs[25] - ref[0][25]).max() <= 1e-6
+        same = (act == ref[1]).all(axis=2)
+        alive = np.logical_and.accumulate(same[:25], axis=0)
+        assert alive[-1].mean() >= (0.9 if wd else 0.97), "envs %d.. of the %d-env job" % (off, E)
+        prior = np.vstack([np.ones((1, n), bool), alive[:4]])
+        err = np.abs(obs[:5].astype(np.float64) - ref[0][:5]).reshape(5, n, -1).max(axis=2)
+        assert (err * prior).max() <= Hp.EPISODE_ATOL, "envs %d.. of the %d-env job" % (off, E)
