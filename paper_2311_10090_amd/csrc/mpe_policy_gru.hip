@@ -9,7 +9,7 @@
 // Design.  The network has 240 KB of bf16 weights, more than the 160 KB of LDS, and 236 matrix
 // instructions per 16 rows: re-reading the weights per wavefront from L2 would cost ~90 GB per
 // rollout.  So the weights are STATIONARY and the activations move: a block is 8 wavefronts around
-// 64 envs (64 N agent rows); wavefront u owns hidden units 16u..16u+15 of every layer and keeps
+// 64 envs (64 N agent rows; 32 or 16 envs for small batches); wavefront u owns hidden units 16u..16u+15 of every layer and keeps
 // its 24 GRU A-operands (r, z, n gates x input/recurrent x 4 K slices) and its embedding operand
 // in registers for the whole rollout (100 of its 256 registers); the small layers' operands
 // (second fully-connected layer, logits) sit in LDS.  Activations of all rows go through LDS as
@@ -102,9 +102,10 @@ __global__ void pack_gru_kernel(uint8_t* __restrict__ out, int D, const float* _
 
 constexpr size_t up16(size_t x) { return (x + 15) & ~size_t(15); }
 
-template <int N>
+template <int N, int EB = 64>
 struct GruSmem {
-  static constexpr int B = 64 * N, D = 6 * N, NT = 4 * N;       // rows, obs width, 16-row tiles
+  static constexpr int B = EB * N, D = 6 * N, NT = B / 16;      // rows, obs width, 16-row tiles
+  static_assert(B % 16 == 0 && EB <= 64, "whole row tiles");
   // bf16 observation tile, 32 columns per row (zero beyond D) + 16 bytes of padding; after the
   // embedding it is dead, and the logits [B][8] of the same step are stored in its place
   static constexpr int OS = 80;
@@ -128,11 +129,14 @@ __device__ __forceinline__ uint2 pack4_bf16(float a, float b, float c, float d) 
   return make_uint2(pack_bf16_rne(a, b), pack_bf16_rne(c, d));
 }
 
-template <int N>
+// EB = envs per block: 64, or 32 / 16 for small batches (every phase of a step is a loop over the block's
+// 16-row tiles, so the step latency of a block, which is the time of a rollout while every block has a CU
+// to itself, falls with its rows).
+template <int N, int EB>
 __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
                                                           float* __restrict__ hidden, uint32_t groups,
                                                           uint32_t groups_per_xcd) {
-  using M = GruSmem<N>;
+  using M = GruSmem<N, EB>;
   constexpr int B = M::B, D = M::D, NT = M::NT;
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   uint8_t* otile = smem + M::OFF_OBS;
@@ -152,9 +156,9 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
   const size_t TE = A.TE;
   const uint32_t grp = (blockIdx.x & 7u) * groups_per_xcd + (blockIdx.x >> 3);
   if (grp >= groups) return;  // whole block, before any barrier
-  const size_t g0 = size_t(grp) * 64;
+  const size_t g0 = size_t(grp) * EB;
   const size_t left = TE - g0;
-  const int nvalid = left < size_t(64) ? int(left) : 64;   // valid envs of this block
+  const int nvalid = left < size_t(EB) ? int(left) : EB;   // valid envs of this block
   const int vrows = nvalid * N;                            // valid agent rows
 
   // ---- stationary operands: this wavefront's GRU and embedding tiles in registers; the small
@@ -477,17 +481,28 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
   }
 }
 
-template <int N>
-hipError_t rollout_gru_impl(const RolloutArgs& A, const PolicyBuffers& pb, float* hidden, hipStream_t s) {
-  using M = GruSmem<N>;
-  auto kern = rollout_gru_kernel<N>;
+template <int N, int EB>
+hipError_t rollout_gru_blocks(const RolloutArgs& A, const PolicyBuffers& pb, float* hidden, hipStream_t s) {
+  using M = GruSmem<N, EB>;
+  auto kern = rollout_gru_kernel<N, EB>;
   static std::atomic<uint64_t> lds_allowed{0};
   if (hipError_t e = allow_lds(reinterpret_cast<const void*>(kern), M::TOTAL, lds_allowed); e != hipSuccess) return e;
-  const uint32_t groups = (A.TE + 63) / 64;
+  const uint32_t groups = (A.TE + EB - 1) / EB;
   const uint32_t per_xcd = (groups + 7) / 8;
   hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(512), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),
                      hidden, groups, per_xcd);
   return hipGetLastError();
+}
+
+template <int N>
+hipError_t rollout_gru_impl(const RolloutArgs& A, const PolicyBuffers& pb, float* hidden, hipStream_t s) {
+  // Smaller blocks while each still gets a CU to itself (measured per 128-step rollout, 3 agents: 16-env
+  // blocks 0.57-0.60 ms up to 4,096 envs and 32-env blocks 0.96-1.01 ms up to 8,192 envs against 1.9 ms with
+  // 64-env blocks; with more blocks than CUs the 64-env blocks are the fastest).
+  const uint32_t cus = compute_units();
+  if ((A.TE + 15) / 16 <= cus) return rollout_gru_blocks<N, 16>(A, pb, hidden, s);
+  if ((A.TE + 31) / 32 <= cus) return rollout_gru_blocks<N, 32>(A, pb, hidden, s);
+  return rollout_gru_blocks<N, 64>(A, pb, hidden, s);
 }
 
 __global__ void fill_zero_kernel(float* __restrict__ p, size_t n) {

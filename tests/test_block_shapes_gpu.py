@@ -148,3 +148,42 @@ def test_predator_prey_block_shapes_agree_bit_for_bit_and_with_the_oracle(mods, 
         prior = np.vstack([np.ones((1, n), bool), alive[:4]])
         err = np.abs(obs[:5].astype(np.float64) - ref[0][:5]).reshape(5, n, -1).max(axis=2)
         assert (err * prior).max() <= Hp.EPISODE_ATOL, "envs %d.. of the %d-env job" % (off, E)
+
+
+# recurrent policy: 16-env blocks up to 4,096 envs, 32-env blocks up to 8,192, 64-env blocks beyond
+@pytest.mark.parametrize("N,sizes", [(3, (4096, 4100, 8192, 8200)), (1, (100, 5000, 9000)), (2, (4090, 8300))])
+def test_recurrent_block_shapes_agree_bit_for_bit_and_with_the_oracle(mods, N, sizes):
+    say("recurrent block shapes N=%d sizes=%s" % (N, sizes))
+    w = synth.gru_weights(23, 1, 6 * N)
+    jobs = []
+    for E in sizes:
+        env = mods[0](Hp.gpu_config(E, N, 1, 128, 1))
+        env.set_gru_policy(*Hp.to_dev(w))
+        env.reset(10)
+        out = env.rollout(T, *env.empty_traj(T))
+        hid = env.get_hidden()
+        torch.cuda.synchronize()
+        env.close()
+        jobs.append((E, out, hid))
+    E0, out0, hid0 = jobs[0]
+    for E, out, hid in jobs[1:]:
+        n = min(E, E0)
+        for k, (a, b) in enumerate(zip(out0, out)):
+            same = torch.equal(a[:, :n], b[:, :n]) if k < 4 else torch.equal(a[:n], b[:n])
+            assert same, "output %d of the %d-env job differs from the %d-env job's" % (k, E, E0)
+        assert torch.equal(hid0[:n], hid[:n]), "carried state"
+    for E, out, hid in jobs:
+        off, n = E - 40, 40
+        orc = mods[1](Hp.oracle_config(n, N, 1, 128, 1, env_offset=off), threads=8)
+        orc.set_gru(*w)
+        orc.reset(10)
+        ref = orc.rollout(T)
+        obs, act = out[0][:, off:off + n].cpu().numpy(), out[1][:, off:off + n].cpu().numpy()
+        assert np.array_equal(out[3][:, off:off + n].cpu().numpy(), ref[3])
+        assert np.array_equal(obs[0].astype(np.float64), ref[0][0]) and np.array_equal(obs[25].astype(np.float64), ref[0][25])
+        same = (act == ref[1]).all(axis=2)
+        alive = np.logical_and.accumulate(same[:25], axis=0)
+        assert alive[-1].mean() >= 0.9, "envs %d.. of the %d-env job" % (off, E)
+        prior = np.vstack([np.ones((1, n), bool), alive[:4]])
+        err = np.abs(obs[:5].astype(np.float64) - ref[0][:5]).reshape(5, n, -1).max(axis=2)
+        assert (err * prior).max() <= Hp.EPISODE_ATOL, "envs %d.. of the %d-env job" % (off, E)
