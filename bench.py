@@ -207,6 +207,24 @@ def main():
         env5.close()
         del b5
 
+    # the paper's own many-seeds setting: 1,024 training runs (App. F) of 16 parallel envs each (App. G, IPPO
+    # on MPE), every run with its own policy weights, and the whole batch at several sizes
+    runs16 = {}
+    if args.workload == "cfg2":
+        k = max(3, args.steps // 3)
+        for nruns, per_run in ((1024, 16), (1024, 32)):
+            env7 = MpeEnv(Hp.gpu_config(per_run, N, nruns, H, 0))
+            env7.set_policy(*Hp.to_dev(synth.policy_weights(0, nruns, D, H)))
+            env7.reset(seed)
+            b7 = env7.empty_traj(T)
+            w7, k7 = time_rollouts(env7, T, b7, k, 2)
+            runs16["%d_runs_x_%d_envs" % (nruns, per_run)] = {
+                "agent_steps_per_s": nruns * per_run * N * T / (w7 / k), "kernel_ms_avg": float(np.mean(k7))}
+            env7.close()
+            del b7
+        runs16["note"] = ("one set of weights per run; runs of 16 envs x 3 agents are blocks of 48 rows + 16 padding rows "
+                          "in two wavefronts; multiples of 64 envs per run (cfg4) are the fast shape")
+
     # second scenario (predator-prey, 3 adversaries + 1 good agent + 2 obstacles) at the same number of
     # envs and steps: fused fp32 policy 16 -> 64 -> 64 -> 5 and env-only with uniform actions
     tag = {}
@@ -335,6 +353,7 @@ def main():
         "mixed_reward": mixed,
         "actor_critic": ac,
         "bf16_policy": bf,
+        "many_small_runs": runs16,
         "tag_scenario": tag,
         "recurrent_policy": gru,
         "single_step": {"us_per_mpe_step_call": step_us, "env_steps_per_s": TE / (step_us * 1e-6),

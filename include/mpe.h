@@ -170,7 +170,8 @@ int mpe_set_policy(mpe_env* env, const float* W1, const float* b1, const float* 
  * (observation after the last step).
  * Any of the five may be NULL (that output is then not written).
  * T >= 1.  Advances the absolute step counter by T.  MPE_ESTATE and the counter's limit as for
- * mpe_step. */
+ * mpe_step.  With a policy and several runs (one set of weights per run) num_envs must be a multiple
+ * of 16 (the 10-agent policy: of 64), MPE_EINVAL otherwise; multiples of 64 run fastest. */
 int mpe_rollout(mpe_env* env, int32_t T, float* obs_traj, uint8_t* act_traj, float* rew_traj,
                 uint8_t* done_traj, float* last_obs, void* stream);
 
@@ -220,8 +221,8 @@ int mpe_set_critic(mpe_env* env, const float* V1, const float* c1, const float* 
  * logp_traj, value_traj [T][TE][N] fp32, last_value [TE][N] fp32; the other arrays as in
  * mpe_rollout (rewards [T][TE][N] where mpe_rollout's are).  Any of the eight may be NULL.  Needs
  * a policy and a critic (MPE_ESTATE if one is missing); with several runs num_envs must be a
- * multiple of 64 (MPE_SCENARIO_TAG: of 512 / num_agents; of 64 with 3 agents), MPE_EINVAL
- * otherwise. */
+ * multiple of 16 (fastest: of 256; MPE_SCENARIO_TAG: of 512 / num_agents, of 64 with 3 agents),
+ * MPE_EINVAL otherwise. */
 int mpe_rollout_ac(mpe_env* env, int32_t T, float* obs_traj, uint8_t* act_traj, float* logp_traj,
                    float* value_traj, float* rew_traj, uint8_t* done_traj, float* last_obs,
                    float* last_value, void* stream);

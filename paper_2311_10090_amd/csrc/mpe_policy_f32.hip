@@ -41,11 +41,13 @@ using SpreadNet = NetShape<6 * N, 4 * N + 2>;
 // Plain rollout: W1A + W2A and the biases of the policy (its W3A lives in registers).
 // Actor-critic rollout (AC): the whole packed image of the policy and of the critic (W1A, W2A,
 // W3A, biases each), a value per row, and one arrival counter per 64-env sync group.
-template <int N, int EB, bool AC = false, bool BF = false>
+// ROWS = the block's agent rows, rounded up to whole wavefronts of RW rows (only 16-env blocks of
+// 3 agents have such padding rows: 48 -> 64; no env owns them and nothing of them leaves the block).
+template <int N, int EB, bool AC = false, bool BF = false, int RW = 64>
 struct SmemF32 {
   using P = PkT<BF>;
   static constexpr int D = 6 * N;
-  static constexpr int ROWS = EB * N;
+  static constexpr int ROWS = (EB * N + RW - 1) / RW * RW;
   static constexpr size_t OFF_BIAS = AC ? P::OFF_BIAS : P::LDS_BYTES;
   static constexpr size_t OFF_CRITIC = OFF_BIAS + P::BIAS_BYTES;     // AC: the critic's packed image
   static constexpr size_t OFF_OBS = OFF_CRITIC + (AC ? P::RUN_BYTES : 0);
@@ -81,14 +83,15 @@ __device__ __forceinline__ void group_barrier(uint32_t* arrived, uint32_t target
 // that store nothing to global memory.  The step latency of a block, which is all that matters when
 // every block has a CU to itself, is then one pair of tiles plus the env step instead of two pairs.
 template <int N, int EB, int MINW, bool PER_AGENT, bool AC, bool BF, int RW = 64>
-__global__ __launch_bounds__(EB * N * (64 / RW), MINW) void rollout_policy_f32_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
+__global__ __launch_bounds__((EB * N + RW - 1) / RW * 64, MINW) void rollout_policy_f32_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
                                                                           const uint8_t* __restrict__ packed_critic,
                                                                           int per_run_weights, uint32_t groups,
                                                                           uint32_t groups_per_xcd) {
-  using M = SmemF32<N, EB, AC, BF>;
+  using M = SmemF32<N, EB, AC, BF, RW>;
   using P = PkT<BF>;
 
-  constexpr int D = 6 * N, ROWS = EB * N, THREADS = ROWS * (64 / RW);
+  constexpr int D = 6 * N, ROWS = M::ROWS, THREADS = ROWS * (64 / RW);
+  constexpr bool kPadded = ROWS != EB * N;
   static_assert(THREADS % 64 == 0, "block must be whole wavefronts");
   static_assert(RW == 64 || (RW == 32 && EB <= 64), "half-filled wavefronts only in blocks of one sync group");
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -112,7 +115,9 @@ __global__ __launch_bounds__(EB * N * (64 / RW), MINW) void rollout_policy_f32_k
   constexpr int kGroups = EB > 64 ? EB / 64 : 1;
   const int wave = kGroups > 1 ? (hw_wave % kGroups) * N + hw_wave / kGroups : hw_wave;
   const int tid = wave * RW + (lane & (RW - 1));     // this lane's row
-  const int el = tid / N, i = tid - el * N;          // env within block, agent
+  const int el_row = tid / N, i = tid - el_row * N;  // env within block, agent
+  const bool in_block = !kPadded || el_row < EB;     // false for padding rows: they shadow env 0 of the block
+  const int el = in_block ? el_row : 0;
   const size_t TE = A.TE;
   // XCD-aware mapping: the hardware deals block b to XCD b % 8; giving each XCD one contiguous
   // range of env groups lets the partial cache lines that neighbouring groups write per step
@@ -121,7 +126,7 @@ __global__ __launch_bounds__(EB * N * (64 / RW), MINW) void rollout_policy_f32_k
   if (grp >= groups) return;  // whole block, before any barrier
   const size_t g0 = size_t(grp) * EB;
   const size_t g = g0 + el;
-  const bool in_range = g < TE;
+  const bool in_range = in_block && g < TE;
   const bool valid = in_range && lane < RW;          // the lane that stores this row's outputs
   const uint32_t gc = in_range ? uint32_t(g) : uint32_t(g0);
   const uint32_t run = gc / A.E;
@@ -700,13 +705,13 @@ hipError_t rollout_reg_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipSt
 
 template <int N, int EB, int MINW, bool PER_AGENT, bool AC, bool BF, int RW = 64>
 hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s, const void* critic = nullptr) {
-  using M = SmemF32<N, EB, AC, BF>;
+  using M = SmemF32<N, EB, AC, BF, RW>;
   auto kern = rollout_policy_f32_kernel<N, EB, MINW, PER_AGENT, AC, BF, RW>;
   static std::atomic<uint64_t> lds_allowed{0};
   if (hipError_t e = allow_lds(reinterpret_cast<const void*>(kern), M::TOTAL, lds_allowed); e != hipSuccess) return e;
   const uint32_t groups = (A.TE + EB - 1) / EB;
   const uint32_t per_xcd = (groups + 7) / 8;
-  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(EB * N * (64 / RW)), M::TOTAL, s, A,
+  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(M::ROWS * (64 / RW)), M::TOTAL, s, A,
                      static_cast<const uint8_t*>(pb.packed), static_cast<const uint8_t*>(critic), int(A.TE != A.E), groups,
                      per_xcd);
   return hipGetLastError();
@@ -783,7 +788,12 @@ hipError_t launch_n(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s
   if (one_run || A.E % 64 == 0)
     return per_agent ? launch_blocks64<N, true, false, BF>(A, pb, s, nullptr)
                      : launch_blocks64<N, false, false, BF>(A, pb, s, nullptr);
-  *why = "with several runs, num_envs per run must be a multiple of 64";
+  // small runs (the paper's IPPO setting is 16 envs per run): blocks of 32 or 16 envs inside a run
+  if (A.E % 32 == 0)
+    return per_agent ? rollout_impl<N, 32, 1, true, false, BF, 32>(A, pb, s) : rollout_impl<N, 32, 1, false, false, BF, 32>(A, pb, s);
+  if (A.E % 16 == 0)
+    return per_agent ? rollout_impl<N, 16, 1, true, false, BF, 32>(A, pb, s) : rollout_impl<N, 16, 1, false, false, BF, 32>(A, pb, s);
+  *why = "with several runs, num_envs per run must be a multiple of 16";
   return hipSuccess;
 }
 
@@ -802,7 +812,13 @@ hipError_t launch_ac_n(const RolloutArgs& A, const PolicyBuffers& pb, const Poli
   if (one_run || A.E % 64 == 0)
     return per_agent ? launch_blocks64<N, true, true, BF>(A, pb, s, critic.packed)
                      : launch_blocks64<N, false, true, BF>(A, pb, s, critic.packed);
-  *why = "with several runs, num_envs per run must be a multiple of 64";
+  if (A.E % 32 == 0)
+    return per_agent ? rollout_impl<N, 32, 1, true, true, BF, 32>(A, pb, s, critic.packed)
+                     : rollout_impl<N, 32, 1, false, true, BF, 32>(A, pb, s, critic.packed);
+  if (A.E % 16 == 0)
+    return per_agent ? rollout_impl<N, 16, 1, true, true, BF, 32>(A, pb, s, critic.packed)
+                     : rollout_impl<N, 16, 1, false, true, BF, 32>(A, pb, s, critic.packed);
+  *why = "with several runs, num_envs per run must be a multiple of 16";
   return hipSuccess;
 }
 

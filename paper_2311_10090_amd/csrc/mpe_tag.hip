@@ -29,9 +29,11 @@ enum TagMode : int { kGiven = 0, kUniform = 1, kPolicy = 2, kPolicyBf = 3, kPoli
 
 // EB = envs per block.  Plain rollouts: 64.  Actor-critic: both packed images (79 KB) are staged per block,
 // so a block is 8 wavefronts where the shape allows it (wavefront-local shapes need no block barrier).
-template <typename S, int MODE, int EB = 64>
+// ROWS = the block's agent rows, rounded up to whole wavefronts of RW rows (only 16-env blocks of 3 agents
+// have such padding rows: 48 -> 64; no env owns them and nothing of them leaves the block).
+template <typename S, int MODE, int EB = 64, int RW = 64>
 struct TagSmem {
-  static constexpr int ROWS = EB * S::N;
+  static constexpr int ROWS = (EB * S::N + RW - 1) / RW * RW;
   static constexpr bool kAc = MODE == kPolicyAc;
   static constexpr bool kHasPolicy = MODE == kPolicy || MODE == kPolicyBf || kAc;
   using P = PkT<MODE == kPolicyBf>;
@@ -152,15 +154,16 @@ __global__ __launch_bounds__(64 * S::N) void tag_reset_kernel(StatePtrs st, uint
 // wavefronts, one pair of 16-row tiles each; lanes 32..63 are exact clones of lanes 0..31 (same row, same
 // inputs, same arithmetic, so their LDS writes repeat the same values) that store nothing to global memory.
 template <typename S, int MODE, int EB = 64, int RW = 64>
-__global__ __launch_bounds__(EB * S::N * (64 / RW), ((MODE == kPolicy || MODE == kPolicyBf) && RW == 64) ? 3 : 1) void tag_rollout_kernel(
+__global__ __launch_bounds__((EB * S::N + RW - 1) / RW * 64, ((MODE == kPolicy || MODE == kPolicyBf) && RW == 64) ? 3 : 1) void tag_rollout_kernel(
     TagArgs TA, const uint8_t* __restrict__ packed, const uint8_t* __restrict__ packed_critic, int per_run_weights,
     uint32_t groups, uint32_t groups_per_xcd) {
-  using M = TagSmem<S, MODE, EB>;
+  using M = TagSmem<S, MODE, EB, RW>;
   constexpr bool AC = MODE == kPolicyAc;
   static_assert(EB <= 64 || S::kWaveLocal, "larger blocks only where wavefronts never exchange data");
   static_assert(RW == 64 || (RW == 32 && (!S::kWaveLocal || 32 % S::N == 0)), "rows per wavefront");
   using Net = NetShape<S::D, S::D <= 16 ? S::D : 16>;
-  constexpr int N = S::N, L = S::L, G = S::G, NA = S::A, D = S::D, ROWS = EB * N, THREADS = ROWS * (64 / RW);
+  constexpr int N = S::N, L = S::L, G = S::G, NA = S::A, D = S::D, ROWS = M::ROWS, THREADS = ROWS * (64 / RW);
+  constexpr bool kPadded = ROWS != EB * N;
   static_assert(THREADS % 64 == 0, "block must be whole wavefronts");
   const RolloutArgs& A = TA.r;
   const TagPhys& tg = TA.tg;
@@ -171,14 +174,16 @@ __global__ __launch_bounds__(EB * S::N * (64 / RW), ((MODE == kPolicy || MODE ==
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
   const int tid = wave * RW + (lane & (RW - 1));     // this lane's row
-  const int el = tid / N, i = tid - el * N;          // env within block, agent
+  const int el_row = tid / N, i = tid - el_row * N;  // env within block, agent
+  const bool in_block = !kPadded || el_row < EB;     // false for padding rows: they shadow env 0 of the block
+  const int el = in_block ? el_row : 0;
   const size_t TE = A.TE;
   // block b runs on XCD b % 8: give each XCD one contiguous range of env groups
   const uint32_t grp = (blockIdx.x & 7u) * groups_per_xcd + (blockIdx.x >> 3);
   if (grp >= groups) return;  // whole block, before any barrier
   const size_t g0 = size_t(grp) * EB;
   const size_t g = g0 + el;
-  const bool in_range = g < TE;
+  const bool in_range = in_block && g < TE;
   const bool valid = in_range && lane < RW;          // the lane that stores this row's outputs
   const uint32_t gc = in_range ? uint32_t(g) : uint32_t(g0);
   const uint32_t run = gc / A.E;
@@ -488,13 +493,13 @@ __global__ __launch_bounds__(EB * S::N * (64 / RW), ((MODE == kPolicy || MODE ==
 
 template <typename S, int MODE, int EB = 64, int RW = 64>
 hipError_t tag_rollout_impl(const TagArgs& A, const void* packed, const void* packed_critic, hipStream_t s) {
-  using M = TagSmem<S, MODE, EB>;
+  using M = TagSmem<S, MODE, EB, RW>;
   auto kern = tag_rollout_kernel<S, MODE, EB, RW>;
   static std::atomic<uint64_t> lds_allowed{0};
   if (hipError_t e = allow_lds(reinterpret_cast<const void*>(kern), M::TOTAL, lds_allowed); e != hipSuccess) return e;
   const uint32_t groups = (A.r.TE + EB - 1) / EB;
   const uint32_t per_xcd = (groups + 7) / 8;
-  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(EB * S::N * (64 / RW)), M::TOTAL, s, A,
+  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(M::ROWS * (64 / RW)), M::TOTAL, s, A,
                      static_cast<const uint8_t*>(packed), static_cast<const uint8_t*>(packed_critic),
                      int(A.r.TE != A.r.E), groups, per_xcd);
   return hipGetLastError();
@@ -510,9 +515,13 @@ hipError_t tag_launch(int mode, const TagArgs& A, const void* packed, const void
     constexpr int kAcEnvs = S::kWaveLocal ? 512 / S::N : 64;
     const uint32_t per_block = mode == kPolicyAc ? uint32_t(kAcEnvs) : 64u;
     if (A.r.TE != A.r.E && A.r.E % per_block != 0) {
-      *why = mode == kPolicyAc ? "with several runs, num_envs per run must be a multiple of the block's envs (512 / agents, "
-                                 "64 for 3 agents)"
-                               : "with several runs, num_envs per run must be a multiple of 64";
+      // small runs (the paper's IPPO setting is 16 envs per run): blocks of 16 envs inside a run
+      if (A.r.E % 16 == 0) {
+        if (mode == kPolicyAc) return tag_rollout_impl<S, kPolicyAc, 16, 32>(A, packed, packed_critic, s);
+        return mode == kPolicyBf ? tag_rollout_impl<S, kPolicyBf, 16, 32>(A, packed, nullptr, s)
+                                 : tag_rollout_impl<S, kPolicy, 16, 32>(A, packed, nullptr, s);
+      }
+      *why = "with several runs, num_envs per run must be a multiple of 16";
       return hipSuccess;
     }
     // Small batches (every block has a CU to itself, so the step latency of one block is the time): the

@@ -187,3 +187,101 @@ def test_recurrent_block_shapes_agree_bit_for_bit_and_with_the_oracle(mods, N, s
         prior = np.vstack([np.ones((1, n), bool), alive[:4]])
         err = np.abs(obs[:5].astype(np.float64) - ref[0][:5]).reshape(5, n, -1).max(axis=2)
         assert (err * prior).max() <= Hp.EPISODE_ATOL, "envs %d.. of the %d-env job" % (off, E)
+
+
+# several runs of 16 k envs each (the paper's IPPO setting on MPE is 16 envs per run, App. G): blocks of 32
+# or 16 envs inside one run, with its weights; 16 envs x 3 agents: 48 rows + 16 padding rows in two
+# wavefronts of 32
+@pytest.mark.parametrize("N,E,R,wd,mixed,ac", [
+    (3, 16, 40, 0, False, False), (3, 48, 5, 0, False, False), (3, 80, 3, 0, True, False), (3, 16, 9, 0, False, True),
+    (3, 16, 12, 1, False, False), (1, 16, 7, 0, False, False), (2, 32, 9, 0, False, False), (2, 16, 5, 0, True, True),
+    (1, 48, 3, 0, False, True), (3, 96, 3, 0, False, False), (3, 32, 6, 0, True, True),
+])
+def test_small_runs_with_their_own_weights_against_the_oracle(mods, N, E, R, wd, mixed, ac):
+    from scipy.special import log_softmax
+    say("small runs N=%d E=%d R=%d wd=%d mixed=%d ac=%d" % (N, E, R, wd, mixed, ac))
+    D, TE = 6 * N, E * R
+    w = synth.policy_weights_with_bias(31, R, D, 64)
+    cw = synth.critic_weights(31, R, D, 64)
+    rm = dict(reward_mode=1 if mixed else 0, local_ratio=0.5)
+    env = mods[0](Hp.gpu_config(E, N, R, 64, wd, **rm))
+    orc = mods[1](Hp.oracle_config(E, N, R, 64, wd, **rm), threads=8)
+    env.set_policy(*Hp.to_dev(w))
+    orc.set_policy(*w)
+    if ac:
+        env.set_critic(*Hp.to_dev(cw))
+        orc.set_critic(*cw)
+    env.reset(11)
+    orc.reset(11)
+    out = env.rollout_ac(T, *env.empty_traj_ac(T)) if ac else env.rollout(T, *env.empty_traj(T))
+    ref = orc.rollout_ac(T) if ac else orc.rollout(T)
+    obs, act = out[0].cpu().numpy(), out[1].cpu().numpy()
+    rew, done = out[4 if ac else 2].cpu().numpy(), out[5 if ac else 3].cpu().numpy()
+    assert np.array_equal(done, ref[5 if ac else 3])
+    assert np.array_equal(obs[0].astype(np.float64), ref[0][0]) and np.array_equal(obs[25].astype(np.float64), ref[0][25])
+    same = (act == ref[1]).all(axis=2)
+    alive = np.logical_and.accumulate(same[:25], axis=0)
+    assert alive[-1].mean() >= (0.9 if wd else 0.97)
+    prior = np.vstack([np.ones((1, TE), bool), alive[:4]])
+    err = np.abs(obs[:5].astype(np.float64) - ref[0][:5]).reshape(5, TE, -1).max(axis=2)
+    assert (err * prior).max() <= Hp.EPISODE_ATOL
+    if not mixed:
+        assert (np.abs(rew[:5] - ref[4 if ac else 2][:5]) * alive[:5]).max() <= Hp.EPISODE_ATOL
+    # the runs use their own weights and streams: first actions differ from run to run
+    a0 = act[0].reshape(R, E, N)
+    assert any(not np.array_equal(a0[0], a0[r]) for r in range(1, R))
+    if ac and not wd:
+        logp, val = out[2].cpu().numpy(), out[3].cpu().numpy()
+        for run in range(R):
+            sl = slice(run * E, (run + 1) * E)
+            rows = obs[:, sl].reshape(-1, D).astype(np.float64)
+            z = orc.policy_logits(rows, run=run)
+            ref_lp = log_softmax(z, axis=1)[np.arange(z.shape[0]), act[:, sl].reshape(-1)]
+            Hp.assert_close_step(logp[:, sl].reshape(-1), ref_lp, "log-prob from recorded obs and actions")
+            Hp.assert_close_step(val[:, sl].reshape(-1), orc.value(rows, run=run), "value from recorded obs")
+    env.close()
+
+
+@pytest.mark.parametrize("shape,E,R,wd,ac", [
+    ((4, 2, 3), 16, 20, 0, False), ((4, 2, 3), 48, 4, 1, False), ((4, 2, 3), 16, 6, 0, True), ((4, 2, 3), 64, 3, 0, True),
+    ((2, 1, 1), 16, 9, 0, False), ((2, 1, 1), 80, 2, 0, True), ((3, 0, 2), 16, 10, 0, False), ((3, 0, 2), 48, 3, 0, True),
+])
+def test_predator_prey_small_runs_with_their_own_weights_against_the_oracle(mods, shape, E, R, wd, ac):
+    from scipy.special import log_softmax
+    say("tag small runs %s E=%d R=%d wd=%d ac=%d" % (shape, E, R, wd, ac))
+    N, D, TE = shape[0], Hp.tag_obs_dim(*shape), E * R
+    w = synth.policy_weights_with_bias(32, R, D, 64)
+    cw = synth.critic_weights(32, R, D, 64)
+    env = mods[0](Hp.tag_gpu_config(E, *shape, R, 64, wd=wd))
+    orc = mods[1](Hp.tag_oracle_config(E, *shape, R, 64, wd=wd), threads=8)
+    env.set_policy(*Hp.to_dev(w))
+    orc.set_policy(*w)
+    if ac:
+        env.set_critic(*Hp.to_dev(cw))
+        orc.set_critic(*cw)
+    env.reset(12)
+    orc.reset(12)
+    out = env.rollout_ac(T, *env.empty_traj_ac(T)) if ac else env.rollout(T, *env.empty_traj(T))
+    ref = orc.rollout_ac(T) if ac else orc.rollout(T)
+    obs, act = out[0].cpu().numpy(), out[1].cpu().numpy()
+    rew, done = out[4 if ac else 2].cpu().numpy(), out[5 if ac else 3].cpu().numpy()
+    assert np.array_equal(done, ref[5 if ac else 3])
+    assert np.abs(obs[0] - ref[0][0]).max() <= 1e-6 and np.abs(obs[25] - ref[0][25]).max() <= 1e-6
+    same = (act == ref[1]).all(axis=2)
+    alive = np.logical_and.accumulate(same[:25], axis=0)
+    assert alive[-1].mean() >= (0.9 if wd else 0.97)
+    prior = np.vstack([np.ones((1, TE), bool), alive[:4]])
+    err = np.abs(obs[:5].astype(np.float64) - ref[0][:5]).reshape(5, TE, -1).max(axis=2)
+    assert (err * prior).max() <= Hp.EPISODE_ATOL
+    a0 = act[0].reshape(R, E, N)
+    assert any(not np.array_equal(a0[0], a0[r]) for r in range(1, R))
+    if ac:
+        logp, val = out[2].cpu().numpy(), out[3].cpu().numpy()
+        for run in range(R):
+            sl = slice(run * E, (run + 1) * E)
+            rows = obs[:, sl].reshape(-1, D).astype(np.float64)
+            z = orc.policy_logits(rows, run=run)
+            ref_lp = log_softmax(z, axis=1)[np.arange(z.shape[0]), act[:, sl].reshape(-1)]
+            Hp.assert_close_step(logp[:, sl].reshape(-1), ref_lp, "log-prob from recorded obs and actions")
+            Hp.assert_close_step(val[:, sl].reshape(-1), orc.value(rows, run=run), "value from recorded obs")
+    env.close()

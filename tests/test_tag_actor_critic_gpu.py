@@ -147,7 +147,7 @@ def test_errors_and_absent_outputs(mods):
         big.set_critic(*Hp.to_dev(synth.critic_weights(0, 1, 20, 64)))
     assert ei.value.code == MPE_EINVAL
     big.close()
-    runs = _env(mods, 64, shape, R=2)                                  # several runs: whole 128-env blocks per run
+    runs = _env(mods, 40, shape, R=2)                                  # several runs: multiples of 16 envs per run
     runs.reset(0)
     with pytest.raises(MpeError) as ei:
         runs.rollout_ac(2)
