@@ -155,7 +155,7 @@ int mpe_step(mpe_env* env, const uint8_t* actions, float* obs, float* reward, ui
  * operand layout on `stream` (rounding W to bf16, ties to even, when weight_dtype is
  * MPE_WEIGHTS_BF16); the caller's arrays are not referenced after that work has run.
  * Policies are built for (num_agents, hidden, weight_dtype) in (1..3, 64, fp32 or bf16) and
- * (10, 128, bf16); with MPE_SCENARIO_TAG for hidden 64, fp32 or bf16, and the shapes with D <= 16
+ * (4 | 6 | 8 | 10, 64 | 128, bf16); with MPE_SCENARIO_TAG for hidden 64, fp32 or bf16, and the shapes with D <= 16
  * (all but (6, 2, 2)).  MPE_EINVAL for other shapes, if only some pointers are NULL, or if the config has no
  * usable `hidden`. */
 int mpe_set_policy(mpe_env* env, const float* W1, const float* b1, const float* W2,
@@ -171,7 +171,8 @@ int mpe_set_policy(mpe_env* env, const float* W1, const float* b1, const float* 
  * Any of the five may be NULL (that output is then not written).
  * T >= 1.  Advances the absolute step counter by T.  MPE_ESTATE and the counter's limit as for
  * mpe_step.  With a policy and several runs (one set of weights per run) num_envs must be a multiple
- * of 16 (the 10-agent policy: of 64), MPE_EINVAL otherwise; multiples of 64 run fastest. */
+ * of 16 (the policies for 4 and more agents: of 64; of 32 with 8 agents), MPE_EINVAL otherwise;
+ * multiples of 64 run fastest. */
 int mpe_rollout(mpe_env* env, int32_t T, float* obs_traj, uint8_t* act_traj, float* rew_traj,
                 uint8_t* done_traj, float* last_obs, void* stream);
 

@@ -605,12 +605,19 @@ hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream
 
 }  // namespace
 
-// General shapes built: (N, H, envs per block, min waves per SIMD), bf16 operands.
+// General shapes built: (N, H, envs per block, min waves per SIMD), bf16 operands.  The kernel takes any
+// even agent count (rows of 6N floats are moved as 16-byte chunks) and any width that is a multiple of 32;
+// a block is at most four sync groups (the smallest env count whose rows fill whole wavefronts: 16 envs
+// with 4 agents, 32 with 6, 8 with 8, 32 with 10).
+#define MPE_WIDE_POLICY_CASES(X) \
+  X(10, 128, 64, 3) X(10, 64, 64, 3) X(8, 128, 32, 3) X(8, 64, 32, 3) X(6, 128, 64, 3) X(6, 64, 64, 3) X(4, 128, 64, 3) X(4, 64, 64, 3)
+// Env-only rollouts that use this kernel's lane-per-agent mapping (the other agent counts use the
+// env-per-lane kernels).
 #define MPE_WIDE_CASES(X) X(10, 128, 64, 3)
 
 bool wide_supported(int N, int H) {
 #define X(N_, H_, EB_, MW_) if (N == N_ && H == H_) return true;
-  MPE_WIDE_CASES(X)
+  MPE_WIDE_POLICY_CASES(X)
 #undef X
   return false;
 }
@@ -618,7 +625,7 @@ bool wide_supported(int N, int H) {
 hipError_t pack_policy_wide(PolicyBuffers& pb, int N, int H, int R, const float* W1, const float* b1,
                             const float* W2, const float* b2, const float* W3, const float* b3, hipStream_t s) {
 #define X(N_, H_, EB_, MW_) if (N == N_ && H == H_) return pack_impl<N_, H_>(pb, R, W1, b1, W2, b2, W3, b3, s);
-  MPE_WIDE_CASES(X)
+  MPE_WIDE_POLICY_CASES(X)
 #undef X
   return hipErrorInvalidValue;
 }
@@ -653,7 +660,7 @@ hipError_t launch_rollout_policy_wide(int N, int H, const RolloutArgs& A, const 
     return A.ph.reward_mode == 1 ? rollout_impl<N_, H_, EB_, MW_, true>(A, pb, s)                \
                                  : rollout_impl<N_, H_, EB_, MW_, false>(A, pb, s);              \
   }
-  MPE_WIDE_CASES(X)
+  MPE_WIDE_POLICY_CASES(X)
 #undef X
   return hipErrorInvalidValue;
 }

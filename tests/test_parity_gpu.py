@@ -380,6 +380,47 @@ def test_policy_bf16_wide_ragged_and_per_run(mods, E, R):
     env.close()
 
 
+@pytest.mark.parametrize("N,H,E,R", [(4, 64, 200, 1), (4, 128, 64, 2), (6, 64, 100, 1), (6, 128, 64, 3), (8, 64, 75, 1),
+                                     (8, 128, 32, 3), (10, 64, 130, 1), (4, 64, 2100, 1)])
+def test_policy_bf16_other_even_agent_counts(mods, N, H, E, R):
+    """The bf16 lane-per-agent kernel for 4, 6, 8 and 10 agents and both widths: sync groups of 16, 32, 8
+    and 32 envs, ragged last groups and blocks, one set of weights per run; and the mixed reward."""
+    say("policy bf16 N=%d H=%d E=%d R=%d" % (N, H, E, R))
+    env, orc = _policy_pair(mods, E, N, R, H, 1, wseed=15)
+    frac, total, worst = _teacher_forced(env, orc, seed=7, T=8)
+    say("  bf16 agreement %.5f over %d samples" % (frac, total))
+    assert frac >= 0.99
+
+    def make_oracle():
+        o = mods[1](Hp.oracle_config(E, N, R, H, 1), threads=8)
+        o.set_policy(*synth.policy_weights_with_bias(15, R, 6 * N, H))
+        return o
+
+    frac2, ww, n_ill, n_all = _free_running(env, orc, 3, 30, make_oracle)
+    say("  bf16 identical episodes %.4f ; worst error %.2e" % (frac2, ww))
+    assert frac2 >= 0.95
+    env.close()
+    # mixed per-agent reward through the same kernel: rewards of the first steps against the oracle
+    MpeEnv, Oracle = mods
+    w = synth.policy_weights_with_bias(15, R, 6 * N, H)
+    envm = MpeEnv(Hp.gpu_config(E, N, R, H, 1, reward_mode=1, local_ratio=0.5))
+    orcm = Oracle(Hp.oracle_config(E, N, R, H, 1, reward_mode=1, local_ratio=0.5), threads=8)
+    envm.set_policy(*Hp.to_dev(w))
+    orcm.set_policy(*w)
+    envm.reset(3)
+    orcm.reset(3)
+    obs, act, rew, done, last = [x.cpu().numpy() for x in envm.rollout(3, *envm.empty_traj(3))]
+    robs, ract, rrew, rdone, rlast = orcm.rollout(3)
+    assert rew.shape == (3, E * R, N)
+    alive = np.logical_and.accumulate((act == ract).all(axis=2), axis=0)
+    pos = robs[1][:, :, 2:4]
+    d = np.linalg.norm(pos[:, :, None, :] - pos[:, None, :, :], axis=3)
+    d[:, np.arange(N), np.arange(N)] = np.inf
+    mask = (np.abs(d - 0.3) > 1e-4).all(axis=2) & alive[0][:, None]
+    assert mask.sum() > 0 and np.abs(rew[0][mask] - rrew[0][mask]).max() <= Hp.EPISODE_ATOL
+    envm.close()
+
+
 def test_policy_bf16_wide_null_outputs_and_continuation(mods):
     """Any output may be absent; two rollouts of T/2 equal one of T (rewards of the last step
     of a call are summed after the loop, all others one step late)."""
