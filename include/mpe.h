@@ -155,7 +155,7 @@ int mpe_step(mpe_env* env, const uint8_t* actions, float* obs, float* reward, ui
  * operand layout on `stream` (rounding W to bf16, ties to even, when weight_dtype is
  * MPE_WEIGHTS_BF16); the caller's arrays are not referenced after that work has run.
  * Policies are built for (num_agents, hidden, weight_dtype) in (1..3, 64, fp32 or bf16) and
- * (4 | 6 | 8 | 10, 64 | 128, bf16); with MPE_SCENARIO_TAG for hidden 64, fp32 or bf16, and the shapes with D <= 16
+ * (4..10, 64 | 128, bf16); with MPE_SCENARIO_TAG for hidden 64, fp32 or bf16, and the shapes with D <= 16
  * (all but (6, 2, 2)).  MPE_EINVAL for other shapes, if only some pointers are NULL, or if the config has no
  * usable `hidden`. */
 int mpe_set_policy(mpe_env* env, const float* W1, const float* b1, const float* W2,

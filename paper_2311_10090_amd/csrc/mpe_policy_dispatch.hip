@@ -24,7 +24,7 @@ void free_policy(PolicyBuffers& pb) {
 }
 
 static const char* kUnsupported =
-    "unsupported policy shape: need (num_agents, hidden, dtype) in {(1..3, 64, fp32 or bf16), (4 | 6 | 8 | 10, 64 | 128, bf16)}";
+    "unsupported policy shape: need (num_agents, hidden, dtype) in {(1..3, 64, fp32 or bf16), (4..10, 64 | 128, bf16)}";
 
 hipError_t pack_policy(PolicyBuffers& pb, int N, int H, int R, int weight_dtype, const float* W1,
                        const float* b1, const float* W2, const float* b2, const float* W3,

@@ -270,7 +270,8 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
   constexpr int PD = S::S1 * 16;             // dwords of one row as bf16 pairs, zero padded to whole K slices
   constexpr int GE = sync_group_envs(N), GW = GE * N / 64;   // envs / wavefronts of one sync group
   static_assert(EB % GE == 0 && EB / GE <= 4, "a block is whole sync groups");
-  static_assert(D % 4 == 0 && KIN % 2 == 0, "rows are stored as 16-byte chunks and packed as bf16 pairs");
+  static_assert((UNIFORM ? D % 4 == 0 : D % 2 == 0) && KIN % 2 == 0,
+                "rows are stored as 16-byte chunks (8-byte with an odd agent count) and packed as bf16 pairs");
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   uint8_t* wsm = smem;
   float* bias = reinterpret_cast<float*>(smem + M::OFF_BIAS);
@@ -388,13 +389,24 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
       }
       wave_sync();
     } else if (lane < wave_rows) {
-      v4f* d4 = reinterpret_cast<v4f*>(dst) + lane * RF4;
+      if constexpr (D % 4 == 0) {
+        v4f* d4 = reinterpret_cast<v4f*>(dst) + lane * RF4;
 #pragma unroll
-      for (int q = 0; q < RF4; ++q) {
-        v4f v;
+        for (int q = 0; q < RF4; ++q) {
+          v4f v;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = (4 * q + e < KIN) ? o[(4 * q + e < KIN) ? 4 * q + e : 0] : 0.0f;
-        d4[q] = v;
+          for (int e = 0; e < 4; ++e) v[e] = (4 * q + e < KIN) ? o[(4 * q + e < KIN) ? 4 * q + e : 0] : 0.0f;
+          d4[q] = v;
+        }
+      } else {   // odd agent counts: rows of 24 N bytes are only 8-byte aligned
+        v2f* d2 = reinterpret_cast<v2f*>(dst) + lane * (D / 2);
+#pragma unroll
+        for (int q = 0; q < D / 2; ++q) {
+          v2f v;
+          v[0] = (2 * q < KIN) ? o[(2 * q < KIN) ? 2 * q : 0] : 0.0f;
+          v[1] = (2 * q < KIN) ? o[(2 * q < KIN) ? 2 * q + 1 : 0] : 0.0f;
+          d2[q] = v;
+        }
       }
     }
   };
@@ -606,11 +618,12 @@ hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream
 }  // namespace
 
 // General shapes built: (N, H, envs per block, min waves per SIMD), bf16 operands.  The kernel takes any
-// even agent count (rows of 6N floats are moved as 16-byte chunks) and any width that is a multiple of 32;
-// a block is at most four sync groups (the smallest env count whose rows fill whole wavefronts: 16 envs
-// with 4 agents, 32 with 6, 8 with 8, 32 with 10).
+// agent count (rows of 6N floats leave as 16-byte chunks, 8-byte ones when N is odd) and any width that is
+// a multiple of 32; a block is at most four sync groups (the smallest env count whose rows fill whole
+// wavefronts: 16 envs with 4 agents, 32 with 6, 8 with 8, 32 with 10, 64 with an odd count).
 #define MPE_WIDE_POLICY_CASES(X) \
-  X(10, 128, 64, 3) X(10, 64, 64, 3) X(8, 128, 32, 3) X(8, 64, 32, 3) X(6, 128, 64, 3) X(6, 64, 64, 3) X(4, 128, 64, 3) X(4, 64, 64, 3)
+  X(10, 128, 64, 3) X(10, 64, 64, 3) X(9, 128, 64, 3) X(9, 64, 64, 3) X(8, 128, 32, 3) X(8, 64, 32, 3) X(7, 128, 64, 3) \
+  X(7, 64, 64, 3) X(6, 128, 64, 3) X(6, 64, 64, 3) X(5, 128, 64, 3) X(5, 64, 64, 3) X(4, 128, 64, 3) X(4, 64, 64, 3)
 // Env-only rollouts that use this kernel's lane-per-agent mapping (the other agent counts use the
 // env-per-lane kernels).
 #define MPE_WIDE_CASES(X) X(10, 128, 64, 3)

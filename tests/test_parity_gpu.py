@@ -381,10 +381,12 @@ def test_policy_bf16_wide_ragged_and_per_run(mods, E, R):
 
 
 @pytest.mark.parametrize("N,H,E,R", [(4, 64, 200, 1), (4, 128, 64, 2), (6, 64, 100, 1), (6, 128, 64, 3), (8, 64, 75, 1),
-                                     (8, 128, 32, 3), (10, 64, 130, 1), (4, 64, 2100, 1)])
-def test_policy_bf16_other_even_agent_counts(mods, N, H, E, R):
-    """The bf16 lane-per-agent kernel for 4, 6, 8 and 10 agents and both widths: sync groups of 16, 32, 8
-    and 32 envs, ragged last groups and blocks, one set of weights per run; and the mixed reward."""
+                                     (8, 128, 32, 3), (10, 64, 130, 1), (4, 64, 2100, 1), (5, 64, 100, 1), (5, 128, 64, 2),
+                                     (7, 64, 70, 1), (7, 128, 64, 2), (9, 64, 50, 1), (9, 128, 64, 2)])
+def test_policy_bf16_other_agent_counts(mods, N, H, E, R):
+    """The bf16 lane-per-agent kernel for 4 to 10 agents and both widths: sync groups of 16, 32, 8 and 32
+    envs (64 with an odd count, whose rows leave as 8-byte pieces), ragged last groups and blocks, one set
+    of weights per run; and the mixed reward."""
     say("policy bf16 N=%d H=%d E=%d R=%d" % (N, H, E, R))
     env, orc = _policy_pair(mods, E, N, R, H, 1, wseed=15)
     frac, total, worst = _teacher_forced(env, orc, seed=7, T=8)
