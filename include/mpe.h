@@ -184,16 +184,17 @@ int mpe_rollout(mpe_env* env, int32_t T, float* obs_traj, uint8_t* act_traj, flo
  *   r = sigmoid(Wi_r^T e + bi_r + Wh_r^T h + bh_r),  z likewise,
  *   n = tanh(Wi_n^T e + bi_n + r * (Wh_n^T h + bh_n)),  h <- (1 - z) * n + z * h
  *   y = tanh(Wf^T h + bf),  logits = Wo^T y + bo
- * We [D][128], be [128], Wi, Wh [128][384] (columns r | z | n), bi, bh [384], Wf [128][128], bf [128],
- * Wo [128][5], bo [5]: fp32 device pointers, row-major [fan_in][fan_out], copied on `stream`.  The
+ * We [R][D][128], be [R][128], Wi, Wh [R][128][384] (columns r | z | n), bi, bh [R][384],
+ * Wf [R][128][128], bf [R][128], Wo [R][128][5], bo [R][5] (one set per run): fp32 device pointers,
+ * row-major [fan_in][fan_out], copied on `stream`.  The
  * matrices and every vector that enters a matrix product (obs, e, h, y) are rounded to bf16 (ties
  * to even); sums, biases, gate arithmetic and the carried h are fp32.  While installed it takes
  * precedence over the policy of mpe_set_policy.  h is owned by the handle, cleared by mpe_reset and
  * wherever an episode ends inside mpe_rollout, carried across mpe_rollout calls, untouched by
  * mpe_set_state and by mpe_step (which takes its actions from the caller and neither advances nor
  * clears h: a caller that mixes the two sets h itself with mpe_set_hidden).
- * Built for MPE_SCENARIO_SPREAD, 1..3 agents, hidden 128, MPE_WEIGHTS_BF16, num_runs 1; MPE_EINVAL
- * otherwise or if only some pointers are NULL. */
+ * Built for MPE_SCENARIO_SPREAD, 1..3 agents, hidden 128, MPE_WEIGHTS_BF16; MPE_EINVAL otherwise or if
+ * only some pointers are NULL.  With several runs mpe_rollout needs num_envs to be a multiple of 16. */
 int mpe_set_gru_policy(mpe_env* env, const float* We, const float* be, const float* Wi, const float* bi,
                        const float* Wh, const float* bh, const float* Wf, const float* bf, const float* Wo,
                        const float* bo, void* stream);

@@ -291,7 +291,9 @@ int mpe_rollout(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, float
   A.done_traj = done_traj;
   A.last_obs = last_obs;
   if (e->has_gru) {
-    hipError_t err = launch_rollout_gru(e->N, A, e->gru, e->hidden, static_cast<hipStream_t>(stream));
+    const char* why = nullptr;
+    hipError_t err = launch_rollout_gru(e->N, A, e->gru, e->hidden, static_cast<hipStream_t>(stream), &why);
+    if (why) return fail(MPE_EINVAL, "mpe_rollout: %s", why);
     if (err != hipSuccess) return fail(MPE_EHIP, "mpe_rollout: %s", hipGetErrorString(err));
   } else if (e->tag) {
     TagArgs TA{};
@@ -329,9 +331,9 @@ int mpe_set_gru_policy(mpe_env* e, const float* We, const float* be, const float
     return MPE_OK;
   }
   if (given != 10) return fail(MPE_EINVAL, "mpe_set_gru_policy: pass all ten arrays or none");
-  if (e->tag || e->R != 1 || !gru_supported(e->N, e->H, e->cfg.weight_dtype))
+  if (e->tag || !gru_supported(e->N, e->H, e->cfg.weight_dtype))
     return fail(MPE_EINVAL, "mpe_set_gru_policy: the recurrent policy is built for MPE_SCENARIO_SPREAD with 1..3 "
-                            "agents, hidden 128, MPE_WEIGHTS_BF16 and num_runs 1");
+                            "agents, hidden 128 and MPE_WEIGHTS_BF16");
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (!e->hidden) {
     const size_t n = size_t(e->TE) * e->N * 128;
@@ -339,7 +341,7 @@ int mpe_set_gru_policy(mpe_env* e, const float* We, const float* be, const float
     launch_fill_zero(e->hidden, n, s);
     MPE_HIP(hipGetLastError());
   }
-  hipError_t err = pack_policy_gru(e->gru, e->N, We, be, Wi, bi, Wh, bh, Wf, bf, Wo, bo, s);
+  hipError_t err = pack_policy_gru(e->gru, e->N, int(e->R), We, be, Wi, bi, Wh, bh, Wf, bf, Wo, bo, s);
   if (err != hipSuccess) return fail(MPE_EHIP, "mpe_set_gru_policy: %s", hipGetErrorString(err));
   e->has_gru = true;
   return MPE_OK;

@@ -129,11 +129,12 @@ hipError_t ensure_policy_bytes(PolicyBuffers& pb, size_t bytes);
 
 // Recurrent policy (hidden 128, bf16): simple spread with 1..3 agents.
 bool gru_supported(int N, int H, int weight_dtype);
-hipError_t pack_policy_gru(PolicyBuffers& pb, int N, const float* We, const float* be, const float* Wi,
+hipError_t pack_policy_gru(PolicyBuffers& pb, int N, int R, const float* We, const float* be, const float* Wi,
                            const float* bi, const float* Wh, const float* bh, const float* Wf, const float* bf,
                            const float* Wo, const float* bo, hipStream_t s);
 // hidden: [TE][N][128] fp32, read at the start and written at the end of the rollout
-hipError_t launch_rollout_gru(int N, const RolloutArgs& A, const PolicyBuffers& pb, float* hidden, hipStream_t s);
+hipError_t launch_rollout_gru(int N, const RolloutArgs& A, const PolicyBuffers& pb, float* hidden, hipStream_t s,
+                              const char** why);
 void launch_fill_zero(float* p, size_t n, hipStream_t s);
 
 }  // namespace mpe

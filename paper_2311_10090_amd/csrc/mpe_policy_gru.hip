@@ -40,18 +40,31 @@ struct GruPk {
   static constexpr size_t OFF_OUT = OFF_FC + 32 * 1024;        // [s 4][lane 64]  (5 outputs padded to 16)
   static constexpr size_t OFF_BIAS = OFF_OUT + 4 * 1024;       // fp32: be, bi_r + bh_r, bi_z + bh_z, bi_n, bh_n, bf [128 each], bo [16]
   static constexpr int BIAS_FLOATS = 6 * kG + 16;
-  static constexpr size_t BYTES = OFF_BIAS + size_t(BIAS_FLOATS) * 4;
+  static constexpr size_t BYTES = OFF_BIAS + size_t(BIAS_FLOATS) * 4;   // one run; runs follow each other
+  static_assert(BYTES % 16 == 0, "images of consecutive runs stay 16-byte aligned");
   static constexpr int N_EMB = 8 * 64 * 8, N_GRU = 8 * 24 * 64 * 8, N_FC = 8 * 4 * 64 * 8, N_OUT = 4 * 64 * 8;
   static constexpr int THREADS = N_EMB + N_GRU + N_FC + N_OUT + BIAS_FLOATS;
 };
 
-// One thread per packed bf16 weight or fp32 bias.  D = observation width (<= 32).
+// One thread per packed bf16 weight or fp32 bias of one run (blockIdx.y).  D = observation width (<= 32).
 __global__ void pack_gru_kernel(uint8_t* __restrict__ out, int D, const float* __restrict__ We,
                                 const float* __restrict__ be, const float* __restrict__ Wi,
                                 const float* __restrict__ bi, const float* __restrict__ Wh,
                                 const float* __restrict__ bh, const float* __restrict__ Wf,
                                 const float* __restrict__ bf, const float* __restrict__ Wo,
                                 const float* __restrict__ bo) {
+  const size_t run = blockIdx.y;
+  out += run * GruPk::BYTES;
+  We += run * size_t(D) * kG;
+  be += run * kG;
+  Wi += run * size_t(kG) * 3 * kG;
+  bi += run * 3 * kG;
+  Wh += run * size_t(kG) * 3 * kG;
+  bh += run * 3 * kG;
+  Wf += run * size_t(kG) * kG;
+  bf += run * kG;
+  Wo += run * size_t(kG) * kNumActions;
+  bo += run * kNumActions;
   int idx = blockIdx.x * blockDim.x + threadIdx.x;
   if (idx < GruPk::N_EMB) {
     const int e = idx % 8, lane = (idx / 8) % 64, u = idx / 512;
@@ -134,8 +147,8 @@ __device__ __forceinline__ uint2 pack4_bf16(float a, float b, float c, float d) 
 // to itself, falls with its rows).
 template <int N, int EB>
 __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
-                                                          float* __restrict__ hidden, uint32_t groups,
-                                                          uint32_t groups_per_xcd) {
+                                                          float* __restrict__ hidden, int per_run_weights,
+                                                          uint32_t groups, uint32_t groups_per_xcd) {
   using M = GruSmem<N, EB>;
   constexpr int B = M::B, D = M::D, NT = M::NT;
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -160,6 +173,7 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
   const size_t left = TE - g0;
   const int nvalid = left < size_t(EB) ? int(left) : EB;   // valid envs of this block
   const int vrows = nvalid * N;                            // valid agent rows
+  if (per_run_weights) packed += size_t(uint32_t(g0) / A.E) * GruPk::BYTES;   // the run of this block's envs
 
   // ---- stationary operands: this wavefront's GRU and embedding tiles in registers; the small
   // layers and all biases in LDS
@@ -490,18 +504,25 @@ hipError_t rollout_gru_blocks(const RolloutArgs& A, const PolicyBuffers& pb, flo
   const uint32_t groups = (A.TE + EB - 1) / EB;
   const uint32_t per_xcd = (groups + 7) / 8;
   hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(512), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),
-                     hidden, groups, per_xcd);
+                     hidden, int(A.TE != A.E), groups, per_xcd);
   return hipGetLastError();
 }
 
 template <int N>
-hipError_t rollout_gru_impl(const RolloutArgs& A, const PolicyBuffers& pb, float* hidden, hipStream_t s) {
+hipError_t rollout_gru_impl(const RolloutArgs& A, const PolicyBuffers& pb, float* hidden, hipStream_t s, const char** why) {
   // Smaller blocks while each still gets a CU to itself (measured per 128-step rollout, 3 agents: 16-env
   // blocks 0.57-0.60 ms up to 4,096 envs and 32-env blocks 0.96-1.01 ms up to 8,192 envs against 1.9 ms with
   // 64-env blocks; with more blocks than CUs the 64-env blocks are the fastest).
+  // With one set of weights per run a block must lie inside a run: the largest of 64, 32, 16 that divides
+  // the run size bounds the choice.
   const uint32_t cus = compute_units();
-  if ((A.TE + 15) / 16 <= cus) return rollout_gru_blocks<N, 16>(A, pb, hidden, s);
-  if ((A.TE + 31) / 32 <= cus) return rollout_gru_blocks<N, 32>(A, pb, hidden, s);
+  const bool runs = A.TE != A.E;
+  if (runs && A.E % 16 != 0) {
+    *why = "with several runs, num_envs per run must be a multiple of 16";
+    return hipSuccess;
+  }
+  if ((A.TE + 15) / 16 <= cus || (runs && A.E % 32 != 0)) return rollout_gru_blocks<N, 16>(A, pb, hidden, s);
+  if ((A.TE + 31) / 32 <= cus || (runs && A.E % 64 != 0)) return rollout_gru_blocks<N, 32>(A, pb, hidden, s);
   return rollout_gru_blocks<N, 64>(A, pb, hidden, s);
 }
 
@@ -519,20 +540,21 @@ void launch_fill_zero(float* p, size_t n, hipStream_t s) {
 
 bool gru_supported(int N, int H, int weight_dtype) { return N >= 1 && N <= 3 && H == kG && weight_dtype == 1; }
 
-hipError_t pack_policy_gru(PolicyBuffers& pb, int N, const float* We, const float* be, const float* Wi,
+hipError_t pack_policy_gru(PolicyBuffers& pb, int N, int R, const float* We, const float* be, const float* Wi,
                            const float* bi, const float* Wh, const float* bh, const float* Wf, const float* bf,
                            const float* Wo, const float* bo, hipStream_t s) {
-  if (hipError_t e = ensure_policy_bytes(pb, GruPk::BYTES); e != hipSuccess) return e;
-  hipLaunchKernelGGL(pack_gru_kernel, dim3((GruPk::THREADS + 255) / 256), dim3(256), 0, s,
+  if (hipError_t e = ensure_policy_bytes(pb, size_t(R) * GruPk::BYTES); e != hipSuccess) return e;
+  hipLaunchKernelGGL(pack_gru_kernel, dim3((GruPk::THREADS + 255) / 256, R), dim3(256), 0, s,
                      static_cast<uint8_t*>(pb.packed), 6 * N, We, be, Wi, bi, Wh, bh, Wf, bf, Wo, bo);
   return hipGetLastError();
 }
 
-hipError_t launch_rollout_gru(int N, const RolloutArgs& A, const PolicyBuffers& pb, float* hidden, hipStream_t s) {
+hipError_t launch_rollout_gru(int N, const RolloutArgs& A, const PolicyBuffers& pb, float* hidden, hipStream_t s,
+                              const char** why) {
   switch (N) {
-    case 1: return rollout_gru_impl<1>(A, pb, hidden, s);
-    case 2: return rollout_gru_impl<2>(A, pb, hidden, s);
-    case 3: return rollout_gru_impl<3>(A, pb, hidden, s);
+    case 1: return rollout_gru_impl<1>(A, pb, hidden, s, why);
+    case 2: return rollout_gru_impl<2>(A, pb, hidden, s, why);
+    case 3: return rollout_gru_impl<3>(A, pb, hidden, s, why);
     default: return hipErrorInvalidValue;
   }
 }

@@ -188,9 +188,49 @@ def test_removing_the_recurrent_policy_and_refusals(mods):
     assert ei.value.code == MPE_EINVAL
     env.close()
     for cfg in (Hp.gpu_config(64, 3, 1, 64, 0), Hp.gpu_config(64, 3, 1, 128, 0), Hp.gpu_config(64, 5, 1, 128, 1),
-                Hp.gpu_config(64, 3, 2, 128, 1), Hp.tag_gpu_config(64, 4, 2, 3, 1, 64)):
+                Hp.tag_gpu_config(64, 4, 2, 3, 1, 64)):
         env = MpeEnv(cfg)
         with pytest.raises(MpeError) as ei:
             env.set_gru_policy(*Hp.to_dev(synth.gru_weights(2, 1, env.D)))
         assert ei.value.code == MPE_EINVAL
         env.close()
+    # several runs whose size is not a multiple of 16: the policy is accepted, the rollout is not
+    env = MpeEnv(Hp.gpu_config(40, 3, 2, 128, 1))
+    env.set_gru_policy(*Hp.to_dev(synth.gru_weights(2, 2, 18)))
+    env.reset(1)
+    with pytest.raises(MpeError) as ei:
+        env.rollout(2)
+    assert ei.value.code == MPE_EINVAL
+    env.close()
+
+
+@pytest.mark.parametrize("E,N,R", [(64, 3, 3), (16, 3, 5), (48, 2, 2), (32, 1, 4), (128, 3, 2)])
+def test_several_runs_with_their_own_weights(mods, E, N, R):
+    """One set of recurrent-policy weights per run (blocks of 64, 32 or 16 envs inside a run): free-running
+    episodes against the oracle's runs, carried state included."""
+    say("recurrent policy, %d runs x %d envs, N=%d" % (R, E, N))
+    MpeEnv, Oracle = mods
+    env = MpeEnv(Hp.gpu_config(E, N, R, 128, 1))
+    orc = Oracle(Hp.oracle_config(E, N, R, 128, 1), threads=8)
+    w = synth.gru_weights(9, R, 6 * N)
+    env.set_gru_policy(*Hp.to_dev(w))
+    orc.set_gru(*w)
+    orc.reset(7)
+    env.reset(7)
+    T, TE = 12, E * R
+    obs, act, rew, done, last = [x.cpu().numpy() for x in env.rollout(T, *env.empty_traj(T))]
+    robs, ract, rrew, rdone, rlast = orc.rollout(T)
+    assert np.array_equal(done, rdone)
+    assert np.array_equal(obs[0].astype(np.float64), robs[0])
+    same = (act == ract).all(axis=2)
+    alive = np.logical_and.accumulate(same, axis=0)
+    say("  envs identical after 5 / 12 steps: %.3f / %.3f" % (alive[4].mean(), alive[-1].mean()))
+    assert alive[4].mean() > 0.97 and alive[-1].mean() > 0.93
+    prior = np.vstack([np.ones((1, TE), bool), alive[:-1]])
+    e = np.abs(obs.astype(np.float64) - robs).reshape(T, TE, -1).max(axis=2)
+    assert (e * prior).max() < 1e-3
+    d = np.abs(env.get_hidden().cpu().numpy().astype(np.float64) - orc.get_hidden())[alive[-1]]
+    assert d.size and np.median(d) < 1e-4 and d.max() < 5e-2
+    a0 = act[0].reshape(R, E, N)
+    assert any(not np.array_equal(a0[0], a0[r]) for r in range(1, R))
+    env.close()
