@@ -210,9 +210,10 @@ int mpe_set_hidden(mpe_env* env, const float* hidden, void* stream);
  * the paper's IPPO, Sec. 3.2; App. G: two tanh layers of width 64):
  *   value = V3^T tanh(V2^T tanh(V1^T obs + c1) + c2) + c3
  * V1 [R][D][H], c1 [R][H], V2 [R][H][H], c2 [R][H], V3 [R][H], c3 [R], fp32 device pointers;
- * copied (and rounded, with MPE_WEIGHTS_BF16) as in mpe_set_policy.  Built for hidden 64 and
- * 1..3 agents of MPE_SCENARIO_SPREAD (fp32 or bf16 weights), and for MPE_SCENARIO_TAG with fp32
- * weights, hidden 64 and observation rows of at most 16 floats; MPE_EINVAL otherwise. */
+ * copied (and rounded, with MPE_WEIGHTS_BF16) as in mpe_set_policy.  Built for the shapes of
+ * mpe_set_policy with MPE_SCENARIO_SPREAD (1..3 agents, hidden 64, fp32 or bf16 weights; 4..10 agents,
+ * hidden 64 or 128, bf16 weights), and for MPE_SCENARIO_TAG with fp32 weights, hidden 64 and
+ * observation rows of at most 16 floats; MPE_EINVAL otherwise. */
 int mpe_set_critic(mpe_env* env, const float* V1, const float* c1, const float* V2,
                    const float* c2, const float* V3, const float* c3, void* stream);
 
@@ -223,8 +224,9 @@ int mpe_set_critic(mpe_env* env, const float* V1, const float* c1, const float* 
  * logp_traj, value_traj [T][TE][N] fp32, last_value [TE][N] fp32; the other arrays as in
  * mpe_rollout (rewards [T][TE][N] where mpe_rollout's are).  Any of the eight may be NULL.  Needs
  * a policy and a critic (MPE_ESTATE if one is missing); with several runs num_envs must be a
- * multiple of 16 (fastest: of 256; MPE_SCENARIO_TAG: of 512 / num_agents, of 64 with 3 agents),
- * MPE_EINVAL otherwise. */
+ * multiple of 16 (fastest: of 256; 4 and more agents: of 64, of 32 with 8 agents;
+ * MPE_SCENARIO_TAG: fastest with multiples of 512 / num_agents, of 64 with 3 agents), MPE_EINVAL
+ * otherwise. */
 int mpe_rollout_ac(mpe_env* env, int32_t T, float* obs_traj, uint8_t* act_traj, float* logp_traj,
                    float* value_traj, float* rew_traj, uint8_t* done_traj, float* last_obs,
                    float* last_value, void* stream);

@@ -386,10 +386,12 @@ int mpe_set_critic(mpe_env* e, const float* V1, const float* c1, const float* V2
                               "for fp32 weights, hidden 64 and observation rows of at most 16 floats");
     err = pack_policy_tag(e->critic, e->N, e->L, e->G, int(e->R), false, 1, V1, c1, V2, c2, V3, c3,
                           static_cast<hipStream_t>(stream));
+  } else if (e->cfg.weight_dtype == MPE_WEIGHTS_BF16 && wide_supported(e->N, e->H)) {
+    err = pack_policy_wide(e->critic, e->N, e->H, int(e->R), V1, c1, V2, c2, V3, c3, 1, static_cast<hipStream_t>(stream));
   } else {
     if (!f32_supported(e->N, e->H))
-      return fail(MPE_EINVAL, "mpe_set_critic: unsupported shape: the actor-critic rollout is built for "
-                              "hidden 64 and 1..3 agents");
+      return fail(MPE_EINVAL, "mpe_set_critic: unsupported shape: the actor-critic rollout is built for the "
+                              "shapes of mpe_set_policy");
     err = pack_policy_f32(e->critic, e->N, int(e->R), V1, c1, V2, c2, V3, c3, 1,
                           e->cfg.weight_dtype == MPE_WEIGHTS_BF16, static_cast<hipStream_t>(stream));
   }
@@ -407,7 +409,8 @@ int mpe_rollout_ac(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, fl
   if (!e->has_policy || !e->has_critic)
     return fail(MPE_ESTATE, "mpe_rollout_ac: needs mpe_set_policy and mpe_set_critic first");
   if (e->has_gru) return fail(MPE_ESTATE, "mpe_rollout_ac: remove the recurrent policy first (feed-forward networks only)");
-  if (!e->tag && !f32_supported(e->N, e->H)) return fail(MPE_EINVAL, "mpe_rollout_ac: unsupported shape");
+  const bool wide = !e->tag && e->cfg.weight_dtype == MPE_WEIGHTS_BF16 && wide_supported(e->N, e->H);
+  if (!e->tag && !wide && !f32_supported(e->N, e->H)) return fail(MPE_EINVAL, "mpe_rollout_ac: unsupported shape");
   if (e->tag && e->cfg.weight_dtype != MPE_WEIGHTS_FP32) return fail(MPE_EINVAL, "mpe_rollout_ac: unsupported shape");
   for (const float* p : {obs_traj, logp_traj, value_traj, rew_traj, last_obs, last_value})
     if (p && !aligned16(p)) return fail(MPE_EINVAL, "mpe_rollout_ac: float outputs must be 16-byte aligned");
@@ -438,6 +441,8 @@ int mpe_rollout_ac(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, fl
     TA.actions_in = nullptr;
     err = launch_tag_rollout(e->N, e->L, e->G, 4, TA, e->pol.packed, e->critic.packed,
                              static_cast<hipStream_t>(stream), &why);
+  } else if (wide) {
+    err = launch_rollout_ac_wide(e->N, e->H, A, e->pol, e->critic, static_cast<hipStream_t>(stream), &why);
   } else {
     err = launch_rollout_ac_f32(e->N, e->cfg.weight_dtype == MPE_WEIGHTS_BF16, A, e->pol, e->critic,
                                 static_cast<hipStream_t>(stream), &why);

@@ -113,7 +113,10 @@ void free_policy(PolicyBuffers& pb);
 // Per-kernel-family entry points behind pack_policy / launch_rollout_policy.
 bool wide_supported(int N, int H);                       // bf16 general kernel
 hipError_t pack_policy_wide(PolicyBuffers& pb, int N, int H, int R, const float* W1, const float* b1,
-                            const float* W2, const float* b2, const float* W3, const float* b3, hipStream_t s);
+                            const float* W2, const float* b2, const float* W3, const float* b3, int nout,
+                            hipStream_t s);
+hipError_t launch_rollout_ac_wide(int N, int H, const RolloutArgs& A, const PolicyBuffers& pb,
+                                  const PolicyBuffers& critic, hipStream_t s, const char** why);
 hipError_t launch_rollout_policy_wide(int N, int H, const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s,
                                       const char** why);
 bool uniform_wide_supported(int N);                      // env-only rollout with the wide kernel's mapping

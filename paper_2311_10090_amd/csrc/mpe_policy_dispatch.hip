@@ -29,7 +29,7 @@ static const char* kUnsupported =
 hipError_t pack_policy(PolicyBuffers& pb, int N, int H, int R, int weight_dtype, const float* W1,
                        const float* b1, const float* W2, const float* b2, const float* W3,
                        const float* b3, hipStream_t s, const char** why) {
-  if (weight_dtype == 1 && wide_supported(N, H)) return pack_policy_wide(pb, N, H, R, W1, b1, W2, b2, W3, b3, s);
+  if (weight_dtype == 1 && wide_supported(N, H)) return pack_policy_wide(pb, N, H, R, W1, b1, W2, b2, W3, b3, 5, s);
   if (f32_supported(N, H)) return pack_policy_f32(pb, N, R, W1, b1, W2, b2, W3, b3, 5, weight_dtype == 1, s);
   *why = kUnsupported;
   return hipSuccess;

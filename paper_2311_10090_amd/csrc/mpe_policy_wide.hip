@@ -82,11 +82,12 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
 }
 
 // One thread per packed element of one run (weights rounded to bf16, ties to even).
+// nout = outputs of the network: 5 (policy) or 1 (critic; W3 [H], b3 [1] per run).
 template <int N, int H>
 __global__ void pack_policy_kernel(uint8_t* __restrict__ packed, const float* __restrict__ W1,
                                    const float* __restrict__ b1, const float* __restrict__ W2,
                                    const float* __restrict__ b2, const float* __restrict__ W3,
-                                   const float* __restrict__ b3) {
+                                   const float* __restrict__ b3, int nout) {
   using S = Shape<N, H>;
   const int run = blockIdx.y;
   uint8_t* out = packed + size_t(run) * S::RUN_BYTES;
@@ -94,8 +95,8 @@ __global__ void pack_policy_kernel(uint8_t* __restrict__ packed, const float* __
   b1 += size_t(run) * H;
   W2 += size_t(run) * H * H;
   b2 += size_t(run) * H;
-  W3 += size_t(run) * H * kNumActions;
-  b3 += size_t(run) * kNumActions;
+  W3 += size_t(run) * H * nout;
+  b3 += size_t(run) * nout;
   constexpr int n1 = S::MT * S::S1 * 64 * 8, n2 = S::MT * S::S2 * 64 * 8, n3 = S::S2 * 64 * 8, nb = 2 * H + 16;
   int idx = blockIdx.x * blockDim.x + threadIdx.x;
   auto put = [&](size_t off, int i, float v) { reinterpret_cast<uint16_t*>(out + off)[i] = f32_to_bf16_rne(v); };
@@ -114,7 +115,7 @@ __global__ void pack_policy_kernel(uint8_t* __restrict__ packed, const float* __
   idx -= n2;
   if (idx < n3) {   // [s][lane][e]
     const int e = idx % 8, lane = (idx / 8) % 64, s = idx / 512, o = lane % 16;
-    put(S::OFF_W3A, idx, o < kNumActions ? W3[size_t(hidden_of(s, lane / 16, e)) * kNumActions + o] : 0.0f);
+    put(S::OFF_W3A, idx, o < nout ? W3[size_t(hidden_of(s, lane / 16, e)) * nout + o] : 0.0f);
     return;
   }
   idx -= n3;
@@ -122,7 +123,7 @@ __global__ void pack_policy_kernel(uint8_t* __restrict__ packed, const float* __
     float v;
     if (idx < H) v = b1[idx];
     else if (idx < 2 * H) v = b2[idx - H];
-    else v = (idx - 2 * H) < kNumActions ? b3[idx - 2 * H] : 0.0f;
+    else v = (idx - 2 * H) < nout ? b3[idx - 2 * H] : 0.0f;
     reinterpret_cast<float*>(out + S::OFF_BIAS)[idx] = v;
   }
 }
@@ -130,21 +131,25 @@ __global__ void pack_policy_kernel(uint8_t* __restrict__ packed, const float* __
 // LDS plan of one block (bytes).
 // UNIFORM (no policy: seeded uniform actions): no weights; the stage holds one 16-row tile of
 // observations on its way to the trajectory.
-template <int N, int H, int EB, bool UNIFORM = false>
+// AC (actor-critic rollout): the critic's packed image follows the policy's, and every wavefront has a
+// second stage for the critic's outputs.
+template <int N, int H, int EB, bool UNIFORM = false, bool AC = false>
 struct Smem {
   using S = Shape<N, H>;
   static constexpr int ROWS = EB * N, WAVES = ROWS / 64;
   static constexpr size_t WEIGHTS = UNIFORM ? 0 : S::OFF_BIAS;     // W1A + W2A + W3A
   static constexpr size_t OFF_BIAS = WEIGHTS;
-  static constexpr size_t STAGE_WAVE = UNIFORM ? size_t(16) * S::D * 4 : size_t(64) * 5 * 4;   // else the wave's logits [64][5]
-  static constexpr size_t OFF_STAGE = OFF_BIAS + (UNIFORM ? 0 : S::BIAS_BYTES);
+  static constexpr size_t OFF_CRITIC = OFF_BIAS + (UNIFORM ? 0 : S::BIAS_BYTES);   // AC: W1A, W2A, W3A, biases of the critic
+  static constexpr size_t STAGE_WAVE = UNIFORM ? size_t(16) * S::D * 4 : size_t(AC ? 2 : 1) * 64 * 5 * 4;   // else the wave's logits [64][5] (AC: + values)
+  static constexpr size_t OFF_STAGE = OFF_CRITIC + (AC ? S::RUN_BYTES : 0);
   static constexpr size_t OFF_NEWPOS = OFF_STAGE + WAVES * STAGE_WAVE;   // [2][ROWS] float2, by step parity
   static constexpr size_t OFF_DMIN = OFF_NEWPOS + size_t(2) * ROWS * 8;  // [2][ROWS] float,  by step parity
   static constexpr size_t OFF_LM = OFF_DMIN + size_t(2) * ROWS * 4;      // [EB][N] float2 landmark positions
   static constexpr size_t OFF_RESPOS = OFF_LM + size_t(ROWS) * 8;        // [EB][N] float2 positions after a reset
   static constexpr size_t OFF_ARRIVED = OFF_RESPOS + size_t(ROWS) * 8;   // arrival counter of each sync group
   static constexpr size_t TOTAL = OFF_ARRIVED + 16;
-  static_assert(OFF_STAGE % 16 == 0 && STAGE_WAVE % 16 == 0 && OFF_NEWPOS % 16 == 0, "alignment");
+  static_assert(OFF_STAGE % 16 == 0 && STAGE_WAVE % 16 == 0 && OFF_NEWPOS % 16 == 0 && OFF_CRITIC % 16 == 0, "alignment");
+  static_assert(TOTAL <= 160 * 1024 && !(UNIFORM && AC), "LDS");
 };
 
 // Round two floats to bf16 (nearest even) and pack them: low half <- a.
@@ -259,12 +264,15 @@ __device__ __forceinline__ void policy_tile(const uint8_t* __restrict__ wsm, con
 // UNIFORM: no policy; every agent's action is the seeded uniform draw.  The kernel is then bound
 // by the trajectory stores, and the observation rows leave 16 at a time through the wave's LDS
 // stage as contiguous 3,840-byte pieces (per-lane stores of 240-byte rows sustain only ~3 TB/s).
-template <int N, int H, int EB, int MINW, bool PER_AGENT, bool UNIFORM>
+// AC: a critic of the same shape with one output (`packed_critic`) is evaluated on every observation
+// acted on; its value and the log-probability of the sampled action are recorded (paper Sec. 3.2: IPPO).
+template <int N, int H, int EB, int MINW, bool PER_AGENT, bool UNIFORM, bool AC = false>
 __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
+                                                                      const uint8_t* __restrict__ packed_critic,
                                                                       int per_run_weights, uint32_t groups,
                                                                       uint32_t groups_per_xcd) {
   using S = Shape<N, H>;
-  using M = Smem<N, H, EB, UNIFORM>;
+  using M = Smem<N, H, EB, UNIFORM, AC>;
   constexpr int D = S::D, KIN = S::KIN, ROWS = EB * N, THREADS = ROWS;
   constexpr int RF4 = D / 4;                 // 16-byte chunks of one observation row
   constexpr int PD = S::S1 * 16;             // dwords of one row as bf16 pairs, zero padded to whole K slices
@@ -314,6 +322,12 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
     const uint4* src = reinterpret_cast<const uint4*>(run_weights);
     uint4* dst = reinterpret_cast<uint4*>(wsm);
     for (int k = tid; k < int(S::RUN_BYTES / 16); k += THREADS) dst[k] = src[k];
+    if constexpr (AC) {
+      const uint4* csrc = reinterpret_cast<const uint4*>(
+          packed_critic + (per_run_weights ? size_t(uint32_t(g0) / A.E) * S::RUN_BYTES : 0));
+      uint4* cdst = reinterpret_cast<uint4*>(smem + M::OFF_CRITIC);
+      for (int k = tid; k < int(S::RUN_BYTES / 16); k += THREADS) cdst[k] = csrc[k];
+    }
   }
 
   // ---- registers: own agent and landmark i (the one whose coverage distance this lane
@@ -411,6 +425,32 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
     }
   };
 
+  // The lane's observation as bf16 pairs -> the layer-1 B operands of the wave's four 16-row tiles.
+  [[maybe_unused]] auto pack_operands = [&](const float (&o)[KIN], bf16x8 (&b1)[4][S::S1]) {
+    uint32_t pk[PD];
+#pragma unroll
+    for (int d = 0; d < PD; ++d) pk[d] = (2 * d < KIN) ? pack_bf16(o[(2 * d < KIN) ? 2 * d : 0], o[(2 * d < KIN) ? 2 * d + 1 : 0]) : 0u;
+    // chunk g of slice s = dwords 16 s + 4 g .. + 3 of the packed row
+#pragma unroll
+    for (int s = 0; s < S::S1; ++s) {
+      u32x4 tile_b[4];
+#pragma unroll
+      for (int d = 0; d < 4; ++d) {
+        uint32_t v[4] = {pk[16 * s + d], pk[16 * s + 4 + d], pk[16 * s + 8 + d], pk[16 * s + 12 + d]};
+        transpose_groups(v);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) tile_b[c][d] = v[c];
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c) b1[c][s] = __builtin_bit_cast(bf16x8, tile_b[c]);
+    }
+  };
+  [[maybe_unused]] const uint8_t* csm = smem + M::OFF_CRITIC;                                        // AC only
+  [[maybe_unused]] const float* cbias = reinterpret_cast<const float*>(smem + M::OFF_CRITIC + S::OFF_BIAS);
+  [[maybe_unused]] float* vstage = stage + 64 * 5;                                                   // AC: the critic's outputs
+  [[maybe_unused]] float* logp_base = A.logp_traj;
+  [[maybe_unused]] float* value_base = A.value_traj;
+
   const size_t wave_row0 = (g0 * N + size_t(wave) * 64) * D;   // float offset of this wavefront's rows in a slice
   float* obs_p = A.obs_traj ? A.obs_traj + wave_row0 : nullptr;
   uint8_t* act_base = A.act_traj;
@@ -455,33 +495,42 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
         flush_rows(o, obs_p);
         obs_p += TE * (N * D);
       }
-      uint32_t pk[PD];
-#pragma unroll
-      for (int d = 0; d < PD; ++d) pk[d] = (2 * d < KIN) ? pack_bf16(o[(2 * d < KIN) ? 2 * d : 0], o[(2 * d < KIN) ? 2 * d + 1 : 0]) : 0u;
-      // chunk g of slice s = dwords 16 s + 4 g .. + 3 of the packed row
-#pragma unroll
-      for (int s = 0; s < S::S1; ++s) {
-        u32x4 tile_b[4];
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-          uint32_t v[4] = {pk[16 * s + d], pk[16 * s + 4 + d], pk[16 * s + 8 + d], pk[16 * s + 12 + d]};
-          transpose_groups(v);
-#pragma unroll
-          for (int c = 0; c < 4; ++c) tile_b[c][d] = v[c];
-        }
-#pragma unroll
-        for (int c = 0; c < 4; ++c) b1[c][s] = __builtin_bit_cast(bf16x8, tile_b[c]);
-      }
+      pack_operands(o, b1);
     }
     // ---- policy: four 16-row tiles per wavefront
     if constexpr (!UNIFORM) {
 #pragma unroll
       for (int c = 0; c < 4; ++c) policy_tile<N, H>(wsm, bias, b1[c], stage + c * 16 * 5, lane);
+      if constexpr (AC) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) policy_tile<N, H>(csm, cbias, b1[c], vstage + c * 16 * 5, lane);
+      }
       wave_sync();
       float z[kNumActions];
 #pragma unroll
       for (int k = 0; k < kNumActions; ++k) z[k] = stage[lane * 5 + k];
       act = gumbel_argmax(z, A.seed, run, env, step, uint32_t(i));
+      if constexpr (AC) {
+        // log pi(act | obs) = z_act - max - ln sum exp(z - max)
+        float zmax = z[0], zact = z[0];
+#pragma unroll
+        for (int k = 1; k < kNumActions; ++k) {
+          zmax = fmaxf(zmax, z[k]);
+          zact = act == uint32_t(k) ? z[k] : zact;
+        }
+        float sum = 0.0f;
+#pragma unroll
+        for (int k = 0; k < kNumActions; ++k) sum += hw_exp2((z[k] - zmax) * kLog2e);
+        if (logp_base) {
+          if (valid) logp_base[row_off] = (zact - zmax) - kLn2 * hw_log2(sum);
+          logp_base += TE * N;
+        }
+        if (value_base) {
+          if (valid) value_base[row_off] = vstage[lane * 5];
+          value_base += TE * N;
+        }
+        wave_sync();   // the stages are rewritten by the next step's tiles
+      }
     }
     if (act_base) {
       if (valid) act_base[row_off] = uint8_t(act);
@@ -577,6 +626,18 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
     build_obs(o);
     flush_rows(o, A.last_obs + wave_row0);
   }
+  if constexpr (AC) {
+    if (A.last_value) {   // value of the observation after the last step
+      float o[KIN];
+      build_obs(o);
+      bf16x8 b1[4][S::S1];
+      pack_operands(o, b1);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) policy_tile<N, H>(csm, cbias, b1[c], vstage + c * 16 * 5, lane);
+      wave_sync();
+      if (valid) A.last_value[row_off] = vstage[lane * 5];
+    }
+  }
 
   // ---- state back to HBM
   if (valid) {
@@ -592,26 +653,26 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
 
 template <int N, int H>
 hipError_t pack_impl(PolicyBuffers& pb, int R, const float* W1, const float* b1, const float* W2,
-                     const float* b2, const float* W3, const float* b3, hipStream_t s) {
+                     const float* b2, const float* W3, const float* b3, int nout, hipStream_t s) {
   using S = Shape<N, H>;
   if (hipError_t e = ensure_policy_bytes(pb, size_t(R) * S::RUN_BYTES); e != hipSuccess) return e;
   const int total = int(S::RUN_BYTES / 2);  // upper bound on elements of one run
   dim3 grid(cdiv(total, 256), R);
   hipLaunchKernelGGL((pack_policy_kernel<N, H>), grid, dim3(256), 0, s,
-                     static_cast<uint8_t*>(pb.packed), W1, b1, W2, b2, W3, b3);
+                     static_cast<uint8_t*>(pb.packed), W1, b1, W2, b2, W3, b3, nout);
   return hipGetLastError();
 }
 
-template <int N, int H, int EB, int MINW, bool PER_AGENT, bool UNIFORM = false>
-hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s) {
-  using M = Smem<N, H, EB, UNIFORM>;
-  auto kern = rollout_policy_kernel<N, H, EB, MINW, PER_AGENT, UNIFORM>;
+template <int N, int H, int EB, int MINW, bool PER_AGENT, bool UNIFORM = false, bool AC = false>
+hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s, const void* critic = nullptr) {
+  using M = Smem<N, H, EB, UNIFORM, AC>;
+  auto kern = rollout_policy_kernel<N, H, EB, MINW, PER_AGENT, UNIFORM, AC>;
   static std::atomic<uint64_t> lds_allowed{0};
   if (hipError_t e = allow_lds(reinterpret_cast<const void*>(kern), M::TOTAL, lds_allowed); e != hipSuccess) return e;
   const uint32_t groups = (A.TE + EB - 1) / EB;
   const uint32_t per_xcd = (groups + 7) / 8;
   hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(EB * N), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),
-                     int(A.TE != A.E), groups, per_xcd);
+                     static_cast<const uint8_t*>(critic), int(A.TE != A.E), groups, per_xcd);
   return hipGetLastError();
 }
 
@@ -636,8 +697,9 @@ bool wide_supported(int N, int H) {
 }
 
 hipError_t pack_policy_wide(PolicyBuffers& pb, int N, int H, int R, const float* W1, const float* b1,
-                            const float* W2, const float* b2, const float* W3, const float* b3, hipStream_t s) {
-#define X(N_, H_, EB_, MW_) if (N == N_ && H == H_) return pack_impl<N_, H_>(pb, R, W1, b1, W2, b2, W3, b3, s);
+                            const float* W2, const float* b2, const float* W3, const float* b3, int nout,
+                            hipStream_t s) {
+#define X(N_, H_, EB_, MW_) if (N == N_ && H == H_) return pack_impl<N_, H_>(pb, R, W1, b1, W2, b2, W3, b3, nout, s);
   MPE_WIDE_POLICY_CASES(X)
 #undef X
   return hipErrorInvalidValue;
@@ -672,6 +734,23 @@ hipError_t launch_rollout_policy_wide(int N, int H, const RolloutArgs& A, const 
     }                                                                                            \
     return A.ph.reward_mode == 1 ? rollout_impl<N_, H_, EB_, MW_, true>(A, pb, s)                \
                                  : rollout_impl<N_, H_, EB_, MW_, false>(A, pb, s);              \
+  }
+  MPE_WIDE_POLICY_CASES(X)
+#undef X
+  return hipErrorInvalidValue;
+}
+
+// Actor-critic rollout with the lane-per-agent kernel: policy and critic images both staged per block.
+hipError_t launch_rollout_ac_wide(int N, int H, const RolloutArgs& A, const PolicyBuffers& pb,
+                                  const PolicyBuffers& critic, hipStream_t s, const char** why) {
+#define X(N_, H_, EB_, MW_)                                                                          \
+  if (N == N_ && H == H_) {                                                                          \
+    if (A.TE != A.E && (A.E % EB_) != 0) {                                                           \
+      *why = "with several runs, num_envs per run must be a multiple of the block's env count";      \
+      return hipSuccess;                                                                             \
+    }                                                                                                \
+    return A.ph.reward_mode == 1 ? rollout_impl<N_, H_, EB_, MW_, true, false, true>(A, pb, s, critic.packed)  \
+                                 : rollout_impl<N_, H_, EB_, MW_, false, false, true>(A, pb, s, critic.packed); \
   }
   MPE_WIDE_POLICY_CASES(X)
 #undef X

@@ -142,11 +142,11 @@ def test_actor_critic_errors_and_absent_outputs(mods):
         assert torch.equal(x, y) if hasattr(x, "shape") else x == y
     env.close()
     ref.close()
-    wide = MpeEnv(Hp.gpu_config(64, 10, 1, 128, 1))
+    five = MpeEnv(Hp.gpu_config(64, 5, 1, 64, 0))     # 4 and more agents: bf16 weights only
     with pytest.raises(MpeError) as ei:
-        wide.set_critic(*Hp.to_dev(synth.critic_weights(0, 1, 60, 128)))
+        five.set_critic(*Hp.to_dev(synth.critic_weights(0, 1, 30, 64)))
     assert ei.value.code == MPE_EINVAL
-    wide.close()
+    five.close()
     runs = MpeEnv(Hp.gpu_config(40, 3, 2, 64, 0))     # several runs need num_envs % 64 == 0
     runs.set_policy(*Hp.to_dev(synth.policy_weights(0, 2, 18, 64)))
     runs.set_critic(*Hp.to_dev(synth.critic_weights(0, 2, 18, 64)))
@@ -155,3 +155,56 @@ def test_actor_critic_errors_and_absent_outputs(mods):
         runs.rollout_ac(2)
     assert ei.value.code == MPE_EINVAL
     runs.close()
+
+
+
+@pytest.mark.parametrize("N,H,E,R,kw", [(10, 128, 96, 1, {}), (4, 64, 200, 1, {}), (7, 64, 70, 1, {}), (8, 128, 32, 2, {}),
+                                        (6, 64, 64, 2, dict(reward_mode=1, local_ratio=0.5)), (5, 128, 130, 1, {})])
+def test_actor_critic_with_four_and_more_agents(mods, N, H, E, R, kw):
+    """The lane-per-agent bf16 kernel with a critic: plain outputs bit-identical to mpe_rollout's, T steps =
+    T/2 + T/2, log-probabilities and values against the oracle's bf16 networks on the recorded observations
+    (the statistical bar of bf16 layer inputs: most outputs within the fp32 bar, all within a loose one)."""
+    from scipy.special import log_softmax
+    MpeEnv, Oracle = mods
+    T, D, TE = 16, 6 * N, E * R
+    say("actor-critic N=%d H=%d E=%d R=%d %s" % (N, H, E, R, kw))
+    pw = synth.policy_weights_with_bias(19, R, D, H)
+    cw = synth.critic_weights(19, R, D, H)
+
+    def make(critic=True):
+        e = MpeEnv(Hp.gpu_config(E, N, R, H, 1, **kw))
+        e.set_policy(*Hp.to_dev(pw))
+        if critic:
+            e.set_critic(*Hp.to_dev(cw))
+        e.reset(23)
+        return e
+    a, b, c = make(), make(False), make()
+    orc = Oracle(Hp.oracle_config(E, N, R, H, 1, **kw), threads=8)
+    orc.set_policy(*pw)
+    orc.set_critic(*cw)
+    full = a.rollout_ac(T, *a.empty_traj_ac(T))
+    plain = b.rollout(T, *b.empty_traj(T))
+    for k_ac, k_pl in ((0, 0), (1, 1), (4, 2), (5, 3), (6, 4)):
+        assert torch.equal(full[k_ac], plain[k_pl]), "output %d differs from mpe_rollout" % k_ac
+    h1 = [x.clone() for x in c.rollout_ac(T // 2, *c.empty_traj_ac(T // 2))]
+    h2 = c.rollout_ac(T // 2, *c.empty_traj_ac(T // 2))
+    for k in range(6):
+        assert torch.equal(full[k], torch.cat([h1[k], h2[k]])), "continuation, output %d" % k
+    assert torch.equal(full[6], h2[6]) and torch.equal(full[7], h2[7])
+    obs, act, logp, val = [x.cpu().numpy() for x in full[:4]]
+    last, lastv = full[6].cpu().numpy(), full[7].cpu().numpy()
+    assert logp.shape == (T, TE, N) and val.shape == (T, TE, N) and lastv.shape == (TE, N)
+    for run in range(R):
+        sl = slice(run * E, (run + 1) * E)
+        rows = obs[:, sl].reshape(-1, D).astype(np.float64)
+        z = orc.policy_logits(rows, run=run)
+        ref_lp = log_softmax(z, axis=1)[np.arange(z.shape[0]), act[:, sl].reshape(-1)]
+        pairs = ((logp[:, sl].reshape(-1), ref_lp, "log-prob"), (val[:, sl].reshape(-1), orc.value(rows, run=run), "value"),
+                 (lastv[sl].reshape(-1), orc.value(last[sl].reshape(-1, D).astype(np.float64), run=run), "bootstrap value"))
+        for got, ref, what in pairs:
+            err = np.abs(got - ref) / np.maximum(1.0, np.abs(ref))
+            say("  run %d %s: within 1e-5 %.3f, mean %.2e, worst %.2e" % (run, what, (err <= Hp.STEP_RTOL).mean(), err.mean(), err.max()))
+            assert (err <= Hp.STEP_RTOL).mean() >= 0.9 and err.max() < 2e-2 and err.mean() < 1e-4, what
+    assert bool((full[2] <= 0).all()) and bool(torch.isfinite(full[3]).all())
+    for e in (a, b, c):
+        e.close()
