@@ -278,7 +278,7 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
   constexpr int PD = S::S1 * 16;             // dwords of one row as bf16 pairs, zero padded to whole K slices
   constexpr int GE = sync_group_envs(N), GW = GE * N / 64;   // envs / wavefronts of one sync group
   static_assert(EB % GE == 0 && EB / GE <= 4, "a block is whole sync groups");
-  static_assert((UNIFORM ? D % 4 == 0 : D % 2 == 0) && KIN % 2 == 0,
+  static_assert(D % 2 == 0 && KIN % 2 == 0,
                 "rows are stored as 16-byte chunks (8-byte with an odd agent count) and packed as bf16 pairs");
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   uint8_t* wsm = smem;
@@ -376,30 +376,33 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
   // Store this wavefront's rows to dst (its slot in a [env][N][D] slice).
   auto flush_rows = [&](const float (&o)[KIN], float* dst) {
     if constexpr (UNIFORM) {
-      v4f* st4 = reinterpret_cast<v4f*>(stage);
+      // rows of 6N floats: whole 16-byte chunks when N is even, 8-byte ones when it is odd
+      constexpr int CW = D % 4 == 0 ? 4 : 2, RFC = D / CW;
+      typedef float vC __attribute__((ext_vector_type(CW)));
+      vC* stc = reinterpret_cast<vC*>(stage);
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         wave_sync();  // the stage is free (previous readers done)
         if ((lane >> 4) == c) {
 #pragma unroll
-          for (int q = 0; q < RF4; ++q) {
-            v4f v;
+          for (int q = 0; q < RFC; ++q) {
+            vC v;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = (4 * q + e < KIN) ? o[(4 * q + e < KIN) ? 4 * q + e : 0] : 0.0f;
-            st4[(lane & 15) * RF4 + q] = v;
+            for (int e = 0; e < CW; ++e) v[e] = (CW * q + e < KIN) ? o[(CW * q + e < KIN) ? CW * q + e : 0] : 0.0f;
+            stc[(lane & 15) * RFC + q] = v;
           }
         }
         wave_sync();
-        const int n4 = min(max(wave_rows - 16 * c, 0), 16) * RF4;   // 16-byte chunks of this tile that are valid
-        constexpr int kRounds = (16 * RF4 + 63) / 64;
-        v4f v[kRounds];
+        const int nc = min(max(wave_rows - 16 * c, 0), 16) * RFC;   // chunks of this tile that are valid
+        constexpr int kRounds = (16 * RFC + 63) / 64;
+        vC v[kRounds];
 #pragma unroll
         for (int rd = 0; rd < kRounds; ++rd)
-          if (rd * 64 + lane < n4) v[rd] = st4[rd * 64 + lane];
-        v4f* d4 = reinterpret_cast<v4f*>(dst) + c * (16 * RF4);
+          if (rd * 64 + lane < nc) v[rd] = stc[rd * 64 + lane];
+        vC* dc = reinterpret_cast<vC*>(dst) + c * (16 * RFC);
 #pragma unroll
         for (int rd = 0; rd < kRounds; ++rd)
-          if (rd * 64 + lane < n4) __builtin_nontemporal_store(v[rd], &d4[rd * 64 + lane]);
+          if (rd * 64 + lane < nc) __builtin_nontemporal_store(v[rd], &dc[rd * 64 + lane]);
       }
       wave_sync();
     } else if (lane < wave_rows) {
@@ -685,9 +688,11 @@ hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream
 #define MPE_WIDE_POLICY_CASES(X) \
   X(10, 128, 64, 3) X(10, 64, 64, 3) X(9, 128, 64, 3) X(9, 64, 64, 3) X(8, 128, 32, 3) X(8, 64, 32, 3) X(7, 128, 64, 3) \
   X(7, 64, 64, 3) X(6, 128, 64, 3) X(6, 64, 64, 3) X(5, 128, 64, 3) X(5, 64, 64, 3) X(4, 128, 64, 3) X(4, 64, 64, 3)
-// Env-only rollouts that use this kernel's lane-per-agent mapping (the other agent counts use the
-// env-per-lane kernels).
-#define MPE_WIDE_CASES(X) X(10, 128, 64, 3)
+// Env-only rollouts that use this kernel's lane-per-agent mapping: 4 and more agents (measured 4.6-5.3 TB/s
+// of trajectory writes against 1.8-4.2 TB/s of the env-per-lane kernel, whose lanes each own 6 N^2 floats
+// per step); the width is not used there.
+#define MPE_WIDE_CASES(X) \
+  X(10, 128, 64, 3) X(9, 64, 64, 3) X(8, 64, 32, 3) X(7, 64, 64, 3) X(6, 64, 64, 3) X(5, 64, 64, 3) X(4, 64, 64, 3)
 
 bool wide_supported(int N, int H) {
 #define X(N_, H_, EB_, MW_) if (N == N_ && H == H_) return true;

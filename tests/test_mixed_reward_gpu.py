@@ -102,7 +102,7 @@ def test_step_mixed_reward(mods, E, N):
     env.close()
 
 
-@pytest.mark.parametrize("E,N,R", [(64, 3, 1), (100, 3, 1), (128, 2, 2), (70, 10, 1)])
+@pytest.mark.parametrize("E,N,R", [(64, 3, 1), (100, 3, 1), (128, 2, 2), (70, 10, 1), (50, 7, 2), (40, 6, 1), (33, 9, 1)])
 def test_uniform_rollout_mixed_reward(mods, E, N, R):
     say("mixed reward, env-only rollout E=%d N=%d R=%d" % (E, N, R))
     env, orc = _pair(mods, E, N, R)

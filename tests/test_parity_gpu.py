@@ -108,7 +108,9 @@ def _episode_errors(obs, ref_obs, done_ref):
                                                (50, 10, 60, 4, False), (64, 1, 30, 5, True), (65, 2, 30, 6, False),
                                                (33, 4, 30, 7, False), (1000, 3, 125, 8, False),
                                                (1024, 3, 50, 9, False), (128, 2, 30, 10, False),
-                                               (130, 10, 30, 11, False), (64, 10, 27, 12, False)])
+                                               (130, 10, 30, 11, False), (64, 10, 27, 12, False),
+                                               (70, 5, 30, 13, False), (40, 6, 30, 14, False), (100, 7, 27, 15, False),
+                                               (24, 8, 30, 16, False), (65, 9, 30, 17, False)])
 def test_uniform_rollout_matches_oracle(mods, E, N, T, seed, strict):
     MpeEnv, Oracle = mods
     say("uniform rollout E=%d N=%d T=%d seed=%d" % (E, N, T, seed))
