@@ -48,9 +48,13 @@ struct SmemF32 {
   using P = PkT<BF>;
   static constexpr int D = 6 * N;
   static constexpr int ROWS = (EB * N + RW - 1) / RW * RW;
-  static constexpr size_t OFF_BIAS = AC ? P::OFF_BIAS : P::LDS_BYTES;
+  // LEAN (actor-critic in 16-env blocks, i.e. many small runs): W3A of both networks stays in global memory
+  // (re-read every step, 64 bytes per lane), so that two blocks fit a CU instead of one.
+  static constexpr bool LEAN = AC && EB == 16;
+  static constexpr size_t OFF_BIAS = (AC && !LEAN) ? P::OFF_BIAS : P::LDS_BYTES;
   static constexpr size_t OFF_CRITIC = OFF_BIAS + P::BIAS_BYTES;     // AC: the critic's packed image
-  static constexpr size_t OFF_OBS = OFF_CRITIC + (AC ? P::RUN_BYTES : 0);
+  static constexpr size_t CRITIC_BIAS = LEAN ? P::LDS_BYTES : P::OFF_BIAS;   // offset of its biases inside it
+  static constexpr size_t OFF_OBS = OFF_CRITIC + (AC ? (LEAN ? P::LDS_BYTES + P::BIAS_BYTES : P::RUN_BYTES) : 0);
   static constexpr size_t OBS = size_t(ROWS) * D * 4 + 64;           // + zeroed tail: layer 1 reads 16 cols
   static constexpr size_t OFF_NEWPOS = OFF_OBS + OBS;                // [2][ROWS] float2, by step parity
   static constexpr size_t OFF_VALUE = OFF_NEWPOS + size_t(2) * ROWS * 8;   // AC: [ROWS] float
@@ -100,7 +104,7 @@ __global__ __launch_bounds__((EB * N + RW - 1) / RW * 64, MINW) void rollout_pol
   float* tile = reinterpret_cast<float*>(smem + M::OFF_OBS);
   float2* newpos = reinterpret_cast<float2*>(smem + M::OFF_NEWPOS);
   const uint8_t* csm = smem + M::OFF_CRITIC;                                         // AC only
-  const float* cbias = reinterpret_cast<const float*>(smem + M::OFF_CRITIC + P::OFF_BIAS);
+  const float* cbias = reinterpret_cast<const float*>(smem + M::OFF_CRITIC + M::CRITIC_BIAS);
   float* values = reinterpret_cast<float*>(smem + M::OFF_VALUE);
 
   // Wavefront -> rows.  With several sync groups per block (EB > 64) the N wavefronts of group g are
@@ -138,6 +142,11 @@ __global__ __launch_bounds__((EB * N + RW - 1) / RW * 64, MINW) void rollout_pol
 
   // ---- stage this block's weights (the run of its first env): W1A, W2A, biases in LDS; W3A in registers
   const uint8_t* run_weights = packed + (per_run_weights ? size_t(uint32_t(g0) / A.E) * P::RUN_BYTES : 0);
+  [[maybe_unused]] const uint8_t* critic_weights =
+      AC ? packed_critic + (per_run_weights ? size_t(uint32_t(g0) / A.E) * P::RUN_BYTES : 0) : nullptr;
+  // where the layer-3 operands are re-read from in the actor-critic rollout
+  [[maybe_unused]] const uint8_t* w3_policy = M::LEAN ? run_weights : smem;
+  [[maybe_unused]] const uint8_t* w3_critic = M::LEAN ? critic_weights : smem + M::OFF_CRITIC;
   // A operands of layer 3 from a packed image (global memory or LDS)
   auto load_w3 = [&](const uint8_t* image) {
     W3Terms w;
@@ -160,10 +169,25 @@ __global__ __launch_bounds__((EB * N + RW - 1) / RW * 64, MINW) void rollout_pol
     // the packed image is W1A, W2A, W3A, biases; plain rollouts skip W3A (it is in registers)
     const uint4* src = reinterpret_cast<const uint4*>(run_weights);
     uint4* dst = reinterpret_cast<uint4*>(wsm);
-    if constexpr (AC) {
+    if constexpr (M::LEAN) {
+      // W1A + W2A and the biases of both networks
+      const uint4* csrc = reinterpret_cast<const uint4*>(critic_weights);
+      uint4* cdst = reinterpret_cast<uint4*>(smem + M::OFF_CRITIC);
+      for (int k = threadIdx.x; k < int(P::LDS_BYTES / 16); k += THREADS) {
+        dst[k] = src[k];
+        cdst[k] = csrc[k];
+      }
+      const uint4* bsrc = reinterpret_cast<const uint4*>(run_weights + P::OFF_BIAS);
+      const uint4* cbsrc = reinterpret_cast<const uint4*>(critic_weights + P::OFF_BIAS);
+      uint4* bdst = reinterpret_cast<uint4*>(bias);
+      uint4* cbdst = reinterpret_cast<uint4*>(smem + M::OFF_CRITIC + M::CRITIC_BIAS);
+      for (int k = threadIdx.x; k < int(P::BIAS_BYTES / 16); k += THREADS) {
+        bdst[k] = bsrc[k];
+        cbdst[k] = cbsrc[k];
+      }
+    } else if constexpr (AC) {
       for (int k = threadIdx.x; k < int(P::RUN_BYTES / 16); k += THREADS) dst[k] = src[k];
-      const uint4* csrc = reinterpret_cast<const uint4*>(
-          packed_critic + (per_run_weights ? size_t(uint32_t(g0) / A.E) * P::RUN_BYTES : 0));
+      const uint4* csrc = reinterpret_cast<const uint4*>(critic_weights);
       uint4* cdst = reinterpret_cast<uint4*>(smem + M::OFF_CRITIC);
       for (int k = threadIdx.x; k < int(P::RUN_BYTES / 16); k += THREADS) cdst[k] = csrc[k];
     } else {
@@ -241,7 +265,7 @@ __global__ __launch_bounds__((EB * N + RW - 1) / RW * 64, MINW) void rollout_pol
     for (int pr = 0; pr < RW / 32; ++pr) {
       float* rows = tile + (wave * RW + pr * 32) * D;
       float* vals = values + wave * RW + pr * 32;
-      const W3Terms wc = load_w3(csm);
+      const W3Terms wc = load_w3(w3_critic);
       if constexpr (BF) policy_pair_bf<SpreadNet<N>, true>(csm, cbias, wc, rows, rows + 16 * D, lane, vals, vals + 16);
       else policy_pair<SpreadNet<N>, true>(csm, cbias, wc, rows, rows + 16 * D, lane, vals, vals + 16);
     }
@@ -266,7 +290,7 @@ __global__ __launch_bounds__((EB * N + RW - 1) / RW * 64, MINW) void rollout_pol
 #pragma unroll 1
     for (int pr = 0; pr < RW / 32; ++pr) {
       float* rows = tile + (wave * RW + pr * 32) * D;
-      if constexpr (AC) w3 = load_w3(wsm);
+      if constexpr (AC) w3 = load_w3(w3_policy);
       if constexpr (BF) policy_pair_bf<SpreadNet<N>>(wsm, bias, w3, rows, rows + 16 * D, lane);
       else policy_pair<SpreadNet<N>>(wsm, bias, w3, rows, rows + 16 * D, lane);
     }
