@@ -332,7 +332,7 @@ int mpe_set_gru_policy(mpe_env* e, const float* We, const float* be, const float
   }
   if (given != 10) return fail(MPE_EINVAL, "mpe_set_gru_policy: pass all ten arrays or none");
   if (e->tag || !gru_supported(e->N, e->H, e->cfg.weight_dtype))
-    return fail(MPE_EINVAL, "mpe_set_gru_policy: the recurrent policy is built for MPE_SCENARIO_SPREAD with 1..3 "
+    return fail(MPE_EINVAL, "mpe_set_gru_policy: the recurrent policy is built for MPE_SCENARIO_SPREAD with 1..5 "
                             "agents, hidden 128 and MPE_WEIGHTS_BF16");
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (!e->hidden) {

@@ -522,8 +522,10 @@ hipError_t rollout_gru_impl(const RolloutArgs& A, const PolicyBuffers& pb, float
     return hipSuccess;
   }
   if ((A.TE + 15) / 16 <= cus || (runs && A.E % 32 != 0)) return rollout_gru_blocks<N, 16>(A, pb, hidden, s);
-  if ((A.TE + 31) / 32 <= cus || (runs && A.E % 64 != 0)) return rollout_gru_blocks<N, 32>(A, pb, hidden, s);
-  return rollout_gru_blocks<N, 64>(A, pb, hidden, s);
+  // 4 and 5 agents: the activations of 64 envs do not fit the LDS, their largest block is 32 envs
+  if (N > 3 || (A.TE + 31) / 32 <= cus || (runs && A.E % 64 != 0)) return rollout_gru_blocks<N, 32>(A, pb, hidden, s);
+  if constexpr (N <= 3) return rollout_gru_blocks<N, 64>(A, pb, hidden, s);
+  return hipErrorInvalidValue;
 }
 
 __global__ void fill_zero_kernel(float* __restrict__ p, size_t n) {
@@ -538,7 +540,8 @@ void launch_fill_zero(float* p, size_t n, hipStream_t s) {
   hipLaunchKernelGGL(fill_zero_kernel, dim3(uint32_t(blocks < 4096 ? blocks : 4096)), dim3(256), 0, s, p, n);
 }
 
-bool gru_supported(int N, int H, int weight_dtype) { return N >= 1 && N <= 3 && H == kG && weight_dtype == 1; }
+// The observation (6 N floats) must fit the one K slice of 32 inputs of the embedding: N <= 5.
+bool gru_supported(int N, int H, int weight_dtype) { return N >= 1 && N <= 5 && H == kG && weight_dtype == 1; }
 
 hipError_t pack_policy_gru(PolicyBuffers& pb, int N, int R, const float* We, const float* be, const float* Wi,
                            const float* bi, const float* Wh, const float* bh, const float* Wf, const float* bf,
@@ -555,6 +558,8 @@ hipError_t launch_rollout_gru(int N, const RolloutArgs& A, const PolicyBuffers& 
     case 1: return rollout_gru_impl<1>(A, pb, hidden, s, why);
     case 2: return rollout_gru_impl<2>(A, pb, hidden, s, why);
     case 3: return rollout_gru_impl<3>(A, pb, hidden, s, why);
+    case 4: return rollout_gru_impl<4>(A, pb, hidden, s, why);
+    case 5: return rollout_gru_impl<5>(A, pb, hidden, s, why);
     default: return hipErrorInvalidValue;
   }
 }

@@ -151,7 +151,8 @@ def test_predator_prey_block_shapes_agree_bit_for_bit_and_with_the_oracle(mods, 
 
 
 # recurrent policy: 16-env blocks up to 4,096 envs, 32-env blocks up to 8,192, 64-env blocks beyond
-@pytest.mark.parametrize("N,sizes", [(3, (4096, 4100, 8192, 8200)), (1, (100, 5000, 9000)), (2, (4090, 8300))])
+@pytest.mark.parametrize("N,sizes", [(3, (4096, 4100, 8192, 8200)), (1, (100, 5000, 9000)), (2, (4090, 8300)),
+                                     (4, (3000, 4200, 9000)), (5, (4096, 8200))])
 def test_recurrent_block_shapes_agree_bit_for_bit_and_with_the_oracle(mods, N, sizes):
     say("recurrent block shapes N=%d sizes=%s" % (N, sizes))
     w = synth.gru_weights(23, 1, 6 * N)

@@ -43,7 +43,7 @@ def _pair(mods, E, N, wseed=3, max_ep=synth.MAX_EPISODE_STEPS, reward_mode=0):
     return env, orc, w
 
 
-@pytest.mark.parametrize("E,N,T", [(256, 3, 12), (100, 3, 12), (64, 1, 12), (130, 2, 12), (2048, 3, 6)])
+@pytest.mark.parametrize("E,N,T", [(256, 3, 12), (100, 3, 12), (64, 1, 12), (130, 2, 12), (2048, 3, 6), (100, 4, 8), (70, 5, 8)])
 def test_teacher_forced_steps(mods, E, N, T):
     say("recurrent policy, forced steps E=%d N=%d T=%d" % (E, N, T))
     env, orc, _ = _pair(mods, E, N)
@@ -90,7 +90,7 @@ def test_teacher_forced_steps(mods, E, N, T):
     env.close()
 
 
-@pytest.mark.parametrize("E,N", [(200, 3), (64, 2)])
+@pytest.mark.parametrize("E,N", [(200, 3), (64, 2), (90, 4), (50, 5)])
 def test_free_running_statistics(mods, E, N):
     """Free-running episodes: actions equal until the first bf16 rounding flip that changes a
     sample; the share of (env, agent, step) samples that agree stays high over an episode."""
@@ -187,7 +187,7 @@ def test_removing_the_recurrent_policy_and_refusals(mods):
         env.set_gru_policy(*w[:9], None)
     assert ei.value.code == MPE_EINVAL
     env.close()
-    for cfg in (Hp.gpu_config(64, 3, 1, 64, 0), Hp.gpu_config(64, 3, 1, 128, 0), Hp.gpu_config(64, 5, 1, 128, 1),
+    for cfg in (Hp.gpu_config(64, 3, 1, 64, 0), Hp.gpu_config(64, 3, 1, 128, 0), Hp.gpu_config(64, 6, 1, 128, 1),
                 Hp.tag_gpu_config(64, 4, 2, 3, 1, 64)):
         env = MpeEnv(cfg)
         with pytest.raises(MpeError) as ei:
@@ -204,7 +204,7 @@ def test_removing_the_recurrent_policy_and_refusals(mods):
     env.close()
 
 
-@pytest.mark.parametrize("E,N,R", [(64, 3, 3), (16, 3, 5), (48, 2, 2), (32, 1, 4), (128, 3, 2)])
+@pytest.mark.parametrize("E,N,R", [(64, 3, 3), (16, 3, 5), (48, 2, 2), (32, 1, 4), (128, 3, 2), (32, 4, 3), (16, 5, 4)])
 def test_several_runs_with_their_own_weights(mods, E, N, R):
     """One set of recurrent-policy weights per run (blocks of 64, 32 or 16 envs inside a run): free-running
     episodes against the oracle's runs, carried state included."""
