@@ -200,6 +200,7 @@ __device__ __forceinline__ void policy_tile(const uint8_t* __restrict__ wsm, con
   using S = Shape<N, H>;
   constexpr int MT = S::MT;
   const int j = lane & 15, gq = lane >> 4;
+  __builtin_amdgcn_s_setprio(2);   // the network goes ahead of the vector-only env step of other wavefronts
   // Weights and biases are re-read from LDS for every tile on purpose: the addresses go through
   // an opaque zero offset, so the compiler cannot hoist loop-invariant operands out of the step
   // loop (which would cost registers and a wavefront of occupancy).  The offset is an integer,
@@ -251,6 +252,7 @@ __device__ __forceinline__ void policy_tile(const uint8_t* __restrict__ wsm, con
     else z0 = MPE_MFMA_BF(w3[s * 64], b, z0);
   }
   z0 += z1;
+  __builtin_amdgcn_s_setprio(0);
   // lane (j, gq) holds outputs 4gq + r of row j: outputs 0..3 in group 0, output 4 in group 1
   if (gq == 0) {
 #pragma unroll
