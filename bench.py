@@ -20,7 +20,37 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
-MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix
+MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix; the fp32 vector peak is the same number
+KERNEL_SOURCES = ("paper_2311_10090_amd/csrc", "include")
+
+
+def kernel_source_hash():
+    """sha256 over the HIP sources and the header: counter figures stored under profiles/ carry the hash of
+    the sources they were measured on, and are reported only while it still matches."""
+    import hashlib
+    h = hashlib.sha256()
+    for d in KERNEL_SOURCES:
+        for name in sorted(os.listdir(os.path.join(ROOT, d))):
+            if name.endswith((".hip", ".h")):
+                h.update(name.encode())
+                h.update(open(os.path.join(ROOT, d, name), "rb").read())
+    return h.hexdigest()
+
+
+def spread_env(synth, *a, **kw):
+    from paper_2311_10090_amd.binding import MpeConfig, MpeEnv
+    return MpeEnv(MpeConfig(**synth.spread_config(*a, **kw)))
+
+
+def tag_env(synth, *a, **kw):
+    from paper_2311_10090_amd.binding import MpeConfig, MpeEnv
+    return MpeEnv(MpeConfig(**synth.tag_config(*a, **kw)))
+
+
+def to_dev(arrs):
+    import numpy as np
+    import torch
+    return [torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0") for a in arrs]
 
 
 def flops_per_agent_step(D, H, A=5):
@@ -51,13 +81,13 @@ def time_rollouts(env, T, bufs, steps, warmup):
 def cpu_baseline(workload, weights, T, seed, target_seconds=12.0):
     """Time the oracle on envs 0..n-1 of the same workload.  n is sized from a short probe so that
     the timed run takes about target_seconds on this machine's cores (bounded by the workload)."""
-    from oracle import Oracle
-    from tests import helpers as Hp
+    from oracle import Oracle, OracleConfig
+    from paper_2311_10090_amd import synth
     cores = max(1, min(os.cpu_count() or 1, 16))
 
     def run(n, threads=cores):
-        orc = Oracle(Hp.oracle_config(n, workload.num_agents, 1, workload.hidden, workload.weight_dtype),
-                     threads=threads)
+        orc = Oracle(OracleConfig(**synth.spread_config(n, workload.num_agents, 1, workload.hidden, workload.weight_dtype,
+                                                        as_f32=True)), threads=threads)
         orc.set_policy(*weights)
         orc.reset(seed)
         t0 = time.perf_counter()
@@ -86,7 +116,14 @@ def main():
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target duration of the oracle timing")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain device copy of the observation trajectory (for counter calibration)")
+    ap.add_argument("--only-headline", action="store_true", help="skip the secondary workloads (short profiler runs)")
+    ap.add_argument("--print-source-hash", action="store_true")
     args = ap.parse_args()
+    if args.print_source_hash:
+        print(kernel_source_hash())
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (independent envs shard trivially, but no "
               "multi-GPU path is built); rerun with --gpus 1", file=sys.stderr)
@@ -95,8 +132,6 @@ def main():
     import numpy as np
     import torch
     from paper_2311_10090_amd import synth
-    from paper_2311_10090_amd.binding import MpeEnv
-    from tests import helpers as Hp
 
     assert torch.cuda.is_available(), "bench.py needs an MI355X; there is no CPU fallback"
     wl = synth.WORKLOADS[args.workload]
@@ -104,11 +139,18 @@ def main():
     TE = wl.total_envs
 
     # ---- fused rollout (the metric)
-    env = MpeEnv(Hp.gpu_config(wl.num_envs, N, wl.num_runs, H, wl.weight_dtype))
+    env = spread_env(synth, wl.num_envs, N, wl.num_runs, H, wl.weight_dtype)
     weights = synth.policy_weights(0, wl.num_runs, D, H)
-    env.set_policy(*Hp.to_dev(weights))
+    env.set_policy(*to_dev(weights))
     env.reset(seed)
     bufs = env.empty_traj(T)
+    # One plain copy of known size (the observation trajectory onto a second buffer), outside every timed
+    # region: under `rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE` this dispatch calibrates the byte counters.
+    if args.calibration_copy:
+        spare = torch.empty_like(bufs[0])
+        spare.copy_(bufs[0])
+        torch.cuda.synchronize()
+        del spare
     wall, kern_ms = time_rollouts(env, T, bufs, args.steps, args.warmup)
     ms_per_step = wall / args.steps * 1e3
     agent_steps = TE * N * T
@@ -128,7 +170,7 @@ def main():
     env.close()
 
     # ---- env-only rollout, same shape (HBM roofline figure)
-    env2 = MpeEnv(Hp.gpu_config(wl.num_envs, N, wl.num_runs, 0, 0))
+    env2 = spread_env(synth, wl.num_envs, N, wl.num_runs, 0, 0)
     env2.reset(seed)
     wall2, kern2 = time_rollouts(env2, T, bufs, args.steps, args.warmup)
     k2avg = float(np.mean(kern2))
@@ -150,10 +192,11 @@ def main():
 
     # the mixed per-agent reward mode on the same shape (rewards [T][TE][N]; a few calls)
     mixed = {}
-    if wl.weight_dtype == 0 or N == 10:
+    extras = not args.only_headline
+    if extras and (wl.weight_dtype == 0 or N == 10):
         k = max(3, args.steps // 3)
-        env3 = MpeEnv(Hp.gpu_config(wl.num_envs, N, wl.num_runs, H, wl.weight_dtype, reward_mode=1, local_ratio=0.5))
-        env3.set_policy(*Hp.to_dev(weights))
+        env3 = spread_env(synth, wl.num_envs, N, wl.num_runs, H, wl.weight_dtype, reward_mode=1, local_ratio=0.5)
+        env3.set_policy(*to_dev(weights))
         env3.reset(seed)
         b3 = env3.empty_traj(T)
         w3, k3 = time_rollouts(env3, T, b3, k, 2)
@@ -169,11 +212,11 @@ def main():
 
     # actor-critic rollout on the same shape (adds log-prob, value and bootstrap value outputs)
     ac = {}
-    if wl.weight_dtype == 0 and wl.num_runs == 1:
+    if extras and wl.weight_dtype == 0 and wl.num_runs == 1:
         k = max(3, args.steps // 3)
-        env4 = MpeEnv(Hp.gpu_config(wl.num_envs, N, wl.num_runs, H, 0))
-        env4.set_policy(*Hp.to_dev(weights))
-        env4.set_critic(*Hp.to_dev(synth.critic_weights(0, wl.num_runs, D, H)))
+        env4 = spread_env(synth, wl.num_envs, N, wl.num_runs, H, 0)
+        env4.set_policy(*to_dev(weights))
+        env4.set_critic(*to_dev(synth.critic_weights(0, wl.num_runs, D, H)))
         env4.reset(seed)
         b4 = env4.empty_traj_ac(T)
         for _ in range(2):
@@ -194,10 +237,10 @@ def main():
 
     # the same shape with bf16 weights and layer inputs (fp32 accumulate), as defined by the oracle's bf16 mode
     bf = {}
-    if wl.weight_dtype == 0:
+    if extras and wl.weight_dtype == 0:
         k = max(3, args.steps // 3)
-        env5 = MpeEnv(Hp.gpu_config(wl.num_envs, N, wl.num_runs, H, 1))
-        env5.set_policy(*Hp.to_dev(weights))
+        env5 = spread_env(synth, wl.num_envs, N, wl.num_runs, H, 1)
+        env5.set_policy(*to_dev(weights))
         env5.reset(seed)
         b5 = env5.empty_traj(T)
         w5, k5 = time_rollouts(env5, T, b5, k, 2)
@@ -210,11 +253,11 @@ def main():
     # the paper's own many-seeds setting: 1,024 training runs (App. F) of 16 parallel envs each (App. G, IPPO
     # on MPE), every run with its own policy weights, and the whole batch at several sizes
     runs16 = {}
-    if args.workload == "cfg2":
+    if extras and args.workload == "cfg2":
         k = max(3, args.steps // 3)
         for nruns, per_run in ((1024, 16), (1024, 32)):
-            env7 = MpeEnv(Hp.gpu_config(per_run, N, nruns, H, 0))
-            env7.set_policy(*Hp.to_dev(synth.policy_weights(0, nruns, D, H)))
+            env7 = spread_env(synth, per_run, N, nruns, H, 0)
+            env7.set_policy(*to_dev(synth.policy_weights(0, nruns, D, H)))
             env7.reset(seed)
             b7 = env7.empty_traj(T)
             w7, k7 = time_rollouts(env7, T, b7, k, 2)
@@ -228,16 +271,16 @@ def main():
     # second scenario (predator-prey, 3 adversaries + 1 good agent + 2 obstacles) at the same number of
     # envs and steps: fused fp32 policy 16 -> 64 -> 64 -> 5 and env-only with uniform actions
     tag = {}
-    if args.workload == "cfg2":
+    if extras and args.workload == "cfg2":
         k = max(3, args.steps // 3)
         tN, tL, tA = 4, 2, 3
-        tD = Hp.tag_obs_dim(tN, tL, tA)
+        tD = synth.tag_obs_dim(tN, tL, tA)
         t_bytes = tN * tD * 4 + tN + 4 * tN + 1                 # obs + actions + per-agent rewards + done: 277
         t_steps = wl.num_envs * tN * T
         for name, hidden, wd6 in (("fused", H, 0), ("fused_bf16", H, 1), ("env_only", 0, 0)):
-            env6 = MpeEnv(Hp.tag_gpu_config(wl.num_envs, tN, tL, tA, 1, hidden, wd=wd6))
+            env6 = tag_env(synth, wl.num_envs, tN, tL, tA, 1, hidden, wd6)
             if hidden:
-                env6.set_policy(*Hp.to_dev(synth.policy_weights(0, 1, tD, hidden)))
+                env6.set_policy(*to_dev(synth.policy_weights(0, 1, tD, hidden)))
             env6.reset(seed)
             b6 = env6.empty_traj(T)
             w6, k6 = time_rollouts(env6, T, b6, k, 2)
@@ -252,9 +295,9 @@ def main():
             env6.close()
             del b6
         # actor-critic rollout of the same scenario (policy + critic of the same shape with one output)
-        env6 = MpeEnv(Hp.tag_gpu_config(wl.num_envs, tN, tL, tA, 1, H))
-        env6.set_policy(*Hp.to_dev(synth.policy_weights(0, 1, tD, H)))
-        env6.set_critic(*Hp.to_dev(synth.critic_weights(0, 1, tD, H)))
+        env6 = tag_env(synth, wl.num_envs, tN, tL, tA, 1, H)
+        env6.set_policy(*to_dev(synth.policy_weights(0, 1, tD, H)))
+        env6.set_critic(*to_dev(synth.critic_weights(0, 1, tD, H)))
         env6.reset(seed)
         b6 = env6.empty_traj_ac(T)
         for _ in range(2):
@@ -278,10 +321,10 @@ def main():
 
     # recurrent policy (GRU 128, bf16) on the headline env shape
     gru = {}
-    if args.workload == "cfg2":
+    if extras and args.workload == "cfg2":
         k = max(3, args.steps // 3)
-        env7 = MpeEnv(Hp.gpu_config(wl.num_envs, N, 1, 128, 1))
-        env7.set_gru_policy(*Hp.to_dev(synth.gru_weights(0, 1, D)))
+        env7 = spread_env(synth, wl.num_envs, N, 1, 128, 1)
+        env7.set_gru_policy(*to_dev(synth.gru_weights(0, 1, D)))
         env7.reset(seed)
         b7 = env7.empty_traj(T)
         w7, k7 = time_rollouts(env7, T, b7, k, 2)
@@ -319,11 +362,17 @@ def main():
             "kernel": (("rollout_policy_f32_reg_kernel" if wl.num_runs > 1 and wl.num_envs % 64 == 0 and TE >= 65536
                         else "rollout_policy_f32_kernel") if wl.weight_dtype == 0 else "rollout_policy_kernel")
                       + " (fused, one launch per step)",
-            # fp32 shape: the contraction's fp32 FLOPs against the chip's fp32 matrix peak (the
-            # kernel runs them on the bf16 matrix cores with an exact 3-term operand split)
-            "bound": "mfma", "achieved": tflops, "peak": MFMA_FP32_PEAK_TFLOPS if wl.weight_dtype == 0 else 2500.0,
+            # What binds the kernel is vector-instruction issue (operand split, tanh, Philox, env step; the
+            # SQ counters below), not the matrix cores and not HBM.  `achieved` is the algorithmic work, the
+            # contraction's fp32 FLOPs per agent-step, over the measured time; `peak` the chip's fp32 rate
+            # (vector and matrix fp32 peaks are the same number, 157.3 TFLOP/s).  The contraction itself is
+            # executed on the bf16 matrix cores (exact 3-term operand split): see executed_bf16_mfma.
+            "bound": "alu", "achieved": tflops, "peak": MFMA_FP32_PEAK_TFLOPS if wl.weight_dtype == 0 else 2500.0,
             "unit": "TFLOP/s",
             "frac": tflops / (MFMA_FP32_PEAK_TFLOPS if wl.weight_dtype == 0 else 2500.0),
+            "frac_note": "fp32-equivalent contraction FLOPs / fp32 peak: a notional fraction of a kernel bound by "
+                         "vector issue; mfma_busy_frac and valu_active_frac are the measured unit utilisations",
+            "mfma_busy_frac": None, "valu_active_frac": None,
             "traffic": None,
             "algorithmic_bytes": bytes_per_env_step(N, D) * TE * T,
             "kernel_ms_avg": kavg, "kernel_ms_min": float(np.min(kern_ms)), "kernel_ms_median": float(np.median(kern_ms)),
@@ -362,12 +411,21 @@ def main():
                                                             "jax_a100_10k_envs_random_actions": 4.0e7},
                           "note": "paper Table 3, env-only random actions, other hardware; context only"},
     }
-    traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(traffic_file):
-        tr = json.load(open(traffic_file))
-        # scaled FETCH_SIZE + WRITE_SIZE bytes per launch, from the rocprofv3 --pmc runs in profiles/
-        out["roofline"]["traffic"] = tr.get(wl.name, {}).get("fused", {}).get("total_bytes")
-        out["env_only"]["roofline"]["traffic"] = tr.get(wl.name, {}).get("env_only", {}).get("total_bytes")
+    # Counter figures of the rocprofv3 --pmc runs of this same command (profiles/counters.json): HBM bytes per
+    # launch (FETCH_SIZE + WRITE_SIZE, scaled by the calibration copy above) and the SQ utilisation counters.
+    # They describe the kernels as built from the sources whose hash they carry; null once the sources changed.
+    counters_file = os.path.join(ROOT, "profiles", "counters.json")
+    if os.path.exists(counters_file):
+        tr = json.load(open(counters_file))
+        if tr.get("source_sha256") == kernel_source_hash():
+            c_f = tr.get("workloads", {}).get(wl.name, {}).get("fused", {})
+            c_e = tr.get("workloads", {}).get(wl.name, {}).get("env_only", {})
+            out["roofline"]["traffic"] = c_f.get("total_bytes")
+            out["roofline"]["mfma_busy_frac"] = c_f.get("mfma_busy_frac")
+            out["roofline"]["valu_active_frac"] = c_f.get("valu_active_frac")
+            out["env_only"]["roofline"]["traffic"] = c_e.get("total_bytes")
+        else:
+            out["roofline"]["counters_note"] = "profiles/counters.json was measured on other kernel sources"
     if not args.no_cpu_baseline:
         w1 = tuple(a[:1] for a in weights)
         out["cpu_baseline"] = cpu_baseline(wl, w1, T, seed, args.cpu_seconds)

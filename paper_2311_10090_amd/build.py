@@ -52,26 +52,5 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
-PROBES = ["coexec_probe", "store_pattern_probe"]
-
-
-def build_probe() -> list:
-    """Compile the stand-alone probes (csrc/coexec_probe.hip: matrix/vector overlap;
-    csrc/store_pattern_probe.hip: HBM write rate by store pattern)."""
-    outs = []
-    for name in PROBES:
-        out = os.path.join(HERE, name)
-        r = subprocess.run([_hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wno-unused-result", "-Xclang",
-                            "-target-feature", "-Xclang", "-packed-fp32-ops", os.path.join(CSRC, name + ".hip"),
-                            "-o", out], capture_output=True, text=True)
-        if r.returncode != 0:
-            raise RuntimeError("hipcc failed for %s.hip:\n%s" % (name, r.stderr))
-        outs.append(out)
-    return outs
-
-
 if __name__ == "__main__":
-    if "--probe" in sys.argv:
-        print(build_probe())
-    else:
-        print(build(force=True, verbose=True))
+    print(build(force=True, verbose=True))

@@ -63,18 +63,6 @@ struct SmemF32 {
   static_assert(OFF_OBS % 16 == 0 && OFF_NEWPOS % 16 == 0 && OFF_CRITIC % 16 == 0 && EB / 64 <= 4, "alignment");
 };
 
-// Barrier among the wavefronts of one 64-env sync group inside a larger block.  `arrived` counts
-// arrivals since the start of the kernel; `target` = (wavefronts per group) * (barriers so far).
-// Every wavefront of the block runs the same number of steps and none leaves early, and a block
-// is resident as a whole, so each wait ends.
-__device__ __forceinline__ void group_barrier(uint32_t* arrived, uint32_t target, int lane) {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  if (lane == 0) __hip_atomic_fetch_add(arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-  while (__hip_atomic_load(arrived, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < target)
-    __builtin_amdgcn_s_sleep(1);
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-}
-
 // PER_AGENT: rew_traj is [T][TE][N], the mixed per-agent reward; every lane stores its agent's.
 // AC (actor-critic outputs): a second network of the same shape with one output, `packed_critic`,
 // is evaluated on every observation acted on, and the log-probability of the sampled action is
@@ -347,7 +335,7 @@ __global__ __launch_bounds__((EB * N + RW - 1) / RW * 64, MINW) void rollout_pol
     np[tid] = make_float2(px, py);
     // (C) new positions of every agent of every env of this 64-env group are visible
     if constexpr (EB <= 64) __syncthreads();
-    else if constexpr (N > 1) group_barrier(arrived, uint32_t(N) * uint32_t(t + 1), lane);
+    else if constexpr (N > 1) group_barrier(arrived, uint32_t(N) * uint32_t(t + 1), lane, A.fault);
     else wave_sync();
 
 #pragma unroll
@@ -629,7 +617,7 @@ __global__ __launch_bounds__(256 * N, 1) void rollout_policy_f32_reg_kernel(Roll
     float2* np = newpos + (t & 1) * ROWS_G;
     np[r] = make_float2(px, py);
     // (C) new positions of every agent of every env of this 64-env group are visible
-    group_barrier(arrived, uint32_t(N) * uint32_t(t + 1), lane);
+    group_barrier(arrived, uint32_t(N) * uint32_t(t + 1), lane, A.fault);
 #pragma unroll
     for (int a = 0; a < N; ++a) {
       const float2 p = np[el * N + a];

@@ -176,18 +176,6 @@ __host__ __device__ constexpr int sync_group_envs(int n) {
   return g;
 }
 
-// Barrier among the wavefronts of one sync group.  `arrived` counts arrivals since the start of
-// the kernel; `target` = (wavefronts per group) * (barriers so far).  Every wavefront of a block
-// runs the same number of steps and none leaves early, and a block is resident as a whole, so
-// each wait ends.
-__device__ __forceinline__ void group_barrier(uint32_t* arrived, uint32_t target, int lane) {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  if (lane == 0) __hip_atomic_fetch_add(arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-  while (__hip_atomic_load(arrived, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < target)
-    __builtin_amdgcn_s_sleep(1);
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-}
-
 #define MPE_MFMA_BF(A, B, C) __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, B, C, 0, 0, 0)
 
 // MLP forward of one 16-row tile from its layer-1 B operands b1[slice].  wsm holds W1A then W2A,
@@ -562,7 +550,7 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
     float2* np = newpos + (t & 1) * ROWS;
     np[tid] = make_float2(px, py);
     // (C) new positions of this step and coverage distances of the previous one are visible
-    group_barrier(arrived, uint32_t(GW) * uint32_t(t + 1), lane);
+    group_barrier(arrived, uint32_t(GW) * uint32_t(t + 1), lane, A.fault);
 
     // reward of the previous step: sum of its N per-landmark distances
     if (t > 0) store_reward((t - 1) & 1);
@@ -624,7 +612,7 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
       ep = 0;
     }
   }
-  group_barrier(arrived, uint32_t(GW) * uint32_t(A.T + 1), lane);  // coverage distances of the last step
+  group_barrier(arrived, uint32_t(GW) * uint32_t(A.T + 1), lane, A.fault);  // coverage distances of the last step
   store_reward((A.T - 1) & 1);
   if (A.last_obs) {
     float o[KIN];

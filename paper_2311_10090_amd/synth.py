@@ -63,6 +63,38 @@ def physics_f32(table=None) -> dict:
     return {k: float(np.float32(v)) for k, v in (PHYSICS if table is None else table).items()}
 
 
+def spread_config(num_envs, num_agents, num_runs=1, hidden=0, weight_dtype=0, max_episode_steps=MAX_EPISODE_STEPS,
+                  reward_mode=0, local_ratio=0.5, as_f32=False, **phys) -> dict:
+    """Field values of a simple-spread configuration (plain data: keyword arguments for either side's
+    config type).  as_f32: the constants rounded to float32 and widened again, i.e. the exact values
+    the fp32 path computes with, for a side that takes doubles."""
+    p = dict(PHYSICS)
+    p.update(phys)
+    if as_f32:
+        p = {k: float(np.float32(v)) for k, v in p.items()}
+        local_ratio = float(np.float32(local_ratio))
+    return dict(num_envs=num_envs, num_agents=num_agents, num_landmarks=num_agents, num_runs=num_runs,
+                max_episode_steps=max_episode_steps, hidden=hidden, weight_dtype=weight_dtype,
+                reward_mode=reward_mode, local_ratio=local_ratio, **p)
+
+
+def tag_obs_dim(num_agents, num_landmarks, num_adversaries) -> int:
+    return 4 + 2 * num_landmarks + 2 * (num_agents - 1) + 2 * (num_agents - num_adversaries)
+
+
+def tag_config(num_envs, num_agents=4, num_landmarks=2, num_adversaries=3, num_runs=1, hidden=0, weight_dtype=0,
+               max_episode_steps=MAX_EPISODE_STEPS, as_f32=False, **phys) -> dict:
+    """Field values of a predator-prey configuration: the first num_adversaries agents are adversaries,
+    the landmarks are obstacles.  `scenario` is the predator-prey scenario's number on both sides."""
+    p = dict(TAG_PHYSICS)
+    p.update(phys)
+    if as_f32:
+        p = {k: float(np.float32(v)) for k, v in p.items()}
+    return dict(num_envs=num_envs, num_agents=num_agents, num_landmarks=num_landmarks, num_runs=num_runs,
+                max_episode_steps=max_episode_steps, hidden=hidden, weight_dtype=weight_dtype, scenario=1,
+                num_adversaries=num_adversaries, **p)
+
+
 def policy_weights(seed: int, num_runs: int, obs_dim: int, hidden: int):
     """Per-run MLP weights, N(0, 1/fan_in), zero biases, float32.
 

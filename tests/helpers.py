@@ -17,41 +17,30 @@ ACTION_AGREEMENT = 0.9999
 def oracle_config(E, N, R=1, H=0, wd=0, env_offset=0, run_offset=0, max_ep=synth.MAX_EPISODE_STEPS,
                   reward_mode=0, local_ratio=0.5, **phys):
     from oracle import OracleConfig
-    p = synth.physics_f32()
-    p.update({k: float(np.float32(v)) for k, v in phys.items()})
-    return OracleConfig(num_envs=E, num_agents=N, num_landmarks=N, num_runs=R, max_episode_steps=max_ep,
-                        hidden=H, weight_dtype=wd, env_offset=env_offset, run_offset=run_offset,
-                        reward_mode=reward_mode, local_ratio=float(np.float32(local_ratio)), **p)
+    return OracleConfig(env_offset=env_offset, run_offset=run_offset,
+                        **synth.spread_config(E, N, R, H, wd, max_ep, reward_mode, local_ratio, as_f32=True, **phys))
 
 
 def gpu_config(E, N, R=1, H=0, wd=0, max_ep=synth.MAX_EPISODE_STEPS, reward_mode=0, local_ratio=0.5, **phys):
     from paper_2311_10090_amd.binding import MpeConfig
-    p = dict(synth.PHYSICS)
-    p.update(phys)
-    return MpeConfig(num_envs=E, num_agents=N, num_landmarks=N, num_runs=R, max_episode_steps=max_ep,
-                     hidden=H, weight_dtype=wd, reward_mode=reward_mode, local_ratio=local_ratio, **p)
+    return MpeConfig(**synth.spread_config(E, N, R, H, wd, max_ep, reward_mode, local_ratio, **phys))
 
 
-def tag_obs_dim(N, L, A):
-    return 4 + 2 * L + 2 * (N - 1) + 2 * (N - A)
+tag_obs_dim = synth.tag_obs_dim
 
 
 def tag_oracle_config(E, N=4, L=2, A=3, R=1, H=0, env_offset=0, run_offset=0, max_ep=synth.MAX_EPISODE_STEPS, wd=0,
                       **phys):
     """Predator-prey scenario: N agents of which the first A are adversaries, L obstacle landmarks."""
     from oracle import OracleConfig
-    p = synth.physics_f32(synth.TAG_PHYSICS)
-    p.update({k: float(np.float32(v)) for k, v in phys.items()})
-    return OracleConfig(num_envs=E, num_agents=N, num_landmarks=L, num_runs=R, max_episode_steps=max_ep, hidden=H,
-                        weight_dtype=wd, env_offset=env_offset, run_offset=run_offset, scenario=1, num_adversaries=A, **p)
+    return OracleConfig(env_offset=env_offset, run_offset=run_offset,
+                        **synth.tag_config(E, N, L, A, R, H, wd, max_ep, as_f32=True, **phys))
 
 
 def tag_gpu_config(E, N=4, L=2, A=3, R=1, H=0, max_ep=synth.MAX_EPISODE_STEPS, wd=0, **phys):
     from paper_2311_10090_amd.binding import MpeConfig, SCENARIO_TAG
-    p = dict(synth.TAG_PHYSICS)
-    p.update(phys)
-    return MpeConfig(num_envs=E, num_agents=N, num_landmarks=L, num_runs=R, max_episode_steps=max_ep, hidden=H,
-                     weight_dtype=wd, scenario=SCENARIO_TAG, num_adversaries=A, **p)
+    assert SCENARIO_TAG == 1
+    return MpeConfig(**synth.tag_config(E, N, L, A, R, H, wd, max_ep, **phys))
 
 
 def state_to_gpu(pos_a, vel_a, pos_l, ep, device="cuda:0"):
@@ -104,19 +93,51 @@ def to_dev(arrs, device="cuda:0"):
 
 
 # ---------------------------------------------------------------------------------------------
-# Conditioning of a free-running episode.  Contacts are stiff (force gradient 100 per unit of
-# overlap, dt = 0.1): while two agents overlap, a position difference grows ~2.3x per step, so an
-# episode with a long contact amplifies ANY rounding difference (fp32 state has ~6e-8 relative
-# spacing) beyond 1e-4 within 25 steps, whichever fp32 code computes it.  The oracle itself tells
-# which episodes those are: re-run the episode from its start state with agent positions moved by
-# one step of the 2^-23 reset grid and see how far the oracle drifts from itself.
+# The 25-step bar, |error| <= 1e-4 absolute, and where it cannot hold as stated.
+#
+# Contacts are stiff (force gradient 100 per unit of overlap, dt = 0.1): while two agents overlap, a
+# position difference grows ~2.3x per step, so an episode with a long contact amplifies ANY rounding
+# difference (fp32 state has ~6e-8 relative spacing) beyond 1e-4 within 25 steps, whichever fp32
+# code computes it.  The oracle itself tells which episodes those are and how badly: re-run the
+# episode from its start state with the agent positions moved by one step of the 2^-23 reset grid
+# (N_PERT independent nudges) and see how far the oracle drifts from itself.
+#
+# What the tests assert of every compared episode (an episode = the steps between two resets of one env):
+#   (1) an episode WITHOUT a contact (no pair ever closer than its contact distance + 10 margins, where
+#       the contact force is below 5e-6 and its gradient below 5e-3): error <= 1e-5,
+#       a tenth of the stated bar (measured worst over 200,000 such episodes: 1.8e-6);
+#   (2) every other episode: error <= max(1e-4, SENS_FACTOR * drift): the stated bar wherever the
+#       oracle's own conditioning permits it, and never more than SENS_FACTOR times what the oracle
+#       moves under a one-grid-step nudge of its start (measured worst error / drift over the 1,300
+#       episodes beyond 1e-4 of all shapes: 1.9; SENS_FACTOR = 4 leaves a factor two);
+#   (3) the number of episodes beyond plain 1e-4 is at most what the measured share for that number of
+#       colliding bodies predicts, plus four standard deviations of the count (exceed_share below).
+# Measured shares and ratios per shape are recorded by the tests themselves (record()).
 # ---------------------------------------------------------------------------------------------
-SENS_FACTOR = 30.0     # an fp32 path injects ~1 ulp per step for 25 steps; the nudge is ~2 ulp once
-WITHIN_BAR = 0.97      # share of episodes that must meet the plain 1e-4 bar (3 agents: 3 pairs)
-WITHIN_BAR_CROWDED = 0.85  # 10 agents: 45 pairs, contacts in nearly every episode
+N_PERT = 8                 # independent nudges per episode start
+SENS_FACTOR = 4.0
+CONTACT_FREE_GAP = 10.0    # in units of the contact margin
+CONTACT_FREE_ATOL = 1e-5
+
+# Share of 25-step episodes whose fp32 trajectory ends more than 1e-4 from the fp64 oracle's, measured on
+# 2,000 to 65,000 episodes per agent count with uniform and policy actions (upper end over the seeds
+# measured).  Simple spread, by number of agents (all pairs collide):
+EXCEED_SHARE_SPREAD = {1: 0.0, 2: 1e-4, 3: 2e-4, 4: 8e-4, 5: 3e-3, 6: 7e-3, 7: 2e-2, 8: 3e-2, 9: 6.5e-2, 10: 9.5e-2}
+# Predator-prey, by (agents, obstacle landmarks): smaller bodies, fewer contacts.
+EXCEED_SHARE_TAG = {(2, 1): 1e-4, (3, 0): 2e-4, (4, 2): 8e-4, (6, 2): 2e-3}
 
 
-def oracle_sensitivity(make_oracle, seed, T, max_ep=synth.MAX_EPISODE_STEPS, n_pert=3):
+def record(line):
+    """Print a measured figure and, on the GPU machine, append it to gpurun_out/parity_margins.txt."""
+    import os
+    print(line, flush=True)
+    out = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(out):
+        with open(os.path.join(out, "parity_margins.txt"), "a") as f:
+            f.write(line + "\n")
+
+
+def oracle_sensitivity(make_oracle, seed, T, max_ep=synth.MAX_EPISODE_STEPS, n_pert=N_PERT):
     """Per (t, env) drift of the oracle's obs trajectory under nudged episode starts: [T][TE]."""
     base = make_oracle()
     base.reset(seed)
@@ -128,33 +149,110 @@ def oracle_sensitivity(make_oracle, seed, T, max_ep=synth.MAX_EPISODE_STEPS, n_p
         n = min(max_ep, T - t0)
         pa, va, pl, ep, s = base.get_state()
         assert s == t0 and np.all(ep == 0)
-        ref = base.rollout(n)[0]
+        out = base.rollout(n)
+        ref, ref_last = out[0], out[4]
         for _ in range(n_pert):
             nudge = g.integers(-1, 2, size=pa.shape).astype(np.float64) * 2.0 ** -23
             pert.set_state(pa + nudge, va, pl, ep, seed, t0)
-            alt = pert.rollout(n)[0]
-            d = np.abs(alt - ref).reshape(n, TE, -1).max(axis=2)
+            pert.set_hidden(None)   # a recurrent policy's carried state is zero at an episode start
+            out = pert.rollout(n)
+            d = np.abs(out[0] - ref).reshape(n, TE, -1).max(axis=2)
             sens[t0:t0 + n] = np.maximum(sens[t0:t0 + n], d)
+            if t0 + n == T and n < max_ep:   # the observation after the last step belongs to the unfinished episode
+                sens[T - 1] = np.maximum(sens[T - 1], np.abs(out[4] - ref_last).reshape(TE, -1).max(axis=1))
     return sens
 
 
-def assert_episodes_close(err, sens, max_ep=synth.MAX_EPISODE_STEPS, what="", within=WITHIN_BAR):
-    """err, sens: [T][TE] max-abs error / oracle drift under a one-grid-step nudge.
-    Every episode must be within max(1e-4, SENS_FACTOR * drift): the 1e-4 bar wherever the
-    oracle's own conditioning permits it, and never worse than the oracle drifts from itself.
+def min_gap_spread(robs, N, agent_radius=synth.PHYSICS["agent_radius"], margin=synth.PHYSICS["contact_margin"]):
+    """[T][TE]: smallest (pair distance - contact distance) among the agent pairs of an env at the start
+    of each step, in units of the contact margin, from the oracle's observations (the other agents'
+    relative positions are columns 4 + 2N .. of a row)."""
+    T, TE = robs.shape[:2]
+    if N < 2:
+        return np.full((T, TE), np.inf)
+    rel = robs[:, :, :, 4 + 2 * N:4 + 2 * N + 2 * (N - 1)].reshape(T, TE, N, N - 1, 2)
+    return (np.linalg.norm(rel, axis=-1).min(axis=(2, 3)) - 2.0 * agent_radius) / margin
+
+
+def min_gap_tag(robs, shape, phys=synth.TAG_PHYSICS):
+    """As min_gap_spread for the predator-prey scenario, shape = (agents, landmarks, adversaries): agent
+    pairs and (agent, obstacle) pairs, each against the sum of its two radii."""
+    N, L, A = shape
+    r = np.array([phys["adv_radius"]] * A + [phys["agent_radius"]] * (N - A))
+    T, TE = robs.shape[:2]
+    gap = np.full((T, TE), np.inf)
+    if L:
+        rel = robs[:, :, :, 4:4 + 2 * L].reshape(T, TE, N, L, 2)
+        d = np.linalg.norm(rel, axis=-1) - (r[None, None, :, None] + phys["landmark_radius"])
+        gap = np.minimum(gap, d.min(axis=(2, 3)))
+    if N > 1:
+        rel = robs[:, :, :, 4 + 2 * L:4 + 2 * L + 2 * (N - 1)].reshape(T, TE, N, N - 1, 2)
+        d = np.linalg.norm(rel, axis=-1)
+        for i in range(N):
+            d[:, :, i, :] -= r[i] + r[[j for j in range(N) if j != i]]
+        gap = np.minimum(gap, d.min(axis=(2, 3)))
+    return gap / phys["contact_margin"]
+
+
+def allowed_beyond_bar(share, n_episodes):
+    """Largest number of episodes beyond 1e-4 that the measured share explains: mean + 4 standard
+    deviations of a Poisson count, + 1."""
+    mean = share * n_episodes
+    return int(np.ceil(mean + 4.0 * np.sqrt(mean) + 1.0))
+
+
+def assert_episodes_close(err, sens, gap, exceed_share, max_ep=synth.MAX_EPISODE_STEPS, what=""):
+    """err, sens, gap: [T][TE] max-abs error, oracle drift under a one-grid-step nudge, smallest contact
+    gap in margins (see above).  Asserts (1)-(3) of the comment above and records the measured figures.
     Returns (worst error, episodes beyond 1e-4, episodes)."""
     T, TE = err.shape
-    n_over = n_all = 0
-    worst = 0.0
+    es, ss, gs = [], [], []
     for t0 in range(0, T, max_ep):
-        e = err[t0:t0 + max_ep].max(axis=0)
-        s = sens[t0:t0 + max_ep].max(axis=0)
-        bound = np.maximum(EPISODE_ATOL, SENS_FACTOR * s)
-        bad = e > bound
-        assert not bad.any(), "%s: env %d error %.3e, oracle drift %.3e" % (
-            what, int(np.argmax(bad)), e[bad].max(), s[np.argmax(bad)])
-        n_all += TE
-        n_over += int((e > EPISODE_ATOL).sum())
-        worst = max(worst, float(e.max()))
-    assert n_all - n_over >= within * n_all - 1, "%s: %d of %d episodes beyond 1e-4" % (what, n_over, n_all)
-    return worst, n_over, n_all
+        es.append(err[t0:t0 + max_ep].max(axis=0))
+        ss.append(sens[t0:t0 + max_ep].max(axis=0))
+        gs.append(gap[t0:t0 + max_ep].min(axis=0))
+    e, s, g = np.concatenate(es), np.concatenate(ss), np.concatenate(gs)
+    free = g >= CONTACT_FREE_GAP
+    worst_free = float(e[free].max()) if free.any() else 0.0
+    assert worst_free <= CONTACT_FREE_ATOL, "%s: contact-free episode with error %.3e" % (what, worst_free)
+    bad = e > np.maximum(EPISODE_ATOL, SENS_FACTOR * s)
+    assert not bad.any(), "%s: episode %d error %.3e, oracle drift %.3e" % (
+        what, int(np.argmax(bad)), e[bad].max(), s[np.argmax(bad)])
+    over = e > EPISODE_ATOL
+    n_over, n_all = int(over.sum()), int(e.size)
+    ratio = float((e[over] / np.maximum(s[over], 1e-300)).max()) if n_over else 0.0
+    allowed = allowed_beyond_bar(exceed_share, n_all)
+    record("%s: %d episodes, %d contact-free (worst %.2e); beyond 1e-4: %d (share %.5f, allowed %d); "
+           "worst error %.2e, worst error/drift beyond 1e-4: %.2f"
+           % (what, n_all, int(free.sum()), worst_free, n_over, n_over / n_all, allowed, float(e.max()), ratio))
+    assert n_over <= allowed, "%s: %d of %d episodes beyond 1e-4, share %.2e allows %d" % (
+        what, n_over, n_all, exceed_share, allowed)
+    return float(e.max()), n_over, n_all
+
+
+def episode_errors(obs, act, rew, robs, ract, rrew, max_ep=synth.MAX_EPISODE_STEPS, with_reward=True,
+                   last=None, rlast=None):
+    """Free-running comparison of device and oracle trajectories (numpy, [T][TE]...): an episode is
+    compared while all its actions so far agree.  Returns err [T][TE] (observation and, for one reward
+    per env, reward error; zero where not comparable), the share of episodes whose actions all agree,
+    and (equal, total) sampled actions in the teacher-forced view (identical history so far).
+    last / rlast: the observation after the last step, counted into the last row of an unfinished episode."""
+    T, TE = obs.shape[:2]
+    err = np.zeros((T, TE))
+    seg_same = seg_total = agree = total = 0
+    for t0 in range(0, T, max_ep):
+        t1 = min(t0 + max_ep, T)
+        same = (act[t0:t1] == ract[t0:t1]).all(axis=2)
+        alive = np.logical_and.accumulate(same, axis=0)
+        prior = np.vstack([np.ones((1, TE), bool), alive[:-1]])
+        agree += int((act[t0:t1] == ract[t0:t1])[prior].sum())
+        total += int(prior.sum()) * act.shape[2]
+        seg_total += TE
+        seg_same += int(alive[-1].sum())
+        e = np.abs(obs[t0:t1].astype(np.float64) - robs[t0:t1]).reshape(t1 - t0, TE, -1).max(axis=2) * prior
+        if with_reward and rew is not None and rew.ndim == 2:
+            e = np.maximum(e, np.abs(rew[t0:t1] - rrew[t0:t1]) * alive)
+        if last is not None and t1 == T and t1 - t0 < max_ep:
+            e[-1] = np.maximum(e[-1], np.abs(last.astype(np.float64) - rlast).reshape(TE, -1).max(axis=1) * alive[-1])
+        err[t0:t1] = e
+    return err, seg_same / max(seg_total, 1), (agree, total)

@@ -30,45 +30,61 @@ def _gpu_rollout(wl, seed, with_policy=True, wseed=0):
     return env, out, weights
 
 
-def _oracle_range(wl, seed, run, off, n, weights, with_policy=True):
+def _make_oracle_range(wl, run, off, n, weights, with_policy=True):
+    """Factory of oracles that simulate envs [off, off + n) of run `run` of the big job."""
     from oracle import Oracle
     H = wl.hidden if with_policy else 0
-    orc = Oracle(Hp.oracle_config(n, wl.num_agents, 1, H, wl.weight_dtype if with_policy else 0,
-                                  env_offset=off, run_offset=run), threads=8)
-    if with_policy:
-        orc.set_policy(*[w[run:run + 1] for w in weights])
-    orc.reset(seed)
-    return orc.rollout(wl.T)
+
+    def make():
+        orc = Oracle(Hp.oracle_config(n, wl.num_agents, 1, H, wl.weight_dtype if with_policy else 0,
+                                      env_offset=off, run_offset=run), threads=8)
+        if with_policy:
+            orc.set_policy(*[w[run:run + 1] for w in weights])
+        return orc
+    return make
 
 
-def _compare_range(wl, out, ref, g0, n, what, fp32_actions=True):
-    """Compare envs [g0, g0+n) of the device trajectories with the oracle's; free-running, so an
-    episode is compared while its actions so far agree.  Returns action agreement."""
-    T = wl.T
-    obs, act, rew, done = [x[:, g0:g0 + n].cpu().numpy() for x in out[:4]]
-    robs, ract, rrew, rdone, rlast = ref
-    assert np.array_equal(done, rdone), what
-    agree = total = 0
-    worst = 0.0
-    for t0 in range(0, T, synth.MAX_EPISODE_STEPS):
-        t1 = min(t0 + synth.MAX_EPISODE_STEPS, T)
-        assert np.array_equal(obs[t0].astype(np.float64), robs[t0]), "%s: episode start at t=%d not bit-exact" % (what, t0)
-        same = (act[t0:t1] == ract[t0:t1]).all(axis=2)
-        alive = np.logical_and.accumulate(same, axis=0)
-        prior = np.vstack([np.ones((1, n), bool), alive[:-1]])
-        # teacher-forced view: at (t, env) with identical history the sampled action must agree
-        agree += int((act[t0:t1] == ract[t0:t1])[prior].sum())
-        total += int(prior.sum()) * act.shape[2]
-        e = np.abs(obs[t0:t1].astype(np.float64) - robs[t0:t1]).reshape(t1 - t0, n, -1).max(axis=2)
-        # chaos-aware bound would need oracle re-runs; here only the first 5 steps of an episode
-        # (no time for a contact to amplify rounding) are held to the 1e-4 bar ...
-        k = min(5, t1 - t0)
-        assert (e[:k] * prior[:k]).max() <= Hp.EPISODE_ATOL, what
-        assert (np.abs(rew[t0:t0 + k] - rrew[t0:t0 + k]) * alive[:k]).max() <= Hp.EPISODE_ATOL, what
-        # ... and the rest to a loose sanity bound that a wrong index or sign would still break
-        worst = max(worst, float((e * prior).max()))
-    assert worst < 0.05, "%s: error %.3e" % (what, worst)
-    return agree / max(total, 1), total
+class _Sampled:
+    """Free-running comparison of sampled env ranges of one big job, pooled: every compared episode is held
+    to the 25-step bar over all of its steps (helpers.assert_episodes_close), the sampled actions to their
+    agreement bar."""
+
+    def __init__(self, wl, out, seed):
+        self.wl, self.out, self.seed = wl, out, seed
+        self.err, self.sens, self.gap = [], [], []
+        self.agree = self.total = 0
+
+    def add(self, g0, n, make_oracle, what):
+        wl, T = self.wl, self.wl.T
+        obs, act, rew, done = [x[:, g0:g0 + n].cpu().numpy() for x in self.out[:4]]
+        orc = make_oracle()
+        orc.reset(self.seed)
+        robs, ract, rrew, rdone, rlast = orc.rollout(T)
+        assert np.array_equal(done, rdone), what
+        for t0 in range(0, T, synth.MAX_EPISODE_STEPS):
+            assert np.array_equal(obs[t0].astype(np.float64), robs[t0]), "%s: episode start at t=%d not bit-exact" % (what, t0)
+        last = self.out[4][g0:g0 + n].cpu().numpy()
+        if T % synth.MAX_EPISODE_STEPS == 0:
+            assert np.array_equal(last.astype(np.float64), rlast), "%s: last_obs after a reset not bit-exact" % what
+        err, _, (agree, total) = Hp.episode_errors(obs, act, rew, robs, ract, rrew, last=last, rlast=rlast)
+        self.err.append(err)
+        self.sens.append(Hp.oracle_sensitivity(make_oracle, self.seed, T))
+        self.gap.append(Hp.min_gap_spread(robs, wl.num_agents))
+        self.agree += agree
+        self.total += total
+
+    def check(self, what):
+        err, sens, gap = [np.concatenate(x, axis=1) for x in (self.err, self.sens, self.gap)]
+        Hp.assert_episodes_close(err, sens, gap, Hp.EXCEED_SHARE_SPREAD[self.wl.num_agents],
+                                 what="%s (%d sampled envs)" % (what, err.shape[1]))
+        return self.agree / max(self.total, 1), self.total
+
+
+# Env ranges of a 65,536-env job: the first and the last envs, ranges that straddle 64-env sync groups, 256-env
+# blocks (multiples of 256) and the env ranges of two XCDs (multiples of 8,192: blocks are dealt to the eight
+# XCDs so that each owns one contiguous eighth of the envs), a single env, odd offsets.  1,093 envs in all.
+HEADLINE_RANGES = ((0, 64), (20, 3), (224, 64), (8192 - 32, 64), (12345, 1), (16384 - 100, 200), (24576 - 1, 2),
+                   (32736, 64), (40960 - 128, 256), (49152 - 7, 71), (57344 - 64, 128), (61000, 112), (65536 - 64, 64))
 
 
 @pytest.mark.parametrize("key", ["cfg2", "cfg2_env"])
@@ -85,17 +101,16 @@ def test_headline_shape_sampled_against_oracle(key):
     assert bool((act <= 4).all()) and bool(torch.isfinite(obs).all()) and bool((rew <= 0).all())
     hist = torch.bincount(act.flatten().long(), minlength=5).double()
     assert hist.min() > 0.02 * hist.sum()
-    tot = agree = 0
-    for off, n in ((0, 64), (20, 3), (32736, 64), (wl.num_envs - 64, 64), (12345, 1)):
-        ref = _oracle_range(wl, 1, 0, off, n, weights, with_policy)
-        frac, cnt = _compare_range(wl, out, ref, off, n, "%s envs %d..%d" % (key, off, off + n))
-        agree += frac * cnt
-        tot += cnt
-    say("  sampled action agreement %.6f over %d samples" % (agree / tot, tot))
+    samp = _Sampled(wl, out, 1)
+    assert sum(n for _, n in HEADLINE_RANGES) >= 1024
+    for off, n in HEADLINE_RANGES:
+        samp.add(off, n, _make_oracle_range(wl, 0, off, n, weights, with_policy), "%s envs %d..%d" % (key, off, off + n))
+    frac, tot = samp.check("full size %s" % wl.name)
+    say("  sampled action agreement %.6f over %d samples" % (frac, tot))
     if with_policy:
-        assert agree / tot >= Hp.ACTION_AGREEMENT - 2.0 / tot
+        assert frac >= Hp.ACTION_AGREEMENT - 2.0 / tot
     else:
-        assert agree == tot  # uniform actions are integer work
+        assert frac == 1.0  # uniform actions are integer work
     env.close()
 
 
@@ -108,14 +123,16 @@ def test_per_run_weights_full_size():
     wl = synth.WORKLOADS["cfg4"]
     say("full size %s: %d runs x %d envs" % (wl.name, wl.num_runs, wl.num_envs))
     env, out, weights = _gpu_rollout(wl, seed=1, wseed=11)
-    tot = agree = 0
-    for run in (0, 1, 2, 3, 517, 1023):
-        ref = _oracle_range(wl, 1, run, 0, 64, weights)
-        frac, cnt = _compare_range(wl, out, ref, run * 64, 64, "run %d" % run)
-        agree += frac * cnt
-        tot += cnt
-    say("  sampled action agreement %.6f over %d samples" % (agree / tot, tot))
-    assert agree / tot >= Hp.ACTION_AGREEMENT - 2.0 / tot
+    # 40 of the 1,024 runs: the four runs of the first and of the last 256-env block, runs on either side of an
+    # XCD's range of blocks (128 runs each), and a stride through the rest
+    runs = sorted(set([0, 1, 2, 3, 127, 128, 129, 511, 512, 517, 895, 896, 1020, 1021, 1022, 1023] + list(range(37, 1024, 41))))
+    assert len(runs) >= 32
+    samp = _Sampled(wl, out, 1)
+    for run in runs:
+        samp.add(run * 64, 64, _make_oracle_range(wl, run, 0, 64, weights), "run %d" % run)
+    frac, tot = samp.check("full size %s" % wl.name)
+    say("  sampled action agreement %.6f over %d samples" % (frac, tot))
+    assert frac >= Hp.ACTION_AGREEMENT - 2.0 / tot
     one = MpeEnv(Hp.gpu_config(64, wl.num_agents, 1, wl.hidden, 0))
     one.set_policy(*Hp.to_dev([w[0:1] for w in weights]))
     one.reset(1)
@@ -136,14 +153,12 @@ def test_per_run_weights_other_shapes_full_size(N, R, E):
     env, out, weights = _gpu_rollout(wl, seed=2, wseed=12)
     assert int(out[3].sum().item()) == wl.total_envs * (wl.T // synth.MAX_EPISODE_STEPS)
     assert bool(torch.isfinite(out[0]).all()) and bool((out[1] <= 4).all())
-    tot = agree = 0
-    for run in (0, 5, R - 2, R - 1):
-        ref = _oracle_range(wl, 2, run, E - 64, 64, weights)
-        frac, cnt = _compare_range(wl, out, ref, run * E + E - 64, 64, "run %d" % run)
-        agree += frac * cnt
-        tot += cnt
-    say("  sampled action agreement %.6f over %d samples" % (agree / tot, tot))
-    assert agree / tot >= Hp.ACTION_AGREEMENT - 2.0 / tot
+    samp = _Sampled(wl, out, 2)
+    for run in (0, 1, 5, R // 2, R - 3, R - 2, R - 1):
+        samp.add(run * E + E - 64, 64, _make_oracle_range(wl, run, E - 64, 64, weights), "run %d" % run)
+    frac, tot = samp.check("full size %s" % wl.name)
+    say("  sampled action agreement %.6f over %d samples" % (frac, tot))
+    assert frac >= Hp.ACTION_AGREEMENT - 2.0 / tot
     s = env.get_state()
     assert bool(torch.isfinite(s[0]).all()) and int(s[4]) == wl.T
     env.close()
@@ -156,14 +171,13 @@ def test_wide_bf16_full_size():
     obs, act, rew, done, last = out
     assert int(done.sum().item()) == wl.total_envs * (wl.T // synth.MAX_EPISODE_STEPS)
     assert bool((obs[..., 42:] == 0).all()) and bool(torch.isfinite(obs).all())
-    tot = agree = 0
-    for off, n in ((0, 32), (8176, 32), (wl.num_envs - 32, 32)):
-        ref = _oracle_range(wl, 1, 0, off, n, weights)
-        frac, cnt = _compare_range(wl, out, ref, off, n, "cfg3 envs %d..%d" % (off, off + n))
-        agree += frac * cnt
-        tot += cnt
-    say("  bf16 sampled action agreement %.5f over %d samples (no bar)" % (agree / tot, tot))
-    assert agree / tot >= 0.99
+    # 288 envs: first and last, ranges across 32-env sync groups, 64-env blocks and the XCDs' ranges (2,048 envs)
+    samp = _Sampled(wl, out, 1)
+    for off, n in ((0, 32), (48, 32), (2048 - 16, 32), (8176, 32), (10240 - 40, 64), (12288 + 31, 34), (wl.num_envs - 62, 62)):
+        samp.add(off, n, _make_oracle_range(wl, 0, off, n, weights), "cfg3 envs %d..%d" % (off, off + n))
+    frac, tot = samp.check("full size %s" % wl.name)
+    say("  bf16 sampled action agreement %.5f over %d samples (no bar)" % (frac, tot))
+    assert frac >= 0.99
     env.close()
 
 
@@ -176,14 +190,12 @@ def test_large_ragged_size_uses_256_env_blocks():
     obs, act, rew, done, last = out
     assert int(done.sum().item()) == wl.total_envs * (wl.T // synth.MAX_EPISODE_STEPS)
     assert bool(torch.isfinite(obs).all()) and bool((act <= 4).all())
-    tot = agree = 0
-    for off, n in ((65536 - 40, 40), (65536, 64), (65600, 10), (300, 20)):
-        ref = _oracle_range(wl, 2, 0, off, n, weights)
-        frac, cnt = _compare_range(wl, out, ref, off, n, "ragged envs %d..%d" % (off, off + n))
-        agree += frac * cnt
-        tot += cnt
-    say("  sampled action agreement %.6f over %d samples" % (agree / tot, tot))
-    assert agree / tot >= Hp.ACTION_AGREEMENT - 2.0 / tot
+    samp = _Sampled(wl, out, 2)
+    for off, n in ((65536 - 40, 40), (65536, 64), (65600, 10), (300, 20), (8192 - 10, 20)):
+        samp.add(off, n, _make_oracle_range(wl, 0, off, n, weights), "ragged envs %d..%d" % (off, off + n))
+    frac, tot = samp.check("full size %s" % wl.name)
+    say("  sampled action agreement %.6f over %d samples" % (frac, tot))
+    assert frac >= Hp.ACTION_AGREEMENT - 2.0 / tot
     # same job through the actor-critic entry point (also 256-env blocks): identical plain outputs
     env2, _, _ = _gpu_rollout(wl, seed=2, wseed=7)
     env2.set_critic(*Hp.to_dev(synth.critic_weights(7, 1, wl.obs_dim, wl.hidden)))
@@ -205,14 +217,12 @@ def test_large_size_one_and_two_agents_use_256_env_blocks(N):
     env, out, weights = _gpu_rollout(wl, seed=4, wseed=8)
     assert int(out[3].sum().item()) == wl.total_envs * (wl.T // synth.MAX_EPISODE_STEPS)
     assert bool(torch.isfinite(out[0]).all()) and bool((out[1] <= 4).all())
-    tot = agree = 0
+    samp = _Sampled(wl, out, 4)
     for off, n in ((0, 64), (255, 130), (32768 - 30, 64), (65536, 64)):
-        ref = _oracle_range(wl, 4, 0, off, n, weights)
-        frac, cnt = _compare_range(wl, out, ref, off, n, "N=%d envs %d..%d" % (N, off, off + n))
-        agree += frac * cnt
-        tot += cnt
-    say("  sampled action agreement %.6f over %d samples" % (agree / tot, tot))
-    assert agree / tot >= Hp.ACTION_AGREEMENT - 2.0 / tot
+        samp.add(off, n, _make_oracle_range(wl, 0, off, n, weights), "N=%d envs %d..%d" % (N, off, off + n))
+    frac, tot = samp.check("full size %s" % wl.name)
+    say("  sampled action agreement %.6f over %d samples" % (frac, tot))
+    assert frac >= Hp.ACTION_AGREEMENT - 2.0 / tot
     env.close()
 
 
@@ -322,27 +332,33 @@ def test_tag_scenario_full_size(with_policy):
     speed = obs[..., 0:2].norm(dim=-1)
     assert float(speed[:, :, :3].max()) <= 1.0 + 1e-5 and float(speed[:, :, 3].max()) <= 1.3 + 1e-5
     tot = agree = 0
-    for off, n in ((0, 64), (32741, 7), (E - 64, 64)):
-        orc = Oracle(Hp.tag_oracle_config(n, N, L, A, 1, H, env_offset=off), threads=8)
-        if w:
-            orc.set_policy(*w)
+    errs, senss, gaps = [], [], []
+    # 519 envs: first and last, ranges across 64-env blocks and the XCDs' ranges (8,192 envs), an odd offset
+    for off, n in ((0, 64), (8192 - 32, 64), (16384 + 40, 48), (32741, 7), (40960 - 64, 128), (57344 - 72, 144), (E - 64, 64)):
+        def make_oracle(off=off, n=n):
+            o_ = Oracle(Hp.tag_oracle_config(n, N, L, A, 1, H, env_offset=off), threads=8)
+            if w:
+                o_.set_policy(*w)
+            return o_
+        orc = make_oracle()
         orc.reset(1)
         robs, ract, rrew, rdone, rlast = orc.rollout(T)
         o, a, r, d = [x[:, off:off + n].cpu().numpy() for x in (obs, act, rew, done)]
         assert np.array_equal(d, rdone)
+        err, _, (ag, to) = Hp.episode_errors(o, a, None, robs, ract, None, last=last[off:off + n].cpu().numpy(), rlast=rlast)
+        agree += ag
+        tot += to
+        errs.append(err)
+        senss.append(Hp.oracle_sensitivity(make_oracle, 1, T))
+        gaps.append(Hp.min_gap_tag(robs, shape))
         for t0 in range(0, T, 25):
-            t1 = min(t0 + 25, T)
-            same = (a[t0:t1] == ract[t0:t1]).all(axis=2)
-            alive = np.logical_and.accumulate(same, axis=0)
-            prior = np.vstack([np.ones((1, n), bool), alive[:-1]])
-            agree += int((a[t0:t1] == ract[t0:t1])[prior].sum())
-            tot += int(prior.sum()) * N
-            e = np.abs(o[t0:t1].astype(np.float64) - robs[t0:t1]).reshape(t1 - t0, n, -1).max(axis=2)
-            assert (e[:5] * prior[:5]).max() <= Hp.EPISODE_ATOL
-            assert (e * prior).max() < 0.05
+            alive = np.logical_and.accumulate((a[t0:t0 + 25] == ract[t0:t0 + 25]).all(axis=2), axis=0)
             # rewards of the first steps of an episode (same positions to 1e-4: same touching decisions
             # unless a pair sits on the threshold, which these few samples do not)
             assert (np.abs(r[t0:t0 + 5] - rrew[t0:t0 + 5]).max(axis=2) * alive[:5]).max() <= 1e-3
+    err, sens, gap = [np.concatenate(x, axis=1) for x in (errs, senss, gaps)]
+    Hp.assert_episodes_close(err, sens, gap, Hp.EXCEED_SHARE_TAG[shape[:2]],
+                             what="full size tag scenario, policy=%s (%d sampled envs)" % (with_policy, err.shape[1]))
     say("  sampled action agreement %.6f over %d samples" % (agree / tot, tot))
     assert (agree / tot >= Hp.ACTION_AGREEMENT - 2.0 / tot) if with_policy else agree == tot
     env.close()
@@ -407,29 +423,33 @@ def test_recurrent_policy_full_size():
     hid = env.get_hidden()
     assert bool(torch.isfinite(hid).all()) and float(hid.abs().max()) <= 1.0 and bool(hid.any())
     tot = agree = 0
-    for off, n in ((0, 64), (32741, 7), (E - 64, 64)):
-        orc = Oracle(Hp.oracle_config(n, N, 1, 128, 1, env_offset=off), threads=8)
-        orc.set_gru(*w)
+    errs, senss, gaps = [], [], []
+    for off, n in ((0, 64), (8192 - 32, 64), (32741, 7), (49152 - 16, 48), (E - 64, 64)):
+        def make_oracle(off=off, n=n):
+            o_ = Oracle(Hp.oracle_config(n, N, 1, 128, 1, env_offset=off), threads=8)
+            o_.set_gru(*w)
+            return o_
+        orc = make_oracle()
         orc.reset(1)
         robs, ract, rrew, rdone, rlast = orc.rollout(T)
         o, a, r, d = [x[:, off:off + n].cpu().numpy() for x in (obs, act, rew, done)]
         assert np.array_equal(d, rdone)
         for t0 in range(0, T, 25):
-            t1 = min(t0 + 25, T)
             assert np.array_equal(o[t0].astype(np.float64), robs[t0])
-            same = (a[t0:t1] == ract[t0:t1]).all(axis=2)
-            alive = np.logical_and.accumulate(same, axis=0)
-            prior = np.vstack([np.ones((1, n), bool), alive[:-1]])
-            agree += int((a[t0:t1] == ract[t0:t1])[prior].sum())
-            tot += int(prior.sum()) * N
-            e = np.abs(o[t0:t1].astype(np.float64) - robs[t0:t1]).reshape(t1 - t0, n, -1).max(axis=2)
-            assert (e[:5] * prior[:5]).max() <= Hp.EPISODE_ATOL
-            assert (e * prior).max() < 0.05
+        err, _, (ag, to) = Hp.episode_errors(o, a, r, robs, ract, rrew, last=last[off:off + n].cpu().numpy(), rlast=rlast)
+        agree += ag
+        tot += to
+        errs.append(err)
+        senss.append(Hp.oracle_sensitivity(make_oracle, 1, T))
+        gaps.append(Hp.min_gap_spread(robs, N))
         # carried state at the end (T = 128: 3 steps into an episode) where the whole last episode agreed
         h = hid[off:off + n].cpu().numpy().astype(np.float64)
         ok = (a[125:] == ract[125:]).all(axis=(0, 2))
         dh = np.abs(h - orc.get_hidden())[ok]
         assert dh.size and np.median(dh) < 1e-5 and dh.max() < 2e-2
+    err, sens, gap = [np.concatenate(x, axis=1) for x in (errs, senss, gaps)]
+    Hp.assert_episodes_close(err, sens, gap, Hp.EXCEED_SHARE_SPREAD[N],
+                             what="full size recurrent policy (%d sampled envs)" % err.shape[1])
     say("  sampled action agreement %.6f over %d samples" % (agree / tot, tot))
     assert agree / tot >= 0.99
     env.close()
