@@ -64,6 +64,7 @@ extern "C" {
 
 #define MPE_NUM_ACTIONS 5
 #define MPE_MAX_AGENTS  10
+#define MPE_MAX_ROLLOUT_STEPS (1 << 24)  /* largest T of one mpe_rollout / mpe_rollout_ac call */
 
 #define MPE_WEIGHTS_FP32 0
 #define MPE_WEIGHTS_BF16 1  /* weights and layer inputs rounded to bf16 (RNE), fp32 accumulate */
@@ -113,14 +114,17 @@ typedef struct {
   float   good_max_speed;    /* 1.3 : > 0                                                  */
 } mpe_config;
 
-/* Validate `cfg` (host only), then allocate the device state of TE environments:
+/* The paper's make(name) (App. C, API listing: an environment object from the registry), with the
+ * scenario and its constants given as a struct instead of a name.
+ * Validate `cfg` (host only), then allocate the device state of TE environments:
  * pos_a, vel_a [2][N][TE] fp32, pos_l [2][L][TE] fp32, ep_step [TE] int32.
  * MPE_SCENARIO_TAG is built for (N, L, good agents) in (4, 2, 1), (2, 1, 1), (3, 0, 1), (6, 2, 2);
  * MPE_EINVAL for other shapes.
  * `*out` receives the handle.  MPE_EINVAL for a bad config, MPE_EHIP if allocation fails. */
 int mpe_create(const mpe_config* cfg, mpe_env** out);
 
-/* Free the handle and its device buffers (synchronises the device first). NULL is allowed. */
+/* Free the handle and its device buffers (synchronises the device first). NULL is allowed.  (The paper's
+ * environments are garbage-collected Python objects, App. C; a C handle needs the explicit call.) */
 int mpe_destroy(mpe_env* env);
 
 /* Observation length D of this handle (6N; tag: 4 + 2L + 2(N-1) + 2G), or MPE_EINVAL for NULL. */
@@ -169,8 +173,10 @@ int mpe_set_policy(mpe_env* env, const float* W1, const float* b1, const float* 
  * ([T][TE][N] with MPE_REWARD_MIXED and MPE_SCENARIO_TAG), done_traj [T][TE] uint8, last_obs [TE][N][D] fp32
  * (observation after the last step).
  * Any of the five may be NULL (that output is then not written).
- * T >= 1.  Advances the absolute step counter by T.  MPE_ESTATE and the counter's limit as for
- * mpe_step.  With a policy and several runs (one set of weights per run) num_envs must be a multiple
+ * 1 <= T <= MPE_MAX_ROLLOUT_STEPS.  Advances the absolute step counter by T.  MPE_ESTATE and the counter's
+ * limit as for mpe_step.  MPE_EHIP, on this and every later stepping call of the handle, if a kernel of an
+ * earlier call gave up one of its bounded waits (it then ran to its end with invalid results; that takes a
+ * defect in the library, and the handle is to be destroyed).  With a policy and several runs (one set of weights per run) num_envs must be a multiple
  * of 16 (the policies for 4 and more agents: of 64; of 32 with 8 agents), MPE_EINVAL otherwise;
  * multiples of 64 run fastest. */
 int mpe_rollout(mpe_env* env, int32_t T, float* obs_traj, uint8_t* act_traj, float* rew_traj,
@@ -231,7 +237,10 @@ int mpe_rollout_ac(mpe_env* env, int32_t T, float* obs_traj, uint8_t* act_traj, 
                    float* value_traj, float* rew_traj, uint8_t* done_traj, float* last_obs,
                    float* last_value, void* stream);
 
-/* Copy the state out / in (device to device, on `stream`).  Layouts: pos_a, vel_a
+/* The environment state as an explicit value (App. C: step takes the state and returns the new one;
+ * "the state is passed explicitly"): here it lives in the handle and is copied out / in on request, which is
+ * also what a checkpoint or a teacher-forced test needs.
+ * Copy the state out / in (device to device, on `stream`).  Layouts: pos_a, vel_a
  * [2][N][TE], pos_l [2][L][TE] fp32 (coordinate-major, env fastest), ep_step [TE] int32.
  * Output pointers of mpe_get_state may be NULL individually; abs_step is a HOST pointer
  * (may be NULL).  mpe_set_state needs all four arrays (pos_l may be NULL when there are no
@@ -241,7 +250,8 @@ int mpe_get_state(mpe_env* env, float* pos_a, float* vel_a, float* pos_l, int32_
 int mpe_set_state(mpe_env* env, const float* pos_a, const float* vel_a, const float* pos_l,
                   const int32_t* ep_step, uint32_t seed, uint32_t abs_step, void* stream);
 
-/* Text of the calling thread's most recent error ("" if none). Never NULL; static storage. */
+/* Text of the calling thread's most recent error ("" if none). Never NULL; static storage.  (C stand-in for
+ * the exceptions of the paper's Python interface, App. C.) */
 const char* mpe_last_error(void);
 
 #ifdef __cplusplus

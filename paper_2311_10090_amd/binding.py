@@ -99,6 +99,8 @@ def load_library():
     lib.mpe_set_gru_policy.argtypes = [vp] + [vp] * 10 + [vp]
     lib.mpe_get_hidden.argtypes = [vp, vp, vp]
     lib.mpe_set_hidden.argtypes = [vp, vp, vp]
+    lib.mpe_set_critic.argtypes = [vp] + [vp] * 6 + [vp]
+    lib.mpe_rollout_ac.argtypes = [vp, C.c_int32] + [vp] * 9
     for n in EXPORTS:
         if n != "mpe_last_error":
             getattr(lib, n).restype = C.c_int
@@ -243,3 +245,4 @@ class MpeEnv:
             _check(self.lib.mpe_set_state(self.h, _ptr(pos_a, torch.float32), _ptr(vel_a, torch.float32),
                                           _ptr(pos_l, torch.float32), _ptr(ep_step, torch.int32), seed, abs_step,
                                           _stream()))
+

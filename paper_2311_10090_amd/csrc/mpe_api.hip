@@ -1,6 +1,7 @@
 // C ABI of libmpe (see include/mpe.h): handle, host-side validation, dispatch to kernels.
 #include "../../include/mpe.h"
 
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -31,6 +32,10 @@ struct mpe_env {
   PolicyBuffers gru{};        // recurrent policy; takes precedence over `pol` while set
   bool has_gru = false;
   float* hidden = nullptr;    // [TE][N][128] carried state of the recurrent policy (allocated with it)
+  // One word of pinned host memory, mapped into the device: a kernel whose bounded wait gave up raises it
+  // (see group_barrier); the host reads it, without any synchronisation, at the start of the next call.
+  uint32_t* fault_host = nullptr;
+  uint32_t* fault_dev = nullptr;
 };
 
 namespace {
@@ -103,18 +108,8 @@ int validate(const mpe_config* c) {
 size_t agent_floats(const mpe_env* e) { return size_t(2) * e->N * e->TE; }
 size_t landmark_floats(const mpe_env* e) { return size_t(2) * e->L * e->TE; }
 
-}  // namespace
-
-extern "C" {
-
-const char* mpe_last_error(void) { return g_err; }
-
-int mpe_create(const mpe_config* cfg, mpe_env** out) {
-  if (!cfg || !out) return fail(MPE_EINVAL, "mpe_create: NULL argument");
-  *out = nullptr;
-  if (int rc = validate(cfg)) return rc;
-  mpe_env* e = new (std::nothrow) mpe_env();
-  if (!e) return fail(MPE_EHIP, "out of host memory");
+// Fill the host-side fields of a handle from a validated config (no device work).
+void init_from_config(mpe_env* e, const mpe_config* cfg) {
   e->cfg = *cfg;
   e->N = cfg->num_agents;
   e->L = cfg->num_landmarks;
@@ -157,14 +152,63 @@ int mpe_create(const mpe_config* cfg, mpe_env** out) {
     const double touch = double(cfg->adv_radius) + double(cfg->agent_radius);
     t.touch_sq = float(touch * touch);
   }
+}
+
+// A kernel of an earlier call on this handle gave up a bounded wait: its results, and the state it wrote
+// back, are invalid.
+int check_fault(const mpe_env* e, const char* who) {
+  if (e->fault_host && *static_cast<volatile const uint32_t*>(e->fault_host) != 0u)
+    return fail(MPE_EHIP, "%s: a kernel of an earlier call on this handle gave up waiting at a wavefront barrier; "
+                          "the handle's state is invalid (destroy it)", who);
+  return MPE_OK;
+}
+
+RolloutArgs rollout_args(const mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, float* rew_traj,
+                         uint8_t* done_traj, float* last_obs) {
+  RolloutArgs A;
+  A.st = e->st;
+  A.ph = e->ph;
+  A.TE = e->TE;
+  A.E = e->E;
+  A.seed = e->seed;
+  A.abs_step = e->abs_step;
+  A.T = T;
+  A.obs_traj = obs_traj;
+  A.act_traj = act_traj;
+  A.rew_traj = rew_traj;
+  A.done_traj = done_traj;
+  A.last_obs = last_obs;
+  A.fault = e->fault_dev;
+  return A;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* mpe_last_error(void) { return g_err; }
+
+int mpe_create(const mpe_config* cfg, mpe_env** out) {
+  if (!cfg || !out) return fail(MPE_EINVAL, "mpe_create: NULL argument");
+  *out = nullptr;
+  if (int rc = validate(cfg)) return rc;
+  mpe_env* e = new (std::nothrow) mpe_env();
+  if (!e) return fail(MPE_EHIP, "out of host memory");
+  init_from_config(e, cfg);
   const size_t nf = agent_floats(e) * sizeof(float);
   hipError_t err = hipMalloc(&e->st.pos_a, nf);
   if (err == hipSuccess) err = hipMalloc(&e->st.vel_a, nf);
   if (err == hipSuccess) err = hipMalloc(&e->st.pos_l, landmark_floats(e) * sizeof(float) + 16);
   if (err == hipSuccess) err = hipMalloc(&e->st.ep_step, size_t(e->TE) * sizeof(int32_t));
+  if (err == hipSuccess) err = hipHostMalloc(reinterpret_cast<void**>(&e->fault_host), sizeof(uint32_t), hipHostMallocMapped);
+  if (err == hipSuccess) {
+    *e->fault_host = 0u;
+    err = hipHostGetDevicePointer(reinterpret_cast<void**>(&e->fault_dev), e->fault_host, 0);
+  }
   if (err != hipSuccess) {
-    int rc = fail(MPE_EHIP, "mpe_create: hipMalloc failed: %s", hipGetErrorString(err));
+    int rc = fail(MPE_EHIP, "mpe_create: allocation failed: %s", hipGetErrorString(err));
     (void)hipFree(e->st.pos_a); (void)hipFree(e->st.vel_a); (void)hipFree(e->st.pos_l); (void)hipFree(e->st.ep_step);
+    if (e->fault_host) (void)hipHostFree(e->fault_host);
     delete e;
     return rc;
   }
@@ -183,6 +227,7 @@ int mpe_destroy(mpe_env* e) {
   free_policy(e->critic);
   free_policy(e->gru);
   if (e->hidden) (void)hipFree(e->hidden);
+  if (e->fault_host) (void)hipHostFree(e->fault_host);
   delete e;
   return MPE_OK;
 }
@@ -209,6 +254,7 @@ int mpe_step(mpe_env* e, const uint8_t* actions, float* obs, float* reward, uint
   if (!e) return fail(MPE_EINVAL, "mpe_step: NULL handle");
   if (!actions) return fail(MPE_EINVAL, "mpe_step: actions is NULL");
   if (!e->ready) return fail(MPE_ESTATE, "mpe_step: call mpe_reset or mpe_set_state first");
+  if (int rc = check_fault(e, "mpe_step")) return rc;
   if ((obs && !aligned16(obs)) || (reward && !aligned16(reward)))
     return fail(MPE_EINVAL, "mpe_step: obs and reward must be 16-byte aligned");
   if (e->abs_step == 0xFFFFFFFFu) return fail(MPE_EINVAL, "mpe_step: absolute step counter would overflow 32 bits");
@@ -223,6 +269,7 @@ int mpe_step(mpe_env* e, const uint8_t* actions, float* obs, float* reward, uint
     A.r.rew_traj = reward;
     A.r.done_traj = done;
     A.r.last_obs = obs;
+    A.r.fault = e->fault_dev;
     A.tg = e->tg;
     A.actions_in = actions;
     const char* why = nullptr;
@@ -251,6 +298,7 @@ int mpe_set_policy(mpe_env* e, const float* W1, const float* b1, const float* W2
   if (e->H != 64 && e->H != 128) return fail(MPE_EINVAL, "mpe_set_policy: config.hidden must be 64 or 128");
   const char* why = nullptr;
   hipError_t err;
+  e->has_policy = false;   // a failure below must not leave an earlier policy installed on a partly rewritten buffer
   if (e->tag) {
     if (!tag_policy_supported(e->N, e->L, e->G, e->H, e->cfg.weight_dtype))
       return fail(MPE_EINVAL, "mpe_set_policy: MPE_SCENARIO_TAG policies are built for hidden 64 and observation "
@@ -270,26 +318,16 @@ int mpe_set_policy(mpe_env* e, const float* W1, const float* b1, const float* W2
 int mpe_rollout(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, float* rew_traj,
                 uint8_t* done_traj, float* last_obs, void* stream) {
   if (!e) return fail(MPE_EINVAL, "mpe_rollout: NULL handle");
-  if (T < 1) return fail(MPE_EINVAL, "mpe_rollout: T must be >= 1 (got %d)", T);
+  if (T < 1 || T > MPE_MAX_ROLLOUT_STEPS)
+    return fail(MPE_EINVAL, "mpe_rollout: T must be in [1, %d] (got %d)", MPE_MAX_ROLLOUT_STEPS, T);
   if (!e->ready) return fail(MPE_ESTATE, "mpe_rollout: call mpe_reset or mpe_set_state first");
+  if (int rc = check_fault(e, "mpe_rollout")) return rc;
   if ((obs_traj && !aligned16(obs_traj)) || (rew_traj && !aligned16(rew_traj)) ||
       (last_obs && !aligned16(last_obs)))
     return fail(MPE_EINVAL, "mpe_rollout: float outputs must be 16-byte aligned");
   if (uint64_t(e->abs_step) + uint64_t(T) > 0xFFFFFFFFull)
     return fail(MPE_EINVAL, "mpe_rollout: absolute step counter would overflow 32 bits");
-  RolloutArgs A;
-  A.st = e->st;
-  A.ph = e->ph;
-  A.TE = e->TE;
-  A.E = e->E;
-  A.seed = e->seed;
-  A.abs_step = e->abs_step;
-  A.T = T;
-  A.obs_traj = obs_traj;
-  A.act_traj = act_traj;
-  A.rew_traj = rew_traj;
-  A.done_traj = done_traj;
-  A.last_obs = last_obs;
+  const RolloutArgs A = rollout_args(e, T, obs_traj, act_traj, rew_traj, done_traj, last_obs);
   if (e->has_gru) {
     const char* why = nullptr;
     hipError_t err = launch_rollout_gru(e->N, A, e->gru, e->hidden, static_cast<hipStream_t>(stream), &why);
@@ -341,6 +379,9 @@ int mpe_set_gru_policy(mpe_env* e, const float* We, const float* be, const float
     launch_fill_zero(e->hidden, n, s);
     MPE_HIP(hipGetLastError());
   }
+  // until the new image is packed the handle has no recurrent policy: a failure below must not leave an
+  // earlier one installed on a partly rewritten buffer
+  e->has_gru = false;
   hipError_t err = pack_policy_gru(e->gru, e->N, int(e->R), We, be, Wi, bi, Wh, bh, Wf, bf, Wo, bo, s);
   if (err != hipSuccess) return fail(MPE_EHIP, "mpe_set_gru_policy: %s", hipGetErrorString(err));
   e->has_gru = true;
@@ -380,6 +421,7 @@ int mpe_set_critic(mpe_env* e, const float* V1, const float* c1, const float* V2
   }
   if (given != 6) return fail(MPE_EINVAL, "mpe_set_critic: pass all six arrays or none");
   hipError_t err;
+  e->has_critic = false;   // as in mpe_set_policy
   if (e->tag) {
     if (e->cfg.weight_dtype != MPE_WEIGHTS_FP32 || !tag_policy_supported(e->N, e->L, e->G, e->H, e->cfg.weight_dtype))
       return fail(MPE_EINVAL, "mpe_set_critic: unsupported shape: the MPE_SCENARIO_TAG actor-critic rollout is built "
@@ -404,8 +446,10 @@ int mpe_rollout_ac(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, fl
                    float* value_traj, float* rew_traj, uint8_t* done_traj, float* last_obs,
                    float* last_value, void* stream) {
   if (!e) return fail(MPE_EINVAL, "mpe_rollout_ac: NULL handle");
-  if (T < 1) return fail(MPE_EINVAL, "mpe_rollout_ac: T must be >= 1 (got %d)", T);
+  if (T < 1 || T > MPE_MAX_ROLLOUT_STEPS)
+    return fail(MPE_EINVAL, "mpe_rollout_ac: T must be in [1, %d] (got %d)", MPE_MAX_ROLLOUT_STEPS, T);
   if (!e->ready) return fail(MPE_ESTATE, "mpe_rollout_ac: call mpe_reset or mpe_set_state first");
+  if (int rc = check_fault(e, "mpe_rollout_ac")) return rc;
   if (!e->has_policy || !e->has_critic)
     return fail(MPE_ESTATE, "mpe_rollout_ac: needs mpe_set_policy and mpe_set_critic first");
   if (e->has_gru) return fail(MPE_ESTATE, "mpe_rollout_ac: remove the recurrent policy first (feed-forward networks only)");
@@ -416,19 +460,7 @@ int mpe_rollout_ac(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, fl
     if (p && !aligned16(p)) return fail(MPE_EINVAL, "mpe_rollout_ac: float outputs must be 16-byte aligned");
   if (uint64_t(e->abs_step) + uint64_t(T) > 0xFFFFFFFFull)
     return fail(MPE_EINVAL, "mpe_rollout_ac: absolute step counter would overflow 32 bits");
-  RolloutArgs A;
-  A.st = e->st;
-  A.ph = e->ph;
-  A.TE = e->TE;
-  A.E = e->E;
-  A.seed = e->seed;
-  A.abs_step = e->abs_step;
-  A.T = T;
-  A.obs_traj = obs_traj;
-  A.act_traj = act_traj;
-  A.rew_traj = rew_traj;
-  A.done_traj = done_traj;
-  A.last_obs = last_obs;
+  RolloutArgs A = rollout_args(e, T, obs_traj, act_traj, rew_traj, done_traj, last_obs);
   A.logp_traj = logp_traj;
   A.value_traj = value_traj;
   A.last_value = last_value;

@@ -52,6 +52,8 @@ struct RolloutArgs {
   float* logp_traj = nullptr;   // [T][TE][N] log-probability of the sampled action
   float* value_traj = nullptr;  // [T][TE][N] critic value of the observation acted on
   float* last_value = nullptr;  // [TE][N]    critic value of last_obs
+  // Word that a kernel raises (system scope) when a bounded wait gave up; null = not reported.
+  uint32_t* fault = nullptr;
 };
 
 // Predator-prey scenario: constants by role (index 0 adversary, 1 good agent), combined on the
@@ -96,11 +98,15 @@ void launch_step(int N, const StatePtrs& st, const Phys& ph, uint32_t TE, uint32
                  hipStream_t s);
 void launch_rollout_uniform(int N, const RolloutArgs& A, hipStream_t s);
 
-// Policy weights re-packed into MFMA A-operand order (device memory owned by the handle).
+// Policy weights re-packed into MFMA A-operand order (device memory owned by the handle, or, `borrowed`,
+// a piece of memory of `bytes` bytes that is never freed or grown here).
 struct PolicyBuffers {
   void* packed = nullptr;
   size_t bytes = 0;
+  bool borrowed = false;
 };
+// Bytes that pack_policy writes for R runs (0 for an unsupported shape).
+size_t packed_policy_bytes(int N, int H, int R, int weight_dtype);
 
 // Both return a HIP status; *why is set (and nothing launched) when the shape is unsupported.
 hipError_t pack_policy(PolicyBuffers& pb, int N, int H, int R, int weight_dtype, const float* W1,
@@ -112,6 +118,7 @@ void free_policy(PolicyBuffers& pb);
 
 // Per-kernel-family entry points behind pack_policy / launch_rollout_policy.
 bool wide_supported(int N, int H);                       // bf16 general kernel
+size_t packed_run_bytes_wide(int N, int H);
 hipError_t pack_policy_wide(PolicyBuffers& pb, int N, int H, int R, const float* W1, const float* b1,
                             const float* W2, const float* b2, const float* W3, const float* b3, int nout,
                             hipStream_t s);
@@ -122,6 +129,7 @@ hipError_t launch_rollout_policy_wide(int N, int H, const RolloutArgs& A, const 
 bool uniform_wide_supported(int N);                      // env-only rollout with the wide kernel's mapping
 hipError_t launch_rollout_uniform_wide(int N, const RolloutArgs& A, hipStream_t s);
 bool f32_supported(int N, int H);                        // headline kernel (H = 64, N <= 3), fp32 or bf16 weights
+size_t packed_run_bytes_f32(bool bf16);
 hipError_t pack_policy_f32(PolicyBuffers& pb, int N, int R, const float* W1, const float* b1, const float* W2,
                            const float* b2, const float* W3, const float* b3, int nout, bool bf16, hipStream_t s);
 hipError_t launch_rollout_ac_f32(int N, bool bf16, const RolloutArgs& A, const PolicyBuffers& pb,

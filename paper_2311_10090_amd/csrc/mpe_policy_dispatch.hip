@@ -5,6 +5,7 @@ namespace mpe {
 
 hipError_t ensure_policy_bytes(PolicyBuffers& pb, size_t bytes) {
   if (pb.bytes >= bytes) return hipSuccess;
+  if (pb.borrowed) return hipErrorOutOfMemory;   // the caller sized it with packed_policy_bytes
   if (pb.packed) {
     hipError_t e = hipFree(pb.packed);
     if (e != hipSuccess) return e;
@@ -18,13 +19,19 @@ hipError_t ensure_policy_bytes(PolicyBuffers& pb, size_t bytes) {
 }
 
 void free_policy(PolicyBuffers& pb) {
-  if (pb.packed) (void)hipFree(pb.packed);
+  if (pb.packed && !pb.borrowed) (void)hipFree(pb.packed);
   pb.packed = nullptr;
   pb.bytes = 0;
 }
 
 static const char* kUnsupported =
     "unsupported policy shape: need (num_agents, hidden, dtype) in {(1..3, 64, fp32 or bf16), (4..10, 64 | 128, bf16)}";
+
+size_t packed_policy_bytes(int N, int H, int R, int weight_dtype) {
+  if (weight_dtype == 1 && wide_supported(N, H)) return size_t(R) * packed_run_bytes_wide(N, H);
+  if (f32_supported(N, H)) return size_t(R) * packed_run_bytes_f32(weight_dtype == 1);
+  return 0;
+}
 
 hipError_t pack_policy(PolicyBuffers& pb, int N, int H, int R, int weight_dtype, const float* W1,
                        const float* b1, const float* W2, const float* b2, const float* W3,

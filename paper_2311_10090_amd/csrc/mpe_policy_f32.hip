@@ -1,6 +1,6 @@
 // Fused rollout kernel for the headline shape: fp32 policy 6N -> 64 -> 64 -> 5 (N <= 3 agents),
 // shared by all agents or one set of weights per run (paper: App. G IPPO table, two tanh layers
-// of width 64; Sec. 3.2 parameter sharing; Sec. 4.2 / App. F vmap over whole training runs).
+// of width 64; Sec. 3.2 parameter sharing; Sec. 5.2 and App. E: whole training runs vectorised on one device).
 //
 // Where the contraction runs.  On gfx950 the fp32 MFMA shares the vector datapath: fp32 matrix
 // and fp32 vector peaks are the same number, and measured MFMA-f32 and VALU time add up instead
@@ -241,7 +241,7 @@ __global__ __launch_bounds__((EB * N + RW - 1) / RW * 64, MINW) void rollout_pol
   uint8_t* done_base = A.done_traj;
   float* logp_base = A.logp_traj;
   float* value_base = A.value_traj;
-  const uint32_t row_off = uint32_t(gc) * N + i;      // index of this agent inside a time slice
+  const uint32_t row_off = uint32_t(gc) * N + i;      // index of this agent inside a time slice (TE <= 2^30 and N <= 3: below 2^32)
   const bool env_writer = valid && i == 0;            // the lane that stores per-env outputs
   uint32_t step = A.abs_step;
   const float* wtile = tile + wave * (RW * D);        // this wavefront's rows
@@ -837,6 +837,8 @@ hipError_t launch_ac_n(const RolloutArgs& A, const PolicyBuffers& pb, const Poli
 }  // namespace
 
 bool f32_supported(int N, int H) { return H == kH && N >= 1 && N <= 3; }
+
+size_t packed_run_bytes_f32(bool bf16) { return bf16 ? PkB::RUN_BYTES : Pk::RUN_BYTES; }
 
 hipError_t pack_policy_f32(PolicyBuffers& pb, int N, int R, const float* W1, const float* b1, const float* W2,
                            const float* b2, const float* W3, const float* b3, int nout, bool bf16, hipStream_t s) {

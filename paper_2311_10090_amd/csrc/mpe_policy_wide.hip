@@ -449,7 +449,7 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
   uint8_t* act_base = A.act_traj;
   float* rew_base = A.rew_traj;
   uint8_t* done_base = A.done_traj;
-  const uint32_t row_off = uint32_t(gc) * N + i;      // index of this agent inside a time slice
+  const size_t row_off = size_t(gc) * N + i;          // index of this agent inside a time slice (can pass 2^32)
   const bool env_writer = valid && i == 0;            // the lane that stores per-env outputs
   uint32_t step = A.abs_step;
   uint32_t overlaps = 0;   // PER_AGENT: other agents this one overlapped after the latest step
@@ -689,6 +689,13 @@ bool wide_supported(int N, int H) {
   MPE_WIDE_POLICY_CASES(X)
 #undef X
   return false;
+}
+
+size_t packed_run_bytes_wide(int N, int H) {
+#define X(N_, H_, EB_, MW_) if (N == N_ && H == H_) return Shape<N_, H_>::RUN_BYTES;
+  MPE_WIDE_POLICY_CASES(X)
+#undef X
+  return 0;
 }
 
 hipError_t pack_policy_wide(PolicyBuffers& pb, int N, int H, int R, const float* W1, const float* b1,

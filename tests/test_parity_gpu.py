@@ -676,3 +676,24 @@ def test_other_physics_constants_and_episode_length(mods, N, H, wd):
         Hp.assert_close_step(rew[mask], rrew[mask], "mixed reward t=%d" % t, sc[mask])
     assert dones == 2 * E   # 7-step episodes: done on steps 7 and 14
     env.close()
+
+
+def test_sync_group_barriers_end_and_long_rollouts_are_refused(mods):
+    """The kernels whose wavefronts meet at arrival counters in LDS (256-env blocks of the fused kernel,
+    per-run weights in register rows, the lane-per-agent kernel) leave the handle's fault word clear: a
+    later call on the same handle succeeds.  T beyond the documented limit is refused on the host."""
+    MpeEnv, _ = mods
+    from paper_2311_10090_amd.binding import MpeError, MPE_EINVAL
+    for (E, N, R, H, wd) in ((65536, 3, 1, 64, 0), (64, 3, 1024, 64, 0), (4096, 10, 1, 128, 1)):
+        env = MpeEnv(Hp.gpu_config(E, N, R, H, wd))
+        env.set_policy(*Hp.to_dev(synth.policy_weights(1, R, 6 * N, H)))
+        env.reset(2)
+        for _ in range(3):
+            env.rollout(30)
+            torch.cuda.synchronize()   # a give-up of an earlier call would be visible to the host now
+        env.rollout(1)
+        with pytest.raises(MpeError) as ei:
+            env.rollout((1 << 24) + 1)
+        assert ei.value.code == MPE_EINVAL
+        assert env.get_state()[4] == 91
+        env.close()
