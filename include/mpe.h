@@ -250,6 +250,29 @@ int mpe_get_state(mpe_env* env, float* pos_a, float* vel_a, float* pos_l, int32_
 int mpe_set_state(mpe_env* env, const float* pos_a, const float* vel_a, const float* pos_l,
                   const int32_t* ep_step, uint32_t seed, uint32_t abs_step, void* stream);
 
+/* For callers that cannot allocate device memory -- code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc: mpe_create + mpe_reset(seed) + mpe_set_policy + mpe_rollout(T) in ONE
+ * call that allocates nothing (no hipMalloc / hipFree / hipHostMalloc, no handle).  The memory that the
+ * handle-based calls own -- the SoA state of the TE environments (pos_a, vel_a, pos_l, ep_step), the packed
+ * policy image, one fault word -- is a static device array of MPE_NOALLOC_SCRATCH_BYTES inside the library,
+ * one copy per GPU, held until the process ends.
+ * cfg: as for mpe_create, MPE_SCENARIO_SPREAD only.  W1..b3: fp32 device pointers laid out as for
+ * mpe_set_policy (shapes as there), or all six NULL for seeded uniform actions.  Outputs as for mpe_rollout
+ * (any may be NULL); they are bit-identical to those of the four calls above, and the absolute step
+ * counter runs 0..T-1.  Nothing survives the call: the final state stays in the scratch array only until
+ * the next call on that GPU.
+ * MPE_EINVAL if the state of TE environments plus the packed policy does not fit the array
+ * (256 + 4 regions rounded up to 256 bytes: 2 x 8 N TE, 8 L TE + 16, 4 TE bytes; + the packed image:
+ * 33,344 bytes per run for the fp32 64-wide policies, up to 53,824 for the bf16 ones; 65,536 envs of 3
+ * agents need 5.0 MB), and for every argument mpe_create, mpe_set_policy or mpe_rollout would refuse.
+ * Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (two streams, two
+ * threads) race, and so would a replay of a captured graph overlapping another call; order them. */
+#define MPE_NOALLOC_SCRATCH_BYTES (8u << 20)
+int mpe_rollout_noalloc(const mpe_config* cfg, uint32_t seed, const float* W1, const float* b1,
+                        const float* W2, const float* b2, const float* W3, const float* b3, int32_t T,
+                        float* obs_traj, uint8_t* act_traj, float* rew_traj, uint8_t* done_traj,
+                        float* last_obs, void* stream);
+
 /* Text of the calling thread's most recent error ("" if none). Never NULL; static storage.  (C stand-in for
  * the exceptions of the paper's Python interface, App. C.) */
 const char* mpe_last_error(void);

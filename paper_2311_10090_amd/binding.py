@@ -23,7 +23,7 @@ NUM_ACTIONS = 5
 
 EXPORTS = ("mpe_create", "mpe_destroy", "mpe_obs_dim", "mpe_reset", "mpe_step", "mpe_set_policy",
            "mpe_rollout", "mpe_set_critic", "mpe_rollout_ac", "mpe_get_state", "mpe_set_state",
-           "mpe_set_gru_policy", "mpe_get_hidden", "mpe_set_hidden", "mpe_last_error")
+           "mpe_set_gru_policy", "mpe_get_hidden", "mpe_set_hidden", "mpe_rollout_noalloc", "mpe_last_error")
 GRU_HIDDEN = 128
 
 
@@ -101,6 +101,7 @@ def load_library():
     lib.mpe_set_hidden.argtypes = [vp, vp, vp]
     lib.mpe_set_critic.argtypes = [vp] + [vp] * 6 + [vp]
     lib.mpe_rollout_ac.argtypes = [vp, C.c_int32] + [vp] * 9
+    lib.mpe_rollout_noalloc.argtypes = [C.POINTER(_CConfig), C.c_uint32] + [vp] * 6 + [C.c_int32] + [vp] * 6
     for n in EXPORTS:
         if n != "mpe_last_error":
             getattr(lib, n).restype = C.c_int
@@ -246,3 +247,17 @@ class MpeEnv:
                                           _ptr(pos_l, torch.float32), _ptr(ep_step, torch.int32), seed, abs_step,
                                           _stream()))
 
+
+def rollout_noalloc(cfg: MpeConfig, seed: int, weights=None, T: int = 1, obs_traj=None, act_traj=None, rew_traj=None,
+                    done_traj=None, last_obs=None, device="cuda:0"):
+    """mpe_rollout_noalloc: reset(seed) + policy (six device tensors, or None for uniform actions) + T fused
+    steps in one call that allocates no device memory; outputs as MpeEnv.rollout."""
+    lib = load_library()
+    w = [_ptr(a, torch.float32) for a in (weights if weights is not None else (None,) * 6)]
+    assert len(w) == 6
+    with torch.cuda.device(torch.device(device)):
+        cc = cfg.to_c()
+        _check(lib.mpe_rollout_noalloc(C.byref(cc), seed, *w, T, _ptr(obs_traj, torch.float32),
+                                       _ptr(act_traj, torch.uint8), _ptr(rew_traj, torch.float32),
+                                       _ptr(done_traj, torch.uint8), _ptr(last_obs, torch.float32), _stream()))
+    return obs_traj, act_traj, rew_traj, done_traj, last_obs

@@ -518,4 +518,109 @@ int mpe_set_state(mpe_env* e, const float* pos_a, const float* vel_a, const floa
   return MPE_OK;
 }
 
+// ---------------------------------------------------------------------------------------------------
+// mpe_rollout_noalloc: reset + policy + T fused steps in one call that allocates nothing.  What the
+// handle-based path keeps in memory of its own -- the SoA state of the environments, the packed policy
+// image, the fault word -- lives in one static device array.
+// ---------------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[MPE_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<unsigned char*> g_scratch_ptr[kMaxDevices];   // address of `scratch` on each device, once known
+
+// `scratch` in host code is only a stand-in for the symbol; the device address of this device's copy comes
+// from the runtime, once per device (with that device current), and is what kernels and copies are given.
+int scratch_of_current_device(unsigned char** out) {
+  int dev = -1;
+  hipError_t err = hipGetDevice(&dev);
+  if (err != hipSuccess) return fail(MPE_EHIP, "mpe_rollout_noalloc: hipGetDevice: %s", hipGetErrorString(err));
+  if (dev < 0 || dev >= kMaxDevices) return fail(MPE_EHIP, "mpe_rollout_noalloc: device ordinal %d not supported", dev);
+  unsigned char* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    void* sym = nullptr;
+    err = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+    if (err != hipSuccess || !sym)
+      return fail(MPE_EHIP, "mpe_rollout_noalloc: hipGetSymbolAddress(scratch): %s", hipGetErrorString(err));
+    p = static_cast<unsigned char*>(sym);
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return MPE_OK;
+}
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace
+
+int mpe_rollout_noalloc(const mpe_config* cfg, uint32_t seed, const float* W1, const float* b1, const float* W2,
+                        const float* b2, const float* W3, const float* b3, int32_t T, float* obs_traj,
+                        uint8_t* act_traj, float* rew_traj, uint8_t* done_traj, float* last_obs, void* stream) {
+  if (!cfg) return fail(MPE_EINVAL, "mpe_rollout_noalloc: NULL config");
+  if (int rc = validate(cfg)) return rc;
+  if (cfg->scenario != MPE_SCENARIO_SPREAD)
+    return fail(MPE_EINVAL, "mpe_rollout_noalloc: built for MPE_SCENARIO_SPREAD");
+  if (T < 1 || T > MPE_MAX_ROLLOUT_STEPS)
+    return fail(MPE_EINVAL, "mpe_rollout_noalloc: T must be in [1, %d] (got %d)", MPE_MAX_ROLLOUT_STEPS, T);
+  if ((obs_traj && !aligned16(obs_traj)) || (rew_traj && !aligned16(rew_traj)) || (last_obs && !aligned16(last_obs)))
+    return fail(MPE_EINVAL, "mpe_rollout_noalloc: float outputs must be 16-byte aligned");
+  const int given = (W1 != nullptr) + (b1 != nullptr) + (W2 != nullptr) + (b2 != nullptr) + (W3 != nullptr) + (b3 != nullptr);
+  if (given != 0 && given != 6) return fail(MPE_EINVAL, "mpe_rollout_noalloc: pass all six weight arrays or none");
+  mpe_env e;   // host fields only, on the stack: nothing here owns memory
+  init_from_config(&e, cfg);
+  size_t packed_bytes = 0;
+  if (given) {
+    if (e.H != 64 && e.H != 128) return fail(MPE_EINVAL, "mpe_rollout_noalloc: config.hidden must be 64 or 128");
+    packed_bytes = packed_policy_bytes(e.N, e.H, int(e.R), cfg->weight_dtype);
+    if (!packed_bytes)
+      return fail(MPE_EINVAL, "mpe_rollout_noalloc: unsupported policy shape (see mpe_set_policy)");
+  }
+  // ---- layout inside the scratch array: fault word | pos_a | vel_a | pos_l | ep_step | packed policy
+  const size_t nf = agent_floats(&e) * sizeof(float);
+  const size_t off_pos = 256;
+  const size_t off_vel = align_up(off_pos + nf, 256);
+  const size_t off_lm = align_up(off_vel + nf, 256);
+  const size_t off_ep = align_up(off_lm + landmark_floats(&e) * sizeof(float) + 16, 256);
+  const size_t off_pk = align_up(off_ep + size_t(e.TE) * sizeof(int32_t), 256);
+  const size_t need = off_pk + packed_bytes;
+  if (need > size_t(MPE_NOALLOC_SCRATCH_BYTES))
+    return fail(MPE_EINVAL, "mpe_rollout_noalloc: %zu envs of %d agents (and the packed policy) need %zu bytes of "
+                            "library memory; the static scratch holds %zu", size_t(e.TE), e.N, need,
+                size_t(MPE_NOALLOC_SCRATCH_BYTES));
+  unsigned char* base = nullptr;
+  if (int rc = scratch_of_current_device(&base)) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  e.st.pos_a = reinterpret_cast<float*>(base + off_pos);
+  e.st.vel_a = reinterpret_cast<float*>(base + off_vel);
+  e.st.pos_l = reinterpret_cast<float*>(base + off_lm);
+  e.st.ep_step = reinterpret_cast<int32_t*>(base + off_ep);
+  e.fault_dev = reinterpret_cast<uint32_t*>(base);
+  // The array keeps the last call's contents.  Cleared here: the fault word (a fill kernel, not a memset node, so
+  // that the call can be captured into a graph).  Overwritten in full before use: the state (reset kernel) and
+  // the packed image (the pack kernel writes every byte of it that a rollout kernel reads).
+  launch_fill_zero(reinterpret_cast<float*>(base), 1, s);
+  launch_reset(e.N, e.st, e.TE, e.E, seed, nullptr, s);
+  MPE_HIP(hipGetLastError());
+  e.seed = seed;
+  e.abs_step = 0;
+  const RolloutArgs A = rollout_args(&e, T, obs_traj, act_traj, rew_traj, done_traj, last_obs);
+  const char* why = nullptr;
+  if (given) {
+    e.pol.packed = base + off_pk;
+    e.pol.bytes = packed_bytes;
+    e.pol.borrowed = true;
+    hipError_t err = pack_policy(e.pol, e.N, e.H, int(e.R), cfg->weight_dtype, W1, b1, W2, b2, W3, b3, s, &why);
+    if (why) return fail(MPE_EINVAL, "mpe_rollout_noalloc: %s", why);
+    if (err != hipSuccess) return fail(MPE_EHIP, "mpe_rollout_noalloc: %s", hipGetErrorString(err));
+    err = launch_rollout_policy(e.N, e.H, cfg->weight_dtype, A, e.pol, s, &why);
+    if (why) return fail(MPE_EINVAL, "mpe_rollout_noalloc: %s", why);
+    if (err != hipSuccess) return fail(MPE_EHIP, "mpe_rollout_noalloc: %s", hipGetErrorString(err));
+  } else {
+    launch_rollout_uniform(e.N, A, s);
+  }
+  MPE_HIP(hipGetLastError());
+  return MPE_OK;
+}
+
 }  // extern "C"
