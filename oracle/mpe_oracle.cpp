@@ -181,7 +181,7 @@ void reset_env(Oracle& o, int run, int env, uint32_t s) {
 void observe_env_tag(const Oracle& o, size_t ge, double* obs /* [N][D] */) {
   const double* pa = &o.pos_a[ge * o.N * 2];
   const double* va = &o.vel_a[ge * o.N * 2];
-  const double* pl = &o.pos_l[ge * o.L * 2];
+  const double* pl = o.pos_l.data() + ge * o.L * 2;   // (pos_l is empty without landmarks)
   const int A = o.cfg.num_adversaries;
   for (int i = 0; i < o.N; ++i) {
     double* ob = obs + size_t(i) * o.D;
@@ -212,7 +212,7 @@ void observe_env(const Oracle& o, size_t ge, double* obs /* [N][D] */) {
   if (o.cfg.scenario == 1) { observe_env_tag(o, ge, obs); return; }
   const double* pa = &o.pos_a[ge * o.N * 2];
   const double* va = &o.vel_a[ge * o.N * 2];
-  const double* pl = &o.pos_l[ge * o.L * 2];
+  const double* pl = o.pos_l.data() + ge * o.L * 2;   // (pos_l is empty without landmarks)
   for (int i = 0; i < o.N; ++i) {
     double* ob = obs + size_t(i) * o.D;
     int c = 0;
@@ -286,7 +286,7 @@ void step_env_tag(Oracle& o, int run, int env, uint32_t s, const uint8_t* act /*
   const size_t ge = size_t(run) * o.E + env;
   double* pa = &o.pos_a[ge * o.N * 2];
   double* va = &o.vel_a[ge * o.N * 2];
-  const double* pl = &o.pos_l[ge * o.L * 2];
+  const double* pl = o.pos_l.data() + ge * o.L * 2;   // (pos_l is empty without landmarks)
   const int A = c.num_adversaries;
   auto radius = [&](int i) { return i < A ? c.adv_radius : c.agent_radius; };
   auto gain = [&](int i) { return i < A ? c.adv_accel : c.accel; };
@@ -371,7 +371,7 @@ void step_env(Oracle& o, int run, int env, uint32_t s, const uint8_t* act /* [N]
   const size_t ge = size_t(run) * o.E + env;
   double* pa = &o.pos_a[ge * o.N * 2];
   double* va = &o.vel_a[ge * o.N * 2];
-  const double* pl = &o.pos_l[ge * o.L * 2];
+  const double* pl = o.pos_l.data() + ge * o.L * 2;   // (pos_l is empty without landmarks)
 
   std::vector<double> F(size_t(o.N) * 2, 0.0);
   for (int i = 0; i < o.N; ++i) {
@@ -974,9 +974,10 @@ int orc_rollout_ac(void* h, int32_t T, double* obs_traj, uint8_t* act_traj, doub
 int orc_get_state(void* h, double* pos_a, double* vel_a, double* pos_l, int32_t* ep_step,
                   uint32_t* abs_step) {
   Oracle& o = *static_cast<Oracle*>(h);
+  // (a scenario without landmarks has an empty pos_l: nothing to copy, and no pointer to copy from)
   if (pos_a) std::memcpy(pos_a, o.pos_a.data(), o.pos_a.size() * sizeof(double));
   if (vel_a) std::memcpy(vel_a, o.vel_a.data(), o.vel_a.size() * sizeof(double));
-  if (pos_l) std::memcpy(pos_l, o.pos_l.data(), o.pos_l.size() * sizeof(double));
+  if (pos_l && !o.pos_l.empty()) std::memcpy(pos_l, o.pos_l.data(), o.pos_l.size() * sizeof(double));
   if (ep_step) std::memcpy(ep_step, o.ep_step.data(), o.ep_step.size() * sizeof(int32_t));
   if (abs_step) *abs_step = o.abs_step;
   return 0;
@@ -984,11 +985,12 @@ int orc_get_state(void* h, double* pos_a, double* vel_a, double* pos_l, int32_t*
 
 int orc_set_state(void* h, const double* pos_a, const double* vel_a, const double* pos_l,
                   const int32_t* ep_step, uint32_t seed, uint32_t abs_step) {
-  if (!h || !pos_a || !vel_a || !pos_l || !ep_step) return fail("null argument");
+  if (!h || !pos_a || !vel_a || !ep_step) return fail("null argument");
   Oracle& o = *static_cast<Oracle*>(h);
+  if (!pos_l && !o.pos_l.empty()) return fail("null argument");
   std::memcpy(o.pos_a.data(), pos_a, o.pos_a.size() * sizeof(double));
   std::memcpy(o.vel_a.data(), vel_a, o.vel_a.size() * sizeof(double));
-  std::memcpy(o.pos_l.data(), pos_l, o.pos_l.size() * sizeof(double));
+  if (!o.pos_l.empty()) std::memcpy(o.pos_l.data(), pos_l, o.pos_l.size() * sizeof(double));
   std::memcpy(o.ep_step.data(), ep_step, o.ep_step.size() * sizeof(int32_t));
   o.seed = seed;
   o.abs_step = abs_step;

@@ -78,7 +78,9 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(build())
+        # MPE_ORACLE_LIB: load another build of the same source instead (the sanitizer and mutation tests
+        # compile instrumented or deliberately broken copies into a temporary folder)
+        _lib = C.CDLL(os.environ.get("MPE_ORACLE_LIB") or build())
         _lib.orc_last_error.restype = C.c_char_p
         _lib.orc_round_to_bf16.restype = C.c_double
         _lib.orc_round_to_bf16.argtypes = [C.c_double]

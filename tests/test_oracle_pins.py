@@ -469,6 +469,29 @@ def test_rollout_equals_repeated_steps_with_uniform_actions():
     assert all(np.array_equal(a, b) for a, b in zip(r3, (obs_t, act_t, rew_t, done_t, last)))
 
 
+def test_rollout_in_two_calls_continues_the_step_counter():
+    """The absolute step is part of every random stream's counter: a rollout of T1 steps followed by one of T2
+    steps is the rollout of T1 + T2 steps (uniform actions, and an auto-reset inside the second call), and the
+    state reports T1 + T2 steps; steps taken one at a time count the same way."""
+    E, N, T1, T2 = 5, 3, 11, 20
+    a, b, c = make(N=N, E=E), make(N=N, E=E), make(N=N, E=E)
+    for o in (a, b, c):
+        o.reset(4)
+    full = a.rollout(T1 + T2)
+    p1, p2 = b.rollout(T1), b.rollout(T2)
+    for k in range(4):
+        assert np.array_equal(full[k], np.concatenate([p1[k], p2[k]]))
+    assert np.array_equal(full[4], p2[4])
+    assert a.get_state()[4] == b.get_state()[4] == T1 + T2
+    # the second call draws its actions from counter steps T1, T1 + 1, ...
+    exp = np.array([[uniform_action(4, 0, e, T1, i) for i in range(N)] for e in range(E)], np.uint8)
+    assert np.array_equal(p2[1][0], exp)
+    for t in range(T1):
+        c.step(full[1][t])
+    assert c.get_state()[4] == T1
+    assert np.array_equal(c.rollout(T2)[1], p2[1])
+
+
 def test_env_offset_selects_the_same_streams():
     big = Oracle(OracleConfig(num_envs=10, num_agents=3, num_landmarks=3, num_runs=3))
     sub = Oracle(OracleConfig(num_envs=2, num_agents=3, num_landmarks=3, num_runs=1, env_offset=4, run_offset=2))

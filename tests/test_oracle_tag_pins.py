@@ -63,6 +63,8 @@ def test_hand_worked_two_step_example():
 # ------------------------------------------------------------------ boundary penalty of good agents
 @pytest.mark.parametrize("xy,penalty", [
     ((0.5, -0.3), 0.0),
+    ((0.85, -0.8999), 0.0),                   # nothing below 0.9
+    ((0.90625, 0.0), 0.0625),                 # the linear part starts at 0.9: 10 (u - 0.9)
     ((0.95, 0.0), 0.5),                       # linear part: 10 (u - 0.9)
     ((0.0, -0.99), 0.9),
     ((1.0, 0.0), 1.0),                        # exp(0)
