@@ -350,8 +350,8 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32" if wl.weight_dtype == 0 else "bf16xbf16->f32",
-        "dtype_note": ("env math f32; policy contraction: every f32 operand split exactly into 3 bf16 terms, "
-                       "6 cross products on the bf16 matrix cores, f32 accumulate") if wl.weight_dtype == 0 else
+        "dtype_note": ("env math f32; policy contraction: every f32 operand split into 3 fp16 terms (exact for |x| >= 0.5, "
+                       "2^-24 absolute below), 6 cross products on the 16-bit matrix cores, f32 accumulate") if wl.weight_dtype == 0 else
                       "weights and layer inputs rounded to bf16, f32 accumulate",
         "data": "synthetic",
         "config": {"workload": wl.name, "envs": TE, "agents": N, "T": T, "policy": "%d->%d->%d->5 tanh" % (D, H, H),
@@ -366,7 +366,7 @@ def main():
             # SQ counters below), not the matrix cores and not HBM.  `achieved` is the algorithmic work, the
             # contraction's fp32 FLOPs per agent-step, over the measured time; `peak` the chip's fp32 rate
             # (vector and matrix fp32 peaks are the same number, 157.3 TFLOP/s).  The contraction itself is
-            # executed on the bf16 matrix cores (exact 3-term operand split): see executed_bf16_mfma.
+            # executed on the 16-bit matrix cores (3-term fp16 operand split): see executed_16bit_mfma.
             "bound": "alu", "achieved": tflops, "peak": MFMA_FP32_PEAK_TFLOPS if wl.weight_dtype == 0 else 2500.0,
             "unit": "TFLOP/s",
             "frac": tflops / (MFMA_FP32_PEAK_TFLOPS if wl.weight_dtype == 0 else 2500.0),
@@ -379,11 +379,11 @@ def main():
             "flop_per_agent_step": flops_per_agent_step(D, H),
             "hbm_achieved_GBs": fused_gbs,
             # what the matrix cores really execute: matrix instructions per 64 agent rows and step
-            # (16 x 16 x 32 bf16 each = 16,384 FLOP), against the bf16 matrix peak
-            "executed_bf16_mfma": (lambda n_mfma: {
+            # (16 x 16 x 32 fp16 or bf16 each = 16,384 FLOP), against the fp16 / bf16 matrix peak (2.5 PFLOP/s)
+            "executed_16bit_mfma": (lambda n_mfma: {
                 "instructions_per_64_rows_step": n_mfma,
                 "TFLOPs": n_mfma * 16384 * (agent_steps / 64) / (kavg * 1e-3) / 1e12,
-                "frac_of_bf16_peak": n_mfma * 16384 * (agent_steps / 64) / (kavg * 1e-3) / 1e12 / 2500.0,
+                "frac_of_16bit_peak": n_mfma * 16384 * (agent_steps / 64) / (kavg * 1e-3) / 1e12 / 2500.0,
             })(264 if (wl.weight_dtype == 0 and N >= 2) else 288 if wl.weight_dtype == 0 else 208 if H == 128 else 56),
         },
         "env_only": {

@@ -1,5 +1,5 @@
-// The 64-wide two-layer tanh MLP of the fused rollout kernels on the bf16 matrix cores: packing of
-// the weights into A-operand order, the exact three-term operand split that gives fp32 products,
+// The 64-wide two-layer tanh MLP of the fused rollout kernels on the 16-bit matrix cores: packing of
+// the weights into A-operand order, the three-term operand split that gives fp32 products,
 // and the forward pass of two 16-row tiles (fp32-exact and bf16 variants).  Shared by the kernels
 // of both scenarios; everything is templated on a shape S:
 //   S::D         floats per observation row in the LDS tile (row stride)
@@ -27,25 +27,51 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kH = 64;                    // hidden width
 constexpr float kPre = 2.0f * kLog2e;     // both tanh layers get pre-activations already times 2*log2(e)
 
-// ------------------------------------------------------------------------------ exact split
-// Bit patterns of the three terms as floats whose low 16 bits are zero.
-__host__ __device__ __forceinline__ void split3(float x, uint32_t& h, uint32_t& m, uint32_t& l) {
-#if defined(__HIP_DEVICE_COMPILE__)
-  h = __float_as_uint(x) & 0xFFFF0000u;
-  const float r1 = x - __uint_as_float(h);
-  m = __float_as_uint(r1) & 0xFFFF0000u;
-  l = __float_as_uint(r1 - __uint_as_float(m));
-#else
-  h = m = l = 0;
-  (void)x;
-#endif
-}
-// Pack the high halves of two float bit patterns: low 16 bits <- a, high 16 bits <- b.
-__device__ __forceinline__ uint32_t pack_hi16(uint32_t a, uint32_t b) {
-  return __builtin_amdgcn_perm(b, a, 0x07060302u);
+// ------------------------------------------------------------------------------ three-term split
+// An fp32 operand as the sum of three fp16 terms, x = h + m + l: h = x truncated to fp16 (11 significant
+// bits), m = (x - h) truncated, l = x - h - m truncated; both differences are exact in fp32.  11 + 11 + 2
+// bits cover the 24 of an fp32 number, so the split is EXACT for |x| >= 0.5 (and < 65,504); below that the
+// third term lies on fp16's subnormal grid and x is represented to within 2^-24 ABSOLUTE (6e-8, half of what
+// the hardware tanh that produces the activations is accurate to).  The matrix instruction takes subnormal
+// fp16 inputs at full precision (checked on the chip).  Truncation (round toward zero) keeps every term of
+// the sign of x and is one instruction for two values (v_cvt_pkrtz_f16_f32); a difference is one mixed-
+// precision fma that reads the fp16 half in place (v_fma_mix_f32): 7 instructions per PAIR of values, and
+// the packed pairs are the matrix operands as they are.  (An fp32 = 3 x bf16 split, 8 + 8 + 8 bits, is exact
+// everywhere but costs 11 instructions per pair: and, sub, and, sub per value and three byte-permutes.)
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+// c - a, where a is the low (HI = false) or high half of a packed fp16 pair: one v_fma_mix_f32, which
+// widens the half in place.  (Written as a * -1 + c in plain C++ the compiler folds it into a conversion
+// and a subtraction, two instructions.)
+template <bool HI>
+__device__ __forceinline__ float sub_half(uint32_t pair, float c) {
+  float d;
+  if constexpr (HI) asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(pair), "v"(c));
+  else asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel_hi:[1,0,0]" : "=v"(d) : "v"(pair), "v"(c));
+  return d;
 }
 
-// Packed per-run layout (bytes).  A operands of v_mfma_f32_16x16x32_bf16: lane (i = lane%16,
+// Two values at once: the packed pairs (low half <- x0) of the three terms.
+__device__ __forceinline__ void split3_pair(float x0, float x1, uint32_t& ph, uint32_t& pm, uint32_t& pl) {
+  ph = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(x0, x1));
+  const float r0 = sub_half<false>(ph, x0);
+  const float r1 = sub_half<true>(ph, x1);
+  pm = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(r0, r1));
+  const float s0 = sub_half<false>(pm, r0);
+  const float s1 = sub_half<true>(pm, r1);
+  pl = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(s0, s1));
+}
+// One value: the 16-bit patterns of its three terms.
+__device__ __forceinline__ void split3(float x, uint32_t& h, uint32_t& m, uint32_t& l) {
+  uint32_t ph, pm, pl;
+  split3_pair(x, 0.0f, ph, pm, pl);
+  h = ph & 0xFFFFu;
+  m = pm & 0xFFFFu;
+  l = pl & 0xFFFFu;
+}
+
+// Packed per-run layout (bytes).  A operands of v_mfma_f32_16x16x32_f16 (fp16 terms of the split): lane (i = lane%16,
 // gq = lane/16) holds weights [k = 8 gq + e][out = 16 m + i], e = 0..7 (16 bytes), per term.
 //   W1A [m 4][combo 2][lane 64]  layer 1 has only 16 inputs, half of the instruction's K = 32, so
 //                                 two cross terms share one instruction: K positions 0..15 (lanes
@@ -111,9 +137,9 @@ __global__ void pack_split_kernel(uint8_t* __restrict__ packed, const float* __r
     uint32_t h, m, l;
     split3(v, h, m, l);
     uint16_t* base = reinterpret_cast<uint16_t*>(out + off) + size_t(blk) * 3 * lanes * 8 + lane * 8 + e;
-    base[0] = uint16_t(h >> 16);
-    base[size_t(lanes) * 8] = uint16_t(m >> 16);
-    base[size_t(2) * lanes * 8] = uint16_t(l >> 16);
+    base[0] = uint16_t(h);
+    base[size_t(lanes) * 8] = uint16_t(m);
+    base[size_t(2) * lanes * 8] = uint16_t(l);
   };
   if (idx < n1) {
     const int e = idx % 8, lane = (idx / 8) % 64, m = idx / 512;
@@ -121,8 +147,8 @@ __global__ void pack_split_kernel(uint8_t* __restrict__ packed, const float* __r
     uint32_t h, mm, l;
     split3(k < KIN ? kPre * W1[size_t(k) * kH + o] : 0.0f, h, mm, l);
     uint16_t* base = reinterpret_cast<uint16_t*>(out + Pk::OFF_W1A) + size_t(m) * 2 * 64 * 8 + lane * 8 + e;
-    base[0] = uint16_t((gq < 2 ? h : mm) >> 16);        // combo 0 = (h | m)
-    base[64 * 8] = uint16_t((gq < 2 ? h : l) >> 16);    // combo 1 = (h | l)
+    base[0] = uint16_t(gq < 2 ? h : mm);        // combo 0 = (h | m)
+    base[64 * 8] = uint16_t(gq < 2 ? h : l);    // combo 1 = (h | l)
     return;
   }
   idx -= n1;
@@ -140,7 +166,7 @@ __global__ void pack_split_kernel(uint8_t* __restrict__ packed, const float* __r
       const int out_o = l3_row_output(o), term = l3_row_term(o);
       uint32_t t3[3] = {0u, 0u, 0u};
       if (out_o >= 0 && out_o < nout) split3(W3[size_t(k) * nout + out_o], t3[0], t3[1], t3[2]);
-      reinterpret_cast<uint16_t*>(out + Pk::OFF_W3A)[(size_t(s) * 64 + lane) * 8 + e] = uint16_t(t3[term] >> 16);
+      reinterpret_cast<uint16_t*>(out + Pk::OFF_W3A)[(size_t(s) * 64 + lane) * 8 + e] = uint16_t(t3[term]);
     } else {
       put3(Pk::OFF_W3A, s, 64, lane, e, o < nout ? W3[size_t(k) * nout + o] : 0.0f);
     }
@@ -160,21 +186,20 @@ __global__ void pack_split_kernel(uint8_t* __restrict__ packed, const float* __r
 }
 
 // ------------------------------------------------------------------------------ operands
-struct Terms {   // the three bf16x8 terms of one B (or A) operand
+struct Terms {   // the three terms of one B (or A) operand: 8 x 16 bits each (fp16; one bf16 term in the bf16 variant)
   bf16x8 h, m, l;
 };
 
 // Split 8 fp32 activations into the three packed terms.
 __device__ __forceinline__ Terms split_operand(const float (&v)[8]) {
-  uint32_t h[8], m[8], l[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) split3(v[e], h[e], m[e], l[e]);
   u32x4 ph, pm, pl;
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
-    ph[q] = pack_hi16(h[2 * q], h[2 * q + 1]);
-    pm[q] = pack_hi16(m[2 * q], m[2 * q + 1]);
-    pl[q] = pack_hi16(l[2 * q], l[2 * q + 1]);
+    uint32_t a, b, c;
+    split3_pair(v[2 * q], v[2 * q + 1], a, b, c);
+    ph[q] = a;
+    pm[q] = b;
+    pl[q] = c;
   }
   Terms t;
   t.h = __builtin_bit_cast(bf16x8, ph);
@@ -184,15 +209,19 @@ __device__ __forceinline__ Terms split_operand(const float (&v)[8]) {
 }
 
 #define MPE_MFMA_BF(A, B, C) __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, B, C, 0, 0, 0)
+// the same shape on fp16 operands, for the terms of the three-term split (stored as raw 8 x 16 bits)
+#define MPE_MFMA_SPLIT(A, B, C) \
+  __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, A), __builtin_bit_cast(f16x8, B), C, 0, 0, 0)
 
-// acc += A * B from the six significant cross terms, smallest first.
+// acc += A * B from the six cross terms of weight >= 2^-22 (terms h, m, l weigh 1, 2^-11, 2^-22; the
+// dropped m l, l m, l l are below 2^-33 of the product), smallest first.
 __device__ __forceinline__ f32x4 mma_split(const Terms& a, const Terms& b, f32x4 acc) {
-  acc = MPE_MFMA_BF(a.l, b.h, acc);
-  acc = MPE_MFMA_BF(a.h, b.l, acc);
-  acc = MPE_MFMA_BF(a.m, b.m, acc);
-  acc = MPE_MFMA_BF(a.m, b.h, acc);
-  acc = MPE_MFMA_BF(a.h, b.m, acc);
-  acc = MPE_MFMA_BF(a.h, b.h, acc);
+  acc = MPE_MFMA_SPLIT(a.l, b.h, acc);
+  acc = MPE_MFMA_SPLIT(a.h, b.l, acc);
+  acc = MPE_MFMA_SPLIT(a.m, b.m, acc);
+  acc = MPE_MFMA_SPLIT(a.m, b.h, acc);
+  acc = MPE_MFMA_SPLIT(a.h, b.m, acc);
+  acc = MPE_MFMA_SPLIT(a.h, b.h, acc);
   return acc;
 }
 
@@ -257,9 +286,9 @@ __device__ __forceinline__ void policy_core(const uint8_t* __restrict__ wsm, con
   auto layer1 = [&](int m, const Terms& b, const bf16x8& b_lh, f32x4 acc) {
     const bf16x8 a_hm = w1[(m * 2 + 0) * 64 + lane];
     const bf16x8 a_hl = w1[(m * 2 + 1) * 64 + lane];
-    acc = MPE_MFMA_BF(a_hl, b_lh, acc);
-    acc = MPE_MFMA_BF(a_hm, b.m, acc);
-    acc = MPE_MFMA_BF(a_hm, b.h, acc);
+    acc = MPE_MFMA_SPLIT(a_hl, b_lh, acc);
+    acc = MPE_MFMA_SPLIT(a_hm, b.m, acc);
+    acc = MPE_MFMA_SPLIT(a_hm, b.h, acc);
     return acc;
   };
   auto load_w2 = [&](int m, int s) {
@@ -273,9 +302,9 @@ __device__ __forceinline__ void policy_core(const uint8_t* __restrict__ wsm, con
   // (all nine cross terms, smallest first); otherwise the six significant ones.
   auto layer3 = [&](const Terms& a, const Terms& b, f32x4 acc) {
     if constexpr (S::kRowTerms) {
-      acc = MPE_MFMA_BF(a.h, b.l, acc);
-      acc = MPE_MFMA_BF(a.h, b.m, acc);
-      acc = MPE_MFMA_BF(a.h, b.h, acc);
+      acc = MPE_MFMA_SPLIT(a.h, b.l, acc);
+      acc = MPE_MFMA_SPLIT(a.h, b.m, acc);
+      acc = MPE_MFMA_SPLIT(a.h, b.h, acc);
       return acc;
     } else {
       return mma_split(a, b, acc);

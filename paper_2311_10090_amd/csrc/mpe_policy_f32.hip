@@ -4,18 +4,21 @@
 //
 // Where the contraction runs.  On gfx950 the fp32 MFMA shares the vector datapath: fp32 matrix
 // and fp32 vector peaks are the same number, and measured MFMA-f32 and VALU time add up instead
-// of overlapping.  The 16-bit matrix cores are a separate unit, 16x faster per K, and do overlap
-// with VALU work.  So every fp32 operand is split EXACTLY into three bf16 terms
-//     x = h + m + l,   h = top 16 bits of x, m = top 16 bits of (x - h), l = x - h - m
-// (8 + 8 + 8 = 24 significant bits; each difference is exact in fp32) and the product of two
-// operands is accumulated in fp32 from the six cross terms of weight >= 2^-16:
-//     x*w ~= hh + hm + mh + hl + lh + mm      (dropped: ml + lm + ll <= 2^-23 |x w|)
-// i.e. the same operand values as an fp32 GEMM, with a truncation of the order of one fp32
-// rounding.  Weights are split once by the pack kernel; activations are split in registers.
+// of overlapping.  The 16-bit matrix cores are a separate unit, 16x faster per K.  So every fp32
+// operand is split into three fp16 terms
+//     x = h + m + l,   h = x truncated to fp16, m = (x - h) truncated, l = x - h - m truncated
+// (11 + 11 + 2 = 24 significant bits, each difference exact in fp32: the split is exact for
+// 0.5 <= |x| < 65,504 and within 2^-24 absolute below, see mpe_mlp64.h) and the product of two
+// operands is accumulated in fp32 from the six cross terms of weight >= 2^-22:
+//     x*w ~= hh + hm + mh + mm + hl + lh      (dropped: ml + lm + ll <= 2^-32 |x w|)
+// i.e. the operand values of an fp32 GEMM to within half an fp32 rounding of a number of size 1.
+// Weights are split once by the pack kernel; activations are split in registers (7 vector
+// instructions per pair of values; the earlier split into three bf16 terms, 8 + 8 + 8 bits, exact
+// everywhere, took 11 and made the whole rollout 4-5 % slower).
 //
 // Mapping: one lane per agent row; a wavefront owns 64 rows = two pairs of 16-row tiles; each
 // A operand (weights, from LDS) is loaded once per pair.  The accumulator layout of
-// v_mfma_f32_16x16x32_bf16 (lane (j, gq) holds batch row j and hidden units 16m + 4gq + r) is
+// v_mfma_f32_16x16x32_f16 / _bf16 (lane (j, gq) holds batch row j and hidden units 16m + 4gq + r) is
 // again a B-operand layout for the next layer when the weights are packed in the matching K
 // order, so activations stay in registers between layers.  Every wavefront works on its own
 // rows of the LDS observation tile; the only cross-wavefront data are the new positions of the

@@ -13,8 +13,10 @@
 // its 24 GRU A-operands (r, z, n gates x input/recurrent x 4 K slices) and its embedding operand
 // in registers for the whole rollout (100 of its 256 registers); the small layers' operands
 // (second fully-connected layer, logits) sit in LDS.  Activations of all rows go through LDS as
-// bf16 rows of 128 (+ 16 bytes of padding per row, which spreads the 16-byte operand reads evenly
-// over the banks): every wavefront reads all K of a row tile and writes its own 16 units.  The
+// bf16 rows of 128 (+ 16 bytes of padding per row) in which the rows 8..15 of every 16-row tile hold
+// each pair of neighbouring 16-byte pieces swapped (act_piece below): padding and swap together make
+// the 16-byte operand reads free of bank conflicts.  Every wavefront reads all K of a row tile
+// and writes its own 16 units.  The
 // carried state stays in fp32 registers of the owning wavefront (4 values per lane and row tile);
 // its bf16 copy for the next product lives in LDS.  Phases of a step, separated by block barriers:
 //   embed -> X | gates (reads X, HB) | HB <- h' | fc (reads HB) -> Y=X | logits -> L |
@@ -30,6 +32,19 @@ namespace {
 
 constexpr int kG = 128;    // hidden width of every layer
 constexpr int kAS = 272;   // bytes per activation row in LDS: 128 bf16 + 16 bytes of padding
+
+// Where the 16-byte piece w (= units 8w .. 8w + 7) of row j of a 16-row tile sits inside the row: piece
+// w for rows 0..7, piece w ^ 1 for rows 8..15.  Measured on this chip (bank-conflict counter on stand-alone
+// access patterns): a 16-byte LDS read is served in four passes of 16 lanes over 64 banks, and a pass is
+// lanes 0-7 + 24-31, 8-15 + 16-23, 32-39 + 56-63 or 40-47 + 48-55.  With lane (j, gq) reading piece 4 s + gq
+// of row j, a pass holds rows 0..7 at one gq and rows 8..15 at gq ^ 1; with rows 68 dwords apart the first
+// eight start at banks 4 j + 4 gq, the other eight, unswapped, at 4 j + 4 (gq ^ 1): row 15 meets row 0 (one
+// extra pass on EVERY read, which is what the padding alone cost).  The swap puts both halves at the same gq
+// parity: 16 different pieces, no conflict (an exhaustive search over per-row swaps inside a K slice finds
+// this one and its mirror images only; wider swizzles cost address registers, which this kernel spills).
+// 8-byte writes are served over 32 banks in passes of 16 consecutive lanes: the 16 rows of a pass share 8
+// bank pairs, one extra cycle per pass, with or without the swap.
+__device__ __forceinline__ int act_piece(int w, int row_in_tile) { return w ^ (row_in_tile >> 3); }
 
 // Packed weight image (bytes).  A operands of v_mfma_f32_16x16x32_bf16: lane (i = lane % 16,
 // gq = lane / 16) holds weights [k = 32 s + 8 gq + e][out = 16 u + i], e = 0..7.
@@ -166,6 +181,13 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
   const int lane = tid & 63;
   const int u = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront = owned unit tile
   const int j = lane & 15, gq = lane >> 4;
+  // Byte offsets of this lane inside a tile of 16 activation rows (every row it touches is row j of its
+  // tile): where it writes its 4 units 16 u + 4 gq .. + 3 (8 bytes: half gq & 1 of piece 2 u + gq / 2), and
+  // where it reads piece gq of K slice 0 (slice s is 64 s bytes further).  Two values per lane for the whole
+  // rollout; tile and slice offsets are constants of the unrolled loops and go into the instructions.
+  const int wr_off = j * kAS + 16 * act_piece(2 * u + (gq >> 1), j) + 8 * (gq & 1);
+  const int rd_off = j * kAS + 16 * act_piece(gq, j);
+  constexpr int kTile = 16 * kAS;   // bytes of one tile of 16 activation rows
   const size_t TE = A.TE;
   const uint32_t grp = (blockIdx.x & 7u) * groups_per_xcd + (blockIdx.x >> 3);
   if (grp >= groups) return;  // whole block, before any barrier
@@ -205,7 +227,7 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
     if (row < vrows) v = *reinterpret_cast<const f32x4*>(hidden + (g0 * N + row) * kG + 16 * u + 4 * gq);
 #pragma unroll
     for (int r = 0; r < 4; ++r) hreg[rt][r] = v[r];
-    *reinterpret_cast<uint2*>(hbuf + row * kAS + (16 * u + 4 * gq) * 2) = pack4_bf16(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<uint2*>(hbuf + rt * kTile + wr_off) = pack4_bf16(v[0], v[1], v[2], v[3]);
   }
 
   // ---- agents: the first B threads, one lane per agent row
@@ -298,7 +320,7 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
       const int row = 16 * rt + j;
       f32x4 acc = *reinterpret_cast<const f32x4*>(bias + 16 * u + 4 * gq);
       acc = MPE_MFMA_BF(we, *reinterpret_cast<const bf16x8*>(otile + row * M::OS + 16 * gq), acc);
-      *reinterpret_cast<uint2*>(xbuf + row * kAS + (16 * u + 4 * gq) * 2) =
+      *reinterpret_cast<uint2*>(xbuf + rt * kTile + wr_off) =
           pack4_bf16(fast_tanh(acc[0]), fast_tanh(acc[1]), fast_tanh(acc[2]), fast_tanh(acc[3]));
     }
     __syncthreads();   // X complete; the observation tile has been read
@@ -315,8 +337,8 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
       f32x4 anh = *reinterpret_cast<const f32x4*>(bias + 4 * kG + 16 * u + 4 * gq);
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        const bf16x8 bx = *reinterpret_cast<const bf16x8*>(xbuf + row * kAS + 64 * s + 16 * gq);
-        const bf16x8 bh = *reinterpret_cast<const bf16x8*>(hbuf + row * kAS + 64 * s + 16 * gq);
+        const bf16x8 bx = *reinterpret_cast<const bf16x8*>(xbuf + rt * kTile + 64 * s + rd_off);
+        const bf16x8 bh = *reinterpret_cast<const bf16x8*>(hbuf + rt * kTile + 64 * s + rd_off);
         // dependent accumulations three instructions apart
         ar = MPE_MFMA_BF(wg[0][0][s], bx, ar);
         az = MPE_MFMA_BF(wg[1][0][s], bx, az);
@@ -337,7 +359,7 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
     __syncthreads();   // every wavefront has read the old HB
 #pragma unroll
     for (int rt = 0; rt < NT; ++rt)
-      *reinterpret_cast<uint2*>(hbuf + (16 * rt + j) * kAS + (16 * u + 4 * gq) * 2) =
+      *reinterpret_cast<uint2*>(hbuf + rt * kTile + wr_off) =
           pack4_bf16(hreg[rt][0], hreg[rt][1], hreg[rt][2], hreg[rt][3]);
     __syncthreads();   // HB = bf16(h')
 
@@ -348,12 +370,11 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
       for (int s = 0; s < 4; ++s) wf[s] = fcw[(u * 4 + s) * 64 + lane];
 #pragma unroll
       for (int rt = 0; rt < NT; ++rt) {
-        const int row = 16 * rt + j;
         f32x4 acc = *reinterpret_cast<const f32x4*>(bias + 5 * kG + 16 * u + 4 * gq);
 #pragma unroll
         for (int s = 0; s < 4; ++s)
-          acc = MPE_MFMA_BF(wf[s], *reinterpret_cast<const bf16x8*>(hbuf + row * kAS + 64 * s + 16 * gq), acc);
-        *reinterpret_cast<uint2*>(xbuf + row * kAS + (16 * u + 4 * gq) * 2) =
+          acc = MPE_MFMA_BF(wf[s], *reinterpret_cast<const bf16x8*>(hbuf + rt * kTile + 64 * s + rd_off), acc);
+        *reinterpret_cast<uint2*>(xbuf + rt * kTile + wr_off) =
             pack4_bf16(fast_tanh(acc[0]), fast_tanh(acc[1]), fast_tanh(acc[2]), fast_tanh(acc[3]));
       }
     }
@@ -365,7 +386,7 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
       f32x4 acc = *reinterpret_cast<const f32x4*>(bias + 6 * kG + 4 * gq);
 #pragma unroll
       for (int s = 0; s < 4; ++s)
-        acc = MPE_MFMA_BF(outw[s * 64 + lane], *reinterpret_cast<const bf16x8*>(xbuf + row * kAS + 64 * s + 16 * gq), acc);
+        acc = MPE_MFMA_BF(outw[s * 64 + lane], *reinterpret_cast<const bf16x8*>(xbuf + rt * kTile + 64 * s + rd_off), acc);
       if (gq == 0) *reinterpret_cast<f32x4*>(logits + row * 8) = acc;       // outputs 0..3
       else if (gq == 1) logits[row * 8 + 4] = acc[0];                       // output 4
     }
