@@ -4,10 +4,13 @@ accumulation and carried state) against the oracle, through the C ABI.
 What can be asked of a bf16 network: both sides round the same fp32/fp64 values to bf16 at the same
 points, but a value that sits within ~1e-7 of a rounding boundary can round the other way on the
 fp32 path (its tanh / sigmoid / sums carry ~1e-7 of error), which moves one input of the next
-product by 2^-9 relative.  So teacher-forced single steps are compared statistically: most carried
-states within 1e-5, none beyond a few 1e-3, actions >= 99 % equal (the bf16 bar of the wide
-feed-forward policy); everything that is not arithmetic (state carry across calls, clearing at
-episode ends, time slots, determinism) is compared bit for bit."""
+product by one bf16 step.  The teacher-forced test therefore EXPLAINS every deviation of the carried
+state: a float64 re-derivation of the network (numpy, below) finds the embedding outputs that sit
+within 4e-7 of a bf16 rounding boundary ("fragile" inputs); a row without any must match the oracle to
+1e-5 in every element, and a row with some may deviate by at most the first-order effect of flipping
+exactly those roundings.  Actions must agree for >= 99.95 % of the samples.  Everything that is not
+arithmetic (state carry across calls, clearing at episode ends, time slots, determinism) is compared
+bit for bit."""
 import numpy as np
 import pytest
 
@@ -43,16 +46,73 @@ def _pair(mods, E, N, wseed=3, max_ep=synth.MAX_EPISODE_STEPS, reward_mode=0):
     return env, orc, w
 
 
+def _bf16(x):
+    """float64 array -> nearest bfloat16 value (ties to even), one rounding, by integer arithmetic on the
+    bit pattern (bfloat16 keeps 7 of the 52 stored mantissa bits)."""
+    u = np.ascontiguousarray(x, np.float64).view(np.int64)
+    lsb = (u >> 45) & 1
+    return ((u + ((1 << 44) - 1) + lsb) & ~((1 << 45) - 1)).view(np.float64)
+
+
+def _bf16_step_and_boundary_distance(x):
+    """Spacing of the bfloat16 grid at x and the distance of x to the nearest rounding boundary (the
+    midpoint of two neighbouring bfloat16 values)."""
+    m, e = np.frexp(x)                      # x = m 2^e, 0.5 <= |m| < 1: grid spacing 2^(e - 8)
+    step = np.ldexp(1.0, e - 8)
+    frac = np.abs(m) * 256.0
+    frac = frac - np.floor(frac)
+    return step, np.abs(frac - 0.5) * step
+
+
+def _carried_state_bound(w, obs, h0, fragile_tol=4e-7):
+    """float64 re-derivation of one step of the recurrent policy's state update (the reading documented in
+    include/mpe.h) for rows obs [n][D], h0 [n][128].  Returns (new state, bound [n][128], rows whose
+    OBSERVATION has an entry near a rounding boundary, fragile roundings per row): bound = 1e-5 + the
+    first-order effect, on every element of the new state, of flipping the bf16 rounding of each embedding
+    output that lies within fragile_tol of a boundary and of each carried-state element that lies within a
+    float32 rounding of one."""
+    We, be, Wi, bi, Wh, bh = [np.asarray(a[0], np.float64) for a in w[:6]]
+    We, Wi, Wh = _bf16(We), _bf16(Wi), _bf16(Wh)
+    e = np.tanh(_bf16(obs) @ We + be)
+    hb = _bf16(h0)
+    gi, gh = _bf16(e) @ Wi + bi, hb @ Wh + bh
+    r = 1.0 / (1.0 + np.exp(-(gi[:, :G] + gh[:, :G])))
+    z = 1.0 / (1.0 + np.exp(-(gi[:, G:2 * G] + gh[:, G:2 * G])))
+    n = np.tanh(gi[:, 2 * G:] + r * gh[:, 2 * G:])
+    h1 = (1.0 - z) * n + z * h0
+    step, dist = _bf16_step_and_boundary_distance(e)
+    flip = np.where(dist <= fragile_tol, step, 0.0)              # [n][128]: size of a possible flip of e_k
+    # the carried state arrives as float32 on the device and as float64 here (2^-24 relative apart): its
+    # rounding to bf16 can flip too
+    hstep, hdist = _bf16_step_and_boundary_distance(np.where(h0 == 0.0, 1.0, h0))
+    hflip = np.where((hdist <= 1.5e-7 * np.maximum(np.abs(h0), 2.0 ** -10)) & (h0.astype(np.float32).astype(np.float64) != h0),
+                     hstep, 0.0)
+    d_r = flip @ np.abs(Wi[:, :G]) + hflip @ np.abs(Wh[:, :G])   # change of the gates' pre-activations
+    d_z = flip @ np.abs(Wi[:, G:2 * G]) + hflip @ np.abs(Wh[:, G:2 * G])
+    d_n = flip @ np.abs(Wi[:, 2 * G:])
+    d_hn = hflip @ np.abs(Wh[:, 2 * G:])
+    # |sigmoid'| <= 1/4, |tanh'| <= 1; n = tanh(gi_n + r gh_n)
+    dn = d_n + 0.25 * d_r * np.abs(gh[:, 2 * G:]) + r * d_hn
+    bound = 1e-5 + 1.1 * ((1.0 - z) * dn + 0.25 * d_z * np.abs(h0 - n))
+    flip = flip + hflip
+    # (entries below 1e-4 cannot matter: a flip there moves the embedding's input by less than 4e-7)
+    _, odist = _bf16_step_and_boundary_distance(np.where(np.abs(obs) < 1e-4, 1.0, obs))
+    # a value that float32 holds exactly reaches both sides as the same number and rounds the same way
+    inexact = obs.astype(np.float32).astype(np.float64) != obs
+    obs_fragile = ((odist <= 2e-7 * np.maximum(1.0, np.abs(obs))) & inexact).any(axis=1)
+    return h1, bound, obs_fragile, (flip > 0).sum(axis=1)
+
+
 @pytest.mark.parametrize("E,N,T", [(256, 3, 12), (100, 3, 12), (64, 1, 12), (130, 2, 12), (2048, 3, 6), (100, 4, 8), (70, 5, 8)])
 def test_teacher_forced_steps(mods, E, N, T):
     say("recurrent policy, forced steps E=%d N=%d T=%d" % (E, N, T))
-    env, orc, _ = _pair(mods, E, N)
+    env, orc, w = _pair(mods, E, N)
     orc.reset(21)
     env.reset(21)
     g = np.random.Generator(np.random.PCG64(5))
     agree = total = 0
-    n_h = n_h_close = 0
-    worst_h = sum_h = 0.0
+    rows = rows_clean = rows_fragile = rows_obs_fragile = deviating = 0
+    worst_clean = worst_ratio = 0.0
     bufs = env.empty_traj(1)
     for t in range(T):
         if t == 3:      # an arbitrary carried state, not one the network produced
@@ -75,18 +135,39 @@ def test_teacher_forced_steps(mods, E, N, T):
         # carried state after the step (all rows: it does not depend on the sampled action)
         h1 = env.get_hidden().cpu().numpy().astype(np.float64)
         rh1 = orc.get_hidden()
-        d = np.abs(h1 - rh1)
-        n_h += d.size
-        n_h_close += int((d <= 1e-5).sum())
-        worst_h = max(worst_h, float(d.max()))
-        sum_h += float(d.sum())
         if rdone.all():
             assert not h1.any() and not rh1.any()
-    say("  action agreement %.5f over %d samples; carried state: %.4f within 1e-5, mean %.2e, worst %.2e"
-        % (agree / total, total, n_h_close / n_h, sum_h / n_h, worst_h))
-    assert agree / total >= 0.99
-    # each new state element sums 128 products with bf16-rounded e: a few per cent see one flipped input
-    assert n_h_close / n_h >= 0.9 and sum_h / n_h < 1e-4 and worst_h < 2e-2
+            continue
+        live = np.repeat(rdone[0] == 0, N)                        # rows whose episode goes on
+        ref, bound, obs_fragile, n_fragile = _carried_state_bound(w, robs[0].reshape(E * N, -1), h0.reshape(E * N, G))
+        np.testing.assert_allclose(ref[live], rh1.reshape(E * N, G)[live], rtol=0, atol=1e-12)   # the re-derivation is the oracle's network
+        d = np.abs(h1 - rh1).reshape(E * N, G)
+        check = live & ~obs_fragile
+        assert (d[check] <= bound[check]).all(), "carried state beyond what the fragile roundings explain: %.3e" % (
+            (d[check] / bound[check]).max())
+        clean = check & (n_fragile == 0)
+        rows += int(live.sum())
+        rows_clean += int(clean.sum())
+        rows_fragile += int((check & (n_fragile > 0)).sum())
+        rows_obs_fragile += int((live & obs_fragile).sum())
+        deviating += int((d[live].max(axis=1) > 1e-5).sum())
+        worst_clean = max(worst_clean, float(d[clean].max(initial=0.0)))
+        worst_ratio = max(worst_ratio, float((d[check] / bound[check]).max(initial=0.0)))
+        assert d[live].max() < 2e-2                              # rows with a fragile observation entry: loose bound only
+    say("  action agreement %.5f over %d samples; carried state: %d rows, %d without a fragile rounding (worst %.2e), "
+        "%d with fragile embedding outputs, %d with a fragile observation entry; %d rows deviate by more than 1e-5; "
+        "worst deviation / bound %.2f"
+        % (agree / total, total, rows, rows_clean, worst_clean, rows_fragile, rows_obs_fragile, deviating, worst_ratio))
+    Hp.record("recurrent policy E=%d N=%d: carried state of %d rows: %d clean rows within %.2e, %d rows with fragile bf16 roundings "
+              "within %.2f of their first-order bound, %d rows with a fragile observation entry; actions %.5f equal over %d"
+              % (E, N, rows, rows_clean, worst_clean, rows_fragile, worst_ratio, rows_obs_fragile, agree / total, total))
+    assert agree / total >= 0.9995
+    # Most rows are clean, few are left to the loose bound, and nothing deviates that has no fragile rounding.
+    # (Fragile roundings are common here by the nature of the workload: an embedding output near zero lies on a
+    # fine bf16 grid while the hardware tanh is accurate to ~1e-7 absolute; and without contacts the velocities
+    # are dyadic numbers of 9 or 10 bits, i.e. exact ties of the bf16 rounding, plus the ~1e-8 tail of a far
+    # contact force.)
+    assert rows_clean >= 0.6 * rows and rows_obs_fragile <= 0.1 * rows + 2 and deviating <= rows_fragile + rows_obs_fragile
     env.close()
 
 
