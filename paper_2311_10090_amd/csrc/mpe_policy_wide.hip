@@ -30,9 +30,14 @@
 // Occupancy.  At ~168 registers a SIMD holds three wavefronts, and the hardware places a block's
 // wavefronts on the four SIMDs as a unit: two 5-wavefront blocks do not fit one CU (measured:
 // one resident block per CU), a 10-wavefront block does (3 + 3 + 2 + 2).  So a block is TWO
-// independent 32-env groups of 5 wavefronts that share the staged weights, and the per-step
-// barrier is per group: an arrival counter in LDS instead of the block barrier, so that a group
-// never waits for the other one.
+// independent 32-env groups that share the staged weights, and the per-step barrier is per group:
+// an arrival counter in LDS instead of the block barrier, so that a group never waits for the other.
+//
+// Balance (10 agents).  640 rows are ten wavefronts of 64, which the four SIMDs can only hold as
+// 3 + 3 + 2 + 2: two SIMDs idle a third of the time (measured: vector and matrix units together busy
+// 83 % of the SIMD cycles).  The network is work per 16-row TILE, 40 tiles per block, so the 10-agent
+// shape runs TWELVE wavefronts instead, three per SIMD, that own 4, 3 and 3 tiles (64, 48, 48 rows;
+// the last 16 lanes of a 48-row wavefront own no row and store nothing): ten tiles on every SIMD.
 #include "mpe_policy_common.h"
 
 namespace mpe {
@@ -133,14 +138,37 @@ __global__ void pack_policy_kernel(uint8_t* __restrict__ packed, const float* __
 // observations on its way to the trajectory.
 // AC (actor-critic rollout): the critic's packed image follows the policy's, and every wavefront has a
 // second stage for the critic's outputs.
+// Envs of one sync group: the smallest count whose agent rows fill whole wavefronts.
+__host__ __device__ constexpr int sync_group_envs(int n) {
+  int g = 64;
+  while (g > 1 && (n % 2 == 0)) { g /= 2; n /= 2; }
+  return g;
+}
+
+// Rows -> wavefronts.  Plain: wavefront w owns rows 64 w .. 64 w + 63.  Balanced (10 agents, two 32-env
+// sync groups of 320 rows = 20 tiles): six wavefronts per group own 4, 4, 3, 3, 3, 3 tiles; the hardware
+// deals wavefront h of a block to SIMD h % 4 and group g gets the hardware wavefronts g, g + 2, g + 4, ...,
+// so wavefronts 0, 2, 4 of a group share one SIMD and 1, 3, 5 another: 4 + 3 + 3 tiles each.
+template <int N, int EB, bool UNIFORM>
+struct RowMap {
+  static constexpr bool kBalanced = (N == 10 && EB == 64 && !UNIFORM);
+  static constexpr int ROWS = EB * N;
+  static constexpr int GE = sync_group_envs(N);                     // envs of one sync group
+  static constexpr int GW = kBalanced ? 6 : GE * N / 64;            // wavefronts of one sync group
+  static constexpr int WAVES = kBalanced ? 12 : ROWS / 64;
+  // first row and row count of wavefront v of a group (row numbers inside the group)
+  __host__ __device__ static constexpr int first_row(int v) { return kBalanced ? (v < 2 ? 64 * v : 128 + 48 * (v - 2)) : 64 * v; }
+  __host__ __device__ static constexpr int rows_of(int v) { return kBalanced ? (v < 2 ? 64 : 48) : 64; }
+};
+
 template <int N, int H, int EB, bool UNIFORM = false, bool AC = false>
 struct Smem {
   using S = Shape<N, H>;
-  static constexpr int ROWS = EB * N, WAVES = ROWS / 64;
+  static constexpr int ROWS = EB * N, WAVES = RowMap<N, EB, UNIFORM>::WAVES;
   static constexpr size_t WEIGHTS = UNIFORM ? 0 : S::OFF_BIAS;     // W1A + W2A + W3A
   static constexpr size_t OFF_BIAS = WEIGHTS;
   static constexpr size_t OFF_CRITIC = OFF_BIAS + (UNIFORM ? 0 : S::BIAS_BYTES);   // AC: W1A, W2A, W3A, biases of the critic
-  static constexpr size_t STAGE_WAVE = UNIFORM ? size_t(16) * S::D * 4 : size_t(AC ? 2 : 1) * 64 * 5 * 4;   // else the wave's logits [64][5] (AC: + values)
+  static constexpr size_t STAGE_WAVE = UNIFORM ? size_t(16) * S::D * 4 : size_t(64) * 5 * 4;   // else the wave's logits [64][5] (AC: first the values)
   static constexpr size_t OFF_STAGE = OFF_CRITIC + (AC ? S::RUN_BYTES : 0);
   static constexpr size_t OFF_NEWPOS = OFF_STAGE + WAVES * STAGE_WAVE;   // [2][ROWS] float2, by step parity
   static constexpr size_t OFF_DMIN = OFF_NEWPOS + size_t(2) * ROWS * 8;  // [2][ROWS] float,  by step parity
@@ -167,13 +195,6 @@ __device__ __forceinline__ bf16x8 tanh_pack(const f32x4& a0, const f32x4& a1) {
   p[2] = pack_bf16(fast_tanh(a1[0]), fast_tanh(a1[1]));
   p[3] = pack_bf16(fast_tanh(a1[2]), fast_tanh(a1[3]));
   return __builtin_bit_cast(bf16x8, p);
-}
-
-// Envs of one sync group: the smallest count whose agent rows fill whole wavefronts.
-__host__ __device__ constexpr int sync_group_envs(int n) {
-  int g = 64;
-  while (g > 1 && (n % 2 == 0)) { g /= 2; n /= 2; }
-  return g;
 }
 
 #define MPE_MFMA_BF(A, B, C) __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, B, C, 0, 0, 0)
@@ -257,16 +278,17 @@ __device__ __forceinline__ void policy_tile(const uint8_t* __restrict__ wsm, con
 // AC: a critic of the same shape with one output (`packed_critic`) is evaluated on every observation
 // acted on; its value and the log-probability of the sampled action are recorded (paper Sec. 3.2: IPPO).
 template <int N, int H, int EB, int MINW, bool PER_AGENT, bool UNIFORM, bool AC = false>
-__global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
+__global__ __launch_bounds__((RowMap<N, EB, UNIFORM>::WAVES * 64), MINW) void rollout_policy_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
                                                                       const uint8_t* __restrict__ packed_critic,
                                                                       int per_run_weights, uint32_t groups,
                                                                       uint32_t groups_per_xcd) {
   using S = Shape<N, H>;
   using M = Smem<N, H, EB, UNIFORM, AC>;
-  constexpr int D = S::D, KIN = S::KIN, ROWS = EB * N, THREADS = ROWS;
+  using RM = RowMap<N, EB, UNIFORM>;
+  constexpr int D = S::D, KIN = S::KIN, ROWS = EB * N, THREADS = RM::WAVES * 64;
   constexpr int RF4 = D / 4;                 // 16-byte chunks of one observation row
   constexpr int PD = S::S1 * 16;             // dwords of one row as bf16 pairs, zero padded to whole K slices
-  constexpr int GE = sync_group_envs(N), GW = GE * N / 64;   // envs / wavefronts of one sync group
+  constexpr int GE = RM::GE, GW = RM::GW;                    // envs / wavefronts of one sync group
   static_assert(EB % GE == 0 && EB / GE <= 4, "a block is whole sync groups");
   static_assert(D % 2 == 0 && KIN % 2 == 0,
                 "rows are stored as 16-byte chunks (8-byte with an odd agent count) and packed as bf16 pairs");
@@ -286,7 +308,11 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
   const int hw_wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
   constexpr int kGroups = EB / GE;
   const int wave = kGroups > 1 ? (hw_wave % kGroups) * GW + hw_wave / kGroups : hw_wave;
-  const int tid = wave * 64 + lane;
+  const int wv = wave % GW;                          // wavefront inside its sync group
+  const int wave_first = (wave / GW) * (GE * N) + RM::first_row(wv);   // its first row inside the block
+  const int wave_count = RM::rows_of(wv);            // rows it owns: 64, or 48 (three tiles) in the balanced map
+  const bool active = !RM::kBalanced || lane < wave_count;   // false for the 16 spare lanes of a 48-row wavefront:
+  const int tid = wave_first + (active ? lane : 0);           // they shadow the wavefront's first row and store nothing
   const int el = tid / N, i = tid - el * N;          // env within block, agent
   float* stage = reinterpret_cast<float*>(smem + M::OFF_STAGE + size_t(wave) * M::STAGE_WAVE);
   uint32_t* arrived = reinterpret_cast<uint32_t*>(smem + M::OFF_ARRIVED) + wave / GW;
@@ -297,13 +323,13 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
   if (grp >= groups) return;  // whole block, before any barrier
   const size_t g0 = size_t(grp) * EB;
   const size_t g = g0 + el;
-  const bool valid = g < TE;
+  const bool valid = active && g < TE;
   const uint32_t gc = valid ? uint32_t(g) : uint32_t(g0);
   const uint32_t run = gc / A.E;
   const uint32_t env = gc - run * A.E;
   const size_t left = TE - g0;
   const int nvalid = left < size_t(EB) ? int(left) : EB;   // valid envs in this block
-  const int wave_rows = min(max(nvalid * N - wave * 64, 0), 64);   // rows of this wavefront that belong to valid envs
+  const int wave_rows = min(max(nvalid * N - wave_first, 0), wave_count);   // rows of this wavefront that belong to valid envs
 
   // ---- stage this block's weights (the run of its first env) in LDS: the packed buffer is
   // W1A, W2A, W3A, biases in that order, and so is the LDS image
@@ -311,12 +337,12 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
     const uint8_t* run_weights = packed + (per_run_weights ? size_t(uint32_t(g0) / A.E) * S::RUN_BYTES : 0);
     const uint4* src = reinterpret_cast<const uint4*>(run_weights);
     uint4* dst = reinterpret_cast<uint4*>(wsm);
-    for (int k = tid; k < int(S::RUN_BYTES / 16); k += THREADS) dst[k] = src[k];
+    for (int k = threadIdx.x; k < int(S::RUN_BYTES / 16); k += THREADS) dst[k] = src[k];
     if constexpr (AC) {
       const uint4* csrc = reinterpret_cast<const uint4*>(
           packed_critic + (per_run_weights ? size_t(uint32_t(g0) / A.E) * S::RUN_BYTES : 0));
       uint4* cdst = reinterpret_cast<uint4*>(smem + M::OFF_CRITIC);
-      for (int k = tid; k < int(S::RUN_BYTES / 16); k += THREADS) cdst[k] = csrc[k];
+      for (int k = threadIdx.x; k < int(S::RUN_BYTES / 16); k += THREADS) cdst[k] = csrc[k];
     }
   }
 
@@ -328,7 +354,7 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
   // `respos` when the env has just been reset (or at the start of the call).
   float px = 0.0f, py = 0.0f, vx = 0.0f, vy = 0.0f, mylx = 0.0f, myly = 0.0f;
   int32_t ep = 0;
-  if (valid) {
+  if (g < TE) {   // (a spare lane loads the row it shadows)
     px = A.st.pos_a[(0 * N + i) * TE + g];
     py = A.st.pos_a[(1 * N + i) * TE + g];
     mylx = A.st.pos_l[(0 * N + i) * TE + g];
@@ -337,10 +363,12 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
     vy = A.st.vel_a[(1 * N + i) * TE + g];
     ep = A.st.ep_step[g];
   }
-  respos[tid] = make_float2(px, py);
+  if (active) {
+    respos[tid] = make_float2(px, py);
+    lmbuf[tid] = make_float2(mylx, myly);   // tid = el * N + i
+  }
   const float2* cur = respos + el * N;
-  lmbuf[tid] = make_float2(mylx, myly);   // tid = el * N + i
-  if (tid < EB / GE) reinterpret_cast<uint32_t*>(smem + M::OFF_ARRIVED)[tid] = 0u;
+  if (threadIdx.x < EB / GE) reinterpret_cast<uint32_t*>(smem + M::OFF_ARRIVED)[threadIdx.x] = 0u;
   __syncthreads();  // weights, biases, landmarks and counters staged; the only block-wide barrier
 
   // The lane's observation: its KIN leading entries (the trailing communication slots are zeros).
@@ -440,11 +468,10 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
   };
   [[maybe_unused]] const uint8_t* csm = smem + M::OFF_CRITIC;                                        // AC only
   [[maybe_unused]] const float* cbias = reinterpret_cast<const float*>(smem + M::OFF_CRITIC + S::OFF_BIAS);
-  [[maybe_unused]] float* vstage = stage + 64 * 5;                                                   // AC: the critic's outputs
   [[maybe_unused]] float* logp_base = A.logp_traj;
   [[maybe_unused]] float* value_base = A.value_traj;
 
-  const size_t wave_row0 = (g0 * N + size_t(wave) * 64) * D;   // float offset of this wavefront's rows in a slice
+  const size_t wave_row0 = (g0 * N + size_t(wave_first)) * D;  // float offset of this wavefront's rows in a slice
   float* obs_p = A.obs_traj ? A.obs_traj + wave_row0 : nullptr;
   uint8_t* act_base = A.act_traj;
   float* rew_base = A.rew_traj;
@@ -492,12 +519,19 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
     }
     // ---- policy: four 16-row tiles per wavefront
     if constexpr (!UNIFORM) {
+      // (a 48-row wavefront has three tiles: the branch is uniform over the wavefront)
+      [[maybe_unused]] float value = 0.0f;
+      if constexpr (AC) {   // the critic first, through the same stage: its one output is column 0
 #pragma unroll
-      for (int c = 0; c < 4; ++c) policy_tile<N, H>(wsm, bias, b1[c], stage + c * 16 * 5, lane);
-      if constexpr (AC) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) policy_tile<N, H>(csm, cbias, b1[c], vstage + c * 16 * 5, lane);
+        for (int c = 0; c < 4; ++c)
+          if (c < 3 || wave_count == 64) policy_tile<N, H>(csm, cbias, b1[c], stage + c * 16 * 5, lane);
+        wave_sync();
+        value = stage[lane * 5];
+        wave_sync();
       }
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        if (c < 3 || wave_count == 64) policy_tile<N, H>(wsm, bias, b1[c], stage + c * 16 * 5, lane);
       wave_sync();
       float z[kNumActions];
 #pragma unroll
@@ -519,7 +553,7 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
           logp_base += TE * N;
         }
         if (value_base) {
-          if (valid) value_base[row_off] = vstage[lane * 5];
+          if (valid) value_base[row_off] = value;
           value_base += TE * N;
         }
         wave_sync();   // the stages are rewritten by the next step's tiles
@@ -548,7 +582,7 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
     vx = fmaf(fx, A.ph.dt_over_mass, vx * A.ph.keep);
     vy = fmaf(fy, A.ph.dt_over_mass, vy * A.ph.keep);
     float2* np = newpos + (t & 1) * ROWS;
-    np[tid] = make_float2(px, py);
+    if (active) np[tid] = make_float2(px, py);
     // (C) new positions of this step and coverage distances of the previous one are visible
     group_barrier(arrived, uint32_t(GW) * uint32_t(t + 1), lane, A.fault);
 
@@ -580,7 +614,7 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
         const float dx = qx[a] - mylx, dy = qy[a] - myly;
         best2 = fminf(best2, fmaf(dx, dx, dy * dy));
       }
-      dminbuf[(t & 1) * ROWS + tid] = hw_sqrt(best2);
+      if (active) dminbuf[(t & 1) * ROWS + tid] = hw_sqrt(best2);
     }
     ep += 1;
     const bool done = ep >= A.ph.max_ep;
@@ -601,10 +635,10 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
       for (int a = 0; a < N; ++a) {
         const uint4 w = philox4x32_10(env_r, step + 1u, uint32_t(a), kTagResetPos, A.seed, run);
         const float2 p = make_float2(word_to_position(w.x), word_to_position(w.y));
-        respos[el * N + a] = p;
+        if (active) respos[el * N + a] = p;
         const uint4 wl = philox4x32_10(env_r, step + 1u, uint32_t(N + a), kTagResetPos, A.seed, run);
         const float2 lm = make_float2(word_to_position(wl.x), word_to_position(wl.y));
-        lmbuf[el * N + a] = lm;
+        if (active) lmbuf[el * N + a] = lm;
         if (a == i) { px = p.x; py = p.y; mylx = lm.x; myly = lm.y; }
       }
       cur = respos + el * N;
@@ -626,9 +660,10 @@ __global__ __launch_bounds__(EB * N, MINW) void rollout_policy_kernel(RolloutArg
       bf16x8 b1[4][S::S1];
       pack_operands(o, b1);
 #pragma unroll
-      for (int c = 0; c < 4; ++c) policy_tile<N, H>(csm, cbias, b1[c], vstage + c * 16 * 5, lane);
+      for (int c = 0; c < 4; ++c)
+        if (c < 3 || wave_count == 64) policy_tile<N, H>(csm, cbias, b1[c], stage + c * 16 * 5, lane);
       wave_sync();
-      if (valid) A.last_value[row_off] = vstage[lane * 5];
+      if (valid) A.last_value[row_off] = stage[lane * 5];
     }
   }
 
@@ -664,7 +699,7 @@ hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream
   if (hipError_t e = allow_lds(reinterpret_cast<const void*>(kern), M::TOTAL, lds_allowed); e != hipSuccess) return e;
   const uint32_t groups = (A.TE + EB - 1) / EB;
   const uint32_t per_xcd = (groups + 7) / 8;
-  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(EB * N), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),
+  hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(RowMap<N, EB, UNIFORM>::WAVES * 64), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),
                      static_cast<const uint8_t*>(critic), int(A.TE != A.E), groups, per_xcd);
   return hipGetLastError();
 }
