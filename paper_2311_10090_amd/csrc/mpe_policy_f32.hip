@@ -102,8 +102,8 @@ __global__ __launch_bounds__((EB * N + RW - 1) / RW * 64, MINW) void rollout_pol
   // the hardware wavefronts g, g + G, g + 2G (G = EB / 64 groups): the hardware deals the wavefronts
   // of a block to the four SIMDs in turn, so with G = 4 a group's wavefronts share ONE SIMD, and a
   // wavefront waiting at the group's per-step barrier yields its issue slots to the very wavefronts
-  // it is waiting for (measured: 2.30 -> 2.06 ms per rollout, the time of the same kernel with the barrier
-  // taken out; with the wavefronts of a group on three different SIMDs the barrier cost 12 %).
+  // it is waiting for (measured at 65,536 envs x 128 steps: 2.06 ms per rollout against 2.30 ms with the
+  // wavefronts of a group dealt to three different SIMDs).
   // `wave` and `tid` below are these virtual indices: row = tid.
   const int lane = threadIdx.x & 63;
   const int hw_wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
