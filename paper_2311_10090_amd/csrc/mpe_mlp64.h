@@ -1,6 +1,6 @@
 // The 64-wide two-layer tanh MLP of the fused rollout kernels on the 16-bit matrix cores: packing of
 // the weights into A-operand order, the three-term operand split that gives fp32 products,
-// and the forward pass of two 16-row tiles (fp32-exact and bf16 variants).  Shared by the kernels
+// and the forward pass of two 16-row tiles (fp32 split-operand and bf16 variants).  Shared by the kernels
 // of both scenarios; everything is templated on a shape S:
 //   S::D         floats per observation row in the LDS tile (row stride)
 //   S::KIN       leading inputs of a row that the first layer reads (<= 16; the rest of the row is

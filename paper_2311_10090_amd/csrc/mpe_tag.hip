@@ -1,6 +1,6 @@
 // Predator-prey ("simple tag") scenario of the MPE family (paper App. B.7: every scenario of the
 // family is implemented; Sec. 3.1 "MPE"): reset, single step, and the persistent T-step rollout
-// with uniform actions or with the fused policy, fp32-exact or bf16 (App. G: two tanh layers of width 64).
+// with uniform actions or with the fused policy, fp32 (three-term fp16 operand split) or bf16 (App. G: two tanh layers of width 64).
 //
 // Mapping: one lane per agent row, a block is 64 envs = N wavefronts (as in the fused simple-spread
 // kernel).  A lane keeps its own agent's position and velocity, the positions of all agents of its
@@ -23,7 +23,7 @@ struct TagShape {
   static_assert(G_ >= 1 && A >= 1 && L_ >= 0 && D % 2 == 0, "roles");
 };
 
-// kPolicy / kPolicyBf: fp32-exact / bf16 policy.  kPolicyAc: fp32-exact policy plus a critic of the same
+// kPolicy / kPolicyBf: fp32 (split-operand) / bf16 policy.  kPolicyAc: fp32 policy plus a critic of the same
 // shape with one output: log-probability of the sampled action and value per agent and step.
 enum TagMode : int { kGiven = 0, kUniform = 1, kPolicy = 2, kPolicyBf = 3, kPolicyAc = 4 };
 
