@@ -13,7 +13,7 @@
 // its 24 GRU A-operands (r, z, n gates x input/recurrent x 4 K slices) and its embedding operand
 // in registers for the whole rollout (100 of its 256 registers); the small layers' operands
 // (second fully-connected layer, logits) sit in LDS.  Activations of all rows go through LDS as
-// bf16 rows of 128 (+ 16 bytes of padding per row) in which the rows 8..15 of every 16-row tile hold
+// bf16 rows of 128 (+ 16 bytes of padding per row) in which the rows 4..11 of every 16-row tile hold
 // each pair of neighbouring 16-byte pieces swapped (act_piece below): padding and swap together make
 // the 16-byte operand reads free of bank conflicts.  Every wavefront reads all K of a row tile
 // and writes its own 16 units.  The
@@ -33,18 +33,30 @@ namespace {
 constexpr int kG = 128;    // hidden width of every layer
 constexpr int kAS = 272;   // bytes per activation row in LDS: 128 bf16 + 16 bytes of padding
 
-// Where the 16-byte piece w (= units 8w .. 8w + 7) of row j of a 16-row tile sits inside the row: piece
-// w for rows 0..7, piece w ^ 1 for rows 8..15.  Measured on this chip (bank-conflict counter on stand-alone
-// access patterns): a 16-byte LDS read is served in four passes of 16 lanes over 64 banks, and a pass is
-// lanes 0-7 + 24-31, 8-15 + 16-23, 32-39 + 56-63 or 40-47 + 48-55.  With lane (j, gq) reading piece 4 s + gq
-// of row j, a pass holds rows 0..7 at one gq and rows 8..15 at gq ^ 1; with rows 68 dwords apart the first
-// eight start at banks 4 j + 4 gq, the other eight, unswapped, at 4 j + 4 (gq ^ 1): row 15 meets row 0 (one
-// extra pass on EVERY read, which is what the padding alone cost).  The swap puts both halves at the same gq
-// parity: 16 different pieces, no conflict (an exhaustive search over per-row swaps inside a K slice finds
-// this one and its mirror images only; wider swizzles cost address registers, which this kernel spills).
-// 8-byte writes are served over 32 banks in passes of 16 consecutive lanes: the 16 rows of a pass share 8
-// bank pairs, one extra cycle per pass, with or without the swap.
-__device__ __forceinline__ int act_piece(int w, int row_in_tile) { return w ^ (row_in_tile >> 3); }
+// LDS access rules of this chip, read off the bank-conflict counter (SQ_LDS_BANK_CONFLICT) on stand-alone
+// access patterns, two active lanes at a time:
+//   16-byte read:  64 banks of 4 bytes; four passes of 16 lanes: {0-3, 12-15, 20-27}, {4-11, 16-19, 28-31}
+//                  and the same two sets + 32;
+//   16-byte write: 32 banks; eight passes of 8 consecutive lanes;
+//   8-byte write:  32 banks; four passes of 16 consecutive lanes;
+//   4-byte read:   32 banks; two passes of 32 consecutive lanes.
+// A k-way conflict inside a pass costs k - 1 extra cycles.
+//
+// Where the 16-byte piece w (= units 8w .. 8w + 7) of row j of a 16-row tile sits inside the row: piece w
+// for rows 0..3 and 12..15, piece w ^ 1 for rows 4..11.  Lane (j, gq) reads piece 4 s + gq of row j, so a
+// read pass holds rows {0-3, 12-15} at one gq and rows 4..11 at gq ^ 1; with rows 17 pieces apart, piece
+// index j + gq (mod 16) would meet twice in every pass (one extra cycle per pass, four per read: what the
+// padding alone costs); the swap turns the pass into 16 different pieces.  An exhaustive search over per-row
+// XOR masks inside a K slice finds 8 such layouts at this row stride; masks that reach across slices cost
+// address registers, which this kernel spills.  The 8-byte writes of a pass are the same 8 bytes of 16
+// different rows: with 16-byte-aligned rows they share 8 bank pairs, one extra cycle per pass, whatever
+// the layout.
+__device__ __forceinline__ int act_piece(int w, int row_in_tile) { return w ^ (((row_in_tile + 4) >> 3) & 1); }
+
+// The observation tile: bf16 rows of 32 columns = four 16-byte pieces, 64 bytes apart, piece q of row
+// `row` at position q ^ ((row >> 1) & 3): free of conflicts both for the embedding's 16-byte reads (lane
+// (j, gq) reads piece gq of row 16 rt + j) and for the agent lanes' 16-byte writes (lane = row).
+__device__ __forceinline__ int obs_piece(int q, int row) { return q ^ ((row >> 1) & 3); }
 
 // Packed weight image (bytes).  A operands of v_mfma_f32_16x16x32_bf16: lane (i = lane % 16,
 // gq = lane / 16) holds weights [k = 32 s + 8 gq + e][out = 16 u + i], e = 0..7.
@@ -134,11 +146,12 @@ template <int N, int EB = 64>
 struct GruSmem {
   static constexpr int B = EB * N, D = 6 * N, NT = B / 16;      // rows, obs width, 16-row tiles
   static_assert(B % 16 == 0 && EB <= 64, "whole row tiles");
-  // bf16 observation tile, 32 columns per row (zero beyond D) + 16 bytes of padding; after the
-  // embedding it is dead, and the logits [B][8] of the same step are stored in its place
-  static constexpr int OS = 80;
+  // bf16 observation tile, 32 columns per row (zero beyond D); after the embedding it is dead, and the
+  // logits of the same step, [5][B] floats (action-major: the agent lanes read consecutive words), are
+  // stored in its place
+  static constexpr int OS = 64;
   static constexpr size_t OBS_BYTES = size_t(B) * OS;
-  static constexpr size_t LOGIT_BYTES = size_t(B) * 8 * 4;
+  static constexpr size_t LOGIT_BYTES = size_t(B) * kNumActions * 4;
   static constexpr size_t OFF_OBS = 0;
   static constexpr size_t OFF_X = up16(OBS_BYTES > LOGIT_BYTES ? OBS_BYTES : LOGIT_BYTES);   // e, later y
   static constexpr size_t OFF_HB = OFF_X + size_t(B) * kAS;                                  // bf16 copy of h
@@ -286,7 +299,7 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
       u32x4 v;
 #pragma unroll
       for (int e = 0; e < 4; ++e) v[e] = pack_bf16_rne(o[8 * q + 2 * e], o[8 * q + 2 * e + 1]);
-      row[q] = v;
+      row[obs_piece(q, tid)] = v;
     }
     if (dst && valid) {
 #pragma unroll
@@ -319,7 +332,7 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
     for (int rt = 0; rt < NT; ++rt) {
       const int row = 16 * rt + j;
       f32x4 acc = *reinterpret_cast<const f32x4*>(bias + 16 * u + 4 * gq);
-      acc = MPE_MFMA_BF(we, *reinterpret_cast<const bf16x8*>(otile + row * M::OS + 16 * gq), acc);
+      acc = MPE_MFMA_BF(we, *reinterpret_cast<const bf16x8*>(otile + row * M::OS + 16 * obs_piece(gq, j)), acc);
       *reinterpret_cast<uint2*>(xbuf + rt * kTile + wr_off) =
           pack4_bf16(fast_tanh(acc[0]), fast_tanh(acc[1]), fast_tanh(acc[2]), fast_tanh(acc[3]));
     }
@@ -387,8 +400,12 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
 #pragma unroll
       for (int s = 0; s < 4; ++s)
         acc = MPE_MFMA_BF(outw[s * 64 + lane], *reinterpret_cast<const bf16x8*>(xbuf + rt * kTile + 64 * s + rd_off), acc);
-      if (gq == 0) *reinterpret_cast<f32x4*>(logits + row * 8) = acc;       // outputs 0..3
-      else if (gq == 1) logits[row * 8 + 4] = acc[0];                       // output 4
+      if (gq == 0) {                                                        // outputs 0..3
+#pragma unroll
+        for (int r = 0; r < 4; ++r) logits[r * B + row] = acc[r];
+      } else if (gq == 1) {
+        logits[4 * B + row] = acc[0];                                       // output 4
+      }
     }
     __syncthreads();   // L complete
 
@@ -396,7 +413,7 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
     if (agent) {
       float z[kNumActions];
 #pragma unroll
-      for (int k = 0; k < kNumActions; ++k) z[k] = logits[tid * 8 + k];
+      for (int k = 0; k < kNumActions; ++k) z[k] = logits[k * B + tid];
       const uint32_t act = gumbel_argmax(z, A.seed, run, env, step, uint32_t(i));
       if (act_base && valid) act_base[row_off] = uint8_t(act);
       float fx = A.ph.accel * action_dir_x(act);
