@@ -199,8 +199,9 @@ int mpe_rollout(mpe_env* env, int32_t T, float* obs_traj, uint8_t* act_traj, flo
  * wherever an episode ends inside mpe_rollout, carried across mpe_rollout calls, untouched by
  * mpe_set_state and by mpe_step (which takes its actions from the caller and neither advances nor
  * clears h: a caller that mixes the two sets h itself with mpe_set_hidden).
- * Built for MPE_SCENARIO_SPREAD, 1..5 agents, hidden 128, MPE_WEIGHTS_BF16; MPE_EINVAL otherwise or if
- * only some pointers are NULL.  With several runs mpe_rollout needs num_envs to be a multiple of 16. */
+ * Built for hidden 128 and MPE_WEIGHTS_BF16: MPE_SCENARIO_SPREAD with 1..10 agents and every
+ * MPE_SCENARIO_TAG shape mpe_create accepts (D = the scenario's observation length, at most 64);
+ * MPE_EINVAL otherwise or if only some pointers are NULL.  With several runs mpe_rollout needs num_envs to be a multiple of 16. */
 int mpe_set_gru_policy(mpe_env* env, const float* We, const float* be, const float* Wi, const float* bi,
                        const float* Wh, const float* bh, const float* Wf, const float* bf, const float* Wo,
                        const float* bo, void* stream);

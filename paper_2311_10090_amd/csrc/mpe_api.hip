@@ -329,8 +329,13 @@ int mpe_rollout(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, float
     return fail(MPE_EINVAL, "mpe_rollout: absolute step counter would overflow 32 bits");
   const RolloutArgs A = rollout_args(e, T, obs_traj, act_traj, rew_traj, done_traj, last_obs);
   if (e->has_gru) {
+    TagArgs TA{};
+    TA.r = A;
+    TA.tg = e->tg;
+    TA.actions_in = nullptr;
     const char* why = nullptr;
-    hipError_t err = launch_rollout_gru(e->N, A, e->gru, e->hidden, static_cast<hipStream_t>(stream), &why);
+    hipError_t err = launch_rollout_gru(e->tag, e->N, e->L, e->G, TA, e->gru, e->hidden,
+                                        static_cast<hipStream_t>(stream), &why);
     if (why) return fail(MPE_EINVAL, "mpe_rollout: %s", why);
     if (err != hipSuccess) return fail(MPE_EHIP, "mpe_rollout: %s", hipGetErrorString(err));
   } else if (e->tag) {
@@ -369,9 +374,9 @@ int mpe_set_gru_policy(mpe_env* e, const float* We, const float* be, const float
     return MPE_OK;
   }
   if (given != 10) return fail(MPE_EINVAL, "mpe_set_gru_policy: pass all ten arrays or none");
-  if (e->tag || !gru_supported(e->N, e->H, e->cfg.weight_dtype))
-    return fail(MPE_EINVAL, "mpe_set_gru_policy: the recurrent policy is built for MPE_SCENARIO_SPREAD with 1..5 "
-                            "agents, hidden 128 and MPE_WEIGHTS_BF16");
+  if (!gru_supported(e->tag, e->N, e->L, e->G, e->H, e->cfg.weight_dtype))
+    return fail(MPE_EINVAL, "mpe_set_gru_policy: the recurrent policy needs hidden 128 and MPE_WEIGHTS_BF16 (simple "
+                            "spread: 1..10 agents; predator-prey: every shape mpe_create accepts)");
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (!e->hidden) {
     const size_t n = size_t(e->TE) * e->N * 128;
@@ -382,7 +387,7 @@ int mpe_set_gru_policy(mpe_env* e, const float* We, const float* be, const float
   // until the new image is packed the handle has no recurrent policy: a failure below must not leave an
   // earlier one installed on a partly rewritten buffer
   e->has_gru = false;
-  hipError_t err = pack_policy_gru(e->gru, e->N, int(e->R), We, be, Wi, bi, Wh, bh, Wf, bf, Wo, bo, s);
+  hipError_t err = pack_policy_gru(e->gru, e->D, int(e->R), We, be, Wi, bi, Wh, bh, Wf, bf, Wo, bo, s);
   if (err != hipSuccess) return fail(MPE_EHIP, "mpe_set_gru_policy: %s", hipGetErrorString(err));
   e->has_gru = true;
   return MPE_OK;

@@ -139,13 +139,16 @@ hipError_t launch_rollout_policy_f32(int N, bool bf16, const RolloutArgs& A, con
 hipError_t ensure_policy_bytes(PolicyBuffers& pb, size_t bytes);
 
 // Recurrent policy (hidden 128, bf16): simple spread with 1..3 agents.
-bool gru_supported(int N, int H, int weight_dtype);
-hipError_t pack_policy_gru(PolicyBuffers& pb, int N, int R, const float* We, const float* be, const float* Wi,
+// tag: the predator-prey scenario with (N, L, G) agents, landmarks, good agents; otherwise simple spread (L, G unused)
+bool gru_supported(bool tag, int N, int L, int G, int H, int weight_dtype);
+// D = observation width of the scenario
+hipError_t pack_policy_gru(PolicyBuffers& pb, int D, int R, const float* We, const float* be, const float* Wi,
                            const float* bi, const float* Wh, const float* bh, const float* Wf, const float* bf,
                            const float* Wo, const float* bo, hipStream_t s);
-// hidden: [TE][N][128] fp32, read at the start and written at the end of the rollout
-hipError_t launch_rollout_gru(int N, const RolloutArgs& A, const PolicyBuffers& pb, float* hidden, hipStream_t s,
-                              const char** why);
+// hidden: [TE][N][128] fp32, read at the start and written at the end of the rollout; A.tg is read by the
+// predator-prey shapes only
+hipError_t launch_rollout_gru(bool tag, int N, int L, int G, const TagArgs& A, const PolicyBuffers& pb, float* hidden,
+                              hipStream_t s, const char** why);
 void launch_fill_zero(float* p, size_t n, hipStream_t s);
 
 }  // namespace mpe

@@ -24,7 +24,12 @@
 // (the agent lanes store their fp32 observation rows straight to the trajectory and leave a bf16
 // copy in LDS for the embedding).
 // The first 64 N threads are also the agents (one lane per agent row) for the environment part.
+// The kernel is a template over the scenario of the family (App. B.7): simple spread with 1..10 agents or a
+// predator-prey shape; the network phases see only rows, the two agent phases hold the scenario's own
+// transition, rewards, reset and observation.  Observations wider than 32 entries (6 and more agents of
+// simple spread) enter the embedding as two K slices.
 #include "mpe_mlp64.h"
+#include "mpe_tag_device.h"
 
 namespace mpe {
 
@@ -56,24 +61,43 @@ __device__ __forceinline__ int act_piece(int w, int row_in_tile) { return w ^ ((
 // The observation tile: bf16 rows of 32 columns = four 16-byte pieces, 64 bytes apart, piece q of row
 // `row` at position q ^ ((row >> 1) & 3): free of conflicts both for the embedding's 16-byte reads (lane
 // (j, gq) reads piece gq of row 16 rt + j) and for the agent lanes' 16-byte writes (lane = row).
-__device__ __forceinline__ int obs_piece(int q, int row) { return q ^ ((row >> 1) & 3); }
+// With two K slices per row (observations of 33..64 entries) rows are 160 bytes apart and piece q = 4 s + p
+// sits at 4 s + (p ^ ((row >> 2) & 1)): again free of conflicts for both access kinds.
+template <int KS>
+__device__ __forceinline__ int obs_piece(int q, int row) {
+  return KS == 1 ? (q ^ ((row >> 1) & 3)) : (q ^ ((row >> 2) & 1));
+}
+
+// The scenario a kernel instance runs: agents N, observation width D, landmarks L.
+template <int N_>
+struct GruSpread {
+  static constexpr int N = N_, D = 6 * N_, L = N_;
+  static constexpr bool kTag = false;
+  using Shape = TagShape<2, 1, 1>;   // unused
+};
+template <int N_, int L_, int G_>
+struct GruTag {
+  using Shape = TagShape<N_, L_, G_>;
+  static constexpr int N = N_, D = Shape::D, L = L_;
+  static constexpr bool kTag = true;
+};
 
 // Packed weight image (bytes).  A operands of v_mfma_f32_16x16x32_bf16: lane (i = lane % 16,
 // gq = lane / 16) holds weights [k = 32 s + 8 gq + e][out = 16 u + i], e = 0..7.
 struct GruPk {
-  static constexpr size_t OFF_EMB = 0;                         // [u 8][lane 64]  (K = 32 >= obs width)
-  static constexpr size_t OFF_GRU = OFF_EMB + 8 * 1024;        // [u 8][gate 3][src 2][s 4][lane 64]
+  static constexpr size_t OFF_EMB = 0;                         // [u 8][s 2][lane 64]  (K = 64 >= obs width)
+  static constexpr size_t OFF_GRU = OFF_EMB + 16 * 1024;       // [u 8][gate 3][src 2][s 4][lane 64]
   static constexpr size_t OFF_FC = OFF_GRU + 8 * 24 * 1024;    // [u 8][s 4][lane 64]
   static constexpr size_t OFF_OUT = OFF_FC + 32 * 1024;        // [s 4][lane 64]  (5 outputs padded to 16)
   static constexpr size_t OFF_BIAS = OFF_OUT + 4 * 1024;       // fp32: be, bi_r + bh_r, bi_z + bh_z, bi_n, bh_n, bf [128 each], bo [16]
   static constexpr int BIAS_FLOATS = 6 * kG + 16;
   static constexpr size_t BYTES = OFF_BIAS + size_t(BIAS_FLOATS) * 4;   // one run; runs follow each other
   static_assert(BYTES % 16 == 0, "images of consecutive runs stay 16-byte aligned");
-  static constexpr int N_EMB = 8 * 64 * 8, N_GRU = 8 * 24 * 64 * 8, N_FC = 8 * 4 * 64 * 8, N_OUT = 4 * 64 * 8;
+  static constexpr int N_EMB = 8 * 2 * 64 * 8, N_GRU = 8 * 24 * 64 * 8, N_FC = 8 * 4 * 64 * 8, N_OUT = 4 * 64 * 8;
   static constexpr int THREADS = N_EMB + N_GRU + N_FC + N_OUT + BIAS_FLOATS;
 };
 
-// One thread per packed bf16 weight or fp32 bias of one run (blockIdx.y).  D = observation width (<= 32).
+// One thread per packed bf16 weight or fp32 bias of one run (blockIdx.y).  D = observation width (<= 64).
 __global__ void pack_gru_kernel(uint8_t* __restrict__ out, int D, const float* __restrict__ We,
                                 const float* __restrict__ be, const float* __restrict__ Wi,
                                 const float* __restrict__ bi, const float* __restrict__ Wh,
@@ -94,8 +118,8 @@ __global__ void pack_gru_kernel(uint8_t* __restrict__ out, int D, const float* _
   bo += run * kNumActions;
   int idx = blockIdx.x * blockDim.x + threadIdx.x;
   if (idx < GruPk::N_EMB) {
-    const int e = idx % 8, lane = (idx / 8) % 64, u = idx / 512;
-    const int k = 8 * (lane / 16) + e, o = 16 * u + lane % 16;
+    const int e = idx % 8, lane = (idx / 8) % 64, sl = (idx / 512) % 2, u = idx / 1024;
+    const int k = 32 * sl + 8 * (lane / 16) + e, o = 16 * u + lane % 16;
     reinterpret_cast<uint16_t*>(out + GruPk::OFF_EMB)[idx] = f32_to_bf16_rne(k < D ? We[size_t(k) * kG + o] : 0.0f);
     return;
   }
@@ -142,14 +166,16 @@ __global__ void pack_gru_kernel(uint8_t* __restrict__ out, int D, const float* _
 
 constexpr size_t up16(size_t x) { return (x + 15) & ~size_t(15); }
 
-template <int N, int EB = 64>
+template <typename Scn, int EB = 64>
 struct GruSmem {
-  static constexpr int B = EB * N, D = 6 * N, NT = B / 16;      // rows, obs width, 16-row tiles
-  static_assert(B % 16 == 0 && EB <= 64, "whole row tiles");
-  // bf16 observation tile, 32 columns per row (zero beyond D); after the embedding it is dead, and the
+  static constexpr int N = Scn::N;
+  static constexpr int B = EB * N, D = Scn::D, NT = B / 16;     // rows, obs width, 16-row tiles
+  static constexpr int KS = D <= 32 ? 1 : 2;                    // K slices of the embedding
+  static_assert(B % 16 == 0 && EB <= 64 && D <= 64 && D % 2 == 0, "whole row tiles; at most two K slices");
+  // bf16 observation tile, 32 KS columns per row (zero beyond D); after the embedding it is dead, and the
   // logits of the same step, [5][B] floats (action-major: the agent lanes read consecutive words), are
   // stored in its place
-  static constexpr int OS = 64;
+  static constexpr int OS = KS == 1 ? 64 : 160;
   static constexpr size_t OBS_BYTES = size_t(B) * OS;
   static constexpr size_t LOGIT_BYTES = size_t(B) * kNumActions * 4;
   static constexpr size_t OFF_OBS = 0;
@@ -158,8 +184,9 @@ struct GruSmem {
   static constexpr size_t OFF_FCW = OFF_HB + size_t(B) * kAS;
   static constexpr size_t OFF_OUTW = OFF_FCW + 32 * 1024;
   static constexpr size_t OFF_BIAS = OFF_OUTW + 4 * 1024;
-  static constexpr size_t OFF_XCH = up16(OFF_BIAS + size_t(GruPk::BIAS_FLOATS) * 4);         // [B] float2: new positions
-  static constexpr size_t OFF_DONE = OFF_XCH + size_t(B) * 8;                                // [64] bytes
+  // [B] new positions (float2); predator-prey: new position and velocity (float4)
+  static constexpr size_t OFF_XCH = up16(OFF_BIAS + size_t(GruPk::BIAS_FLOATS) * 4);
+  static constexpr size_t OFF_DONE = OFF_XCH + size_t(B) * (Scn::kTag ? 16 : 8);             // [64] bytes
   static constexpr size_t TOTAL = OFF_DONE + 64;
   static_assert(TOTAL <= 160 * 1024, "LDS");
 };
@@ -172,13 +199,18 @@ __device__ __forceinline__ uint2 pack4_bf16(float a, float b, float c, float d) 
 
 // EB = envs per block: 64, or 32 / 16 for small batches (every phase of a step is a loop over the block's
 // 16-row tiles, so the step latency of a block, which is the time of a rollout while every block has a CU
-// to itself, falls with its rows).
-template <int N, int EB>
-__global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const uint8_t* __restrict__ packed,
+// to itself, falls with its rows) and for the shapes whose activations would not fit the LDS otherwise.
+template <typename Scn, int EB>
+__global__ __launch_bounds__(512) void rollout_gru_kernel(TagArgs TA, const uint8_t* __restrict__ packed,
                                                           float* __restrict__ hidden, int per_run_weights,
                                                           uint32_t groups, uint32_t groups_per_xcd) {
-  using M = GruSmem<N, EB>;
-  constexpr int B = M::B, D = M::D, NT = M::NT;
+  using M = GruSmem<Scn, EB>;
+  using TS = typename Scn::Shape;                      // predator-prey only
+  constexpr bool kTag = Scn::kTag;
+  constexpr int N = Scn::N, L = Scn::L, B = M::B, D = M::D, NT = M::NT, KS = M::KS;
+  constexpr int G = kTag ? TS::G : 1, NA = kTag ? TS::A : 0;   // good agents, adversaries
+  const RolloutArgs& A = TA.r;
+  [[maybe_unused]] const TagPhys& tg = TA.tg;
   extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
   uint8_t* otile = smem + M::OFF_OBS;
   float* logits = reinterpret_cast<float*>(smem + M::OFF_OBS);
@@ -187,7 +219,8 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
   const bf16x8* fcw0 = reinterpret_cast<const bf16x8*>(smem + M::OFF_FCW);
   const bf16x8* outw0 = reinterpret_cast<const bf16x8*>(smem + M::OFF_OUTW);
   const float* bias0 = reinterpret_cast<const float*>(smem + M::OFF_BIAS);
-  float2* xch = reinterpret_cast<float2*>(smem + M::OFF_XCH);
+  [[maybe_unused]] float2* xch2 = reinterpret_cast<float2*>(smem + M::OFF_XCH);
+  [[maybe_unused]] float4* xch4 = reinterpret_cast<float4*>(smem + M::OFF_XCH);
   uint8_t* donef = smem + M::OFF_DONE;
 
   const int tid = threadIdx.x;
@@ -220,7 +253,9 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
 #pragma unroll
       for (int s = 0; s < 4; ++s)
         wg[gate][src][s] = reinterpret_cast<const bf16x8*>(packed + GruPk::OFF_GRU)[(((u * 3 + gate) * 2 + src) * 4 + s) * 64 + lane];
-  const bf16x8 we = reinterpret_cast<const bf16x8*>(packed + GruPk::OFF_EMB)[u * 64 + lane];
+  bf16x8 we[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) we[s] = reinterpret_cast<const bf16x8*>(packed + GruPk::OFF_EMB)[(u * 2 + s) * 64 + lane];
   {
     const uint4* src = reinterpret_cast<const uint4*>(packed + GruPk::OFF_FC);
     uint4* dst = reinterpret_cast<uint4*>(smem + M::OFF_FCW);
@@ -252,17 +287,33 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
   const uint32_t run = gc / A.E;
   const uint32_t env = gc - run * A.E;
   float px = 0.0f, py = 0.0f, vx = 0.0f, vy = 0.0f;
-  float qx[N], qy[N], lx[N], ly[N];     // all agents' positions and the landmarks of this lane's env
+  // all agents' positions and the landmarks of this lane's env; predator-prey: the good agents' velocities
+  float qx[N], qy[N], lx[L + 1], ly[L + 1];
+  [[maybe_unused]] float gvx[G], gvy[G];
   int32_t ep = 0;
 #pragma unroll
-  for (int a = 0; a < N; ++a) qx[a] = qy[a] = lx[a] = ly[a] = 0.0f;
+  for (int a = 0; a < N; ++a) qx[a] = qy[a] = 0.0f;
+#pragma unroll
+  for (int k = 0; k < L + 1; ++k) lx[k] = ly[k] = 0.0f;
+#pragma unroll
+  for (int k = 0; k < G; ++k) gvx[k] = gvy[k] = 0.0f;
   if (valid) {
 #pragma unroll
     for (int a = 0; a < N; ++a) {
       qx[a] = A.st.pos_a[(0 * N + a) * TE + g];
       qy[a] = A.st.pos_a[(1 * N + a) * TE + g];
-      lx[a] = A.st.pos_l[(0 * N + a) * TE + g];
-      ly[a] = A.st.pos_l[(1 * N + a) * TE + g];
+    }
+#pragma unroll
+    for (int k = 0; k < L; ++k) {
+      lx[k] = A.st.pos_l[(0 * L + k) * TE + g];
+      ly[k] = A.st.pos_l[(1 * L + k) * TE + g];
+    }
+    if constexpr (kTag) {
+#pragma unroll
+      for (int k = 0; k < G; ++k) {
+        gvx[k] = A.st.vel_a[(0 * N + NA + k) * TE + g];
+        gvy[k] = A.st.vel_a[(1 * N + NA + k) * TE + g];
+      }
     }
     vx = A.st.vel_a[(0 * N + i) * TE + g];
     vy = A.st.vel_a[(1 * N + i) * TE + g];
@@ -272,34 +323,43 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
   for (int a = 0; a < N; ++a) {
     if (a == i) { px = qx[a]; py = qy[a]; }
   }
+  // predator-prey: the constants of this lane's role
+  [[maybe_unused]] const int role = i < NA ? 0 : 1;
+  [[maybe_unused]] float my_radius = 0.0f, my_gain = 0.0f, my_limit = 0.0f, my_limit_sq = 0.0f;
+  if constexpr (kTag) {
+    my_radius = role == 0 ? tg.radius[0] : tg.radius[1];
+    my_gain = role == 0 ? tg.gain[0] : tg.gain[1];
+    my_limit = role == 0 ? tg.limit[0] : tg.limit[1];
+    my_limit_sq = role == 0 ? tg.limit_sq[0] : tg.limit_sq[1];
+  }
 
   // Observation row of this lane from the registers above: bf16 (nearest even) into the LDS tile
   // for the embedding, fp32 to `dst` (this lane's row of a trajectory slice, may be null).
   auto write_obs_row = [&](float* dst) {
-    float o[32];
+    float o[32 * KS];
 #pragma unroll
-    for (int c = 0; c < 32; ++c) o[c] = 0.0f;
-    o[0] = vx; o[1] = vy; o[2] = px; o[3] = py;
+    for (int c = 0; c < 32 * KS; ++c) o[c] = 0.0f;
+    if constexpr (kTag) {
+      tag_obs_regs<TS>(o, i, px, py, vx, vy, qx, qy, lx, ly, gvx, gvy);
+    } else {
+      o[0] = vx; o[1] = vy; o[2] = px; o[3] = py;
 #pragma unroll
-    for (int l = 0; l < N; ++l) { o[4 + 2 * l] = lx[l] - px; o[5 + 2 * l] = ly[l] - py; }
+      for (int l = 0; l < N; ++l) { o[4 + 2 * l] = lx[l] - px; o[5 + 2 * l] = ly[l] - py; }
+      // the k-th OTHER agent is agent k (k < i) or k + 1, ascending
 #pragma unroll
-    for (int a = 0; a < N; ++a) {
-      // the other agents in ascending order: agent a sits in slot a - (a > i)
-#pragma unroll
-      for (int slot = 0; slot < N - 1; ++slot) {
-        if (a != i && a - (a > i ? 1 : 0) == slot) {
-          o[4 + 2 * N + 2 * slot] = qx[a] - px;
-          o[5 + 2 * N + 2 * slot] = qy[a] - py;
-        }
+      for (int k = 0; k < N - 1; ++k) {
+        const bool up = k >= i;
+        o[4 + 2 * N + 2 * k] = (up ? qx[k + 1] : qx[k]) - px;
+        o[5 + 2 * N + 2 * k] = (up ? qy[k + 1] : qy[k]) - py;
       }
     }
     u32x4* row = reinterpret_cast<u32x4*>(otile + tid * M::OS);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
+    for (int q = 0; q < 4 * KS; ++q) {
       u32x4 v;
 #pragma unroll
       for (int e = 0; e < 4; ++e) v[e] = pack_bf16_rne(o[8 * q + 2 * e], o[8 * q + 2 * e + 1]);
-      row[obs_piece(q, tid)] = v;
+      row[obs_piece<KS>(q, tid)] = v;
     }
     if (dst && valid) {
 #pragma unroll
@@ -317,6 +377,7 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
   uint8_t* done_base = A.done_traj;
   const size_t row_off = size_t(gc) * N + i;
   const bool env_writer = valid && i == 0;
+  const bool per_agent_reward = kTag || A.ph.reward_mode == 1;
   uint32_t step = A.abs_step;
 
   for (int t = 0; t < A.T; ++t, ++step) {
@@ -332,7 +393,9 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
     for (int rt = 0; rt < NT; ++rt) {
       const int row = 16 * rt + j;
       f32x4 acc = *reinterpret_cast<const f32x4*>(bias + 16 * u + 4 * gq);
-      acc = MPE_MFMA_BF(we, *reinterpret_cast<const bf16x8*>(otile + row * M::OS + 16 * obs_piece(gq, j)), acc);
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+        acc = MPE_MFMA_BF(we[s], *reinterpret_cast<const bf16x8*>(otile + row * M::OS + 16 * obs_piece<KS>(4 * s + gq, j)), acc);
       *reinterpret_cast<uint2*>(xbuf + rt * kTile + wr_off) =
           pack4_bf16(fast_tanh(acc[0]), fast_tanh(acc[1]), fast_tanh(acc[2]), fast_tanh(acc[3]));
     }
@@ -416,75 +479,148 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
       for (int k = 0; k < kNumActions; ++k) z[k] = logits[k * B + tid];
       const uint32_t act = gumbel_argmax(z, A.seed, run, env, step, uint32_t(i));
       if (act_base && valid) act_base[row_off] = uint8_t(act);
-      float fx = A.ph.accel * action_dir_x(act);
-      float fy = A.ph.accel * action_dir_y(act);
-      // the k-th OTHER agent is agent k (k < i) or k + 1: N - 1 evaluations, ascending agent order
+      if constexpr (kTag) {
+        // control, contacts with the other agents and the obstacles on the pre-step positions, position
+        // with the old velocity, damped velocity, speed limit
+        float fx = my_gain * action_dir_x(act);
+        float fy = my_gain * action_dir_y(act);
 #pragma unroll
-      for (int k = 0; k < N - 1; ++k) {
-        const bool up = k >= i;
-        const float dx = px - (up ? qx[k + 1] : qx[k]);
-        const float dy = py - (up ? qy[k + 1] : qy[k]);
-        const float kf = contact_factor(dx, dy, A.ph);
-        fx = fmaf(kf, dx, fx);
-        fy = fmaf(kf, dy, fy);
+        for (int k = 0; k < N - 1; ++k) {
+          const bool up = k >= i;
+          const float ox = up ? qx[k + 1] : qx[k], oy = up ? qy[k + 1] : qy[k];
+          const float r_lo = tg.radius[k < NA ? 0 : 1], r_hi = tg.radius[k + 1 < NA ? 0 : 1];
+          const float orad = ((k < NA) == (k + 1 < NA)) ? r_lo : (up ? r_hi : r_lo);
+          const float dx = px - ox, dy = py - oy;
+          const float kf = tag_contact(dx, dy, my_radius + orad, tg);
+          fx = fmaf(kf, dx, fx);
+          fy = fmaf(kf, dy, fy);
+        }
+#pragma unroll
+        for (int l = 0; l < L; ++l) {
+          const float dx = px - lx[l], dy = py - ly[l];
+          const float kf = tag_contact(dx, dy, my_radius + tg.lm_radius, tg);
+          fx = fmaf(kf, dx, fx);
+          fy = fmaf(kf, dy, fy);
+        }
+        px = fmaf(vx, tg.dt, px);
+        py = fmaf(vy, tg.dt, py);
+        vx = fmaf(fx, tg.dt_over_mass, vx * tg.keep);
+        vy = fmaf(fy, tg.dt_over_mass, vy * tg.keep);
+        const float s2 = fmaf(vx, vx, vy * vy);
+        if (s2 > my_limit_sq) {
+          const float kf = my_limit * hw_rsq(s2);
+          vx *= kf;
+          vy *= kf;
+        }
+        xch4[tid] = make_float4(px, py, vx, vy);
+      } else {
+        float fx = A.ph.accel * action_dir_x(act);
+        float fy = A.ph.accel * action_dir_y(act);
+        // the k-th OTHER agent is agent k (k < i) or k + 1: N - 1 evaluations, ascending agent order
+#pragma unroll
+        for (int k = 0; k < N - 1; ++k) {
+          const bool up = k >= i;
+          const float dx = px - (up ? qx[k + 1] : qx[k]);
+          const float dy = py - (up ? qy[k + 1] : qy[k]);
+          const float kf = contact_factor(dx, dy, A.ph);
+          fx = fmaf(kf, dx, fx);
+          fy = fmaf(kf, dy, fy);
+        }
+        px = fmaf(vx, A.ph.dt, px);
+        py = fmaf(vy, A.ph.dt, py);
+        vx = fmaf(fx, A.ph.dt_over_mass, vx * A.ph.keep);
+        vy = fmaf(fy, A.ph.dt_over_mass, vy * A.ph.keep);
+        xch2[tid] = make_float2(px, py);
       }
-      px = fmaf(vx, A.ph.dt, px);
-      py = fmaf(vy, A.ph.dt, py);
-      vx = fmaf(fx, A.ph.dt_over_mass, vx * A.ph.keep);
-      vy = fmaf(fy, A.ph.dt_over_mass, vy * A.ph.keep);
-      xch[tid] = make_float2(px, py);
     }
     if (act_base) act_base += TE * N;
     __syncthreads();   // new positions visible; L has been read
 
     // ---- agents: reward, done, auto-reset, next observation (written over L)
     if (agent) {
-#pragma unroll
-      for (int a = 0; a < N; ++a) {
-        const float2 p = xch[el * N + a];
-        qx[a] = p.x;
-        qy[a] = p.y;
-      }
-      float r = 0.0f;
-#pragma unroll
-      for (int l = 0; l < N; ++l) {
-        float best2 = INFINITY;
+      int32_t max_ep;
+      if constexpr (kTag) {
 #pragma unroll
         for (int a = 0; a < N; ++a) {
-          const float dx = qx[a] - lx[l], dy = qy[a] - ly[l];
-          best2 = fminf(best2, fmaf(dx, dx, dy * dy));
-        }
-        r -= hw_sqrt(best2);
-      }
-      if (A.ph.reward_mode == 1) {
-        uint32_t overlaps = 0;
-#pragma unroll
-        for (int a = 0; a < N; ++a) {
-          if (a != i) {
-            const float dx = px - qx[a], dy = py - qy[a];
-            overlaps += fmaf(dx, dx, dy * dy) < A.ph.two_r_sq ? 1u : 0u;
+          const float4 p = xch4[el * N + a];
+          qx[a] = p.x;
+          qy[a] = p.y;
+          if (a >= NA) {
+            gvx[a - NA] = p.z;
+            gvy[a - NA] = p.w;
           }
         }
-        if (rew_base && valid) rew_base[row_off] = mixed_reward(r, overlaps, A.ph);
-      } else if (rew_base && env_writer) {
-        rew_base[gc] = r;
+        // touching (good, adversary) pairs on the new positions
+        uint32_t caught = 0, hits = 0;
+#pragma unroll
+        for (int a = 0; a < NA; ++a) {
+#pragma unroll
+          for (int b = NA; b < N; ++b) {
+            const float dx = qx[a] - qx[b], dy = qy[a] - qy[b];
+            const uint32_t touch = fmaf(dx, dx, dy * dy) < tg.touch_sq ? 1u : 0u;
+            caught += touch;
+            hits += b == i ? touch : 0u;
+          }
+        }
+        const float r_good = -10.0f * float(hits) - tag_bound(fabsf(px)) - tag_bound(fabsf(py));
+        const float r = role == 0 ? 10.0f * float(caught) : r_good;
+        if (rew_base && valid) rew_base[row_off] = r;
+        max_ep = tg.max_ep;
+      } else {
+#pragma unroll
+        for (int a = 0; a < N; ++a) {
+          const float2 p = xch2[el * N + a];
+          qx[a] = p.x;
+          qy[a] = p.y;
+        }
+        float r = 0.0f;
+#pragma unroll
+        for (int l = 0; l < N; ++l) {
+          float best2 = INFINITY;
+#pragma unroll
+          for (int a = 0; a < N; ++a) {
+            const float dx = qx[a] - lx[l], dy = qy[a] - ly[l];
+            best2 = fminf(best2, fmaf(dx, dx, dy * dy));
+          }
+          r -= hw_sqrt(best2);
+        }
+        if (A.ph.reward_mode == 1) {
+          uint32_t overlaps = 0;
+#pragma unroll
+          for (int a = 0; a < N; ++a) {
+            if (a != i) {
+              const float dx = px - qx[a], dy = py - qy[a];
+              overlaps += fmaf(dx, dx, dy * dy) < A.ph.two_r_sq ? 1u : 0u;
+            }
+          }
+          if (rew_base && valid) rew_base[row_off] = mixed_reward(r, overlaps, A.ph);
+        } else if (rew_base && env_writer) {
+          rew_base[gc] = r;
+        }
+        max_ep = A.ph.max_ep;
       }
       ep += 1;
-      const bool done = ep >= A.ph.max_ep;
+      const bool done = ep >= max_ep;
       if (done_base && env_writer) done_base[gc] = done ? 1 : 0;
       if (i == 0) donef[el] = done ? 1 : 0;     // read by the gate phase of the next step
       if (done) {
         // new episode keyed by step + 1; every lane regenerates its whole env (1 step in max_ep)
         uint32_t env_r = env;
         asm volatile("" : "+v"(env_r));
+        if constexpr (kTag) {
+          tag_draw_positions<TS>(qx, qy, lx, ly, env_r, step + 1u, A.seed, run);
 #pragma unroll
-        for (int a = 0; a < N; ++a) {
-          const uint4 w = philox4x32_10(env_r, step + 1u, uint32_t(a), kTagResetPos, A.seed, run);
-          qx[a] = word_to_position(w.x);
-          qy[a] = word_to_position(w.y);
-          const uint4 wl = philox4x32_10(env_r, step + 1u, uint32_t(N + a), kTagResetPos, A.seed, run);
-          lx[a] = word_to_position(wl.x);
-          ly[a] = word_to_position(wl.y);
+          for (int k = 0; k < G; ++k) gvx[k] = gvy[k] = 0.0f;
+        } else {
+#pragma unroll
+          for (int a = 0; a < N; ++a) {
+            const uint4 w = philox4x32_10(env_r, step + 1u, uint32_t(a), kTagResetPos, A.seed, run);
+            qx[a] = word_to_position(w.x);
+            qy[a] = word_to_position(w.y);
+            const uint4 wl = philox4x32_10(env_r, step + 1u, uint32_t(N + a), kTagResetPos, A.seed, run);
+            lx[a] = word_to_position(wl.x);
+            ly[a] = word_to_position(wl.y);
+          }
         }
 #pragma unroll
         for (int a = 0; a < N; ++a) {
@@ -500,7 +636,7 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
       if (obs_row) obs_row += slice;
       write_obs_row(t + 1 < A.T ? obs_row : last_row);
     }
-    if (rew_base) rew_base += A.ph.reward_mode == 1 ? TE * N : TE;
+    if (rew_base) rew_base += per_agent_reward ? TE * N : TE;
     if (done_base) done_base += TE;
     __syncthreads();   // next observation and the done flags complete
   }
@@ -522,47 +658,59 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(RolloutArgs A, const u
     A.st.pos_a[(1 * N + i) * TE + g] = py;
     A.st.vel_a[(0 * N + i) * TE + g] = vx;
     A.st.vel_a[(1 * N + i) * TE + g] = vy;
+    // landmark l is written back by the lane of agent l % N (every lane holds all of them)
 #pragma unroll
-    for (int l = 0; l < N; ++l) {
-      if (l == i) {
-        A.st.pos_l[(0 * N + l) * TE + g] = lx[l];
-        A.st.pos_l[(1 * N + l) * TE + g] = ly[l];
+    for (int l = 0; l < L; ++l) {
+      if (l % N == i) {
+        A.st.pos_l[(0 * L + l) * TE + g] = lx[l];
+        A.st.pos_l[(1 * L + l) * TE + g] = ly[l];
       }
     }
     if (i == 0) A.st.ep_step[g] = ep;
   }
 }
 
-template <int N, int EB>
-hipError_t rollout_gru_blocks(const RolloutArgs& A, const PolicyBuffers& pb, float* hidden, hipStream_t s) {
-  using M = GruSmem<N, EB>;
-  auto kern = rollout_gru_kernel<N, EB>;
+template <typename Scn, int EB>
+hipError_t rollout_gru_blocks(const TagArgs& A, const PolicyBuffers& pb, float* hidden, hipStream_t s) {
+  using M = GruSmem<Scn, EB>;
+  auto kern = rollout_gru_kernel<Scn, EB>;
   static std::atomic<uint64_t> lds_allowed{0};
   if (hipError_t e = allow_lds(reinterpret_cast<const void*>(kern), M::TOTAL, lds_allowed); e != hipSuccess) return e;
-  const uint32_t groups = (A.TE + EB - 1) / EB;
+  const uint32_t groups = (A.r.TE + EB - 1) / EB;
   const uint32_t per_xcd = (groups + 7) / 8;
   hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(512), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),
-                     hidden, int(A.TE != A.E), groups, per_xcd);
+                     hidden, int(A.r.TE != A.r.E), groups, per_xcd);
   return hipGetLastError();
 }
 
-template <int N>
-hipError_t rollout_gru_impl(const RolloutArgs& A, const PolicyBuffers& pb, float* hidden, hipStream_t s, const char** why) {
+// The largest block (in envs) whose activations fit the LDS: 64 envs for up to 3 agents, 32 envs for up to 6
+// agents whose observation fits one K slice, 16 envs otherwise.
+template <typename Scn>
+constexpr int gru_max_envs() {
+  return Scn::N <= 3 ? 64 : ((Scn::N <= 6 && Scn::D <= 32) ? 32 : 16);
+}
+
+template <typename Scn>
+hipError_t rollout_gru_impl(const TagArgs& A, const PolicyBuffers& pb, float* hidden, hipStream_t s, const char** why) {
   // Smaller blocks while each still gets a CU to itself (measured per 128-step rollout, 3 agents: 16-env
   // blocks 0.57-0.60 ms up to 4,096 envs and 32-env blocks 0.96-1.01 ms up to 8,192 envs against 1.9 ms with
-  // 64-env blocks; with more blocks than CUs the 64-env blocks are the fastest).
+  // 64-env blocks; with more blocks than CUs the largest blocks are the fastest).
   // With one set of weights per run a block must lie inside a run: the largest of 64, 32, 16 that divides
   // the run size bounds the choice.
+  constexpr int kMax = gru_max_envs<Scn>();
   const uint32_t cus = compute_units();
-  const bool runs = A.TE != A.E;
-  if (runs && A.E % 16 != 0) {
+  const bool runs = A.r.TE != A.r.E;
+  if (runs && A.r.E % 16 != 0) {
     *why = "with several runs, num_envs per run must be a multiple of 16";
     return hipSuccess;
   }
-  if ((A.TE + 15) / 16 <= cus || (runs && A.E % 32 != 0)) return rollout_gru_blocks<N, 16>(A, pb, hidden, s);
-  // 4 and 5 agents: the activations of 64 envs do not fit the LDS, their largest block is 32 envs
-  if (N > 3 || (A.TE + 31) / 32 <= cus || (runs && A.E % 64 != 0)) return rollout_gru_blocks<N, 32>(A, pb, hidden, s);
-  if constexpr (N <= 3) return rollout_gru_blocks<N, 64>(A, pb, hidden, s);
+  if (kMax == 16 || (A.r.TE + 15) / 16 <= cus || (runs && A.r.E % 32 != 0))
+    return rollout_gru_blocks<Scn, 16>(A, pb, hidden, s);
+  if constexpr (kMax >= 32) {
+    if (kMax == 32 || (A.r.TE + 31) / 32 <= cus || (runs && A.r.E % 64 != 0))
+      return rollout_gru_blocks<Scn, 32>(A, pb, hidden, s);
+  }
+  if constexpr (kMax >= 64) return rollout_gru_blocks<Scn, 64>(A, pb, hidden, s);
   return hipErrorInvalidValue;
 }
 
@@ -578,26 +726,48 @@ void launch_fill_zero(float* p, size_t n, hipStream_t s) {
   hipLaunchKernelGGL(fill_zero_kernel, dim3(uint32_t(blocks < 4096 ? blocks : 4096)), dim3(256), 0, s, p, n);
 }
 
-// The observation (6 N floats) must fit the one K slice of 32 inputs of the embedding: N <= 5.
-bool gru_supported(int N, int H, int weight_dtype) { return N >= 1 && N <= 5 && H == kG && weight_dtype == 1; }
+// Simple spread with 1..10 agents and every predator-prey shape that is built; hidden 128, bf16 weights.
+#define MPE_GRU_TAG_SHAPES(X) X(4, 2, 1) X(2, 1, 1) X(3, 0, 1) X(6, 2, 2)
 
-hipError_t pack_policy_gru(PolicyBuffers& pb, int N, int R, const float* We, const float* be, const float* Wi,
+bool gru_supported(bool tag, int N, int L, int G, int H, int weight_dtype) {
+  if (H != kG || weight_dtype != 1) return false;
+  if (!tag) return N >= 1 && N <= 10;
+#define X(n, l, g) if (N == n && L == l && G == g) return true;
+  MPE_GRU_TAG_SHAPES(X)
+#undef X
+  return false;
+}
+
+hipError_t pack_policy_gru(PolicyBuffers& pb, int D, int R, const float* We, const float* be, const float* Wi,
                            const float* bi, const float* Wh, const float* bh, const float* Wf, const float* bf,
                            const float* Wo, const float* bo, hipStream_t s) {
+  if (D < 1 || D > 64) return hipErrorInvalidValue;
   if (hipError_t e = ensure_policy_bytes(pb, size_t(R) * GruPk::BYTES); e != hipSuccess) return e;
   hipLaunchKernelGGL(pack_gru_kernel, dim3((GruPk::THREADS + 255) / 256, R), dim3(256), 0, s,
-                     static_cast<uint8_t*>(pb.packed), 6 * N, We, be, Wi, bi, Wh, bh, Wf, bf, Wo, bo);
+                     static_cast<uint8_t*>(pb.packed), D, We, be, Wi, bi, Wh, bh, Wf, bf, Wo, bo);
   return hipGetLastError();
 }
 
-hipError_t launch_rollout_gru(int N, const RolloutArgs& A, const PolicyBuffers& pb, float* hidden, hipStream_t s,
-                              const char** why) {
+hipError_t launch_rollout_gru(bool tag, int N, int L, int G, const TagArgs& A, const PolicyBuffers& pb, float* hidden,
+                              hipStream_t s, const char** why) {
+  if (tag) {
+#define X(n, l, g) \
+    if (N == n && L == l && G == g) return rollout_gru_impl<GruTag<n, l, g>>(A, pb, hidden, s, why);
+    MPE_GRU_TAG_SHAPES(X)
+#undef X
+    return hipErrorInvalidValue;
+  }
   switch (N) {
-    case 1: return rollout_gru_impl<1>(A, pb, hidden, s, why);
-    case 2: return rollout_gru_impl<2>(A, pb, hidden, s, why);
-    case 3: return rollout_gru_impl<3>(A, pb, hidden, s, why);
-    case 4: return rollout_gru_impl<4>(A, pb, hidden, s, why);
-    case 5: return rollout_gru_impl<5>(A, pb, hidden, s, why);
+    case 1: return rollout_gru_impl<GruSpread<1>>(A, pb, hidden, s, why);
+    case 2: return rollout_gru_impl<GruSpread<2>>(A, pb, hidden, s, why);
+    case 3: return rollout_gru_impl<GruSpread<3>>(A, pb, hidden, s, why);
+    case 4: return rollout_gru_impl<GruSpread<4>>(A, pb, hidden, s, why);
+    case 5: return rollout_gru_impl<GruSpread<5>>(A, pb, hidden, s, why);
+    case 6: return rollout_gru_impl<GruSpread<6>>(A, pb, hidden, s, why);
+    case 7: return rollout_gru_impl<GruSpread<7>>(A, pb, hidden, s, why);
+    case 8: return rollout_gru_impl<GruSpread<8>>(A, pb, hidden, s, why);
+    case 9: return rollout_gru_impl<GruSpread<9>>(A, pb, hidden, s, why);
+    case 10: return rollout_gru_impl<GruSpread<10>>(A, pb, hidden, s, why);
     default: return hipErrorInvalidValue;
   }
 }

@@ -10,18 +10,11 @@
 // 64 rows are one contiguous piece of the trajectory and leave with 16-byte stores over whole
 // cache lines.  Rewards are per agent, so every lane stores its own.
 #include "mpe_mlp64.h"
+#include "mpe_tag_device.h"
 
 namespace mpe {
 
 namespace {
-
-template <int N_, int L_, int G_>
-struct TagShape {
-  static constexpr int N = N_, L = L_, G = G_, A = N_ - G_;   // A adversaries first, then G good agents
-  static constexpr int D = 4 + 2 * L_ + 2 * (N_ - 1) + 2 * G_;
-  static constexpr bool kWaveLocal = (64 % N_) == 0;          // the rows of an env lie in one wavefront
-  static_assert(G_ >= 1 && A >= 1 && L_ >= 0 && D % 2 == 0, "roles");
-};
 
 // kPolicy / kPolicyBf: fp32 (split-operand) / bf16 policy.  kPolicyAc: fp32 policy plus a critic of the same
 // shape with one output: log-probability of the sampled action and value per agent and step.
@@ -49,64 +42,6 @@ struct TagSmem {
   static_assert(OFF_OBS % 16 == 0 && OFF_XCH % 16 == 0 && P::RUN_BYTES % 16 == 0, "alignment");
   static_assert(TOTAL <= 160 * 1024, "LDS budget");
 };
-
-// Contact force factor k of a pair with separation (dx, dy) and contact distance dmin: the force
-// on the first entity is k * (dx, dy).
-__device__ __forceinline__ float tag_contact(float dx, float dy, float dmin, const TagPhys& tg) {
-  const float d2 = fmaxf(fmaf(dx, dx, dy * dy), 1e-24f);
-  const float inv_d = hw_rsq(d2);
-  const float d = d2 * inv_d;
-  return tg.force_margin * softplus((dmin - d) * tg.inv_margin) * inv_d;
-}
-
-// Boundary penalty of a good agent for one coordinate, u = |coordinate|.
-__device__ __forceinline__ float tag_bound(float u) {
-  const float lin = (u - 0.9f) * 10.0f;
-  const float ex = fminf(hw_exp2((2.0f * u - 2.0f) * kLog2e), 10.0f);
-  return u < 0.9f ? 0.0f : (u < 1.0f ? lin : ex);
-}
-
-// Fresh positions of every entity of an env for the episode that starts at `step`.
-template <typename S>
-__device__ __forceinline__ void tag_draw_positions(float (&qx)[S::N], float (&qy)[S::N], float (&lx)[S::L + 1],
-                                                   float (&ly)[S::L + 1], uint32_t env, uint32_t step,
-                                                   uint32_t seed, uint32_t run) {
-#pragma unroll
-  for (int a = 0; a < S::N; ++a) {
-    const uint4 w = philox4x32_10(env, step, uint32_t(a), kTagResetPos, seed, run);
-    qx[a] = word_to_position(w.x);
-    qy[a] = word_to_position(w.y);
-  }
-#pragma unroll
-  for (int k = 0; k < S::L; ++k) {
-    const uint4 w = philox4x32_10(env, step, uint32_t(S::N + k), kTagResetPos, seed, run);
-    lx[k] = word_to_position(w.x) * 0.9f;   // obstacles start inside [-0.9, 0.9): one fp32 product
-    ly[k] = word_to_position(w.y) * 0.9f;
-  }
-}
-
-// Observation row of agent i: own velocity, own position, landmarks and other agents relative,
-// velocities of the other good agents, zero padding (good agents see one velocity fewer).
-template <typename S>
-__device__ __forceinline__ void tag_write_row(float2* row, int i, float px, float py, float vx, float vy,
-                                              const float (&qx)[S::N], const float (&qy)[S::N],
-                                              const float (&lx)[S::L + 1], const float (&ly)[S::L + 1],
-                                              const float (&gvx)[S::G], const float (&gvy)[S::G]) {
-  int c = 0;
-  row[c++] = make_float2(vx, vy);
-  row[c++] = make_float2(px, py);
-#pragma unroll
-  for (int k = 0; k < S::L; ++k) row[c++] = make_float2(lx[k] - px, ly[k] - py);
-#pragma unroll
-  for (int a = 0; a < S::N; ++a) {
-    if (a != i) row[c++] = make_float2(qx[a] - px, qy[a] - py);
-  }
-#pragma unroll
-  for (int k = 0; k < S::G; ++k) {
-    if (S::A + k != i) row[c++] = make_float2(gvx[k], gvy[k]);
-  }
-  if (i >= S::A) row[S::D / 2 - 1] = make_float2(0.0f, 0.0f);
-}
 
 template <typename S>
 __global__ __launch_bounds__(64 * S::N) void tag_reset_kernel(StatePtrs st, uint32_t TE, uint32_t E, uint32_t seed,

@@ -36,14 +36,67 @@ def say(msg):
     print(msg, flush=True)
 
 
-def _pair(mods, E, N, wseed=3, max_ep=synth.MAX_EPISODE_STEPS, reward_mode=0):
+def _configs(E, scn, R=1, max_ep=synth.MAX_EPISODE_STEPS, reward_mode=0):
+    """scn: the number of agents of simple spread, or (agents, landmarks, adversaries) of predator-prey."""
+    if isinstance(scn, tuple):
+        N, L, A = scn
+        return (Hp.tag_gpu_config(E, N, L, A, R, 128, max_ep=max_ep, wd=1),
+                Hp.tag_oracle_config(E, N, L, A, R, 128, max_ep=max_ep, wd=1), N)
+    return (Hp.gpu_config(E, scn, R, 128, 1, max_ep=max_ep, reward_mode=reward_mode),
+            Hp.oracle_config(E, scn, R, 128, 1, max_ep=max_ep, reward_mode=reward_mode), scn)
+
+
+def _pair(mods, E, scn, wseed=3, max_ep=synth.MAX_EPISODE_STEPS, reward_mode=0, R=1):
     MpeEnv, Oracle = mods
-    env = MpeEnv(Hp.gpu_config(E, N, 1, 128, 1, max_ep=max_ep, reward_mode=reward_mode))
-    orc = Oracle(Hp.oracle_config(E, N, 1, 128, 1, max_ep=max_ep, reward_mode=reward_mode), threads=8)
-    w = synth.gru_weights(wseed, 1, 6 * N)
+    gcfg, ocfg, N = _configs(E, scn, R, max_ep, reward_mode)
+    env = MpeEnv(gcfg)
+    orc = Oracle(ocfg, threads=8)
+    assert env.D == orc.D
+    w = synth.gru_weights(wseed, R, env.D)
     env.set_gru_policy(*Hp.to_dev(w))
     orc.set_gru(*w)
     return env, orc, w
+
+
+def _step_unit(scn, pa, pl):
+    """Per-env unit of the single-step bar (grows for nearly coincident centres)."""
+    if isinstance(scn, tuple):
+        from tests.test_tag_gpu import _scale
+        return _scale(pa, pl, scn)
+    return Hp.step_scale(pa)
+
+
+def _assert_first_obs(scn, obs, robs):
+    if isinstance(scn, tuple):
+        from tests.test_tag_gpu import _assert_start_obs
+        _assert_start_obs(obs, robs, scn)
+    else:
+        assert np.array_equal(obs.astype(np.float64), robs)
+
+
+def _assert_free_running(mods, scn, R, E, w, seed, obs, act, rew, robs, ract, rrew, what):
+    """The 25-step bar of every free-running comparison (helpers.assert_episodes_close) on the episodes whose
+    sampled actions agree so far."""
+    _, Oracle = mods
+    tag = isinstance(scn, tuple)
+    ocfg = _configs(E, scn, R)[1]
+
+    def make_oracle():
+        o = Oracle(ocfg, threads=8)
+        o.set_gru(*w)
+        return o
+    T = obs.shape[0]
+    err, _, _ = Hp.episode_errors(obs, act, None if tag else rew, robs, ract, None if tag else rrew)
+    sens = Hp.oracle_sensitivity(make_oracle, seed, T)
+    if tag:
+        Hp.assert_episodes_close(err, sens, Hp.min_gap_tag(robs, scn), Hp.EXCEED_SHARE_TAG[scn[:2]], what=what)
+    else:
+        Hp.assert_episodes_close(err, sens, Hp.min_gap_spread(robs, scn), Hp.EXCEED_SHARE_SPREAD[scn], what=what)
+
+
+SPREAD_AND_TAG = [(256, 3, 12), (100, 3, 12), (64, 1, 12), (130, 2, 12), (2048, 3, 6), (100, 4, 8), (70, 5, 8),
+                  (64, 6, 6), (50, 7, 5), (40, 8, 5), (36, 9, 5), (50, 10, 6),
+                  (128, (4, 2, 3), 8), (130, (2, 1, 1), 8), (100, (3, 0, 2), 8), (70, (6, 2, 4), 6)]
 
 
 def _bf16(x):
@@ -103,10 +156,12 @@ def _carried_state_bound(w, obs, h0, fragile_tol=4e-7):
     return h1, bound, obs_fragile, (flip > 0).sum(axis=1)
 
 
-@pytest.mark.parametrize("E,N,T", [(256, 3, 12), (100, 3, 12), (64, 1, 12), (130, 2, 12), (2048, 3, 6), (100, 4, 8), (70, 5, 8)])
-def test_teacher_forced_steps(mods, E, N, T):
-    say("recurrent policy, forced steps E=%d N=%d T=%d" % (E, N, T))
-    env, orc, w = _pair(mods, E, N)
+@pytest.mark.parametrize("E,scn,T", SPREAD_AND_TAG)
+def test_teacher_forced_steps(mods, E, scn, T):
+    say("recurrent policy, forced steps E=%d scenario=%s T=%d" % (E, scn, T))
+    env, orc, w = _pair(mods, E, scn)
+    N = env.N
+    tag = isinstance(scn, tuple)
     orc.reset(21)
     env.reset(21)
     g = np.random.Generator(np.random.PCG64(5))
@@ -129,9 +184,16 @@ def test_teacher_forced_steps(mods, E, N, T):
         agree += int(same.sum())
         total += same.size
         ok = same.all(axis=2)[0]
-        scale = Hp.step_scale(pa)[ok]
+        scale = _step_unit(scn, pa, pl)[ok]
         Hp.assert_close_step(last[ok], rlast[ok], "next obs", scale[:, None, None])
-        Hp.assert_close_step(rew[0][ok], rrew[0][ok], "reward", scale)
+        if tag:
+            # rewards hold integers decided by a distance comparison: leave out the envs whose (good, adversary)
+            # distance lies within 1e-5 of the touching threshold
+            from tests.test_tag_gpu import _reward_unambiguous
+            sel = _reward_unambiguous(orc.get_state()[0], scn)[ok] & (rdone[0][ok] == 0)   # (a reset env has lost its post-step positions)
+            Hp.assert_close_step(rew[0][ok][sel], rrew[0][ok][sel], "reward", scale[sel][:, None])
+        else:
+            Hp.assert_close_step(rew[0][ok], rrew[0][ok], "reward", scale)
         # carried state after the step (all rows: it does not depend on the sampled action)
         h1 = env.get_hidden().cpu().numpy().astype(np.float64)
         rh1 = orc.get_hidden()
@@ -158,9 +220,9 @@ def test_teacher_forced_steps(mods, E, N, T):
         "%d with fragile embedding outputs, %d with a fragile observation entry; %d rows deviate by more than 1e-5; "
         "worst deviation / bound %.2f"
         % (agree / total, total, rows, rows_clean, worst_clean, rows_fragile, rows_obs_fragile, deviating, worst_ratio))
-    Hp.record("recurrent policy E=%d N=%d: carried state of %d rows: %d clean rows within %.2e, %d rows with fragile bf16 roundings "
+    Hp.record("recurrent policy E=%d scenario=%s: carried state of %d rows: %d clean rows within %.2e, %d rows with fragile bf16 roundings "
               "within %.2f of their first-order bound, %d rows with a fragile observation entry; actions %.5f equal over %d"
-              % (E, N, rows, rows_clean, worst_clean, rows_fragile, worst_ratio, rows_obs_fragile, agree / total, total))
+              % (E, scn, rows, rows_clean, worst_clean, rows_fragile, worst_ratio, rows_obs_fragile, agree / total, total))
     assert agree / total >= 0.9995
     # Most rows are clean, few are left to the loose bound, and nothing deviates that has no fragile rounding.
     # (Fragile roundings are common here by the nature of the workload: an embedding output near zero lies on a
@@ -171,39 +233,43 @@ def test_teacher_forced_steps(mods, E, N, T):
     env.close()
 
 
-@pytest.mark.parametrize("E,N", [(200, 3), (64, 2), (90, 4), (50, 5)])
-def test_free_running_statistics(mods, E, N):
+@pytest.mark.parametrize("E,scn", [(200, 3), (64, 2), (90, 4), (50, 5), (48, 6), (40, 8), (35, 10),
+                                   (128, (4, 2, 3)), (100, (2, 1, 1)), (90, (3, 0, 2)), (60, (6, 2, 4))])
+def test_free_running_statistics(mods, E, scn):
     """Free-running episodes: actions equal until the first bf16 rounding flip that changes a
     sample; the share of (env, agent, step) samples that agree stays high over an episode."""
-    say("recurrent policy, free running E=%d N=%d" % (E, N))
-    env, orc, _ = _pair(mods, E, N)
+    say("recurrent policy, free running E=%d scenario=%s" % (E, scn))
+    env, orc, w = _pair(mods, E, scn)
     orc.reset(7)
     env.reset(7)
     T = 25
     obs, act, rew, done, last = [x.cpu().numpy() for x in env.rollout(T, *env.empty_traj(T))]
     robs, ract, rrew, rdone, rlast = orc.rollout(T)
     assert np.array_equal(done, rdone)
-    assert np.array_equal(obs[0].astype(np.float64), robs[0])
+    _assert_first_obs(scn, obs[0], robs[0])
     same = (act == ract).all(axis=2)
     alive = np.logical_and.accumulate(same, axis=0)
     say("  envs identical after 5 / 25 steps: %.3f / %.3f" % (alive[4].mean(), alive[-1].mean()))
-    assert alive[4].mean() > 0.98 and alive[-1].mean() > 0.95
+    # with many agents per env one flipped sample anywhere ends the env's agreement
+    many = env.N > 5
+    assert alive[4].mean() > (0.95 if many else 0.98) and alive[-1].mean() > (0.85 if many else 0.95)
     # while an env's actions agree its trajectory does too
-    prior = np.vstack([np.ones((1, E), bool), alive[:-1]])
-    e = np.abs(obs.astype(np.float64) - robs).reshape(T, E, -1).max(axis=2)
-    assert (e * prior).max() < 1e-3
+    _assert_free_running(mods, scn, 1, E, w, 7, obs, act, rew, robs, ract, rrew,
+                         "recurrent policy, free running E=%d scenario=%s" % (E, scn))
     assert not env.get_hidden().any()          # the episode ended at the last step
     env.close()
 
 
-@pytest.mark.parametrize("N,reward_mode", [(3, 0), (3, 1), (1, 0), (2, 0)])
+@pytest.mark.parametrize("N,reward_mode", [(3, 0), (3, 1), (1, 0), (2, 0), (6, 0), (10, 1), ((4, 2, 3), 0), ((6, 2, 4), 0)])
 def test_state_carry_time_slots_and_null_outputs(mods, N, reward_mode):
     """T steps = T1 + T2 steps bit for bit (the carried state crosses the call boundary and an
     episode end), one step at a time too; NULL outputs are not written; runs are deterministic."""
     MpeEnv, _ = mods
     E, T = 100, 30
-    w = Hp.to_dev(synth.gru_weights(9, 1, 6 * N))
-    envs = [MpeEnv(Hp.gpu_config(E, N, 1, 128, 1, reward_mode=reward_mode)) for _ in range(4)]
+    scn = N
+    envs = [MpeEnv(_configs(E, scn, reward_mode=reward_mode)[0]) for _ in range(4)]
+    N = envs[0].N
+    w = Hp.to_dev(synth.gru_weights(9, 1, envs[0].D))
     for e in envs:
         e.set_gru_policy(*w)
         e.reset(4)
@@ -268,8 +334,8 @@ def test_removing_the_recurrent_policy_and_refusals(mods):
         env.set_gru_policy(*w[:9], None)
     assert ei.value.code == MPE_EINVAL
     env.close()
-    for cfg in (Hp.gpu_config(64, 3, 1, 64, 0), Hp.gpu_config(64, 3, 1, 128, 0), Hp.gpu_config(64, 6, 1, 128, 1),
-                Hp.tag_gpu_config(64, 4, 2, 3, 1, 64)):
+    for cfg in (Hp.gpu_config(64, 3, 1, 64, 0), Hp.gpu_config(64, 3, 1, 128, 0), Hp.gpu_config(64, 6, 1, 64, 1),
+                Hp.tag_gpu_config(64, 4, 2, 3, 1, 64), Hp.tag_gpu_config(64, 4, 2, 3, 1, 128, wd=0)):
         env = MpeEnv(cfg)
         with pytest.raises(MpeError) as ei:
             env.set_gru_policy(*Hp.to_dev(synth.gru_weights(2, 1, env.D)))
@@ -285,31 +351,28 @@ def test_removing_the_recurrent_policy_and_refusals(mods):
     env.close()
 
 
-@pytest.mark.parametrize("E,N,R", [(64, 3, 3), (16, 3, 5), (48, 2, 2), (32, 1, 4), (128, 3, 2), (32, 4, 3), (16, 5, 4)])
+@pytest.mark.parametrize("E,N,R", [(64, 3, 3), (16, 3, 5), (48, 2, 2), (32, 1, 4), (128, 3, 2), (32, 4, 3), (16, 5, 4),
+                                   (16, 7, 3), (32, 10, 2), (32, (4, 2, 3), 3), (16, (6, 2, 4), 2), (64, (2, 1, 1), 2)])
 def test_several_runs_with_their_own_weights(mods, E, N, R):
     """One set of recurrent-policy weights per run (blocks of 64, 32 or 16 envs inside a run): free-running
     episodes against the oracle's runs, carried state included."""
-    say("recurrent policy, %d runs x %d envs, N=%d" % (R, E, N))
-    MpeEnv, Oracle = mods
-    env = MpeEnv(Hp.gpu_config(E, N, R, 128, 1))
-    orc = Oracle(Hp.oracle_config(E, N, R, 128, 1), threads=8)
-    w = synth.gru_weights(9, R, 6 * N)
-    env.set_gru_policy(*Hp.to_dev(w))
-    orc.set_gru(*w)
+    say("recurrent policy, %d runs x %d envs, scenario=%s" % (R, E, N))
+    scn = N
+    env, orc, w = _pair(mods, E, scn, wseed=9, R=R)
+    N = env.N
     orc.reset(7)
     env.reset(7)
     T, TE = 12, E * R
     obs, act, rew, done, last = [x.cpu().numpy() for x in env.rollout(T, *env.empty_traj(T))]
     robs, ract, rrew, rdone, rlast = orc.rollout(T)
     assert np.array_equal(done, rdone)
-    assert np.array_equal(obs[0].astype(np.float64), robs[0])
+    _assert_first_obs(scn, obs[0], robs[0])
     same = (act == ract).all(axis=2)
     alive = np.logical_and.accumulate(same, axis=0)
     say("  envs identical after 5 / 12 steps: %.3f / %.3f" % (alive[4].mean(), alive[-1].mean()))
-    assert alive[4].mean() > 0.97 and alive[-1].mean() > 0.93
-    prior = np.vstack([np.ones((1, TE), bool), alive[:-1]])
-    e = np.abs(obs.astype(np.float64) - robs).reshape(T, TE, -1).max(axis=2)
-    assert (e * prior).max() < 1e-3
+    assert alive[4].mean() > (0.9 if N > 5 else 0.97) and alive[-1].mean() > (0.85 if N > 5 else 0.93)
+    _assert_free_running(mods, scn, R, E, w, 7, obs, act, rew, robs, ract, rrew,
+                         "recurrent policy, %d runs x %d envs, scenario=%s" % (R, E, scn))
     d = np.abs(env.get_hidden().cpu().numpy().astype(np.float64) - orc.get_hidden())[alive[-1]]
     assert d.size and np.median(d) < 1e-4 and d.max() < 5e-2
     a0 = act[0].reshape(R, E, N)

@@ -110,12 +110,17 @@ def test_tag_kernels(mods, E, shape, H, wd):
 
 
 @pytest.mark.parametrize("E", SIZES)
-@pytest.mark.parametrize("N", [1, 2, 3])
+@pytest.mark.parametrize("N", [1, 2, 3, 7, (4, 2, 3)])
 def test_recurrent_kernel(mods, E, N):
+    """N: agents of simple spread, or (agents, landmarks, adversaries) of predator-prey."""
     MpeEnv, Oracle = mods
-    env = MpeEnv(Hp.gpu_config(E, N, 1, 128, 1))
-    orc = Oracle(Hp.oracle_config(E, N, 1, 128, 1), threads=4)
-    w = synth.gru_weights(6, 1, 6 * N)
+    if isinstance(N, tuple):
+        env = MpeEnv(Hp.tag_gpu_config(E, N[0], N[1], N[2], 1, 128, wd=1))
+        orc = Oracle(Hp.tag_oracle_config(E, N[0], N[1], N[2], 1, 128, wd=1), threads=4)
+    else:
+        env = MpeEnv(Hp.gpu_config(E, N, 1, 128, 1))
+        orc = Oracle(Hp.oracle_config(E, N, 1, 128, 1), threads=4)
+    w = synth.gru_weights(6, 1, env.D)
     env.set_gru_policy(*Hp.to_dev(w))
     orc.set_gru(*w)
     ok = _check(env, orc, 11 + E, exact_actions=False, min_agree=0.95)
