@@ -118,8 +118,8 @@ typedef struct {
  * scenario and its constants given as a struct instead of a name.
  * Validate `cfg` (host only), then allocate the device state of TE environments:
  * pos_a, vel_a [2][N][TE] fp32, pos_l [2][L][TE] fp32, ep_step [TE] int32.
- * MPE_SCENARIO_TAG is built for (N, L, good agents) in (4, 2, 1), (2, 1, 1), (3, 0, 1), (6, 2, 2);
- * MPE_EINVAL for other shapes.
+ * MPE_SCENARIO_TAG is built for (N, L, good agents) in (4, 2, 1), (2, 1, 1), (3, 0, 1), (6, 2, 2),
+ * (5, 2, 1), (8, 2, 2), (10, 3, 2); MPE_EINVAL for other shapes.
  * `*out` receives the handle.  MPE_EINVAL for a bad config, MPE_EHIP if allocation fails. */
 int mpe_create(const mpe_config* cfg, mpe_env** out);
 
@@ -159,8 +159,8 @@ int mpe_step(mpe_env* env, const uint8_t* actions, float* obs, float* reward, ui
  * operand layout on `stream` (rounding W to bf16, ties to even, when weight_dtype is
  * MPE_WEIGHTS_BF16); the caller's arrays are not referenced after that work has run.
  * Policies are built for (num_agents, hidden, weight_dtype) in (1..3, 64, fp32 or bf16) and
- * (4..10, 64 | 128, bf16); with MPE_SCENARIO_TAG for hidden 64, fp32 or bf16, and the shapes with D <= 16
- * (all but (6, 2, 2)).  MPE_EINVAL for other shapes, if only some pointers are NULL, or if the config has no
+ * (4..10, 64 | 128, bf16); with MPE_SCENARIO_TAG for hidden 64, fp32 or bf16, every shape of mpe_create
+ * (D <= 32).  MPE_EINVAL for other shapes, if only some pointers are NULL, or if the config has no
  * usable `hidden`. */
 int mpe_set_policy(mpe_env* env, const float* W1, const float* b1, const float* W2,
                    const float* b2, const float* W3, const float* b3, void* stream);
@@ -219,8 +219,8 @@ int mpe_set_hidden(mpe_env* env, const float* hidden, void* stream);
  * V1 [R][D][H], c1 [R][H], V2 [R][H][H], c2 [R][H], V3 [R][H], c3 [R], fp32 device pointers;
  * copied (and rounded, with MPE_WEIGHTS_BF16) as in mpe_set_policy.  Built for the shapes of
  * mpe_set_policy with MPE_SCENARIO_SPREAD (1..3 agents, hidden 64, fp32 or bf16 weights; 4..10 agents,
- * hidden 64 or 128, bf16 weights), and for MPE_SCENARIO_TAG with fp32 weights, hidden 64 and
- * observation rows of at most 16 floats; MPE_EINVAL otherwise. */
+ * hidden 64 or 128, bf16 weights), and for MPE_SCENARIO_TAG with hidden 64, fp32 or bf16 weights;
+ * MPE_EINVAL otherwise. */
 int mpe_set_critic(mpe_env* env, const float* V1, const float* c1, const float* V2,
                    const float* c2, const float* V3, const float* c3, void* stream);
 
@@ -232,7 +232,8 @@ int mpe_set_critic(mpe_env* env, const float* V1, const float* c1, const float* 
  * mpe_rollout (rewards [T][TE][N] where mpe_rollout's are).  Any of the eight may be NULL.  Needs
  * a policy and a critic (MPE_ESTATE if one is missing); with several runs num_envs must be a
  * multiple of 16 (fastest: of 256; 4 and more agents: of 64, of 32 with 8 agents;
- * MPE_SCENARIO_TAG: fastest with multiples of 512 / num_agents, of 64 with 3 agents), MPE_EINVAL
+ * MPE_SCENARIO_TAG: fastest with multiples of 512 / num_agents where that divides 64, else of 64, of 32
+ * with 10 agents), MPE_EINVAL
  * otherwise. */
 int mpe_rollout_ac(mpe_env* env, int32_t T, float* obs_traj, uint8_t* act_traj, float* logp_traj,
                    float* value_traj, float* rew_traj, uint8_t* done_traj, float* last_obs,

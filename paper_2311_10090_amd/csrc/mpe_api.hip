@@ -302,7 +302,7 @@ int mpe_set_policy(mpe_env* e, const float* W1, const float* b1, const float* W2
   if (e->tag) {
     if (!tag_policy_supported(e->N, e->L, e->G, e->H, e->cfg.weight_dtype))
       return fail(MPE_EINVAL, "mpe_set_policy: MPE_SCENARIO_TAG policies are built for hidden 64 and observation "
-                              "rows of at most 16 floats");
+                              "rows of at most 32 floats");
     err = pack_policy_tag(e->pol, e->N, e->L, e->G, int(e->R), e->cfg.weight_dtype == MPE_WEIGHTS_BF16, 5, W1, b1, W2,
                           b2, W3, b3, static_cast<hipStream_t>(stream));
   } else {
@@ -428,11 +428,11 @@ int mpe_set_critic(mpe_env* e, const float* V1, const float* c1, const float* V2
   hipError_t err;
   e->has_critic = false;   // as in mpe_set_policy
   if (e->tag) {
-    if (e->cfg.weight_dtype != MPE_WEIGHTS_FP32 || !tag_policy_supported(e->N, e->L, e->G, e->H, e->cfg.weight_dtype))
+    if (!tag_policy_supported(e->N, e->L, e->G, e->H, e->cfg.weight_dtype))
       return fail(MPE_EINVAL, "mpe_set_critic: unsupported shape: the MPE_SCENARIO_TAG actor-critic rollout is built "
-                              "for fp32 weights, hidden 64 and observation rows of at most 16 floats");
-    err = pack_policy_tag(e->critic, e->N, e->L, e->G, int(e->R), false, 1, V1, c1, V2, c2, V3, c3,
-                          static_cast<hipStream_t>(stream));
+                              "for hidden 64 and observation rows of at most 32 floats");
+    err = pack_policy_tag(e->critic, e->N, e->L, e->G, int(e->R), e->cfg.weight_dtype == MPE_WEIGHTS_BF16, 1, V1, c1,
+                          V2, c2, V3, c3, static_cast<hipStream_t>(stream));
   } else if (e->cfg.weight_dtype == MPE_WEIGHTS_BF16 && wide_supported(e->N, e->H)) {
     err = pack_policy_wide(e->critic, e->N, e->H, int(e->R), V1, c1, V2, c2, V3, c3, 1, static_cast<hipStream_t>(stream));
   } else {
@@ -460,7 +460,6 @@ int mpe_rollout_ac(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, fl
   if (e->has_gru) return fail(MPE_ESTATE, "mpe_rollout_ac: remove the recurrent policy first (feed-forward networks only)");
   const bool wide = !e->tag && e->cfg.weight_dtype == MPE_WEIGHTS_BF16 && wide_supported(e->N, e->H);
   if (!e->tag && !wide && !f32_supported(e->N, e->H)) return fail(MPE_EINVAL, "mpe_rollout_ac: unsupported shape");
-  if (e->tag && e->cfg.weight_dtype != MPE_WEIGHTS_FP32) return fail(MPE_EINVAL, "mpe_rollout_ac: unsupported shape");
   for (const float* p : {obs_traj, logp_traj, value_traj, rew_traj, last_obs, last_value})
     if (p && !aligned16(p)) return fail(MPE_EINVAL, "mpe_rollout_ac: float outputs must be 16-byte aligned");
   if (uint64_t(e->abs_step) + uint64_t(T) > 0xFFFFFFFFull)
@@ -476,8 +475,8 @@ int mpe_rollout_ac(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, fl
     TA.r = A;
     TA.tg = e->tg;
     TA.actions_in = nullptr;
-    err = launch_tag_rollout(e->N, e->L, e->G, 4, TA, e->pol.packed, e->critic.packed,
-                             static_cast<hipStream_t>(stream), &why);
+    err = launch_tag_rollout(e->N, e->L, e->G, e->cfg.weight_dtype == MPE_WEIGHTS_BF16 ? 5 : 4, TA, e->pol.packed,
+                             e->critic.packed, static_cast<hipStream_t>(stream), &why);
   } else if (wide) {
     err = launch_rollout_ac_wide(e->N, e->H, A, e->pol, e->critic, static_cast<hipStream_t>(stream), &why);
   } else {

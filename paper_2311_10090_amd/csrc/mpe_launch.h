@@ -82,7 +82,7 @@ void launch_tag_reset(int N, int L, int G, const StatePtrs& st, uint32_t TE, uin
                       hipStream_t s);
 // mode 0: one step under A.actions_in (r.T must be 1; obs after the step -> r.last_obs, reward ->
 // r.rew_traj, done -> r.done_traj); mode 1: uniform random actions; mode 2: the packed fp32 policy;
-// mode 3: the packed bf16 policy; mode 4: the packed fp32 policy and critic (actor-critic outputs in r)
+// mode 3: the packed bf16 policy; mode 4 / 5: the packed fp32 / bf16 policy and critic (actor-critic outputs in r)
 hipError_t launch_tag_rollout(int N, int L, int G, int mode, const TagArgs& A, const void* packed,
                               const void* packed_critic, hipStream_t s, const char** why);
 struct PolicyBuffers;

@@ -3,8 +3,10 @@
 // and the forward pass of two 16-row tiles (fp32 split-operand and bf16 variants).  Shared by the kernels
 // of both scenarios; everything is templated on a shape S:
 //   S::D         floats per observation row in the LDS tile (row stride)
-//   S::KIN       leading inputs of a row that the first layer reads (<= 16; the rest of the row is
-//                zero in every observation)
+//   S::KIN       leading inputs of a row that the first layer reads (<= 32; the rest of the row is
+//                zero in every observation); up to 16 inputs ride in half of an instruction's K
+//                positions and the other half carries a second term (S::kWideIn false), 17..32 inputs
+//                fill the K slice and layer 1 takes the six instructions of any other product
 //   S::kRowTerms layer 3 with the weight terms along the output rows (needs 7 scratch floats per row)
 #pragma once
 
@@ -17,7 +19,8 @@ struct NetShape {
   static constexpr int D = D_;
   static constexpr int KIN = KIN_;
   static constexpr bool kRowTerms = KIN_ >= 7;
-  static_assert(KIN_ <= 16 && KIN_ <= D_ && D_ % 2 == 0, "layer 1 reads 16 inputs, rows are float2-aligned");
+  static constexpr bool kWideIn = KIN_ > 16;
+  static_assert(KIN_ <= 32 && KIN_ <= D_ && D_ % 2 == 0, "layer 1 reads one K slice, rows are float2-aligned");
 };
 
 namespace {
@@ -78,6 +81,7 @@ __device__ __forceinline__ void split3(float x, uint32_t& h, uint32_t& m, uint32
 //                                 gq < 2) carry one term of input k' = 8 (gq & 1) + e, positions
 //                                 16..31 (gq >= 2) another term of the same inputs.
 //                                 combo 0 = (h | m), combo 1 = (h | l)
+//   W1A [m 4][term 3][lane 64]   shapes with 17..32 inputs (kWideIn): k = 8 gq + e, all three terms
 //   W2A [m 4][s 2][term 3][lane 64]
 //   W3A [s 2][term 3][lane 64]   (5 outputs padded to 16), shapes without kRowTerms only
 //   W3A [s 2][lane 64]           kRowTerms: the 16 output rows of the instruction carry the three
@@ -86,12 +90,12 @@ __device__ __forceinline__ void split3(float x, uint32_t& h, uint32_t& m, uint32
 //   bias b1*pre [64], b2*pre [64], b3 [16] fp32 (kRowTerms: b3 in the h-term row of each output)
 //
 // bf16 variant (BF): one term per weight, rounded to bf16 (nearest even), nothing pre-scaled:
-//   W1A [m 4][lane 64]  (K positions 16..31 are zero), W2A [m 4][s 2][lane 64], W3A [s 2][lane 64]
+//   W1A [m 4][lane 64]  (K positions 16..31 are zero unless kWideIn), W2A [m 4][s 2][lane 64], W3A [s 2][lane 64]
 //   (5 outputs padded to 16), bias b1 [64], b2 [64], b3 [16] fp32
-template <bool BF>
+template <bool BF, bool WIDE_IN = false>
 struct PkT {
   static constexpr size_t OFF_W1A = 0;
-  static constexpr size_t W1A_BYTES = BF ? 4 * 64 * 16 : 4 * 2 * 64 * 16;
+  static constexpr size_t W1A_BYTES = BF ? 4 * 64 * 16 : (WIDE_IN ? 4 * 3 * 64 * 16 : 4 * 2 * 64 * 16);
   static constexpr size_t OFF_W2A = OFF_W1A + W1A_BYTES;
   static constexpr size_t W2A_BYTES = BF ? 4 * 2 * 64 * 16 : 4 * 2 * 3 * 64 * 16;
   static constexpr size_t OFF_W3A = OFF_W2A + W2A_BYTES;
@@ -121,6 +125,7 @@ __global__ void pack_split_kernel(uint8_t* __restrict__ packed, const float* __r
                                   const float* __restrict__ b2, const float* __restrict__ W3,
                                   const float* __restrict__ b3, int nout) {
   // nout = outputs of the last layer: 5 (policy logits) or 1 (critic value); W3 is [H][nout]
+  using Pk = PkT<false, S::kWideIn>;
   constexpr int D = S::D, KIN = S::KIN;
   const int run = blockIdx.y;
   uint8_t* out = packed + size_t(run) * Pk::RUN_BYTES;
@@ -143,6 +148,11 @@ __global__ void pack_split_kernel(uint8_t* __restrict__ packed, const float* __r
   };
   if (idx < n1) {
     const int e = idx % 8, lane = (idx / 8) % 64, m = idx / 512;
+    if constexpr (S::kWideIn) {
+      const int k = 8 * (lane / 16) + e;
+      put3(Pk::OFF_W1A, m, 64, lane, e, k < KIN ? kPre * W1[size_t(k) * kH + 16 * m + lane % 16] : 0.0f);
+      return;
+    }
     const int gq = lane / 16, k = 8 * (gq & 1) + e, o = 16 * m + lane % 16;
     uint32_t h, mm, l;
     split3(k < KIN ? kPre * W1[size_t(k) * kH + o] : 0.0f, h, mm, l);
@@ -259,11 +269,12 @@ __device__ __forceinline__ Terms tanh_split(const f32x4& a0, const f32x4& a1) {
 // VALUE: the network has one output (a critic); it goes to valX[j] / valY[j] and the rows are
 // left untouched.
 // The network itself, registers in and out: vx / vy = this lane's 8 inputs of tile X / Y (lane (j, gq):
-// inputs 8 (gq & 1) .. + 7 of row j), zX / zY = the layer-3 accumulators of the two tiles.
+// inputs 8 (gq & 1) .. + 7 of row j; kWideIn: inputs 8 gq .. + 7, zero beyond the row), zX / zY = the layer-3 accumulators of the two tiles.
 template <typename S>
 __device__ __forceinline__ void policy_core(const uint8_t* __restrict__ wsm, const float* __restrict__ bias,
                                             const W3Terms& w3, const float (&vx)[8], const float (&vy)[8],
                                             f32x4& zX, f32x4& zY, int lane) {
+  using Pk = PkT<false, S::kWideIn>;
   const int gq = lane >> 4;
   // The network runs at a raised wavefront priority: a wavefront that has matrix instructions to issue goes
   // ahead of the wavefronts of its SIMD that are in the (vector-only) env step, whose instructions then fill
@@ -279,11 +290,18 @@ __device__ __forceinline__ void policy_core(const uint8_t* __restrict__ wsm, con
     wsm += zero;
     bias += zero;
   }
-  const bf16x8* w1 = reinterpret_cast<const bf16x8*>(wsm + Pk::OFF_W1A);  // [m][combo][lane64]
+  const bf16x8* w1 = reinterpret_cast<const bf16x8*>(wsm + Pk::OFF_W1A);  // [m][combo][lane64]; kWideIn: [m][term][lane64]
   const bf16x8* w2 = reinterpret_cast<const bf16x8*>(wsm + Pk::OFF_W2A);  // [m][s][term][lane64]
   // Layer 1, one output tile: the six cross terms in three instructions, smallest first:
   //   (Wh | Wl) x (Xl | Xh) = hl + lh,  (Wh | Wm) x (Xm | Xm) = hm + mm,  (Wh | Wm) x (Xh | Xh) = hh + mh
   auto layer1 = [&](int m, const Terms& b, const bf16x8& b_lh, f32x4 acc) {
+    if constexpr (S::kWideIn) {   // 17..32 inputs fill the K slice: the six cross terms, one instruction each
+      Terms a;
+      a.h = w1[(m * 3 + 0) * 64 + lane];
+      a.m = w1[(m * 3 + 1) * 64 + lane];
+      a.l = w1[(m * 3 + 2) * 64 + lane];
+      return mma_split(a, b, acc);
+    }
     const bf16x8 a_hm = w1[(m * 2 + 0) * 64 + lane];
     const bf16x8 a_hl = w1[(m * 2 + 1) * 64 + lane];
     acc = MPE_MFMA_SPLIT(a_hl, b_lh, acc);
@@ -410,6 +428,25 @@ __device__ __forceinline__ void policy_core(const uint8_t* __restrict__ wsm, con
   __builtin_amdgcn_s_setprio(0);
 }
 
+// This lane's 8 layer-1 inputs of row j (see policy_core): columns 8 (gq & 1) .. + 7, or, with 17..32 inputs,
+// columns 8 gq .. + 7 with zeros beyond the row's D columns (what lies there is the next row).
+template <typename S>
+__device__ __forceinline__ void load_row_inputs(const float* __restrict__ rows, int j, int gq, float (&v)[8]) {
+  constexpr int D = S::D;
+  const int c0 = S::kWideIn ? 8 * gq : 8 * (gq & 1);
+  // rows are D*4 bytes apart (a multiple of 8, not of 16): read as float2
+  const float2* src = reinterpret_cast<const float2*>(rows + j * D + c0);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    float2 x = src[q];
+    if constexpr (S::kWideIn) {
+      if (c0 + 2 * q >= D) x = make_float2(0.0f, 0.0f);
+    }
+    v[2 * q] = x.x;
+    v[2 * q + 1] = x.y;
+  }
+}
+
 template <typename S, bool VALUE = false>
 __device__ __forceinline__ void policy_pair(const uint8_t* __restrict__ wsm, const float* __restrict__ bias,
                                             const W3Terms& w3, float* __restrict__ rowsX,
@@ -418,17 +455,8 @@ __device__ __forceinline__ void policy_pair(const uint8_t* __restrict__ wsm, con
   constexpr int D = S::D;
   const int j = lane & 15, gq = lane >> 4;
   float vx[8], vy[8];
-  {
-    // rows are D*4 bytes apart (a multiple of 8, not of 16): read as float2
-    const float2* xs = reinterpret_cast<const float2*>(rowsX + j * D + 8 * (gq & 1));
-    const float2* ys = reinterpret_cast<const float2*>(rowsY + j * D + 8 * (gq & 1));
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const float2 xv = xs[q], yv = ys[q];
-      vx[2 * q] = xv.x; vx[2 * q + 1] = xv.y;
-      vy[2 * q] = yv.x; vy[2 * q + 1] = yv.y;
-    }
-  }
+  load_row_inputs<S>(rowsX, j, gq, vx);
+  load_row_inputs<S>(rowsY, j, gq, vy);
   f32x4 zX, zY;
   policy_core<S>(wsm, bias, w3, vx, vy, zX, zY, lane);
   if constexpr (VALUE) {
@@ -486,10 +514,10 @@ __global__ void pack_bf16_kernel(uint8_t* __restrict__ packed, const float* __re
   b3 += size_t(run) * nout;
   constexpr int n1 = 4 * 64 * 8, n2 = 4 * 2 * 64 * 8, n3 = 2 * 64 * 8, nb = 2 * kH + 16;
   int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx < n1) {   // [m][lane][e]; k = 8 gq + e for gq < 2, zero above
+  if (idx < n1) {   // [m][lane][e]; k = 8 gq + e for gq < 2, zero above (all four lane groups when kWideIn)
     const int e = idx % 8, lane = (idx / 8) % 64, m = idx / 512;
     const int gq = lane / 16, k = 8 * gq + e, o = 16 * m + lane % 16;
-    reinterpret_cast<uint16_t*>(out + PkB::OFF_W1A)[idx] = f32_to_bf16_rne((gq < 2 && k < KIN) ? W1[size_t(k) * kH + o] : 0.0f);
+    reinterpret_cast<uint16_t*>(out + PkB::OFF_W1A)[idx] = f32_to_bf16_rne(((gq < 2 || S::kWideIn) && k < KIN) ? W1[size_t(k) * kH + o] : 0.0f);
     return;
   }
   idx -= n1;
@@ -552,17 +580,18 @@ __device__ __forceinline__ void policy_pair_bf(const uint8_t* __restrict__ wsm, 
   }
   const bf16x8* w1 = reinterpret_cast<const bf16x8*>(wsm + PkB::OFF_W1A);  // [m][lane]
   const bf16x8* w2 = reinterpret_cast<const bf16x8*>(wsm + PkB::OFF_W2A);  // [m][s][lane]
-  // layer-1 B operands: inputs 8 (gq & 1) .. + 7 of the row; lane groups 2, 3 meet zero weights
+  // layer-1 B operands: inputs 8 (gq & 1) .. + 7 of the row, lane groups 2, 3 meet zero weights; with
+  // 17..32 inputs, inputs 8 gq .. + 7
   bf16x8 bx, by;
   {
-    const float2* xs = reinterpret_cast<const float2*>(rowsX + j * D + 8 * (gq & 1));
-    const float2* ys = reinterpret_cast<const float2*>(rowsY + j * D + 8 * (gq & 1));
+    float vx[8], vy[8];
+    load_row_inputs<S>(rowsX, j, gq, vx);
+    load_row_inputs<S>(rowsY, j, gq, vy);
     u32x4 px, py;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const float2 xv = xs[q], yv = ys[q];
-      px[q] = pack_bf16_rne(xv.x, xv.y);
-      py[q] = pack_bf16_rne(yv.x, yv.y);
+      px[q] = pack_bf16_rne(vx[2 * q], vx[2 * q + 1]);
+      py[q] = pack_bf16_rne(vy[2 * q], vy[2 * q + 1]);
     }
     bx = __builtin_bit_cast(bf16x8, px);
     by = __builtin_bit_cast(bf16x8, py);

@@ -727,7 +727,7 @@ void launch_fill_zero(float* p, size_t n, hipStream_t s) {
 }
 
 // Simple spread with 1..10 agents and every predator-prey shape that is built; hidden 128, bf16 weights.
-#define MPE_GRU_TAG_SHAPES(X) X(4, 2, 1) X(2, 1, 1) X(3, 0, 1) X(6, 2, 2)
+#define MPE_GRU_TAG_SHAPES(X) X(4, 2, 1) X(2, 1, 1) X(3, 0, 1) X(6, 2, 2) X(5, 2, 1) X(8, 2, 2) X(10, 3, 2)
 
 bool gru_supported(bool tag, int N, int L, int G, int H, int weight_dtype) {
   if (H != kG || weight_dtype != 1) return false;

@@ -16,9 +16,11 @@ namespace mpe {
 
 namespace {
 
-// kPolicy / kPolicyBf: fp32 (split-operand) / bf16 policy.  kPolicyAc: fp32 policy plus a critic of the same
-// shape with one output: log-probability of the sampled action and value per agent and step.
-enum TagMode : int { kGiven = 0, kUniform = 1, kPolicy = 2, kPolicyBf = 3, kPolicyAc = 4 };
+// kPolicy / kPolicyBf: fp32 (split-operand) / bf16 policy.  kPolicyAc / kPolicyAcBf: the policy plus a critic
+// of the same shape with one output: log-probability of the sampled action and value per agent and step.
+enum TagMode : int { kGiven = 0, kUniform = 1, kPolicy = 2, kPolicyBf = 3, kPolicyAc = 4, kPolicyAcBf = 5 };
+constexpr bool mode_is_ac(int mode) { return mode == kPolicyAc || mode == kPolicyAcBf; }
+constexpr bool mode_is_bf(int mode) { return mode == kPolicyBf || mode == kPolicyAcBf; }
 
 // EB = envs per block.  Plain rollouts: 64.  Actor-critic: both packed images (79 KB) are staged per block,
 // so a block is 8 wavefronts where the shape allows it (wavefront-local shapes need no block barrier).
@@ -27,15 +29,15 @@ enum TagMode : int { kGiven = 0, kUniform = 1, kPolicy = 2, kPolicyBf = 3, kPoli
 template <typename S, int MODE, int EB = 64, int RW = 64>
 struct TagSmem {
   static constexpr int ROWS = (EB * S::N + RW - 1) / RW * RW;
-  static constexpr bool kAc = MODE == kPolicyAc;
+  static constexpr bool kAc = mode_is_ac(MODE);
   static constexpr bool kHasPolicy = MODE == kPolicy || MODE == kPolicyBf || kAc;
-  using P = PkT<MODE == kPolicyBf>;
+  using P = PkT<mode_is_bf(MODE), (S::D > 16)>;
   // plain policy: W1A, W2A, then the biases (W3A lives in registers); actor-critic: the whole image of
   // the policy, then the whole image of the critic (their W3A are re-read every step)
   static constexpr size_t OFF_BIAS = kAc ? P::OFF_BIAS : (kHasPolicy ? P::LDS_BYTES : 0);
   static constexpr size_t OFF_CRITIC = P::RUN_BYTES;                                    // kAc only
   static constexpr size_t OFF_OBS = kAc ? 2 * P::RUN_BYTES : OFF_BIAS + (kHasPolicy ? P::BIAS_BYTES : 0);
-  static constexpr size_t OBS = size_t(ROWS) * S::D * 4 + 64;   // + zeroed tail: layer 1 reads 16 cols
+  static constexpr size_t OBS = size_t(ROWS) * S::D * 4 + 64;   // + zeroed tail: layer 1 reads 16 (32) cols
   static constexpr size_t OFF_XCH = OFF_OBS + OBS;              // [parity][ROWS] float4 (px, py, vx, vy)
   static constexpr size_t OFF_VALUE = OFF_XCH + size_t(S::kWaveLocal ? 1 : 2) * ROWS * 16;   // kAc: [ROWS] float
   static constexpr size_t TOTAL = OFF_VALUE + (kAc ? size_t(ROWS) * 4 : 0);
@@ -88,15 +90,24 @@ __global__ __launch_bounds__(64 * S::N) void tag_reset_kernel(StatePtrs st, uint
 // RW = rows per wavefront: 64 (one lane per row), or 32 for small batches of the policy modes: twice the
 // wavefronts, one pair of 16-row tiles each; lanes 32..63 are exact clones of lanes 0..31 (same row, same
 // inputs, same arithmetic, so their LDS writes repeat the same values) that store nothing to global memory.
+// Wavefronts per SIMD the register budget is set for: three blocks per CU for the plain policy kernels whose
+// LDS allows it, one block otherwise.
+template <typename S, int MODE, int EB, int RW>
+struct TagOccupancy {
+  static constexpr bool kThree =
+      (MODE == kPolicy || MODE == kPolicyBf) && RW == 64 && 3 * TagSmem<S, MODE, EB, RW>::TOTAL <= 160 * 1024;
+  static constexpr int kWavesPerSimd = kThree ? 3 : 1;
+};
+
 template <typename S, int MODE, int EB = 64, int RW = 64>
-__global__ __launch_bounds__((EB * S::N + RW - 1) / RW * 64, ((MODE == kPolicy || MODE == kPolicyBf) && RW == 64) ? 3 : 1) void tag_rollout_kernel(
+__global__ __launch_bounds__((EB * S::N + RW - 1) / RW * 64, (TagOccupancy<S, MODE, EB, RW>::kWavesPerSimd)) void tag_rollout_kernel(
     TagArgs TA, const uint8_t* __restrict__ packed, const uint8_t* __restrict__ packed_critic, int per_run_weights,
     uint32_t groups, uint32_t groups_per_xcd) {
   using M = TagSmem<S, MODE, EB, RW>;
-  constexpr bool AC = MODE == kPolicyAc;
+  constexpr bool AC = mode_is_ac(MODE), BF = mode_is_bf(MODE);
   static_assert(EB <= 64 || S::kWaveLocal, "larger blocks only where wavefronts never exchange data");
   static_assert(RW == 64 || (RW == 32 && (!S::kWaveLocal || 32 % S::N == 0)), "rows per wavefront");
-  using Net = NetShape<S::D, S::D <= 16 ? S::D : 16>;
+  using Net = NetShape<S::D, S::D <= 32 ? S::D : 32>;
   constexpr int N = S::N, L = S::L, G = S::G, NA = S::A, D = S::D, ROWS = M::ROWS, THREADS = ROWS * (64 / RW);
   constexpr bool kPadded = ROWS != EB * N;
   static_assert(THREADS % 64 == 0, "block must be whole wavefronts");
@@ -131,7 +142,6 @@ __global__ __launch_bounds__((EB * S::N + RW - 1) / RW * 64, ((MODE == kPolicy |
   // actor-critic: both whole images in LDS, W3A of the network in use re-read from there
   using Pk = typename M::P;
   [[maybe_unused]] auto load_w3 = [&](const uint8_t* image) {
-    constexpr bool BF = MODE == kPolicyBf;
     W3Terms w;
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
@@ -233,7 +243,8 @@ __global__ __launch_bounds__((EB * S::N + RW - 1) / RW * 64, ((MODE == kPolicy |
         float* rows = tile + (wave * RW + pr * 32) * D;
         float* vals = values + wave * RW + pr * 32;
         const W3Terms wc = load_w3(csm);
-        policy_pair<Net, true>(csm, cbias, wc, rows, rows + 16 * D, lane, vals, vals + 16);
+        if constexpr (BF) policy_pair_bf<Net, true>(csm, cbias, wc, rows, rows + 16 * D, lane, vals, vals + 16);
+        else policy_pair<Net, true>(csm, cbias, wc, rows, rows + 16 * D, lane, vals, vals + 16);
       }
     }
   };
@@ -266,14 +277,14 @@ __global__ __launch_bounds__((EB * S::N + RW - 1) / RW * 64, ((MODE == kPolicy |
       for (int pr = 0; pr < RW / 32; ++pr) {
         float* rows = tile + (wave * RW + pr * 32) * D;
         if constexpr (AC) w3 = load_w3(smem);
-        if constexpr (MODE == kPolicyBf) policy_pair_bf<Net>(smem, bias, w3, rows, rows + 16 * D, lane);
+        if constexpr (BF) policy_pair_bf<Net>(smem, bias, w3, rows, rows + 16 * D, lane);
         else policy_pair<Net>(smem, bias, w3, rows, rows + 16 * D, lane);
       }
       wave_sync();
       float z[kNumActions];
 #pragma unroll
       for (int k = 0; k < kNumActions; ++k) z[k] = tile[tid * D + k];
-      if constexpr (MODE != kPolicyBf && Net::kRowTerms) z[4] = (z[4] + tile[tid * D + 5]) + tile[tid * D + 6];
+      if constexpr (!BF && Net::kRowTerms) z[4] = (z[4] + tile[tid * D + 5]) + tile[tid * D + 6];
       act = gumbel_argmax(z, A.seed, run, env, step, uint32_t(i));
       if constexpr (AC) {
         // log pi(act | obs) = z_act - max - ln sum exp(z - max)
@@ -440,42 +451,54 @@ hipError_t tag_rollout_impl(const TagArgs& A, const void* packed, const void* pa
   return hipGetLastError();
 }
 
+// One policy mode at one block shape: the critic's image goes along in the actor-critic modes only.
+template <typename S, int EB, int RW, bool AC>
+hipError_t tag_policy_impl(int mode, const TagArgs& A, const void* packed, const void* packed_critic, hipStream_t s) {
+  if constexpr (AC) {
+    if (mode == kPolicyAc) return tag_rollout_impl<S, kPolicyAc, EB, RW>(A, packed, packed_critic, s);
+    if (mode == kPolicyAcBf) return tag_rollout_impl<S, kPolicyAcBf, EB, RW>(A, packed, packed_critic, s);
+  } else {
+    if (mode == kPolicy) return tag_rollout_impl<S, kPolicy, EB, RW>(A, packed, nullptr, s);
+    if (mode == kPolicyBf) return tag_rollout_impl<S, kPolicyBf, EB, RW>(A, packed, nullptr, s);
+  }
+  return hipErrorInvalidValue;
+}
+
 template <typename S>
 hipError_t tag_launch(int mode, const TagArgs& A, const void* packed, const void* packed_critic, hipStream_t s,
                       const char** why) {
   if (mode == kGiven) return tag_rollout_impl<S, kGiven>(A, nullptr, nullptr, s);
   if (mode == kUniform) return tag_rollout_impl<S, kUniform>(A, nullptr, nullptr, s);
-  if constexpr (S::D <= 16) {
-    // actor-critic: 8 wavefronts share the two staged images where wavefronts never exchange data
-    constexpr int kAcEnvs = S::kWaveLocal ? 512 / S::N : 64;
-    const uint32_t per_block = mode == kPolicyAc ? uint32_t(kAcEnvs) : 64u;
+  if constexpr (S::D <= 32) {
+    // actor-critic: both images are staged per block; 8 wavefronts share them where wavefronts never exchange
+    // data, otherwise the largest of 64 and 32 envs whose rows fit beside the two images
+    constexpr int kAcEnvs = S::kWaveLocal ? 512 / S::N : (S::N <= 6 ? 64 : 32);
+    const bool ac = mode_is_ac(mode);
+    const uint32_t per_block = ac ? uint32_t(kAcEnvs) : 64u;
     if (A.r.TE != A.r.E && A.r.E % per_block != 0) {
       // small runs (the paper's IPPO setting is 16 envs per run): blocks of 16 envs inside a run
-      if (A.r.E % 16 == 0) {
-        if (mode == kPolicyAc) return tag_rollout_impl<S, kPolicyAc, 16, 32>(A, packed, packed_critic, s);
-        return mode == kPolicyBf ? tag_rollout_impl<S, kPolicyBf, 16, 32>(A, packed, nullptr, s)
-                                 : tag_rollout_impl<S, kPolicy, 16, 32>(A, packed, nullptr, s);
-      }
+      if (A.r.E % 16 == 0)
+        return ac ? tag_policy_impl<S, 16, 32, true>(mode, A, packed, packed_critic, s)
+                  : tag_policy_impl<S, 16, 32, false>(mode, A, packed, nullptr, s);
       *why = "with several runs, num_envs per run must be a multiple of 16";
       return hipSuccess;
     }
-    // Small batches (every block has a CU to itself, so the step latency of one block is the time): the
-    // rows spread over wavefronts of 32 rows, one per SIMD: 64 envs x 2 agents, 32 envs x 3 or 4 agents.
-    // Measured per 128-step rollout up to 8,192 envs of 4 agents: 0.54 against 0.84 ms, bf16 0.36 against
-    // 0.59 ms, actor-critic 0.88 against 2.41 ms; two such blocks per CU still win with 2 agents (1.55x)
-    // and for the actor-critic rollout of 4 agents (1.4x).
-    constexpr int kSmallEnvs = S::N == 2 ? 64 : 32;
-    const uint32_t per_cu = (S::N == 2 || (S::N == 4 && mode == kPolicyAc)) ? 2u : 1u;
-    if ((A.r.TE + kSmallEnvs - 1) / kSmallEnvs <= per_cu * compute_units()) {
-      if (mode == kPolicyAc) return tag_rollout_impl<S, kPolicyAc, kSmallEnvs, 32>(A, packed, packed_critic, s);
-      return mode == kPolicyBf ? tag_rollout_impl<S, kPolicyBf, kSmallEnvs, 32>(A, packed, nullptr, s)
-                               : tag_rollout_impl<S, kPolicy, kSmallEnvs, 32>(A, packed, nullptr, s);
+    if constexpr (S::D <= 16) {
+      // Small batches (every block has a CU to itself, so the step latency of one block is the time): the
+      // rows spread over wavefronts of 32 rows, one per SIMD: 64 envs x 2 agents, 32 envs x 3 or 4 agents.
+      // Measured per 128-step rollout up to 8,192 envs of 4 agents: 0.54 against 0.84 ms, bf16 0.36 against
+      // 0.59 ms, actor-critic 0.88 against 2.41 ms; two such blocks per CU still win with 2 agents (1.55x)
+      // and for the actor-critic rollout of 4 agents (1.4x).
+      constexpr int kSmallEnvs = S::N == 2 ? 64 : 32;
+      const uint32_t per_cu = (S::N == 2 || (S::N == 4 && ac)) ? 2u : 1u;
+      if ((A.r.TE + kSmallEnvs - 1) / kSmallEnvs <= per_cu * compute_units())
+        return ac ? tag_policy_impl<S, kSmallEnvs, 32, true>(mode, A, packed, packed_critic, s)
+                  : tag_policy_impl<S, kSmallEnvs, 32, false>(mode, A, packed, nullptr, s);
     }
-    if (mode == kPolicyAc) return tag_rollout_impl<S, kPolicyAc, kAcEnvs>(A, packed, packed_critic, s);
-    return mode == kPolicyBf ? tag_rollout_impl<S, kPolicyBf>(A, packed, nullptr, s)
-                             : tag_rollout_impl<S, kPolicy>(A, packed, nullptr, s);
+    if (ac) return tag_policy_impl<S, kAcEnvs, 64, true>(mode, A, packed, packed_critic, s);
+    return tag_policy_impl<S, 64, 64, false>(mode, A, packed, nullptr, s);
   } else {
-    *why = "no policy kernel for this shape (observation rows longer than 16)";
+    *why = "no policy kernel for this shape (observation rows longer than 32)";
     return hipSuccess;
   }
 }
@@ -483,9 +506,10 @@ hipError_t tag_launch(int mode, const TagArgs& A, const void* packed, const void
 template <typename S>
 hipError_t tag_pack(PolicyBuffers& pb, int R, bool bf16, int nout, const float* W1, const float* b1, const float* W2,
                     const float* b2, const float* W3, const float* b3, hipStream_t s) {
-  if constexpr (S::D <= 16) {
+  if constexpr (S::D <= 32) {
     using Net = NetShape<S::D, S::D>;
-    if (hipError_t e = ensure_policy_bytes(pb, size_t(R) * (bf16 ? PkB::RUN_BYTES : Pk::RUN_BYTES)); e != hipSuccess)
+    using P = PkT<false, Net::kWideIn>;
+    if (hipError_t e = ensure_policy_bytes(pb, size_t(R) * (bf16 ? PkB::RUN_BYTES : P::RUN_BYTES)); e != hipSuccess)
       return e;
     constexpr int total = 4 * 64 * 8 + 4 * 2 * 64 * 8 + 2 * 64 * 8 + 2 * kH + 16;   // one thread per weight / bias
     if (bf16)
@@ -503,7 +527,7 @@ hipError_t tag_pack(PolicyBuffers& pb, int R, bool bf16, int nout, const float* 
 }  // namespace
 
 // The shapes that are built: (agents, landmarks, good agents).
-#define MPE_TAG_SHAPES(X) X(4, 2, 1) X(2, 1, 1) X(3, 0, 1) X(6, 2, 2)
+#define MPE_TAG_SHAPES(X) X(4, 2, 1) X(2, 1, 1) X(3, 0, 1) X(6, 2, 2) X(5, 2, 1) X(8, 2, 2) X(10, 3, 2)
 
 bool tag_supported(int N, int L, int G) {
 #define X(n, l, g) if (N == n && L == l && G == g) return true;
@@ -514,7 +538,7 @@ bool tag_supported(int N, int L, int G) {
 
 bool tag_policy_supported(int N, int L, int G, int H, int weight_dtype) {
   return tag_supported(N, L, G) && H == kH && (weight_dtype == 0 || weight_dtype == 1) &&
-         4 + 2 * L + 2 * (N - 1) + 2 * G <= 16;
+         4 + 2 * L + 2 * (N - 1) + 2 * G <= 32;
 }
 
 void launch_tag_reset(int N, int L, int G, const StatePtrs& st, uint32_t TE, uint32_t E, uint32_t seed, float* obs,

@@ -121,7 +121,7 @@ def _expected_valid(c):
         if not (1 <= c["num_adversaries"] < c["num_agents"]):
             return False
         shape = (c["num_agents"], c["num_landmarks"], c["num_agents"] - c["num_adversaries"])
-        if shape not in ((4, 2, 1), (2, 1, 1), (3, 0, 1), (6, 2, 2)):
+        if shape not in ((4, 2, 1), (2, 1, 1), (3, 0, 1), (6, 2, 2), (5, 2, 1), (8, 2, 2), (10, 3, 2)):
             return False
         if not (fin(c["adv_radius"]) and c["adv_radius"] >= 0 and fin(c["adv_accel"])):
             return False

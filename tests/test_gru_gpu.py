@@ -96,7 +96,8 @@ def _assert_free_running(mods, scn, R, E, w, seed, obs, act, rew, robs, ract, rr
 
 SPREAD_AND_TAG = [(256, 3, 12), (100, 3, 12), (64, 1, 12), (130, 2, 12), (2048, 3, 6), (100, 4, 8), (70, 5, 8),
                   (64, 6, 6), (50, 7, 5), (40, 8, 5), (36, 9, 5), (50, 10, 6),
-                  (128, (4, 2, 3), 8), (130, (2, 1, 1), 8), (100, (3, 0, 2), 8), (70, (6, 2, 4), 6)]
+                  (128, (4, 2, 3), 8), (130, (2, 1, 1), 8), (100, (3, 0, 2), 8), (70, (6, 2, 4), 6), (64, (5, 2, 4), 6),
+                  (40, (8, 2, 6), 5), (32, (10, 3, 8), 5)]
 
 
 def _bf16(x):
@@ -234,7 +235,8 @@ def test_teacher_forced_steps(mods, E, scn, T):
 
 
 @pytest.mark.parametrize("E,scn", [(200, 3), (64, 2), (90, 4), (50, 5), (48, 6), (40, 8), (35, 10),
-                                   (128, (4, 2, 3)), (100, (2, 1, 1)), (90, (3, 0, 2)), (60, (6, 2, 4))])
+                                   (128, (4, 2, 3)), (100, (2, 1, 1)), (90, (3, 0, 2)), (60, (6, 2, 4)), (48, (8, 2, 6)),
+                                   (40, (10, 3, 8))])
 def test_free_running_statistics(mods, E, scn):
     """Free-running episodes: actions equal until the first bf16 rounding flip that changes a
     sample; the share of (env, agent, step) samples that agree stays high over an episode."""

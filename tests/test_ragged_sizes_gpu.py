@@ -95,7 +95,8 @@ def test_spread_variants(mods, E, mode):
 
 @pytest.mark.parametrize("E", SIZES)
 @pytest.mark.parametrize("shape,H,wd", [((4, 2, 3), 0, 0), ((4, 2, 3), 64, 0), ((4, 2, 3), 64, 1), ((3, 0, 2), 64, 0),
-                                        ((2, 1, 1), 0, 0), ((6, 2, 4), 0, 0)])
+                                        ((2, 1, 1), 0, 0), ((6, 2, 4), 0, 0), ((6, 2, 4), 64, 0), ((10, 3, 8), 64, 1), ((5, 2, 4), 64, 0),
+                                        ((8, 2, 6), 0, 0)])
 def test_tag_kernels(mods, E, shape, H, wd):
     MpeEnv, Oracle = mods
     N, L, A = shape

@@ -33,8 +33,8 @@ def _weights(shape, R, wseed):
     return synth.policy_weights_with_bias(wseed, R, D, 64), synth.critic_weights(wseed, R, D, 64)
 
 
-def _env(mods, E, shape, R=1, wseed=3, critic=True):
-    env = mods[0](Hp.tag_gpu_config(E, *shape, R, 64))
+def _env(mods, E, shape, R=1, wseed=3, critic=True, wd=0):
+    env = mods[0](Hp.tag_gpu_config(E, *shape, R, 64, wd=wd))
     pw, cw = _weights(shape, R, wseed)
     env.set_policy(*Hp.to_dev(pw))
     if critic:
@@ -42,23 +42,40 @@ def _env(mods, E, shape, R=1, wseed=3, critic=True):
     return env
 
 
-def _oracle(mods, E, shape, R=1, wseed=3):
-    orc = mods[1](Hp.tag_oracle_config(E, *shape, R, 64), threads=8)
+def _oracle(mods, E, shape, R=1, wseed=3, wd=0):
+    orc = mods[1](Hp.tag_oracle_config(E, *shape, R, 64, wd=wd), threads=8)
     pw, cw = _weights(shape, R, wseed)
     orc.set_policy(*pw)
     orc.set_critic(*cw)
     return orc
 
 
-@pytest.mark.parametrize("shape,E,R", [((4, 2, 3), 1024, 1), ((4, 2, 3), 200, 1), ((4, 2, 3), 1, 1), ((4, 2, 3), 129, 1),
-                                       ((2, 1, 1), 300, 1), ((2, 1, 1), 256, 1), ((3, 0, 2), 130, 1),
-                                       ((4, 2, 3), 128, 3), ((2, 1, 1), 256, 2), ((3, 0, 2), 64, 2)])
-def test_matches_plain_rollout_continues_and_agrees_with_the_oracles_networks(mods, shape, E, R):
+def _assert_network_outputs(got, ref, what, wd):
+    """fp32 weights: the single-step bar.  bf16 weights and layer inputs: a value that sits on a bf16 rounding
+    boundary can round the other way on the fp32 path and move an output by ~1e-3, so most outputs must
+    meet the fp32 bar and all a loose one (the bar of the simple-spread bf16 networks)."""
+    if wd == 0:
+        Hp.assert_close_step(got, ref, what)
+        return
+    err = np.abs(got - ref) / np.maximum(1.0, np.abs(ref))
+    say("  %s: within 1e-5 %.3f, mean %.2e, worst %.2e" % (what, (err <= Hp.STEP_RTOL).mean(), err.mean(), err.max()))
+    assert (err <= Hp.STEP_RTOL).mean() >= 0.9 and err.max() < 2e-2 and err.mean() < 1e-4, what
+
+
+@pytest.mark.parametrize("shape,E,R,wd", [((4, 2, 3), 1024, 1, 0), ((4, 2, 3), 200, 1, 0), ((4, 2, 3), 1, 1, 0), ((4, 2, 3), 129, 1, 0),
+                                          ((2, 1, 1), 300, 1, 0), ((2, 1, 1), 256, 1, 0), ((3, 0, 2), 130, 1, 0),
+                                          ((4, 2, 3), 128, 3, 0), ((2, 1, 1), 256, 2, 0), ((3, 0, 2), 64, 2, 0),
+                                          ((6, 2, 4), 130, 1, 0), ((5, 2, 4), 100, 1, 0), ((8, 2, 6), 64, 2, 0), ((10, 3, 8), 70, 1, 0),
+                                          ((6, 2, 4), 16, 3, 0), ((10, 3, 8), 32, 2, 0),
+                                          ((4, 2, 3), 200, 1, 1), ((2, 1, 1), 256, 2, 1), ((3, 0, 2), 130, 1, 1), ((6, 2, 4), 100, 1, 1),
+                                          ((10, 3, 8), 64, 1, 1), ((4, 2, 3), 16, 4, 1)])
+def test_matches_plain_rollout_continues_and_agrees_with_the_oracles_networks(mods, shape, E, R, wd):
     N, T = shape[0], 32
     D = Hp.tag_obs_dim(*shape)
-    say("tag actor-critic shape=%s E=%d R=%d" % (shape, E, R))
-    a, b, c = _env(mods, E, shape, R, 9), _env(mods, E, shape, R, 9, critic=False), _env(mods, E, shape, R, 9)
-    orc = _oracle(mods, E, shape, R, 9)
+    say("tag actor-critic shape=%s E=%d R=%d dtype=%d" % (shape, E, R, wd))
+    a, b, c = (_env(mods, E, shape, R, 9, wd=wd), _env(mods, E, shape, R, 9, critic=False, wd=wd),
+               _env(mods, E, shape, R, 9, wd=wd))
+    orc = _oracle(mods, E, shape, R, 9, wd=wd)
     for e in (a, b, c):
         e.reset(21)
     full = a.rollout_ac(T, *a.empty_traj_ac(T))
@@ -79,16 +96,16 @@ def test_matches_plain_rollout_continues_and_agrees_with_the_oracles_networks(mo
         rows = obs[:, sl].reshape(-1, D).astype(np.float64)
         z = orc.policy_logits(rows, run=run)
         ref_lp = log_softmax(z, axis=1)[np.arange(z.shape[0]), act[:, sl].reshape(-1)]
-        Hp.assert_close_step(logp[:, sl].reshape(-1), ref_lp, "log-prob from recorded obs and actions")
-        Hp.assert_close_step(val[:, sl].reshape(-1), orc.value(rows, run=run), "value from recorded obs")
+        _assert_network_outputs(logp[:, sl].reshape(-1), ref_lp, "log-prob from recorded obs and actions", wd)
+        _assert_network_outputs(val[:, sl].reshape(-1), orc.value(rows, run=run), "value from recorded obs", wd)
         last_rows = full[6][sl].cpu().numpy().reshape(-1, D).astype(np.float64)
-        Hp.assert_close_step(full[7][sl].cpu().numpy().reshape(-1), orc.value(last_rows, run=run), "bootstrap value")
+        _assert_network_outputs(full[7][sl].cpu().numpy().reshape(-1), orc.value(last_rows, run=run), "bootstrap value", wd)
     assert bool((full[2] <= 0).all()) and bool(torch.isfinite(full[3]).all()) and full[3].shape == (T, TE, N)
     for e in (a, b, c):
         e.close()
 
 
-@pytest.mark.parametrize("shape,E,T", [((4, 2, 3), 2048, 12), ((2, 1, 1), 200, 12)])
+@pytest.mark.parametrize("shape,E,T", [((4, 2, 3), 2048, 12), ((2, 1, 1), 200, 12), ((6, 2, 4), 512, 10), ((10, 3, 8), 100, 10)])
 def test_teacher_forced_against_the_oracles_rollout(mods, shape, E, T):
     """The oracle runs free; before every step its state is forced into the library, which then does one
     actor-critic step: actions, log-probabilities, values and the bootstrap value against orc.rollout_ac."""
@@ -137,14 +154,9 @@ def test_errors_and_absent_outputs(mods):
     assert ei.value.code == MPE_ESTATE
     env.close()
     ref.close()
-    bf = MpeEnv(Hp.tag_gpu_config(64, *shape, 1, 64, wd=1))          # bf16 weights: no actor-critic variant
+    big = MpeEnv(Hp.tag_gpu_config(64, 6, 2, 4, 1, 128))              # networks of this scenario are 64 wide
     with pytest.raises(MpeError) as ei:
-        bf.set_critic(*Hp.to_dev(_weights(shape, 1, 3)[1]))
-    assert ei.value.code == MPE_EINVAL
-    bf.close()
-    big = MpeEnv(Hp.tag_gpu_config(64, 6, 2, 4, 1, 64))               # rows of 20 floats: no policy kernel
-    with pytest.raises(MpeError) as ei:
-        big.set_critic(*Hp.to_dev(synth.critic_weights(0, 1, 20, 64)))
+        big.set_critic(*Hp.to_dev(synth.critic_weights(0, 1, big.D, 128)))
     assert ei.value.code == MPE_EINVAL
     big.close()
     runs = _env(mods, 40, shape, R=2)                                  # several runs: multiples of 16 envs per run

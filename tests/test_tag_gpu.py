@@ -17,8 +17,8 @@ pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
 
-SHAPES = [(4, 2, 3), (2, 1, 1), (3, 0, 2), (6, 2, 4)]          # (N, L, A): agents, landmarks, adversaries
-POLICY_SHAPES = [(4, 2, 3), (2, 1, 1), (3, 0, 2)]
+SHAPES = [(4, 2, 3), (2, 1, 1), (3, 0, 2), (6, 2, 4), (5, 2, 4), (8, 2, 6), (10, 3, 8)]   # (N, L, A): agents, landmarks, adversaries
+POLICY_SHAPES = SHAPES   # rows of up to 16 floats ride in half a K slice, longer ones (up to 32) fill it
 P = synth.TAG_PHYSICS
 
 
@@ -259,7 +259,8 @@ def _free_running(env, orc, shape, seed, T, make_oracle, max_ep=25):
 
 
 @pytest.mark.parametrize("shape,E,T", [((4, 2, 3), 256, 100), ((4, 2, 3), 100, 50), ((2, 1, 1), 200, 50),
-                                       ((3, 0, 2), 130, 50), ((6, 2, 4), 70, 50)])
+                                       ((3, 0, 2), 130, 50), ((6, 2, 4), 70, 50), ((5, 2, 4), 100, 50), ((8, 2, 6), 64, 50),
+                                       ((10, 3, 8), 50, 50)])
 def test_uniform_rollout_free_running(mods, shape, E, T):
     say("tag env-only rollout, free running, shape=%s E=%d T=%d" % (shape, E, T))
     env, orc = _pair(mods, E, shape)
@@ -273,7 +274,8 @@ def test_uniform_rollout_free_running(mods, shape, E, T):
 
 # ------------------------------------------------------------------------------------- fused policy
 @pytest.mark.parametrize("shape,E,T", [((4, 2, 3), 4096, 8), ((4, 2, 3), 200, 30), ((2, 1, 1), 130, 30),
-                                       ((3, 0, 2), 100, 30)])
+                                       ((3, 0, 2), 100, 30), ((6, 2, 4), 2048, 8), ((6, 2, 4), 100, 25), ((5, 2, 4), 130, 25),
+                                       ((8, 2, 6), 70, 20), ((10, 3, 8), 1024, 8), ((10, 3, 8), 50, 20)])
 def test_policy_teacher_forced(mods, shape, E, T):
     say("tag fused rollout, forced steps, shape=%s E=%d T=%d" % (shape, E, T))
     env, orc = _pair(mods, E, shape, 1, 64, wseed=3)
@@ -286,7 +288,7 @@ def test_policy_teacher_forced(mods, shape, E, T):
     env.close()
 
 
-@pytest.mark.parametrize("shape,E,T", [((4, 2, 3), 2048, 75), ((2, 1, 1), 200, 50)])
+@pytest.mark.parametrize("shape,E,T", [((4, 2, 3), 2048, 75), ((2, 1, 1), 200, 50), ((6, 2, 4), 256, 50), ((10, 3, 8), 100, 50)])
 def test_policy_free_running(mods, shape, E, T):
     say("tag fused rollout, free running, shape=%s E=%d T=%d" % (shape, E, T))
     env, orc = _pair(mods, E, shape, 1, 64, wseed=5)
@@ -304,7 +306,8 @@ def test_policy_free_running(mods, shape, E, T):
 
 
 @pytest.mark.parametrize("shape,E,R,T", [((4, 2, 3), 4096, 1, 8), ((4, 2, 3), 200, 1, 30), ((2, 1, 1), 130, 1, 30),
-                                         ((3, 0, 2), 100, 1, 30), ((4, 2, 3), 64, 3, 20)])
+                                         ((3, 0, 2), 100, 1, 30), ((4, 2, 3), 64, 3, 20), ((6, 2, 4), 130, 1, 20), ((8, 2, 6), 64, 2, 15),
+                                         ((10, 3, 8), 70, 1, 15)])
 def test_policy_bf16_teacher_forced(mods, shape, E, R, T):
     """bf16 weights and layer inputs (the oracle's bf16 mode): the rounding points are the same on both
     sides, a sample flips only when an fp32 value sits on a bf16 rounding boundary."""
@@ -330,7 +333,8 @@ def test_policy_per_run_weights(mods):
 
 # ------------------------------------------------------------------------------------- plumbing
 @pytest.mark.parametrize("shape,H,wd", [((4, 2, 3), 0, 0), ((4, 2, 3), 64, 0), ((3, 0, 2), 0, 0), ((3, 0, 2), 64, 0),
-                                        ((6, 2, 4), 0, 0), ((4, 2, 3), 64, 1), ((2, 1, 1), 64, 1)])
+                                        ((6, 2, 4), 0, 0), ((4, 2, 3), 64, 1), ((2, 1, 1), 64, 1), ((6, 2, 4), 64, 0), ((10, 3, 8), 64, 1),
+                                        ((5, 2, 4), 64, 0)])
 @pytest.mark.parametrize("E", [100, 128])   # 128: whole blocks, the env-only variant with a writer wavefront
 def test_time_slots_continuation_and_null_outputs(mods, shape, H, wd, E):
     """One rollout of T steps equals T rollouts of one step bit for bit (across an episode end), a
@@ -397,8 +401,8 @@ def test_other_constants_and_episode_length(mods, H):
 def test_refusals(mods):
     from paper_2311_10090_amd.binding import MpeError, MPE_EINVAL, MPE_ESTATE
     MpeEnv, _ = mods
-    env = MpeEnv(Hp.tag_gpu_config(64, 6, 2, 4, 1, 64))                    # rows of 22 floats: no policy kernel
-    w = Hp.to_dev(synth.policy_weights(1, 1, env.D, 64))
+    env = MpeEnv(Hp.tag_gpu_config(64, 6, 2, 4, 1, 128))                   # policies of this scenario are 64 wide
+    w = Hp.to_dev(synth.policy_weights(1, 1, env.D, 128))
     with pytest.raises(MpeError) as ei:
         env.set_policy(*w)
     assert ei.value.code == MPE_EINVAL
@@ -408,7 +412,7 @@ def test_refusals(mods):
     env.close()
     env = MpeEnv(Hp.tag_gpu_config(64, 4, 2, 3, 1, 64, wd=1))
     with pytest.raises(MpeError) as ei:
-        env.set_critic(*Hp.to_dev(synth.critic_weights(1, 1, env.D, 64)))    # actor-critic: fp32 weights only
+        env.set_critic(*Hp.to_dev(synth.critic_weights(1, 1, env.D, 64))[:5], None)   # all six arrays or none
     assert ei.value.code == MPE_EINVAL
     env.close()
     env = MpeEnv(Hp.tag_gpu_config(50, 4, 2, 3, 2, 64))                    # runs of 50 envs: blocks would straddle runs
