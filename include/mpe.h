@@ -212,6 +212,14 @@ int mpe_set_gru_policy(mpe_env* env, const float* We, const float* be, const flo
 int mpe_get_hidden(mpe_env* env, float* hidden, void* stream);
 int mpe_set_hidden(mpe_env* env, const float* hidden, void* stream);
 
+/* Failure-handling hook.  The rollout kernels whose wavefronts meet at counters in LDS (the large block
+ * shapes of mpe_rollout / mpe_rollout_ac) bound every such wait: after `polls` polls a wavefront gives up,
+ * the kernel still runs to its end with invalid results, and every later stepping call on the handle
+ * returns MPE_EHIP (see mpe_rollout).  The default, 2^24 polls (about a second; a wait normally ends within
+ * microseconds), is restored by polls = 0.  A test lowers the limit to a few polls to drive that path from
+ * the host; there is no other use for it.  MPE_EINVAL for a NULL handle. */
+int mpe_set_barrier_poll_limit(mpe_env* env, uint32_t polls);
+
 /* Install (or with all six NULL, remove) the critic used by mpe_rollout_ac: a second network of
  * the policy's shape with ONE output, fed the agent's own observation (the actor-critic pair of
  * the paper's IPPO, Sec. 3.2; App. G: two tanh layers of width 64):

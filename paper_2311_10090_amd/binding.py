@@ -23,7 +23,8 @@ NUM_ACTIONS = 5
 
 EXPORTS = ("mpe_create", "mpe_destroy", "mpe_obs_dim", "mpe_reset", "mpe_step", "mpe_set_policy",
            "mpe_rollout", "mpe_set_critic", "mpe_rollout_ac", "mpe_get_state", "mpe_set_state",
-           "mpe_set_gru_policy", "mpe_get_hidden", "mpe_set_hidden", "mpe_rollout_noalloc", "mpe_last_error")
+           "mpe_set_gru_policy", "mpe_get_hidden", "mpe_set_hidden", "mpe_rollout_noalloc",
+           "mpe_set_barrier_poll_limit", "mpe_last_error")
 GRU_HIDDEN = 128
 
 
@@ -99,6 +100,7 @@ def load_library():
     lib.mpe_set_gru_policy.argtypes = [vp] + [vp] * 10 + [vp]
     lib.mpe_get_hidden.argtypes = [vp, vp, vp]
     lib.mpe_set_hidden.argtypes = [vp, vp, vp]
+    lib.mpe_set_barrier_poll_limit.argtypes = [vp, C.c_uint32]
     lib.mpe_set_critic.argtypes = [vp] + [vp] * 6 + [vp]
     lib.mpe_rollout_ac.argtypes = [vp, C.c_int32] + [vp] * 9
     lib.mpe_rollout_noalloc.argtypes = [C.POINTER(_CConfig), C.c_uint32] + [vp] * 6 + [C.c_int32] + [vp] * 6
@@ -229,6 +231,10 @@ class MpeEnv:
     def set_hidden(self, hidden=None):
         with torch.cuda.device(self.device):
             _check(self.lib.mpe_set_hidden(self.h, _ptr(hidden, torch.float32), _stream()))
+
+    def set_barrier_poll_limit(self, polls):
+        """Failure-handling hook (see include/mpe.h): 0 restores the default."""
+        _check(self.lib.mpe_set_barrier_poll_limit(self.h, int(polls)))
 
     def get_state(self):
         """Returns pos_a, vel_a ([2][N][TE]), pos_l ([2][L][TE] fp32), ep_step ([TE] int32) tensors and abs_step."""

@@ -36,6 +36,7 @@ struct mpe_env {
   // (see group_barrier); the host reads it, without any synchronisation, at the start of the next call.
   uint32_t* fault_host = nullptr;
   uint32_t* fault_dev = nullptr;
+  uint32_t barrier_polls = 1u << 24;   // see mpe_set_barrier_poll_limit
 };
 
 namespace {
@@ -179,6 +180,7 @@ RolloutArgs rollout_args(const mpe_env* e, int32_t T, float* obs_traj, uint8_t* 
   A.done_traj = done_traj;
   A.last_obs = last_obs;
   A.fault = e->fault_dev;
+  A.barrier_polls = e->barrier_polls;
   return A;
 }
 
@@ -412,6 +414,12 @@ int mpe_set_hidden(mpe_env* e, const float* hidden, void* stream) {
     launch_fill_zero(e->hidden, n, static_cast<hipStream_t>(stream));
     MPE_HIP(hipGetLastError());
   }
+  return MPE_OK;
+}
+
+int mpe_set_barrier_poll_limit(mpe_env* e, uint32_t polls) {
+  if (!e) return fail(MPE_EINVAL, "mpe_set_barrier_poll_limit: NULL handle");
+  e->barrier_polls = polls == 0u ? (1u << 24) : polls;
   return MPE_OK;
 }
 

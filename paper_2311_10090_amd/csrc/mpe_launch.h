@@ -54,6 +54,8 @@ struct RolloutArgs {
   float* last_value = nullptr;  // [TE][N]    critic value of last_obs
   // Word that a kernel raises (system scope) when a bounded wait gave up; null = not reported.
   uint32_t* fault = nullptr;
+  // Polls after which a wait at a sync-group barrier gives up (kBarrierSpinLimit unless a test lowers it).
+  uint32_t barrier_polls = 1u << 24;
 };
 
 // Predator-prey scenario: constants by role (index 0 adversary, 1 good agent), combined on the

@@ -30,20 +30,21 @@ __device__ __forceinline__ void wave_sync() {
 // kernel; `target` = (wavefronts per group) * (barriers so far), below 2^31 (the host bounds T).  Every
 // wavefront of a block runs the same number of steps and none leaves early, and a block is resident as a
 // whole, so each wait ends after at most one step of the slowest wavefront (microseconds).  The wait is
-// bounded all the same: after kBarrierSpinLimit polls (each a sleep of 64 clocks plus an LDS read: about a
-// second in all) the wavefront gives up, sets the top bit of the counter, which lets every later wait of
+// bounded all the same: after `limit` polls (kBarrierSpinLimit unless the host lowers it to test this very
+// path; each poll is a sleep of 64 clocks plus an LDS read: about a second in all) the wavefront gives up, sets the top bit of the counter, which lets every later wait of
 // the group fall through at once, and raises *fault, a word the host reads before its next call on the
 // handle.  A kernel therefore always runs to its end; after a give-up its results are invalid.
 constexpr uint32_t kBarrierSpinLimit = 1u << 24;
 constexpr uint32_t kBarrierBroken = 0x80000000u;
 
-__device__ __forceinline__ void group_barrier(uint32_t* arrived, uint32_t target, int lane, uint32_t* fault) {
+__device__ __forceinline__ void group_barrier(uint32_t* arrived, uint32_t target, int lane, uint32_t* fault,
+                                              uint32_t limit) {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   if (lane == 0) __hip_atomic_fetch_add(arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
   uint32_t polls = 0;
   while (__hip_atomic_load(arrived, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < target) {
     __builtin_amdgcn_s_sleep(1);
-    if (++polls >= kBarrierSpinLimit) {
+    if (++polls >= limit) {
       if (lane == 0) {
         __hip_atomic_fetch_or(arrived, kBarrierBroken, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         if (fault) __hip_atomic_store(fault, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);

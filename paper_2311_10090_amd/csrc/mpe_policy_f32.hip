@@ -338,7 +338,7 @@ __global__ __launch_bounds__((EB * N + RW - 1) / RW * 64, MINW) void rollout_pol
     np[tid] = make_float2(px, py);
     // (C) new positions of every agent of every env of this 64-env group are visible
     if constexpr (EB <= 64) __syncthreads();
-    else if constexpr (N > 1) group_barrier(arrived, uint32_t(N) * uint32_t(t + 1), lane, A.fault);
+    else if constexpr (N > 1) group_barrier(arrived, uint32_t(N) * uint32_t(t + 1), lane, A.fault, A.barrier_polls);
     else wave_sync();
 
 #pragma unroll
@@ -620,7 +620,7 @@ __global__ __launch_bounds__(256 * N, 1) void rollout_policy_f32_reg_kernel(Roll
     float2* np = newpos + (t & 1) * ROWS_G;
     np[r] = make_float2(px, py);
     // (C) new positions of every agent of every env of this 64-env group are visible
-    group_barrier(arrived, uint32_t(N) * uint32_t(t + 1), lane, A.fault);
+    group_barrier(arrived, uint32_t(N) * uint32_t(t + 1), lane, A.fault, A.barrier_polls);
 #pragma unroll
     for (int a = 0; a < N; ++a) {
       const float2 p = np[el * N + a];

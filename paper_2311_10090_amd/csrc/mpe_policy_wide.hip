@@ -584,7 +584,7 @@ __global__ __launch_bounds__((RowMap<N, EB, UNIFORM>::WAVES * 64), MINW) void ro
     float2* np = newpos + (t & 1) * ROWS;
     if (active) np[tid] = make_float2(px, py);
     // (C) new positions of this step and coverage distances of the previous one are visible
-    group_barrier(arrived, uint32_t(GW) * uint32_t(t + 1), lane, A.fault);
+    group_barrier(arrived, uint32_t(GW) * uint32_t(t + 1), lane, A.fault, A.barrier_polls);
 
     // reward of the previous step: sum of its N per-landmark distances
     if (t > 0) store_reward((t - 1) & 1);
@@ -646,7 +646,7 @@ __global__ __launch_bounds__((RowMap<N, EB, UNIFORM>::WAVES * 64), MINW) void ro
       ep = 0;
     }
   }
-  group_barrier(arrived, uint32_t(GW) * uint32_t(A.T + 1), lane, A.fault);  // coverage distances of the last step
+  group_barrier(arrived, uint32_t(GW) * uint32_t(A.T + 1), lane, A.fault, A.barrier_polls);  // coverage distances of the last step
   store_reward((A.T - 1) & 1);
   if (A.last_obs) {
     float o[KIN];

@@ -697,3 +697,35 @@ def test_sync_group_barriers_end_and_long_rollouts_are_refused(mods):
         assert ei.value.code == MPE_EINVAL
         assert env.get_state()[4] == 91
         env.close()
+
+
+@pytest.mark.parametrize("E,N,R,H,wd", [(65536, 3, 1, 64, 0), (64, 3, 1024, 64, 0), (4096, 10, 1, 128, 1)])
+def test_a_barrier_wait_that_gives_up_is_reported_and_every_kernel_still_ends(mods, E, N, R, H, wd):
+    """The give-up path of the bounded barrier wait, forced from the host: with a limit of one poll the
+    wavefronts of a sync group stop waiting for each other, the kernel runs to its end all the same (its
+    results are then invalid, not checked), the call itself returns normally, and the NEXT stepping call on
+    the handle reports MPE_EHIP.  A fresh handle is unaffected, and the default limit never trips."""
+    MpeEnv, _ = mods
+    from paper_2311_10090_amd.binding import MpeError, MPE_EHIP
+    w = Hp.to_dev(synth.policy_weights(1, R, 6 * N, H))
+    env = MpeEnv(Hp.gpu_config(E, N, R, H, wd))
+    env.set_policy(*w)
+    env.reset(2)
+    env.set_barrier_poll_limit(1)
+    out = env.rollout(8, *env.empty_traj(8))      # returns normally; the kernel drains
+    torch.cuda.synchronize()
+    assert out[3].shape[0] == 8
+    with pytest.raises(MpeError) as ei:
+        env.rollout(1)
+    assert ei.value.code == MPE_EHIP and "gave up" in str(ei.value)
+    with pytest.raises(MpeError):
+        env.step(torch.zeros((E * R, N), dtype=torch.uint8, device="cuda"))
+    env.close()
+    ok = MpeEnv(Hp.gpu_config(E, N, R, H, wd))
+    ok.set_policy(*w)
+    ok.reset(2)
+    ok.set_barrier_poll_limit(0)                  # the default
+    ok.rollout(8)
+    torch.cuda.synchronize()
+    ok.rollout(1)
+    ok.close()
