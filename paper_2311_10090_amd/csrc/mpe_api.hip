@@ -444,7 +444,7 @@ int mpe_set_critic(mpe_env* e, const float* V1, const float* c1, const float* V2
   } else if (e->cfg.weight_dtype == MPE_WEIGHTS_BF16 && wide_supported(e->N, e->H)) {
     err = pack_policy_wide(e->critic, e->N, e->H, int(e->R), V1, c1, V2, c2, V3, c3, 1, static_cast<hipStream_t>(stream));
   } else {
-    if (!f32_supported(e->N, e->H))
+    if (!f32_supported(e->N, e->H, e->cfg.weight_dtype == MPE_WEIGHTS_BF16))
       return fail(MPE_EINVAL, "mpe_set_critic: unsupported shape: the actor-critic rollout is built for the "
                               "shapes of mpe_set_policy");
     err = pack_policy_f32(e->critic, e->N, int(e->R), V1, c1, V2, c2, V3, c3, 1,
@@ -467,7 +467,7 @@ int mpe_rollout_ac(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, fl
     return fail(MPE_ESTATE, "mpe_rollout_ac: needs mpe_set_policy and mpe_set_critic first");
   if (e->has_gru) return fail(MPE_ESTATE, "mpe_rollout_ac: remove the recurrent policy first (feed-forward networks only)");
   const bool wide = !e->tag && e->cfg.weight_dtype == MPE_WEIGHTS_BF16 && wide_supported(e->N, e->H);
-  if (!e->tag && !wide && !f32_supported(e->N, e->H)) return fail(MPE_EINVAL, "mpe_rollout_ac: unsupported shape");
+  if (!e->tag && !wide && !f32_supported(e->N, e->H, e->cfg.weight_dtype == MPE_WEIGHTS_BF16)) return fail(MPE_EINVAL, "mpe_rollout_ac: unsupported shape");
   for (const float* p : {obs_traj, logp_traj, value_traj, rew_traj, last_obs, last_value})
     if (p && !aligned16(p)) return fail(MPE_EINVAL, "mpe_rollout_ac: float outputs must be 16-byte aligned");
   if (uint64_t(e->abs_step) + uint64_t(T) > 0xFFFFFFFFull)

@@ -25,11 +25,12 @@ void free_policy(PolicyBuffers& pb) {
 }
 
 static const char* kUnsupported =
-    "unsupported policy shape: need (num_agents, hidden, dtype) in {(1..3, 64, fp32 or bf16), (4..10, 64 | 128, bf16)}";
+    "unsupported policy shape: need (num_agents, hidden, dtype) in {(1..3, 64, fp32 or bf16), (4..7, 64, fp32), "
+    "(4..10, 64 | 128, bf16)}";
 
 size_t packed_policy_bytes(int N, int H, int R, int weight_dtype) {
   if (weight_dtype == 1 && wide_supported(N, H)) return size_t(R) * packed_run_bytes_wide(N, H);
-  if (f32_supported(N, H)) return size_t(R) * packed_run_bytes_f32(weight_dtype == 1);
+  if (f32_supported(N, H, weight_dtype == 1)) return size_t(R) * packed_run_bytes_f32(N, weight_dtype == 1);
   return 0;
 }
 
@@ -37,7 +38,7 @@ hipError_t pack_policy(PolicyBuffers& pb, int N, int H, int R, int weight_dtype,
                        const float* b1, const float* W2, const float* b2, const float* W3,
                        const float* b3, hipStream_t s, const char** why) {
   if (weight_dtype == 1 && wide_supported(N, H)) return pack_policy_wide(pb, N, H, R, W1, b1, W2, b2, W3, b3, 5, s);
-  if (f32_supported(N, H)) return pack_policy_f32(pb, N, R, W1, b1, W2, b2, W3, b3, 5, weight_dtype == 1, s);
+  if (f32_supported(N, H, weight_dtype == 1)) return pack_policy_f32(pb, N, R, W1, b1, W2, b2, W3, b3, 5, weight_dtype == 1, s);
   *why = kUnsupported;
   return hipSuccess;
 }
@@ -45,7 +46,7 @@ hipError_t pack_policy(PolicyBuffers& pb, int N, int H, int R, int weight_dtype,
 hipError_t launch_rollout_policy(int N, int H, int weight_dtype, const RolloutArgs& A,
                                  const PolicyBuffers& pb, hipStream_t s, const char** why) {
   if (weight_dtype == 1 && wide_supported(N, H)) return launch_rollout_policy_wide(N, H, A, pb, s, why);
-  if (f32_supported(N, H)) return launch_rollout_policy_f32(N, weight_dtype == 1, A, pb, s, why);
+  if (f32_supported(N, H, weight_dtype == 1)) return launch_rollout_policy_f32(N, weight_dtype == 1, A, pb, s, why);
   *why = kUnsupported;
   return hipSuccess;
 }

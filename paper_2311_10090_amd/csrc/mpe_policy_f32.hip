@@ -1,4 +1,5 @@
-// Fused rollout kernel for the headline shape: fp32 policy 6N -> 64 -> 64 -> 5 (N <= 3 agents),
+// Fused rollout kernel for the headline shape: fp32 policy 6N -> 64 -> 64 -> 5 (N <= 3 agents; with fp32 weights
+// also 4 to 7 agents, whose 4N + 2 live inputs still fit the one K slice of layer 1, in 64-env blocks),
 // shared by all agents or one set of weights per run (paper: App. G IPPO table, two tanh layers
 // of width 64; Sec. 3.2 parameter sharing; Sec. 5.2 and App. E: whole training runs vectorised on one device).
 //
@@ -48,7 +49,7 @@ using SpreadNet = NetShape<6 * N, 4 * N + 2>;
 // 3 agents have such padding rows: 48 -> 64; no env owns them and nothing of them leaves the block).
 template <int N, int EB, bool AC = false, bool BF = false, int RW = 64>
 struct SmemF32 {
-  using P = PkT<BF>;
+  using P = PkT<BF, SpreadNet<N>::kWideIn>;
   static constexpr int D = 6 * N;
   static constexpr int ROWS = (EB * N + RW - 1) / RW * RW;
   // LEAN (actor-critic in 16-env blocks, i.e. many small runs): W3A of both networks stays in global memory
@@ -83,7 +84,7 @@ __global__ __launch_bounds__((EB * N + RW - 1) / RW * 64, MINW) void rollout_pol
                                                                           int per_run_weights, uint32_t groups,
                                                                           uint32_t groups_per_xcd) {
   using M = SmemF32<N, EB, AC, BF, RW>;
-  using P = PkT<BF>;
+  using P = typename M::P;
 
   constexpr int D = 6 * N, ROWS = M::ROWS, THREADS = ROWS * (64 / RW);
   constexpr bool kPadded = ROWS != EB * N;
@@ -244,7 +245,7 @@ __global__ __launch_bounds__((EB * N + RW - 1) / RW * 64, MINW) void rollout_pol
   uint8_t* done_base = A.done_traj;
   float* logp_base = A.logp_traj;
   float* value_base = A.value_traj;
-  const uint32_t row_off = uint32_t(gc) * N + i;      // index of this agent inside a time slice (TE <= 2^30 and N <= 3: below 2^32)
+  const size_t row_off = size_t(gc) * N + i;          // index of this agent inside a time slice
   const bool env_writer = valid && i == 0;            // the lane that stores per-env outputs
   uint32_t step = A.abs_step;
   const float* wtile = tile + wave * (RW * D);        // this wavefront's rows
@@ -735,7 +736,7 @@ hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream
 template <int N>
 hipError_t pack_impl(PolicyBuffers& pb, int R, const float* W1, const float* b1, const float* W2,
                      const float* b2, const float* W3, const float* b3, int nout, bool bf16, hipStream_t s) {
-  const size_t run_bytes = bf16 ? PkB::RUN_BYTES : Pk::RUN_BYTES;
+  const size_t run_bytes = bf16 ? PkB::RUN_BYTES : PkT<false, SpreadNet<N>::kWideIn>::RUN_BYTES;
   if (hipError_t e = ensure_policy_bytes(pb, size_t(R) * run_bytes); e != hipSuccess) return e;
   constexpr int total = 4 * 64 * 8 + 4 * 2 * 64 * 8 + 2 * 64 * 8 + 2 * kH + 16;   // threads: one per weight / bias
   dim3 grid((total + 255) / 256, R);
@@ -787,6 +788,16 @@ template <int N, bool BF>
 hipError_t launch_n(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s, const char** why) {
   const bool one_run = A.TE == A.E;
   const bool per_agent = A.ph.reward_mode == 1;
+  if constexpr (N > 3) {
+    // 4 to 7 agents (fp32 weights; bf16 ones run the lane-per-agent bf16 kernel): 64-env blocks of N wavefronts,
+    // one or two per CU by their LDS
+    static_assert(!BF, "bf16 weights with 4 and more agents are another kernel's");
+    if (!one_run && A.E % 64 != 0) {
+      *why = "with several runs and 4 or more agents, num_envs per run must be a multiple of 64";
+      return hipSuccess;
+    }
+    return per_agent ? rollout_impl<N, 64, 1, true, false, false>(A, pb, s) : rollout_impl<N, 64, 1, false, false, false>(A, pb, s);
+  } else {
   if (one_run && A.TE / 256 >= compute_units())
     return per_agent ? rollout_impl<N, 256, 3, true, false, BF>(A, pb, s) : rollout_impl<N, 256, 3, false, false, BF>(A, pb, s);
   if constexpr (!BF && N >= 2) {
@@ -810,6 +821,7 @@ hipError_t launch_n(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s
     return per_agent ? rollout_impl<N, 16, 1, true, false, BF, 32>(A, pb, s) : rollout_impl<N, 16, 1, false, false, BF, 32>(A, pb, s);
   *why = "with several runs, num_envs per run must be a multiple of 16";
   return hipSuccess;
+  }
 }
 
 // Actor-critic rollout: 256 envs per block = four 64-env sync groups (12 wavefronts at N = 3)
@@ -821,6 +833,17 @@ hipError_t launch_ac_n(const RolloutArgs& A, const PolicyBuffers& pb, const Poli
                        const char** why) {
   const bool one_run = A.TE == A.E;
   const bool per_agent = A.ph.reward_mode == 1;
+  if constexpr (N > 3) {
+    // both staged images and the block's observation rows: 64 envs up to 6 agents, 32 envs with 7
+    static_assert(!BF, "bf16 weights with 4 and more agents are another kernel's");
+    constexpr int kEnvs = N <= 6 ? 64 : 32;
+    if (!one_run && A.E % kEnvs != 0) {
+      *why = "with several runs and 4 or more agents, num_envs per run must be a multiple of 64 (of 32 with 7 agents)";
+      return hipSuccess;
+    }
+    return per_agent ? rollout_impl<N, kEnvs, 1, true, true, false>(A, pb, s, critic.packed)
+                     : rollout_impl<N, kEnvs, 1, false, true, false>(A, pb, s, critic.packed);
+  } else {
   if (one_run ? A.TE / 256 >= compute_units() / 2 : A.E % 256 == 0)
     return per_agent ? rollout_impl<N, 256, 3, true, true, BF>(A, pb, s, critic.packed)
                      : rollout_impl<N, 256, 3, false, true, BF>(A, pb, s, critic.packed);
@@ -835,13 +858,18 @@ hipError_t launch_ac_n(const RolloutArgs& A, const PolicyBuffers& pb, const Poli
                      : rollout_impl<N, 16, 1, false, true, BF, 32>(A, pb, s, critic.packed);
   *why = "with several runs, num_envs per run must be a multiple of 16";
   return hipSuccess;
+  }
 }
 
 }  // namespace
 
-bool f32_supported(int N, int H) { return H == kH && N >= 1 && N <= 3; }
+// fp32 weights: 1..7 agents (the 4N + 2 live inputs of a row fit layer 1's one K slice); bf16 weights: 1..3
+// (4 and more agents with bf16 weights run the lane-per-agent bf16 kernel)
+bool f32_supported(int N, int H, bool bf16) { return H == kH && N >= 1 && N <= (bf16 ? 3 : 7); }
 
-size_t packed_run_bytes_f32(bool bf16) { return bf16 ? PkB::RUN_BYTES : Pk::RUN_BYTES; }
+size_t packed_run_bytes_f32(int N, bool bf16) {
+  return bf16 ? PkB::RUN_BYTES : (4 * N + 2 > 16 ? PkT<false, true>::RUN_BYTES : Pk::RUN_BYTES);
+}
 
 hipError_t pack_policy_f32(PolicyBuffers& pb, int N, int R, const float* W1, const float* b1, const float* W2,
                            const float* b2, const float* W3, const float* b3, int nout, bool bf16, hipStream_t s) {
@@ -849,6 +877,10 @@ hipError_t pack_policy_f32(PolicyBuffers& pb, int N, int R, const float* W1, con
     case 1: return pack_impl<1>(pb, R, W1, b1, W2, b2, W3, b3, nout, bf16, s);
     case 2: return pack_impl<2>(pb, R, W1, b1, W2, b2, W3, b3, nout, bf16, s);
     case 3: return pack_impl<3>(pb, R, W1, b1, W2, b2, W3, b3, nout, bf16, s);
+    case 4: return bf16 ? hipErrorInvalidValue : pack_impl<4>(pb, R, W1, b1, W2, b2, W3, b3, nout, false, s);
+    case 5: return bf16 ? hipErrorInvalidValue : pack_impl<5>(pb, R, W1, b1, W2, b2, W3, b3, nout, false, s);
+    case 6: return bf16 ? hipErrorInvalidValue : pack_impl<6>(pb, R, W1, b1, W2, b2, W3, b3, nout, false, s);
+    case 7: return bf16 ? hipErrorInvalidValue : pack_impl<7>(pb, R, W1, b1, W2, b2, W3, b3, nout, false, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -858,6 +890,10 @@ hipError_t pack_policy_f32(PolicyBuffers& pb, int N, int R, const float* W1, con
     case 1: return bf16 ? FN<1, true>(__VA_ARGS__) : FN<1, false>(__VA_ARGS__);  \
     case 2: return bf16 ? FN<2, true>(__VA_ARGS__) : FN<2, false>(__VA_ARGS__);  \
     case 3: return bf16 ? FN<3, true>(__VA_ARGS__) : FN<3, false>(__VA_ARGS__);  \
+    case 4: return bf16 ? hipErrorInvalidValue : FN<4, false>(__VA_ARGS__);      \
+    case 5: return bf16 ? hipErrorInvalidValue : FN<5, false>(__VA_ARGS__);      \
+    case 6: return bf16 ? hipErrorInvalidValue : FN<6, false>(__VA_ARGS__);      \
+    case 7: return bf16 ? hipErrorInvalidValue : FN<7, false>(__VA_ARGS__);      \
     default: return hipErrorInvalidValue;                                        \
   }
 
