@@ -338,6 +338,33 @@ def main():
         env7.close()
         del b7
 
+    # the wider shapes of the same kernel families, three timed calls each: fp32 weights with 6 agents, the
+    # predator-prey scenario with 10 agents (rows of 32 floats), the recurrent policy on that scenario's
+    # default shape and on 10 agents of simple spread
+    wider = {}
+    if extras and args.workload == "cfg2":
+        def timed(env8, n_agents):
+            env8.reset(seed)
+            b8 = env8.empty_traj(T)
+            w8, k8 = time_rollouts(env8, T, b8, 3, 2)
+            res = {"envs": env8.TE, "agents": n_agents, "kernel_ms_avg": float(np.mean(k8)),
+                   "agent_steps_per_s": env8.TE * n_agents * T / (w8 / 3)}
+            env8.close()
+            return res
+        env8 = spread_env(synth, 32768, 6, 1, 64, 0)
+        env8.set_policy(*to_dev(synth.policy_weights(0, 1, 36, 64)))
+        wider["spread_6_agents_fp32"] = timed(env8, 6)
+        env8 = tag_env(synth, 16384, 10, 3, 8, 1, 64, 0)
+        env8.set_policy(*to_dev(synth.policy_weights(0, 1, synth.tag_obs_dim(10, 3, 8), 64)))
+        wider["tag_10_agents_3_obstacles_fp32"] = timed(env8, 10)
+        env8 = tag_env(synth, 32768, 4, 2, 3, 1, 128, 1)
+        env8.set_gru_policy(*to_dev(synth.gru_weights(0, 1, synth.tag_obs_dim(4, 2, 3))))
+        wider["tag_4_agents_recurrent"] = timed(env8, 4)
+        env8 = spread_env(synth, 16384, 10, 1, 128, 1)
+        env8.set_gru_policy(*to_dev(synth.gru_weights(0, 1, 60)))
+        wider["spread_10_agents_recurrent"] = timed(env8, 10)
+        wider["note"] = "128-step rollouts, all outputs written; sizes chosen to fill the chip with each shape's block"
+
     out = {
         "metric": "agent-steps/sec fused MPE rollout @65,536 envs, 1 MI355X; % HBM roofline",
         "value": value,
@@ -403,6 +430,7 @@ def main():
         "actor_critic": ac,
         "bf16_policy": bf,
         "many_small_runs": runs16,
+        "wider_shapes": wider,
         "tag_scenario": tag,
         "recurrent_policy": gru,
         "single_step": {"us_per_mpe_step_call": step_us, "env_steps_per_s": TE / (step_us * 1e-6),
