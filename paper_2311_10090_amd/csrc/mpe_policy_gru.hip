@@ -324,14 +324,8 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(TagArgs TA, const uint
     if (a == i) { px = qx[a]; py = qy[a]; }
   }
   // predator-prey: the constants of this lane's role
-  [[maybe_unused]] const int role = i < NA ? 0 : 1;
-  [[maybe_unused]] float my_radius = 0.0f, my_gain = 0.0f, my_limit = 0.0f, my_limit_sq = 0.0f;
-  if constexpr (kTag) {
-    my_radius = role == 0 ? tg.radius[0] : tg.radius[1];
-    my_gain = role == 0 ? tg.gain[0] : tg.gain[1];
-    my_limit = role == 0 ? tg.limit[0] : tg.limit[1];
-    my_limit_sq = role == 0 ? tg.limit_sq[0] : tg.limit_sq[1];
-  }
+  [[maybe_unused]] TagRole me{};
+  if constexpr (kTag) me = tag_role<TS>(i, tg);
 
   // Observation row of this lane from the registers above: bf16 (nearest even) into the LDS tile
   // for the embedding, fp32 to `dst` (this lane's row of a trajectory slice, may be null).
@@ -480,38 +474,7 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(TagArgs TA, const uint
       const uint32_t act = gumbel_argmax(z, A.seed, run, env, step, uint32_t(i));
       if (act_base && valid) act_base[row_off] = uint8_t(act);
       if constexpr (kTag) {
-        // control, contacts with the other agents and the obstacles on the pre-step positions, position
-        // with the old velocity, damped velocity, speed limit
-        float fx = my_gain * action_dir_x(act);
-        float fy = my_gain * action_dir_y(act);
-#pragma unroll
-        for (int k = 0; k < N - 1; ++k) {
-          const bool up = k >= i;
-          const float ox = up ? qx[k + 1] : qx[k], oy = up ? qy[k + 1] : qy[k];
-          const float r_lo = tg.radius[k < NA ? 0 : 1], r_hi = tg.radius[k + 1 < NA ? 0 : 1];
-          const float orad = ((k < NA) == (k + 1 < NA)) ? r_lo : (up ? r_hi : r_lo);
-          const float dx = px - ox, dy = py - oy;
-          const float kf = tag_contact(dx, dy, my_radius + orad, tg);
-          fx = fmaf(kf, dx, fx);
-          fy = fmaf(kf, dy, fy);
-        }
-#pragma unroll
-        for (int l = 0; l < L; ++l) {
-          const float dx = px - lx[l], dy = py - ly[l];
-          const float kf = tag_contact(dx, dy, my_radius + tg.lm_radius, tg);
-          fx = fmaf(kf, dx, fx);
-          fy = fmaf(kf, dy, fy);
-        }
-        px = fmaf(vx, tg.dt, px);
-        py = fmaf(vy, tg.dt, py);
-        vx = fmaf(fx, tg.dt_over_mass, vx * tg.keep);
-        vy = fmaf(fy, tg.dt_over_mass, vy * tg.keep);
-        const float s2 = fmaf(vx, vx, vy * vy);
-        if (s2 > my_limit_sq) {
-          const float kf = my_limit * hw_rsq(s2);
-          vx *= kf;
-          vy *= kf;
-        }
+        tag_move<TS>(act, i, me, tg, px, py, vx, vy, qx, qy, lx, ly);
         xch4[tid] = make_float4(px, py, vx, vy);
       } else {
         float fx = A.ph.accel * action_dir_x(act);
@@ -550,21 +513,7 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(TagArgs TA, const uint
             gvy[a - NA] = p.w;
           }
         }
-        // touching (good, adversary) pairs on the new positions
-        uint32_t caught = 0, hits = 0;
-#pragma unroll
-        for (int a = 0; a < NA; ++a) {
-#pragma unroll
-          for (int b = NA; b < N; ++b) {
-            const float dx = qx[a] - qx[b], dy = qy[a] - qy[b];
-            const uint32_t touch = fmaf(dx, dx, dy * dy) < tg.touch_sq ? 1u : 0u;
-            caught += touch;
-            hits += b == i ? touch : 0u;
-          }
-        }
-        const float r_good = -10.0f * float(hits) - tag_bound(fabsf(px)) - tag_bound(fabsf(py));
-        const float r = role == 0 ? 10.0f * float(caught) : r_good;
-        if (rew_base && valid) rew_base[row_off] = r;
+        if (rew_base && valid) rew_base[row_off] = tag_reward<TS>(i, me, tg, px, py, qx, qy);
         max_ep = tg.max_ep;
       } else {
 #pragma unroll

@@ -178,11 +178,7 @@ __global__ __launch_bounds__((EB * S::N + RW - 1) / RW * 64, (TagOccupancy<S, MO
   if (threadIdx.x < 16) tile[ROWS * D + threadIdx.x] = 0.0f;
 
   // ---- registers: own agent, all agents' positions, good agents' velocities, landmarks
-  const int role = i < NA ? 0 : 1;
-  const float my_radius = role == 0 ? tg.radius[0] : tg.radius[1];
-  const float my_gain = role == 0 ? tg.gain[0] : tg.gain[1];
-  const float my_limit = role == 0 ? tg.limit[0] : tg.limit[1];
-  const float my_limit_sq = role == 0 ? tg.limit_sq[0] : tg.limit_sq[1];
+  const TagRole me = tag_role<S>(i, tg);
   float px = 0.0f, py = 0.0f, vx = 0.0f, vy = 0.0f;
   float qx[N], qy[N], lx[L + 1], ly[L + 1], gvx[G], gvy[G];
   int32_t ep = 0;
@@ -312,42 +308,8 @@ __global__ __launch_bounds__((EB * S::N + RW - 1) / RW * 64, (TagOccupancy<S, MO
       act_base += TE * N;
     }
 
-    // ---- transition of this lane's agent: control, contacts with agents and obstacles on the
-    // pre-step positions, position with the old velocity, damped velocity, speed limit
-    float fx = my_gain * action_dir_x(act);
-    float fy = my_gain * action_dir_y(act);
-    // the k-th OTHER agent is agent k (k < i) or k + 1: N - 1 evaluations with selected operands, in
-    // ascending agent order (a loop over all agents that skips a == i runs N masked evaluations)
-#pragma unroll
-    for (int k = 0; k < N - 1; ++k) {
-      const bool up = k >= i;
-      const float ox = up ? qx[k + 1] : qx[k], oy = up ? qy[k + 1] : qy[k];
-      const float r_lo = tg.radius[k < NA ? 0 : 1], r_hi = tg.radius[k + 1 < NA ? 0 : 1];
-      const float orad = ((k < NA) == (k + 1 < NA)) ? r_lo : (up ? r_hi : r_lo);
-      const float dx = px - ox, dy = py - oy;
-      const float kf = tag_contact(dx, dy, my_radius + orad, tg);
-      fx = fmaf(kf, dx, fx);
-      fy = fmaf(kf, dy, fy);
-    }
-#pragma unroll
-    for (int l = 0; l < L; ++l) {
-      const float dx = px - lx[l], dy = py - ly[l];
-      const float k = tag_contact(dx, dy, my_radius + tg.lm_radius, tg);
-      fx = fmaf(k, dx, fx);
-      fy = fmaf(k, dy, fy);
-    }
-    px = fmaf(vx, tg.dt, px);
-    py = fmaf(vy, tg.dt, py);
-    vx = fmaf(fx, tg.dt_over_mass, vx * tg.keep);
-    vy = fmaf(fy, tg.dt_over_mass, vy * tg.keep);
-    {
-      const float s2 = fmaf(vx, vx, vy * vy);
-      if (s2 > my_limit_sq) {
-        const float k = my_limit * hw_rsq(s2);
-        vx *= k;
-        vy *= k;
-      }
-    }
+    // ---- transition of this lane's agent
+    tag_move<S>(act, i, me, tg, px, py, vx, vy, qx, qy, lx, ly);
     float4* slot = xch + (S::kWaveLocal ? 0 : (t & 1) * ROWS);
     slot[tid] = make_float4(px, py, vx, vy);
     // new positions and velocities of every agent of this env are visible
@@ -364,25 +326,11 @@ __global__ __launch_bounds__((EB * S::N + RW - 1) / RW * 64, (TagOccupancy<S, MO
     }
     if constexpr (S::kWaveLocal) wave_sync();   // the slots are rewritten in the next step
 
-    // ---- rewards on the new positions: touching (good, adversary) pairs
-    {
-      uint32_t caught = 0, hits = 0;
-#pragma unroll
-      for (int a = 0; a < NA; ++a) {
-#pragma unroll
-        for (int b = NA; b < N; ++b) {
-          const float dx = qx[a] - qx[b], dy = qy[a] - qy[b];
-          const uint32_t touch = fmaf(dx, dx, dy * dy) < tg.touch_sq ? 1u : 0u;
-          caught += touch;
-          hits += b == i ? touch : 0u;
-        }
-      }
-      const float r_good = -10.0f * float(hits) - tag_bound(fabsf(px)) - tag_bound(fabsf(py));
-      const float r = role == 0 ? 10.0f * float(caught) : r_good;
-      if (rew_base) {
-        if (valid) rew_base[row_off] = r;
-        rew_base += TE * N;
-      }
+    // ---- rewards on the new positions
+    if (rew_base) {
+      const float r = tag_reward<S>(i, me, tg, px, py, qx, qy);
+      if (valid) rew_base[row_off] = r;
+      rew_base += TE * N;
     }
     ep += 1;
     const bool done = ep >= tg.max_ep;

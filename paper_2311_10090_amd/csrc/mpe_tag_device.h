@@ -75,6 +75,83 @@ __device__ __forceinline__ void tag_write_row(float2* row, int i, float px, floa
   if (i >= S::A) row[S::D / 2 - 1] = make_float2(0.0f, 0.0f);
 }
 
+// The constants of an agent's role (adversaries come first).
+struct TagRole {
+  int role;            // 0 adversary, 1 good agent
+  float radius, gain, limit, limit_sq;
+};
+template <typename S>
+__device__ __forceinline__ TagRole tag_role(int i, const TagPhys& tg) {
+  TagRole r;
+  r.role = i < S::A ? 0 : 1;
+  r.radius = r.role == 0 ? tg.radius[0] : tg.radius[1];
+  r.gain = r.role == 0 ? tg.gain[0] : tg.gain[1];
+  r.limit = r.role == 0 ? tg.limit[0] : tg.limit[1];
+  r.limit_sq = r.role == 0 ? tg.limit_sq[0] : tg.limit_sq[1];
+  return r;
+}
+
+// Transition of agent i under action `act`: control force, contacts with the other agents and with the obstacle
+// landmarks on the pre-step positions, position with the old velocity, damped velocity, speed limit.
+template <typename S>
+__device__ __forceinline__ void tag_move(uint32_t act, int i, const TagRole& me, const TagPhys& tg, float& px, float& py,
+                                         float& vx, float& vy, const float (&qx)[S::N], const float (&qy)[S::N],
+                                         const float (&lx)[S::L + 1], const float (&ly)[S::L + 1]) {
+  constexpr int N = S::N, NA = S::A;
+  float fx = me.gain * action_dir_x(act);
+  float fy = me.gain * action_dir_y(act);
+  // the k-th OTHER agent is agent k (k < i) or k + 1: N - 1 evaluations with selected operands, in
+  // ascending agent order (a loop over all agents that skips a == i runs N masked evaluations)
+#pragma unroll
+  for (int k = 0; k < N - 1; ++k) {
+    const bool up = k >= i;
+    const float ox = up ? qx[k + 1] : qx[k], oy = up ? qy[k + 1] : qy[k];
+    const float r_lo = tg.radius[k < NA ? 0 : 1], r_hi = tg.radius[k + 1 < NA ? 0 : 1];
+    const float orad = ((k < NA) == (k + 1 < NA)) ? r_lo : (up ? r_hi : r_lo);
+    const float dx = px - ox, dy = py - oy;
+    const float kf = tag_contact(dx, dy, me.radius + orad, tg);
+    fx = fmaf(kf, dx, fx);
+    fy = fmaf(kf, dy, fy);
+  }
+#pragma unroll
+  for (int l = 0; l < S::L; ++l) {
+    const float dx = px - lx[l], dy = py - ly[l];
+    const float k = tag_contact(dx, dy, me.radius + tg.lm_radius, tg);
+    fx = fmaf(k, dx, fx);
+    fy = fmaf(k, dy, fy);
+  }
+  px = fmaf(vx, tg.dt, px);
+  py = fmaf(vy, tg.dt, py);
+  vx = fmaf(fx, tg.dt_over_mass, vx * tg.keep);
+  vy = fmaf(fy, tg.dt_over_mass, vy * tg.keep);
+  const float s2 = fmaf(vx, vx, vy * vy);
+  if (s2 > me.limit_sq) {
+    const float k = me.limit * hw_rsq(s2);
+    vx *= k;
+    vy *= k;
+  }
+}
+
+// Reward of agent i on the new positions q (its own: px, py): every adversary gets 10 per touching (good,
+// adversary) pair, a good agent loses 10 per adversary touching it and pays the boundary penalty.
+template <typename S>
+__device__ __forceinline__ float tag_reward(int i, const TagRole& me, const TagPhys& tg, float px, float py,
+                                            const float (&qx)[S::N], const float (&qy)[S::N]) {
+  uint32_t caught = 0, hits = 0;
+#pragma unroll
+  for (int a = 0; a < S::A; ++a) {
+#pragma unroll
+    for (int b = S::A; b < S::N; ++b) {
+      const float dx = qx[a] - qx[b], dy = qy[a] - qy[b];
+      const uint32_t touch = fmaf(dx, dx, dy * dy) < tg.touch_sq ? 1u : 0u;
+      caught += touch;
+      hits += b == i ? touch : 0u;
+    }
+  }
+  const float r_good = -10.0f * float(hits) - tag_bound(fabsf(px)) - tag_bound(fabsf(py));
+  return me.role == 0 ? 10.0f * float(caught) : r_good;
+}
+
 // The same observation row into a register array (every index a compile-time constant): entries
 // 0 .. D - 1 of o; the caller zeroes what lies beyond.
 template <typename S, int W>
