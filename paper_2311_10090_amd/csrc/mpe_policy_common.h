@@ -55,6 +55,66 @@ __device__ __forceinline__ void group_barrier(uint32_t* arrived, uint32_t target
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 }
 
+// Lane-per-agent pieces of the simple-spread step, shared by the kernels that keep one agent per lane with all
+// positions of its env in registers.
+// Transition of agent i under `act`: control force, contacts with the N - 1 other agents on the pre-step
+// positions (the k-th OTHER agent is agent k for k < i, else k + 1: N - 1 evaluations on selected operands, in
+// ascending agent order; a loop over all agents that skips a == i would run N masked evaluations), position
+// with the old velocity, damped velocity.
+template <int N>
+__device__ __forceinline__ void agent_move(uint32_t act, int i, const Phys& ph, float& px, float& py, float& vx,
+                                           float& vy, const float (&qx)[N], const float (&qy)[N]) {
+  float fx = ph.accel * action_dir_x(act);
+  float fy = ph.accel * action_dir_y(act);
+#pragma unroll
+  for (int k = 0; k < N - 1; ++k) {
+    const bool up = k >= i;
+    const float dx = px - (up ? qx[k + 1] : qx[k]);
+    const float dy = py - (up ? qy[k + 1] : qy[k]);
+    const float kf = contact_factor(dx, dy, ph);
+    fx = fmaf(kf, dx, fx);
+    fy = fmaf(kf, dy, fy);
+  }
+  px = fmaf(vx, ph.dt, px);
+  py = fmaf(vy, ph.dt, py);
+  vx = fmaf(fx, ph.dt_over_mass, vx * ph.keep);
+  vy = fmaf(fy, ph.dt_over_mass, vy * ph.keep);
+}
+
+// Shared coverage reward of an env: minus the sum over landmarks of the distance to the nearest agent.
+template <int N, int LA>
+__device__ __forceinline__ float coverage_reward(const float (&qx)[N], const float (&qy)[N], const float (&lx)[LA],
+                                                 const float (&ly)[LA]) {
+  static_assert(LA >= N, "one landmark per agent");
+  float r = 0.0f;
+#pragma unroll
+  for (int l = 0; l < N; ++l) {
+    float best2 = INFINITY;
+#pragma unroll
+    for (int a = 0; a < N; ++a) {
+      const float dx = qx[a] - lx[l], dy = qy[a] - ly[l];
+      best2 = fminf(best2, fmaf(dx, dx, dy * dy));
+    }
+    r -= hw_sqrt(best2);
+  }
+  return r;
+}
+
+// Other agents whose centre is strictly closer than 2 r to agent i (mixed per-agent reward).
+template <int N>
+__device__ __forceinline__ uint32_t overlap_count(int i, float px, float py, const float (&qx)[N], const float (&qy)[N],
+                                                  const Phys& ph) {
+  uint32_t overlaps = 0;
+#pragma unroll
+  for (int a = 0; a < N; ++a) {
+    if (a != i) {
+      const float dx = px - qx[a], dy = py - qy[a];
+      overlaps += fmaf(dx, dx, dy * dy) < ph.two_r_sq ? 1u : 0u;
+    }
+  }
+  return overlaps;
+}
+
 // 4 x 4 transpose between register index and lane group (lane = 16 * group + j):
 // out[c] at lane (j, g) = in[g] at lane (j, c).  No memory involved.
 __device__ __forceinline__ void transpose_groups(uint32_t (&v)[4]) {

@@ -318,23 +318,7 @@ __global__ __launch_bounds__((EB * N + RW - 1) / RW * 64, MINW) void rollout_pol
     }
 
     // ---- transition of this lane's agent
-    float fx = A.ph.accel * action_dir_x(act);
-    float fy = A.ph.accel * action_dir_y(act);
-    // the k-th OTHER agent is agent k (k < i) or k + 1: N - 1 evaluations on selected operands, in
-    // ascending agent order (a loop over all agents that skips a == i runs N masked evaluations)
-#pragma unroll
-    for (int k = 0; k < N - 1; ++k) {
-      const bool up = k >= i;
-      const float dx = px - (up ? qx[k + 1] : qx[k]);
-      const float dy = py - (up ? qy[k + 1] : qy[k]);
-      const float kf = contact_factor(dx, dy, A.ph);
-      fx = fmaf(kf, dx, fx);
-      fy = fmaf(kf, dy, fy);
-    }
-    px = fmaf(vx, A.ph.dt, px);
-    py = fmaf(vy, A.ph.dt, py);
-    vx = fmaf(fx, A.ph.dt_over_mass, vx * A.ph.keep);
-    vy = fmaf(fy, A.ph.dt_over_mass, vy * A.ph.keep);
+    agent_move<N>(act, i, A.ph, px, py, vx, vy, qx, qy);
     float2* np = newpos + (t & 1) * ROWS;
     np[tid] = make_float2(px, py);
     // (C) new positions of every agent of every env of this 64-env group are visible
@@ -350,26 +334,9 @@ __global__ __launch_bounds__((EB * N + RW - 1) / RW * 64, MINW) void rollout_pol
     }
     // shared coverage reward, evaluated by every lane (N*N distances), stored by agent 0
     {
-      float r = 0.0f;
-#pragma unroll
-      for (int l = 0; l < N; ++l) {
-        float best2 = INFINITY;
-#pragma unroll
-        for (int a = 0; a < N; ++a) {
-          const float dx = qx[a] - lx[l], dy = qy[a] - ly[l];
-          best2 = fminf(best2, fmaf(dx, dx, dy * dy));
-        }
-        r -= hw_sqrt(best2);
-      }
+      const float r = coverage_reward(qx, qy, lx, ly);
       if constexpr (PER_AGENT) {
-        uint32_t overlaps = 0;
-#pragma unroll
-        for (int a = 0; a < N; ++a) {
-          if (a != i) {
-            const float dx = px - qx[a], dy = py - qy[a];
-            overlaps += fmaf(dx, dx, dy * dy) < A.ph.two_r_sq ? 1u : 0u;
-          }
-        }
+        const uint32_t overlaps = overlap_count<N>(i, px, py, qx, qy, A.ph);
         if (rew_base) {
           if (valid) rew_base[row_off] = mixed_reward(r, overlaps, A.ph);
           rew_base += TE * N;

@@ -477,22 +477,7 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(TagArgs TA, const uint
         tag_move<TS>(act, i, me, tg, px, py, vx, vy, qx, qy, lx, ly);
         xch4[tid] = make_float4(px, py, vx, vy);
       } else {
-        float fx = A.ph.accel * action_dir_x(act);
-        float fy = A.ph.accel * action_dir_y(act);
-        // the k-th OTHER agent is agent k (k < i) or k + 1: N - 1 evaluations, ascending agent order
-#pragma unroll
-        for (int k = 0; k < N - 1; ++k) {
-          const bool up = k >= i;
-          const float dx = px - (up ? qx[k + 1] : qx[k]);
-          const float dy = py - (up ? qy[k + 1] : qy[k]);
-          const float kf = contact_factor(dx, dy, A.ph);
-          fx = fmaf(kf, dx, fx);
-          fy = fmaf(kf, dy, fy);
-        }
-        px = fmaf(vx, A.ph.dt, px);
-        py = fmaf(vy, A.ph.dt, py);
-        vx = fmaf(fx, A.ph.dt_over_mass, vx * A.ph.keep);
-        vy = fmaf(fy, A.ph.dt_over_mass, vy * A.ph.keep);
+        agent_move<N>(act, i, A.ph, px, py, vx, vy, qx, qy);
         xch2[tid] = make_float2(px, py);
       }
     }
@@ -522,26 +507,9 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(TagArgs TA, const uint
           qx[a] = p.x;
           qy[a] = p.y;
         }
-        float r = 0.0f;
-#pragma unroll
-        for (int l = 0; l < N; ++l) {
-          float best2 = INFINITY;
-#pragma unroll
-          for (int a = 0; a < N; ++a) {
-            const float dx = qx[a] - lx[l], dy = qy[a] - ly[l];
-            best2 = fminf(best2, fmaf(dx, dx, dy * dy));
-          }
-          r -= hw_sqrt(best2);
-        }
+        const float r = coverage_reward(qx, qy, lx, ly);
         if (A.ph.reward_mode == 1) {
-          uint32_t overlaps = 0;
-#pragma unroll
-          for (int a = 0; a < N; ++a) {
-            if (a != i) {
-              const float dx = px - qx[a], dy = py - qy[a];
-              overlaps += fmaf(dx, dx, dy * dy) < A.ph.two_r_sq ? 1u : 0u;
-            }
-          }
+          const uint32_t overlaps = overlap_count<N>(i, px, py, qx, qy, A.ph);
           if (rew_base && valid) rew_base[row_off] = mixed_reward(r, overlaps, A.ph);
         } else if (rew_base && env_writer) {
           rew_base[gc] = r;
