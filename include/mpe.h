@@ -158,7 +158,7 @@ int mpe_step(mpe_env* env, const uint8_t* actions, float* obs, float* reward, ui
  * row-major [fan_in][fan_out], device pointers.  The library copies them into its own
  * operand layout on `stream` (rounding W to bf16, ties to even, when weight_dtype is
  * MPE_WEIGHTS_BF16); the caller's arrays are not referenced after that work has run.
- * Policies are built for (num_agents, hidden, weight_dtype) in (1..3, 64, fp32 or bf16), (4..7, 64, fp32)
+ * Policies are built for (num_agents, hidden, weight_dtype) in (1..3, 64, fp32 or bf16), (4..10, 64, fp32)
  * and (4..10, 64 | 128, bf16); with MPE_SCENARIO_TAG for hidden 64, fp32 or bf16, every shape of mpe_create
  * (D <= 32).  MPE_EINVAL for other shapes, if only some pointers are NULL, or if the config has no
  * usable `hidden`. */
@@ -226,7 +226,7 @@ int mpe_set_barrier_poll_limit(mpe_env* env, uint32_t polls);
  *   value = V3^T tanh(V2^T tanh(V1^T obs + c1) + c2) + c3
  * V1 [R][D][H], c1 [R][H], V2 [R][H][H], c2 [R][H], V3 [R][H], c3 [R], fp32 device pointers;
  * copied (and rounded, with MPE_WEIGHTS_BF16) as in mpe_set_policy.  Built for the shapes of
- * mpe_set_policy with MPE_SCENARIO_SPREAD (1..3 agents, hidden 64, fp32 or bf16 weights; 4..7 agents,
+ * mpe_set_policy with MPE_SCENARIO_SPREAD (1..3 agents, hidden 64, fp32 or bf16 weights; 4..10 agents,
  * hidden 64, fp32 weights; 4..10 agents, hidden 64 or 128, bf16 weights), and for MPE_SCENARIO_TAG with hidden 64, fp32 or bf16 weights;
  * MPE_EINVAL otherwise. */
 int mpe_set_critic(mpe_env* env, const float* V1, const float* c1, const float* V2,
@@ -239,8 +239,8 @@ int mpe_set_critic(mpe_env* env, const float* V1, const float* c1, const float* 
  * logp_traj, value_traj [T][TE][N] fp32, last_value [TE][N] fp32; the other arrays as in
  * mpe_rollout (rewards [T][TE][N] where mpe_rollout's are).  Any of the eight may be NULL.  Needs
  * a policy and a critic (MPE_ESTATE if one is missing); with several runs num_envs must be a
- * multiple of 16 (fastest: of 256; 4 and more agents: of 64, of 32 with 8 agents, and with 7 agents and
- * fp32 weights;
+ * multiple of 16 (fastest: of 256; 4 and more agents: of 64, of 32 with 8 agents and bf16 weights or 7
+ * agents and fp32 weights, of 16 with 8 to 10 agents and fp32 weights;
  * MPE_SCENARIO_TAG: fastest with multiples of 512 / num_agents where that divides 64, else of 64, of 32
  * with 10 agents), MPE_EINVAL
  * otherwise. */

@@ -130,7 +130,7 @@ hipError_t launch_rollout_policy_wide(int N, int H, const RolloutArgs& A, const 
                                       const char** why);
 bool uniform_wide_supported(int N);                      // env-only rollout with the wide kernel's mapping
 hipError_t launch_rollout_uniform_wide(int N, const RolloutArgs& A, hipStream_t s);
-bool f32_supported(int N, int H, bool bf16);             // headline kernel (H = 64; N <= 3, with fp32 weights N <= 7)
+bool f32_supported(int N, int H, bool bf16);             // headline kernel (H = 64; N <= 3, with fp32 weights N <= 10)
 size_t packed_run_bytes_f32(int N, bool bf16);
 hipError_t pack_policy_f32(PolicyBuffers& pb, int N, int R, const float* W1, const float* b1, const float* W2,
                            const float* b2, const float* W3, const float* b3, int nout, bool bf16, hipStream_t s);

@@ -3,10 +3,11 @@
 // and the forward pass of two 16-row tiles (fp32 split-operand and bf16 variants).  Shared by the kernels
 // of both scenarios; everything is templated on a shape S:
 //   S::D         floats per observation row in the LDS tile (row stride)
-//   S::KIN       leading inputs of a row that the first layer reads (<= 32; the rest of the row is
+//   S::KIN       leading inputs of a row that the first layer reads (<= 64; the rest of the row is
 //                zero in every observation); up to 16 inputs ride in half of an instruction's K
 //                positions and the other half carries a second term (S::kWideIn false), 17..32 inputs
-//                fill the K slice and layer 1 takes the six instructions of any other product
+//                fill the K slice and layer 1 takes the six instructions of any other product,
+//                33..64 inputs are two such slices (S::kSlices1)
 //   S::kRowTerms layer 3 with the weight terms along the output rows (needs 7 scratch floats per row)
 #pragma once
 
@@ -20,7 +21,8 @@ struct NetShape {
   static constexpr int KIN = KIN_;
   static constexpr bool kRowTerms = KIN_ >= 7;
   static constexpr bool kWideIn = KIN_ > 16;
-  static_assert(KIN_ <= 32 && KIN_ <= D_ && D_ % 2 == 0, "layer 1 reads one K slice, rows are float2-aligned");
+  static constexpr int kSlices1 = KIN_ > 32 ? 2 : 1;     // K slices of layer 1
+  static_assert(KIN_ <= 64 && KIN_ <= D_ && D_ % 2 == 0, "layer 1 reads at most two K slices, rows are float2-aligned");
 };
 
 namespace {
@@ -81,7 +83,8 @@ __device__ __forceinline__ void split3(float x, uint32_t& h, uint32_t& m, uint32
 //                                 gq < 2) carry one term of input k' = 8 (gq & 1) + e, positions
 //                                 16..31 (gq >= 2) another term of the same inputs.
 //                                 combo 0 = (h | m), combo 1 = (h | l)
-//   W1A [m 4][term 3][lane 64]   shapes with 17..32 inputs (kWideIn): k = 8 gq + e, all three terms
+//   W1A [m 4][s][term 3][lane 64]  shapes with 17..64 inputs (kWideIn; s = K slice, one or two): k = 32 s + 8 gq + e,
+//                                 all three terms
 //   W2A [m 4][s 2][term 3][lane 64]
 //   W3A [s 2][term 3][lane 64]   (5 outputs padded to 16), shapes without kRowTerms only
 //   W3A [s 2][lane 64]           kRowTerms: the 16 output rows of the instruction carry the three
@@ -90,12 +93,13 @@ __device__ __forceinline__ void split3(float x, uint32_t& h, uint32_t& m, uint32
 //   bias b1*pre [64], b2*pre [64], b3 [16] fp32 (kRowTerms: b3 in the h-term row of each output)
 //
 // bf16 variant (BF): one term per weight, rounded to bf16 (nearest even), nothing pre-scaled:
-//   W1A [m 4][lane 64]  (K positions 16..31 are zero unless kWideIn), W2A [m 4][s 2][lane 64], W3A [s 2][lane 64]
+//   W1A [m 4][s][lane 64]  (K positions 16..31 are zero unless kWideIn; s = K slice as above), W2A [m 4][s 2][lane 64], W3A [s 2][lane 64]
 //   (5 outputs padded to 16), bias b1 [64], b2 [64], b3 [16] fp32
-template <bool BF, bool WIDE_IN = false>
+template <bool BF, bool WIDE_IN = false, int KS1 = 1>
 struct PkT {
+  static_assert(KS1 == 1 || WIDE_IN, "two K slices only in the wide-input layout");
   static constexpr size_t OFF_W1A = 0;
-  static constexpr size_t W1A_BYTES = BF ? 4 * 64 * 16 : (WIDE_IN ? 4 * 3 * 64 * 16 : 4 * 2 * 64 * 16);
+  static constexpr size_t W1A_BYTES = BF ? 4 * KS1 * 64 * 16 : (WIDE_IN ? 4 * KS1 * 3 * 64 * 16 : 4 * 2 * 64 * 16);
   static constexpr size_t OFF_W2A = OFF_W1A + W1A_BYTES;
   static constexpr size_t W2A_BYTES = BF ? 4 * 2 * 64 * 16 : 4 * 2 * 3 * 64 * 16;
   static constexpr size_t OFF_W3A = OFF_W2A + W2A_BYTES;
@@ -118,6 +122,10 @@ __host__ __device__ constexpr int l3_row_term(int i) { return i % 4 < 3 ? i % 4 
 // hidden unit of K position (slice s, lane group gq, element e) in layers 2/3
 __host__ __device__ constexpr int hidden_k(int s, int gq, int e) { return 32 * s + 16 * (e / 4) + 4 * gq + (e % 4); }
 
+// Threads of either pack kernel: one per weight (layer 1 padded to its K slices) or bias value.
+template <typename S>
+constexpr int pack_threads() { return 4 * S::kSlices1 * 64 * 8 + 4 * 2 * 64 * 8 + 2 * 64 * 8 + 2 * kH + 16; }
+
 // One thread per packed bf16 element (all three terms of one weight) or bias value.
 template <typename S>
 __global__ void pack_split_kernel(uint8_t* __restrict__ packed, const float* __restrict__ W1,
@@ -125,8 +133,8 @@ __global__ void pack_split_kernel(uint8_t* __restrict__ packed, const float* __r
                                   const float* __restrict__ b2, const float* __restrict__ W3,
                                   const float* __restrict__ b3, int nout) {
   // nout = outputs of the last layer: 5 (policy logits) or 1 (critic value); W3 is [H][nout]
-  using Pk = PkT<false, S::kWideIn>;
-  constexpr int D = S::D, KIN = S::KIN;
+  using Pk = PkT<false, S::kWideIn, S::kSlices1>;
+  constexpr int D = S::D, KIN = S::KIN, KS1 = S::kSlices1;
   const int run = blockIdx.y;
   uint8_t* out = packed + size_t(run) * Pk::RUN_BYTES;
   W1 += size_t(run) * D * kH;
@@ -135,7 +143,7 @@ __global__ void pack_split_kernel(uint8_t* __restrict__ packed, const float* __r
   b2 += size_t(run) * kH;
   W3 += size_t(run) * kH * nout;
   b3 += size_t(run) * nout;
-  constexpr int n1 = 4 * 64 * 8, n2 = 4 * 2 * 64 * 8, n3 = 2 * 64 * 8, nb = 2 * kH + 16;
+  constexpr int n1 = 4 * KS1 * 64 * 8, n2 = 4 * 2 * 64 * 8, n3 = 2 * 64 * 8, nb = 2 * kH + 16;
   int idx = blockIdx.x * blockDim.x + threadIdx.x;
   auto put3 = [&](size_t off, int blk, int lanes, int lane, int e, float v) {
     // blk = index of the [term][lane] group; terms are `lanes` * 16 bytes apart
@@ -147,12 +155,14 @@ __global__ void pack_split_kernel(uint8_t* __restrict__ packed, const float* __r
     base[size_t(2) * lanes * 8] = uint16_t(l);
   };
   if (idx < n1) {
-    const int e = idx % 8, lane = (idx / 8) % 64, m = idx / 512;
+    const int e = idx % 8, lane = (idx / 8) % 64;
     if constexpr (S::kWideIn) {
-      const int k = 8 * (lane / 16) + e;
-      put3(Pk::OFF_W1A, m, 64, lane, e, k < KIN ? kPre * W1[size_t(k) * kH + 16 * m + lane % 16] : 0.0f);
+      const int sl = (idx / 512) % KS1, mw = idx / (512 * KS1);
+      const int k = 32 * sl + 8 * (lane / 16) + e;
+      put3(Pk::OFF_W1A, mw * KS1 + sl, 64, lane, e, k < KIN ? kPre * W1[size_t(k) * kH + 16 * mw + lane % 16] : 0.0f);
       return;
     }
+    const int m = idx / 512;
     const int gq = lane / 16, k = 8 * (gq & 1) + e, o = 16 * m + lane % 16;
     uint32_t h, mm, l;
     split3(k < KIN ? kPre * W1[size_t(k) * kH + o] : 0.0f, h, mm, l);
@@ -272,9 +282,10 @@ __device__ __forceinline__ Terms tanh_split(const f32x4& a0, const f32x4& a1) {
 // inputs 8 (gq & 1) .. + 7 of row j; kWideIn: inputs 8 gq .. + 7, zero beyond the row), zX / zY = the layer-3 accumulators of the two tiles.
 template <typename S>
 __device__ __forceinline__ void policy_core(const uint8_t* __restrict__ wsm, const float* __restrict__ bias,
-                                            const W3Terms& w3, const float (&vx)[8], const float (&vy)[8],
-                                            f32x4& zX, f32x4& zY, int lane) {
-  using Pk = PkT<false, S::kWideIn>;
+                                            const W3Terms& w3, const float (&vx)[S::kSlices1][8],
+                                            const float (&vy)[S::kSlices1][8], f32x4& zX, f32x4& zY, int lane) {
+  using Pk = PkT<false, S::kWideIn, S::kSlices1>;
+  constexpr int KS1 = S::kSlices1;
   const int gq = lane >> 4;
   // The network runs at a raised wavefront priority: a wavefront that has matrix instructions to issue goes
   // ahead of the wavefronts of its SIMD that are in the (vector-only) env step, whose instructions then fill
@@ -294,19 +305,23 @@ __device__ __forceinline__ void policy_core(const uint8_t* __restrict__ wsm, con
   const bf16x8* w2 = reinterpret_cast<const bf16x8*>(wsm + Pk::OFF_W2A);  // [m][s][term][lane64]
   // Layer 1, one output tile: the six cross terms in three instructions, smallest first:
   //   (Wh | Wl) x (Xl | Xh) = hl + lh,  (Wh | Wm) x (Xm | Xm) = hm + mm,  (Wh | Wm) x (Xh | Xh) = hh + mh
-  auto layer1 = [&](int m, const Terms& b, const bf16x8& b_lh, f32x4 acc) {
-    if constexpr (S::kWideIn) {   // 17..32 inputs fill the K slice: the six cross terms, one instruction each
-      Terms a;
-      a.h = w1[(m * 3 + 0) * 64 + lane];
-      a.m = w1[(m * 3 + 1) * 64 + lane];
-      a.l = w1[(m * 3 + 2) * 64 + lane];
-      return mma_split(a, b, acc);
+  auto layer1 = [&](int m, const Terms (&b)[KS1], const bf16x8& b_lh, f32x4 acc) {
+    if constexpr (S::kWideIn) {   // 17..64 inputs fill one or two K slices: the six cross terms, one instruction each
+#pragma unroll
+      for (int s = 0; s < KS1; ++s) {
+        Terms a;
+        a.h = w1[((m * KS1 + s) * 3 + 0) * 64 + lane];
+        a.m = w1[((m * KS1 + s) * 3 + 1) * 64 + lane];
+        a.l = w1[((m * KS1 + s) * 3 + 2) * 64 + lane];
+        acc = mma_split(a, b[s], acc);
+      }
+      return acc;
     }
     const bf16x8 a_hm = w1[(m * 2 + 0) * 64 + lane];
     const bf16x8 a_hl = w1[(m * 2 + 1) * 64 + lane];
     acc = MPE_MFMA_SPLIT(a_hl, b_lh, acc);
-    acc = MPE_MFMA_SPLIT(a_hm, b.m, acc);
-    acc = MPE_MFMA_SPLIT(a_hm, b.h, acc);
+    acc = MPE_MFMA_SPLIT(a_hm, b[0].m, acc);
+    acc = MPE_MFMA_SPLIT(a_hm, b[0].h, acc);
     return acc;
   };
   auto load_w2 = [&](int m, int s) {
@@ -330,13 +345,16 @@ __device__ __forceinline__ void policy_core(const uint8_t* __restrict__ wsm, con
   };
   // ---- split(obs): 16 inputs (cols 0..15 of the row; cols >= 4N+2 are zeros or meet zero weights);
   // lanes gq and gq + 2 hold the same 8 inputs
-  Terms bx, by;
-  bf16x8 bx_lh, by_lh;  // (Xl | Xh): l in K positions 0..15, h in 16..31
+  Terms bx[KS1], by[KS1];
+  bf16x8 bx_lh, by_lh;  // (Xl | Xh): l in K positions 0..15, h in 16..31 (shapes of up to 16 inputs)
   {
-    bx = split_operand(vx);
-    by = split_operand(vy);
-    bx_lh = gq < 2 ? bx.l : bx.h;
-    by_lh = gq < 2 ? by.l : by.h;
+#pragma unroll
+    for (int s = 0; s < KS1; ++s) {
+      bx[s] = split_operand(vx[s]);
+      by[s] = split_operand(vy[s]);
+    }
+    bx_lh = gq < 2 ? bx[0].l : bx[0].h;
+    by_lh = gq < 2 ? by[0].l : by[0].h;
   }
   f32x4 accX[4], accY[4];
 #pragma unroll
@@ -428,12 +446,13 @@ __device__ __forceinline__ void policy_core(const uint8_t* __restrict__ wsm, con
   __builtin_amdgcn_s_setprio(0);
 }
 
-// This lane's 8 layer-1 inputs of row j (see policy_core): columns 8 (gq & 1) .. + 7, or, with 17..32 inputs,
-// columns 8 gq .. + 7 with zeros beyond the row's D columns (what lies there is the next row).
+// This lane's 8 layer-1 inputs of row j for one K slice (see policy_core): columns 8 (gq & 1) .. + 7, or, with
+// 17..64 inputs, columns 32 slice + 8 gq .. + 7 with zeros beyond the row's D columns (what lies there is the
+// next row).
 template <typename S>
-__device__ __forceinline__ void load_row_inputs(const float* __restrict__ rows, int j, int gq, float (&v)[8]) {
+__device__ __forceinline__ void load_row_inputs(const float* __restrict__ rows, int j, int gq, int slice, float (&v)[8]) {
   constexpr int D = S::D;
-  const int c0 = S::kWideIn ? 8 * gq : 8 * (gq & 1);
+  const int c0 = 32 * slice + (S::kWideIn ? 8 * gq : 8 * (gq & 1));
   // rows are D*4 bytes apart (a multiple of 8, not of 16): read as float2
   const float2* src = reinterpret_cast<const float2*>(rows + j * D + c0);
 #pragma unroll
@@ -454,9 +473,12 @@ __device__ __forceinline__ void policy_pair(const uint8_t* __restrict__ wsm, con
                                             float* __restrict__ valX = nullptr, float* __restrict__ valY = nullptr) {
   constexpr int D = S::D;
   const int j = lane & 15, gq = lane >> 4;
-  float vx[8], vy[8];
-  load_row_inputs<S>(rowsX, j, gq, vx);
-  load_row_inputs<S>(rowsY, j, gq, vy);
+  float vx[S::kSlices1][8], vy[S::kSlices1][8];
+#pragma unroll
+  for (int s = 0; s < S::kSlices1; ++s) {
+    load_row_inputs<S>(rowsX, j, gq, s, vx[s]);
+    load_row_inputs<S>(rowsY, j, gq, s, vy[s]);
+  }
   f32x4 zX, zY;
   policy_core<S>(wsm, bias, w3, vx, vy, zX, zY, lane);
   if constexpr (VALUE) {
@@ -503,7 +525,8 @@ __global__ void pack_bf16_kernel(uint8_t* __restrict__ packed, const float* __re
                                  const float* __restrict__ b1, const float* __restrict__ W2,
                                  const float* __restrict__ b2, const float* __restrict__ W3,
                                  const float* __restrict__ b3, int nout) {
-  constexpr int D = S::D, KIN = S::KIN;
+  using PkB = PkT<true, S::kWideIn, S::kSlices1>;
+  constexpr int D = S::D, KIN = S::KIN, KS1 = S::kSlices1;
   const int run = blockIdx.y;
   uint8_t* out = packed + size_t(run) * PkB::RUN_BYTES;
   W1 += size_t(run) * D * kH;
@@ -512,11 +535,11 @@ __global__ void pack_bf16_kernel(uint8_t* __restrict__ packed, const float* __re
   b2 += size_t(run) * kH;
   W3 += size_t(run) * kH * nout;
   b3 += size_t(run) * nout;
-  constexpr int n1 = 4 * 64 * 8, n2 = 4 * 2 * 64 * 8, n3 = 2 * 64 * 8, nb = 2 * kH + 16;
+  constexpr int n1 = 4 * KS1 * 64 * 8, n2 = 4 * 2 * 64 * 8, n3 = 2 * 64 * 8, nb = 2 * kH + 16;
   int idx = blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx < n1) {   // [m][lane][e]; k = 8 gq + e for gq < 2, zero above (all four lane groups when kWideIn)
-    const int e = idx % 8, lane = (idx / 8) % 64, m = idx / 512;
-    const int gq = lane / 16, k = 8 * gq + e, o = 16 * m + lane % 16;
+  if (idx < n1) {   // [m][s][lane][e]; k = 8 gq + e for gq < 2, zero above (all four lane groups when kWideIn)
+    const int e = idx % 8, lane = (idx / 8) % 64, sl = (idx / 512) % KS1, m = idx / (512 * KS1);
+    const int gq = lane / 16, k = 32 * sl + 8 * gq + e, o = 16 * m + lane % 16;
     reinterpret_cast<uint16_t*>(out + PkB::OFF_W1A)[idx] = f32_to_bf16_rne(((gq < 2 || S::kWideIn) && k < KIN) ? W1[size_t(k) * kH + o] : 0.0f);
     return;
   }
@@ -578,23 +601,26 @@ __device__ __forceinline__ void policy_pair_bf(const uint8_t* __restrict__ wsm, 
     wsm += zero;
     bias += zero;
   }
-  const bf16x8* w1 = reinterpret_cast<const bf16x8*>(wsm + PkB::OFF_W1A);  // [m][lane]
+  using PkB = PkT<true, S::kWideIn, S::kSlices1>;
+  constexpr int KS1 = S::kSlices1;
+  const bf16x8* w1 = reinterpret_cast<const bf16x8*>(wsm + PkB::OFF_W1A);  // [m][slice][lane]
   const bf16x8* w2 = reinterpret_cast<const bf16x8*>(wsm + PkB::OFF_W2A);  // [m][s][lane]
   // layer-1 B operands: inputs 8 (gq & 1) .. + 7 of the row, lane groups 2, 3 meet zero weights; with
   // 17..32 inputs, inputs 8 gq .. + 7
-  bf16x8 bx, by;
-  {
+  bf16x8 bx[KS1], by[KS1];
+#pragma unroll
+  for (int s = 0; s < KS1; ++s) {
     float vx[8], vy[8];
-    load_row_inputs<S>(rowsX, j, gq, vx);
-    load_row_inputs<S>(rowsY, j, gq, vy);
+    load_row_inputs<S>(rowsX, j, gq, s, vx);
+    load_row_inputs<S>(rowsY, j, gq, s, vy);
     u32x4 px, py;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       px[q] = pack_bf16_rne(vx[2 * q], vx[2 * q + 1]);
       py[q] = pack_bf16_rne(vy[2 * q], vy[2 * q + 1]);
     }
-    bx = __builtin_bit_cast(bf16x8, px);
-    by = __builtin_bit_cast(bf16x8, py);
+    bx[s] = __builtin_bit_cast(bf16x8, px);
+    by[s] = __builtin_bit_cast(bf16x8, py);
   }
   f32x4 accX[4], accY[4];
 #pragma unroll
@@ -604,9 +630,12 @@ __device__ __forceinline__ void policy_pair_bf(const uint8_t* __restrict__ wsm, 
   }
 #pragma unroll
   for (int m = 0; m < 4; ++m) {
-    const bf16x8 a = w1[m * 64 + lane];
-    accX[m] = MPE_MFMA_BF(a, bx, accX[m]);
-    accY[m] = MPE_MFMA_BF(a, by, accY[m]);
+#pragma unroll
+    for (int s = 0; s < KS1; ++s) {
+      const bf16x8 a = w1[(m * KS1 + s) * 64 + lane];
+      accX[m] = MPE_MFMA_BF(a, bx[s], accX[m]);
+      accY[m] = MPE_MFMA_BF(a, by[s], accY[m]);
+    }
   }
   bf16x8 hx[2], hy[2];
 #pragma unroll

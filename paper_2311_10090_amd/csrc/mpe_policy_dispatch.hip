@@ -25,7 +25,7 @@ void free_policy(PolicyBuffers& pb) {
 }
 
 static const char* kUnsupported =
-    "unsupported policy shape: need (num_agents, hidden, dtype) in {(1..3, 64, fp32 or bf16), (4..7, 64, fp32), "
+    "unsupported policy shape: need (num_agents, hidden, dtype) in {(1..3, 64, fp32 or bf16), (4..10, 64, fp32), "
     "(4..10, 64 | 128, bf16)}";
 
 size_t packed_policy_bytes(int N, int H, int R, int weight_dtype) {

@@ -1,5 +1,6 @@
 // Fused rollout kernel for the headline shape: fp32 policy 6N -> 64 -> 64 -> 5 (N <= 3 agents; with fp32 weights
-// also 4 to 7 agents, whose 4N + 2 live inputs still fit the one K slice of layer 1, in 64-env blocks),
+// also 4 to 10 agents, whose 4N + 2 live inputs fill one K slice of layer 1 (up to 7 agents, 64-env blocks) or two
+// (8 to 10 agents, 32-env blocks)),
 // shared by all agents or one set of weights per run (paper: App. G IPPO table, two tanh layers
 // of width 64; Sec. 3.2 parameter sharing; Sec. 5.2 and App. E: whole training runs vectorised on one device).
 //
@@ -49,7 +50,7 @@ using SpreadNet = NetShape<6 * N, 4 * N + 2>;
 // 3 agents have such padding rows: 48 -> 64; no env owns them and nothing of them leaves the block).
 template <int N, int EB, bool AC = false, bool BF = false, int RW = 64>
 struct SmemF32 {
-  using P = PkT<BF, SpreadNet<N>::kWideIn>;
+  using P = PkT<BF, SpreadNet<N>::kWideIn, SpreadNet<N>::kSlices1>;
   static constexpr int D = 6 * N;
   static constexpr int ROWS = (EB * N + RW - 1) / RW * RW;
   // LEAN (actor-critic in 16-env blocks, i.e. many small runs): W3A of both networks stays in global memory
@@ -537,13 +538,13 @@ __global__ __launch_bounds__(256 * N, 1) void rollout_policy_f32_reg_kernel(Roll
     f32x4 z[4];
 #pragma unroll
     for (int pr = 0; pr < 2; ++pr) {
-      float inX[8], inY[8];
+      float inX[1][8], inY[1][8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         uint32_t v[4] = {__float_as_uint(o[e]), __float_as_uint(o[8 + e]), __float_as_uint(o[e]), __float_as_uint(o[8 + e])};
         transpose_groups(v);
-        inX[e] = __uint_as_float(v[2 * pr]);
-        inY[e] = __uint_as_float(v[2 * pr + 1]);
+        inX[0][e] = __uint_as_float(v[2 * pr]);
+        inY[0][e] = __uint_as_float(v[2 * pr + 1]);
       }
       policy_core<Net>(wsm, bias, w3, inX, inY, z[2 * pr], z[2 * pr + 1], lane);
     }
@@ -570,21 +571,7 @@ __global__ __launch_bounds__(256 * N, 1) void rollout_policy_f32_reg_kernel(Roll
     }
 
     // ---- transition of this lane's agent
-    float fx = A.ph.accel * action_dir_x(act);
-    float fy = A.ph.accel * action_dir_y(act);
-#pragma unroll
-    for (int k = 0; k < N - 1; ++k) {
-      const bool up = k >= i;
-      const float dx = px - (up ? qx[k + 1] : qx[k]);
-      const float dy = py - (up ? qy[k + 1] : qy[k]);
-      const float kf = contact_factor(dx, dy, A.ph);
-      fx = fmaf(kf, dx, fx);
-      fy = fmaf(kf, dy, fy);
-    }
-    px = fmaf(vx, A.ph.dt, px);
-    py = fmaf(vy, A.ph.dt, py);
-    vx = fmaf(fx, A.ph.dt_over_mass, vx * A.ph.keep);
-    vy = fmaf(fy, A.ph.dt_over_mass, vy * A.ph.keep);
+    agent_move<N>(act, i, A.ph, px, py, vx, vy, qx, qy);
     float2* np = newpos + (t & 1) * ROWS_G;
     np[r] = make_float2(px, py);
     // (C) new positions of every agent of every env of this 64-env group are visible
@@ -597,26 +584,9 @@ __global__ __launch_bounds__(256 * N, 1) void rollout_policy_f32_reg_kernel(Roll
     }
     // shared coverage reward, evaluated by every lane (N*N distances), stored by agent 0
     {
-      float rw = 0.0f;
-#pragma unroll
-      for (int l = 0; l < N; ++l) {
-        float best2 = INFINITY;
-#pragma unroll
-        for (int a = 0; a < N; ++a) {
-          const float dx = qx[a] - lx[l], dy = qy[a] - ly[l];
-          best2 = fminf(best2, fmaf(dx, dx, dy * dy));
-        }
-        rw -= hw_sqrt(best2);
-      }
+      const float rw = coverage_reward(qx, qy, lx, ly);
       if constexpr (PER_AGENT) {
-        uint32_t overlaps = 0;
-#pragma unroll
-        for (int a = 0; a < N; ++a) {
-          if (a != i) {
-            const float dx = px - qx[a], dy = py - qy[a];
-            overlaps += fmaf(dx, dx, dy * dy) < A.ph.two_r_sq ? 1u : 0u;
-          }
-        }
+        const uint32_t overlaps = overlap_count<N>(i, px, py, qx, qy, A.ph);
         if (rew_base) {
           if (valid) rew_base[row_off] = mixed_reward(rw, overlaps, A.ph);
           rew_base += TE * N;
@@ -703,16 +673,21 @@ hipError_t rollout_impl(const RolloutArgs& A, const PolicyBuffers& pb, hipStream
 template <int N>
 hipError_t pack_impl(PolicyBuffers& pb, int R, const float* W1, const float* b1, const float* W2,
                      const float* b2, const float* W3, const float* b3, int nout, bool bf16, hipStream_t s) {
-  const size_t run_bytes = bf16 ? PkB::RUN_BYTES : PkT<false, SpreadNet<N>::kWideIn>::RUN_BYTES;
-  if (hipError_t e = ensure_policy_bytes(pb, size_t(R) * run_bytes); e != hipSuccess) return e;
-  constexpr int total = 4 * 64 * 8 + 4 * 2 * 64 * 8 + 2 * 64 * 8 + 2 * kH + 16;   // threads: one per weight / bias
+  const size_t run_bytes = PkT<false, SpreadNet<N>::kWideIn, SpreadNet<N>::kSlices1>::RUN_BYTES;
+  if (bf16 && N > 3) return hipErrorInvalidValue;
+  const size_t bytes1 = bf16 ? PkB::RUN_BYTES : run_bytes;
+  if (hipError_t e = ensure_policy_bytes(pb, size_t(R) * bytes1); e != hipSuccess) return e;
+  constexpr int total = pack_threads<SpreadNet<N>>();
   dim3 grid((total + 255) / 256, R);
-  if (bf16)
-    hipLaunchKernelGGL(pack_bf16_kernel<SpreadNet<N>>, grid, dim3(256), 0, s, static_cast<uint8_t*>(pb.packed), W1, b1, W2,
-                       b2, W3, b3, nout);
-  else
-    hipLaunchKernelGGL(pack_split_kernel<SpreadNet<N>>, grid, dim3(256), 0, s, static_cast<uint8_t*>(pb.packed), W1, b1, W2,
-                       b2, W3, b3, nout);
+  if constexpr (N <= 3) {
+    if (bf16) {
+      hipLaunchKernelGGL(pack_bf16_kernel<SpreadNet<N>>, grid, dim3(256), 0, s, static_cast<uint8_t*>(pb.packed), W1, b1, W2,
+                         b2, W3, b3, nout);
+      return hipGetLastError();
+    }
+  }
+  hipLaunchKernelGGL(pack_split_kernel<SpreadNet<N>>, grid, dim3(256), 0, s, static_cast<uint8_t*>(pb.packed), W1, b1, W2,
+                     b2, W3, b3, nout);
   return hipGetLastError();
 }
 
@@ -756,14 +731,15 @@ hipError_t launch_n(const RolloutArgs& A, const PolicyBuffers& pb, hipStream_t s
   const bool one_run = A.TE == A.E;
   const bool per_agent = A.ph.reward_mode == 1;
   if constexpr (N > 3) {
-    // 4 to 7 agents (fp32 weights; bf16 ones run the lane-per-agent bf16 kernel): 64-env blocks of N wavefronts,
-    // one or two per CU by their LDS
+    // 4 to 10 agents (fp32 weights; bf16 ones run the lane-per-agent bf16 kernel): blocks of 64 envs (N wavefronts,
+    // one or two per CU by their LDS) up to 7 agents, of 32 envs beyond (the rows are 6 N floats wide)
     static_assert(!BF, "bf16 weights with 4 and more agents are another kernel's");
-    if (!one_run && A.E % 64 != 0) {
-      *why = "with several runs and 4 or more agents, num_envs per run must be a multiple of 64";
+    constexpr int kEnvs = N <= 7 ? 64 : 32;
+    if (!one_run && A.E % kEnvs != 0) {
+      *why = "with several runs and 4 or more agents, num_envs per run must be a multiple of 64 (of 32 with 8 to 10 agents)";
       return hipSuccess;
     }
-    return per_agent ? rollout_impl<N, 64, 1, true, false, false>(A, pb, s) : rollout_impl<N, 64, 1, false, false, false>(A, pb, s);
+    return per_agent ? rollout_impl<N, kEnvs, 1, true, false, false>(A, pb, s) : rollout_impl<N, kEnvs, 1, false, false, false>(A, pb, s);
   } else {
   if (one_run && A.TE / 256 >= compute_units())
     return per_agent ? rollout_impl<N, 256, 3, true, false, BF>(A, pb, s) : rollout_impl<N, 256, 3, false, false, BF>(A, pb, s);
@@ -801,11 +777,11 @@ hipError_t launch_ac_n(const RolloutArgs& A, const PolicyBuffers& pb, const Poli
   const bool one_run = A.TE == A.E;
   const bool per_agent = A.ph.reward_mode == 1;
   if constexpr (N > 3) {
-    // both staged images and the block's observation rows: 64 envs up to 6 agents, 32 envs with 7
+    // both staged images and the block's observation rows: 64 envs up to 6 agents, 32 envs with 7, 16 envs beyond
     static_assert(!BF, "bf16 weights with 4 and more agents are another kernel's");
-    constexpr int kEnvs = N <= 6 ? 64 : 32;
+    constexpr int kEnvs = N <= 6 ? 64 : (N == 7 ? 32 : 16);
     if (!one_run && A.E % kEnvs != 0) {
-      *why = "with several runs and 4 or more agents, num_envs per run must be a multiple of 64 (of 32 with 7 agents)";
+      *why = "with several runs and 4 or more agents, num_envs per run must be a multiple of 64 (of 32 with 7 agents, of 16 with 8 to 10)";
       return hipSuccess;
     }
     return per_agent ? rollout_impl<N, kEnvs, 1, true, true, false>(A, pb, s, critic.packed)
@@ -830,12 +806,14 @@ hipError_t launch_ac_n(const RolloutArgs& A, const PolicyBuffers& pb, const Poli
 
 }  // namespace
 
-// fp32 weights: 1..7 agents (the 4N + 2 live inputs of a row fit layer 1's one K slice); bf16 weights: 1..3
-// (4 and more agents with bf16 weights run the lane-per-agent bf16 kernel)
-bool f32_supported(int N, int H, bool bf16) { return H == kH && N >= 1 && N <= (bf16 ? 3 : 7); }
+// fp32 weights: 1..10 agents (the 4N + 2 live inputs of a row fill half a K slice of layer 1, one slice or
+// two); bf16 weights: 1..3 (4 and more agents with bf16 weights run the lane-per-agent bf16 kernel)
+bool f32_supported(int N, int H, bool bf16) { return H == kH && N >= 1 && N <= (bf16 ? 3 : 10); }
 
 size_t packed_run_bytes_f32(int N, bool bf16) {
-  return bf16 ? PkB::RUN_BYTES : (4 * N + 2 > 16 ? PkT<false, true>::RUN_BYTES : Pk::RUN_BYTES);
+  if (bf16) return PkB::RUN_BYTES;
+  const int kin = 4 * N + 2;
+  return kin > 32 ? PkT<false, true, 2>::RUN_BYTES : (kin > 16 ? PkT<false, true>::RUN_BYTES : Pk::RUN_BYTES);
 }
 
 hipError_t pack_policy_f32(PolicyBuffers& pb, int N, int R, const float* W1, const float* b1, const float* W2,
@@ -848,6 +826,9 @@ hipError_t pack_policy_f32(PolicyBuffers& pb, int N, int R, const float* W1, con
     case 5: return bf16 ? hipErrorInvalidValue : pack_impl<5>(pb, R, W1, b1, W2, b2, W3, b3, nout, false, s);
     case 6: return bf16 ? hipErrorInvalidValue : pack_impl<6>(pb, R, W1, b1, W2, b2, W3, b3, nout, false, s);
     case 7: return bf16 ? hipErrorInvalidValue : pack_impl<7>(pb, R, W1, b1, W2, b2, W3, b3, nout, false, s);
+    case 8: return bf16 ? hipErrorInvalidValue : pack_impl<8>(pb, R, W1, b1, W2, b2, W3, b3, nout, false, s);
+    case 9: return bf16 ? hipErrorInvalidValue : pack_impl<9>(pb, R, W1, b1, W2, b2, W3, b3, nout, false, s);
+    case 10: return bf16 ? hipErrorInvalidValue : pack_impl<10>(pb, R, W1, b1, W2, b2, W3, b3, nout, false, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -861,6 +842,9 @@ hipError_t pack_policy_f32(PolicyBuffers& pb, int N, int R, const float* W1, con
     case 5: return bf16 ? hipErrorInvalidValue : FN<5, false>(__VA_ARGS__);      \
     case 6: return bf16 ? hipErrorInvalidValue : FN<6, false>(__VA_ARGS__);      \
     case 7: return bf16 ? hipErrorInvalidValue : FN<7, false>(__VA_ARGS__);      \
+    case 8: return bf16 ? hipErrorInvalidValue : FN<8, false>(__VA_ARGS__);      \
+    case 9: return bf16 ? hipErrorInvalidValue : FN<9, false>(__VA_ARGS__);      \
+    case 10: return bf16 ? hipErrorInvalidValue : FN<10, false>(__VA_ARGS__);    \
     default: return hipErrorInvalidValue;                                        \
   }
 

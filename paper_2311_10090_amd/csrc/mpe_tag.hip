@@ -459,7 +459,7 @@ hipError_t tag_pack(PolicyBuffers& pb, int R, bool bf16, int nout, const float* 
     using P = PkT<false, Net::kWideIn>;
     if (hipError_t e = ensure_policy_bytes(pb, size_t(R) * (bf16 ? PkB::RUN_BYTES : P::RUN_BYTES)); e != hipSuccess)
       return e;
-    constexpr int total = 4 * 64 * 8 + 4 * 2 * 64 * 8 + 2 * 64 * 8 + 2 * kH + 16;   // one thread per weight / bias
+    constexpr int total = pack_threads<Net>();
     if (bf16)
       hipLaunchKernelGGL(pack_bf16_kernel<Net>, dim3((total + 255) / 256, R), dim3(256), 0, s,
                          static_cast<uint8_t*>(pb.packed), W1, b1, W2, b2, W3, b3, nout);

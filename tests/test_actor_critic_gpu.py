@@ -41,7 +41,8 @@ def _pair(mods, E, N, R=1, wseed=3, wd=0, **kw):
 
 @pytest.mark.parametrize("E,N,R,T,wd", [(1024, 3, 1, 30, 0), (300, 3, 1, 30, 0), (100, 2, 1, 20, 0), (70, 1, 1, 20, 0),
                                         (256, 3, 2, 12, 0), (64, 3, 3, 12, 0), (300, 3, 1, 20, 1), (70, 1, 1, 10, 1),
-                                        (300, 4, 1, 15, 0), (130, 5, 1, 12, 0), (64, 6, 2, 10, 0), (100, 7, 1, 10, 0), (32, 7, 3, 8, 0)])
+                                        (300, 4, 1, 15, 0), (130, 5, 1, 12, 0), (64, 6, 2, 10, 0), (100, 7, 1, 10, 0), (32, 7, 3, 8, 0),
+                                        (100, 8, 1, 8, 0), (16, 9, 3, 8, 0), (70, 10, 1, 8, 0)])
 def test_actor_critic_teacher_forced(mods, E, N, R, T, wd):
     """The oracle runs free; before every step its state is forced into the library, which then does
     one actor-critic step.  wd = 1: bf16 weights and layer inputs on both sides."""
@@ -143,9 +144,9 @@ def test_actor_critic_errors_and_absent_outputs(mods):
         assert torch.equal(x, y) if hasattr(x, "shape") else x == y
     env.close()
     ref.close()
-    eight = MpeEnv(Hp.gpu_config(64, 8, 1, 64, 0))    # 8 and more agents: bf16 weights only
+    eight = MpeEnv(Hp.gpu_config(64, 8, 1, 128, 0))   # fp32 networks are 64 wide
     with pytest.raises(MpeError) as ei:
-        eight.set_critic(*Hp.to_dev(synth.critic_weights(0, 1, 48, 64)))
+        eight.set_critic(*Hp.to_dev(synth.critic_weights(0, 1, 48, 128)))
     assert ei.value.code == MPE_EINVAL
     eight.close()
     runs = MpeEnv(Hp.gpu_config(40, 3, 2, 64, 0))     # several runs need num_envs % 64 == 0

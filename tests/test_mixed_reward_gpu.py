@@ -113,7 +113,7 @@ def test_uniform_rollout_mixed_reward(mods, E, N, R):
 
 
 @pytest.mark.parametrize("E,N,R,H,wd", [(256, 3, 1, 64, 0), (100, 2, 1, 64, 0), (64, 3, 3, 64, 0),
-                                        (100, 10, 1, 128, 1), (200, 3, 1, 64, 1), (100, 5, 1, 64, 0), (64, 7, 2, 64, 0)])
+                                        (100, 10, 1, 128, 1), (200, 3, 1, 64, 1), (100, 5, 1, 64, 0), (64, 7, 2, 64, 0), (64, 10, 1, 64, 0)])
 def test_fused_rollout_mixed_reward(mods, E, N, R, H, wd):
     say("mixed reward, fused rollout E=%d N=%d R=%d H=%d dtype=%d" % (E, N, R, H, wd))
     env, orc = _pair(mods, E, N, R, H, wd, wseed=4)

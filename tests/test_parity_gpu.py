@@ -252,9 +252,10 @@ def _teacher_forced(env, orc, seed, T):
 
 
 # 65,536 envs: the launch configuration of the headline measurement (256-env blocks), 4.9 million samples
-# 4 to 7 agents: the same kernel with layer 1 over a whole K slice (4N + 2 live inputs)
+# 4 to 10 agents: the same kernel with layer 1 over one whole K slice (4N + 2 live inputs) or two
 @pytest.mark.parametrize("E,N,T", [(4096, 3, 30), (200, 3, 60), (64, 1, 30), (100, 2, 30), (65536, 3, 25),
-                                   (2048, 4, 20), (130, 4, 30), (100, 5, 30), (1024, 6, 15), (70, 6, 25), (64, 7, 25), (1000, 7, 12)])
+                                   (2048, 4, 20), (130, 4, 30), (100, 5, 30), (1024, 6, 15), (70, 6, 25), (64, 7, 25), (1000, 7, 12),
+                                   (512, 8, 12), (70, 8, 20), (100, 9, 15), (1024, 10, 10), (50, 10, 20)])
 def test_policy_actions_teacher_forced_fp32(mods, E, N, T):
     say("policy teacher-forced E=%d N=%d T=%d" % (E, N, T))
     env, orc = _policy_pair(mods, E, N, 1, 64, 0, wseed=3)
@@ -283,7 +284,8 @@ def _free_running(env, orc, seed, T, make_oracle, what="policy rollout"):
     return frac_same, ww, n_ill, n_all
 
 
-@pytest.mark.parametrize("E,N,T", [(4096, 3, 128), (200, 3, 50), (1024, 4, 50), (256, 5, 50), (200, 6, 50), (130, 7, 50)])
+@pytest.mark.parametrize("E,N,T", [(4096, 3, 128), (200, 3, 50), (1024, 4, 50), (256, 5, 50), (200, 6, 50), (130, 7, 50),
+                                   (100, 8, 50), (128, 10, 50)])
 def test_policy_rollout_free_running_fp32(mods, E, N, T):
     say("policy free-running E=%d N=%d T=%d" % (E, N, T))
     env, orc = _policy_pair(mods, E, N, 1, 64, 0, wseed=5)
@@ -468,9 +470,9 @@ def test_rollouts_are_deterministic(mods):
 def test_unsupported_policy_shapes_are_refused(mods):
     MpeEnv, _ = mods
     from paper_2311_10090_amd.binding import MpeError, MPE_EINVAL
-    # 8 agents with fp32 weights: no kernel is built for it (fp32 up to 7 agents, bf16 up to 10)
-    env = MpeEnv(Hp.gpu_config(64, 8, 1, 64, 0))
-    w = synth.policy_weights(0, 1, 48, 64)
+    # fp32 weights at width 128: no kernel is built for it (fp32 policies are 64 wide)
+    env = MpeEnv(Hp.gpu_config(64, 8, 1, 128, 0))
+    w = synth.policy_weights(0, 1, 48, 128)
     with pytest.raises(MpeError) as ei:
         env.set_policy(*Hp.to_dev(w))
     assert ei.value.code == MPE_EINVAL and "unsupported" in str(ei.value)

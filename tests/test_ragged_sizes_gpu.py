@@ -54,7 +54,7 @@ def mods():
 
 
 @pytest.mark.parametrize("E", SIZES)
-@pytest.mark.parametrize("N,H,wd", [(3, 0, 0), (3, 64, 0), (3, 64, 1), (1, 64, 0), (2, 0, 0), (10, 0, 0), (10, 128, 1), (5, 64, 0), (7, 64, 0)])
+@pytest.mark.parametrize("N,H,wd", [(3, 0, 0), (3, 64, 0), (3, 64, 1), (1, 64, 0), (2, 0, 0), (10, 0, 0), (10, 128, 1), (5, 64, 0), (7, 64, 0), (9, 64, 0)])
 def test_spread_kernels(mods, E, N, H, wd):
     MpeEnv, Oracle = mods
     env = MpeEnv(Hp.gpu_config(E, N, 1, H, wd))

@@ -44,6 +44,7 @@ PAIRS = [
     ((8192, 3, 1, 0, 0, 50), (130, 3, 1, 0, 0, 50)),          # no policy: seeded uniform actions
     ((300, 5, 1, 0, 0, 30), (64, 1, 1, 64, 1, 30)),           # uniform actions, then a bf16 policy
     ((1024, 6, 1, 64, 0, 26), (100, 4, 1, 64, 0, 26)),        # fp32 weights with 4 and more agents
+    ((512, 10, 1, 64, 0, 26), (70, 8, 1, 64, 0, 26)),         # ... with layer 1 over two K slices
 ]
 
 
@@ -98,7 +99,7 @@ def test_refusals():
         rollout_noalloc(Hp.gpu_config(64, 3, 1, 64, 0), 1, w[:5] + [None], 2)
     assert ei.value.code == MPE_EINVAL
     with pytest.raises(MpeError) as ei:                      # a policy shape that mpe_set_policy refuses
-        rollout_noalloc(Hp.gpu_config(64, 8, 1, 64, 0), 1, Hp.to_dev(synth.policy_weights(1, 1, 48, 64)), 2)
+        rollout_noalloc(Hp.gpu_config(64, 8, 1, 128, 0), 1, Hp.to_dev(synth.policy_weights(1, 1, 48, 128)), 2)
     assert ei.value.code == MPE_EINVAL
     with pytest.raises(MpeError) as ei:                      # the second scenario is not built here
         rollout_noalloc(Hp.tag_gpu_config(64), 1, None, 2)
