@@ -104,6 +104,12 @@ struct GruPolicy {
   std::vector<double> We, be, Wi, bi, Wh, bh, Wf, bf, Wo, bo;
 };
 
+// R-16 critic head of the recurrent actor-critic: per run Wc[G][G], bc[G], wv[G], bv[1].
+struct GruCritic {
+  bool set = false;
+  std::vector<double> Wc, bc, wv, bv;
+};
+
 struct Oracle {
   Config cfg;
   int E, N, L, R, D, H;
@@ -116,6 +122,7 @@ struct Oracle {
   Policy pol;
   Policy critic;   // same shape with ONE output: W3[H][1], b3[1]  (R-13)
   GruPolicy gru;                 // R-15; takes precedence over `pol` when set
+  GruCritic gru_critic;          // R-16; used by the actor-critic rollout while `gru` is set
   std::vector<double> hidden;    // [run][env][agent][GRU_H], carried between steps and calls
   int nthreads = 1;
 };
@@ -519,7 +526,35 @@ double critic_value(const Oracle& o, int run, const double* ob) {
 // ---------------------------------------------------------------------------------
 double sigmoid(double x) { return 1.0 / (1.0 + std::exp(-x)); }
 
-void gru_forward(const Oracle& o, int run, const double* ob, double* h /* [GRU_H] in/out */, double* z5 /* [5] */) {
+// R-16  Critic of the recurrent actor-critic.  The paper's PPO baselines are actor-critic (Sec. 3.2; App. G lists a
+// value loss coefficient) and its recurrent network has two fully-connected layers of width 128 around the
+// recurrent unit (App. G "Recurrent network"); the critic is not printed.  Reading taken: actor and critic
+// share the first fully-connected layer and the recurrent unit, and the critic has a second fully-connected
+// layer of its own and one output, fed the NEW carried state h' of the step:
+//     yc = tanh(Wc^T h' + bc),   value = wv^T yc + bv
+// with the rounding points of R-15 (h' and yc are rounded to bf16 where they enter a product).
+double gru_value(const Oracle& o, int run, const double* hnew /* [GRU_H] */) {
+  const int G = GRU_H;
+  const GruCritic& C = o.gru_critic;
+  const bool bf = o.cfg.weight_dtype == 1;
+  auto rnd = [&](double v) { return bf ? round_to_bf16(v) : v; };
+  const double* Wc = &C.Wc[size_t(run) * G * G];
+  const double* bc = &C.bc[size_t(run) * G];
+  const double* wv = &C.wv[size_t(run) * G];
+  std::vector<double> hb(G);
+  for (int k = 0; k < G; ++k) hb[k] = rnd(hnew[k]);
+  double v = C.bv[size_t(run)];
+  for (int j = 0; j < G; ++j) {
+    double acc = 0.0;
+    for (int k = 0; k < G; ++k) acc += hb[k] * Wc[size_t(k) * G + j];
+    v += rnd(std::tanh(acc + bc[j])) * wv[j];
+  }
+  return v;
+}
+
+// `value` (nullable): the critic head of R-16 on the new carried state.
+void gru_forward(const Oracle& o, int run, const double* ob, double* h /* [GRU_H] in/out */, double* z5 /* [5] */,
+                 double* value = nullptr) {
   const int D = o.D, G = GRU_H;
   const GruPolicy& P = o.gru;
   const bool bf = o.cfg.weight_dtype == 1;
@@ -558,6 +593,7 @@ void gru_forward(const Oracle& o, int run, const double* ob, double* h /* [GRU_H
     hn[j] = (1.0 - zz) * n + zz * h[j];
   }
   for (int j = 0; j < G; ++j) h[j] = hn[j];
+  if (value) *value = gru_value(o, run, hn.data());
   for (int k = 0; k < G; ++k) hb[k] = rnd(hn[k]);
   for (int j = 0; j < G; ++j) {
     double acc = 0.0;
@@ -607,14 +643,20 @@ int uniform_action(uint32_t seed, uint32_t run, uint32_t env, uint32_t s, uint32
 }
 
 void choose_actions(Oracle& o, int run, int env, uint32_t s, const double* obs /* [N][D] */,
-                    uint8_t* act /* [N] */, double* logp = nullptr /* [N], needs a policy */) {
+                    uint8_t* act /* [N] */, double* logp = nullptr /* [N], needs a policy */,
+                    double* gru_values = nullptr /* [N], recurrent actor-critic only */) {
   for (int i = 0; i < o.N; ++i) {
     if (o.gru.set) {
       double z[NUM_ACTIONS];
       double* h = &o.hidden[((size_t(run) * o.E + env) * o.N + i) * GRU_H];
-      gru_forward(o, run, obs + size_t(i) * o.D, h, z);
+      gru_forward(o, run, obs + size_t(i) * o.D, h, z, gru_values ? gru_values + i : nullptr);
       act[i] = uint8_t(gumbel_max_action(o.seed, uint32_t(o.cfg.run_offset + run),
                                          uint32_t(o.cfg.env_offset + env), s, uint32_t(i), z));
+      if (logp) {
+        double lp[NUM_ACTIONS];
+        log_probs(z, lp);
+        logp[i] = lp[act[i]];
+      }
     } else if (o.pol.set) {
       double z[NUM_ACTIONS];
       policy_logits(o, run, obs + size_t(i) * o.D, z);
@@ -637,7 +679,9 @@ void choose_actions(Oracle& o, int run, int env, uint32_t s, const double* obs /
 // actions (policy + Gumbel-max, or uniform), record them, apply one transition, record
 // reward and done.  After the loop last_obs is the current observation.  Actor-critic outputs
 // (R-13, all nullable): logp_traj, value_traj [T][TE][N] and last_value [TE][N], the value of
-// last_obs.
+// last_obs.  With the recurrent policy (R-16) the value of step t is the critic head on the carried state
+// that step t produces, and last_value is the value that one more network evaluation on last_obs would
+// give; that evaluation does not advance the carried state.
 // ---------------------------------------------------------------------------------
 void rollout_range(Oracle& o, size_t g0, size_t g1, int T, double* obs_traj, uint8_t* act_traj,
                    double* rew_traj, uint8_t* done_traj, double* last_obs, double* logp_traj = nullptr,
@@ -654,13 +698,16 @@ void rollout_range(Oracle& o, size_t g0, size_t g1, int T, double* obs_traj, uin
       const uint32_t s = o.abs_step + uint32_t(t);
       observe_env(o, ge, ob.data());
       if (obs_traj) std::memcpy(obs_traj + (size_t(t) * TE + ge) * row, ob.data(), row * sizeof(double));
-      std::vector<double> lp(o.N);
-      choose_actions(o, run, env, s, ob.data(), act.data(), logp_traj ? lp.data() : nullptr);
+      std::vector<double> lp(o.N), gv(o.N);
+      const bool rec_value = o.gru.set && value_traj != nullptr;
+      choose_actions(o, run, env, s, ob.data(), act.data(), logp_traj ? lp.data() : nullptr,
+                     rec_value ? gv.data() : nullptr);
       if (act_traj) std::memcpy(act_traj + (size_t(t) * TE + ge) * o.N, act.data(), o.N);
       if (logp_traj) std::memcpy(logp_traj + (size_t(t) * TE + ge) * o.N, lp.data(), o.N * sizeof(double));
       if (value_traj)
         for (int i = 0; i < o.N; ++i)
-          value_traj[(size_t(t) * TE + ge) * o.N + i] = critic_value(o, run, ob.data() + size_t(i) * o.D);
+          value_traj[(size_t(t) * TE + ge) * o.N + i] =
+              o.gru.set ? gv[i] : critic_value(o, run, ob.data() + size_t(i) * o.D);
       uint8_t d;
       step_env(o, run, env, s, act.data(), r.data(), &d);
       if (d && o.gru.set) std::fill_n(&o.hidden[ge * o.N * GRU_H], size_t(o.N) * GRU_H, 0.0);   // new episode
@@ -670,7 +717,16 @@ void rollout_range(Oracle& o, size_t g0, size_t g1, int T, double* obs_traj, uin
     if (last_obs) observe_env(o, ge, last_obs + ge * row);
     if (last_value) {
       observe_env(o, ge, ob.data());
-      for (int i = 0; i < o.N; ++i) last_value[ge * o.N + i] = critic_value(o, run, ob.data() + size_t(i) * o.D);
+      for (int i = 0; i < o.N; ++i) {
+        if (o.gru.set) {
+          // one more evaluation on a copy of the carried state
+          std::vector<double> hcopy(&o.hidden[(ge * o.N + i) * GRU_H], &o.hidden[(ge * o.N + i) * GRU_H] + GRU_H);
+          double z[NUM_ACTIONS];
+          gru_forward(o, run, ob.data() + size_t(i) * o.D, hcopy.data(), z, &last_value[ge * o.N + i]);
+        } else {
+          last_value[ge * o.N + i] = critic_value(o, run, ob.data() + size_t(i) * o.D);
+        }
+      }
     }
   }
 }
@@ -867,13 +923,38 @@ int orc_set_gru(void* h, const float* We, const float* be, const float* Wi, cons
   return 0;
 }
 
-// One recurrent-policy evaluation per row: obs [n][D], hidden [n][128] in/out, logits [n][5].
-int orc_gru_forward(void* h, int run, const double* obs, int n, double* hidden, double* logits) {
+// Critic head of the recurrent actor-critic (R-16) as float32, [R] leading dimension: Wc[128][128] bc[128]
+// wv[128] bv[1].  All four null => removed.
+int orc_set_gru_critic(void* h, const float* Wc, const float* bc, const float* wv, const float* bv) {
+  if (!h) return fail("null handle");
+  Oracle& o = *static_cast<Oracle*>(h);
+  const int given = (Wc != nullptr) + (bc != nullptr) + (wv != nullptr) + (bv != nullptr);
+  if (given == 0) { o.gru_critic.set = false; return 0; }
+  if (given != 4) return fail("all four critic-head arrays or none");
+  const bool b16 = o.cfg.weight_dtype == 1;
+  auto load = [&](std::vector<double>& dst, const float* src, size_t n, bool round_it) {
+    dst.resize(n);
+    for (size_t i = 0; i < n; ++i) dst[i] = round_it ? round_to_bf16(double(src[i])) : double(src[i]);
+  };
+  const size_t R = o.R, G = GRU_H;
+  load(o.gru_critic.Wc, Wc, R * G * G, b16);
+  load(o.gru_critic.bc, bc, R * G, false);
+  load(o.gru_critic.wv, wv, R * G, b16);
+  load(o.gru_critic.bv, bv, R, false);
+  o.gru_critic.set = true;
+  return 0;
+}
+
+// One recurrent-policy evaluation per row: obs [n][D], hidden [n][128] in/out, logits [n][5]; values [n]
+// (nullable) the critic head of R-16 on the new hidden state.
+int orc_gru_forward(void* h, int run, const double* obs, int n, double* hidden, double* logits, double* values) {
   Oracle& o = *static_cast<Oracle*>(h);
   if (!o.gru.set) return fail("no recurrent policy");
+  if (values && !o.gru_critic.set) return fail("no recurrent critic head");
   if (run < 0 || run >= o.R) return fail("bad run");
   for (int r = 0; r < n; ++r)
-    gru_forward(o, run, obs + size_t(r) * o.D, hidden + size_t(r) * GRU_H, logits + size_t(r) * NUM_ACTIONS);
+    gru_forward(o, run, obs + size_t(r) * o.D, hidden + size_t(r) * GRU_H, logits + size_t(r) * NUM_ACTIONS,
+                values ? values + r : nullptr);
   return 0;
 }
 
@@ -953,8 +1034,11 @@ int orc_rollout_ac(void* h, int32_t T, double* obs_traj, uint8_t* act_traj, doub
   if (!h || T < 1) return fail("bad argument");
   Oracle& o = *static_cast<Oracle*>(h);
   if (!o.was_reset) return fail("rollout before reset");
-  if (!o.pol.set || !o.critic.set) return fail("actor-critic rollout needs a policy and a critic");
-  if (o.gru.set) return fail("actor-critic rollout is defined for the feed-forward policy only");
+  if (o.gru.set) {
+    if (!o.gru_critic.set) return fail("actor-critic rollout with the recurrent policy needs its critic head");
+  } else if (!o.pol.set || !o.critic.set) {
+    return fail("actor-critic rollout needs a policy and a critic");
+  }
   const size_t TE = size_t(o.R) * o.E;
   const int nt = int(std::max<size_t>(1, std::min<size_t>(size_t(o.nthreads), TE)));
   std::vector<std::thread> th;

@@ -105,7 +105,8 @@ def _load():
         _lib.orc_log_probs.restype = None
         _lib.orc_rollout_ac.argtypes = [C.c_void_p, C.c_int32] + [C.c_void_p] * 8
         _lib.orc_set_gru.argtypes = [C.c_void_p] + [C.c_void_p] * 10
-        _lib.orc_gru_forward.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        _lib.orc_gru_forward.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
+        _lib.orc_set_gru_critic.argtypes = [C.c_void_p] + [C.c_void_p] * 4
         _lib.orc_get_hidden.argtypes = [C.c_void_p, C.c_void_p]
         _lib.orc_set_hidden.argtypes = [C.c_void_p, C.c_void_p]
     return _lib
@@ -227,13 +228,26 @@ class Oracle:
         assert len(arrs) == 10
         _check(self.lib.orc_set_gru(self.h, *[_ptr(a) for a in arrs]))
 
-    def gru_forward(self, obs_rows, hidden, run: int = 0):
-        """One evaluation per row: returns (new hidden [n][128], logits [n][5])."""
+    def set_gru_critic(self, Wc=None, bc=None, wv=None, bv=None):
+        """Critic head of the recurrent actor-critic: Wc [R][128][128], bc [R][128], wv [R][128], bv [R]
+        (or nothing to remove it)."""
+        if Wc is None:
+            _check(self.lib.orc_set_gru_critic(self.h, None, None, None, None))
+            return
+        G, R = self.GRU_H, self.R
+        shapes = [(R, G, G), (R, G), (R, G), (R,)]
+        arrs = [np.ascontiguousarray(a, dtype=np.float32).reshape(sh) for a, sh in zip((Wc, bc, wv, bv), shapes)]
+        _check(self.lib.orc_set_gru_critic(self.h, *[_ptr(a) for a in arrs]))
+
+    def gru_forward(self, obs_rows, hidden, run: int = 0, with_value: bool = False):
+        """One evaluation per row: returns (new hidden [n][128], logits [n][5]) and, with_value, the critic
+        head's value [n] of the new hidden state."""
         o = np.ascontiguousarray(obs_rows, dtype=np.float64).reshape(-1, self.D)
         h = np.array(hidden, dtype=np.float64).reshape(o.shape[0], self.GRU_H).copy()
         z = np.empty((o.shape[0], 5), dtype=np.float64)
-        _check(self.lib.orc_gru_forward(self.h, run, _ptr(o), o.shape[0], _ptr(h), _ptr(z)))
-        return h, z
+        v = np.empty(o.shape[0], dtype=np.float64) if with_value else None
+        _check(self.lib.orc_gru_forward(self.h, run, _ptr(o), o.shape[0], _ptr(h), _ptr(z), _ptr(v) if with_value else None))
+        return (h, z, v) if with_value else (h, z)
 
     def get_hidden(self) -> np.ndarray:
         h = np.empty((self.TE, self.N, self.GRU_H), dtype=np.float64)

@@ -158,6 +158,15 @@ def gru_weights(seed: int, num_runs: int, obs_dim: int):
             mat(G, NUM_ACTIONS), vec(NUM_ACTIONS))
 
 
+def gru_critic_weights(seed: int, num_runs: int):
+    """Critic head of the recurrent actor-critic, float32: Wc[R][G][G] N(0, 1/G), bc[R][G] U(-0.5, 0.5),
+    wv[R][G] N(0, 1/G), bv[R] U(-0.5, 0.5)."""
+    G, R = GRU_HIDDEN, num_runs
+    g = np.random.Generator(np.random.PCG64(seed + 49979687))
+    return ((g.standard_normal((R, G, G)) / np.sqrt(G)).astype(np.float32), g.uniform(-0.5, 0.5, (R, G)).astype(np.float32),
+            (g.standard_normal((R, G)) / np.sqrt(G)).astype(np.float32), g.uniform(-0.5, 0.5, (R,)).astype(np.float32))
+
+
 def random_actions(seed: int, shape) -> np.ndarray:
     g = np.random.Generator(np.random.PCG64(seed))
     return g.integers(0, NUM_ACTIONS, size=shape, dtype=np.uint8)

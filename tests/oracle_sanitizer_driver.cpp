@@ -79,7 +79,17 @@ void exercise(int scenario, int E, int N, int L, int R, int H, int wd, int rewar
     std::vector<double> hid(TE * N * 128), z(size_t(N) * 5);
     OK(orc_get_hidden(h, hid.data()));
     OK(orc_set_hidden(h, hid.data()));
-    OK(orc_gru_forward(h, 0, obs.data(), int(N), hid.data(), z.data()));
+    OK(orc_gru_forward(h, 0, obs.data(), int(N), hid.data(), z.data(), nullptr));
+    // the recurrent actor-critic: critic head, rollout with values, removal
+    const size_t G = 128;
+    auto Wc = fill(g, R * G * G), bc = fill(g, R * G), wv = fill(g, R * G), bv = fill(g, size_t(R));
+    OK(orc_set_gru_critic(h, Wc.data(), bc.data(), wv.data(), bv.data()));
+    std::vector<double> vals(N);
+    OK(orc_gru_forward(h, R - 1, obs.data(), int(N), hid.data(), z.data(), vals.data()));
+    std::vector<double> lp(size_t(T) * TE * N), val(size_t(T) * TE * N), lv(TE * N);
+    OK(orc_rollout_ac(h, T, ot.data(), at.data(), lp.data(), val.data(), rt.data(), dt.data(), last.data(), lv.data()));
+    OK(orc_rollout_ac(h, 2, nullptr, nullptr, nullptr, val.data(), nullptr, nullptr, nullptr, lv.data()));
+    OK(orc_set_gru_critic(h, nullptr, nullptr, nullptr, nullptr));
     OK(orc_set_hidden(h, nullptr));
   }
   std::vector<double> pa(TE * N * 2), va(TE * N * 2), pl(TE * L * 2);
@@ -106,6 +116,7 @@ int main() {
   exercise(0, 3, 10, 10, 1, 128, 1, 0, 2, false, false);
   exercise(0, 6, 10, 10, 2, 0, 0, 1, 4, false, false);
   exercise(0, 5, 3, 3, 2, 128, 1, 0, 2, true, false);
+  exercise(1, 4, 4, 2, 1, 128, 0, 0, 3, true, false);   // recurrent policy on the second scenario
   exercise(1, 6, 4, 2, 1, 64, 0, 0, 2, false, true);
   exercise(1, 5, 3, 0, 2, 64, 1, 0, 1, false, false);   // no landmarks: empty pos_l
   exercise(1, 4, 6, 2, 1, 0, 0, 0, 3, false, false);

@@ -199,3 +199,121 @@ def test_recurrent_policy_takes_precedence_and_can_be_removed():
     assert not np.array_equal(a_gru, a_uni)
     with pytest.raises(RuntimeError):
         o.gru_forward(np.zeros((1, o.D)), np.zeros((1, G)))
+
+
+# ------------------------------------------------------------------------------------------------
+# Critic head of the recurrent actor-critic: yc = tanh(Wc^T h' + bc), value = wv^T yc + bv on the NEW
+# carried state h' of the step.
+# ------------------------------------------------------------------------------------------------
+def make_ac(E=2, N=3, wd=0, seed=1, **kw):
+    o, w = make(E, N, wd, seed, **kw)
+    c = synth.gru_critic_weights(seed, 1)
+    o.set_gru_critic(*c)
+    return o, w, c
+
+
+def torch_value(c, h_new, rnd=lambda t: t):
+    Wc, bc, wv, bv = [torch.from_numpy(np.asarray(a[0], np.float64)) for a in c]
+    with torch.no_grad():
+        yc = torch.tanh(torch.nn.functional.linear(rnd(torch.from_numpy(np.asarray(h_new, np.float64))), rnd(Wc).T, bc))
+        return (torch.nn.functional.linear(rnd(yc), rnd(wv)[None, :]) + bv).numpy()[:, 0]
+
+
+def test_critic_head_matches_torch_linear_float64_on_the_new_state():
+    o, w, c = make_ac()
+    g = np.random.Generator(np.random.PCG64(13))
+    obs = g.uniform(-1.5, 1.5, (40, o.D))
+    h = g.uniform(-1, 1, (40, G))
+    h1, z1, v1 = o.gru_forward(obs, h, with_value=True)
+    h2, z2 = torch_chain(w, obs, h)
+    np.testing.assert_allclose(h1, h2, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(z1, z2, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(v1, torch_value(c, h2), rtol=0, atol=1e-13)
+    # the head reads the new state, not the one it was given
+    assert np.abs(v1 - torch_value(c, h)).max() > 1e-2
+    # logits and the carried state do not depend on the head being asked for
+    h3, z3 = o.gru_forward(obs, h)
+    assert np.array_equal(h1, h3) and np.array_equal(z1, z3)
+
+
+def test_critic_head_closed_forms():
+    o, w, c = make_ac()
+    g = np.random.Generator(np.random.PCG64(14))
+    obs, h = g.uniform(-1, 1, (6, o.D)), g.uniform(-1, 1, (6, G))
+    f32 = lambda a: np.float64(np.float32(a))
+    bc, wv, bv = g.uniform(-1, 1, (1, G)), g.uniform(-1, 1, (1, G)), g.uniform(-1, 1, (1,))
+    o.set_gru_critic(np.zeros((1, G, G)), bc, wv, bv)                    # no dependence on the state
+    v = o.gru_forward(obs, h, with_value=True)[2]
+    np.testing.assert_allclose(v, np.full(6, (np.tanh(f32(bc[0])) * f32(wv[0])).sum() + f32(bv[0])), rtol=0, atol=1e-13)
+    o.set_gru_critic(c[0], c[1], np.zeros((1, G)), bv)                   # no output weights: the bias alone
+    np.testing.assert_array_equal(o.gru_forward(obs, h, with_value=True)[2], np.full(6, f32(bv[0])))
+    # one unit only: value = wv_j tanh(sum_k h'_k Wc[k][j] + bc_j) + bv
+    j = 17
+    one = np.zeros((1, G)); one[0, j] = 1.5
+    o.set_gru_critic(c[0], c[1], one, bv)
+    h1, _, v = o.gru_forward(obs, h, with_value=True)
+    np.testing.assert_allclose(v, 1.5 * np.tanh(h1 @ f32(c[0][0][:, j]) + f32(c[1][0][j])) + f32(bv[0]), rtol=0, atol=1e-13)
+
+
+def test_critic_head_bf16_rounding_points():
+    o, w, c = make_ac(wd=1)
+    rnd = _bf16_bits
+    g = np.random.Generator(np.random.PCG64(15))
+    obs = g.uniform(-1.5, 1.5, (60, o.D)).astype(np.float32).astype(np.float64)
+    h = g.uniform(-1, 1, (60, G)).astype(np.float32).astype(np.float64)
+    h1, _, v1 = o.gru_forward(obs, h, with_value=True)
+    v2 = torch_value(c, h1, rnd)                 # from the oracle's own new state: the head alone
+    assert (np.abs(v1 - v2) > 1e-13).mean() < 0.05 and np.abs(v1 - v2).max() < 1e-3
+    assert np.abs(v1 - torch_value(c, h1)).max() > 1e-5     # and it is not the unrounded head
+
+
+@pytest.mark.parametrize("wd", [0, 1])
+def test_actor_critic_rollout_with_the_recurrent_policy(wd):
+    """Values and log-probabilities of the rollout re-derived step by step from the recorded observations
+    with the carried state replayed outside; the bootstrap value is one more evaluation that does not
+    advance the carried state; everything else equals the plain rollout."""
+    from scipy.special import log_softmax
+    E, N, T = 3, 3, 9
+    a, w, c = make_ac(E=E, N=N, wd=wd, max_episode_steps=4)
+    b, _ = make(E=E, N=N, wd=wd, max_episode_steps=4)
+    a.reset(11)
+    b.reset(11)
+    obs, act, logp, val, rew, done, last, lastv = a.rollout_ac(T)
+    pobs, pact, prew, pdone, plast = b.rollout(T)
+    for x, y in ((obs, pobs), (act, pact), (rew, prew), (done, pdone), (last, plast)):
+        assert np.array_equal(x, y)
+    np.testing.assert_array_equal(a.get_hidden(), b.get_hidden())      # the bootstrap evaluation left no trace
+    h = np.zeros((E * N, G))
+    for t in range(T):
+        h, z, v = a.gru_forward(obs[t].reshape(E * N, -1), h, with_value=True)
+        ref_lp = log_softmax(z, axis=1)[np.arange(E * N), act[t].reshape(-1)]
+        np.testing.assert_allclose(logp[t].reshape(-1), ref_lp, rtol=0, atol=1e-12)
+        np.testing.assert_array_equal(val[t].reshape(-1), v)
+        if done[t].all():
+            h[:] = 0.0
+    np.testing.assert_array_equal(a.get_hidden().reshape(E * N, G), h)
+    _, _, v_last = a.gru_forward(last.reshape(E * N, -1), h, with_value=True)
+    np.testing.assert_array_equal(lastv.reshape(-1), v_last)
+    assert np.abs(val).max() > 0.05 and (logp < 0).all()
+    # T steps = T1 + T2 steps, values included
+    a2, _, _ = make_ac(E=E, N=N, wd=wd, max_episode_steps=4)
+    a2.reset(11)
+    first = a2.rollout_ac(5)
+    second = a2.rollout_ac(T - 5)
+    for k in (1, 2, 3):
+        assert np.array_equal(np.concatenate([first[k], second[k]]), (obs, act, logp, val)[k])
+    assert np.array_equal(second[7], lastv)
+
+
+def test_recurrent_actor_critic_needs_its_head():
+    o, _ = make()
+    o.reset(1)
+    with pytest.raises(RuntimeError):
+        o.rollout_ac(2)
+    with pytest.raises(RuntimeError):
+        o.gru_forward(np.zeros((1, o.D)), np.zeros((1, G)), with_value=True)
+    o.set_gru_critic(*synth.gru_critic_weights(2, 1))
+    o.rollout_ac(2)
+    o.set_gru_critic()
+    with pytest.raises(RuntimeError):
+        o.rollout_ac(2)

@@ -93,10 +93,10 @@ MUTANTS = [
     ("gumbel counter fields swapped", BASE, "const uint32_t c0[4] = {env, s, agent, TAG_GUMBEL0};", "const uint32_t c0[4] = {env, agent, s, TAG_GUMBEL0};", 0),
     ("uniform action from the reset stream", BASE, "const uint32_t c[4] = {env, s, agent, TAG_UNIFORM_ACTION};", "const uint32_t c[4] = {env, s, agent, TAG_RESET_POS};", 0),
     ("log-sum-exp without the shift added back", BASE, "const double lse = m + std::log(sum);", "const double lse = std::log(sum);", 0),
-    ("log-probability of action 0", BASE, "logp[i] = lp[act[i]];", "logp[i] = lp[0];", 0),
+    ("log-probability of action 0", BASE, "logp[i] = lp[act[i]];", "logp[i] = lp[0];", 1),   # (0 is the recurrent branch)
     ("critic reads the policy's weights", BASE, "mlp_forward(o, o.critic, 1, run, ob, &v);", "mlp_forward(o, o.pol, 1, run, ob, &v);", 0),
-    ("value of agent 0's row for every agent", BASE, "value_traj[(size_t(t) * TE + ge) * o.N + i] = critic_value(o, run, ob.data() + size_t(i) * o.D);",
-     "value_traj[(size_t(t) * TE + ge) * o.N + i] = critic_value(o, run, ob.data());", 0),
+    ("value of agent 0's row for every agent", BASE, "o.gru.set ? gv[i] : critic_value(o, run, ob.data() + size_t(i) * o.D);",
+     "o.gru.set ? gv[i] : critic_value(o, run, ob.data());", 0),
     # ---- rollout
     ("rollout: step not advanced", BASE, "const uint32_t s = o.abs_step + uint32_t(t);", "const uint32_t s = o.abs_step;", 0),
     ("rollout: stale last_obs", BASE, "if (last_obs) observe_env(o, ge, last_obs + ge * row);", "if (last_obs) std::memcpy(last_obs + ge * row, ob.data(), row * sizeof(double));", 0),
@@ -143,6 +143,21 @@ MUTANTS = [
     ("gru: state survives an episode end", GRU, "if (d && o.gru.set) std::fill_n(", "if (false && o.gru.set) std::fill_n(", 0),
     ("gru: new state rounded before it is carried", GRU, "  for (int j = 0; j < G; ++j) h[j] = hn[j];\n", "  for (int j = 0; j < G; ++j) h[j] = rnd(hn[j]);\n", 0),
     ("gru: logits from the unrounded second layer", GRU, "y[j] = rnd(std::tanh(acc + bff[j]));", "y[j] = std::tanh(acc + bff[j]);", 0),
+    # critic head of the recurrent actor-critic
+    ("gru critic: hidden bias dropped", GRU, "v += rnd(std::tanh(acc + bc[j])) * wv[j];", "v += rnd(std::tanh(acc)) * wv[j];", 0),
+    ("gru critic: output bias dropped", GRU, "double v = C.bv[size_t(run)];", "double v = 0.0;", 0),
+    ("gru critic: Wc transposed", GRU, "acc += hb[k] * Wc[size_t(k) * G + j];", "acc += hb[k] * Wc[size_t(j) * G + k];", 0),
+    ("gru critic: second layer not rounded", GRU, "v += rnd(std::tanh(acc + bc[j])) * wv[j];", "v += std::tanh(acc + bc[j]) * wv[j];", 0),
+    ("gru critic: state not rounded", GRU, "for (int k = 0; k < G; ++k) hb[k] = rnd(hnew[k]);", "for (int k = 0; k < G; ++k) hb[k] = hnew[k];", 0),
+    ("gru critic: value of the state before the step", GRU,
+     "  for (int j = 0; j < G; ++j) h[j] = hn[j];\n  if (value) *value = gru_value(o, run, hn.data());",
+     "  if (value) *value = gru_value(o, run, h);\n  for (int j = 0; j < G; ++j) h[j] = hn[j];", 0),
+    ("gru critic: bootstrap value advances the carried state", GRU,
+     "gru_forward(o, run, ob.data() + size_t(i) * o.D, hcopy.data(), z, &last_value[ge * o.N + i]);",
+     "gru_forward(o, run, ob.data() + size_t(i) * o.D, &o.hidden[(ge * o.N + i) * GRU_H], z, &last_value[ge * o.N + i]);", 0),
+    ("gru critic: log-probability of action 0", GRU, "logp[i] = lp[act[i]];", "logp[i] = lp[0];", 0),
+    ("gru critic: value of agent 0 for all", GRU, "o.gru.set ? gv[i] : critic_value(", "o.gru.set ? gv[0] : critic_value(", 0),
+    ("gru critic: output weights not rounded in bf16 mode", GRU, "load(o.gru_critic.wv, wv, R * G, b16);", "load(o.gru_critic.wv, wv, R * G, false);", 0),
 ]
 
 
