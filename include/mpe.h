@@ -206,6 +206,19 @@ int mpe_set_gru_policy(mpe_env* env, const float* We, const float* be, const flo
                        const float* Wh, const float* bh, const float* Wf, const float* bf, const float* Wo,
                        const float* bo, void* stream);
 
+/* Install (or with all four NULL, remove) the critic head of the RECURRENT actor-critic used by
+ * mpe_rollout_ac while a recurrent policy is installed (the paper's IPPO with an RNN agent, Sec. 3.2 and
+ * App. G: actor and critic share the embedding and the recurrent layer; each has its own fully-connected
+ * layer of width 128).  With h' the carried state AFTER this step's update (the vector the actor's second
+ * layer reads):
+ *   yc = tanh(Wc^T h' + bc),  value = wv^T yc + bv
+ * Wc [R][128][128] (row-major [fan_in][fan_out]), bc [R][128], wv [R][128], bv [R]: fp32 device pointers,
+ * copied on `stream`.  Wc, wv and the vectors entering the two products (h', yc) are rounded to bf16 (ties
+ * to even); sums and biases are fp32.  Needs the configuration of mpe_set_gru_policy (hidden 128,
+ * MPE_WEIGHTS_BF16); MPE_EINVAL otherwise or if only some pointers are NULL. */
+int mpe_set_gru_critic(mpe_env* env, const float* Wc, const float* bc, const float* wv, const float* bv,
+                       void* stream);
+
 /* Copy the carried state of the recurrent policy out / in: hidden [TE][N][128] fp32 device pointer
  * (device to device, on `stream`); mpe_set_hidden(NULL) clears it.  MPE_ESTATE if no recurrent
  * policy has been installed on this handle. */
@@ -237,7 +250,11 @@ int mpe_set_critic(mpe_env* env, const float* V1, const float* c1, const float* 
  * critic's value of the observation acted on; and the value of the observation after the last
  * step (the bootstrap value).
  * logp_traj, value_traj [T][TE][N] fp32, last_value [TE][N] fp32; the other arrays as in
- * mpe_rollout (rewards [T][TE][N] where mpe_rollout's are).  Any of the eight may be NULL.  Needs
+ * mpe_rollout (rewards [T][TE][N] where mpe_rollout's are).  Any of the eight may be NULL.
+ * With a recurrent policy installed (mpe_set_gru_policy) the critic is the head of mpe_set_gru_critic:
+ * value_traj holds the value of the carried state each step produced, last_value one more evaluation of the
+ * network on the observation after the last step, which does not advance the carried state; the carried
+ * state moves exactly as under mpe_rollout, and every other output equals mpe_rollout's bit for bit.  Needs
  * a policy and a critic (MPE_ESTATE if one is missing); with several runs num_envs must be a
  * multiple of 16 (fastest: of 256; 4 and more agents: of 64, of 32 with 8 agents and bf16 weights or 7
  * agents and fp32 weights, of 16 with 8 to 10 agents and fp32 weights;

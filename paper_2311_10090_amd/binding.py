@@ -23,7 +23,7 @@ NUM_ACTIONS = 5
 
 EXPORTS = ("mpe_create", "mpe_destroy", "mpe_obs_dim", "mpe_reset", "mpe_step", "mpe_set_policy",
            "mpe_rollout", "mpe_set_critic", "mpe_rollout_ac", "mpe_get_state", "mpe_set_state",
-           "mpe_set_gru_policy", "mpe_get_hidden", "mpe_set_hidden", "mpe_rollout_noalloc",
+           "mpe_set_gru_policy", "mpe_set_gru_critic", "mpe_get_hidden", "mpe_set_hidden", "mpe_rollout_noalloc",
            "mpe_set_barrier_poll_limit", "mpe_last_error")
 GRU_HIDDEN = 128
 
@@ -98,6 +98,7 @@ def load_library():
     lib.mpe_get_state.argtypes = [vp, vp, vp, vp, vp, C.POINTER(C.c_uint32), vp]
     lib.mpe_set_state.argtypes = [vp, vp, vp, vp, vp, C.c_uint32, C.c_uint32, vp]
     lib.mpe_set_gru_policy.argtypes = [vp] + [vp] * 10 + [vp]
+    lib.mpe_set_gru_critic.argtypes = [vp] + [vp] * 4 + [vp]
     lib.mpe_get_hidden.argtypes = [vp, vp, vp]
     lib.mpe_set_hidden.argtypes = [vp, vp, vp]
     lib.mpe_set_barrier_poll_limit.argtypes = [vp, C.c_uint32]
@@ -221,6 +222,13 @@ class MpeEnv:
         assert len(arrays) == 10
         with torch.cuda.device(self.device):
             _check(self.lib.mpe_set_gru_policy(self.h, *[_ptr(a, torch.float32) for a in arrays], _stream()))
+
+    def set_gru_critic(self, *arrays):
+        """Wc, bc, wv, bv device tensors (or nothing to remove the head)."""
+        arrays = arrays if arrays else (None,) * 4
+        assert len(arrays) == 4
+        with torch.cuda.device(self.device):
+            _check(self.lib.mpe_set_gru_critic(self.h, *[_ptr(a, torch.float32) for a in arrays], _stream()))
 
     def get_hidden(self):
         h = torch.empty((self.TE, self.N, GRU_HIDDEN), dtype=torch.float32, device=self.device)

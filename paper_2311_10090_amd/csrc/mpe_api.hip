@@ -32,6 +32,8 @@ struct mpe_env {
   PolicyBuffers gru{};        // recurrent policy; takes precedence over `pol` while set
   bool has_gru = false;
   float* hidden = nullptr;    // [TE][N][128] carried state of the recurrent policy (allocated with it)
+  PolicyBuffers gru_critic{}; // critic head of the recurrent actor-critic
+  bool has_gru_critic = false;
   // One word of pinned host memory, mapped into the device: a kernel whose bounded wait gave up raises it
   // (see group_barrier); the host reads it, without any synchronisation, at the start of the next call.
   uint32_t* fault_host = nullptr;
@@ -228,6 +230,7 @@ int mpe_destroy(mpe_env* e) {
   free_policy(e->pol);
   free_policy(e->critic);
   free_policy(e->gru);
+  free_policy(e->gru_critic);
   if (e->hidden) (void)hipFree(e->hidden);
   if (e->fault_host) (void)hipHostFree(e->fault_host);
   delete e;
@@ -336,7 +339,7 @@ int mpe_rollout(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, float
     TA.tg = e->tg;
     TA.actions_in = nullptr;
     const char* why = nullptr;
-    hipError_t err = launch_rollout_gru(e->tag, e->N, e->L, e->G, TA, e->gru, e->hidden,
+    hipError_t err = launch_rollout_gru(e->tag, e->N, e->L, e->G, TA, e->gru, nullptr, e->hidden,
                                         static_cast<hipStream_t>(stream), &why);
     if (why) return fail(MPE_EINVAL, "mpe_rollout: %s", why);
     if (err != hipSuccess) return fail(MPE_EHIP, "mpe_rollout: %s", hipGetErrorString(err));
@@ -392,6 +395,23 @@ int mpe_set_gru_policy(mpe_env* e, const float* We, const float* be, const float
   hipError_t err = pack_policy_gru(e->gru, e->D, int(e->R), We, be, Wi, bi, Wh, bh, Wf, bf, Wo, bo, s);
   if (err != hipSuccess) return fail(MPE_EHIP, "mpe_set_gru_policy: %s", hipGetErrorString(err));
   e->has_gru = true;
+  return MPE_OK;
+}
+
+int mpe_set_gru_critic(mpe_env* e, const float* Wc, const float* bc, const float* wv, const float* bv, void* stream) {
+  if (!e) return fail(MPE_EINVAL, "mpe_set_gru_critic: NULL handle");
+  const int given = (Wc != nullptr) + (bc != nullptr) + (wv != nullptr) + (bv != nullptr);
+  if (given == 0) {
+    e->has_gru_critic = false;
+    return MPE_OK;
+  }
+  if (given != 4) return fail(MPE_EINVAL, "mpe_set_gru_critic: pass all four arrays or none");
+  if (!gru_supported(e->tag, e->N, e->L, e->G, e->H, e->cfg.weight_dtype))
+    return fail(MPE_EINVAL, "mpe_set_gru_critic: the recurrent actor-critic needs hidden 128 and MPE_WEIGHTS_BF16");
+  e->has_gru_critic = false;   // as in mpe_set_gru_policy
+  hipError_t err = pack_gru_critic(e->gru_critic, int(e->R), Wc, bc, wv, bv, static_cast<hipStream_t>(stream));
+  if (err != hipSuccess) return fail(MPE_EHIP, "mpe_set_gru_critic: %s", hipGetErrorString(err));
+  e->has_gru_critic = true;
   return MPE_OK;
 }
 
@@ -463,11 +483,16 @@ int mpe_rollout_ac(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, fl
     return fail(MPE_EINVAL, "mpe_rollout_ac: T must be in [1, %d] (got %d)", MPE_MAX_ROLLOUT_STEPS, T);
   if (!e->ready) return fail(MPE_ESTATE, "mpe_rollout_ac: call mpe_reset or mpe_set_state first");
   if (int rc = check_fault(e, "mpe_rollout_ac")) return rc;
-  if (!e->has_policy || !e->has_critic)
-    return fail(MPE_ESTATE, "mpe_rollout_ac: needs mpe_set_policy and mpe_set_critic first");
-  if (e->has_gru) return fail(MPE_ESTATE, "mpe_rollout_ac: remove the recurrent policy first (feed-forward networks only)");
+  if (e->has_gru) {
+    if (!e->has_gru_critic)
+      return fail(MPE_ESTATE, "mpe_rollout_ac: with a recurrent policy, needs mpe_set_gru_critic first");
+  } else if (!e->has_policy || !e->has_critic) {
+    return fail(MPE_ESTATE, "mpe_rollout_ac: needs mpe_set_policy and mpe_set_critic (or mpe_set_gru_policy and "
+                            "mpe_set_gru_critic) first");
+  }
   const bool wide = !e->tag && e->cfg.weight_dtype == MPE_WEIGHTS_BF16 && wide_supported(e->N, e->H);
-  if (!e->tag && !wide && !f32_supported(e->N, e->H, e->cfg.weight_dtype == MPE_WEIGHTS_BF16)) return fail(MPE_EINVAL, "mpe_rollout_ac: unsupported shape");
+  if (!e->has_gru && !e->tag && !wide && !f32_supported(e->N, e->H, e->cfg.weight_dtype == MPE_WEIGHTS_BF16))
+    return fail(MPE_EINVAL, "mpe_rollout_ac: unsupported shape");
   for (const float* p : {obs_traj, logp_traj, value_traj, rew_traj, last_obs, last_value})
     if (p && !aligned16(p)) return fail(MPE_EINVAL, "mpe_rollout_ac: float outputs must be 16-byte aligned");
   if (uint64_t(e->abs_step) + uint64_t(T) > 0xFFFFFFFFull)
@@ -478,7 +503,14 @@ int mpe_rollout_ac(mpe_env* e, int32_t T, float* obs_traj, uint8_t* act_traj, fl
   A.last_value = last_value;
   const char* why = nullptr;
   hipError_t err;
-  if (e->tag) {
+  if (e->has_gru) {
+    TagArgs TA{};
+    TA.r = A;
+    TA.tg = e->tg;
+    TA.actions_in = nullptr;
+    err = launch_rollout_gru(e->tag, e->N, e->L, e->G, TA, e->gru, e->gru_critic.packed, e->hidden,
+                             static_cast<hipStream_t>(stream), &why);
+  } else if (e->tag) {
     TagArgs TA{};
     TA.r = A;
     TA.tg = e->tg;

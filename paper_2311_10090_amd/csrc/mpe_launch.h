@@ -149,8 +149,13 @@ hipError_t pack_policy_gru(PolicyBuffers& pb, int D, int R, const float* We, con
                            const float* Wo, const float* bo, hipStream_t s);
 // hidden: [TE][N][128] fp32, read at the start and written at the end of the rollout; A.tg is read by the
 // predator-prey shapes only
-hipError_t launch_rollout_gru(bool tag, int N, int L, int G, const TagArgs& A, const PolicyBuffers& pb, float* hidden,
-                              hipStream_t s, const char** why);
+// critic: the packed critic head (pack_gru_critic) for the actor-critic rollout (A.r.logp_traj, value_traj,
+// last_value), or null for the plain one
+hipError_t launch_rollout_gru(bool tag, int N, int L, int G, const TagArgs& A, const PolicyBuffers& pb, const void* critic,
+                              float* hidden, hipStream_t s, const char** why);
+// Critic head of the recurrent actor-critic: Wc [R][128][128], bc [R][128], wv [R][128], bv [R]
+hipError_t pack_gru_critic(PolicyBuffers& pb, int R, const float* Wc, const float* bc, const float* wv, const float* bv,
+                           hipStream_t s);
 void launch_fill_zero(float* p, size_t n, hipStream_t s);
 
 }  // namespace mpe

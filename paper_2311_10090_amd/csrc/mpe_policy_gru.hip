@@ -164,9 +164,49 @@ __global__ void pack_gru_kernel(uint8_t* __restrict__ out, int D, const float* _
   }
 }
 
+// Packed critic head of the recurrent actor-critic (bytes, per run): the second fully-connected layer of the
+// critic as A operands, [u 8][s 4][lane 64] like the actor's, then fp32: bc [128], wv [128] (rounded to
+// bf16), bv [1] and padding.
+struct GruCriticPk {
+  static constexpr size_t OFF_FC = 0;
+  static constexpr size_t OFF_TAIL = 32 * 1024;
+  static constexpr int TAIL_FLOATS = 2 * kG + 4;
+  static constexpr size_t BYTES = OFF_TAIL + size_t(TAIL_FLOATS) * 4;
+  static_assert(BYTES % 16 == 0, "images of consecutive runs stay 16-byte aligned");
+  static constexpr int N_FC = 8 * 4 * 64 * 8;
+  static constexpr int THREADS = N_FC + TAIL_FLOATS;
+};
+
+__global__ void pack_gru_critic_kernel(uint8_t* __restrict__ out, const float* __restrict__ Wc, const float* __restrict__ bc,
+                                       const float* __restrict__ wv, const float* __restrict__ bv) {
+  const size_t run = blockIdx.y;
+  out += run * GruCriticPk::BYTES;
+  Wc += run * size_t(kG) * kG;
+  bc += run * kG;
+  wv += run * kG;
+  bv += run;
+  int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx < GruCriticPk::N_FC) {
+    const int e = idx % 8, lane = (idx / 8) % 64, s = (idx / 512) % 4, u = idx / 2048;
+    const int k = 32 * s + 8 * (lane / 16) + e;
+    reinterpret_cast<uint16_t*>(out + GruCriticPk::OFF_FC)[idx] = f32_to_bf16_rne(Wc[size_t(k) * kG + 16 * u + lane % 16]);
+    return;
+  }
+  idx -= GruCriticPk::N_FC;
+  if (idx < GruCriticPk::TAIL_FLOATS) {
+    float v = 0.0f;
+    if (idx < kG) v = bc[idx];
+    else if (idx < 2 * kG) v = __uint_as_float(uint32_t(f32_to_bf16_rne(wv[idx - kG])) << 16);
+    else if (idx == 2 * kG) v = bv[0];
+    reinterpret_cast<float*>(out + GruCriticPk::OFF_TAIL)[idx] = v;
+  }
+}
+
 constexpr size_t up16(size_t x) { return (x + 15) & ~size_t(15); }
 
-template <typename Scn, int EB = 64>
+// AC: the actor-critic rollout: the critic head's tail (bc, wv, bv) and, per wavefront, the partial value of
+// every row (summed by the row's agent lane in a fixed order, so results do not depend on timing).
+template <typename Scn, int EB = 64, bool AC = false>
 struct GruSmem {
   static constexpr int N = Scn::N;
   static constexpr int B = EB * N, D = Scn::D, NT = B / 16;     // rows, obs width, 16-row tiles
@@ -187,7 +227,9 @@ struct GruSmem {
   // [B] new positions (float2); predator-prey: new position and velocity (float4)
   static constexpr size_t OFF_XCH = up16(OFF_BIAS + size_t(GruPk::BIAS_FLOATS) * 4);
   static constexpr size_t OFF_DONE = OFF_XCH + size_t(B) * (Scn::kTag ? 16 : 8);             // [64] bytes
-  static constexpr size_t TOTAL = OFF_DONE + 64;
+  static constexpr size_t OFF_CTAIL = OFF_DONE + 64;                                         // AC: bc, wv, bv
+  static constexpr size_t OFF_VPART = OFF_CTAIL + (AC ? size_t(GruCriticPk::TAIL_FLOATS) * 4 : 0);   // AC: [8][B] floats
+  static constexpr size_t TOTAL = OFF_VPART + (AC ? size_t(8) * B * 4 : 0);
   static_assert(TOTAL <= 160 * 1024, "LDS");
 };
 
@@ -200,11 +242,12 @@ __device__ __forceinline__ uint2 pack4_bf16(float a, float b, float c, float d) 
 // EB = envs per block: 64, or 32 / 16 for small batches (every phase of a step is a loop over the block's
 // 16-row tiles, so the step latency of a block, which is the time of a rollout while every block has a CU
 // to itself, falls with its rows) and for the shapes whose activations would not fit the LDS otherwise.
-template <typename Scn, int EB>
+template <typename Scn, int EB, bool AC>
 __global__ __launch_bounds__(512) void rollout_gru_kernel(TagArgs TA, const uint8_t* __restrict__ packed,
+                                                          const uint8_t* __restrict__ packed_critic,
                                                           float* __restrict__ hidden, int per_run_weights,
                                                           uint32_t groups, uint32_t groups_per_xcd) {
-  using M = GruSmem<Scn, EB>;
+  using M = GruSmem<Scn, EB, AC>;
   using TS = typename Scn::Shape;                      // predator-prey only
   constexpr bool kTag = Scn::kTag;
   constexpr int N = Scn::N, L = Scn::L, B = M::B, D = M::D, NT = M::NT, KS = M::KS;
@@ -222,6 +265,8 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(TagArgs TA, const uint
   [[maybe_unused]] float2* xch2 = reinterpret_cast<float2*>(smem + M::OFF_XCH);
   [[maybe_unused]] float4* xch4 = reinterpret_cast<float4*>(smem + M::OFF_XCH);
   uint8_t* donef = smem + M::OFF_DONE;
+  [[maybe_unused]] const float* ctail0 = reinterpret_cast<const float*>(smem + M::OFF_CTAIL);
+  [[maybe_unused]] float* vpart = reinterpret_cast<float*>(smem + M::OFF_VPART);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -242,6 +287,9 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(TagArgs TA, const uint
   const int nvalid = left < size_t(EB) ? int(left) : EB;   // valid envs of this block
   const int vrows = nvalid * N;                            // valid agent rows
   if (per_run_weights) packed += size_t(uint32_t(g0) / A.E) * GruPk::BYTES;   // the run of this block's envs
+  if constexpr (AC) {
+    if (per_run_weights) packed_critic += size_t(uint32_t(g0) / A.E) * GruCriticPk::BYTES;
+  }
 
   // ---- stationary operands: this wavefront's GRU and embedding tiles in registers; the small
   // layers and all biases in LDS
@@ -264,6 +312,11 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(TagArgs TA, const uint
     float* bdst = reinterpret_cast<float*>(smem + M::OFF_BIAS);
     for (int k = tid; k < GruPk::BIAS_FLOATS; k += 512) bdst[k] = bsrc[k];
     if (tid < 64) donef[tid] = 0;
+    if constexpr (AC) {
+      const float* csrc = reinterpret_cast<const float*>(packed_critic + GruCriticPk::OFF_TAIL);
+      float* cdst = reinterpret_cast<float*>(smem + M::OFF_CTAIL);
+      for (int k = tid; k < GruCriticPk::TAIL_FLOATS; k += 512) cdst[k] = csrc[k];
+    }
   }
 
   // ---- carried state of this wavefront's units: hreg[rt][r] = h[row 16 rt + j][unit 16 u + 4 gq + r]
@@ -373,8 +426,38 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(TagArgs TA, const uint
   const bool env_writer = valid && i == 0;
   const bool per_agent_reward = kTag || A.ph.reward_mode == 1;
   uint32_t step = A.abs_step;
+  [[maybe_unused]] float* logp_base = A.logp_traj;
+  [[maybe_unused]] float* value_base = A.value_traj;
 
-  for (int t = 0; t < A.T; ++t, ++step) {
+  // The carried state back to HBM (cleared where the last step ended an episode).
+  auto store_hidden = [&]() {
+#pragma unroll
+    for (int rt = 0; rt < NT; ++rt) {
+      const int row = 16 * rt + j;
+      if (row < vrows) {
+        const bool fresh = donef[row / N] != 0;
+        f32x4 v;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = fresh ? 0.0f : hreg[rt][r];
+        *reinterpret_cast<f32x4*>(hidden + (g0 * N + row) * kG + 16 * u + 4 * gq) = v;
+      }
+    }
+  };
+  // This row's value: the critic head's output bias plus the eight wavefronts' partial sums, in a fixed order.
+  [[maybe_unused]] auto row_value = [&]() {
+    float v = ctail0[2 * kG];
+#pragma unroll
+    for (int w8 = 0; w8 < 8; ++w8) v += vpart[w8 * B + tid];
+    return v;
+  };
+
+  // Actor-critic with a bootstrap value: one more pass of the network over the observation after the last
+  // step, on the carried state as it stands; that pass writes nothing back (the state has been stored by then).
+  const bool bootstrap = AC && A.last_value != nullptr;
+  const int passes = A.T + (bootstrap ? 1 : 0);
+  for (int t = 0; t < passes; ++t, ++step) {
+    const bool extra = AC && t == A.T;
+    if (extra) store_hidden();   // the registers of the carried state are free from here on
     // Opaque zero: keeps the step-invariant LDS reads (biases, small-layer operands) inside the step
     // loop; hoisted out of it they would pin ~40 registers for the whole rollout.
     uint32_t zero = 0;
@@ -433,22 +516,57 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(TagArgs TA, const uint
           pack4_bf16(hreg[rt][0], hreg[rt][1], hreg[rt][2], hreg[rt][3]);
     __syncthreads();   // HB = bf16(h')
 
-    // ---- second fully-connected layer: y = tanh(Wf^T h' + bf) -> X (e is dead)
+    // ---- second fully-connected layer: y = tanh(Wf^T h' + bf) -> X (e is dead); actor-critic: also the
+    // critic's second layer yc = tanh(Wc^T h' + bc) and this wavefront's share of value = wv^T yc + bv
     {
       bf16x8 wf[4];
 #pragma unroll
       for (int s = 0; s < 4; ++s) wf[s] = fcw[(u * 4 + s) * 64 + lane];
+      [[maybe_unused]] bf16x8 wc[4];
+      [[maybe_unused]] f32x4 bcv, wvv;
+      if constexpr (AC) {
+        // the critic's operands come from global memory every step (32 KB per run, cache-resident): the LDS
+        // has no room for them beside the actor's
+        const bf16x8* cw = reinterpret_cast<const bf16x8*>(packed_critic + GruCriticPk::OFF_FC) + zero;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) wc[s] = cw[(u * 4 + s) * 64 + lane];
+        const float* ctail = ctail0 + zero;
+        bcv = *reinterpret_cast<const f32x4*>(ctail + 16 * u + 4 * gq);
+        wvv = *reinterpret_cast<const f32x4*>(ctail + kG + 16 * u + 4 * gq);
+      }
 #pragma unroll
       for (int rt = 0; rt < NT; ++rt) {
         f32x4 acc = *reinterpret_cast<const f32x4*>(bias + 5 * kG + 16 * u + 4 * gq);
+        [[maybe_unused]] f32x4 accc;
+        if constexpr (AC) accc = bcv;
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
-          acc = MPE_MFMA_BF(wf[s], *reinterpret_cast<const bf16x8*>(hbuf + rt * kTile + 64 * s + rd_off), acc);
+        for (int s = 0; s < 4; ++s) {
+          const bf16x8 bh = *reinterpret_cast<const bf16x8*>(hbuf + rt * kTile + 64 * s + rd_off);
+          acc = MPE_MFMA_BF(wf[s], bh, acc);
+          if constexpr (AC) accc = MPE_MFMA_BF(wc[s], bh, accc);
+        }
         *reinterpret_cast<uint2*>(xbuf + rt * kTile + wr_off) =
             pack4_bf16(fast_tanh(acc[0]), fast_tanh(acc[1]), fast_tanh(acc[2]), fast_tanh(acc[3]));
+        if constexpr (AC) {
+          // yc enters the last product rounded to bf16; lane (j, gq) holds units 16 u + 4 gq .. + 3 of row j
+          const uint2 yc = pack4_bf16(fast_tanh(accc[0]), fast_tanh(accc[1]), fast_tanh(accc[2]), fast_tanh(accc[3]));
+          float pv = __uint_as_float(yc.x << 16) * wvv[0];
+          pv = fmaf(__uint_as_float(yc.x & 0xFFFF0000u), wvv[1], pv);
+          pv = fmaf(__uint_as_float(yc.y << 16), wvv[2], pv);
+          pv = fmaf(__uint_as_float(yc.y & 0xFFFF0000u), wvv[3], pv);
+          pv += __shfl_xor(pv, 16);
+          pv += __shfl_xor(pv, 32);
+          if (gq == 0) vpart[u * B + 16 * rt + j] = pv;
+        }
       }
     }
-    __syncthreads();   // Y complete
+    __syncthreads();   // Y complete (and the partial values)
+    if constexpr (AC) {
+      if (extra) {   // bootstrap pass: the value of the observation after the last step, nothing else
+        if (valid) A.last_value[row_off] = row_value();
+        break;
+      }
+    }
 
     // ---- logits of row tiles u, u + 8 -> L (in place of the observation tile)
     for (int rt = u; rt < NT; rt += 8) {
@@ -473,6 +591,20 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(TagArgs TA, const uint
       for (int k = 0; k < kNumActions; ++k) z[k] = logits[k * B + tid];
       const uint32_t act = gumbel_argmax(z, A.seed, run, env, step, uint32_t(i));
       if (act_base && valid) act_base[row_off] = uint8_t(act);
+      if constexpr (AC) {
+        // log pi(act | obs) = z_act - max - ln sum exp(z - max); value of the carried state this step produced
+        float zmax = z[0], zact = z[0];
+#pragma unroll
+        for (int k = 1; k < kNumActions; ++k) {
+          zmax = fmaxf(zmax, z[k]);
+          zact = act == uint32_t(k) ? z[k] : zact;
+        }
+        float sum = 0.0f;
+#pragma unroll
+        for (int k = 0; k < kNumActions; ++k) sum += hw_exp2((z[k] - zmax) * kLog2e);
+        if (logp_base && valid) logp_base[row_off] = (zact - zmax) - kLn2 * hw_log2(sum);
+        if (value_base && valid) value_base[row_off] = row_value();
+      }
       if constexpr (kTag) {
         tag_move<TS>(act, i, me, tg, px, py, vx, vy, qx, qy, lx, ly);
         xch4[tid] = make_float4(px, py, vx, vy);
@@ -482,6 +614,10 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(TagArgs TA, const uint
       }
     }
     if (act_base) act_base += TE * N;
+    if constexpr (AC) {
+      if (logp_base) logp_base += TE * N;
+      if (value_base) value_base += TE * N;
+    }
     __syncthreads();   // new positions visible; L has been read
 
     // ---- agents: reward, done, auto-reset, next observation (written over L)
@@ -558,18 +694,8 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(TagArgs TA, const uint
     __syncthreads();   // next observation and the done flags complete
   }
 
-  // ---- state back to HBM: the carried state (cleared where the last step ended an episode), agents
-#pragma unroll
-  for (int rt = 0; rt < NT; ++rt) {
-    const int row = 16 * rt + j;
-    if (row < vrows) {
-      const bool fresh = donef[row / N] != 0;
-      f32x4 v;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) v[r] = fresh ? 0.0f : hreg[rt][r];
-      *reinterpret_cast<f32x4*>(hidden + (g0 * N + row) * kG + 16 * u + 4 * gq) = v;
-    }
-  }
+  // ---- state back to HBM: the carried state (unless the bootstrap pass has stored it), agents
+  if (!bootstrap) store_hidden();
   if (valid) {
     A.st.pos_a[(0 * N + i) * TE + g] = px;
     A.st.pos_a[(1 * N + i) * TE + g] = py;
@@ -587,16 +713,16 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(TagArgs TA, const uint
   }
 }
 
-template <typename Scn, int EB>
-hipError_t rollout_gru_blocks(const TagArgs& A, const PolicyBuffers& pb, float* hidden, hipStream_t s) {
-  using M = GruSmem<Scn, EB>;
-  auto kern = rollout_gru_kernel<Scn, EB>;
+template <typename Scn, int EB, bool AC>
+hipError_t rollout_gru_blocks(const TagArgs& A, const PolicyBuffers& pb, const void* critic, float* hidden, hipStream_t s) {
+  using M = GruSmem<Scn, EB, AC>;
+  auto kern = rollout_gru_kernel<Scn, EB, AC>;
   static std::atomic<uint64_t> lds_allowed{0};
   if (hipError_t e = allow_lds(reinterpret_cast<const void*>(kern), M::TOTAL, lds_allowed); e != hipSuccess) return e;
   const uint32_t groups = (A.r.TE + EB - 1) / EB;
   const uint32_t per_xcd = (groups + 7) / 8;
   hipLaunchKernelGGL(kern, dim3(per_xcd * 8), dim3(512), M::TOTAL, s, A, static_cast<const uint8_t*>(pb.packed),
-                     hidden, int(A.r.TE != A.r.E), groups, per_xcd);
+                     static_cast<const uint8_t*>(critic), hidden, int(A.r.TE != A.r.E), groups, per_xcd);
   return hipGetLastError();
 }
 
@@ -608,7 +734,8 @@ constexpr int gru_max_envs() {
 }
 
 template <typename Scn>
-hipError_t rollout_gru_impl(const TagArgs& A, const PolicyBuffers& pb, float* hidden, hipStream_t s, const char** why) {
+hipError_t rollout_gru_impl(const TagArgs& A, const PolicyBuffers& pb, const void* critic, float* hidden, hipStream_t s,
+                            const char** why) {
   // Smaller blocks while each still gets a CU to itself (measured per 128-step rollout, 3 agents: 16-env
   // blocks 0.57-0.60 ms up to 4,096 envs and 32-env blocks 0.96-1.01 ms up to 8,192 envs against 1.9 ms with
   // 64-env blocks; with more blocks than CUs the largest blocks are the fastest).
@@ -621,13 +748,21 @@ hipError_t rollout_gru_impl(const TagArgs& A, const PolicyBuffers& pb, float* hi
     *why = "with several runs, num_envs per run must be a multiple of 16";
     return hipSuccess;
   }
+  if (critic) {
+    // actor-critic: the partial values take LDS of their own, so blocks are 32 envs up to 3 agents, 16 otherwise
+    constexpr int kAc = Scn::N <= 3 ? 32 : 16;
+    if (kAc == 16 || (A.r.TE + 15) / 16 <= cus || (runs && A.r.E % 32 != 0))
+      return rollout_gru_blocks<Scn, 16, true>(A, pb, critic, hidden, s);
+    if constexpr (kAc == 32) return rollout_gru_blocks<Scn, 32, true>(A, pb, critic, hidden, s);
+    return hipErrorInvalidValue;
+  }
   if (kMax == 16 || (A.r.TE + 15) / 16 <= cus || (runs && A.r.E % 32 != 0))
-    return rollout_gru_blocks<Scn, 16>(A, pb, hidden, s);
+    return rollout_gru_blocks<Scn, 16, false>(A, pb, nullptr, hidden, s);
   if constexpr (kMax >= 32) {
     if (kMax == 32 || (A.r.TE + 31) / 32 <= cus || (runs && A.r.E % 64 != 0))
-      return rollout_gru_blocks<Scn, 32>(A, pb, hidden, s);
+      return rollout_gru_blocks<Scn, 32, false>(A, pb, nullptr, hidden, s);
   }
-  if constexpr (kMax >= 64) return rollout_gru_blocks<Scn, 64>(A, pb, hidden, s);
+  if constexpr (kMax >= 64) return rollout_gru_blocks<Scn, 64, false>(A, pb, nullptr, hidden, s);
   return hipErrorInvalidValue;
 }
 
@@ -665,26 +800,34 @@ hipError_t pack_policy_gru(PolicyBuffers& pb, int D, int R, const float* We, con
   return hipGetLastError();
 }
 
-hipError_t launch_rollout_gru(bool tag, int N, int L, int G, const TagArgs& A, const PolicyBuffers& pb, float* hidden,
-                              hipStream_t s, const char** why) {
+hipError_t pack_gru_critic(PolicyBuffers& pb, int R, const float* Wc, const float* bc, const float* wv, const float* bv,
+                           hipStream_t s) {
+  if (hipError_t e = ensure_policy_bytes(pb, size_t(R) * GruCriticPk::BYTES); e != hipSuccess) return e;
+  hipLaunchKernelGGL(pack_gru_critic_kernel, dim3((GruCriticPk::THREADS + 255) / 256, R), dim3(256), 0, s,
+                     static_cast<uint8_t*>(pb.packed), Wc, bc, wv, bv);
+  return hipGetLastError();
+}
+
+hipError_t launch_rollout_gru(bool tag, int N, int L, int G, const TagArgs& A, const PolicyBuffers& pb, const void* critic,
+                              float* hidden, hipStream_t s, const char** why) {
   if (tag) {
 #define X(n, l, g) \
-    if (N == n && L == l && G == g) return rollout_gru_impl<GruTag<n, l, g>>(A, pb, hidden, s, why);
+    if (N == n && L == l && G == g) return rollout_gru_impl<GruTag<n, l, g>>(A, pb, critic, hidden, s, why);
     MPE_GRU_TAG_SHAPES(X)
 #undef X
     return hipErrorInvalidValue;
   }
   switch (N) {
-    case 1: return rollout_gru_impl<GruSpread<1>>(A, pb, hidden, s, why);
-    case 2: return rollout_gru_impl<GruSpread<2>>(A, pb, hidden, s, why);
-    case 3: return rollout_gru_impl<GruSpread<3>>(A, pb, hidden, s, why);
-    case 4: return rollout_gru_impl<GruSpread<4>>(A, pb, hidden, s, why);
-    case 5: return rollout_gru_impl<GruSpread<5>>(A, pb, hidden, s, why);
-    case 6: return rollout_gru_impl<GruSpread<6>>(A, pb, hidden, s, why);
-    case 7: return rollout_gru_impl<GruSpread<7>>(A, pb, hidden, s, why);
-    case 8: return rollout_gru_impl<GruSpread<8>>(A, pb, hidden, s, why);
-    case 9: return rollout_gru_impl<GruSpread<9>>(A, pb, hidden, s, why);
-    case 10: return rollout_gru_impl<GruSpread<10>>(A, pb, hidden, s, why);
+    case 1: return rollout_gru_impl<GruSpread<1>>(A, pb, critic, hidden, s, why);
+    case 2: return rollout_gru_impl<GruSpread<2>>(A, pb, critic, hidden, s, why);
+    case 3: return rollout_gru_impl<GruSpread<3>>(A, pb, critic, hidden, s, why);
+    case 4: return rollout_gru_impl<GruSpread<4>>(A, pb, critic, hidden, s, why);
+    case 5: return rollout_gru_impl<GruSpread<5>>(A, pb, critic, hidden, s, why);
+    case 6: return rollout_gru_impl<GruSpread<6>>(A, pb, critic, hidden, s, why);
+    case 7: return rollout_gru_impl<GruSpread<7>>(A, pb, critic, hidden, s, why);
+    case 8: return rollout_gru_impl<GruSpread<8>>(A, pb, critic, hidden, s, why);
+    case 9: return rollout_gru_impl<GruSpread<9>>(A, pb, critic, hidden, s, why);
+    case 10: return rollout_gru_impl<GruSpread<10>>(A, pb, critic, hidden, s, why);
     default: return hipErrorInvalidValue;
   }
 }
