@@ -335,6 +335,22 @@ def main():
                "roofline": {"bound": "mfma", "achieved": g_tf, "peak": 2500.0, "unit": "TFLOP/s", "frac": g_tf / 2500.0},
                "dtype": "bf16xbf16->f32", "kernel": "rollout_gru_kernel<3> (weight-stationary, 8 wavefronts per 64 envs)",
                "note": "mpe_set_gru_policy: 18 -> 128 tanh -> GRU 128 -> 128 tanh -> 5; carried state fp32"}
+        # the recurrent actor-critic on the same shape: critic head on the new carried state, bootstrap pass
+        env7.set_gru_critic(*to_dev(synth.gru_critic_weights(0, 1)))
+        env7.reset(seed)
+        b7 = env7.empty_traj_ac(T)
+        for _ in range(2):
+            env7.rollout_ac(T, *b7)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(k):
+            env7.rollout_ac(T, *b7)
+        torch.cuda.synchronize()
+        dt7 = (time.perf_counter() - t0) / k
+        gc_flop = g_flop + 2 * (128 * 128 + 128)
+        gru["actor_critic"] = {"agent_steps_per_s": agent_steps / dt7, "ms_per_rollout": dt7 * 1e3,
+                               "flop_per_agent_step": gc_flop, "TFLOPs": gc_flop * agent_steps / dt7 / 1e12,
+                               "note": "mpe_set_gru_critic + mpe_rollout_ac, wall time per call; 32-env blocks"}
         env7.close()
         del b7
 
