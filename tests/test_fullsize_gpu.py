@@ -453,3 +453,50 @@ def test_recurrent_policy_full_size():
     say("  sampled action agreement %.6f over %d samples" % (agree / tot, tot))
     assert agree / tot >= 0.99
     env.close()
+
+
+def test_recurrent_actor_critic_full_size():
+    """Recurrent actor-critic at the bench's size (65,536 envs x 3 agents x 128 steps, the launch shape of
+    bench.py's recurrent_policy.actor_critic): plain outputs and carried state bit-identical to mpe_rollout's;
+    sampled env ranges against the oracle's actor-critic rollout, episode by episode (every episode starts
+    from the same reset state on both sides), on the envs whose sampled actions agree so far."""
+    from paper_2311_10090_amd.binding import MpeEnv
+    from oracle import Oracle
+    E, T, N = 65536, 128, 3
+    say("full size recurrent actor-critic")
+    w, c = synth.gru_weights(5, 1, 18), synth.gru_critic_weights(5, 1)
+    env = MpeEnv(Hp.gpu_config(E, N, 1, 128, 1))
+    env.set_gru_policy(*Hp.to_dev(w))
+    env.set_gru_critic(*Hp.to_dev(c))
+    env.reset(1)
+    obs, act, logp, val, rew, done, last, lastv = env.rollout_ac(T, *env.empty_traj_ac(T))
+    hid = env.get_hidden()
+    plain = MpeEnv(Hp.gpu_config(E, N, 1, 128, 1))
+    plain.set_gru_policy(*Hp.to_dev(w))
+    plain.reset(1)
+    p = plain.rollout(T, *plain.empty_traj(T))
+    for got, ref, name in ((obs, p[0], "obs"), (act, p[1], "act"), (rew, p[2], "rew"), (done, p[3], "done"), (last, p[4], "last_obs"),
+                           (hid, plain.get_hidden(), "carried state")):
+        assert torch.equal(got, ref), name
+    plain.close()
+    del p
+    assert bool((logp <= 0).all()) and bool(torch.isfinite(val).all()) and bool(torch.isfinite(lastv).all())
+    ev, el, eb = [], [], []
+    for off, n in ((0, 64), (8192 - 16, 32), (32741, 7), (E - 32, 32)):
+        orc = Oracle(Hp.oracle_config(n, N, 1, 128, 1, env_offset=off), threads=8)
+        orc.set_gru(*w)
+        orc.set_gru_critic(*c)
+        orc.reset(1)
+        robs, ract, rlogp, rval, rrew, rdone, rlast, rlastv = orc.rollout_ac(T)
+        a, lp, v = [x[:, off:off + n].cpu().numpy() for x in (act, logp, val)]
+        same = (a == ract).all(axis=2)
+        for t0 in range(0, T, 25):
+            alive = np.logical_and.accumulate(same[t0:t0 + 25], axis=0)
+            prior = np.vstack([np.ones((1, n), bool), alive[:-1]])
+            ev.append(np.abs(v[t0:t0 + 25] - rval[t0:t0 + 25])[prior])
+            el.append(np.abs(lp[t0:t0 + 25] - rlogp[t0:t0 + 25])[alive])
+        eb.append(np.abs(lastv[off:off + n].cpu().numpy() - rlastv)[alive[-1]])
+    for name, e in (("value", np.concatenate(ev)), ("log-prob", np.concatenate(el)), ("bootstrap value", np.concatenate(eb))):
+        say("  %s: median %.2e, mean %.2e, worst %.2e over %d" % (name, np.median(e), e.mean(), e.max(), e.size))
+        assert e.size > 100 and np.median(e) < 2e-6 and e.mean() < 5e-4 and e.max() < 5e-2, name
+    env.close()
