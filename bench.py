@@ -350,7 +350,7 @@ def main():
         gc_flop = g_flop + 2 * (128 * 128 + 128)
         gru["actor_critic"] = {"agent_steps_per_s": agent_steps / dt7, "ms_per_rollout": dt7 * 1e3,
                                "flop_per_agent_step": gc_flop, "TFLOPs": gc_flop * agent_steps / dt7 / 1e12,
-                               "note": "mpe_set_gru_critic + mpe_rollout_ac, wall time per call; 32-env blocks"}
+                               "note": "mpe_set_gru_critic + mpe_rollout_ac, wall time per call; block shapes of the plain recurrent rollout"}
         env7.close()
         del b7
 

@@ -228,8 +228,11 @@ struct GruSmem {
   static constexpr size_t OFF_XCH = up16(OFF_BIAS + size_t(GruPk::BIAS_FLOATS) * 4);
   static constexpr size_t OFF_DONE = OFF_XCH + size_t(B) * (Scn::kTag ? 16 : 8);             // [64] bytes
   static constexpr size_t OFF_CTAIL = OFF_DONE + 64;                                         // AC: bc, wv, bv
-  static constexpr size_t OFF_VPART = OFF_CTAIL + (AC ? size_t(GruCriticPk::TAIL_FLOATS) * 4 : 0);   // AC: [8][B] floats
-  static constexpr size_t TOTAL = OFF_VPART + (AC ? size_t(8) * B * 4 : 0);
+  static constexpr size_t TOTAL = OFF_CTAIL + (AC ? size_t(GruCriticPk::TAIL_FLOATS) * 4 : 0);
+  // AC: the partial values, [8][B] floats, live behind the logits in the dead observation tile (written in the
+  // second-layer phase, read by the agent lanes before they write the next observation)
+  static constexpr size_t OFF_VPART = OFF_OBS + up16(LOGIT_BYTES);
+  static_assert(!AC || OFF_VPART + size_t(8) * B * 4 <= OFF_X, "partial values fit the observation tile");
   static_assert(TOTAL <= 160 * 1024, "LDS");
 };
 
@@ -522,42 +525,42 @@ __global__ __launch_bounds__(512) void rollout_gru_kernel(TagArgs TA, const uint
       bf16x8 wf[4];
 #pragma unroll
       for (int s = 0; s < 4; ++s) wf[s] = fcw[(u * 4 + s) * 64 + lane];
-      [[maybe_unused]] bf16x8 wc[4];
-      [[maybe_unused]] f32x4 bcv, wvv;
-      if constexpr (AC) {
-        // the critic's operands come from global memory every step (32 KB per run, cache-resident): the LDS
-        // has no room for them beside the actor's
-        const bf16x8* cw = reinterpret_cast<const bf16x8*>(packed_critic + GruCriticPk::OFF_FC) + zero;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) wc[s] = cw[(u * 4 + s) * 64 + lane];
-        const float* ctail = ctail0 + zero;
-        bcv = *reinterpret_cast<const f32x4*>(ctail + 16 * u + 4 * gq);
-        wvv = *reinterpret_cast<const f32x4*>(ctail + kG + 16 * u + 4 * gq);
-      }
 #pragma unroll
       for (int rt = 0; rt < NT; ++rt) {
         f32x4 acc = *reinterpret_cast<const f32x4*>(bias + 5 * kG + 16 * u + 4 * gq);
-        [[maybe_unused]] f32x4 accc;
-        if constexpr (AC) accc = bcv;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          const bf16x8 bh = *reinterpret_cast<const bf16x8*>(hbuf + rt * kTile + 64 * s + rd_off);
-          acc = MPE_MFMA_BF(wf[s], bh, acc);
-          if constexpr (AC) accc = MPE_MFMA_BF(wc[s], bh, accc);
-        }
+        for (int s = 0; s < 4; ++s)
+          acc = MPE_MFMA_BF(wf[s], *reinterpret_cast<const bf16x8*>(hbuf + rt * kTile + 64 * s + rd_off), acc);
         *reinterpret_cast<uint2*>(xbuf + rt * kTile + wr_off) =
             pack4_bf16(fast_tanh(acc[0]), fast_tanh(acc[1]), fast_tanh(acc[2]), fast_tanh(acc[3]));
-        if constexpr (AC) {
-          // yc enters the last product rounded to bf16; lane (j, gq) holds units 16 u + 4 gq .. + 3 of row j
-          const uint2 yc = pack4_bf16(fast_tanh(accc[0]), fast_tanh(accc[1]), fast_tanh(accc[2]), fast_tanh(accc[3]));
-          float pv = __uint_as_float(yc.x << 16) * wvv[0];
-          pv = fmaf(__uint_as_float(yc.x & 0xFFFF0000u), wvv[1], pv);
-          pv = fmaf(__uint_as_float(yc.y << 16), wvv[2], pv);
-          pv = fmaf(__uint_as_float(yc.y & 0xFFFF0000u), wvv[3], pv);
-          pv += __shfl_xor(pv, 16);
-          pv += __shfl_xor(pv, 32);
-          if (gq == 0) vpart[u * B + 16 * rt + j] = pv;
-        }
+      }
+    }
+    if constexpr (AC) {
+      // a pass of its own over the row tiles (the state's bf16 copy is read again), so that the actor's and the
+      // critic's operands are not live together; the critic's come from global memory every step (32 KB per
+      // run, cache-resident): the LDS has no room for them beside the actor's
+      const bf16x8* cw = reinterpret_cast<const bf16x8*>(packed_critic + GruCriticPk::OFF_FC) + zero;
+      bf16x8 wc[4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) wc[s] = cw[(u * 4 + s) * 64 + lane];
+      const float* ctail = ctail0 + zero;
+      const f32x4 bcv = *reinterpret_cast<const f32x4*>(ctail + 16 * u + 4 * gq);
+      const f32x4 wvv = *reinterpret_cast<const f32x4*>(ctail + kG + 16 * u + 4 * gq);
+#pragma unroll
+      for (int rt = 0; rt < NT; ++rt) {
+        f32x4 accc = bcv;
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+          accc = MPE_MFMA_BF(wc[s], *reinterpret_cast<const bf16x8*>(hbuf + rt * kTile + 64 * s + rd_off), accc);
+        // yc enters the last product rounded to bf16; lane (j, gq) holds units 16 u + 4 gq .. + 3 of row j
+        const uint2 yc = pack4_bf16(fast_tanh(accc[0]), fast_tanh(accc[1]), fast_tanh(accc[2]), fast_tanh(accc[3]));
+        float pv = __uint_as_float(yc.x << 16) * wvv[0];
+        pv = fmaf(__uint_as_float(yc.x & 0xFFFF0000u), wvv[1], pv);
+        pv = fmaf(__uint_as_float(yc.y << 16), wvv[2], pv);
+        pv = fmaf(__uint_as_float(yc.y & 0xFFFF0000u), wvv[3], pv);
+        pv += __shfl_xor(pv, 16);
+        pv += __shfl_xor(pv, 32);
+        if (gq == 0) vpart[u * B + 16 * rt + j] = pv;
       }
     }
     __syncthreads();   // Y complete (and the partial values)
@@ -733,9 +736,8 @@ constexpr int gru_max_envs() {
   return Scn::N <= 3 ? 64 : ((Scn::N <= 6 && Scn::D <= 32) ? 32 : 16);
 }
 
-template <typename Scn>
-hipError_t rollout_gru_impl(const TagArgs& A, const PolicyBuffers& pb, const void* critic, float* hidden, hipStream_t s,
-                            const char** why) {
+template <typename Scn, bool AC>
+hipError_t rollout_gru_sized(const TagArgs& A, const PolicyBuffers& pb, const void* critic, float* hidden, hipStream_t s) {
   // Smaller blocks while each still gets a CU to itself (measured per 128-step rollout, 3 agents: 16-env
   // blocks 0.57-0.60 ms up to 4,096 envs and 32-env blocks 0.96-1.01 ms up to 8,192 envs against 1.9 ms with
   // 64-env blocks; with more blocks than CUs the largest blocks are the fastest).
@@ -744,26 +746,27 @@ hipError_t rollout_gru_impl(const TagArgs& A, const PolicyBuffers& pb, const voi
   constexpr int kMax = gru_max_envs<Scn>();
   const uint32_t cus = compute_units();
   const bool runs = A.r.TE != A.r.E;
-  if (runs && A.r.E % 16 != 0) {
+  if (kMax == 16 || (A.r.TE + 15) / 16 <= cus || (runs && A.r.E % 32 != 0))
+    return rollout_gru_blocks<Scn, 16, AC>(A, pb, critic, hidden, s);
+  if constexpr (kMax >= 32) {
+    if (kMax == 32 || (A.r.TE + 31) / 32 <= cus || (runs && A.r.E % 64 != 0))
+      return rollout_gru_blocks<Scn, 32, AC>(A, pb, critic, hidden, s);
+  }
+  if constexpr (kMax >= 64) return rollout_gru_blocks<Scn, 64, AC>(A, pb, critic, hidden, s);
+  return hipErrorInvalidValue;
+}
+
+template <typename Scn>
+hipError_t rollout_gru_impl(const TagArgs& A, const PolicyBuffers& pb, const void* critic, float* hidden, hipStream_t s,
+                            const char** why) {
+  if (A.r.TE != A.r.E && A.r.E % 16 != 0) {
     *why = "with several runs, num_envs per run must be a multiple of 16";
     return hipSuccess;
   }
-  if (critic) {
-    // actor-critic: the partial values take LDS of their own, so blocks are 32 envs up to 3 agents, 16 otherwise
-    constexpr int kAc = Scn::N <= 3 ? 32 : 16;
-    if (kAc == 16 || (A.r.TE + 15) / 16 <= cus || (runs && A.r.E % 32 != 0))
-      return rollout_gru_blocks<Scn, 16, true>(A, pb, critic, hidden, s);
-    if constexpr (kAc == 32) return rollout_gru_blocks<Scn, 32, true>(A, pb, critic, hidden, s);
-    return hipErrorInvalidValue;
-  }
-  if (kMax == 16 || (A.r.TE + 15) / 16 <= cus || (runs && A.r.E % 32 != 0))
-    return rollout_gru_blocks<Scn, 16, false>(A, pb, nullptr, hidden, s);
-  if constexpr (kMax >= 32) {
-    if (kMax == 32 || (A.r.TE + 31) / 32 <= cus || (runs && A.r.E % 64 != 0))
-      return rollout_gru_blocks<Scn, 32, false>(A, pb, nullptr, hidden, s);
-  }
-  if constexpr (kMax >= 64) return rollout_gru_blocks<Scn, 64, false>(A, pb, nullptr, hidden, s);
-  return hipErrorInvalidValue;
+  // critic: the packed head of the actor-critic rollout (same block shapes: its partial values live in LDS
+  // that is dead at that point of the step)
+  return critic ? rollout_gru_sized<Scn, true>(A, pb, critic, hidden, s)
+                : rollout_gru_sized<Scn, false>(A, pb, nullptr, hidden, s);
 }
 
 __global__ void fill_zero_kernel(float* __restrict__ p, size_t n) {
