@@ -393,8 +393,12 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32" if wl.weight_dtype == 0 else "bf16xbf16->f32",
-        "dtype_note": ("env math f32; policy contraction: every f32 operand split into 3 fp16 terms (exact for |x| >= 0.5, "
-                       "2^-24 absolute below), 6 cross products on the 16-bit matrix cores, f32 accumulate") if wl.weight_dtype == 0 else
+        "dtype_note": ("env math f32; policy contraction: f32 operands as sums of fp16 terms, cross products on the 16-bit matrix "
+                       "cores, f32 accumulate: observations and the weights of layers 1 and 3 as three truncated terms (exact for "
+                       "|x| >= 0.5, 2^-24 absolute below), hidden activations (outputs of the hardware tanh, ~1e-7 absolute) and the "
+                       "pre-scaled weights of layer 2 as two terms rounded to nearest (<= 2^-23 relative, one fp32 ulp); mean error of "
+                       "the network outputs against the float64 oracle 1.4e-7, the same as with three terms everywhere (a plain "
+                       "float32 evaluation: 0.7e-7)") if wl.weight_dtype == 0 else
                       "weights and layer inputs rounded to bf16, f32 accumulate",
         "data": "synthetic",
         "config": {"workload": wl.name, "envs": TE, "agents": N, "T": T, "policy": "%d->%d->%d->5 tanh" % (D, H, H),
@@ -427,7 +431,7 @@ def main():
                 "instructions_per_64_rows_step": n_mfma,
                 "TFLOPs": n_mfma * 16384 * (agent_steps / 64) / (kavg * 1e-3) / 1e12,
                 "frac_of_16bit_peak": n_mfma * 16384 * (agent_steps / 64) / (kavg * 1e-3) / 1e12 / 2500.0,
-            })(264 if (wl.weight_dtype == 0 and N >= 2) else 288 if wl.weight_dtype == 0 else 208 if H == 128 else 56),
+            })(192 if (wl.weight_dtype == 0 and N >= 2) else 216 if wl.weight_dtype == 0 else 208 if H == 128 else 56),
         },
         "env_only": {
             "kernel": ("rollout_uniform_ws_kernel" if N <= 3 else

@@ -1,5 +1,5 @@
 // The 64-wide two-layer tanh MLP of the fused rollout kernels on the 16-bit matrix cores: packing of
-// the weights into A-operand order, the three-term operand split that gives fp32 products,
+// the weights into A-operand order, the operand splits (sums of fp16 terms) that give fp32 products,
 // and the forward pass of two 16-row tiles (fp32 split-operand and bf16 variants).  Shared by the kernels
 // of both scenarios; everything is templated on a shape S:
 //   S::D         floats per observation row in the LDS tile (row stride)
@@ -32,17 +32,25 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kH = 64;                    // hidden width
 constexpr float kPre = 2.0f * kLog2e;     // both tanh layers get pre-activations already times 2*log2(e)
 
-// ------------------------------------------------------------------------------ three-term split
-// An fp32 operand as the sum of three fp16 terms, x = h + m + l: h = x truncated to fp16 (11 significant
-// bits), m = (x - h) truncated, l = x - h - m truncated; both differences are exact in fp32.  11 + 11 + 2
-// bits cover the 24 of an fp32 number, so the split is EXACT for |x| >= 0.5 (and < 65,504); below that the
-// third term lies on fp16's subnormal grid and x is represented to within 2^-24 ABSOLUTE (6e-8, half of what
-// the hardware tanh that produces the activations is accurate to).  The matrix instruction takes subnormal
+// ------------------------------------------------------------------------------ operand splits
+// fp32 products on the 16-bit matrix cores: an operand is a sum of fp16 terms, a product the sum of the cross
+// terms that matter, accumulated in fp32.
+// Three terms, x = h + m + l: h = x truncated to fp16 (11 significant bits), m = (x - h) truncated,
+// l = x - h - m truncated; both differences are exact in fp32.  11 + 11 + 2 bits cover the 24 of an fp32
+// number, so the split is EXACT for |x| >= 0.5 (and < 65,504); below that the third term lies on fp16's
+// subnormal grid and x is represented to within 2^-24 ABSOLUTE.  The matrix instruction takes subnormal
 // fp16 inputs at full precision (checked on the chip).  Truncation (round toward zero) keeps every term of
 // the sign of x and is one instruction for two values (v_cvt_pkrtz_f16_f32); a difference is one mixed-
 // precision fma that reads the fp16 half in place (v_fma_mix_f32): 7 instructions per PAIR of values, and
 // the packed pairs are the matrix operands as they are.  (An fp32 = 3 x bf16 split, 8 + 8 + 8 bits, is exact
 // everywhere but costs 11 instructions per pair: and, sub, and, sub per value and three byte-permutes.)
+// Used for the observations and the weights of layers 1 and 3.
+// Two terms, each rounded to NEAREST (split2_pair below): 4 instructions per pair, |x - h - m| <= 2^-23 |x|,
+// one unit in the last place of fp32.  Used where the operand already carries an error of that size: the
+// hidden activations (outputs of the hardware tanh, ~1e-7 absolute) and the weights of layer 2 (stored
+// pre-scaled by 2 log2(e), a product that is itself rounded to fp32).  Measured against the float64
+// networks on 6e5 recorded rows, the outputs' mean error is 1.4e-7 with either split (a plain float32
+// evaluation with a correctly rounded tanh: 0.7e-7): it is set by the tanh, not by the split.
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
@@ -67,6 +75,15 @@ __device__ __forceinline__ void split3_pair(float x0, float x1, uint32_t& ph, ui
   const float s1 = sub_half<true>(pm, r1);
   pl = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(s0, s1));
 }
+// Two terms, each rounded to nearest: x = h + m + d with |d| <= 2^-23 |x| (h keeps 11 significant bits, the
+// remainder is at most half a unit of h's last place and m keeps 11 bits of it), 4 instructions per pair.
+__device__ __forceinline__ void split2_pair(float x0, float x1, uint32_t& ph, uint32_t& pm) {
+  typedef float f32x2_ __attribute__((ext_vector_type(2)));
+  const f32x2_ x = {x0, x1};
+  ph = __builtin_bit_cast(uint32_t, __builtin_convertvector(x, f16x2));       // v_cvt_pk_f16_f32, nearest even
+  const f32x2_ r = {sub_half<false>(ph, x0), sub_half<true>(ph, x1)};
+  pm = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, f16x2));
+}
 // One value: the 16-bit patterns of its three terms.
 __device__ __forceinline__ void split3(float x, uint32_t& h, uint32_t& m, uint32_t& l) {
   uint32_t ph, pm, pl;
@@ -85,7 +102,7 @@ __device__ __forceinline__ void split3(float x, uint32_t& h, uint32_t& m, uint32
 //                                 combo 0 = (h | m), combo 1 = (h | l)
 //   W1A [m 4][s][term 3][lane 64]  shapes with 17..64 inputs (kWideIn; s = K slice, one or two): k = 32 s + 8 gq + e,
 //                                 all three terms
-//   W2A [m 4][s 2][term 3][lane 64]
+//   W2A [m 4][s 2][term 2][lane 64]  the two-term split (split2_pair) of the pre-scaled weights
 //   W3A [s 2][term 3][lane 64]   (5 outputs padded to 16), shapes without kRowTerms only
 //   W3A [s 2][lane 64]           kRowTerms: the 16 output rows of the instruction carry the three
 //                                 terms of the 5 outputs (l3_row_* below), so ONE A operand meets
@@ -101,7 +118,7 @@ struct PkT {
   static constexpr size_t OFF_W1A = 0;
   static constexpr size_t W1A_BYTES = BF ? 4 * KS1 * 64 * 16 : (WIDE_IN ? 4 * KS1 * 3 * 64 * 16 : 4 * 2 * 64 * 16);
   static constexpr size_t OFF_W2A = OFF_W1A + W1A_BYTES;
-  static constexpr size_t W2A_BYTES = BF ? 4 * 2 * 64 * 16 : 4 * 2 * 3 * 64 * 16;
+  static constexpr size_t W2A_BYTES = BF ? 4 * 2 * 64 * 16 : 4 * 2 * 2 * 64 * 16;
   static constexpr size_t OFF_W3A = OFF_W2A + W2A_BYTES;
   static constexpr size_t W3A_BYTES = BF ? 2 * 64 * 16 : 2 * 3 * 64 * 16;
   static constexpr size_t OFF_BIAS = OFF_W3A + W3A_BYTES;
@@ -175,7 +192,11 @@ __global__ void pack_split_kernel(uint8_t* __restrict__ packed, const float* __r
   if (idx < n2) {
     const int e = idx % 8, lane = (idx / 8) % 64, s = (idx / 512) % 2, m = idx / 1024;
     const int k = hidden_k(s, lane / 16, e), o = 16 * m + lane % 16;
-    put3(Pk::OFF_W2A, m * 2 + s, 64, lane, e, kPre * W2[size_t(k) * kH + o]);
+    uint32_t ph, pm;
+    split2_pair(kPre * W2[size_t(k) * kH + o], 0.0f, ph, pm);
+    uint16_t* base = reinterpret_cast<uint16_t*>(out + Pk::OFF_W2A) + size_t(m * 2 + s) * 2 * 64 * 8 + lane * 8 + e;
+    base[0] = uint16_t(ph & 0xFFFFu);
+    base[64 * 8] = uint16_t(pm & 0xFFFFu);
     return;
   }
   idx -= n2;
@@ -228,6 +249,22 @@ __device__ __forceinline__ Terms split_operand(const float (&v)[8]) {
   return t;
 }
 
+// The two-term split of 8 hidden activations (l is left unset and never read).
+__device__ __forceinline__ Terms split_activation(const float (&v)[8]) {
+  u32x4 ph, pm;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    uint32_t a, b;
+    split2_pair(v[2 * q], v[2 * q + 1], a, b);
+    ph[q] = a;
+    pm[q] = b;
+  }
+  Terms t;
+  t.h = __builtin_bit_cast(bf16x8, ph);
+  t.m = __builtin_bit_cast(bf16x8, pm);
+  return t;
+}
+
 #define MPE_MFMA_BF(A, B, C) __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, B, C, 0, 0, 0)
 // the same shape on fp16 operands, for the terms of the three-term split (stored as raw 8 x 16 bits)
 #define MPE_MFMA_SPLIT(A, B, C) \
@@ -243,6 +280,22 @@ __device__ __forceinline__ f32x4 mma_split(const Terms& a, const Terms& b, f32x4
   acc = MPE_MFMA_SPLIT(a.h, b.m, acc);
   acc = MPE_MFMA_SPLIT(a.h, b.h, acc);
   return acc;
+}
+
+// Two-term operands on both sides (terms h, m of a and b): the four cross terms, smallest first.
+__device__ __forceinline__ f32x4 mma_split22(const Terms& a, const Terms& b, f32x4 acc) {
+  acc = MPE_MFMA_SPLIT(a.m, b.m, acc);
+  acc = MPE_MFMA_SPLIT(a.m, b.h, acc);
+  acc = MPE_MFMA_SPLIT(a.h, b.m, acc);
+  acc = MPE_MFMA_SPLIT(a.h, b.h, acc);
+  return acc;
+}
+
+// Three-term weights a against a two-term activation operand b (split_activation): the five cross terms of
+// weight >= 2^-23, smallest first.
+__device__ __forceinline__ f32x4 mma_split_act(const Terms& a, const Terms& b, f32x4 acc) {
+  acc = MPE_MFMA_SPLIT(a.l, b.h, acc);
+  return mma_split22(a, b, acc);
 }
 
 // tanh of a pre-activation that arrives already multiplied by 2*log2(e).
@@ -263,7 +316,7 @@ __device__ __forceinline__ Terms tanh_split(const f32x4& a0, const f32x4& a1) {
     v[e] = tanh_prescaled(a0[e]);
     v[4 + e] = tanh_prescaled(a1[e]);
   }
-  return split_operand(v);
+  return split_activation(v);
 }
 
 // Policy forward of two 16-row tiles X and Y whose observation rows are in LDS (row stride D).
@@ -302,7 +355,7 @@ __device__ __forceinline__ void policy_core(const uint8_t* __restrict__ wsm, con
     bias += zero;
   }
   const bf16x8* w1 = reinterpret_cast<const bf16x8*>(wsm + Pk::OFF_W1A);  // [m][combo][lane64]; kWideIn: [m][term][lane64]
-  const bf16x8* w2 = reinterpret_cast<const bf16x8*>(wsm + Pk::OFF_W2A);  // [m][s][term][lane64]
+  const bf16x8* w2 = reinterpret_cast<const bf16x8*>(wsm + Pk::OFF_W2A);  // [m][s][term 2][lane64]
   // Layer 1, one output tile: the six cross terms in three instructions, smallest first:
   //   (Wh | Wl) x (Xl | Xh) = hl + lh,  (Wh | Wm) x (Xm | Xm) = hm + mm,  (Wh | Wm) x (Xh | Xh) = hh + mh
   auto layer1 = [&](int m, const Terms (&b)[KS1], const bf16x8& b_lh, f32x4 acc) {
@@ -326,21 +379,19 @@ __device__ __forceinline__ void policy_core(const uint8_t* __restrict__ wsm, con
   };
   auto load_w2 = [&](int m, int s) {
     Terms a;
-    a.h = w2[((m * 2 + s) * 3 + 0) * 64 + lane];
-    a.m = w2[((m * 2 + s) * 3 + 1) * 64 + lane];
-    a.l = w2[((m * 2 + s) * 3 + 2) * 64 + lane];
+    a.h = w2[((m * 2 + s) * 2 + 0) * 64 + lane];
+    a.m = w2[((m * 2 + s) * 2 + 1) * 64 + lane];
     return a;
   };
   // Layer 3, one K slice.  Row-term layout: the one A operand against the three activation terms
   // (all nine cross terms, smallest first); otherwise the six significant ones.
   auto layer3 = [&](const Terms& a, const Terms& b, f32x4 acc) {
     if constexpr (S::kRowTerms) {
-      acc = MPE_MFMA_SPLIT(a.h, b.l, acc);
       acc = MPE_MFMA_SPLIT(a.h, b.m, acc);
       acc = MPE_MFMA_SPLIT(a.h, b.h, acc);
       return acc;
     } else {
-      return mma_split(a, b, acc);
+      return mma_split_act(a, b, acc);
     }
   };
   // ---- split(obs): 16 inputs (cols 0..15 of the row; cols >= 4N+2 are zeros or meet zero weights);
@@ -396,14 +447,14 @@ __device__ __forceinline__ void policy_core(const uint8_t* __restrict__ wsm, con
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
       const Terms a = load_w2(m, 0);
-      accX[m] = mma_split(a, cx0, accX[m]);
-      accY[m] = mma_split(a, cy0, accY[m]);
+      accX[m] = mma_split22(a, cx0, accX[m]);
+      accY[m] = mma_split22(a, cy0, accY[m]);
     }
 #pragma unroll
     for (int m = 2; m < 4; ++m) {
       const Terms a = load_w2(m, 0);
-      tX[m - 2] = mma_split(a, cx0, tX[m - 2]);
-      tY[m - 2] = mma_split(a, cy0, tY[m - 2]);
+      tX[m - 2] = mma_split22(a, cx0, tX[m - 2]);
+      tY[m - 2] = mma_split22(a, cy0, tY[m - 2]);
     }
     cx1 = tanh_split(accX[2], accX[3]);
     cy1 = tanh_split(accY[2], accY[3]);
@@ -418,16 +469,16 @@ __device__ __forceinline__ void policy_core(const uint8_t* __restrict__ wsm, con
 #pragma unroll
   for (int m = 0; m < 2; ++m) {
     const Terms a = load_w2(m, 1);
-    accX[m] = mma_split(a, cx1, accX[m]);
-    accY[m] = mma_split(a, cy1, accY[m]);
+    accX[m] = mma_split22(a, cx1, accX[m]);
+    accY[m] = mma_split22(a, cy1, accY[m]);
   }
   __builtin_amdgcn_sched_barrier(0);
   // ---- L2 s1 m23 + T2 s0
 #pragma unroll
   for (int m = 2; m < 4; ++m) {
     const Terms a = load_w2(m, 1);
-    accX[m] = mma_split(a, cx1, accX[m]);
-    accY[m] = mma_split(a, cy1, accY[m]);
+    accX[m] = mma_split22(a, cx1, accX[m]);
+    accY[m] = mma_split22(a, cy1, accY[m]);
   }
   cx0 = tanh_split(accX[0], accX[1]);
   cy0 = tanh_split(accY[0], accY[1]);
