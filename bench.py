@@ -417,8 +417,10 @@ def main():
             "bound": "alu", "achieved": tflops, "peak": MFMA_FP32_PEAK_TFLOPS if wl.weight_dtype == 0 else 2500.0,
             "unit": "TFLOP/s",
             "frac": tflops / (MFMA_FP32_PEAK_TFLOPS if wl.weight_dtype == 0 else 2500.0),
-            "frac_note": "fp32-equivalent contraction FLOPs / fp32 peak: a notional fraction of a kernel bound by "
-                         "vector issue; mfma_busy_frac and valu_active_frac are the measured unit utilisations",
+            "frac_note": "algorithmic (fp32-equivalent) contraction FLOPs / fp32 vector peak: a notional fraction of a kernel "
+                         "bound by vector issue; it can pass 1 because the products run on the 16-bit matrix cores (see "
+                         "executed_16bit_mfma), not on the fp32 units; mfma_busy_frac and valu_active_frac are the measured "
+                         "unit utilisations",
             "mfma_busy_frac": None, "valu_active_frac": None,
             "traffic": None,
             "algorithmic_bytes": bytes_per_env_step(N, D) * TE * T,
