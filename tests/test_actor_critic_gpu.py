@@ -210,3 +210,45 @@ def test_actor_critic_with_four_and_more_agents(mods, N, H, E, R, kw):
     assert bool((full[2] <= 0).all()) and bool(torch.isfinite(full[3]).all())
     for e in (a, b, c):
         e.close()
+
+
+@pytest.mark.parametrize("scn", ["spread", "tag", "spread6"])
+def test_fp32_network_outputs_are_as_close_to_float64_as_a_plain_float32_evaluation(mods, scn):
+    """The fp32 mode runs its products on the 16-bit matrix cores with operands held as sums of fp16 terms (to
+    within one fp32 unit in the last place).  What that costs is measured here on the outputs themselves: over
+    hundreds of thousands of recorded rows, values and log-probabilities must lie as close to the oracle's
+    float64 networks as a plain float32 evaluation of the same networks does (numpy, correctly rounded tanh),
+    up to the error of the hardware tanh (~1e-7 absolute per activation): mean error below 2.5e-7 and at most
+    3 times the plain evaluation's, worst error below 3e-6."""
+    from scipy.special import log_softmax
+    MpeEnv, Oracle = mods
+    E, T = 8192, 25
+    if scn == "tag":
+        gcfg, ocfg = Hp.tag_gpu_config(E, 4, 2, 3, 1, 64), Hp.tag_oracle_config(E, 4, 2, 3, 1, 64)
+    else:
+        N = 6 if scn == "spread6" else 3
+        E = E // (N // 3)
+        gcfg, ocfg = Hp.gpu_config(E, N, 1, 64, 0), Hp.oracle_config(E, N, 1, 64, 0)
+    env, orc = MpeEnv(gcfg), Oracle(ocfg, threads=8)
+    D = env.D
+    w, c = synth.policy_weights_with_bias(3, 1, D, 64), synth.critic_weights(3, 1, D, 64)
+    env.set_policy(*Hp.to_dev(w))
+    env.set_critic(*Hp.to_dev(c))
+    orc.set_policy(*w)
+    orc.set_critic(*c)
+    env.reset(5)
+    obs, act, lp, v = [x.cpu().numpy() for x in env.rollout_ac(T, *env.empty_traj_ac(T))[:4]]
+    rows = obs.reshape(-1, D)
+    rv = orc.value(rows.astype(np.float64))
+    rlp = log_softmax(orc.policy_logits(rows.astype(np.float64)), axis=1)[np.arange(rows.shape[0]), act.reshape(-1)]
+    ev, el = np.abs(v.reshape(-1) - rv), np.abs(lp.reshape(-1) - rlp)
+    V1, c1, V2, c2, V3, c3 = [a[0].astype(np.float32) for a in c]
+    h = np.tanh(np.tanh(rows @ V1 + c1) @ V2 + c2)
+    plain = np.abs(((h @ V3.reshape(64, -1)).reshape(-1) + c3.reshape(-1)[0]).astype(np.float64) - rv)
+    say("  %s: value error mean %.3e worst %.3e, log-prob error mean %.3e worst %.3e over %d rows; plain float32 numpy value error mean %.3e worst %.3e"
+        % (scn, ev.mean(), ev.max(), el.mean(), el.max(), ev.size, plain.mean(), plain.max()))
+    Hp.record("fp32 network outputs against the float64 oracle, %s, %d rows: value error mean %.3e worst %.3e, log-prob error mean %.3e worst %.3e; "
+              "plain float32 numpy evaluation of the value head: mean %.3e worst %.3e" % (scn, ev.size, ev.mean(), ev.max(), el.mean(), el.max(), plain.mean(), plain.max()))
+    assert ev.mean() < 2.5e-7 and el.mean() < 2.5e-7 and ev.max() < 3e-6 and el.max() < 3e-6
+    assert ev.mean() <= 3.0 * plain.mean()
+    env.close()
