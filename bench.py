@@ -24,16 +24,42 @@ MFMA_FP32_PEAK_TFLOPS = 157.3  # MI355X dense fp32 matrix; the fp32 vector peak 
 KERNEL_SOURCES = ("paper_2311_10090_amd/csrc", "include")
 
 
+def _code_only(text):
+    """C++ source without its comments and with every run of white space collapsed to one blank (string and
+    character literals are kept as they are)."""
+    out, i, n = [], 0, len(text)
+    while i < n:
+        c = text[i]
+        if c in "\"'":
+            j = i + 1
+            while j < n and text[j] != c:
+                j += 2 if text[j] == "\\" else 1
+            out.append(text[i:j + 1])
+            i = j + 1
+        elif text.startswith("//", i):
+            j = text.find("\n", i)
+            i = n if j < 0 else j
+        elif text.startswith("/*", i):
+            j = text.find("*/", i + 2)
+            i = n if j < 0 else j + 2
+            out.append(" ")
+        else:
+            out.append(c)
+            i += 1
+    return " ".join("".join(out).split())
+
+
 def kernel_source_hash():
-    """sha256 over the HIP sources and the header: counter figures stored under profiles/ carry the hash of
-    the sources they were measured on, and are reported only while it still matches."""
+    """sha256 over the code of the HIP sources and the header (comments and white space left out): counter
+    figures stored under profiles/ carry the hash of the sources they were measured on, and are reported only
+    while it still matches."""
     import hashlib
     h = hashlib.sha256()
     for d in KERNEL_SOURCES:
         for name in sorted(os.listdir(os.path.join(ROOT, d))):
             if name.endswith((".hip", ".h")):
                 h.update(name.encode())
-                h.update(open(os.path.join(ROOT, d, name), "rb").read())
+                h.update(_code_only(open(os.path.join(ROOT, d, name), encoding="utf-8").read()).encode())
     return h.hexdigest()
 
 

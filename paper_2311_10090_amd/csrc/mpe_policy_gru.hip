@@ -245,6 +245,9 @@ __device__ __forceinline__ uint2 pack4_bf16(float a, float b, float c, float d) 
 // EB = envs per block: 64, or 32 / 16 for small batches (every phase of a step is a loop over the block's
 // 16-row tiles, so the step latency of a block, which is the time of a rollout while every block has a CU
 // to itself, falls with its rows) and for the shapes whose activations would not fit the LDS otherwise.
+// AC = the actor-critic rollout (packed_critic = the head of pack_gru_critic): per step also the critic's second
+// layer on the new carried state and the log-probability of the sampled action, and, when a bootstrap value
+// is asked for, one more pass of the network phases after the last step that writes nothing else.
 template <typename Scn, int EB, bool AC>
 __global__ __launch_bounds__(512) void rollout_gru_kernel(TagArgs TA, const uint8_t* __restrict__ packed,
                                                           const uint8_t* __restrict__ packed_critic,

@@ -227,3 +227,20 @@ int main(void) {
     r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
     assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
     assert "%d symbols, ok" % len(names) in r.stdout
+
+
+def test_bench_source_hash_ignores_comments_and_layout_but_not_code():
+    """bench.py reports the committed counter figures only while the kernel sources hash to the value stored
+    with them: the hash must not move with a comment or a blank, and must move with the code."""
+    import importlib.util
+    import os
+    spec = importlib.util.spec_from_file_location("bench_for_hash", os.path.join(os.path.dirname(os.path.dirname(__file__)), "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    a = 'int f(int x) {  // adds one\n  /* block\n comment */ return x + 1;\n}\nconst char* s = "// kept /* kept */";\n'
+    b = 'int f(int x) { return x + 1; }\n\n\nconst char* s = "// kept /* kept */";   // trailing\n'
+    c = 'int f(int x) { return x + 2; }\nconst char* s = "// kept /* kept */";\n'
+    d = 'int f(int x) { return x + 1; }\nconst char* s = "// kept /* lost */";\n'
+    assert bench._code_only(a) == bench._code_only(b)
+    assert bench._code_only(a) != bench._code_only(c) and bench._code_only(a) != bench._code_only(d)
+    assert len(bench.kernel_source_hash()) == 64
