@@ -30,8 +30,8 @@ def mods():
     return MpeEnv, Oracle
 
 
-def _env(mods, E, scn, R=1, wseed=3, head=True, max_ep=synth.MAX_EPISODE_STEPS):
-    env = mods[0](_configs(E, scn, R, max_ep)[0])
+def _env(mods, E, scn, R=1, wseed=3, head=True, max_ep=synth.MAX_EPISODE_STEPS, reward_mode=0):
+    env = mods[0](_configs(E, scn, R, max_ep, reward_mode)[0])
     env.set_gru_policy(*Hp.to_dev(synth.gru_weights(wseed, R, env.D)))
     if head:
         env.set_gru_critic(*Hp.to_dev(synth.gru_critic_weights(wseed, R)))
@@ -251,3 +251,39 @@ def test_head_management_and_refusals(mods):
         env.rollout_ac(2, *env.empty_traj_ac(2))
     assert ei.value.code == MPE_EINVAL
     env.close()
+
+
+def test_mixed_reward_and_short_episodes(mods):
+    """The per-agent reward of simple spread and episodes that end every 4 steps (the carried state is cleared
+    and the bootstrap pass starts from zero there): everything but the head's outputs equals mpe_rollout's."""
+    E, T = 150, 17
+    for kw in (dict(reward_mode=1), dict(max_ep=4)):
+        a, b = _env(mods, E, 3, **kw), _env(mods, E, 3, head=False, **kw)
+        a.reset(9)
+        b.reset(9)
+        full = a.rollout_ac(T, *a.empty_traj_ac(T))
+        plain = b.rollout(T, *b.empty_traj(T))
+        for k_ac, k_pl in ((0, 0), (1, 1), (4, 2), (5, 3), (6, 4)):
+            assert torch.equal(full[k_ac], plain[k_pl]), "output %d differs from mpe_rollout (%s)" % (k_ac, kw)
+        assert torch.equal(a.get_hidden(), b.get_hidden())
+        if "max_ep" in kw:
+            # T = 17: step 16 ended an episode?  no: episodes end at steps 3, 7, 11, 15; one step into the fifth
+            assert bool(full[5][3].all()) and bool(full[5][15].all()) and not bool(full[5][16].any())
+            orc = _oracle(mods, E, 3, max_ep=4)
+            orc.reset(9)
+            ref = orc.rollout_ac(T)
+            same = (full[1].cpu().numpy() == ref[1]).all(axis=2)
+            alive = np.logical_and.accumulate(same[12:], axis=0)[-1]     # the last episodes (reset states agree bit for bit)
+            assert alive.mean() > 0.9
+            e = np.abs(full[7].cpu().numpy() - ref[7])[alive]
+            assert np.median(e) < 2e-6 and e.max() < 5e-2
+            # a rollout that ends exactly at an episode end: the bootstrap value is that of a fresh episode
+            a.reset(9)
+            orc.reset(9)
+            lv = a.rollout_ac(4, *a.empty_traj_ac(4))[7].cpu().numpy()
+            rlv = orc.rollout_ac(4)[7]
+            assert not a.get_hidden().any()
+            e = np.abs(lv - rlv)
+            assert np.median(e) < 2e-6 and e.max() < 2e-2
+        a.close()
+        b.close()
