@@ -500,3 +500,57 @@ def test_recurrent_actor_critic_full_size():
         say("  %s: median %.2e, mean %.2e, worst %.2e over %d" % (name, np.median(e), e.mean(), e.max(), e.size))
         assert e.size > 100 and np.median(e) < 2e-6 and e.mean() < 5e-4 and e.max() < 5e-2, name
     env.close()
+
+
+@pytest.mark.parametrize("scn,E,recurrent", [(6, 32768, False), ((10, 3, 8), 16384, False), ((4, 2, 3), 32768, True), (10, 16384, True)])
+def test_wider_shapes_at_the_sizes_the_bench_times(scn, E, recurrent):
+    """The launches of bench.py's wider_shapes section (fp32 weights with 6 agents, predator-prey with 10 agents,
+    the recurrent policy on predator-prey and on 10 agents of simple spread), 128 steps: sampled env ranges
+    against the oracle, every episode of the rollout (each starts from a reset state that is the same bits on
+    both sides), with the 25-step bar of the small-size tests."""
+    from paper_2311_10090_amd.binding import MpeEnv
+    from oracle import Oracle
+    T = 128
+    tag = isinstance(scn, tuple)
+    H, wd = (128, 1) if recurrent else (64, 0)
+    say("full size wider shape scenario=%s E=%d recurrent=%s" % (scn, E, recurrent))
+    if tag:
+        N, L, A = scn
+        env = MpeEnv(Hp.tag_gpu_config(E, N, L, A, 1, H, wd=wd))
+    else:
+        N = scn
+        env = MpeEnv(Hp.gpu_config(E, N, 1, H, wd))
+    w = synth.gru_weights(5, 1, env.D) if recurrent else synth.policy_weights_with_bias(3, 1, env.D, 64)
+    (env.set_gru_policy if recurrent else env.set_policy)(*Hp.to_dev(w))
+    env.reset(1)
+    obs, act, rew, done, last = env.rollout(T, *env.empty_traj(T))
+    torch.cuda.synchronize()
+    assert int(done.sum().item()) == E * (T // 25) and bool((done[24::25] == 1).all())
+    assert bool((act <= 4).all()) and bool(torch.isfinite(obs).all()) and bool(torch.isfinite(rew).all())
+    tot = agree = 0
+    errs, senss, gaps = [], [], []
+    for off, n in ((0, 32), (E // 8 - 16, 32), (E // 2 + 5, 7), (E - 32, 32)):
+        def make_oracle(off=off, n=n):
+            cfg = (Hp.tag_oracle_config(n, N, L, A, 1, H, env_offset=off, wd=wd) if tag
+                   else Hp.oracle_config(n, N, 1, H, wd, env_offset=off))
+            o_ = Oracle(cfg, threads=8)
+            (o_.set_gru if recurrent else o_.set_policy)(*w)
+            return o_
+        orc = make_oracle()
+        orc.reset(1)
+        robs, ract, rrew, rdone, rlast = orc.rollout(T)
+        o, a, r, d = [x[:, off:off + n].cpu().numpy() for x in (obs, act, rew, done)]
+        assert np.array_equal(d, rdone)
+        err, _, (ag, to) = Hp.episode_errors(o, a, None if tag else r, robs, ract, None if tag else rrew,
+                                              last=last[off:off + n].cpu().numpy(), rlast=rlast)
+        agree += ag
+        tot += to
+        errs.append(err)
+        senss.append(Hp.oracle_sensitivity(make_oracle, 1, T))
+        gaps.append(Hp.min_gap_tag(robs, scn) if tag else Hp.min_gap_spread(robs, N))
+    err, sens, gap = [np.concatenate(x, axis=1) for x in (errs, senss, gaps)]
+    share = Hp.EXCEED_SHARE_TAG[scn[:2]] if tag else Hp.EXCEED_SHARE_SPREAD[N]
+    Hp.assert_episodes_close(err, sens, gap, share, what="full size wider shape scenario=%s E=%d recurrent=%s (%d sampled envs)" % (scn, E, recurrent, err.shape[1]))
+    say("  sampled action agreement %.6f over %d samples" % (agree / tot, tot))
+    assert agree / tot >= (0.97 if recurrent else Hp.ACTION_AGREEMENT - 2.0 / tot)
+    env.close()
