@@ -128,7 +128,8 @@ EXCEED_SHARE_TAG = {(2, 1): 1e-4, (3, 0): 2e-4, (4, 2): 8e-4, (5, 2): 1.5e-3, (6
 
 
 def record(line):
-    """Print a measured figure and, on the GPU machine, append it to gpurun_out/parity_margins.txt."""
+    """Print a measured figure and, where the run's output folder exists at the repository root, append it to the
+    parity_margins.txt kept there (the summary under profiles/ is made from that file)."""
     import os
     print(line, flush=True)
     out = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
